@@ -1,0 +1,42 @@
+/*
+ * astra_plan.h -- introspection of the host-side dispatch of the astra library: which kernel variant
+ * and launch geometry a call with the given shape would use.  Pure host arithmetic, no HIP call, so it
+ * can be exercised on a machine without a GPU.  The operators themselves are declared in astra.h.
+ */
+#ifndef ASTRA_PLAN_H
+#define ASTRA_PLAN_H
+
+#include <stdint.h>
+
+#include "astra.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    ASTRA_PATH_NONE = 0,    /* nothing to launch (T == 0) */
+    ASTRA_PATH_VECTOR = 1,  /* 16-byte-per-lane fast path */
+    ASTRA_PATH_GENERIC = 2  /* element-wise path for odd row lengths / unaligned pointers / huge rows */
+} astra_path_t;
+
+typedef struct {
+    int32_t path;             /* astra_path_t */
+    int32_t block;            /* work-items per workgroup */
+    int32_t vectors_per_lane; /* 16-byte vectors each lane keeps in flight (0 on the generic path) */
+    int32_t reserved;
+    int64_t grid;             /* workgroups */
+} astra_launch_info_t;
+
+/* `aligned16` tells whether every tensor pointer of the call is 16-byte aligned (non-zero = yes).
+ * Each function validates shapes like its operator does (ASTRA_ERR_SHAPE, ASTRA_ERR_NULL for `info`). */
+astra_status_t astra_plan_fused_add_rmsnorm(int64_t T, int64_t H, int aligned16, astra_launch_info_t* info);
+astra_status_t astra_plan_silu_and_mul(int64_t T, int64_t d, int aligned16, astra_launch_info_t* info);
+astra_status_t astra_plan_merge_attn_states_lse(int64_t T, int64_t num_heads, int64_t head_dim, int aligned16,
+                                                astra_launch_info_t* info);
+
+#ifdef __cplusplus
+}
+#endif
+
+#endif /* ASTRA_PLAN_H */

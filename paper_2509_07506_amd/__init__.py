@@ -1,0 +1,26 @@
+"""MI355X (gfx950) implementation of the three serving operators of arxiv 2509.07506, Table 1.
+
+The work is done by hand-written HIP kernels behind a C ABI (``include/astra.h``,
+``libastra_hip.so``); this package is a thin ``ctypes`` binding with the same names.  There is no
+fallback path: if the library is not built or cannot be loaded, every call raises.
+"""
+from .binding import (  # noqa: F401
+    ASTRA_BF16,
+    ASTRA_F16,
+    AstraError,
+    LaunchInfo,
+    astra_fused_add_rmsnorm,
+    astra_merge_attn_states_lse,
+    astra_plan_fused_add_rmsnorm,
+    astra_plan_merge_attn_states_lse,
+    astra_plan_silu_and_mul,
+    astra_silu_and_mul,
+    astra_status_string,
+    astra_stream_copy,
+    fused_add_rmsnorm,
+    library_path,
+    load_library,
+    merge_attn_states_lse,
+    silu_and_mul,
+    stream_copy,
+)

@@ -1,0 +1,201 @@
+"""ctypes binding of ``libastra_hip.so`` (declared in ``include/astra.h`` and ``include/astra_plan.h``).
+
+Two layers, both argument marshalling only:
+
+* ``astra_*`` -- the C entry points themselves: integer device addresses, sizes, dtype code, stream
+  handle in, status code out.
+* ``fused_add_rmsnorm`` / ``silu_and_mul`` / ``merge_attn_states_lse`` / ``stream_copy`` -- take torch
+  tensors living on the GPU, check dtype / contiguity / shapes, pass ``data_ptr()`` and torch's current
+  stream, and raise :class:`AstraError` on a non-zero status.
+
+PyTorch is used for device memory and streams only.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+ASTRA_F16 = 0
+ASTRA_BF16 = 1
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG, "libastra_hip.so")
+_lib = None
+
+
+class AstraError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = int(status)
+        super().__init__(f"{where}: status {int(status)} ({astra_status_string(status)})")
+
+
+class LaunchInfo(ctypes.Structure):
+    _fields_ = [("path", ctypes.c_int32), ("block", ctypes.c_int32), ("vectors_per_lane", ctypes.c_int32),
+                ("reserved", ctypes.c_int32), ("grid", ctypes.c_int64)]
+
+    def as_dict(self):
+        return {"path": {0: "none", 1: "vector", 2: "generic"}[self.path], "block": self.block,
+                "vectors_per_lane": self.vectors_per_lane, "grid": self.grid}
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library() -> ctypes.CDLL:
+    """Loads the built library.  Builds it first only when no built library exists at all."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        from . import build as _build
+
+        try:
+            _build.build()
+        except Exception as e:  # no silent fallback: the product path needs the HIP library
+            raise RuntimeError(f"astra HIP library is not built and building it failed: {e}") from e
+    L = ctypes.CDLL(_LIB_PATH)
+    vp, i64, i32, f32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_float
+    L.astra_fused_add_rmsnorm.argtypes = [vp, vp, vp, i64, i64, i32, f32, vp]
+    L.astra_silu_and_mul.argtypes = [vp, vp, i64, i64, i32, vp]
+    L.astra_merge_attn_states_lse.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, i32, vp]
+    L.astra_stream_copy.argtypes = [vp, vp, i64, vp]
+    L.astra_status_string.argtypes = [i32]
+    L.astra_status_string.restype = ctypes.c_char_p
+    pinfo = ctypes.POINTER(LaunchInfo)
+    L.astra_plan_fused_add_rmsnorm.argtypes = [i64, i64, i32, pinfo]
+    L.astra_plan_silu_and_mul.argtypes = [i64, i64, i32, pinfo]
+    L.astra_plan_merge_attn_states_lse.argtypes = [i64, i64, i64, i32, pinfo]
+    for n in ("astra_fused_add_rmsnorm", "astra_silu_and_mul", "astra_merge_attn_states_lse", "astra_stream_copy",
+              "astra_plan_fused_add_rmsnorm", "astra_plan_silu_and_mul", "astra_plan_merge_attn_states_lse"):
+        getattr(L, n).restype = i32
+    _lib = L
+    return L
+
+
+# ---------------------------------------------------------------------------------------------------
+# the C entry points, one to one
+
+def astra_status_string(status: int) -> str:
+    return load_library().astra_status_string(int(status)).decode()
+
+
+def astra_fused_add_rmsnorm(input_ptr, residual_ptr, weight_ptr, T, H, dtype, eps, stream=None) -> int:
+    return load_library().astra_fused_add_rmsnorm(input_ptr, residual_ptr, weight_ptr, T, H, dtype, eps, stream)
+
+
+def astra_silu_and_mul(out_ptr, input_ptr, T, d, dtype, stream=None) -> int:
+    return load_library().astra_silu_and_mul(out_ptr, input_ptr, T, d, dtype, stream)
+
+
+def astra_merge_attn_states_lse(v_out, lse_out, v_a, lse_a, v_b, lse_b, T, num_heads, head_dim, dtype,
+                                stream=None) -> int:
+    return load_library().astra_merge_attn_states_lse(v_out, lse_out, v_a, lse_a, v_b, lse_b, T, num_heads, head_dim,
+                                                      dtype, stream)
+
+
+def astra_stream_copy(dst, src, nbytes, stream=None) -> int:
+    return load_library().astra_stream_copy(dst, src, nbytes, stream)
+
+
+def _plan(fn, *args):
+    info = LaunchInfo()
+    st = fn(*args, ctypes.byref(info))
+    return st, info
+
+
+def astra_plan_fused_add_rmsnorm(T, H, aligned16=True):
+    return _plan(load_library().astra_plan_fused_add_rmsnorm, T, H, int(aligned16))
+
+
+def astra_plan_silu_and_mul(T, d, aligned16=True):
+    return _plan(load_library().astra_plan_silu_and_mul, T, d, int(aligned16))
+
+
+def astra_plan_merge_attn_states_lse(T, num_heads, head_dim, aligned16=True):
+    return _plan(load_library().astra_plan_merge_attn_states_lse, T, num_heads, head_dim, int(aligned16))
+
+
+# ---------------------------------------------------------------------------------------------------
+# torch-tensor convenience layer (marshalling only)
+
+def _dtype_code(t) -> int:
+    import torch
+
+    if t.dtype == torch.bfloat16:
+        return ASTRA_BF16
+    if t.dtype == torch.float16:
+        return ASTRA_F16
+    raise TypeError(f"astra operators take float16 or bfloat16 tensors, got {t.dtype}")
+
+
+def _check_gpu(*tensors):
+    for t in tensors:
+        if not t.is_cuda:
+            raise ValueError("astra operators run on GPU tensors only (there is no CPU path)")
+        if not t.is_contiguous():
+            raise ValueError("astra operators take dense row-major tensors")
+
+
+def _stream(stream):
+    import torch
+
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    return getattr(stream, "cuda_stream", stream)
+
+
+def fused_add_rmsnorm(input, residual, weight, eps: float, stream=None) -> None:
+    """In place: residual <- input + residual, input <- rmsnorm(input + residual) * weight."""
+    _check_gpu(input, residual, weight)
+    T, H = input.shape
+    if residual.shape != (T, H) or weight.shape != (H,) or residual.dtype != input.dtype or weight.dtype != input.dtype:
+        raise ValueError("fused_add_rmsnorm: input/residual [T,H] and weight [H] of one dtype expected")
+    if T == 0:
+        return  # an empty torch tensor has a null data_ptr(), which the C entry point rejects
+    st = astra_fused_add_rmsnorm(input.data_ptr(), residual.data_ptr(), weight.data_ptr(), T, H, _dtype_code(input),
+                                 float(eps), _stream(stream))
+    if st:
+        raise AstraError(st, "astra_fused_add_rmsnorm")
+
+
+def silu_and_mul(out, input, stream=None) -> None:
+    """out[T,d] <- silu(input[:, :d]) * input[:, d:]."""
+    _check_gpu(out, input)
+    T, two_d = input.shape
+    if two_d % 2 or out.shape != (T, two_d // 2) or out.dtype != input.dtype:
+        raise ValueError("silu_and_mul: input [T,2d] and out [T,d] of one dtype expected")
+    if T == 0:
+        return
+    st = astra_silu_and_mul(out.data_ptr(), input.data_ptr(), T, two_d // 2, _dtype_code(input), _stream(stream))
+    if st:
+        raise AstraError(st, "astra_silu_and_mul")
+
+
+def merge_attn_states_lse(v_out, lse_out, v_a, lse_a, v_b, lse_b, stream=None) -> None:
+    """(v_out, lse_out) <- merge of the partial attention states (v_a, lse_a) and (v_b, lse_b)."""
+    import torch
+
+    _check_gpu(v_out, lse_out, v_a, lse_a, v_b, lse_b)
+    T, NH, D = v_a.shape
+    if v_b.shape != (T, NH, D) or v_out.shape != (T, NH, D) or v_b.dtype != v_a.dtype or v_out.dtype != v_a.dtype:
+        raise ValueError("merge_attn_states_lse: v tensors [T,NH,D] of one dtype expected")
+    for s in (lse_a, lse_b, lse_out):
+        if s.shape != (T, NH) or s.dtype != torch.float32:
+            raise ValueError("merge_attn_states_lse: lse tensors [T,NH] float32 expected")
+    if T == 0:
+        return
+    st = astra_merge_attn_states_lse(v_out.data_ptr(), lse_out.data_ptr(), v_a.data_ptr(), lse_a.data_ptr(),
+                                     v_b.data_ptr(), lse_b.data_ptr(), T, NH, D, _dtype_code(v_a), _stream(stream))
+    if st:
+        raise AstraError(st, "astra_merge_attn_states_lse")
+
+
+def stream_copy(dst, src, stream=None) -> None:
+    _check_gpu(dst, src)
+    n = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != n:
+        raise ValueError("stream_copy: sizes differ")
+    st = astra_stream_copy(dst.data_ptr(), src.data_ptr(), n, _stream(stream))
+    if st:
+        raise AstraError(st, "astra_stream_copy")

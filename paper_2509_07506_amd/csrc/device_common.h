@@ -1,0 +1,187 @@
+// Device-side building blocks shared by the three gfx950 kernels: 16-byte vector access, 16-bit
+// storage-type conversion, wave64 and workgroup sum reductions, and the fast transcendental forms.
+//
+// gfx950 only.  A wavefront is 64 lanes; one lane moves 16 bytes (8 storage elements) per access so a
+// wave covers 1 KiB of contiguous memory per instruction.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace astra {
+
+constexpr int kWave = 64;
+constexpr int kVecElems = 8;  // 16-bit elements per 16-byte vector
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+
+enum : int { kF16 = 0, kBF16 = 1 };
+
+// ---------------------------------------------------------------------------------------------
+// global memory access.  Activations are touched exactly once, so they are moved with the
+// non-temporal hint; small reused tensors (the rmsnorm weight, the scores) use plain loads.
+
+template <bool NT>
+__device__ __forceinline__ u32x4 load_vec(const u32x4* p)
+{
+    if constexpr (NT) return __builtin_nontemporal_load(p);
+    else return *p;
+}
+
+template <bool NT>
+__device__ __forceinline__ void store_vec(u32x4* p, u32x4 v)
+{
+    if constexpr (NT) __builtin_nontemporal_store(v, p);
+    else *p = v;
+}
+
+// ---------------------------------------------------------------------------------------------
+// storage types.  unpack2: one dword holding two 16-bit values -> two floats (exact).
+// pack2: two floats -> one dword, round-to-nearest-even (v_cvt_pk_bf16_f32 / v_cvt_pk_f16_f32).
+
+template <int DT>
+struct Storage;
+
+template <>
+struct Storage<kBF16> {
+    static __device__ __forceinline__ f32x2 unpack2(uint32_t w)
+    {
+        f32x2 r;
+        r.x = __builtin_bit_cast(float, w << 16);
+        r.y = __builtin_bit_cast(float, w & 0xffff0000u);
+        return r;
+    }
+    static __device__ __forceinline__ uint32_t pack2(float lo, float hi)
+    {
+        f32x2 v = {lo, hi};
+        return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+    }
+    static __device__ __forceinline__ float widen(uint16_t h) { return __builtin_bit_cast(float, (uint32_t)h << 16); }
+    static __device__ __forceinline__ uint16_t narrow(float f) { return __builtin_bit_cast(uint16_t, (__bf16)f); }
+};
+
+template <>
+struct Storage<kF16> {
+    static __device__ __forceinline__ f32x2 unpack2(uint32_t w)
+    {
+        return __builtin_convertvector(__builtin_bit_cast(f16x2, w), f32x2);
+    }
+    static __device__ __forceinline__ uint32_t pack2(float lo, float hi)
+    {
+        f32x2 v = {lo, hi};
+        return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2));
+    }
+    static __device__ __forceinline__ float widen(uint16_t h) { return (float)__builtin_bit_cast(_Float16, h); }
+    static __device__ __forceinline__ uint16_t narrow(float f) { return __builtin_bit_cast(uint16_t, (_Float16)f); }
+};
+
+template <int DT>
+__device__ __forceinline__ void unpack8(u32x4 v, float (&f)[8])
+{
+    f32x2 a = Storage<DT>::unpack2(v.x), b = Storage<DT>::unpack2(v.y);
+    f32x2 c = Storage<DT>::unpack2(v.z), d = Storage<DT>::unpack2(v.w);
+    f[0] = a.x; f[1] = a.y; f[2] = b.x; f[3] = b.y;
+    f[4] = c.x; f[5] = c.y; f[6] = d.x; f[7] = d.y;
+}
+
+template <int DT>
+__device__ __forceinline__ u32x4 pack8(const float (&f)[8])
+{
+    u32x4 v;
+    v.x = Storage<DT>::pack2(f[0], f[1]);
+    v.y = Storage<DT>::pack2(f[2], f[3]);
+    v.z = Storage<DT>::pack2(f[4], f[5]);
+    v.w = Storage<DT>::pack2(f[6], f[7]);
+    return v;
+}
+
+// ---------------------------------------------------------------------------------------------
+// fast transcendental forms: one hardware op each (v_exp_f32 is 2^x, v_log_f32 is log2), about 1 ulp.
+
+constexpr float kLog2e = 1.44269504088896340736f;
+constexpr float kLn2 = 0.69314718055994530942f;
+
+__device__ __forceinline__ float fast_exp(float x) { return __builtin_amdgcn_exp2f(x * kLog2e); }
+__device__ __forceinline__ float fast_log(float x) { return __builtin_amdgcn_logf(x) * kLn2; }
+__device__ __forceinline__ float fast_rcp(float x) { return __builtin_amdgcn_rcpf(x); }
+__device__ __forceinline__ float fast_rsqrt(float x) { return __builtin_amdgcn_rsqf(x); }
+
+// ---------------------------------------------------------------------------------------------
+// index arithmetic
+
+// n / d for a 32-bit n and a fixed divisor d >= 1, as a multiply-high and two shifts (Granlund and
+// Montgomery, "Division by invariant integers using multiplication", PLDI 1994, the unsigned
+// round-up variant).  Exact for every 32-bit n.  Built on the host, used on the device.
+struct FastDiv {
+    uint32_t mul;
+    uint32_t sh1;
+    uint32_t sh2;
+    __host__ __device__ __forceinline__ uint32_t div(uint32_t n) const
+    {
+#if defined(__HIP_DEVICE_COMPILE__)
+        uint32_t t = __umulhi(n, mul);
+#else
+        uint32_t t = (uint32_t)(((uint64_t)n * mul) >> 32);
+#endif
+        return (t + ((n - t) >> sh1)) >> sh2;
+    }
+};
+
+inline FastDiv make_fastdiv(uint32_t d)
+{
+    FastDiv f;
+    uint32_t l = 0;
+    while (l < 32 && (uint64_t(1) << l) < d) ++l;  // l = ceil(log2 d)
+    f.mul = (uint32_t)(((uint64_t(1) << 32) * ((uint64_t(1) << l) - d)) / d + 1);
+    f.sh1 = l < 1 ? l : 1;
+    f.sh2 = l < 1 ? 0 : l - 1;
+    return f;
+}
+
+// ---------------------------------------------------------------------------------------------
+// reductions
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v)
+{
+    // all rows, all banks, lanes without a source read 0 (never happens for the permutations used)
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
+}
+
+// Sum over the 64 lanes of a wave; the result is wave-uniform.  Four DPP steps leave every lane of
+// a 16-lane row with the row's sum (lane^1, lane^2, mirror within 8, mirror within 16); the four row
+// sums are then read through the scalar unit.  The order of additions is fixed, so the result is
+// reproducible from run to run.
+__device__ __forceinline__ float wave_sum(float v)
+{
+    v += dpp_move<0xB1>(v);   // quad_perm [1,0,3,2]
+    v += dpp_move<0x4E>(v);   // quad_perm [2,3,0,1]
+    v += dpp_move<0x141>(v);  // row_half_mirror
+    v += dpp_move<0x140>(v);  // row_mirror
+    int iv = __builtin_bit_cast(int, v);
+    float r0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 0));
+    float r1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 16));
+    float r2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 32));
+    float r3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 48));
+    return (r0 + r1) + (r2 + r3);
+}
+
+// Sum over a workgroup of `nwaves` full waves (blockDim.x == nwaves * 64, at most 16 waves).  One LDS
+// float per wave and one barrier; every lane then adds the partials in the same order.  `lds` must
+// hold 16 floats and must not be reused before the next barrier of the caller.
+__device__ __forceinline__ float block_sum(float v, float* lds, int nwaves)
+{
+    float w = wave_sum(v);
+    if (nwaves == 1) return w;
+    const int wave = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0) lds[wave] = w;
+    __syncthreads();
+    float total = lds[0];
+    for (int i = 1; i < nwaves; ++i) total += lds[i];
+    return total;
+}
+
+}  // namespace astra

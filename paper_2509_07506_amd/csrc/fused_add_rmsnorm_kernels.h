@@ -1,0 +1,111 @@
+// fused_add_rmsnorm for gfx950 -- paper Table 1, Kernel 2:
+//   y = (x + r) / sqrt(||x + r||^2 / H + eps) (.) w,  input <- y, residual <- x + r (both in place).
+//
+// One pass over HBM: a workgroup holds a whole row of binary32 sums in registers (VPT vectors of 8
+// per lane), so x and r are read once and each written once.  The sum of squares is reduced inside
+// each wave with DPP (registers only) and across waves through one LDS float per wave and a single
+// barrier -- the register-first reduction of the paper's Fig. 3b, on 64-lane waves.
+#pragma once
+
+#include "device_common.h"
+
+namespace astra {
+
+// Fast path: H % 8 == 0, 16-byte aligned pointers, hv = H/8 <= VPT * blockDim.x.
+// blockDim.x is a multiple of 64 and at most MAX_THREADS.  Lane `tid` owns vectors tid + k*blockDim.x.
+// A block walks rows blockIdx.x, blockIdx.x + gridDim.x, ... (normally exactly one row).
+template <int DT, int VPT, int MAX_THREADS, bool NT>
+__global__ __launch_bounds__(MAX_THREADS) void fused_add_rmsnorm_row_kernel(u32x4* input, u32x4* residual,
+                                                                            const u32x4* __restrict__ weight,
+                                                                            int64_t T, uint32_t hv, float inv_h, float eps)
+{
+    __shared__ float partials[2][16];
+    const int nwaves = blockDim.x >> 6;
+    int parity = 0;
+
+    // the weight does not depend on the row: fetch it once (L2 resident, shared by all blocks)
+    u32x4 wv[VPT];
+#pragma unroll
+    for (int k = 0; k < VPT; ++k) {
+        const uint32_t v = threadIdx.x + k * blockDim.x;
+        if (v < hv) wv[k] = weight[v];
+    }
+
+    for (int64_t row = blockIdx.x; row < T; row += gridDim.x, parity ^= 1) {
+        u32x4* xrow = input + row * hv;
+        u32x4* rrow = residual + row * hv;
+        u32x4 xv[VPT], rv[VPT];
+#pragma unroll
+        for (int k = 0; k < VPT; ++k) {
+            const uint32_t v = threadIdx.x + k * blockDim.x;
+            if (v < hv) {
+                xv[k] = load_vec<NT>(xrow + v);
+                rv[k] = load_vec<NT>(rrow + v);
+            }
+        }
+
+        float s[VPT][8];
+        float acc = 0.0f;
+#pragma unroll
+        for (int k = 0; k < VPT; ++k) {
+            const uint32_t v = threadIdx.x + k * blockDim.x;
+            if (v < hv) {
+                float x[8], r[8];
+                unpack8<DT>(xv[k], x);
+                unpack8<DT>(rv[k], r);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    s[k][e] = x[e] + r[e];
+                    acc += s[k][e] * s[k][e];
+                }
+                store_vec<NT>(rrow + v, pack8<DT>(s[k]));
+            }
+        }
+
+        const float total = block_sum(acc, partials[parity], nwaves);
+        const float scale = fast_rsqrt(total * inv_h + eps);
+
+#pragma unroll
+        for (int k = 0; k < VPT; ++k) {
+            const uint32_t v = threadIdx.x + k * blockDim.x;
+            if (v < hv) {
+                float w[8], y[8];
+                unpack8<DT>(wv[k], w);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) y[e] = (s[k][e] * scale) * w[e];
+                store_vec<NT>(xrow + v, pack8<DT>(y));
+            }
+        }
+    }
+}
+
+// Element-wise path for any H and 2-byte aligned pointers: two passes over the row.  The first pass
+// only reads (it needs the unrounded sums, so the residual cannot be written yet); the second
+// recomputes x + r, stores it and the normalised value.  Each element is read and written by the
+// same lane, so the in-place update is safe.
+template <int DT>
+__global__ __launch_bounds__(256) void fused_add_rmsnorm_generic_kernel(uint16_t* input, uint16_t* residual,
+                                                                        const uint16_t* __restrict__ weight, int64_t T,
+                                                                        int64_t H, float inv_h, float eps)
+{
+    __shared__ float partials[2][16];
+    int parity = 0;
+    for (int64_t row = blockIdx.x; row < T; row += gridDim.x, parity ^= 1) {
+        uint16_t* x = input + row * H;
+        uint16_t* r = residual + row * H;
+        float acc = 0.0f;
+        for (int64_t j = threadIdx.x; j < H; j += blockDim.x) {
+            float s = Storage<DT>::widen(x[j]) + Storage<DT>::widen(r[j]);
+            acc += s * s;
+        }
+        const float total = block_sum(acc, partials[parity], blockDim.x >> 6);
+        const float scale = fast_rsqrt(total * inv_h + eps);
+        for (int64_t j = threadIdx.x; j < H; j += blockDim.x) {
+            float s = Storage<DT>::widen(x[j]) + Storage<DT>::widen(r[j]);
+            r[j] = Storage<DT>::narrow(s);
+            x[j] = Storage<DT>::narrow((s * scale) * Storage<DT>::widen(weight[j]));
+        }
+    }
+}
+
+}  // namespace astra

@@ -1,0 +1,80 @@
+// silu_and_mul for gfx950 -- paper Table 1, Kernel 3: out = SiLU(x) (.) g, SiLU(z) = z / (1 + e^-z).
+//
+// The operator is a pure stream: 2 input vectors and 1 output vector per 8 results, no reuse.  The
+// fast kernel gives every lane 16-byte accesses and `UNROLL` independent vector pairs so that enough
+// bytes are in flight per CU, and keeps the transcendental cost at one v_exp_f32 and one v_rcp_f32
+// per element (the reciprocal-multiply form of the paper's Fig. 5b; the plain divide of Fig. 5a
+// expands to a long IEEE division sequence).
+#pragma once
+
+#include "device_common.h"
+
+namespace astra {
+
+__device__ __forceinline__ float silu_fast(float x)
+{
+    // x * 1/(1 + 2^(-x log2 e)).  x << 0: 2^(+big) = inf, 1/inf = 0, x * 0 = -0, the limit value.
+    return x * fast_rcp(1.0f + __builtin_amdgcn_exp2f(x * -kLog2e));
+}
+
+// Fast path: d % 8 == 0 and 16-byte aligned pointers.  Work is the flat list of output vectors
+// (dv = d/8 per row); a block owns 256*UNROLL consecutive ones.  The row of the block's first vector
+// comes from one scalar fast division; lanes then step to the next row when they run past the end
+// of a row (at most a few steps because the host only takes this path when dv >= 32).
+// For output vector (t, j):  x = in[t*2dv + j], g = in[t*2dv + dv + j], out index = t*dv + j.
+template <int DT, int UNROLL, bool NT>
+__global__ __launch_bounds__(256) void silu_and_mul_vec_kernel(u32x4* __restrict__ out, const u32x4* __restrict__ in,
+                                                               uint32_t total_vecs, uint32_t dv, FastDiv by_dv)
+{
+    constexpr uint32_t kSpan = 256u * UNROLL;
+    const uint32_t first = blockIdx.x * kSpan;
+    const uint32_t t0 = by_dv.div(first);
+    const uint32_t j0 = first - t0 * dv;
+
+    u32x4 xv[UNROLL], gv[UNROLL];
+    uint32_t oidx[UNROLL];
+#pragma unroll
+    for (int k = 0; k < UNROLL; ++k) {
+        const uint32_t off = threadIdx.x + 256u * k;
+        oidx[k] = first + off;
+        uint32_t t = t0, j = j0 + off;
+        while (j >= dv) {
+            j -= dv;
+            ++t;
+        }
+        if (oidx[k] < total_vecs) {
+            const u32x4* px = in + (t * 2u * dv + j);  // the host keeps 2*T*dv within 32 bits
+            xv[k] = load_vec<NT>(px);
+            gv[k] = load_vec<NT>(px + dv);
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < UNROLL; ++k) {
+        if (oidx[k] < total_vecs) {
+            float x[8], g[8], o[8];
+            unpack8<DT>(xv[k], x);
+            unpack8<DT>(gv[k], g);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] = silu_fast(x[e]) * g[e];
+            store_vec<NT>(out + oidx[k], pack8<DT>(o));
+        }
+    }
+}
+
+// Element-wise path for any d and any 2-byte aligned pointers: one block walks one row at a time.
+template <int DT>
+__global__ __launch_bounds__(256) void silu_and_mul_generic_kernel(uint16_t* __restrict__ out,
+                                                                   const uint16_t* __restrict__ in, int64_t T, int64_t d)
+{
+    for (int64_t t = blockIdx.x; t < T; t += gridDim.x) {
+        const uint16_t* row = in + t * 2 * d;
+        uint16_t* orow = out + t * d;
+        for (int64_t j = threadIdx.x; j < d; j += blockDim.x) {
+            float x = Storage<DT>::widen(row[j]);
+            float g = Storage<DT>::widen(row[d + j]);
+            orow[j] = Storage<DT>::narrow(silu_fast(x) * g);
+        }
+    }
+}
+
+}  // namespace astra

@@ -1,0 +1,147 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the headers
+declare, rejects bad arguments before touching the device, and plans launches sensibly."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def A():
+    import paper_2509_07506_amd as astra
+
+    if not os.path.exists(astra.library_path()):
+        from paper_2509_07506_amd import build
+
+        build.build()
+    astra.load_library()
+    return astra
+
+
+def _declared_functions():
+    names = []
+    for h in sorted(os.listdir(os.path.join(ROOT, "include"))):
+        text = open(os.path.join(ROOT, "include", h)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names += re.findall(r"\b(astra_[a-z0-9_]+)\s*\(", text)
+    return sorted(set(names))
+
+
+def test_every_declared_symbol_is_exported(A):
+    L = ctypes.CDLL(A.library_path())
+    declared = _declared_functions()
+    assert {"astra_fused_add_rmsnorm", "astra_silu_and_mul", "astra_merge_attn_states_lse", "astra_status_string",
+            "astra_stream_copy", "astra_plan_fused_add_rmsnorm", "astra_plan_silu_and_mul",
+            "astra_plan_merge_attn_states_lse"} <= set(declared)
+    for name in declared:
+        assert hasattr(L, name), f"{name} declared in include/ but not exported"
+
+
+def test_status_strings(A):
+    seen = {A.astra_status_string(i) for i in range(8)}
+    assert len(seen) == 8 and A.astra_status_string(0) == "ok"
+    assert "unknown" in A.astra_status_string(99)
+
+
+def test_rmsnorm_validation_order(A):
+    f = A.astra_fused_add_rmsnorm
+    a, b, c = 0x10000, 0x20000, 0x30000          # never dereferenced: every call below fails validation
+    assert f(0, b, c, 1, 8, 1, 1e-6) == 1 and f(a, 0, c, 1, 8, 1, 1e-6) == 1 and f(a, b, 0, 1, 8, 1, 1e-6) == 1
+    assert f(a, b, c, -1, 8, 1, 1e-6) == 2 and f(a, b, c, 1, 0, 1, 1e-6) == 2 and f(a, b, c, 1 << 40, 1 << 40, 1, 1e-6) == 2
+    assert f(a, b, c, 1, 8, 2, 1e-6) == 3 and f(a, b, c, 1, 8, -1, 1e-6) == 3
+    assert f(a, b, c, 1, 8, 1, -1e-6) == 4 and f(a, b, c, 1, 8, 1, float("nan")) == 4
+    assert f(a + 1, b, c, 1, 8, 1, 1e-6) == 5
+    assert f(a, a + 8, c, 1, 8, 1, 1e-6) == 6 and f(a, b, a + 2, 1, 8, 1, 1e-6) == 6
+    # precedence: null before shape before dtype before eps before alignment before aliasing
+    assert f(0, b, c, -1, 8, 7, -1.0) == 1
+    assert f(a, b, c, -1, 8, 7, -1.0) == 2
+    assert f(a, b, c, 1, 8, 7, -1.0) == 3
+    assert f(a + 1, b, c, 1, 8, 1, -1.0) == 4
+    assert f(a + 1, a + 3, c, 1, 8, 1, 1.0) == 5
+    # T == 0 is fine and launches nothing (works without a GPU)
+    assert f(a, b, c, 0, 8, 1, 1e-6) == 0
+
+
+def test_silu_validation(A):
+    f = A.astra_silu_and_mul
+    a, b = 0x10000, 0x40000
+    assert f(0, b, 1, 8, 1) == 1 and f(a, 0, 1, 8, 1) == 1
+    assert f(a, b, -2, 8, 1) == 2 and f(a, b, 1, 0, 1) == 2 and f(a, b, 1 << 62, 8, 1) == 2
+    assert f(a, b, 1, 8, 3) == 3
+    assert f(a + 1, b, 1, 8, 1) == 5
+    assert f(a, a + 16, 4, 8, 1) == 6 and f(a + 32, a, 4, 8, 1) == 6
+    assert f(a, b, 0, 8, 0) == 0
+
+
+def test_merge_validation(A):
+    f = A.astra_merge_attn_states_lse
+    vo, lo, va, la, vb, lb = 0x10000, 0x20000, 0x30000, 0x40000, 0x50000, 0x60000
+    for i in range(6):
+        args = [vo, lo, va, la, vb, lb]
+        args[i] = 0
+        assert f(*args, 1, 2, 8, 1) == 1
+    assert f(vo, lo, va, la, vb, lb, -1, 2, 8, 1) == 2 and f(vo, lo, va, la, vb, lb, 1, 0, 8, 1) == 2
+    assert f(vo, lo, va, la, vb, lb, 1, 2, 0, 1) == 2 and f(vo, lo, va, la, vb, lb, 1 << 30, 1 << 30, 1 << 30, 1) == 2
+    assert f(vo, lo, va, la, vb, lb, 1, 2, 8, 4) == 3
+    assert f(vo, lo + 2, va, la, vb, lb, 1, 2, 8, 1) == 5 and f(vo + 1, lo, va, la, vb, lb, 1, 2, 8, 1) == 5
+    assert f(vo, lo, vo + 2, la, vb, lb, 4, 2, 8, 1) == 6          # partial overlap of v_out and v_a
+    assert f(vo, la, va, la, vb, lb, 4, 2, 8, 1) == 6              # lse_out on lse_a
+    assert f(vo, lo, va, la, vb, lb, 0, 2, 8, 1) == 0
+    assert f(va, lo, va, la, vb, lb, 0, 2, 8, 1) == 0              # exact aliasing of v_out and v_a is allowed
+
+
+def test_stream_copy_validation(A):
+    f = A.astra_stream_copy
+    assert f(0, 16, 16) == 1 and f(0x1000, 0x2000, -16) == 2 and f(0x1000, 0x2000, 24) == 2
+    assert f(0x1008, 0x2000, 16) == 5 and f(0x1000, 0x1010, 32) == 6 and f(0x1000, 0x2000, 0) == 0
+
+
+def test_rmsnorm_plans(A):
+    def plan(T, H, al=True):
+        st, i = A.astra_plan_fused_add_rmsnorm(T, H, al)
+        assert st == 0
+        return i.as_dict()
+
+    assert plan(0, 4096)["path"] == "none"
+    for T in (1, 8, 64):                      # decode: widest block, one vector per lane
+        p = plan(T, 8192)
+        assert p == {"path": "vector", "block": 1024, "vectors_per_lane": 1, "grid": T}
+    assert plan(16, 4096) == {"path": "vector", "block": 512, "vectors_per_lane": 1, "grid": 16}
+    for T, H in [(8192, 8192), (32768, 8192), (4099, 5120), (4099, 7168), (1024, 4096), (512, 14336), (128, 11008)]:
+        p = plan(T, H)
+        assert p["path"] == "vector" and p["grid"] == T and p["block"] % 64 == 0 and p["block"] <= 1024
+        assert p["block"] * p["vectors_per_lane"] * 8 >= H           # the whole row is register resident
+        assert p["block"] * p["vectors_per_lane"] * 8 < 1.25 * H + 512
+    assert plan(4, 4100)["path"] == "generic" and plan(4, 4096, al=False)["path"] == "generic"
+    assert plan(4, 65536)["path"] == "generic"
+    assert plan(1 << 23, 64)["grid"] < (1 << 22)                      # row loop beyond the grid limit
+    assert A.astra_plan_fused_add_rmsnorm(-1, 8, True)[0] == 2
+
+
+def test_silu_and_merge_plans(A):
+    st, i = A.astra_plan_silu_and_mul(4096, 14336, True)
+    p = i.as_dict()
+    assert st == 0 and p["path"] == "vector"
+    assert p["grid"] * p["block"] * p["vectors_per_lane"] >= 4096 * 14336 // 8
+    assert p["grid"] * p["block"] * p["vectors_per_lane"] < 4096 * 14336 // 8 + p["block"] * p["vectors_per_lane"]
+    assert A.astra_plan_silu_and_mul(3, 100, True)[1].as_dict()["path"] == "generic"
+    assert A.astra_plan_silu_and_mul(3, 1408, False)[1].as_dict()["path"] == "generic"
+    assert A.astra_plan_silu_and_mul(3, 128, True)[1].as_dict()["path"] == "generic"      # rows shorter than 32 vectors
+    assert A.astra_plan_silu_and_mul(1 << 20, 1 << 14, True)[1].as_dict()["path"] == "generic"  # beyond 32-bit vector indices
+    st, i = A.astra_plan_merge_attn_states_lse(4096, 32, 128, True)
+    p = i.as_dict()
+    assert st == 0 and p["path"] == "vector" and p["grid"] * p["block"] * p["vectors_per_lane"] == 4096 * 32 * 16
+    assert A.astra_plan_merge_attn_states_lse(3, 5, 4, True)[1].as_dict()["path"] == "generic"
+    assert A.astra_plan_merge_attn_states_lse(3, 5, 72, True)[1].as_dict()["path"] == "vector"
+    assert A.astra_plan_merge_attn_states_lse(0, 5, 72, True)[1].as_dict()["path"] == "none"
+
+
+def test_binding_refuses_cpu_tensors(A):
+    import torch
+
+    x = torch.zeros((2, 64), dtype=torch.bfloat16)
+    with pytest.raises(ValueError):
+        A.fused_add_rmsnorm(x, x.clone(), torch.ones(64, dtype=torch.bfloat16), 1e-6)
