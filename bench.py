@@ -2,11 +2,11 @@
 """Benchmark of the astra HIP library on one MI355X.
 
 One "step" is one pass of the whole hot path over one batch of synthetic input: fused_add_rmsnorm
-(T=8192, H=8192), silu_and_mul (T=4096, d=14336) and merge_attn_states_lse (T=4096, 32 heads x 128),
-all bf16 storage with binary32 arithmetic -- the bandwidth-regime workloads of the benchmark's config
-list.  Inputs are resident in HBM before the timed region.  The three kernels of a step move ~990 MB
-between them, so no launch finds its operands in the 256 MB last-level cache: every figure is a
-cold-cache (HBM) figure.
+(T=32768, H=8192), silu_and_mul (T=4096, d=14336) and merge_attn_states_lse (T=4096, 32 heads x 128),
+all bf16 storage with binary32 arithmetic -- the large-T, bandwidth-regime workloads of the benchmark's
+config list.  Inputs are resident in HBM before the timed region.  The three kernels of a step move
+~2.6 GB between them, so no launch finds its operands in the 256 MB last-level cache: every figure is
+a cold-cache (HBM) figure.
 
 Prints ONE JSON line.  `value` is the whole step's algorithmic bytes over its wall time; `roofline`
 prices the dominant kernel (fused_add_rmsnorm) against the 8 TB/s HBM peak using HIP-event durations
@@ -15,6 +15,7 @@ taken inside the timed region on the launch stream; `kernels` carries the same f
 
     python bench.py [--gpus 1] [--steps K] [--warmup W]
     python bench.py --sweep          # per-workload table over every config (one JSON line per case)
+    python bench.py --ceiling        # streaming-copy ceiling of the machine (same access pattern)
 """
 from __future__ import annotations
 
@@ -30,7 +31,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E peak
 METRIC = "achieved HBM GB/s and % of MI355X peak per kernel (rmsnorm, silu_mul, lse merge)"
-STEP_CASES = ("c3_rmsnorm_T8192_H8192_bf16", "c1_silu_T4096_d14336_bf16", "c2_merge_T4096_NH32_D128_bf16")
+STEP_CASES = ("c3_rmsnorm_T32768_H8192_bf16", "c1_silu_T4096_d14336_bf16", "c2_merge_T4096_NH32_D128_bf16")
 KERNEL_NAMES = {"rmsnorm": "fused_add_rmsnorm_row_kernel", "silu": "silu_and_mul_vec_kernel",
                 "merge": "merge_attn_states_lse_vec_kernel"}
 
@@ -44,42 +45,60 @@ def _to_dev(bits, dt):
 
 
 class Launcher:
-    """Device buffers of one workload and a closure that enqueues its kernel on torch's current stream."""
+    """Device buffers of one workload (optionally `nsets` independent copies, used round-robin so that no
+    launch re-reads cache-resident bytes) and a closure that enqueues its kernel on a given stream."""
 
-    def __init__(self, astra, case, data):
+    def __init__(self, astra, case, data, nsets: int = 1):
         import torch
 
         self.case = case
+        self.nsets = nsets
         dt = case.dtype
         tdt = {"bf16": torch.bfloat16, "f16": torch.float16}[dt]
         code = astra.ASTRA_BF16 if dt == "bf16" else astra.ASTRA_F16
         s = case.shape
+
+        def pool(t):
+            # [nsets, ...] copies of one tensor, each copy 256-byte aligned
+            n = t.numel()
+            stride = -(-n * t.element_size() // 256) * 256 // t.element_size()
+            p = torch.empty(nsets * stride, dtype=t.dtype, device="cuda")
+            p.view(nsets, stride)[:, :n] = t.reshape(1, n)
+            return p, stride * t.element_size()
+
         if case.kernel == "rmsnorm":
             x, r, w = (_to_dev(a, dt) for a in data)
-            self.bufs = (x, r, w)
-            args = (x.data_ptr(), r.data_ptr(), w.data_ptr(), s["T"], s["H"], code, case.eps)
-            self.fn = lambda st: astra.astra_fused_add_rmsnorm(*args, st)
-            self.plan = astra.astra_plan_fused_add_rmsnorm(s["T"], s["H"], True)[1].as_dict()
+            (xp, xs), (rp, rs) = pool(x), pool(r)
+            self.bufs = (xp, rp, w)
+            T, H, eps = s["T"], s["H"], case.eps
+            x0, r0, w0 = xp.data_ptr(), rp.data_ptr(), w.data_ptr()
+            self.fn = lambda k, st: astra.astra_fused_add_rmsnorm(x0 + k * xs, r0 + k * rs, w0, T, H, code, eps, st)
+            self.plan = astra.astra_plan_fused_add_rmsnorm(T, H, True)[1].as_dict()
         elif case.kernel == "silu":
             a = _to_dev(data[0], dt)
-            out = torch.empty((s["T"], s["d"]), dtype=tdt, device="cuda")
-            self.bufs = (a, out)
-            args = (out.data_ptr(), a.data_ptr(), s["T"], s["d"], code)
-            self.fn = lambda st: astra.astra_silu_and_mul(*args, st)
-            self.plan = astra.astra_plan_silu_and_mul(s["T"], s["d"], True)[1].as_dict()
+            ap, as_ = pool(a)
+            op, os_ = pool(torch.empty((s["T"], s["d"]), dtype=tdt, device="cuda"))
+            self.bufs = (ap, op)
+            T, d = s["T"], s["d"]
+            a0, o0 = ap.data_ptr(), op.data_ptr()
+            self.fn = lambda k, st: astra.astra_silu_and_mul(o0 + k * os_, a0 + k * as_, T, d, code, st)
+            self.plan = astra.astra_plan_silu_and_mul(T, d, True)[1].as_dict()
         else:
             va, la, vb, lb = data
             va, vb = _to_dev(va, dt), _to_dev(vb, dt)
             la, lb = torch.from_numpy(la).cuda(), torch.from_numpy(lb).cuda()
-            vo, lo = torch.empty_like(va), torch.empty_like(la)
-            self.bufs = (va, la, vb, lb, vo, lo)
-            args = (vo.data_ptr(), lo.data_ptr(), va.data_ptr(), la.data_ptr(), vb.data_ptr(), lb.data_ptr(), s["T"],
-                    s["NH"], s["D"], code)
-            self.fn = lambda st: astra.astra_merge_attn_states_lse(*args, st)
-            self.plan = astra.astra_plan_merge_attn_states_lse(s["T"], s["NH"], s["D"], True)[1].as_dict()
+            (vap, vs), (vbp, _), (vop, _) = pool(va), pool(vb), pool(torch.empty_like(va))
+            (lap, ls), (lbp, _), (lop, _) = pool(la), pool(lb), pool(torch.empty_like(la))
+            self.bufs = (vap, vbp, vop, lap, lbp, lop)
+            T, NH, D = s["T"], s["NH"], s["D"]
+            p = [t.data_ptr() for t in (vop, lop, vap, lap, vbp, lbp)]
+            self.fn = lambda k, st: astra.astra_merge_attn_states_lse(p[0] + k * vs, p[1] + k * ls, p[2] + k * vs,
+                                                                      p[3] + k * ls, p[4] + k * vs, p[5] + k * ls, T, NH, D,
+                                                                      code, st)
+            self.plan = astra.astra_plan_merge_attn_states_lse(T, NH, D, True)[1].as_dict()
 
-    def launch(self, stream_handle):
-        st = self.fn(stream_handle)
+    def launch(self, stream_handle, k: int = 0):
+        st = self.fn(k % self.nsets, stream_handle)
         if st != 0:
             raise RuntimeError(f"{self.case.name}: astra status {st}")
 
@@ -150,9 +169,23 @@ def run_step_bench(args):
     stream = torch.cuda.current_stream()
     sh = stream.cuda_stream
 
+    copy_bufs = None
+    if args.with_copy:
+        # profiling aid: a plain copy of known size after each step calibrates the FETCH_SIZE / WRITE_SIZE
+        # counters; it makes the step longer, so a run with it is not a benchmark result
+        n = 512 << 20
+        copy_bufs = (torch.empty(n, dtype=torch.uint8, device="cuda"), torch.zeros(n, dtype=torch.uint8, device="cuda"))
+
+    def extra():
+        if copy_bufs is not None:
+            st = astra.astra_stream_copy(copy_bufs[0].data_ptr(), copy_bufs[1].data_ptr(), copy_bufs[0].numel(), sh)
+            if st != 0:
+                raise RuntimeError(f"astra_stream_copy: status {st}")
+
     for _ in range(args.warmup):
         for L in launchers:
             L.launch(sh)
+        extra()
     torch.cuda.synchronize()
 
     K = args.steps
@@ -164,6 +197,7 @@ def run_step_bench(args):
         for i, L in enumerate(launchers):
             L.launch(sh)
             ev[k][i + 1].record(stream)
+        extra()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
 
@@ -178,7 +212,8 @@ def run_step_bench(args):
             "avg_us": round(avg * 1e3, 3), "median_us": round(_median(d_ms) * 1e3, 3), "min_us": round(min(d_ms) * 1e3, 3),
             "achieved_GBs": round(b / (avg * 1e-3) / 1e9, 1), "frac_of_peak": round(b / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
             "tokens_per_s": round(c.tokens() / (avg * 1e-3), 1),
-            "traffic": traffic.get(c.name),
+            "traffic": (traffic.get(c.name) or {}).get("total_bytes"),
+            "traffic_detail": traffic.get(c.name),
         }
     total_bytes = sum(c.algorithmic_bytes() for c in cases)
     dom = max(per_kernel.values(), key=lambda r: r["avg_us"])
@@ -187,13 +222,16 @@ def run_step_bench(args):
         "warmup": args.warmup, "ms_per_step": round(wall / K * 1e3, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": "+".join(STEP_CASES), "storage_dtype": "bf16", "bytes_per_step": total_bytes,
-                   "cache": "cold (a step streams ~990 MB through a 256 MB last-level cache)"},
+                   "cache": "cold (a step streams ~2.6 GB through a 256 MB last-level cache)"},
         "roofline": {"bound": "hbm", "kernel": dom["kernel"], "workload": dom["workload"],
                      "achieved": dom["achieved_GBs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(dom["achieved_GBs"] / HBM_PEAK_GBS, 4), "traffic": dom["traffic"],
                      "avg_launch_us": dom["avg_us"]},
         "kernels": per_kernel,
     }
+    if args.with_copy:
+        out["config"]["profiling_copy_bytes"] = 512 << 20
+        out["value"] = None  # not a benchmark result
     if not args.no_cpu:
         del launchers
         torch.cuda.empty_cache()
@@ -203,7 +241,8 @@ def run_step_bench(args):
 
 def run_sweep(args):
     """Per-workload figures over every config: 20 warm-up + 100 timed launches (the paper's protocol,
-    Section 4), rotating over enough buffer sets that no launch re-reads cache-resident data."""
+    Section 4).  "cold": the launches rotate over enough independent buffer sets (>= 1 GiB in total, at
+    most 4096 sets) that no launch finds its operands in the 256 MB last-level cache; "hot": one set."""
     import torch
 
     import paper_2509_07506_amd as astra
@@ -218,38 +257,73 @@ def run_sweep(args):
         c = workloads.case(n)
         data = c.generate()
         ws = c.algorithmic_bytes()
-        nsets = 1 if ws > (512 << 20) else min(64, max(2, -(-(1 << 30) // max(ws, 1)) + 1))
-        sets = [Launcher(astra, c, data) for _ in range(nsets)]
+        nsets = 1 if ws > (512 << 20) else min(4096, max(2, -(-(1 << 30) // max(ws, 1)) + 1))
+        L = Launcher(astra, c, data, nsets)
         for hot in (False, True):
             reps, warm = 100, 20
-            pick = (lambda k: sets[0]) if hot else (lambda k: sets[k % nsets])
+            pick = (lambda k: 0) if hot else (lambda k: k)
             for k in range(warm):
-                pick(k).launch(sh)
+                L.launch(sh, pick(k))
             evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
             torch.cuda.synchronize()
             for k in range(reps):
                 evs[k][0].record(stream)
-                pick(k).launch(sh)
+                L.launch(sh, pick(warm + k))
                 evs[k][1].record(stream)
             torch.cuda.synchronize()
             d = [a.elapsed_time(b) for a, b in evs]
-            # one event pair around a batch: for sub-10 us kernels the per-launch event cost matters
-            torch.cuda.synchronize()
+            # one event pair around the whole batch: per-launch event cost matters for sub-10 us kernels
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record(stream)
             for k in range(reps):
-                pick(k).launch(sh)
+                L.launch(sh, pick(warm + k))
             e1.record(stream)
             torch.cuda.synchronize()
             batch_us = e0.elapsed_time(e1) * 1e3 / reps
             med = _median(d) * 1e-3
             print(json.dumps({"case": n, "cache": "hot" if hot else "cold", "buffer_sets": 1 if hot else nsets,
-                              "launch": sets[0].plan, "bytes": ws, "median_us": round(med * 1e6, 2),
+                              "rotation_bytes": ws * (1 if hot else nsets),
+                              "launch": L.plan, "bytes": ws, "median_us": round(med * 1e6, 2),
                               "min_us": round(min(d) * 1e3, 2), "batch_avg_us": round(batch_us, 2),
                               "GBs": round(ws / med / 1e9, 1), "frac_of_peak": round(ws / med / 1e9 / HBM_PEAK_GBS, 4),
                               "tokens_per_s": round(c.tokens() / med, 1)}), flush=True)
-        del sets
+        del L
         torch.cuda.empty_cache()
+
+
+def run_ceiling(args):
+    """Streaming ceiling of this machine with the operators' access pattern: astra_stream_copy over
+    512 MiB, alternating between two source/destination pairs (2 GiB footprint, so always cold)."""
+    import torch
+
+    import paper_2509_07506_amd as astra
+
+    astra.load_library()
+    torch.cuda.set_device(0)
+    stream = torch.cuda.current_stream()
+    sh = stream.cuda_stream
+    n = 512 << 20
+    src = [torch.zeros(n, dtype=torch.uint8, device="cuda") for _ in range(2)]
+    dst = [torch.empty(n, dtype=torch.uint8, device="cuda") for _ in range(2)]
+    reps, warm = 100, 20
+
+    def go(k):
+        st = astra.astra_stream_copy(dst[k & 1].data_ptr(), src[k & 1].data_ptr(), n, sh)
+        if st != 0:
+            raise RuntimeError(f"astra_stream_copy: status {st}")
+
+    for k in range(warm):
+        go(k)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for k in range(reps):
+        go(k)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    us = e0.elapsed_time(e1) * 1e3 / reps
+    print(json.dumps({"case": "stream_copy_512MiB", "cache": "cold", "bytes": 2 * n, "batch_avg_us": round(us, 2),
+                      "GBs": round(2 * n / us / 1e3, 1), "frac_of_peak": round(2 * n / us / 1e3 / HBM_PEAK_GBS, 4)}), flush=True)
 
 
 def main():
@@ -258,14 +332,19 @@ def main():
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--with-copy", action="store_true",
+                    help="profiling aid: add a 512 MiB astra_stream_copy to every step (counter calibration)")
     ap.add_argument("--sweep", action="store_true", help="per-workload table over every config")
     ap.add_argument("--only", default=None, help="with --sweep: substring filter on the case name")
+    ap.add_argument("--ceiling", action="store_true", help="measure the streaming-copy ceiling of the machine")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this path runs on ONE GPU (row-independent kernels, no collectives); "
               "--gpus N with N > 1 is not supported", file=sys.stderr)
         sys.exit(2)
-    if args.sweep:
+    if args.ceiling:
+        run_ceiling(args)
+    elif args.sweep:
         run_sweep(args)
     else:
         run_step_bench(args)

@@ -24,8 +24,8 @@ typedef struct {
     int32_t path;             /* astra_path_t */
     int32_t block;            /* work-items per workgroup */
     int32_t vectors_per_lane; /* 16-byte vectors each lane keeps in flight (0 on the generic path) */
-    int32_t reserved;
-    int64_t grid;             /* workgroups */
+    int32_t log2_xcd_chunk;   /* workgroups an XCD runs back to back cover 2^this consecutive work units */
+    int64_t grid;             /* workgroups launched (padded to a multiple of 8 * 2^log2_xcd_chunk) */
 } astra_launch_info_t;
 
 /* `aligned16` tells whether every tensor pointer of the call is 16-byte aligned (non-zero = yes).
@@ -34,6 +34,12 @@ astra_status_t astra_plan_fused_add_rmsnorm(int64_t T, int64_t H, int aligned16,
 astra_status_t astra_plan_silu_and_mul(int64_t T, int64_t d, int aligned16, astra_launch_info_t* info);
 astra_status_t astra_plan_merge_attn_states_lse(int64_t T, int64_t num_heads, int64_t head_dim, int aligned16,
                                                 astra_launch_info_t* info);
+
+/* The map from workgroup index to work unit that the kernels apply when log2_xcd_chunk > 0 (the same
+ * function the device code runs): workgroup b executes on XCD b % 8, and the workgroups of one XCD are
+ * given runs of 2^log2_chunk consecutive units.  A permutation of [0, G) for every G that is a multiple
+ * of 8 * 2^log2_chunk.  log2_chunk outside [0, 8] returns `workgroup` unchanged. */
+uint32_t astra_plan_xcd_chunked(uint32_t workgroup, int log2_chunk);
 
 #ifdef __cplusplus
 }

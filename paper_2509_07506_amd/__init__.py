@@ -14,6 +14,7 @@ from .binding import (  # noqa: F401
     astra_plan_fused_add_rmsnorm,
     astra_plan_merge_attn_states_lse,
     astra_plan_silu_and_mul,
+    astra_plan_xcd_chunked,
     astra_silu_and_mul,
     astra_status_string,
     astra_stream_copy,

@@ -31,11 +31,11 @@ class AstraError(RuntimeError):
 
 class LaunchInfo(ctypes.Structure):
     _fields_ = [("path", ctypes.c_int32), ("block", ctypes.c_int32), ("vectors_per_lane", ctypes.c_int32),
-                ("reserved", ctypes.c_int32), ("grid", ctypes.c_int64)]
+                ("log2_xcd_chunk", ctypes.c_int32), ("grid", ctypes.c_int64)]
 
     def as_dict(self):
         return {"path": {0: "none", 1: "vector", 2: "generic"}[self.path], "block": self.block,
-                "vectors_per_lane": self.vectors_per_lane, "grid": self.grid}
+                "vectors_per_lane": self.vectors_per_lane, "log2_xcd_chunk": self.log2_xcd_chunk, "grid": self.grid}
 
 
 def library_path() -> str:
@@ -66,6 +66,8 @@ def load_library() -> ctypes.CDLL:
     L.astra_plan_fused_add_rmsnorm.argtypes = [i64, i64, i32, pinfo]
     L.astra_plan_silu_and_mul.argtypes = [i64, i64, i32, pinfo]
     L.astra_plan_merge_attn_states_lse.argtypes = [i64, i64, i64, i32, pinfo]
+    L.astra_plan_xcd_chunked.argtypes = [ctypes.c_uint32, i32]
+    L.astra_plan_xcd_chunked.restype = ctypes.c_uint32
     for n in ("astra_fused_add_rmsnorm", "astra_silu_and_mul", "astra_merge_attn_states_lse", "astra_stream_copy",
               "astra_plan_fused_add_rmsnorm", "astra_plan_silu_and_mul", "astra_plan_merge_attn_states_lse"):
         getattr(L, n).restype = i32
@@ -114,6 +116,10 @@ def astra_plan_silu_and_mul(T, d, aligned16=True):
 
 def astra_plan_merge_attn_states_lse(T, num_heads, head_dim, aligned16=True):
     return _plan(load_library().astra_plan_merge_attn_states_lse, T, num_heads, head_dim, int(aligned16))
+
+
+def astra_plan_xcd_chunked(workgroup: int, log2_chunk: int) -> int:
+    return int(load_library().astra_plan_xcd_chunked(workgroup, log2_chunk))
 
 
 # ---------------------------------------------------------------------------------------------------

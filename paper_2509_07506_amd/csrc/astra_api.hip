@@ -6,7 +6,6 @@
 
 #include <hip/hip_runtime.h>
 
-#include <cmath>
 #include <cstdint>
 #include <limits>
 
@@ -20,15 +19,46 @@ namespace {
 using namespace astra;
 
 // ---- tuning constants (measured on MI355X) ------------------------------------------------------
-constexpr bool kStreamNT = true;   // non-temporal hint on the once-touched activation streams
-constexpr int kSiluUnroll = 2;     // vector pairs in flight per lane, silu_and_mul
-constexpr int kMergeUnroll = 2;    // vector pairs in flight per lane, merge
-constexpr int kCopyUnroll = 4;
+constexpr bool kNTLoad = true;    // non-temporal hint on the once-read activation streams
+constexpr bool kNTStore = true;   // and on the once-written outputs
+// Vector pairs per lane.  One is fastest on MI355X for every streaming kernel measured: the finest
+// interleaving of loads and stores, full occupancy (32 waves per CU) supplies the bytes in flight.
+constexpr int kSiluUnroll = 1;
+constexpr int kMergeUnroll = 1;
+constexpr int kCopyUnroll = 1;
 
 constexpr int64_t kMaxVecIndex = int64_t(1) << 31;  // 32-bit vector indices with head-room for the tail
 constexpr int64_t kMaxGenericGrid = int64_t(1) << 20;
-constexpr int64_t kMaxRowGrid = (int64_t(1) << 22) - 1;  // grid * 1024 work-items stays below 2^32
-constexpr int kNumCUs = 256;
+constexpr int64_t kMaxRowGrid = int64_t(1) << 21;  // grid * 1024 work-items stays below 2^32; a multiple of 8 * 2^8
+
+// XCD-aware launch order (device_common.h, xcd_chunked): the workgroups one XCD runs back to back
+// cover a contiguous run of memory.  Measured on MI355X the best run is about 256 KiB per stream for
+// the row kernel (+3 to +10 % over the plain order) and 256 workgroups (1 MiB of output) for the flat
+// streaming kernels (+2 to +4 %).  Small grids keep the plain order: padding would dominate.
+constexpr int kRowChunkBytesLog2 = 18;
+constexpr int kFlatChunkLog2 = 8;
+constexpr int kMaxChunkLog2 = 8;
+
+int fit_chunk_log2(int64_t grid, int target)
+{
+    int lc = target < 0 ? 0 : (target > kMaxChunkLog2 ? kMaxChunkLog2 : target);
+    while (lc > 0 && grid < (int64_t(32) << lc)) --lc;  // at least four chunks per XCD
+    return lc;
+}
+
+int64_t pad_grid(int64_t grid, int log2_chunk)
+{
+    if (log2_chunk == 0) return grid;  // identity order: nothing to pad
+    const int64_t m = int64_t(kXcds) << log2_chunk;
+    return (grid + m - 1) / m * m;
+}
+
+int floor_log2(int64_t v)
+{
+    int l = 0;
+    while ((int64_t(2) << l) <= v) ++l;
+    return l;
+}
 
 bool mul_overflows(int64_t a, int64_t b, int64_t* out) { return __builtin_mul_overflow(a, b, out); }
 
@@ -48,40 +78,28 @@ astra_status_t after_launch() { return hipGetLastError() == hipSuccess ? ASTRA_O
 int round_up(int v, int m) { return (v + m - 1) / m * m; }
 
 // ---- fused_add_rmsnorm plan -----------------------------------------------------------------------
-// The row lives in registers: hv = H/8 vectors spread over `block` lanes, `vpt` per lane.
-// Few rows (decode): as many lanes per row as possible, so each lane has one dependent load-reduce-store
-// chain and the row's bytes are requested at once.  Many rows (prefill): about four waves per row, so
-// several rows share a CU and the cross-wave step stays short.
+// The row lives in registers: hv = H/8 vectors spread over `block` lanes, `vpt` per lane.  Measured on
+// MI355X the fewest vectors per lane (widest workgroup) is fastest both for few rows (one dependent
+// load-reduce-store chain per lane, the row's bytes requested at once) and for many rows (finest
+// interleaving of loads and stores; two 1024-lane workgroups fill a CU).  Among equal vpt the block is
+// the smallest multiple of 64 lanes that covers the row.
 struct RowPlan {
     int vpt;
     int block;
 };
 
-bool rmsnorm_row_plan(int64_t T, int64_t hv, RowPlan* plan)
+bool rmsnorm_row_plan(int64_t hv, RowPlan* plan)
 {
     static const int kVpt[4] = {1, 2, 4, 8};
     static const int kMaxBlock[4] = {1024, 1024, 1024, 512};
-    const bool few_rows = T < 2 * kNumCUs;
-    int best = -1, best_block = 0;
-    double best_cost = 0.0;
     for (int i = 0; i < 4; ++i) {
         const int64_t need = (hv + kVpt[i] - 1) / kVpt[i];
         if (need > kMaxBlock[i]) continue;
-        const int block = round_up((int)need, kWave);
-        const double waste = double(block) * kVpt[i] / double(hv) - 1.0;  // idle lane-slots
-        double cost;
-        if (few_rows) cost = kVpt[i] + waste;                             // smallest vpt that fits
-        else cost = waste * 4.0 + std::fabs(std::log2(double(block) / 256.0));
-        if (best < 0 || cost < best_cost) {
-            best = i;
-            best_cost = cost;
-            best_block = block;
-        }
+        plan->vpt = kVpt[i];
+        plan->block = round_up((int)need, kWave);
+        return true;
     }
-    if (best < 0) return false;
-    plan->vpt = kVpt[best];
-    plan->block = best_block;
-    return true;
+    return false;
 }
 
 astra_status_t plan_rmsnorm(int64_t T, int64_t H, bool aligned16, astra_launch_info_t* info)
@@ -91,8 +109,10 @@ astra_status_t plan_rmsnorm(int64_t T, int64_t H, bool aligned16, astra_launch_i
     *info = astra_launch_info_t{ASTRA_PATH_NONE, 0, 0, 0, 0};
     if (T == 0) return ASTRA_OK;
     RowPlan rp;
-    if (aligned16 && H % kVecElems == 0 && rmsnorm_row_plan(T, H / kVecElems, &rp)) {
-        *info = astra_launch_info_t{ASTRA_PATH_VECTOR, rp.block, rp.vpt, 0, T < kMaxRowGrid ? T : kMaxRowGrid};
+    if (aligned16 && H % kVecElems == 0 && rmsnorm_row_plan(H / kVecElems, &rp)) {
+        const int64_t rows = T < kMaxRowGrid ? T : kMaxRowGrid;
+        const int lc = fit_chunk_log2(rows, kRowChunkBytesLog2 - floor_log2(H * 2));
+        *info = astra_launch_info_t{ASTRA_PATH_VECTOR, rp.block, rp.vpt, lc, T < kMaxRowGrid ? pad_grid(rows, lc) : rows};
     } else {
         *info = astra_launch_info_t{ASTRA_PATH_GENERIC, 256, 0, 0, T < kMaxGenericGrid ? T : kMaxGenericGrid};
     }
@@ -111,7 +131,9 @@ astra_status_t plan_silu(int64_t T, int64_t d, bool aligned16, astra_launch_info
     // the input holds 2*T*dv vectors and is indexed with 32 bits
     if (aligned16 && d % kVecElems == 0 && dv >= 32 && 2 * T * dv <= kMaxVecIndex) {
         const int64_t span = 256 * kSiluUnroll;
-        *info = astra_launch_info_t{ASTRA_PATH_VECTOR, 256, kSiluUnroll, 0, (T * dv + span - 1) / span};
+        const int64_t blocks = (T * dv + span - 1) / span;
+        const int lc = fit_chunk_log2(blocks, kFlatChunkLog2);
+        *info = astra_launch_info_t{ASTRA_PATH_VECTOR, 256, kSiluUnroll, lc, pad_grid(blocks, lc)};
     } else {
         *info = astra_launch_info_t{ASTRA_PATH_GENERIC, 256, 0, 0, T < kMaxGenericGrid ? T : kMaxGenericGrid};
     }
@@ -129,7 +151,9 @@ astra_status_t plan_merge(int64_t T, int64_t NH, int64_t D, bool aligned16, astr
     const int64_t dvec = D / kVecElems;
     if (aligned16 && D % kVecElems == 0 && pairs * dvec <= kMaxVecIndex) {
         const int64_t span = 256 * kMergeUnroll;
-        *info = astra_launch_info_t{ASTRA_PATH_VECTOR, 256, kMergeUnroll, 0, (pairs * dvec + span - 1) / span};
+        const int64_t blocks = (pairs * dvec + span - 1) / span;
+        const int lc = fit_chunk_log2(blocks, kFlatChunkLog2);
+        *info = astra_launch_info_t{ASTRA_PATH_VECTOR, 256, kMergeUnroll, lc, pad_grid(blocks, lc)};
     } else {
         *info = astra_launch_info_t{ASTRA_PATH_GENERIC, 256, 0, 0, pairs < kMaxGenericGrid ? pairs : kMaxGenericGrid};
     }
@@ -142,9 +166,9 @@ template <int DT, int VPT, int MAXT>
 void launch_rmsnorm_row(const astra_launch_info_t& li, void* input, void* residual, const void* weight, int64_t T,
                         int64_t H, float eps, hipStream_t stream)
 {
-    fused_add_rmsnorm_row_kernel<DT, VPT, MAXT, kStreamNT><<<dim3((uint32_t)li.grid), dim3(li.block), 0, stream>>>(
+    fused_add_rmsnorm_row_kernel<DT, VPT, MAXT, kNTLoad, kNTStore><<<dim3((uint32_t)li.grid), dim3(li.block), 0, stream>>>(
         static_cast<u32x4*>(input), static_cast<u32x4*>(residual), static_cast<const u32x4*>(weight), T,
-        (uint32_t)(H / kVecElems), 1.0f / (float)H, eps);
+        (uint32_t)(H / kVecElems), 1.0f / (float)H, eps, li.log2_xcd_chunk);
 }
 
 template <int DT>
@@ -174,8 +198,8 @@ void launch_silu(const astra_launch_info_t& li, void* out, const void* in, int64
         return;
     }
     const uint32_t dv = (uint32_t)(d / kVecElems);
-    silu_and_mul_vec_kernel<DT, kSiluUnroll, kStreamNT><<<dim3((uint32_t)li.grid), dim3(256), 0, stream>>>(
-        static_cast<u32x4*>(out), static_cast<const u32x4*>(in), (uint32_t)(T * dv), dv, make_fastdiv(dv));
+    silu_and_mul_vec_kernel<DT, kSiluUnroll, kNTLoad, kNTStore><<<dim3((uint32_t)li.grid), dim3(256), 0, stream>>>(
+        static_cast<u32x4*>(out), static_cast<const u32x4*>(in), (uint32_t)(T * dv), dv, make_fastdiv(dv), li.log2_xcd_chunk);
 }
 
 template <int DT>
@@ -191,9 +215,9 @@ void launch_merge(const astra_launch_info_t& li, void* v_out, float* lse_out, co
     const uint32_t dvec = (uint32_t)(D / kVecElems);
     int log2_dvec = -1;
     if ((dvec & (dvec - 1)) == 0) log2_dvec = __builtin_ctz(dvec);
-    merge_attn_states_lse_vec_kernel<DT, kMergeUnroll, kStreamNT><<<dim3((uint32_t)li.grid), dim3(256), 0, stream>>>(
+    merge_attn_states_lse_vec_kernel<DT, kMergeUnroll, kNTLoad, kNTStore><<<dim3((uint32_t)li.grid), dim3(256), 0, stream>>>(
         static_cast<u32x4*>(v_out), lse_out, static_cast<const u32x4*>(v_a), lse_a, static_cast<const u32x4*>(v_b), lse_b,
-        (uint32_t)(pairs * dvec), dvec, log2_dvec, make_fastdiv(dvec));
+        (uint32_t)(pairs * dvec), dvec, log2_dvec, make_fastdiv(dvec), li.log2_xcd_chunk);
 }
 
 }  // namespace
@@ -216,6 +240,12 @@ const char* astra_status_string(astra_status_t status)
         case ASTRA_ERR_LAUNCH: return "kernel launch failed";
     }
     return "unknown status";
+}
+
+uint32_t astra_plan_xcd_chunked(uint32_t workgroup, int log2_chunk)
+{
+    if (log2_chunk < 0 || log2_chunk > kMaxChunkLog2) return workgroup;
+    return xcd_chunked(workgroup, log2_chunk);
 }
 
 astra_status_t astra_plan_fused_add_rmsnorm(int64_t T, int64_t H, int aligned16, astra_launch_info_t* info)
@@ -310,8 +340,10 @@ astra_status_t astra_stream_copy(void* dst, const void* src, int64_t nbytes, hip
     if (nbytes == 0) return ASTRA_OK;
     const int64_t nvec = nbytes / 16;
     const int64_t span = 256 * kCopyUnroll;
-    stream_copy_kernel<kCopyUnroll, kStreamNT><<<dim3((uint32_t)((nvec + span - 1) / span)), dim3(256), 0, stream>>>(
-        static_cast<u32x4*>(dst), static_cast<const u32x4*>(src), (uint32_t)nvec);
+    const int64_t blocks = (nvec + span - 1) / span;
+    const int lc = fit_chunk_log2(blocks, kFlatChunkLog2);
+    stream_copy_kernel<kCopyUnroll, kNTLoad, kNTStore><<<dim3((uint32_t)pad_grid(blocks, lc)), dim3(256), 0, stream>>>(
+        static_cast<u32x4*>(dst), static_cast<const u32x4*>(src), (uint32_t)nvec, lc);
     return after_launch();
 }
 

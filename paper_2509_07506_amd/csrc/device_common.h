@@ -141,6 +141,20 @@ inline FastDiv make_fastdiv(uint32_t d)
     return f;
 }
 
+// Workgroups are handed to the chip's 8 XCDs (each with its own L2) round-robin: workgroup b runs on
+// XCD b % 8.  With the plain mapping an XCD therefore touches every 8th unit of work.  This remap makes
+// the workgroups that one XCD runs back to back cover 2^log2_chunk consecutive units, then the next
+// XCD the following 2^log2_chunk, and so on: XCD x first gets units [x*C, (x+1)*C), then
+// [(8+x)*C, (8+x+1)*C), ...  It is a permutation of [0, G) whenever G is a multiple of 8*C; the host
+// pads the grid to such a G and surplus workgroups exit.  log2_chunk = 0 is the identity.
+constexpr int kXcds = 8;
+__host__ __device__ __forceinline__ uint32_t xcd_chunked(uint32_t b, int log2_chunk)
+{
+    const uint32_t q = b >> 3, x = b & 7u;
+    const uint32_t c = q >> log2_chunk, j = q & ((1u << log2_chunk) - 1u);
+    return (((c << 3) + x) << log2_chunk) + j;
+}
+
 // ---------------------------------------------------------------------------------------------
 // reductions
 

@@ -13,14 +13,17 @@ namespace astra {
 
 // Fast path: H % 8 == 0, 16-byte aligned pointers, hv = H/8 <= VPT * blockDim.x.
 // blockDim.x is a multiple of 64 and at most MAX_THREADS.  Lane `tid` owns vectors tid + k*blockDim.x.
-// A block walks rows blockIdx.x, blockIdx.x + gridDim.x, ... (normally exactly one row).
-template <int DT, int VPT, int MAX_THREADS, bool NT>
+// A block walks rows r0, r0 + gridDim.x, ... (normally exactly one row), r0 = xcd_chunked(blockIdx.x).
+template <int DT, int VPT, int MAX_THREADS, bool NTL, bool NTS>
 __global__ __launch_bounds__(MAX_THREADS) void fused_add_rmsnorm_row_kernel(u32x4* input, u32x4* residual,
                                                                             const u32x4* __restrict__ weight,
-                                                                            int64_t T, uint32_t hv, float inv_h, float eps)
+                                                                            int64_t T, uint32_t hv, float inv_h, float eps,
+                                                                            int log2_chunk)
 {
     __shared__ float partials[2][16];
     const int nwaves = blockDim.x >> 6;
+    const int64_t first_row = xcd_chunked(blockIdx.x, log2_chunk);
+    if (first_row >= T) return;  // grid padding; uniform for the whole workgroup
     int parity = 0;
 
     // the weight does not depend on the row: fetch it once (L2 resident, shared by all blocks)
@@ -31,7 +34,7 @@ __global__ __launch_bounds__(MAX_THREADS) void fused_add_rmsnorm_row_kernel(u32x
         if (v < hv) wv[k] = weight[v];
     }
 
-    for (int64_t row = blockIdx.x; row < T; row += gridDim.x, parity ^= 1) {
+    for (int64_t row = first_row; row < T; row += gridDim.x, parity ^= 1) {
         u32x4* xrow = input + row * hv;
         u32x4* rrow = residual + row * hv;
         u32x4 xv[VPT], rv[VPT];
@@ -39,8 +42,8 @@ __global__ __launch_bounds__(MAX_THREADS) void fused_add_rmsnorm_row_kernel(u32x
         for (int k = 0; k < VPT; ++k) {
             const uint32_t v = threadIdx.x + k * blockDim.x;
             if (v < hv) {
-                xv[k] = load_vec<NT>(xrow + v);
-                rv[k] = load_vec<NT>(rrow + v);
+                xv[k] = load_vec<NTL>(xrow + v);
+                rv[k] = load_vec<NTL>(rrow + v);
             }
         }
 
@@ -58,7 +61,7 @@ __global__ __launch_bounds__(MAX_THREADS) void fused_add_rmsnorm_row_kernel(u32x
                     s[k][e] = x[e] + r[e];
                     acc += s[k][e] * s[k][e];
                 }
-                store_vec<NT>(rrow + v, pack8<DT>(s[k]));
+                store_vec<NTS>(rrow + v, pack8<DT>(s[k]));
             }
         }
 
@@ -73,7 +76,7 @@ __global__ __launch_bounds__(MAX_THREADS) void fused_add_rmsnorm_row_kernel(u32x
                 unpack8<DT>(wv[k], w);
 #pragma unroll
                 for (int e = 0; e < 8; ++e) y[e] = (s[k][e] * scale) * w[e];
-                store_vec<NT>(xrow + v, pack8<DT>(y));
+                store_vec<NTS>(xrow + v, pack8<DT>(y));
             }
         }
     }

@@ -39,13 +39,14 @@ __device__ __forceinline__ MergeWeights merge_weights(float sa, float sb)
 // per pair.  The pair index is a shift when dvec is a power of two (LOG2_DVEC >= 0), otherwise a
 // multiply-high division.  v_out may alias v_a or v_b exactly: all loads of a lane precede its stores.
 // lse_out must not alias the input scores: the lanes of one pair can sit in different waves.
-template <int DT, int UNROLL, bool NT>
+template <int DT, int UNROLL, bool NTL, bool NTS>
 __global__ __launch_bounds__(256) void merge_attn_states_lse_vec_kernel(u32x4* v_out, float* lse_out, const u32x4* v_a,
                                                                         const float* lse_a, const u32x4* v_b,
                                                                         const float* lse_b, uint32_t total_vecs,
-                                                                        uint32_t dvec, int log2_dvec, FastDiv by_dvec)
+                                                                        uint32_t dvec, int log2_dvec, FastDiv by_dvec,
+                                                                        int log2_chunk)
 {
-    const uint32_t first = blockIdx.x * (256u * UNROLL) + threadIdx.x;
+    const uint32_t first = xcd_chunked(blockIdx.x, log2_chunk) * (256u * UNROLL) + threadIdx.x;
     u32x4 av[UNROLL], bv[UNROLL];
     float sa[UNROLL], sb[UNROLL];
     uint32_t pair[UNROLL];
@@ -54,8 +55,8 @@ __global__ __launch_bounds__(256) void merge_attn_states_lse_vec_kernel(u32x4* v
         const uint32_t i = first + 256u * k;
         if (i < total_vecs) {
             pair[k] = log2_dvec >= 0 ? (i >> log2_dvec) : by_dvec.div(i);
-            av[k] = load_vec<NT>(v_a + i);
-            bv[k] = load_vec<NT>(v_b + i);
+            av[k] = load_vec<NTL>(v_a + i);
+            bv[k] = load_vec<NTL>(v_b + i);
             sa[k] = lse_a[pair[k]];
             sb[k] = lse_b[pair[k]];
         }
@@ -70,7 +71,7 @@ __global__ __launch_bounds__(256) void merge_attn_states_lse_vec_kernel(u32x4* v
             unpack8<DT>(bv[k], b);
 #pragma unroll
             for (int e = 0; e < 8; ++e) o[e] = w.a * a[e] + w.b * b[e];
-            store_vec<NT>(v_out + i, pack8<DT>(o));
+            store_vec<NTS>(v_out + i, pack8<DT>(o));
             if (i == pair[k] * dvec) lse_out[pair[k]] = w.lse;  // first vector of the pair
         }
     }

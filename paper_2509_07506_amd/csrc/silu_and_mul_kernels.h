@@ -22,12 +22,14 @@ __device__ __forceinline__ float silu_fast(float x)
 // comes from one scalar fast division; lanes then step to the next row when they run past the end
 // of a row (at most a few steps because the host only takes this path when dv >= 32).
 // For output vector (t, j):  x = in[t*2dv + j], g = in[t*2dv + dv + j], out index = t*dv + j.
-template <int DT, int UNROLL, bool NT>
+template <int DT, int UNROLL, bool NTL, bool NTS>
 __global__ __launch_bounds__(256) void silu_and_mul_vec_kernel(u32x4* __restrict__ out, const u32x4* __restrict__ in,
-                                                               uint32_t total_vecs, uint32_t dv, FastDiv by_dv)
+                                                               uint32_t total_vecs, uint32_t dv, FastDiv by_dv,
+                                                               int log2_chunk)
 {
     constexpr uint32_t kSpan = 256u * UNROLL;
-    const uint32_t first = blockIdx.x * kSpan;
+    const uint32_t first = xcd_chunked(blockIdx.x, log2_chunk) * kSpan;
+    if (first >= total_vecs) return;  // grid padding
     const uint32_t t0 = by_dv.div(first);
     const uint32_t j0 = first - t0 * dv;
 
@@ -44,8 +46,8 @@ __global__ __launch_bounds__(256) void silu_and_mul_vec_kernel(u32x4* __restrict
         }
         if (oidx[k] < total_vecs) {
             const u32x4* px = in + (t * 2u * dv + j);  // the host keeps 2*T*dv within 32 bits
-            xv[k] = load_vec<NT>(px);
-            gv[k] = load_vec<NT>(px + dv);
+            xv[k] = load_vec<NTL>(px);
+            gv[k] = load_vec<NTL>(px + dv);
         }
     }
 #pragma unroll
@@ -56,7 +58,7 @@ __global__ __launch_bounds__(256) void silu_and_mul_vec_kernel(u32x4* __restrict
             unpack8<DT>(gv[k], g);
 #pragma unroll
             for (int e = 0; e < 8; ++e) o[e] = silu_fast(x[e]) * g[e];
-            store_vec<NT>(out + oidx[k], pack8<DT>(o));
+            store_vec<NTS>(out + oidx[k], pack8<DT>(o));
         }
     }
 }

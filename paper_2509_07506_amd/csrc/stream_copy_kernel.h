@@ -7,21 +7,21 @@
 
 namespace astra {
 
-template <int UNROLL, bool NT>
+template <int UNROLL, bool NTL, bool NTS>
 __global__ __launch_bounds__(256) void stream_copy_kernel(u32x4* __restrict__ dst, const u32x4* __restrict__ src,
-                                                          uint32_t nvec)
+                                                          uint32_t nvec, int log2_chunk)
 {
-    const uint32_t first = blockIdx.x * (256u * UNROLL) + threadIdx.x;
+    const uint32_t first = xcd_chunked(blockIdx.x, log2_chunk) * (256u * UNROLL) + threadIdx.x;
     u32x4 v[UNROLL];
 #pragma unroll
     for (int k = 0; k < UNROLL; ++k) {
         const uint32_t i = first + 256u * k;
-        if (i < nvec) v[k] = load_vec<NT>(src + i);
+        if (i < nvec) v[k] = load_vec<NTL>(src + i);
     }
 #pragma unroll
     for (int k = 0; k < UNROLL; ++k) {
         const uint32_t i = first + 256u * k;
-        if (i < nvec) store_vec<NT>(dst + i, v[k]);
+        if (i < nvec) store_vec<NTS>(dst + i, v[k]);
     }
 }
 

@@ -35,7 +35,7 @@ def test_every_declared_symbol_is_exported(A):
     declared = _declared_functions()
     assert {"astra_fused_add_rmsnorm", "astra_silu_and_mul", "astra_merge_attn_states_lse", "astra_status_string",
             "astra_stream_copy", "astra_plan_fused_add_rmsnorm", "astra_plan_silu_and_mul",
-            "astra_plan_merge_attn_states_lse"} <= set(declared)
+            "astra_plan_merge_attn_states_lse", "astra_plan_xcd_chunked"} <= set(declared)
     for name in declared:
         assert hasattr(L, name), f"{name} declared in include/ but not exported"
 
@@ -106,37 +106,63 @@ def test_rmsnorm_plans(A):
         return i.as_dict()
 
     assert plan(0, 4096)["path"] == "none"
-    for T in (1, 8, 64):                      # decode: widest block, one vector per lane
-        p = plan(T, 8192)
-        assert p == {"path": "vector", "block": 1024, "vectors_per_lane": 1, "grid": T}
-    assert plan(16, 4096) == {"path": "vector", "block": 512, "vectors_per_lane": 1, "grid": 16}
-    for T, H in [(8192, 8192), (32768, 8192), (4099, 5120), (4099, 7168), (1024, 4096), (512, 14336), (128, 11008)]:
+    for T in (1, 8):                          # decode: widest block, one vector per lane, plain launch order
+        assert plan(T, 8192) == {"path": "vector", "block": 1024, "vectors_per_lane": 1, "log2_xcd_chunk": 0, "grid": T}
+    assert plan(16, 4096) == {"path": "vector", "block": 512, "vectors_per_lane": 1, "log2_xcd_chunk": 0, "grid": 16}
+    for T, H in [(8192, 8192), (32768, 8192), (4099, 5120), (4099, 7168), (1024, 4096), (512, 14336), (128, 11008),
+                 (64, 8192), (257, 5120)]:
         p = plan(T, H)
-        assert p["path"] == "vector" and p["grid"] == T and p["block"] % 64 == 0 and p["block"] <= 1024
+        lc = p["log2_xcd_chunk"]
+        assert p["path"] == "vector" and p["block"] % 64 == 0 and p["block"] <= 1024
         assert p["block"] * p["vectors_per_lane"] * 8 >= H           # the whole row is register resident
         assert p["block"] * p["vectors_per_lane"] * 8 < 1.25 * H + 512
+        assert T <= p["grid"] < T + (8 << lc) and (lc == 0 or p["grid"] % (8 << lc) == 0)
+        assert lc == 0 or T >= (32 << lc)                              # at least four chunks per XCD
+        if T >= 4096:
+            assert 128 * 1024 <= (H * 2) << lc <= 512 * 1024           # about 256 KiB per XCD run
     assert plan(4, 4100)["path"] == "generic" and plan(4, 4096, al=False)["path"] == "generic"
     assert plan(4, 65536)["path"] == "generic"
-    assert plan(1 << 23, 64)["grid"] < (1 << 22)                      # row loop beyond the grid limit
+    big = plan(1 << 23, 64)                                            # row loop beyond the grid limit
+    assert big["grid"] == 1 << 21 and big["grid"] % (8 << big["log2_xcd_chunk"]) == 0
     assert A.astra_plan_fused_add_rmsnorm(-1, 8, True)[0] == 2
 
 
 def test_silu_and_merge_plans(A):
     st, i = A.astra_plan_silu_and_mul(4096, 14336, True)
     p = i.as_dict()
+    work = 4096 * 14336 // 8
     assert st == 0 and p["path"] == "vector"
-    assert p["grid"] * p["block"] * p["vectors_per_lane"] >= 4096 * 14336 // 8
-    assert p["grid"] * p["block"] * p["vectors_per_lane"] < 4096 * 14336 // 8 + p["block"] * p["vectors_per_lane"]
+    assert work <= p["grid"] * p["block"] * p["vectors_per_lane"] < work + (8 << p["log2_xcd_chunk"]) * 256
+    assert p["grid"] % (8 << p["log2_xcd_chunk"]) == 0
     assert A.astra_plan_silu_and_mul(3, 100, True)[1].as_dict()["path"] == "generic"
     assert A.astra_plan_silu_and_mul(3, 1408, False)[1].as_dict()["path"] == "generic"
     assert A.astra_plan_silu_and_mul(3, 128, True)[1].as_dict()["path"] == "generic"      # rows shorter than 32 vectors
     assert A.astra_plan_silu_and_mul(1 << 20, 1 << 14, True)[1].as_dict()["path"] == "generic"  # beyond 32-bit vector indices
+    small = A.astra_plan_silu_and_mul(3, 1408, True)[1].as_dict()
+    assert small["log2_xcd_chunk"] == 0 and small["grid"] == 3                           # no padding for small grids
     st, i = A.astra_plan_merge_attn_states_lse(4096, 32, 128, True)
     p = i.as_dict()
     assert st == 0 and p["path"] == "vector" and p["grid"] * p["block"] * p["vectors_per_lane"] == 4096 * 32 * 16
     assert A.astra_plan_merge_attn_states_lse(3, 5, 4, True)[1].as_dict()["path"] == "generic"
     assert A.astra_plan_merge_attn_states_lse(3, 5, 72, True)[1].as_dict()["path"] == "vector"
     assert A.astra_plan_merge_attn_states_lse(0, 5, 72, True)[1].as_dict()["path"] == "none"
+
+
+def test_xcd_chunked_is_a_permutation_with_contiguous_runs(A):
+    """workgroup b runs on XCD b % 8; the map must cover [0, G) exactly once and give each XCD runs of
+    2^lc consecutive units."""
+    for lc in range(0, 9):
+        C = 1 << lc
+        G = 8 * C * 3
+        image = [A.astra_plan_xcd_chunked(b, lc) for b in range(G)]
+        assert sorted(image) == list(range(G))
+        for xcd in range(8):
+            seq = [image[b] for b in range(xcd, G, 8)]           # what this XCD executes, in launch order
+            for k in range(0, len(seq), C):
+                run = seq[k:k + C]
+                assert run == list(range(run[0], run[0] + C)) and run[0] % C == 0
+    assert [A.astra_plan_xcd_chunked(b, 0) for b in range(20)] == list(range(20))
+    assert A.astra_plan_xcd_chunked(5, 99) == 5
 
 
 def test_binding_refuses_cpu_tensors(A):
