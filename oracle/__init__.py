@@ -21,6 +21,9 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "astra_oracle.c")
 _LIB = os.path.join(_HERE, "liboracle.so")
+# Test hook: tests/test_oracle_mutations.py points this at a deliberately broken build to show that the
+# pins catch it.  When set, that library is loaded as is and nothing is compiled.
+_OVERRIDE = os.environ.get("ASTRA_ORACLE_LIB")
 
 DTYPES = {"f16": 0, "bf16": 1}
 
@@ -29,6 +32,8 @@ _lib = None
 
 def build(force: bool = False) -> str:
     """Compile the C oracle with gcc.  No FMA contraction, no fast-math."""
+    if _OVERRIDE:
+        return _OVERRIDE
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         cmd = ["gcc", "-O2", "-std=c11", "-ffp-contract=off", "-fno-fast-math", "-fopenmp", "-fPIC", "-shared",
                "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
@@ -39,8 +44,7 @@ def build(force: bool = False) -> str:
 def lib() -> ctypes.CDLL:
     global _lib
     if _lib is None:
-        build()
-        L = ctypes.CDLL(_LIB)
+        L = ctypes.CDLL(build())
         i64, f32, i32 = ctypes.c_int64, ctypes.c_float, ctypes.c_int
         vp = ctypes.c_void_p
         L.oracle_widen_array.argtypes = [vp, vp, i64, i32]

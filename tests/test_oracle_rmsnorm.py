@@ -122,23 +122,55 @@ def test_rows_are_independent_and_weight_is_per_column(oracle):
 @pytest.mark.parametrize("dt", ["bf16", "f16"])
 def test_stored_residual_is_one_float32_add_one_rounding(oracle, dt):
     """residual <- RNE(float32(x) + float32(r)): expectation built from numpy float32 addition and the
-    library casts (numpy float16 / torch bfloat16), none of which is oracle code.  Includes the
-    double-rounding case where rounding the exact sum directly would differ."""
+    library casts (numpy float16 / torch bfloat16), none of which is oracle code.  Includes exact ties
+    (which must go to the even pattern) and fp16-subnormal sums."""
     T, H = 6, 2048
     xb = workloads.to_bits(_rand((T, H), 13), dt)
     rb = workloads.to_bits(_rand((T, H), 14, 2.0), dt)
-    # tiny operands (fp16 subnormal results) and a double-rounding trap in row 0
+    # tiny operands (fp16 subnormal results) in row 1, an exact tie in row 0
     rb[1, :64] = workloads.to_bits(np.full(64, 2.0 ** -16, np.float32) * np.arange(64, dtype=np.float32), dt)
     xb[1, :64] = workloads.to_bits(np.full(64, 2.0 ** -17, np.float32), dt)
     xb[0, 0] = workloads.to_bits(np.array([1.0], np.float32), dt)[0]
-    tiny = 2.0 ** -8 + 2.0 ** -30 if dt == "bf16" else 2.0 ** -11 + 2.0 ** -24
-    rb[0, 0] = workloads.to_bits(np.array([tiny], np.float32), dt)[0]
+    half_ulp = 2.0 ** -8 if dt == "bf16" else 2.0 ** -11
+    rb[0, 0] = workloads.to_bits(np.array([half_ulp], np.float32), dt)[0]      # 1 + half ulp: tie, rounds to 1.0
+    xb[0, 1] = workloads.to_bits(np.array([1.0 + 2 * half_ulp], np.float32), dt)[0]
+    rb[0, 1] = rb[0, 0]                                                         # odd + half ulp: tie, rounds up
     wb = workloads.to_bits(np.ones(H, np.float32), dt)
     _, res = oracle.fused_add_rmsnorm(xb, rb, wb, 1e-6, dt)
     xf = reference_f64.widen(xb, dt).astype(np.float32)
     rf = reference_f64.widen(rb, dt).astype(np.float32)
     expect = workloads.to_bits(xf + rf, dt)
     assert_bits_equal(res, expect, "residual")
+    one = workloads.to_bits(np.array([1.0, 1.0 + 4 * half_ulp], np.float32), dt)
+    assert res[0, 0] == one[0] and res[0, 1] == one[1]
+
+
+@pytest.mark.parametrize("dt", ["bf16", "f16"])
+def test_stored_residual_is_the_correctly_rounded_exact_sum(oracle, dt):
+    """For 16-bit operands the float32 sum followed by one rounding equals the exact sum rounded once
+    (float32 has at least 2p+2 bits for p = 8 and p = 11, so the double rounding is innocuous).  The
+    exact sum is formed in float64 (exact for these magnitudes) and rounded by a nearest-even search over
+    all representable values -- no float32 and no library cast involved."""
+    T, H = 4, 4096
+    xb = workloads.to_bits(_rand((T, H), 21), dt)
+    rb = workloads.to_bits(_rand((T, H), 22, 2.0), dt)
+    wb = workloads.to_bits(np.ones(H, np.float32), dt)
+    _, res = oracle.fused_add_rmsnorm(xb, rb, wb, 1e-6, dt)
+    exact = reference_f64.widen(xb, dt) + reference_f64.widen(rb, dt)
+    all16 = np.arange(1 << 16, dtype=np.uint32).astype(np.uint16)
+    with np.errstate(invalid="ignore"):
+        table = reference_f64.widen(all16, dt)
+    pos = all16[(all16 < 0x8000) & np.isfinite(table)]
+    vals = table[pos]
+    mag = np.abs(exact).ravel()
+    hi = np.clip(np.searchsorted(vals, mag, side="left"), 1, len(vals) - 1)
+    lo = hi - 1
+    dlo, dhi = mag - vals[lo], vals[hi] - mag
+    pick_hi = (dhi < dlo) | ((dhi == dlo) & (pos[hi] % 2 == 0))
+    expect = np.where(pick_hi, pos[hi], pos[lo]).astype(np.uint16)
+    expect = np.where(np.signbit(exact).ravel(), expect | np.uint16(0x8000), expect).reshape(T, H)
+    zero = (expect & 0x7FFF) == 0
+    assert np.array_equal(res[~zero], expect[~zero]) and np.all((res[zero] & 0x7FFF) == 0)
 
 
 @pytest.mark.parametrize("dt", ["bf16", "f16"])
