@@ -16,6 +16,7 @@ taken inside the timed region on the launch stream; `kernels` carries the same f
     python bench.py [--gpus 1] [--steps K] [--warmup W]
     python bench.py --sweep          # per-workload table over every config (one JSON line per case)
     python bench.py --ceiling        # streaming-copy ceiling of the machine (same access pattern)
+    python bench.py --ablation       # paper Table-4 shapes: tuned vs one-optimisation-removed variants
 """
 from __future__ import annotations
 
@@ -48,11 +49,12 @@ class Launcher:
     """Device buffers of one workload (optionally `nsets` independent copies, used round-robin so that no
     launch re-reads cache-resident bytes) and a closure that enqueues its kernel on a given stream."""
 
-    def __init__(self, astra, case, data, nsets: int = 1):
+    def __init__(self, astra, case, data, nsets: int = 1, variant: int = 0):
         import torch
 
         self.case = case
         self.nsets = nsets
+        v = variant  # 0 = the tuned kernel; otherwise an ablation variant (include/astra_ablation.h)
         dt = case.dtype
         tdt = {"bf16": torch.bfloat16, "f16": torch.float16}[dt]
         code = astra.ASTRA_BF16 if dt == "bf16" else astra.ASTRA_F16
@@ -72,7 +74,11 @@ class Launcher:
             self.bufs = (xp, rp, w)
             T, H, eps = s["T"], s["H"], case.eps
             x0, r0, w0 = xp.data_ptr(), rp.data_ptr(), w.data_ptr()
-            self.fn = lambda k, st: astra.astra_fused_add_rmsnorm(x0 + k * xs, r0 + k * rs, w0, T, H, code, eps, st)
+            if v == 0:
+                self.fn = lambda k, st: astra.astra_fused_add_rmsnorm(x0 + k * xs, r0 + k * rs, w0, T, H, code, eps, st)
+            else:
+                self.fn = lambda k, st: astra.astra_ablation_fused_add_rmsnorm(x0 + k * xs, r0 + k * rs, w0, T, H, code,
+                                                                               eps, v, st)
             self.plan = astra.astra_plan_fused_add_rmsnorm(T, H, True)[1].as_dict()
         elif case.kernel == "silu":
             a = _to_dev(data[0], dt)
@@ -81,7 +87,10 @@ class Launcher:
             self.bufs = (ap, op)
             T, d = s["T"], s["d"]
             a0, o0 = ap.data_ptr(), op.data_ptr()
-            self.fn = lambda k, st: astra.astra_silu_and_mul(o0 + k * os_, a0 + k * as_, T, d, code, st)
+            if v == 0:
+                self.fn = lambda k, st: astra.astra_silu_and_mul(o0 + k * os_, a0 + k * as_, T, d, code, st)
+            else:
+                self.fn = lambda k, st: astra.astra_ablation_silu_and_mul(o0 + k * os_, a0 + k * as_, T, d, code, v, st)
             self.plan = astra.astra_plan_silu_and_mul(T, d, True)[1].as_dict()
         else:
             va, la, vb, lb = data
@@ -92,9 +101,14 @@ class Launcher:
             self.bufs = (vap, vbp, vop, lap, lbp, lop)
             T, NH, D = s["T"], s["NH"], s["D"]
             p = [t.data_ptr() for t in (vop, lop, vap, lap, vbp, lbp)]
-            self.fn = lambda k, st: astra.astra_merge_attn_states_lse(p[0] + k * vs, p[1] + k * ls, p[2] + k * vs,
-                                                                      p[3] + k * ls, p[4] + k * vs, p[5] + k * ls, T, NH, D,
-                                                                      code, st)
+            if v == 0:
+                self.fn = lambda k, st: astra.astra_merge_attn_states_lse(p[0] + k * vs, p[1] + k * ls, p[2] + k * vs,
+                                                                          p[3] + k * ls, p[4] + k * vs, p[5] + k * ls, T, NH,
+                                                                          D, code, st)
+            else:
+                self.fn = lambda k, st: astra.astra_ablation_merge_attn_states_lse(
+                    p[0] + k * vs, p[1] + k * ls, p[2] + k * vs, p[3] + k * ls, p[4] + k * vs, p[5] + k * ls, T, NH, D, code, v,
+                    st)
             self.plan = astra.astra_plan_merge_attn_states_lse(T, NH, D, True)[1].as_dict()
 
     def launch(self, stream_handle, k: int = 0):
@@ -291,6 +305,71 @@ def run_sweep(args):
         torch.cuda.empty_cache()
 
 
+ABLATION_VARIANTS = {"rmsnorm": ((1, "scalar_loads"), (2, "lds_tree_reduction")),
+                     "silu": ((1, "scalar_loads"), (4, "libm_exp_divide")),
+                     "merge": ((1, "scalar_loads"), (3, "unhoisted_weights"))}
+ABLATION_BIG = ("c3_rmsnorm_T8192_H8192_bf16", "c1_silu_T4096_d14336_bf16", "c2_merge_T4096_NH32_D128_bf16")
+
+
+def run_ablation(args):
+    """The paper's experiment re-staged on MI355X: for each of the twelve Table-4 shapes, and for the three
+    bandwidth-regime benchmark workloads, the time of the tuned kernel and of each variant with one of the
+    paper's optimisations removed, the per-shape speedup sigma = t(variant) / t(tuned) and its geometric
+    mean per kernel and variant (the paper's Section 3.1 metric).  20 warm-up + 100 timed launches per
+    point (Section 4), one event pair around the 100; cold = rotating buffer sets, hot = one set."""
+    import math
+
+    import torch
+
+    import paper_2509_07506_amd as astra
+    import workloads
+
+    astra.load_library()
+    torch.cuda.set_device(0)
+    stream = torch.cuda.current_stream()
+    sh = stream.cuda_stream
+    names = sorted(workloads.PAPER_SHAPE_CASES) + list(ABLATION_BIG)
+    speedups = {}
+
+    def timed(L, hot):
+        reps, warm = 100, 20
+        for k in range(warm):
+            L.launch(sh, 0 if hot else k)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for k in range(reps):
+            L.launch(sh, 0 if hot else warm + k)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / reps
+
+    for n in names:
+        c = workloads.case(n)
+        data = c.generate()
+        ws = c.algorithmic_bytes()
+        nsets = 1 if ws > (512 << 20) else min(1024, max(2, -(-(1 << 30) // max(ws, 1)) + 1))
+        group = "paper_table4" if n.startswith("p4_") else "bandwidth_regime"
+        res = {}
+        for v, vname in ((0, "tuned"),) + ABLATION_VARIANTS[c.kernel]:
+            L = Launcher(astra, c, data, nsets, variant=v)
+            res[vname] = {"cold_us": round(timed(L, False), 2), "hot_us": round(timed(L, True), 2)}
+            del L
+            torch.cuda.empty_cache()
+        line = {"case": n, "group": group, "bytes": ws, "times": res, "speedup_of_tuned": {}}
+        for vname, r in res.items():
+            if vname == "tuned":
+                continue
+            sc, sh_ = r["cold_us"] / res["tuned"]["cold_us"], r["hot_us"] / res["tuned"]["hot_us"]
+            line["speedup_of_tuned"][vname] = {"cold": round(sc, 3), "hot": round(sh_, 3)}
+            speedups.setdefault((group, c.kernel, vname), []).append((sc, sh_))
+        print(json.dumps(line), flush=True)
+    for (group, kernel, vname), v in sorted(speedups.items()):
+        gm = lambda xs: math.exp(sum(math.log(x) for x in xs) / len(xs))
+        print(json.dumps({"geomean_speedup_of_tuned_over": vname, "kernel": kernel, "group": group, "shapes": len(v),
+                          "cold": round(gm([a for a, _ in v]), 3), "hot": round(gm([b for _, b in v]), 3)}), flush=True)
+
+
 def run_ceiling(args):
     """Streaming ceiling of this machine with the operators' access pattern: astra_stream_copy over
     512 MiB, alternating between two source/destination pairs (2 GiB footprint, so always cold)."""
@@ -337,12 +416,16 @@ def main():
     ap.add_argument("--sweep", action="store_true", help="per-workload table over every config")
     ap.add_argument("--only", default=None, help="with --sweep: substring filter on the case name")
     ap.add_argument("--ceiling", action="store_true", help="measure the streaming-copy ceiling of the machine")
+    ap.add_argument("--ablation", action="store_true",
+                    help="paper Table-4 shapes and the bandwidth workloads: tuned kernel vs each one-optimisation-removed variant")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this path runs on ONE GPU (row-independent kernels, no collectives); "
               "--gpus N with N > 1 is not supported", file=sys.stderr)
         sys.exit(2)
-    if args.ceiling:
+    if args.ablation:
+        run_ablation(args)
+    elif args.ceiling:
         run_ceiling(args)
     elif args.sweep:
         run_sweep(args)

@@ -6,9 +6,18 @@ fallback path: if the library is not built or cannot be loaded, every call raise
 """
 from .binding import (  # noqa: F401
     ASTRA_BF16,
+    ASTRA_ERR_VARIANT,
     ASTRA_F16,
+    ASTRA_VARIANT_LDS_TREE_REDUCTION,
+    ASTRA_VARIANT_LIBM_EXP_DIVIDE,
+    ASTRA_VARIANT_SCALAR_LOADS,
+    ASTRA_VARIANT_TUNED,
+    ASTRA_VARIANT_UNHOISTED_WEIGHTS,
     AstraError,
     LaunchInfo,
+    astra_ablation_fused_add_rmsnorm,
+    astra_ablation_merge_attn_states_lse,
+    astra_ablation_silu_and_mul,
     astra_fused_add_rmsnorm,
     astra_merge_attn_states_lse,
     astra_plan_fused_add_rmsnorm,

@@ -18,6 +18,14 @@ import os
 ASTRA_F16 = 0
 ASTRA_BF16 = 1
 
+# include/astra_ablation.h
+ASTRA_VARIANT_TUNED = 0
+ASTRA_VARIANT_SCALAR_LOADS = 1
+ASTRA_VARIANT_LDS_TREE_REDUCTION = 2
+ASTRA_VARIANT_UNHOISTED_WEIGHTS = 3
+ASTRA_VARIANT_LIBM_EXP_DIVIDE = 4
+ASTRA_ERR_VARIANT = 8
+
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_PKG, "libastra_hip.so")
 _lib = None
@@ -60,6 +68,9 @@ def load_library() -> ctypes.CDLL:
     L.astra_silu_and_mul.argtypes = [vp, vp, i64, i64, i32, vp]
     L.astra_merge_attn_states_lse.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, i32, vp]
     L.astra_stream_copy.argtypes = [vp, vp, i64, vp]
+    L.astra_ablation_fused_add_rmsnorm.argtypes = [vp, vp, vp, i64, i64, i32, f32, i32, vp]
+    L.astra_ablation_silu_and_mul.argtypes = [vp, vp, i64, i64, i32, i32, vp]
+    L.astra_ablation_merge_attn_states_lse.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, i32, i32, vp]
     L.astra_status_string.argtypes = [i32]
     L.astra_status_string.restype = ctypes.c_char_p
     pinfo = ctypes.POINTER(LaunchInfo)
@@ -69,6 +80,7 @@ def load_library() -> ctypes.CDLL:
     L.astra_plan_xcd_chunked.argtypes = [ctypes.c_uint32, i32]
     L.astra_plan_xcd_chunked.restype = ctypes.c_uint32
     for n in ("astra_fused_add_rmsnorm", "astra_silu_and_mul", "astra_merge_attn_states_lse", "astra_stream_copy",
+              "astra_ablation_fused_add_rmsnorm", "astra_ablation_silu_and_mul", "astra_ablation_merge_attn_states_lse",
               "astra_plan_fused_add_rmsnorm", "astra_plan_silu_and_mul", "astra_plan_merge_attn_states_lse"):
         getattr(L, n).restype = i32
     _lib = L
@@ -98,6 +110,21 @@ def astra_merge_attn_states_lse(v_out, lse_out, v_a, lse_a, v_b, lse_b, T, num_h
 
 def astra_stream_copy(dst, src, nbytes, stream=None) -> int:
     return load_library().astra_stream_copy(dst, src, nbytes, stream)
+
+
+def astra_ablation_fused_add_rmsnorm(input_ptr, residual_ptr, weight_ptr, T, H, dtype, eps, variant, stream=None) -> int:
+    return load_library().astra_ablation_fused_add_rmsnorm(input_ptr, residual_ptr, weight_ptr, T, H, dtype, eps, variant,
+                                                           stream)
+
+
+def astra_ablation_silu_and_mul(out_ptr, input_ptr, T, d, dtype, variant, stream=None) -> int:
+    return load_library().astra_ablation_silu_and_mul(out_ptr, input_ptr, T, d, dtype, variant, stream)
+
+
+def astra_ablation_merge_attn_states_lse(v_out, lse_out, v_a, lse_a, v_b, lse_b, T, num_heads, head_dim, dtype, variant,
+                                         stream=None) -> int:
+    return load_library().astra_ablation_merge_attn_states_lse(v_out, lse_out, v_a, lse_a, v_b, lse_b, T, num_heads,
+                                                               head_dim, dtype, variant, stream)
 
 
 def _plan(fn, *args):

@@ -2,6 +2,7 @@
 // launch geometry) and the kernel launches.  Everything before the first HIP call is plain host
 // arithmetic, so every error path can be exercised without a GPU.
 #include "astra.h"
+#include "astra_ablation.h"
 #include "astra_plan.h"
 
 #include <hip/hip_runtime.h>
@@ -9,6 +10,7 @@
 #include <cstdint>
 #include <limits>
 
+#include "ablation_kernels.h"
 #include "fused_add_rmsnorm_kernels.h"
 #include "merge_attn_states_lse_kernels.h"
 #include "silu_and_mul_kernels.h"
@@ -79,27 +81,29 @@ int round_up(int v, int m) { return (v + m - 1) / m * m; }
 
 // ---- fused_add_rmsnorm plan -----------------------------------------------------------------------
 // The row lives in registers: hv = H/8 vectors spread over `block` lanes, `vpt` per lane.  Measured on
-// MI355X the fewest vectors per lane (widest workgroup) is fastest both for few rows (one dependent
-// load-reduce-store chain per lane, the row's bytes requested at once) and for many rows (finest
-// interleaving of loads and stores; two 1024-lane workgroups fill a CU).  Among equal vpt the block is
-// the smallest multiple of 64 lanes that covers the row.
+// MI355X: rows of up to 1024 vectors (H <= 8192) are fastest with one vector per lane and the widest
+// workgroup, both for few rows (one dependent load-reduce-store chain per lane, the row's bytes
+// requested at once) and for many rows (finest interleaving of loads and stores; two 1024-lane
+// workgroups fill a CU).  Longer rows take four vectors per lane when there are many rows (several
+// mid-sized workgroups per CU beat one huge one by 1-2 %) and two when there are few (more lanes per
+// row).  The block is the smallest multiple of 64 lanes that covers the row.
 struct RowPlan {
     int vpt;
     int block;
 };
 
-bool rmsnorm_row_plan(int64_t hv, RowPlan* plan)
+constexpr int64_t kFewRows = 512;  // fewer rows than this cannot fill the chip twice over
+
+bool rmsnorm_row_plan(int64_t T, int64_t hv, RowPlan* plan)
 {
-    static const int kVpt[4] = {1, 2, 4, 8};
-    static const int kMaxBlock[4] = {1024, 1024, 1024, 512};
-    for (int i = 0; i < 4; ++i) {
-        const int64_t need = (hv + kVpt[i] - 1) / kVpt[i];
-        if (need > kMaxBlock[i]) continue;
-        plan->vpt = kVpt[i];
-        plan->block = round_up((int)need, kWave);
-        return true;
-    }
-    return false;
+    int vpt;
+    if (hv <= 1024) vpt = 1;
+    else if (hv <= 2048 && T < kFewRows) vpt = 2;
+    else if (hv <= 4096) vpt = 4;
+    else return false;
+    plan->vpt = vpt;
+    plan->block = round_up((int)((hv + vpt - 1) / vpt), kWave);
+    return true;
 }
 
 astra_status_t plan_rmsnorm(int64_t T, int64_t H, bool aligned16, astra_launch_info_t* info)
@@ -109,7 +113,7 @@ astra_status_t plan_rmsnorm(int64_t T, int64_t H, bool aligned16, astra_launch_i
     *info = astra_launch_info_t{ASTRA_PATH_NONE, 0, 0, 0, 0};
     if (T == 0) return ASTRA_OK;
     RowPlan rp;
-    if (aligned16 && H % kVecElems == 0 && rmsnorm_row_plan(H / kVecElems, &rp)) {
+    if (aligned16 && H % kVecElems == 0 && rmsnorm_row_plan(T, H / kVecElems, &rp)) {
         const int64_t rows = T < kMaxRowGrid ? T : kMaxRowGrid;
         const int lc = fit_chunk_log2(rows, kRowChunkBytesLog2 - floor_log2(H * 2));
         *info = astra_launch_info_t{ASTRA_PATH_VECTOR, rp.block, rp.vpt, lc, T < kMaxRowGrid ? pad_grid(rows, lc) : rows};
@@ -162,19 +166,36 @@ astra_status_t plan_merge(int64_t T, int64_t NH, int64_t D, bool aligned16, astr
 
 // ---- launches ---------------------------------------------------------------------------------------
 
-template <int DT, int VPT, int MAXT>
+template <int DT, int VPT, int MAXT, bool LDS_TREE = false>
 void launch_rmsnorm_row(const astra_launch_info_t& li, void* input, void* residual, const void* weight, int64_t T,
                         int64_t H, float eps, hipStream_t stream)
 {
-    fused_add_rmsnorm_row_kernel<DT, VPT, MAXT, kNTLoad, kNTStore><<<dim3((uint32_t)li.grid), dim3(li.block), 0, stream>>>(
-        static_cast<u32x4*>(input), static_cast<u32x4*>(residual), static_cast<const u32x4*>(weight), T,
-        (uint32_t)(H / kVecElems), 1.0f / (float)H, eps, li.log2_xcd_chunk);
+    fused_add_rmsnorm_row_kernel<DT, VPT, MAXT, kNTLoad, kNTStore, LDS_TREE>
+        <<<dim3((uint32_t)li.grid), dim3(li.block), 0, stream>>>(
+            static_cast<u32x4*>(input), static_cast<u32x4*>(residual), static_cast<const u32x4*>(weight), T,
+            (uint32_t)(H / kVecElems), 1.0f / (float)H, eps, li.log2_xcd_chunk);
 }
 
 template <int DT>
 void launch_rmsnorm(const astra_launch_info_t& li, void* input, void* residual, const void* weight, int64_t T, int64_t H,
-                    float eps, hipStream_t stream)
+                    float eps, int variant, hipStream_t stream)
 {
+    if (variant == ASTRA_VARIANT_SCALAR_LOADS) {
+        // same decomposition as the tuned kernel (one workgroup per row, row in registers), 16-bit accesses
+        const int block = H >= 1024 ? 1024 : round_up((int)H, kWave);
+        fused_add_rmsnorm_scalar_kernel<DT, 16><<<dim3((uint32_t)(T < kMaxRowGrid ? T : kMaxRowGrid)), dim3(block), 0, stream>>>(
+            static_cast<uint16_t*>(input), static_cast<uint16_t*>(residual), static_cast<const uint16_t*>(weight), T,
+            (uint32_t)H, 1.0f / (float)H, eps);
+        return;
+    }
+    if (variant == ASTRA_VARIANT_LDS_TREE_REDUCTION) {
+        switch (li.vectors_per_lane) {
+            case 1: launch_rmsnorm_row<DT, 1, 1024, true>(li, input, residual, weight, T, H, eps, stream); break;
+            case 2: launch_rmsnorm_row<DT, 2, 1024, true>(li, input, residual, weight, T, H, eps, stream); break;
+            default: launch_rmsnorm_row<DT, 4, 1024, true>(li, input, residual, weight, T, H, eps, stream); break;
+        }
+        return;
+    }
     if (li.path == ASTRA_PATH_GENERIC) {
         fused_add_rmsnorm_generic_kernel<DT><<<dim3((uint32_t)li.grid), dim3(li.block), 0, stream>>>(
             static_cast<uint16_t*>(input), static_cast<uint16_t*>(residual), static_cast<const uint16_t*>(weight), T, H,
@@ -184,14 +205,27 @@ void launch_rmsnorm(const astra_launch_info_t& li, void* input, void* residual, 
     switch (li.vectors_per_lane) {
         case 1: launch_rmsnorm_row<DT, 1, 1024>(li, input, residual, weight, T, H, eps, stream); break;
         case 2: launch_rmsnorm_row<DT, 2, 1024>(li, input, residual, weight, T, H, eps, stream); break;
-        case 4: launch_rmsnorm_row<DT, 4, 1024>(li, input, residual, weight, T, H, eps, stream); break;
-        default: launch_rmsnorm_row<DT, 8, 512>(li, input, residual, weight, T, H, eps, stream); break;
+        default: launch_rmsnorm_row<DT, 4, 1024>(li, input, residual, weight, T, H, eps, stream); break;
     }
 }
 
 template <int DT>
-void launch_silu(const astra_launch_info_t& li, void* out, const void* in, int64_t T, int64_t d, hipStream_t stream)
+void launch_silu(const astra_launch_info_t& li, void* out, const void* in, int64_t T, int64_t d, int variant,
+                 hipStream_t stream)
 {
+    if (variant == ASTRA_VARIANT_SCALAR_LOADS) {
+        const uint32_t n = (uint32_t)(T * d);
+        silu_and_mul_scalar_kernel<DT><<<dim3((n + 255u) / 256u), dim3(256), 0, stream>>>(
+            static_cast<uint16_t*>(out), static_cast<const uint16_t*>(in), n, (uint32_t)d, make_fastdiv((uint32_t)d));
+        return;
+    }
+    if (variant == ASTRA_VARIANT_LIBM_EXP_DIVIDE) {
+        const uint32_t dv = (uint32_t)(d / kVecElems);
+        silu_and_mul_vec_kernel<DT, kSiluUnroll, kNTLoad, kNTStore, true><<<dim3((uint32_t)li.grid), dim3(256), 0, stream>>>(
+            static_cast<u32x4*>(out), static_cast<const u32x4*>(in), (uint32_t)(T * dv), dv, make_fastdiv(dv),
+            li.log2_xcd_chunk);
+        return;
+    }
     if (li.path == ASTRA_PATH_GENERIC) {
         silu_and_mul_generic_kernel<DT><<<dim3((uint32_t)li.grid), dim3(li.block), 0, stream>>>(
             static_cast<uint16_t*>(out), static_cast<const uint16_t*>(in), T, d);
@@ -204,8 +238,24 @@ void launch_silu(const astra_launch_info_t& li, void* out, const void* in, int64
 
 template <int DT>
 void launch_merge(const astra_launch_info_t& li, void* v_out, float* lse_out, const void* v_a, const float* lse_a,
-                  const void* v_b, const float* lse_b, int64_t pairs, int64_t D, hipStream_t stream)
+                  const void* v_b, const float* lse_b, int64_t pairs, int64_t D, int variant, hipStream_t stream)
 {
+    if (variant == ASTRA_VARIANT_SCALAR_LOADS) {
+        const uint32_t n = (uint32_t)(pairs * D);
+        merge_attn_states_lse_scalar_kernel<DT><<<dim3((n + 255u) / 256u), dim3(256), 0, stream>>>(
+            static_cast<uint16_t*>(v_out), lse_out, static_cast<const uint16_t*>(v_a), lse_a,
+            static_cast<const uint16_t*>(v_b), lse_b, n, (uint32_t)D, make_fastdiv((uint32_t)D));
+        return;
+    }
+    if (variant == ASTRA_VARIANT_UNHOISTED_WEIGHTS) {
+        const uint32_t dvec = (uint32_t)(D / kVecElems);
+        const int log2_dvec = (dvec & (dvec - 1)) == 0 ? __builtin_ctz(dvec) : -1;
+        merge_attn_states_lse_vec_kernel<DT, kMergeUnroll, kNTLoad, kNTStore, false>
+            <<<dim3((uint32_t)li.grid), dim3(256), 0, stream>>>(
+                static_cast<u32x4*>(v_out), lse_out, static_cast<const u32x4*>(v_a), lse_a, static_cast<const u32x4*>(v_b),
+                lse_b, (uint32_t)(pairs * dvec), dvec, log2_dvec, make_fastdiv(dvec), li.log2_xcd_chunk);
+        return;
+    }
     if (li.path == ASTRA_PATH_GENERIC) {
         merge_attn_states_lse_generic_kernel<DT><<<dim3((uint32_t)li.grid), dim3(li.block), 0, stream>>>(
             static_cast<uint16_t*>(v_out), lse_out, static_cast<const uint16_t*>(v_a), lse_a,
@@ -239,6 +289,7 @@ const char* astra_status_string(astra_status_t status)
         case ASTRA_ERR_ALIAS: return "output overlaps an input";
         case ASTRA_ERR_LAUNCH: return "kernel launch failed";
     }
+    if ((int)status == ASTRA_ERR_VARIANT) return "ablation variant not applicable to this operator or shape";
     return "unknown status";
 }
 
@@ -267,8 +318,8 @@ astra_status_t astra_plan_merge_attn_states_lse(int64_t T, int64_t num_heads, in
     return plan_merge(T, num_heads, head_dim, aligned16 != 0, info);
 }
 
-astra_status_t astra_fused_add_rmsnorm(void* input, void* residual, const void* weight, int64_t T, int64_t H,
-                                       astra_dtype_t dtype, float eps, hipStream_t stream)
+static astra_status_t run_fused_add_rmsnorm(void* input, void* residual, const void* weight, int64_t T, int64_t H,
+                                            astra_dtype_t dtype, float eps, int variant, hipStream_t stream)
 {
     if (!input || !residual || !weight) return ASTRA_ERR_NULL;
     astra_launch_info_t li;
@@ -282,14 +333,32 @@ astra_status_t astra_fused_add_rmsnorm(void* input, void* residual, const void* 
     if (overlaps(input, bytes, residual, bytes) || overlaps(input, bytes, weight, H * 2) ||
         overlaps(residual, bytes, weight, H * 2))
         return ASTRA_ERR_ALIAS;
+    if (variant != ASTRA_VARIANT_TUNED) {
+        if (variant != ASTRA_VARIANT_SCALAR_LOADS && variant != ASTRA_VARIANT_LDS_TREE_REDUCTION) return (astra_status_t)ASTRA_ERR_VARIANT;
+        if (T > 0 && li.path != ASTRA_PATH_VECTOR) return (astra_status_t)ASTRA_ERR_VARIANT;
+        if (variant == ASTRA_VARIANT_SCALAR_LOADS && H > 16384) return (astra_status_t)ASTRA_ERR_VARIANT;
+    }
     if (T == 0) return ASTRA_OK;
-    if (dtype == ASTRA_BF16) launch_rmsnorm<kBF16>(li, input, residual, weight, T, H, eps, stream);
-    else launch_rmsnorm<kF16>(li, input, residual, weight, T, H, eps, stream);
+    if (dtype == ASTRA_BF16) launch_rmsnorm<kBF16>(li, input, residual, weight, T, H, eps, variant, stream);
+    else launch_rmsnorm<kF16>(li, input, residual, weight, T, H, eps, variant, stream);
     return after_launch();
 }
 
-astra_status_t astra_silu_and_mul(void* out, const void* input, int64_t T, int64_t d, astra_dtype_t dtype,
-                                  hipStream_t stream)
+astra_status_t astra_fused_add_rmsnorm(void* input, void* residual, const void* weight, int64_t T, int64_t H,
+                                       astra_dtype_t dtype, float eps, hipStream_t stream)
+{
+    return run_fused_add_rmsnorm(input, residual, weight, T, H, dtype, eps, ASTRA_VARIANT_TUNED, stream);
+}
+
+astra_status_t astra_ablation_fused_add_rmsnorm(void* input, void* residual, const void* weight, int64_t T, int64_t H,
+                                                astra_dtype_t dtype, float eps, astra_variant_t variant,
+                                                hipStream_t stream)
+{
+    return run_fused_add_rmsnorm(input, residual, weight, T, H, dtype, eps, (int)variant, stream);
+}
+
+static astra_status_t run_silu_and_mul(void* out, const void* input, int64_t T, int64_t d, astra_dtype_t dtype,
+                                       int variant, hipStream_t stream)
 {
     if (!out || !input) return ASTRA_ERR_NULL;
     astra_launch_info_t li;
@@ -298,15 +367,32 @@ astra_status_t astra_silu_and_mul(void* out, const void* input, int64_t T, int64
     if (!valid_dtype((int)dtype)) return ASTRA_ERR_DTYPE;
     if (!aligned(out, 2) || !aligned(input, 2)) return ASTRA_ERR_ALIGN;
     if (overlaps(out, T * d * 2, input, T * d * 4)) return ASTRA_ERR_ALIAS;
+    if (variant != ASTRA_VARIANT_TUNED) {
+        if (variant != ASTRA_VARIANT_SCALAR_LOADS && variant != ASTRA_VARIANT_LIBM_EXP_DIVIDE) return (astra_status_t)ASTRA_ERR_VARIANT;
+        if (T > 0 && li.path != ASTRA_PATH_VECTOR) return (astra_status_t)ASTRA_ERR_VARIANT;
+        if (variant == ASTRA_VARIANT_SCALAR_LOADS && T * d >= (int64_t(1) << 32)) return (astra_status_t)ASTRA_ERR_VARIANT;
+    }
     if (T == 0) return ASTRA_OK;
-    if (dtype == ASTRA_BF16) launch_silu<kBF16>(li, out, input, T, d, stream);
-    else launch_silu<kF16>(li, out, input, T, d, stream);
+    if (dtype == ASTRA_BF16) launch_silu<kBF16>(li, out, input, T, d, variant, stream);
+    else launch_silu<kF16>(li, out, input, T, d, variant, stream);
     return after_launch();
 }
 
-astra_status_t astra_merge_attn_states_lse(void* v_out, float* lse_out, const void* v_a, const float* lse_a,
-                                           const void* v_b, const float* lse_b, int64_t T, int64_t num_heads,
-                                           int64_t head_dim, astra_dtype_t dtype, hipStream_t stream)
+astra_status_t astra_silu_and_mul(void* out, const void* input, int64_t T, int64_t d, astra_dtype_t dtype,
+                                  hipStream_t stream)
+{
+    return run_silu_and_mul(out, input, T, d, dtype, ASTRA_VARIANT_TUNED, stream);
+}
+
+astra_status_t astra_ablation_silu_and_mul(void* out, const void* input, int64_t T, int64_t d, astra_dtype_t dtype,
+                                           astra_variant_t variant, hipStream_t stream)
+{
+    return run_silu_and_mul(out, input, T, d, dtype, (int)variant, stream);
+}
+
+static astra_status_t run_merge_attn_states_lse(void* v_out, float* lse_out, const void* v_a, const float* lse_a,
+                                                const void* v_b, const float* lse_b, int64_t T, int64_t num_heads,
+                                                int64_t head_dim, astra_dtype_t dtype, int variant, hipStream_t stream)
 {
     if (!v_out || !lse_out || !v_a || !lse_a || !v_b || !lse_b) return ASTRA_ERR_NULL;
     astra_launch_info_t li;
@@ -325,10 +411,32 @@ astra_status_t astra_merge_attn_states_lse(void* v_out, float* lse_out, const vo
         overlaps(lse_out, sbytes, v_a, vbytes) || overlaps(lse_out, sbytes, v_b, vbytes) ||
         overlaps(lse_out, sbytes, v_out, vbytes))
         return ASTRA_ERR_ALIAS;
+    if (variant != ASTRA_VARIANT_TUNED) {
+        if (variant != ASTRA_VARIANT_SCALAR_LOADS && variant != ASTRA_VARIANT_UNHOISTED_WEIGHTS) return (astra_status_t)ASTRA_ERR_VARIANT;
+        if (T > 0 && li.path != ASTRA_PATH_VECTOR) return (astra_status_t)ASTRA_ERR_VARIANT;
+        if (variant == ASTRA_VARIANT_SCALAR_LOADS && pairs * head_dim >= (int64_t(1) << 32)) return (astra_status_t)ASTRA_ERR_VARIANT;
+    }
     if (T == 0) return ASTRA_OK;
-    if (dtype == ASTRA_BF16) launch_merge<kBF16>(li, v_out, lse_out, v_a, lse_a, v_b, lse_b, pairs, head_dim, stream);
-    else launch_merge<kF16>(li, v_out, lse_out, v_a, lse_a, v_b, lse_b, pairs, head_dim, stream);
+    if (dtype == ASTRA_BF16) launch_merge<kBF16>(li, v_out, lse_out, v_a, lse_a, v_b, lse_b, pairs, head_dim, variant, stream);
+    else launch_merge<kF16>(li, v_out, lse_out, v_a, lse_a, v_b, lse_b, pairs, head_dim, variant, stream);
     return after_launch();
+}
+
+astra_status_t astra_merge_attn_states_lse(void* v_out, float* lse_out, const void* v_a, const float* lse_a,
+                                           const void* v_b, const float* lse_b, int64_t T, int64_t num_heads,
+                                           int64_t head_dim, astra_dtype_t dtype, hipStream_t stream)
+{
+    return run_merge_attn_states_lse(v_out, lse_out, v_a, lse_a, v_b, lse_b, T, num_heads, head_dim, dtype,
+                                     ASTRA_VARIANT_TUNED, stream);
+}
+
+astra_status_t astra_ablation_merge_attn_states_lse(void* v_out, float* lse_out, const void* v_a, const float* lse_a,
+                                                    const void* v_b, const float* lse_b, int64_t T, int64_t num_heads,
+                                                    int64_t head_dim, astra_dtype_t dtype, astra_variant_t variant,
+                                                    hipStream_t stream)
+{
+    return run_merge_attn_states_lse(v_out, lse_out, v_a, lse_a, v_b, lse_b, T, num_heads, head_dim, dtype, (int)variant,
+                                     stream);
 }
 
 astra_status_t astra_stream_copy(void* dst, const void* src, int64_t nbytes, hipStream_t stream)

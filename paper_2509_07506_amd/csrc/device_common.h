@@ -198,4 +198,26 @@ __device__ __forceinline__ float block_sum(float v, float* lds, int nwaves)
     return total;
 }
 
+// Ablation only -- the reduction of the paper's Fig. 3a: every lane writes its value to LDS, then a
+// tree halves the number of active lanes per step with a barrier after each step.  `lds` holds 1024
+// floats; blockDim.x is a multiple of 64 (not necessarily a power of two: the first step folds the
+// part above the largest power of two onto the bottom).
+__device__ __forceinline__ float block_sum_lds_tree(float v, float* lds)
+{
+    const uint32_t t = threadIdx.x, n = blockDim.x;
+    uint32_t p = 1;
+    while (p * 2 <= n) p *= 2;  // largest power of two <= n
+    lds[t] = v;
+    __syncthreads();
+    if (t + p < n) lds[t] += lds[t + p];
+    __syncthreads();
+    for (uint32_t off = p / 2; off > 0; off >>= 1) {
+        if (t < off) lds[t] += lds[t + off];
+        __syncthreads();
+    }
+    const float total = lds[0];
+    __syncthreads();  // lds is reused by the next row
+    return total;
+}
+
 }  // namespace astra

@@ -11,16 +11,17 @@
 
 namespace astra {
 
-// Fast path: H % 8 == 0, 16-byte aligned pointers, hv = H/8 <= VPT * blockDim.x.
+// Fast path: H % 8 == 0, 16-byte aligned pointers, hv = H/8 <= VPT * blockDim.x (VPT is 1, 2 or 4).
 // blockDim.x is a multiple of 64 and at most MAX_THREADS.  Lane `tid` owns vectors tid + k*blockDim.x.
 // A block walks rows r0, r0 + gridDim.x, ... (normally exactly one row), r0 = xcd_chunked(blockIdx.x).
-template <int DT, int VPT, int MAX_THREADS, bool NTL, bool NTS>
+template <int DT, int VPT, int MAX_THREADS, bool NTL, bool NTS, bool LDS_TREE = false>
 __global__ __launch_bounds__(MAX_THREADS) void fused_add_rmsnorm_row_kernel(u32x4* input, u32x4* residual,
                                                                             const u32x4* __restrict__ weight,
                                                                             int64_t T, uint32_t hv, float inv_h, float eps,
                                                                             int log2_chunk)
 {
     __shared__ float partials[2][16];
+    __shared__ float tree[LDS_TREE ? 1024 : 1];  // ablation only
     const int nwaves = blockDim.x >> 6;
     const int64_t first_row = xcd_chunked(blockIdx.x, log2_chunk);
     if (first_row >= T) return;  // grid padding; uniform for the whole workgroup
@@ -65,7 +66,7 @@ __global__ __launch_bounds__(MAX_THREADS) void fused_add_rmsnorm_row_kernel(u32x
             }
         }
 
-        const float total = block_sum(acc, partials[parity], nwaves);
+        const float total = LDS_TREE ? block_sum_lds_tree(acc, tree) : block_sum(acc, partials[parity], nwaves);
         const float scale = fast_rsqrt(total * inv_h + eps);
 
 #pragma unroll

@@ -39,7 +39,7 @@ __device__ __forceinline__ MergeWeights merge_weights(float sa, float sb)
 // per pair.  The pair index is a shift when dvec is a power of two (LOG2_DVEC >= 0), otherwise a
 // multiply-high division.  v_out may alias v_a or v_b exactly: all loads of a lane precede its stores.
 // lse_out must not alias the input scores: the lanes of one pair can sit in different waves.
-template <int DT, int UNROLL, bool NTL, bool NTS>
+template <int DT, int UNROLL, bool NTL, bool NTS, bool HOIST = true>
 __global__ __launch_bounds__(256) void merge_attn_states_lse_vec_kernel(u32x4* v_out, float* lse_out, const u32x4* v_a,
                                                                         const float* lse_a, const u32x4* v_b,
                                                                         const float* lse_b, uint32_t total_vecs,
@@ -69,8 +69,21 @@ __global__ __launch_bounds__(256) void merge_attn_states_lse_vec_kernel(u32x4* v
             float a[8], b[8], o[8];
             unpack8<DT>(av[k], a);
             unpack8<DT>(bv[k], b);
+            if constexpr (HOIST) {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) o[e] = w.a * a[e] + w.b * b[e];
+                for (int e = 0; e < 8; ++e) o[e] = w.a * a[e] + w.b * b[e];
+            } else {
+                // ablation only (the pattern of the paper's Fig. 2a): the weights are worked out again for
+                // every element.  The empty asm makes the score opaque so the compiler cannot merge the
+                // eight evaluations back into one.
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    float s = sa[k];
+                    asm volatile("" : "+v"(s));
+                    const MergeWeights we = merge_weights(s, sb[k]);
+                    o[e] = we.a * a[e] + we.b * b[e];
+                }
+            }
             store_vec<NTS>(v_out + i, pack8<DT>(o));
             if (i == pair[k] * dvec) lse_out[pair[k]] = w.lse;  // first vector of the pair
         }

@@ -17,12 +17,16 @@ __device__ __forceinline__ float silu_fast(float x)
     return x * fast_rcp(1.0f + __builtin_amdgcn_exp2f(x * -kLog2e));
 }
 
+// The plain form of the paper's Fig. 5a: library expf and an IEEE divide.  Only the ablation entry
+// point uses it (LIBM = true below).
+__device__ __forceinline__ float silu_libm(float x) { return x / (1.0f + expf(-x)); }
+
 // Fast path: d % 8 == 0 and 16-byte aligned pointers.  Work is the flat list of output vectors
 // (dv = d/8 per row); a block owns 256*UNROLL consecutive ones.  The row of the block's first vector
 // comes from one scalar fast division; lanes then step to the next row when they run past the end
 // of a row (at most a few steps because the host only takes this path when dv >= 32).
 // For output vector (t, j):  x = in[t*2dv + j], g = in[t*2dv + dv + j], out index = t*dv + j.
-template <int DT, int UNROLL, bool NTL, bool NTS>
+template <int DT, int UNROLL, bool NTL, bool NTS, bool LIBM = false>
 __global__ __launch_bounds__(256) void silu_and_mul_vec_kernel(u32x4* __restrict__ out, const u32x4* __restrict__ in,
                                                                uint32_t total_vecs, uint32_t dv, FastDiv by_dv,
                                                                int log2_chunk)
@@ -57,7 +61,7 @@ __global__ __launch_bounds__(256) void silu_and_mul_vec_kernel(u32x4* __restrict
             unpack8<DT>(xv[k], x);
             unpack8<DT>(gv[k], g);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) o[e] = silu_fast(x[e]) * g[e];
+            for (int e = 0; e < 8; ++e) o[e] = (LIBM ? silu_libm(x[e]) : silu_fast(x[e])) * g[e];
             store_vec<NTS>(out + oidx[k], pack8<DT>(o));
         }
     }

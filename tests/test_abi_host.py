@@ -41,8 +41,8 @@ def test_every_declared_symbol_is_exported(A):
 
 
 def test_status_strings(A):
-    seen = {A.astra_status_string(i) for i in range(8)}
-    assert len(seen) == 8 and A.astra_status_string(0) == "ok"
+    seen = {A.astra_status_string(i) for i in range(9)}
+    assert len(seen) == 9 and A.astra_status_string(0) == "ok"
     assert "unknown" in A.astra_status_string(99)
 
 
@@ -163,6 +163,23 @@ def test_xcd_chunked_is_a_permutation_with_contiguous_runs(A):
                 assert run == list(range(run[0], run[0] + C)) and run[0] % C == 0
     assert [A.astra_plan_xcd_chunked(b, 0) for b in range(20)] == list(range(20))
     assert A.astra_plan_xcd_chunked(5, 99) == 5
+
+
+def test_ablation_variant_validation(A):
+    """same validation as the plain entry points, then the variant check; nothing here reaches the device"""
+    a, b, c = 0x10000, 0x20000, 0x30000
+    f = A.astra_ablation_fused_add_rmsnorm
+    assert f(0, b, c, 1, 8, 1, 1e-6, 1) == 1 and f(a, b, c, -1, 8, 1, 1e-6, 1) == 2 and f(a, b, c, 1, 8, 9, 1e-6, 1) == 3
+    assert f(a, b, c, 1, 8, 1, 1e-6, 3) == 8 and f(a, b, c, 1, 8, 1, 1e-6, 4) == 8 and f(a, b, c, 1, 8, 1, 1e-6, -1) == 8
+    assert f(a, b, c, 1, 12, 1, 1e-6, 2) == 8            # H % 8 != 0: not the fast path
+    assert f(a, b, c, 1, 32768, 1, 1e-6, 1) == 8         # scalar-load variant keeps at most 16 elements per lane
+    assert f(a, b, c, 0, 8, 1, 1e-6, 2) == 0
+    g = A.astra_ablation_silu_and_mul
+    assert g(a, b, 1, 512, 1, 2) == 8 and g(a, b, 1, 512, 1, 3) == 8 and g(a, b, 1, 100, 1, 1) == 8 and g(a, b, 0, 512, 1, 4) == 0
+    h = A.astra_ablation_merge_attn_states_lse
+    vo, lo, va, la, vb, lb = 0x10000, 0x20000, 0x30000, 0x40000, 0x50000, 0x60000
+    assert h(vo, lo, va, la, vb, lb, 1, 2, 8, 1, 2) == 8 and h(vo, lo, va, la, vb, lb, 1, 2, 8, 1, 4) == 8
+    assert h(vo, lo, va, la, vb, lb, 1, 2, 4, 1, 3) == 8 and h(vo, lo, va, la, vb, lb, 0, 2, 8, 1, 3) == 0
 
 
 def test_binding_refuses_cpu_tensors(A):

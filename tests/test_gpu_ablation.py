@@ -1,0 +1,127 @@
+"""The ablation variants (include/astra_ablation.h) compute the same operators: each is checked against the
+oracle to the operators' own bars, on the paper's Table-4 shapes and on shapes that cross tile edges."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+import workloads
+from tests.gpu_util import TORCH_DT, assert_lse_close, assert_storage_close, to_bits, to_dev
+from tests.util import assert_bits_equal
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def A():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2509_07506_amd as astra
+
+    astra.load_library()
+    O.build()
+    O.set_threads(min(16, len(os.sched_getaffinity(0))))
+    return astra
+
+
+def _code(A, dt):
+    return A.ASTRA_BF16 if dt == "bf16" else A.ASTRA_F16
+
+
+def _rmsnorm(A, x, r, w, eps, dt, variant):
+    xd, rd, wd = to_dev(x, dt), to_dev(r, dt), to_dev(w, dt)
+    T, H = x.shape
+    st = A.astra_ablation_fused_add_rmsnorm(xd.data_ptr(), rd.data_ptr(), wd.data_ptr(), T, H, _code(A, dt), eps, variant,
+                                            torch.cuda.current_stream().cuda_stream)
+    assert st == 0, A.astra_status_string(st)
+    torch.cuda.synchronize()
+    y_ref, res_ref = O.fused_add_rmsnorm(x, r, w, eps, dt)
+    assert_bits_equal(to_bits(rd), res_ref, f"variant {variant}: residual (bit-exact)")
+    assert_storage_close(to_bits(xd), y_ref, dt, f"variant {variant}: normalised output")
+
+
+def _silu(A, a, dt, variant):
+    ad = to_dev(a, dt)
+    T, d = a.shape[0], a.shape[1] // 2
+    out = torch.empty((T, d), dtype=TORCH_DT[dt], device="cuda")
+    st = A.astra_ablation_silu_and_mul(out.data_ptr(), ad.data_ptr(), T, d, _code(A, dt), variant,
+                                       torch.cuda.current_stream().cuda_stream)
+    assert st == 0, A.astra_status_string(st)
+    torch.cuda.synchronize()
+    assert_storage_close(to_bits(out), O.silu_and_mul(a, dt), dt, f"variant {variant}: out")
+
+
+def _merge(A, va, la, vb, lb, dt, variant):
+    vad, vbd = to_dev(va, dt), to_dev(vb, dt)
+    lad, lbd = torch.from_numpy(la).cuda(), torch.from_numpy(lb).cuda()
+    vo, lo = torch.empty_like(vad), torch.empty_like(lad)
+    T, NH, D = va.shape
+    st = A.astra_ablation_merge_attn_states_lse(vo.data_ptr(), lo.data_ptr(), vad.data_ptr(), lad.data_ptr(), vbd.data_ptr(),
+                                                lbd.data_ptr(), T, NH, D, _code(A, dt), variant,
+                                                torch.cuda.current_stream().cuda_stream)
+    assert st == 0, A.astra_status_string(st)
+    torch.cuda.synchronize()
+    vo_ref, lo_ref = O.merge_attn_states_lse(va, la, vb, lb, dt)
+    assert_storage_close(to_bits(vo), vo_ref, dt, f"variant {variant}: v_out")
+    assert_lse_close(lo.cpu().numpy(), lo_ref, f"variant {variant}: lse_out")
+
+
+RMS_VARIANTS = (0, 1, 2)     # tuned, scalar loads, LDS tree reduction
+SILU_VARIANTS = (0, 1, 4)    # tuned, scalar loads, libm exp + divide
+MERGE_VARIANTS = (0, 1, 3)   # tuned, scalar loads, unhoisted weights
+
+
+@pytest.mark.parametrize("name", sorted(workloads.PAPER_SHAPE_CASES))
+def test_paper_table4_shapes_all_variants(A, name):
+    c = workloads.case(name)
+    print(f"[ablation] {name}", flush=True)
+    data = c.generate()
+    if c.kernel == "rmsnorm":
+        for v in RMS_VARIANTS:
+            _rmsnorm(A, *data, c.eps, c.dtype, v)
+    elif c.kernel == "silu":
+        for v in SILU_VARIANTS:
+            _silu(A, data[0], c.dtype, v)
+    else:
+        for v in MERGE_VARIANTS:
+            _merge(A, *data, c.dtype, v)
+
+
+@pytest.mark.parametrize("dt", ["bf16", "f16"])
+@pytest.mark.parametrize("T,H", [(3, 8), (5, 520), (7, 5120), (300, 7168), (2, 8192), (4, 11008), (600, 14336), (3, 16384)])
+def test_rmsnorm_variants_edge_shapes(A, T, H, dt):
+    x, r, w = workloads.rmsnorm_inputs(T, H, dt, np.random.default_rng([31, T, H]), r_std=2.0)
+    for v in RMS_VARIANTS[1:]:
+        _rmsnorm(A, x, r, w, 1e-5, dt, v)
+
+
+@pytest.mark.parametrize("dt", ["bf16", "f16"])
+@pytest.mark.parametrize("T,d", [(1, 256), (3, 264), (7, 1000), (19, 5120), (257, 1408)])
+def test_silu_variants_edge_shapes(A, T, d, dt):
+    a = workloads.silu_inputs(T, d, dt, np.random.default_rng([32, T, d]))
+    a[0, :6] = workloads.to_bits(np.array([-100.0, -89.0, -20.0, 0.0, 20.0, 90.0], np.float32), dt)
+    for v in SILU_VARIANTS[1:]:
+        _silu(A, a, dt, v)
+
+
+@pytest.mark.parametrize("dt", ["bf16", "f16"])
+@pytest.mark.parametrize("T,NH,D", [(1, 1, 8), (7, 3, 72), (9, 8, 80), (257, 40, 64), (33, 32, 128)])
+def test_merge_variants_edge_shapes(A, T, NH, D, dt):
+    m = workloads.merge_inputs(T, NH, D, dt, np.random.default_rng([33, T, NH, D]), empty_p=0.15)
+    for v in MERGE_VARIANTS[1:]:
+        _merge(A, *m, dt, v)
+
+
+def test_variant_validation_on_device(A):
+    buf = torch.zeros(1 << 16, dtype=torch.float16, device="cuda")
+    p = buf.data_ptr()
+    E = A.ASTRA_ERR_VARIANT
+    assert A.astra_ablation_fused_add_rmsnorm(p, p + 8192, p + 16384, 2, 512, A.ASTRA_F16, 1e-6, 3, None) == E
+    assert A.astra_ablation_fused_add_rmsnorm(p, p + 8192, p + 16384, 2, 516, A.ASTRA_F16, 1e-6, 2, None) == E   # not the fast path
+    assert A.astra_ablation_silu_and_mul(p, p + 65536, 2, 512, A.ASTRA_F16, 2, None) == E
+    assert A.astra_ablation_merge_attn_states_lse(p, p + 1024, p + 2048, p + 3072, p + 4096, p + 5120, 1, 2, 8, A.ASTRA_F16, 4, None) == E
+    assert A.astra_ablation_silu_and_mul(p, p + 65536, 2, 512, A.ASTRA_F16, 99, None) == E
+    torch.cuda.synchronize()
+    assert bool((buf == 0).all())

@@ -147,8 +147,27 @@ def _cases():
     return out
 
 
+def _paper_shape_cases():
+    """The twelve shapes of the paper's Table 4 (Section 6.1): [seq_len, heads, head_dim] for the merge,
+    [batch, hidden] for the other two (for silu_and_mul `hidden` is read as the output width d).  fp16,
+    the only storage type the paper's listings show; value recipes as in the benchmark configs."""
+    out = []
+    k = 0
+    for T, NH, D in ((512, 32, 256), (512, 40, 128), (768, 32, 256), (512, 64, 128)):
+        out.append(Case(f"p4_merge_T{T}_NH{NH}_D{D}_f16", "merge", 5, k, "f16", {"T": T, "NH": NH, "D": D}))
+        k += 1
+    for T, H in ((256, 4096), (1024, 4096), (128, 11008), (512, 14336)):
+        out.append(Case(f"p4_rmsnorm_T{T}_H{H}_f16", "rmsnorm", 5, k, "f16", {"T": T, "H": H}, eps=1e-6))
+        k += 1
+    for T, d in ((16, 4096), (32, 5120), (64, 8192), (16, 12288)):
+        out.append(Case(f"p4_silu_T{T}_d{d}_f16", "silu", 5, k, "f16", {"T": T, "d": d}))
+        k += 1
+    return out
+
+
 CASES = {c.name: c for c in _cases()}
+PAPER_SHAPE_CASES = {c.name: c for c in _paper_shape_cases()}
 
 
 def case(name: str) -> Case:
-    return CASES[name]
+    return CASES[name] if name in CASES else PAPER_SHAPE_CASES[name]
