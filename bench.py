@@ -17,6 +17,7 @@ taken inside the timed region on the launch stream; `kernels` carries the same f
     python bench.py --sweep          # per-workload table over every config (one JSON line per case)
     python bench.py --ceiling        # streaming-copy ceiling of the machine (same access pattern)
     python bench.py --ablation       # paper Table-4 shapes: tuned vs one-optimisation-removed variants
+    python bench.py --kway           # K-way merge vs a chain of two-way merges
 """
 from __future__ import annotations
 
@@ -370,6 +371,73 @@ def run_ablation(args):
                           "cold": round(gm([a for a, _ in v]), 3), "hot": round(gm([b for _, b in v]), 3)}), flush=True)
 
 
+def run_kway(args):
+    """K-way merge against a chain of K-1 two-way merges on the headline merge shape (T=4096, 32 heads x
+    128, bf16): microseconds per merged result and GB/s on each path's own algorithmic bytes
+    ((K+1) tensor passes for the K-way kernel, 3(K-1) for the chain).  Cold: buffers rotate."""
+    import numpy as np
+    import torch
+
+    import paper_2509_07506_amd as astra
+    import workloads
+
+    astra.load_library()
+    torch.cuda.set_device(0)
+    stream = torch.cuda.current_stream()
+    sh = stream.cuda_stream
+    T, NH, D = 4096, 32, 128
+    code = astra.ASTRA_BF16
+    for K in (2, 4, 8, 16):
+        rng = np.random.default_rng([7, K])
+        parts = [workloads.merge_inputs(T, NH, D, "bf16", rng)[:2] for _ in range(K)]
+        nsets = max(2, (1 << 30) // (K * T * NH * D * 2) + 1)
+        v = torch.stack([_to_dev(np.stack([p[0] for p in parts]), "bf16")] * nsets)          # [nsets, K, T, NH, D]
+        s = torch.stack([torch.from_numpy(np.stack([p[1] for p in parts])).cuda()] * nsets)
+        vo = torch.empty((nsets, T, NH, D), dtype=torch.bfloat16, device="cuda")
+        tmp = torch.empty((nsets, T, NH, D), dtype=torch.bfloat16, device="cuda")
+        lo = torch.empty((nsets, T, NH), dtype=torch.float32, device="cuda")
+        ltmp = torch.empty((nsets, T, NH), dtype=torch.float32, device="cuda")
+        vb, sb = T * NH * D * 2, T * NH * 4
+
+        def kway(i):
+            st = astra.astra_merge_attn_states_lse_kway(vo[i].data_ptr(), lo[i].data_ptr(), v[i].data_ptr(), s[i].data_ptr(), K,
+                                                        T, NH, D, code, sh)
+            assert st == 0, st
+
+        def chain(i):
+            # ((p0 + p1) + p2) + ...: intermediate results ping-pong between two buffers (v_out may alias v_a)
+            va, la = v[i].data_ptr(), s[i].data_ptr()
+            cur_v, cur_l = va, la
+            for k in range(1, K):
+                ov, ol = (vo[i].data_ptr(), lo[i].data_ptr()) if k % 2 else (tmp[i].data_ptr(), ltmp[i].data_ptr())
+                st = astra.astra_merge_attn_states_lse(ov, ol, cur_v, cur_l, va + k * vb, la + k * sb, T, NH, D, code, sh)
+                assert st == 0, st
+                cur_v, cur_l = ov, ol
+
+        def timed(fn):
+            reps, warm = 50, 10
+            for k in range(warm):
+                fn(k % nsets)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for k in range(reps):
+                fn((warm + k) % nsets)
+            e1.record(stream)
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) * 1e3 / reps
+
+        tk, tc = timed(kway), timed(chain)
+        bk = (K + 1) * (vb + sb)
+        bc = 3 * (K - 1) * (vb + sb)
+        print(json.dumps({"case": f"merge_kway_K{K}_T{T}_NH{NH}_D{D}_bf16", "kway_us": round(tk, 2), "kway_bytes": bk,
+                          "kway_GBs": round(bk / tk / 1e3, 1), "kway_frac_of_peak": round(bk / tk / 1e3 / HBM_PEAK_GBS, 4),
+                          "chain_us": round(tc, 2), "chain_bytes": bc, "chain_GBs": round(bc / tc / 1e3, 1),
+                          "speedup_over_chain": round(tc / tk, 3)}), flush=True)
+        del v, s, vo, tmp, lo, ltmp
+        torch.cuda.empty_cache()
+
+
 def run_ceiling(args):
     """Streaming ceiling of this machine with the operators' access pattern: astra_stream_copy over
     512 MiB, alternating between two source/destination pairs (2 GiB footprint, so always cold)."""
@@ -416,6 +484,7 @@ def main():
     ap.add_argument("--sweep", action="store_true", help="per-workload table over every config")
     ap.add_argument("--only", default=None, help="with --sweep: substring filter on the case name")
     ap.add_argument("--ceiling", action="store_true", help="measure the streaming-copy ceiling of the machine")
+    ap.add_argument("--kway", action="store_true", help="K-way merge vs a chain of two-way merges")
     ap.add_argument("--ablation", action="store_true",
                     help="paper Table-4 shapes and the bandwidth workloads: tuned kernel vs each one-optimisation-removed variant")
     args = ap.parse_args()
@@ -423,7 +492,9 @@ def main():
         print("bench.py: this path runs on ONE GPU (row-independent kernels, no collectives); "
               "--gpus N with N > 1 is not supported", file=sys.stderr)
         sys.exit(2)
-    if args.ablation:
+    if args.kway:
+        run_kway(args)
+    elif args.ablation:
         run_ablation(args)
     elif args.ceiling:
         run_ceiling(args)

@@ -60,6 +60,8 @@ def lib() -> ctypes.CDLL:
         L.oracle_merge_weights_f32.argtypes = [f32, f32, vp, vp, vp]
         L.oracle_merge_attn_states_lse.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, i32]
         L.oracle_merge_attn_states_lse_f32.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64]
+        L.oracle_merge_attn_states_lse_kway.argtypes = [vp, vp, vp, vp, i64, i64, i64, i32]
+        L.oracle_merge_attn_states_lse_kway.restype = None
         for name in ("oracle_widen_array", "oracle_narrow_array", "oracle_set_threads", "oracle_fused_add_rmsnorm_f32",
                      "oracle_fused_add_rmsnorm", "oracle_silu_and_mul", "oracle_silu_and_mul_f32",
                      "oracle_merge_weights_f32", "oracle_merge_attn_states_lse", "oracle_merge_attn_states_lse_f32"):
@@ -193,4 +195,15 @@ def merge_attn_states_lse_f32(va, lse_a, vb, lse_b):
     vo = np.empty((T, NH, D), np.float32)
     lo = np.empty((T, NH), np.float32)
     lib().oracle_merge_attn_states_lse_f32(_ptr(vo), _ptr(lo), _ptr(va), _ptr(la), _ptr(vb), _ptr(lb), T, NH, D)
+    return vo, lo
+
+
+def merge_attn_states_lse_kway(v_parts_bits, lse_parts, dtype: str):
+    """K-way merge.  v_parts [K,T,NH,D] uint16, lse_parts [K,T,NH] float32 -> (v_out [T,NH,D], lse_out [T,NH])."""
+    v, l = _u16(v_parts_bits), _f32(lse_parts)
+    K, T, NH, D = v.shape
+    assert l.shape == (K, T, NH)
+    vo = np.empty((T, NH, D), np.uint16)
+    lo = np.empty((T, NH), np.float32)
+    lib().oracle_merge_attn_states_lse_kway(_ptr(vo), _ptr(lo), _ptr(v), _ptr(l), K, T * NH, D, DTYPES[dtype])
     return vo, lo

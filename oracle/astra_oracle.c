@@ -281,6 +281,38 @@ void oracle_merge_attn_states_lse(uint16_t* v_out, float* lse_out, const uint16_
     }
 }
 
+/* K-way merge: the K-term form of Table 1's Kernel 1,
+     V_out = sum_k e^(S_k) V_k / sum_k e^(S_k),   S_out = log sum_k e^(S_k),
+   evaluated with m = max_k S_k subtracted from every score.  The paper defines only K = 2; this is the
+   same expression with more terms (merging is associative, so it equals any chain of two-way merges up
+   to rounding).  v_parts: [K, P, D] patterns (P = T*NH pairs), lse_parts: [K, P] binary32.
+   Terms are accumulated in the order k = 0, 1, ..., K-1.  All scores -inf: V_out = 0, S_out = -inf. */
+void oracle_merge_attn_states_lse_kway(uint16_t* v_out, float* lse_out, const uint16_t* v_parts,
+                                       const float* lse_parts, int64_t K, int64_t P, int64_t D, int dtype)
+{
+#pragma omp parallel for schedule(static) num_threads(g_threads)
+    for (int64_t p = 0; p < P; ++p) {
+        float m = -INFINITY;
+        for (int64_t k = 0; k < K; ++k) m = fmaxf(m, lse_parts[k * P + p]);
+        if (m == -INFINITY) {
+            lse_out[p] = -INFINITY;
+            for (int64_t j = 0; j < D; ++j) v_out[p * D + j] = narrow(0.0f, dtype);
+            continue;
+        }
+        float den = 0.0f;
+        for (int64_t k = 0; k < K; ++k) den += expf(lse_parts[k * P + p] - m);
+        lse_out[p] = m + logf(den);
+        for (int64_t j = 0; j < D; ++j) {
+            float acc = 0.0f;
+            for (int64_t k = 0; k < K; ++k) {
+                float a = expf(lse_parts[k * P + p] - m) / den;
+                acc += a * widen(v_parts[(k * P + p) * D + j], dtype);
+            }
+            v_out[p * D + j] = narrow(acc, dtype);
+        }
+    }
+}
+
 /* All-binary32 form. */
 void oracle_merge_attn_states_lse_f32(float* v_out, float* lse_out, const float* v_a, const float* lse_a,
                                       const float* v_b, const float* lse_b, int64_t T, int64_t NH, int64_t D)

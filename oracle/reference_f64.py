@@ -71,3 +71,19 @@ def merge_attn_states_lse(va_bits, lse_a, vb_bits, lse_b, dtype: str):
         s_out = np.where(empty, -np.inf, m0 + np.log(den))
     v_out = a[..., None] * va + b[..., None] * vb
     return v_out, s_out
+
+
+def merge_attn_states_lse_kway(v_parts_bits, lse_parts, dtype: str):
+    """K-way merge in float64: softmax over the K scores weights the K partial outputs; S_out is their
+    logsumexp.  v_parts [K,T,NH,D] uint16, lse_parts [K,T,NH].  All scores -inf: 0 and -inf."""
+    v = widen(v_parts_bits, dtype)
+    s = np.asarray(lse_parts, np.float64)
+    m = np.max(s, axis=0)
+    empty = np.isneginf(m)
+    m0 = np.where(empty, 0.0, m)
+    e = np.exp(s - m0)
+    den = e.sum(axis=0)
+    with np.errstate(divide="ignore", invalid="ignore"):
+        a = np.where(empty, 0.0, e / den)
+        s_out = np.where(empty, -np.inf, m0 + np.log(den))
+    return (a[..., None] * v).sum(axis=0), s_out

@@ -20,6 +20,7 @@ from .binding import (  # noqa: F401
     astra_ablation_silu_and_mul,
     astra_fused_add_rmsnorm,
     astra_merge_attn_states_lse,
+    astra_merge_attn_states_lse_kway,
     astra_plan_fused_add_rmsnorm,
     astra_plan_merge_attn_states_lse,
     astra_plan_silu_and_mul,
@@ -31,6 +32,7 @@ from .binding import (  # noqa: F401
     library_path,
     load_library,
     merge_attn_states_lse,
+    merge_attn_states_lse_kway,
     silu_and_mul,
     stream_copy,
 )

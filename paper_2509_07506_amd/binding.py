@@ -62,12 +62,18 @@ def load_library() -> ctypes.CDLL:
             _build.build()
         except Exception as e:  # no silent fallback: the product path needs the HIP library
             raise RuntimeError(f"astra HIP library is not built and building it failed: {e}") from e
+    # PyTorch ships its own HIP runtime; load it first so that this library binds to the same runtime as
+    # the streams and device buffers it is handed (two HIP runtimes in one process do not share streams).
+    import torch  # noqa: F401
+
     L = ctypes.CDLL(_LIB_PATH)
     vp, i64, i32, f32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_float
     L.astra_fused_add_rmsnorm.argtypes = [vp, vp, vp, i64, i64, i32, f32, vp]
     L.astra_silu_and_mul.argtypes = [vp, vp, i64, i64, i32, vp]
     L.astra_merge_attn_states_lse.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, i32, vp]
     L.astra_stream_copy.argtypes = [vp, vp, i64, vp]
+    L.astra_merge_attn_states_lse_kway.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, i32, vp]
+    L.astra_merge_attn_states_lse_kway.restype = i32
     L.astra_ablation_fused_add_rmsnorm.argtypes = [vp, vp, vp, i64, i64, i32, f32, i32, vp]
     L.astra_ablation_silu_and_mul.argtypes = [vp, vp, i64, i64, i32, i32, vp]
     L.astra_ablation_merge_attn_states_lse.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, i32, i32, vp]
@@ -110,6 +116,11 @@ def astra_merge_attn_states_lse(v_out, lse_out, v_a, lse_a, v_b, lse_b, T, num_h
 
 def astra_stream_copy(dst, src, nbytes, stream=None) -> int:
     return load_library().astra_stream_copy(dst, src, nbytes, stream)
+
+
+def astra_merge_attn_states_lse_kway(v_out, lse_out, v_parts, lse_parts, K, T, num_heads, head_dim, dtype, stream=None) -> int:
+    return load_library().astra_merge_attn_states_lse_kway(v_out, lse_out, v_parts, lse_parts, K, T, num_heads, head_dim,
+                                                           dtype, stream)
 
 
 def astra_ablation_fused_add_rmsnorm(input_ptr, residual_ptr, weight_ptr, T, H, dtype, eps, variant, stream=None) -> int:
@@ -222,6 +233,23 @@ def merge_attn_states_lse(v_out, lse_out, v_a, lse_a, v_b, lse_b, stream=None) -
                                      v_b.data_ptr(), lse_b.data_ptr(), T, NH, D, _dtype_code(v_a), _stream(stream))
     if st:
         raise AstraError(st, "astra_merge_attn_states_lse")
+
+
+def merge_attn_states_lse_kway(v_out, lse_out, v_parts, lse_parts, stream=None) -> None:
+    """(v_out, lse_out) <- merge of the K stacked partial states v_parts [K,T,NH,D], lse_parts [K,T,NH]."""
+    import torch
+
+    _check_gpu(v_out, lse_out, v_parts, lse_parts)
+    K, T, NH, D = v_parts.shape
+    if v_out.shape != (T, NH, D) or v_out.dtype != v_parts.dtype or lse_parts.shape != (K, T, NH) or \
+            lse_out.shape != (T, NH) or lse_parts.dtype != torch.float32 or lse_out.dtype != torch.float32:
+        raise ValueError("merge_attn_states_lse_kway: v_parts [K,T,NH,D], lse_parts [K,T,NH] f32, v_out [T,NH,D], lse_out [T,NH] f32")
+    if T == 0:
+        return
+    st = astra_merge_attn_states_lse_kway(v_out.data_ptr(), lse_out.data_ptr(), v_parts.data_ptr(), lse_parts.data_ptr(), K,
+                                          T, NH, D, _dtype_code(v_parts), _stream(stream))
+    if st:
+        raise AstraError(st, "astra_merge_attn_states_lse_kway")
 
 
 def stream_copy(dst, src, stream=None) -> None:

@@ -3,6 +3,7 @@
 // arithmetic, so every error path can be exercised without a GPU.
 #include "astra.h"
 #include "astra_ablation.h"
+#include "astra_kway.h"
 #include "astra_plan.h"
 
 #include <hip/hip_runtime.h>
@@ -28,6 +29,7 @@ constexpr bool kNTStore = true;   // and on the once-written outputs
 constexpr int kSiluUnroll = 1;
 constexpr int kMergeUnroll = 1;
 constexpr int kCopyUnroll = 1;
+constexpr int kKwayGroup = 4;     // partitions folded per step of the streaming K-way merge
 
 constexpr int64_t kMaxVecIndex = int64_t(1) << 31;  // 32-bit vector indices with head-room for the tail
 constexpr int64_t kMaxGenericGrid = int64_t(1) << 20;
@@ -437,6 +439,45 @@ astra_status_t astra_ablation_merge_attn_states_lse(void* v_out, float* lse_out,
 {
     return run_merge_attn_states_lse(v_out, lse_out, v_a, lse_a, v_b, lse_b, T, num_heads, head_dim, dtype, (int)variant,
                                      stream);
+}
+
+astra_status_t astra_merge_attn_states_lse_kway(void* v_out, float* lse_out, const void* v_parts,
+                                                const float* lse_parts, int64_t K, int64_t T, int64_t num_heads,
+                                                int64_t head_dim, astra_dtype_t dtype, hipStream_t stream)
+{
+    if (!v_out || !lse_out || !v_parts || !lse_parts) return ASTRA_ERR_NULL;
+    astra_launch_info_t li;
+    astra_status_t st = plan_merge(T, num_heads, head_dim, aligned(v_out, 16) && aligned(v_parts, 16), &li);
+    if (st != ASTRA_OK) return st;
+    const int64_t pairs = T * num_heads;
+    int64_t part_elems = pairs * head_dim, all_elems;
+    if (K < 1 || K > 65536 || mul_overflows(part_elems, K, &all_elems) || all_elems > std::numeric_limits<int64_t>::max() / 4)
+        return ASTRA_ERR_SHAPE;
+    if (!valid_dtype((int)dtype)) return ASTRA_ERR_DTYPE;
+    if (!aligned(v_out, 2) || !aligned(v_parts, 2) || !aligned(lse_out, 4) || !aligned(lse_parts, 4)) return ASTRA_ERR_ALIGN;
+    const int64_t vbytes = part_elems * 2, sbytes = pairs * 4;
+    if (overlaps(v_out, vbytes, v_parts, vbytes * K) || overlaps(v_out, vbytes, lse_parts, sbytes * K) ||
+        overlaps(lse_out, sbytes, v_parts, vbytes * K) || overlaps(lse_out, sbytes, lse_parts, sbytes * K) ||
+        overlaps(lse_out, sbytes, v_out, vbytes))
+        return ASTRA_ERR_ALIAS;
+    if (T == 0) return ASTRA_OK;
+    // every part starts 16-byte aligned when the base is and head_dim % 8 == 0 (fast-path conditions)
+    const bool generic = li.path == ASTRA_PATH_GENERIC;
+    const uint32_t dvec = (uint32_t)(head_dim / kVecElems);
+    const int log2_dvec = (!generic && (dvec & (dvec - 1)) == 0) ? __builtin_ctz(dvec) : -1;
+#define ASTRA_LAUNCH_KWAY(DT)                                                                                          \
+    if (generic)                                                                                                       \
+        merge_attn_states_lse_kway_generic_kernel<DT><<<dim3((uint32_t)li.grid), dim3(256), 0, stream>>>(              \
+            static_cast<uint16_t*>(v_out), lse_out, static_cast<const uint16_t*>(v_parts), lse_parts, (uint32_t)K, pairs, \
+            head_dim);                                                                                                 \
+    else                                                                                                               \
+        merge_attn_states_lse_kway_vec_kernel<DT, kKwayGroup, kNTLoad, kNTStore><<<dim3((uint32_t)li.grid), dim3(256), 0, stream>>>( \
+            static_cast<u32x4*>(v_out), lse_out, static_cast<const u32x4*>(v_parts), lse_parts, (uint32_t)K,           \
+            (uint32_t)(pairs * dvec), (uint32_t)pairs, dvec, log2_dvec, make_fastdiv(dvec ? dvec : 1), li.log2_xcd_chunk)
+    if (dtype == ASTRA_BF16) { ASTRA_LAUNCH_KWAY(kBF16); }
+    else { ASTRA_LAUNCH_KWAY(kF16); }
+#undef ASTRA_LAUNCH_KWAY
+    return after_launch();
 }
 
 astra_status_t astra_stream_copy(void* dst, const void* src, int64_t nbytes, hipStream_t stream)

@@ -39,20 +39,20 @@ __device__ __forceinline__ MergeWeights merge_weights(float sa, float sb)
 // per pair.  The pair index is a shift when dvec is a power of two (LOG2_DVEC >= 0), otherwise a
 // multiply-high division.  v_out may alias v_a or v_b exactly: all loads of a lane precede its stores.
 // lse_out must not alias the input scores: the lanes of one pair can sit in different waves.
-template <int DT, int UNROLL, bool NTL, bool NTS, bool HOIST = true>
-__global__ __launch_bounds__(256) void merge_attn_states_lse_vec_kernel(u32x4* v_out, float* lse_out, const u32x4* v_a,
+template <int DT, int UNROLL, bool NTL, bool NTS, bool HOIST = true, int BLOCK = 256>
+__global__ __launch_bounds__(BLOCK) void merge_attn_states_lse_vec_kernel(u32x4* v_out, float* lse_out, const u32x4* v_a,
                                                                         const float* lse_a, const u32x4* v_b,
                                                                         const float* lse_b, uint32_t total_vecs,
                                                                         uint32_t dvec, int log2_dvec, FastDiv by_dvec,
                                                                         int log2_chunk)
 {
-    const uint32_t first = xcd_chunked(blockIdx.x, log2_chunk) * (256u * UNROLL) + threadIdx.x;
+    const uint32_t first = xcd_chunked(blockIdx.x, log2_chunk) * (uint32_t(BLOCK) * UNROLL) + threadIdx.x;
     u32x4 av[UNROLL], bv[UNROLL];
     float sa[UNROLL], sb[UNROLL];
     uint32_t pair[UNROLL];
 #pragma unroll
     for (int k = 0; k < UNROLL; ++k) {
-        const uint32_t i = first + 256u * k;
+        const uint32_t i = first + uint32_t(BLOCK) * k;
         if (i < total_vecs) {
             pair[k] = log2_dvec >= 0 ? (i >> log2_dvec) : by_dvec.div(i);
             av[k] = load_vec<NTL>(v_a + i);
@@ -63,7 +63,7 @@ __global__ __launch_bounds__(256) void merge_attn_states_lse_vec_kernel(u32x4* v
     }
 #pragma unroll
     for (int k = 0; k < UNROLL; ++k) {
-        const uint32_t i = first + 256u * k;
+        const uint32_t i = first + uint32_t(BLOCK) * k;
         if (i < total_vecs) {
             const MergeWeights w = merge_weights(sa[k], sb[k]);
             float a[8], b[8], o[8];
@@ -105,6 +105,118 @@ __global__ __launch_bounds__(256) void merge_attn_states_lse_generic_kernel(uint
             v_out[p * D + k] = Storage<DT>::narrow(w.a * a + w.b * b);
         }
         if (threadIdx.x == 0) lse_out[p] = w.lse;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// K-way merge: V_out = sum_k e^(S_k) V_k / sum_k e^(S_k), S_out = log sum_k e^(S_k).
+// kway_stats is the plain three-pass evaluation used by the element-wise path.
+
+struct KwayStats {
+    float m0;   // maximum score (0 when every partition is empty)
+    float inv;  // 1 / sum_k e^(S_k - m0)   (0 when every partition is empty)
+    float lse;
+};
+
+__device__ __forceinline__ KwayStats kway_stats(const float* lse_parts, uint32_t K, size_t pairs, size_t pair)
+{
+    const float ninf = -__builtin_inff();
+    float m = ninf;
+    for (uint32_t k = 0; k < K; ++k) m = fmaxf(m, lse_parts[k * pairs + pair]);
+    const bool empty = (m == ninf);
+    KwayStats st;
+    st.m0 = empty ? 0.0f : m;
+    float den = 0.0f;
+    for (uint32_t k = 0; k < K; ++k) den += fast_exp(lse_parts[k * pairs + pair] - st.m0);
+    st.inv = empty ? 0.0f : fast_rcp(den);
+    st.lse = empty ? ninf : m + fast_log(den);
+    return st;
+}
+
+// Fast path: one lane per output vector; part k of vector i lives at v_parts[k * total_vecs + i].
+// Streaming form: the parts are taken in groups of G.  All G scores and G vectors of a group are
+// requested together (one wait per group; loads return in order, so a score load issued after a
+// vector load cannot be consumed earlier anyway), then folded into a running maximum m, a running
+// denominator and running accumulators that are rescaled by e^(m_old - m_new) whenever the maximum
+// grows.  Equal to the definition up to binary32 rounding; a three-pass form (maximum, denominator,
+// weights) measured 10-14 % slower because every pass waits on memory again.
+template <int DT, int G, bool NTL, bool NTS>
+__global__ __launch_bounds__(256) void merge_attn_states_lse_kway_vec_kernel(u32x4* __restrict__ v_out,
+                                                                             float* __restrict__ lse_out,
+                                                                             const u32x4* __restrict__ v_parts,
+                                                                             const float* __restrict__ lse_parts,
+                                                                             uint32_t K, uint32_t total_vecs, uint32_t pairs,
+                                                                             uint32_t dvec, int log2_dvec, FastDiv by_dvec,
+                                                                             int log2_chunk)
+{
+    const uint32_t i = xcd_chunked(blockIdx.x, log2_chunk) * 256u + threadIdx.x;
+    if (i >= total_vecs) return;
+    const uint32_t pair = log2_dvec >= 0 ? (i >> log2_dvec) : by_dvec.div(i);
+    const float ninf = -__builtin_inff();
+    float m = ninf, den = 0.0f;
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    for (uint32_t k0 = 0; k0 < K; k0 += G) {
+        u32x4 pv[G];
+        float s[G];
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            const uint32_t k = k0 + g;
+            if (k < K) {
+                pv[g] = load_vec<NTL>(v_parts + ((size_t)k * total_vecs + i));
+                s[g] = lse_parts[(size_t)k * pairs + pair];
+            } else {
+                pv[g] = u32x4{0u, 0u, 0u, 0u};
+                s[g] = ninf;
+            }
+        }
+        float gm = s[0];
+#pragma unroll
+        for (int g = 1; g < G; ++g) gm = fmaxf(gm, s[g]);
+        const float mn = fmaxf(m, gm);
+        if (mn != ninf) {  // otherwise every partition so far is empty: nothing to add
+            const float rescale = fast_exp(m - mn);  // first live group: m = -inf, e^-inf = 0, sums are 0 anyway
+            den *= rescale;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[e] *= rescale;
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                const float w = fast_exp(s[g] - mn);
+                den += w;
+                float v[8];
+                unpack8<DT>(pv[g], v);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc[e] += w * v[e];
+            }
+            m = mn;
+        }
+    }
+    const bool empty = (m == ninf);
+    const float inv = empty ? 0.0f : fast_rcp(den);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] *= inv;
+    store_vec<NTS>(v_out + i, pack8<DT>(acc));
+    if (i == pair * dvec) lse_out[pair] = empty ? ninf : m + fast_log(den);
+}
+
+// Element-wise path for any head_dim and 2-byte aligned pointers: one block per (token, head) pair.
+template <int DT>
+__global__ __launch_bounds__(256) void merge_attn_states_lse_kway_generic_kernel(uint16_t* __restrict__ v_out,
+                                                                                 float* __restrict__ lse_out,
+                                                                                 const uint16_t* __restrict__ v_parts,
+                                                                                 const float* __restrict__ lse_parts,
+                                                                                 uint32_t K, int64_t pairs, int64_t D)
+{
+    for (int64_t p = blockIdx.x; p < pairs; p += gridDim.x) {
+        const KwayStats st = kway_stats(lse_parts, K, (size_t)pairs, (size_t)p);
+        for (int64_t j = threadIdx.x; j < D; j += blockDim.x) {
+            float acc = 0.0f;
+            for (uint32_t k = 0; k < K; ++k) {
+                const float w = fast_exp(lse_parts[(size_t)k * pairs + p] - st.m0) * st.inv;
+                acc += w * Storage<DT>::widen(v_parts[((size_t)k * pairs + p) * D + j]);
+            }
+            v_out[p * D + j] = Storage<DT>::narrow(acc);
+        }
+        if (threadIdx.x == 0) lse_out[p] = st.lse;
     }
 }
 

@@ -22,16 +22,16 @@ __device__ __forceinline__ float silu_fast(float x)
 __device__ __forceinline__ float silu_libm(float x) { return x / (1.0f + expf(-x)); }
 
 // Fast path: d % 8 == 0 and 16-byte aligned pointers.  Work is the flat list of output vectors
-// (dv = d/8 per row); a block owns 256*UNROLL consecutive ones.  The row of the block's first vector
+// (dv = d/8 per row); a block owns BLOCK*UNROLL consecutive ones.  The row of the block's first vector
 // comes from one scalar fast division; lanes then step to the next row when they run past the end
 // of a row (at most a few steps because the host only takes this path when dv >= 32).
 // For output vector (t, j):  x = in[t*2dv + j], g = in[t*2dv + dv + j], out index = t*dv + j.
-template <int DT, int UNROLL, bool NTL, bool NTS, bool LIBM = false>
-__global__ __launch_bounds__(256) void silu_and_mul_vec_kernel(u32x4* __restrict__ out, const u32x4* __restrict__ in,
+template <int DT, int UNROLL, bool NTL, bool NTS, bool LIBM = false, int BLOCK = 256>
+__global__ __launch_bounds__(BLOCK) void silu_and_mul_vec_kernel(u32x4* __restrict__ out, const u32x4* __restrict__ in,
                                                                uint32_t total_vecs, uint32_t dv, FastDiv by_dv,
                                                                int log2_chunk)
 {
-    constexpr uint32_t kSpan = 256u * UNROLL;
+    constexpr uint32_t kSpan = uint32_t(BLOCK) * UNROLL;
     const uint32_t first = xcd_chunked(blockIdx.x, log2_chunk) * kSpan;
     if (first >= total_vecs) return;  // grid padding
     const uint32_t t0 = by_dv.div(first);
@@ -41,7 +41,7 @@ __global__ __launch_bounds__(256) void silu_and_mul_vec_kernel(u32x4* __restrict
     uint32_t oidx[UNROLL];
 #pragma unroll
     for (int k = 0; k < UNROLL; ++k) {
-        const uint32_t off = threadIdx.x + 256u * k;
+        const uint32_t off = threadIdx.x + uint32_t(BLOCK) * k;
         oidx[k] = first + off;
         uint32_t t = t0, j = j0 + off;
         while (j >= dv) {

@@ -35,7 +35,8 @@ def test_every_declared_symbol_is_exported(A):
     declared = _declared_functions()
     assert {"astra_fused_add_rmsnorm", "astra_silu_and_mul", "astra_merge_attn_states_lse", "astra_status_string",
             "astra_stream_copy", "astra_plan_fused_add_rmsnorm", "astra_plan_silu_and_mul",
-            "astra_plan_merge_attn_states_lse", "astra_plan_xcd_chunked"} <= set(declared)
+            "astra_plan_merge_attn_states_lse", "astra_plan_xcd_chunked", "astra_merge_attn_states_lse_kway",
+            "astra_ablation_fused_add_rmsnorm", "astra_ablation_silu_and_mul", "astra_ablation_merge_attn_states_lse"} <= set(declared)
     for name in declared:
         assert hasattr(L, name), f"{name} declared in include/ but not exported"
 
@@ -180,6 +181,17 @@ def test_ablation_variant_validation(A):
     vo, lo, va, la, vb, lb = 0x10000, 0x20000, 0x30000, 0x40000, 0x50000, 0x60000
     assert h(vo, lo, va, la, vb, lb, 1, 2, 8, 1, 2) == 8 and h(vo, lo, va, la, vb, lb, 1, 2, 8, 1, 4) == 8
     assert h(vo, lo, va, la, vb, lb, 1, 2, 4, 1, 3) == 8 and h(vo, lo, va, la, vb, lb, 0, 2, 8, 1, 3) == 0
+
+
+def test_kway_validation_without_gpu(A):
+    g = A.astra_merge_attn_states_lse_kway
+    vo, lo, vp, lp = 0x10000, 0x20000, 0x100000, 0x200000
+    assert g(0, lo, vp, lp, 2, 1, 2, 8, 1) == 1 and g(vo, lo, vp, 0, 2, 1, 2, 8, 1) == 1
+    assert g(vo, lo, vp, lp, 0, 1, 2, 8, 1) == 2 and g(vo, lo, vp, lp, 65537, 1, 2, 8, 1) == 2 and g(vo, lo, vp, lp, 2, -1, 2, 8, 1) == 2
+    assert g(vo, lo, vp, lp, 2, 1, 2, 8, 5) == 3
+    assert g(vo + 1, lo, vp, lp, 2, 1, 2, 8, 1) == 5 and g(vo, lo + 2, vp, lp, 2, 1, 2, 8, 1) == 5
+    assert g(vp + 32, lo, vp, lp, 3, 1, 2, 8, 1) == 6                  # output inside the second part
+    assert g(vo, lo, vp, lp, 2, 0, 2, 8, 1) == 0
 
 
 def test_binding_refuses_cpu_tensors(A):
