@@ -30,7 +30,12 @@ MUTANTS = [
     ("merge_weights_swapped", "*a = wa / den;\n        *b = wb / den;", "*a = wb / den;\n        *b = wa / den;", "test_oracle_merge.py"),
     ("merge_lse_drops_max", "*s_out = m + logf(den);", "*s_out = logf(den);", "test_oracle_merge.py"),
     ("merge_unnormalised", "*a = wa / den;", "*a = wa;", "test_oracle_merge.py"),
-    ("merge_no_empty_guard", "if (m == -INFINITY) {", "if (0) {", "test_oracle_merge.py"),
+    ("merge_no_empty_guard", "if (m == -INFINITY) {\n        *a = 0.0f;", "if (0) {\n        *a = 0.0f;", "test_oracle_merge.py"),
+    ("kway_no_empty_guard", "if (m == -INFINITY) {\n            lse_out[p] = -INFINITY;", "if (0) {\n            lse_out[p] = -INFINITY;", "test_oracle_merge_kway.py"),
+    ("kway_sum_not_max", "for (int64_t k = 0; k < K; ++k) m = fmaxf(m, lse_parts[k * P + p]);", "for (int64_t k = 0; k < K; ++k) m = fmaxf(m, 100.0f + lse_parts[k * P + p]);", "test_oracle_merge_kway.py"),
+    ("kway_unnormalised", "float a = expf(lse_parts[k * P + p] - m) / den;", "float a = expf(lse_parts[k * P + p] - m);", "test_oracle_merge_kway.py"),
+    ("kway_part_stride_wrong", "acc += a * widen(v_parts[(k * P + p) * D + j], dtype);", "acc += a * widen(v_parts[(p * K + k) * D + j], dtype);", "test_oracle_merge_kway.py"),
+    ("kway_lse_drops_max", "lse_out[p] = m + logf(den);", "lse_out[p] = logf(den);", "test_oracle_merge_kway.py"),
     ("merge_log_of_sum_of_scores", "float wb = expf(sb - m);", "float wb = expf(sb + m);", "test_oracle_merge.py"),
     ("bf16_truncates", "return (uint16_t)(sign | shr_rne(mag, 16));", "return (uint16_t)(sign | (mag >> 16));", "test_oracle_convert.py"),
     ("f16_flushes_subnormals", "if (e < 101u) return (uint16_t)sign;", "if (e < 113u) return (uint16_t)sign;", "test_oracle_convert.py"),
