@@ -18,6 +18,7 @@ taken inside the timed region on the launch stream; `kernels` carries the same f
     python bench.py --ceiling        # streaming-copy ceiling of the machine (same access pattern)
     python bench.py --ablation       # paper Table-4 shapes: tuned vs one-optimisation-removed variants
     python bench.py --kway           # K-way merge vs a chain of two-way merges
+    python bench.py --decode         # decode-sized launches replayed from a HIP graph
 """
 from __future__ import annotations
 
@@ -438,6 +439,54 @@ def run_kway(args):
         torch.cuda.empty_cache()
 
 
+def run_decode(args):
+    """Decode-sized launches (T <= 64) replayed from a HIP graph: the host's per-call cost (about 4 us through
+    ctypes) is out of the picture and what remains is dispatch + kernel.  200 launches per graph, rotating
+    over 8 buffer sets; microseconds per launch averaged over 20 replays."""
+    import torch
+
+    import paper_2509_07506_amd as astra
+    import workloads
+
+    astra.load_library()
+    torch.cuda.set_device(0)
+    names = ["c0_rmsnorm_T16_H4096_bf16"] + [f"c3_rmsnorm_T{T}_H8192_bf16" for T in (1, 8, 64)] + \
+            ["c4_silu_T1_d11008_f16", "c4_silu_T3_d11008_f16", "c4_merge_T1_NH40_D256_f16", "c4_merge_T3_NH40_D256_f16",
+             "p4_silu_T64_d8192_f16", "p4_rmsnorm_T256_H4096_f16", "p4_merge_T512_NH40_D128_f16"]
+    per_graph, nsets = 200, 8
+    for n in names:
+        c = workloads.case(n)
+        L = Launcher(astra, c, c.generate(), nsets)
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            for k in range(nsets):
+                L.launch(side.cuda_stream, k)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            sh = torch.cuda.current_stream().cuda_stream
+            for k in range(per_graph):
+                L.launch(sh, k)
+        for _ in range(3):
+            g.replay()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = 20
+        e0.record()
+        for _ in range(reps):
+            g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / (reps * per_graph)
+        print(json.dumps({"case": n, "mode": "hip graph replay", "launches_per_graph": per_graph, "us_per_launch": round(us, 3),
+                          "bytes": c.algorithmic_bytes(), "GBs": round(c.algorithmic_bytes() / us / 1e3, 1), "launch": L.plan}),
+              flush=True)
+        del g, L
+        torch.cuda.empty_cache()
+
+
 def run_ceiling(args):
     """Streaming ceiling of this machine with the operators' access pattern: astra_stream_copy over
     512 MiB, alternating between two source/destination pairs (2 GiB footprint, so always cold)."""
@@ -485,6 +534,7 @@ def main():
     ap.add_argument("--only", default=None, help="with --sweep: substring filter on the case name")
     ap.add_argument("--ceiling", action="store_true", help="measure the streaming-copy ceiling of the machine")
     ap.add_argument("--kway", action="store_true", help="K-way merge vs a chain of two-way merges")
+    ap.add_argument("--decode", action="store_true", help="decode-sized launches replayed from a HIP graph")
     ap.add_argument("--ablation", action="store_true",
                     help="paper Table-4 shapes and the bandwidth workloads: tuned kernel vs each one-optimisation-removed variant")
     args = ap.parse_args()
@@ -492,7 +542,9 @@ def main():
         print("bench.py: this path runs on ONE GPU (row-independent kernels, no collectives); "
               "--gpus N with N > 1 is not supported", file=sys.stderr)
         sys.exit(2)
-    if args.kway:
+    if args.decode:
+        run_decode(args)
+    elif args.kway:
         run_kway(args)
     elif args.ablation:
         run_ablation(args)

@@ -409,3 +409,137 @@ def test_stream_copy(A):
     assert A.astra_stream_copy(dst.data_ptr(), src.data_ptr(), n, None) == 0
     torch.cuda.synchronize()
     assert torch.equal(dst[: n // 4], src[: n // 4]) and bool((dst[n // 4:] == 0).all())
+
+
+# ---------------------------------------------------------------------------------------------------
+# maximum sizes: more than 2^31 elements per tensor (byte offsets beyond 32 bits), and more rows than the
+# row kernel's grid limit (row loop).  A small seeded block is tiled on the device; the first tile is
+# checked against the oracle and every other tile must be bit-identical to the first.
+
+def _tile_rows(block_dev, reps):
+    return block_dev.repeat((reps,) + (1,) * (block_dev.dim() - 1))
+
+
+def _all_tiles_equal(t, rows_per_tile):
+    ref = t[:rows_per_tile]
+    n = t.shape[0] // rows_per_tile
+    v = t[: n * rows_per_tile].view(torch.int16).view((n, rows_per_tile) + tuple(t.shape[1:]))
+    same = bool((v == ref.view(torch.int16).unsqueeze(0)).all())
+    tail = t[n * rows_per_tile:]
+    return same and bool((tail.view(torch.int16) == ref[: tail.shape[0]].view(torch.int16)).all())
+
+
+def test_rmsnorm_beyond_2_31_elements(A):
+    dt, B, H = "bf16", 64, 16384
+    T = (1 << 17) + 3                                     # T*H = 2^31 + 49152 elements, 4 GiB per tensor
+    print(f"[parity] rmsnorm huge T={T} H={H}", flush=True)
+    x, r, w = workloads.rmsnorm_inputs(B, H, dt, np.random.default_rng(50), r_std=2.0)
+    reps = -(-T // B)
+    xd = _tile_rows(to_dev(x, dt), reps)[:T].contiguous()
+    rd = _tile_rows(to_dev(r, dt), reps)[:T].contiguous()
+    wd = to_dev(w, dt)
+    A.fused_add_rmsnorm(xd, rd, wd, 1e-5)
+    torch.cuda.synchronize()
+    y_ref, res_ref = O.fused_add_rmsnorm(x, r, w, 1e-5, dt)
+    assert_bits_equal(to_bits(rd[:B]), res_ref, "residual, first tile")
+    assert_storage_close(to_bits(xd[:B]), y_ref, dt, "y, first tile")
+    assert _all_tiles_equal(xd, B) and _all_tiles_equal(rd, B), "rows beyond the first tile differ"
+
+
+def test_rmsnorm_more_rows_than_the_grid_limit(A):
+    dt, B, H = "f16", 256, 8
+    T = (1 << 21) + 259                                   # the row kernel launches at most 2^21 workgroups
+    st, info = A.astra_plan_fused_add_rmsnorm(T, H, True)
+    assert info.as_dict()["grid"] == 1 << 21
+    x, r, w = workloads.rmsnorm_inputs(B, H, dt, np.random.default_rng(51))
+    reps = -(-T // B)
+    xd = _tile_rows(to_dev(x, dt), reps)[:T].contiguous()
+    rd = _tile_rows(to_dev(r, dt), reps)[:T].contiguous()
+    A.fused_add_rmsnorm(xd, rd, to_dev(w, dt), 1e-6)
+    torch.cuda.synchronize()
+    y_ref, res_ref = O.fused_add_rmsnorm(x, r, w, 1e-6, dt)
+    assert_bits_equal(to_bits(rd[:B]), res_ref, "residual, first tile")
+    assert_storage_close(to_bits(xd[:B]), y_ref, dt, "y, first tile")
+    assert _all_tiles_equal(xd, B) and _all_tiles_equal(rd, B)
+
+
+def test_silu_beyond_2_31_elements(A):
+    dt, B, d = "f16", 32, 32768
+    T = (1 << 15) + 5                                     # input T*2d = 2^31 + 327680 elements
+    print(f"[parity] silu huge T={T} d={d}", flush=True)
+    a = workloads.silu_inputs(B, d, dt, np.random.default_rng(52))
+    ad = _tile_rows(to_dev(a, dt), -(-T // B))[:T].contiguous()
+    out = torch.empty((T, d), dtype=TORCH_DT[dt], device="cuda")
+    A.silu_and_mul(out, ad)
+    torch.cuda.synchronize()
+    assert_storage_close(to_bits(out[:B]), O.silu_and_mul(a, dt), dt, "out, first tile")
+    assert _all_tiles_equal(out, B)
+
+
+def test_merge_beyond_2_31_elements(A):
+    dt, B, NH, D = "bf16", 32, 32, 256
+    T = (1 << 18) + 7                                     # T*NH*D = 2^31 + 57344 elements per v tensor
+    print(f"[parity] merge huge T={T} NH={NH} D={D}", flush=True)
+    va, la, vb, lb = workloads.merge_inputs(B, NH, D, dt, np.random.default_rng(53), empty_p=0.05)
+    reps = -(-T // B)
+    vad = _tile_rows(to_dev(va, dt), reps)[:T].contiguous()
+    vbd = _tile_rows(to_dev(vb, dt), reps)[:T].contiguous()
+    lad = _tile_rows(torch.from_numpy(la).cuda(), reps)[:T].contiguous()
+    lbd = _tile_rows(torch.from_numpy(lb).cuda(), reps)[:T].contiguous()
+    vo, lo = torch.empty_like(vad), torch.empty_like(lad)
+    A.merge_attn_states_lse(vo, lo, vad, lad, vbd, lbd)
+    torch.cuda.synchronize()
+    vo_ref, lo_ref = O.merge_attn_states_lse(va, la, vb, lb, dt)
+    assert_storage_close(to_bits(vo[:B]), vo_ref, dt, "v_out, first tile")
+    assert_lse_close(lo[:B].cpu().numpy(), lo_ref, "lse_out, first tile")
+    assert _all_tiles_equal(vo, B)
+    n = T // B
+    assert bool((lo[: n * B].view(torch.int32).view(n, B, NH) == lo[:B].view(torch.int32).unsqueeze(0)).all())
+
+
+def test_graph_capture_and_replay(A):
+    """The entry points only enqueue kernels on the caller's stream (no allocation, no synchronisation,
+    no memset), so a HIP graph can capture them.  Replays are checked against the eager result several
+    times with eager work and synchronisations in between."""
+    dt = "bf16"
+    x, r, w = workloads.rmsnorm_inputs(16, 4096, dt, np.random.default_rng(60))
+    a = workloads.silu_inputs(16, 5120, dt, np.random.default_rng(61))
+    va, la, vb, lb = workloads.merge_inputs(16, 32, 128, dt, np.random.default_rng(62))
+    x0, r0, wd = to_dev(x, dt), to_dev(r, dt), to_dev(w, dt)
+    xd, rd = x0.clone(), r0.clone()
+    ad = to_dev(a, dt)
+    so = torch.empty((16, 5120), dtype=TORCH_DT[dt], device="cuda")
+    vad, vbd = to_dev(va, dt), to_dev(vb, dt)
+    lad, lbd = torch.from_numpy(la).cuda(), torch.from_numpy(lb).cuda()
+    vo, lo = torch.empty_like(vad), torch.empty_like(lad)
+    y_ref, res_ref = O.fused_add_rmsnorm(x, r, w, 1e-6, dt)
+    s_ref = O.silu_and_mul(a, dt)
+    vo_ref, lo_ref = O.merge_attn_states_lse(va, la, vb, lb, dt)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                      # warm-up on the capture stream before capturing
+        A.fused_add_rmsnorm(xd, rd, wd, 1e-6)
+        A.silu_and_mul(so, ad)
+        A.merge_attn_states_lse(vo, lo, vad, lad, vbd, lbd)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        A.fused_add_rmsnorm(xd, rd, wd, 1e-6)
+        A.silu_and_mul(so, ad)
+        A.merge_attn_states_lse(vo, lo, vad, lad, vbd, lbd)
+    for rep in range(4):
+        xd.copy_(x0)                                   # eager work between replays: restore the in-place operands
+        rd.copy_(r0)
+        so.fill_(7.0)
+        vo.fill_(7.0)
+        lo.fill_(7.0)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert_bits_equal(to_bits(rd), res_ref, f"replay {rep}: residual")
+        assert_storage_close(to_bits(xd), y_ref, dt, f"replay {rep}: y")
+        assert_storage_close(to_bits(so), s_ref, dt, f"replay {rep}: silu")
+        assert_storage_close(to_bits(vo), vo_ref, dt, f"replay {rep}: v_out")
+        assert_lse_close(lo.cpu().numpy(), lo_ref, f"replay {rep}: lse_out")
