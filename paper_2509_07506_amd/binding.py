@@ -72,6 +72,8 @@ def load_library() -> ctypes.CDLL:
     L.astra_silu_and_mul.argtypes = [vp, vp, i64, i64, i32, vp]
     L.astra_merge_attn_states_lse.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, i32, vp]
     L.astra_stream_copy.argtypes = [vp, vp, i64, vp]
+    L.astra_fused_add_rmsnorm_strided.argtypes = [vp, i64, vp, i64, vp, i64, vp, i64, vp, i64, i64, i32, f32, vp]
+    L.astra_fused_add_rmsnorm_strided.restype = i32
     L.astra_merge_attn_states_lse_kway.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, i32, vp]
     L.astra_merge_attn_states_lse_kway.restype = i32
     L.astra_ablation_fused_add_rmsnorm.argtypes = [vp, vp, vp, i64, i64, i32, f32, i32, vp]
@@ -116,6 +118,12 @@ def astra_merge_attn_states_lse(v_out, lse_out, v_a, lse_a, v_b, lse_b, T, num_h
 
 def astra_stream_copy(dst, src, nbytes, stream=None) -> int:
     return load_library().astra_stream_copy(dst, src, nbytes, stream)
+
+
+def astra_fused_add_rmsnorm_strided(y_out, y_stride, r_out, r_out_stride, x, x_stride, r, r_stride, weight, T, H, dtype, eps,
+                                    stream=None) -> int:
+    return load_library().astra_fused_add_rmsnorm_strided(y_out, y_stride, r_out, r_out_stride, x, x_stride, r, r_stride,
+                                                          weight, T, H, dtype, eps, stream)
 
 
 def astra_merge_attn_states_lse_kway(v_out, lse_out, v_parts, lse_parts, K, T, num_heads, head_dim, dtype, stream=None) -> int:
@@ -250,6 +258,27 @@ def merge_attn_states_lse_kway(v_out, lse_out, v_parts, lse_parts, stream=None) 
                                           T, NH, D, _dtype_code(v_parts), _stream(stream))
     if st:
         raise AstraError(st, "astra_merge_attn_states_lse_kway")
+
+
+def fused_add_rmsnorm_strided(y_out, r_out, x, r, weight, eps: float, stream=None) -> None:
+    """y_out <- rmsnorm(x + r) * weight, r_out <- x + r, for 2-D tensors whose rows are dense but may be strided views."""
+    for t in (y_out, r_out, x, r, weight):
+        if not t.is_cuda:
+            raise ValueError("astra operators run on GPU tensors only (there is no CPU path)")
+    T, H = x.shape
+    for t in (y_out, r_out, x, r):
+        if t.shape != (T, H) or t.dtype != x.dtype or (H > 1 and t.stride(1) != 1):
+            raise ValueError("fused_add_rmsnorm_strided: [T,H] tensors of one dtype with unit column stride expected")
+    if weight.shape != (H,) or weight.dtype != x.dtype or not weight.is_contiguous():
+        raise ValueError("fused_add_rmsnorm_strided: weight [H], dense")
+    if T == 0:
+        return
+    rs = lambda t: t.stride(0) if T > 1 else H
+    st = astra_fused_add_rmsnorm_strided(y_out.data_ptr(), rs(y_out), r_out.data_ptr(), rs(r_out), x.data_ptr(), rs(x),
+                                         r.data_ptr(), rs(r), weight.data_ptr(), T, H, _dtype_code(x), float(eps),
+                                         _stream(stream))
+    if st:
+        raise AstraError(st, "astra_fused_add_rmsnorm_strided")
 
 
 def stream_copy(dst, src, stream=None) -> None:

@@ -5,6 +5,7 @@
 #include "astra_ablation.h"
 #include "astra_kway.h"
 #include "astra_plan.h"
+#include "astra_strided.h"
 
 #include <hip/hip_runtime.h>
 
@@ -477,6 +478,68 @@ astra_status_t astra_merge_attn_states_lse_kway(void* v_out, float* lse_out, con
     if (dtype == ASTRA_BF16) { ASTRA_LAUNCH_KWAY(kBF16); }
     else { ASTRA_LAUNCH_KWAY(kF16); }
 #undef ASTRA_LAUNCH_KWAY
+    return after_launch();
+}
+
+astra_status_t astra_fused_add_rmsnorm_strided(void* y_out, int64_t y_stride, void* r_out, int64_t r_out_stride,
+                                               const void* x, int64_t x_stride, const void* r, int64_t r_stride,
+                                               const void* weight, int64_t T, int64_t H, astra_dtype_t dtype, float eps,
+                                               hipStream_t stream)
+{
+    if (!y_out || !r_out || !x || !r || !weight) return ASTRA_ERR_NULL;
+    const int64_t strides[4] = {y_stride, r_out_stride, x_stride, r_stride};
+    const void* const bases[4] = {y_out, r_out, x, r};
+    bool fast = aligned(weight, 16);
+    for (int i = 0; i < 4; ++i) fast = fast && aligned(bases[i], 16) && strides[i] % kVecElems == 0;
+    astra_launch_info_t li;
+    astra_status_t st = plan_rmsnorm(T, H, fast, &li);
+    if (st != ASTRA_OK) return st;
+    int64_t span[4];  // bounding extent of each view in bytes
+    for (int i = 0; i < 4; ++i) {
+        int64_t rows_bytes;
+        if (strides[i] < H || mul_overflows(T > 0 ? T - 1 : 0, strides[i], &rows_bytes) ||
+            rows_bytes > std::numeric_limits<int64_t>::max() / 4)
+            return ASTRA_ERR_SHAPE;
+        span[i] = T > 0 ? (rows_bytes + H) * 2 : 0;
+    }
+    if (!valid_dtype((int)dtype)) return ASTRA_ERR_DTYPE;
+    if (!(eps >= 0.0f)) return ASTRA_ERR_EPS;
+    for (int i = 0; i < 4; ++i)
+        if (!aligned(bases[i], 2)) return ASTRA_ERR_ALIGN;
+    if (!aligned(weight, 2)) return ASTRA_ERR_ALIGN;
+    const bool y_in_place = (y_out == x && y_stride == x_stride), r_in_place = (r_out == r && r_out_stride == r_stride);
+    if ((!y_in_place && overlaps(y_out, span[0], x, span[2])) || (!r_in_place && overlaps(r_out, span[1], r, span[3])) ||
+        overlaps(y_out, span[0], r, span[3]) || overlaps(r_out, span[1], x, span[2]) ||
+        overlaps(y_out, span[0], r_out, span[1]) || overlaps(y_out, span[0], weight, H * 2) ||
+        overlaps(r_out, span[1], weight, H * 2))
+        return ASTRA_ERR_ALIAS;
+    if (T == 0) return ASTRA_OK;
+    const float inv_h = 1.0f / (float)H;
+#define ASTRA_LAUNCH_STRIDED(DT)                                                                                         \
+    if (li.path == ASTRA_PATH_GENERIC) {                                                                                 \
+        const RowViews sv{y_stride, r_out_stride, x_stride, r_stride};                                                   \
+        fused_add_rmsnorm_strided_generic_kernel<DT><<<dim3((uint32_t)li.grid), dim3(256), 0, stream>>>(                 \
+            static_cast<uint16_t*>(y_out), static_cast<uint16_t*>(r_out), static_cast<const uint16_t*>(x),               \
+            static_cast<const uint16_t*>(r), static_cast<const uint16_t*>(weight), sv, T, H, inv_h, eps);                \
+    } else {                                                                                                             \
+        const RowViews sv{y_stride / kVecElems, r_out_stride / kVecElems, x_stride / kVecElems, r_stride / kVecElems};   \
+        u32x4* yo = static_cast<u32x4*>(y_out);                                                                          \
+        u32x4* ro = static_cast<u32x4*>(r_out);                                                                          \
+        const u32x4* xi = static_cast<const u32x4*>(x);                                                                  \
+        const u32x4* ri = static_cast<const u32x4*>(r);                                                                  \
+        const u32x4* wi = static_cast<const u32x4*>(weight);                                                             \
+        const uint32_t hv = (uint32_t)(H / kVecElems);                                                                   \
+        const dim3 g((uint32_t)li.grid), b(li.block);                                                                    \
+        if (li.vectors_per_lane == 1)                                                                                    \
+            fused_add_rmsnorm_strided_row_kernel<DT, 1, 1024, kNTLoad, kNTStore><<<g, b, 0, stream>>>(yo, ro, xi, ri, wi, sv, T, hv, inv_h, eps, li.log2_xcd_chunk); \
+        else if (li.vectors_per_lane == 2)                                                                               \
+            fused_add_rmsnorm_strided_row_kernel<DT, 2, 1024, kNTLoad, kNTStore><<<g, b, 0, stream>>>(yo, ro, xi, ri, wi, sv, T, hv, inv_h, eps, li.log2_xcd_chunk); \
+        else                                                                                                             \
+            fused_add_rmsnorm_strided_row_kernel<DT, 4, 1024, kNTLoad, kNTStore><<<g, b, 0, stream>>>(yo, ro, xi, ri, wi, sv, T, hv, inv_h, eps, li.log2_xcd_chunk); \
+    }
+    if (dtype == ASTRA_BF16) { ASTRA_LAUNCH_STRIDED(kBF16) }
+    else { ASTRA_LAUNCH_STRIDED(kF16) }
+#undef ASTRA_LAUNCH_STRIDED
     return after_launch();
 }
 

@@ -112,4 +112,103 @@ __global__ __launch_bounds__(256) void fused_add_rmsnorm_generic_kernel(uint16_t
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Row-strided, out-of-place form: separate input and output views, each with its own row stride (in
+// vectors for the fast kernel, in elements for the element-wise one).  Same structure as the kernels
+// above; y_out == x and r_out == r (same strides) is the in-place operator.
+
+struct RowViews {
+    int64_t y_stride, r_out_stride, x_stride, r_stride;
+};
+
+template <int DT, int VPT, int MAX_THREADS, bool NTL, bool NTS>
+__global__ __launch_bounds__(MAX_THREADS) void fused_add_rmsnorm_strided_row_kernel(u32x4* y_out, u32x4* r_out,
+                                                                                    const u32x4* x, const u32x4* r,
+                                                                                    const u32x4* __restrict__ weight,
+                                                                                    RowViews sv, int64_t T, uint32_t hv,
+                                                                                    float inv_h, float eps, int log2_chunk)
+{
+    __shared__ float partials[2][16];
+    const int nwaves = blockDim.x >> 6;
+    const int64_t first_row = xcd_chunked(blockIdx.x, log2_chunk);
+    if (first_row >= T) return;
+    int parity = 0;
+    u32x4 wv[VPT];
+#pragma unroll
+    for (int k = 0; k < VPT; ++k) {
+        const uint32_t v = threadIdx.x + k * blockDim.x;
+        if (v < hv) wv[k] = weight[v];
+    }
+    for (int64_t row = first_row; row < T; row += gridDim.x, parity ^= 1) {
+        const u32x4* xrow = x + row * sv.x_stride;
+        const u32x4* rrow = r + row * sv.r_stride;
+        u32x4 xv[VPT], rv[VPT];
+#pragma unroll
+        for (int k = 0; k < VPT; ++k) {
+            const uint32_t v = threadIdx.x + k * blockDim.x;
+            if (v < hv) {
+                xv[k] = load_vec<NTL>(xrow + v);
+                rv[k] = load_vec<NTL>(rrow + v);
+            }
+        }
+        float s[VPT][8];
+        float acc = 0.0f;
+#pragma unroll
+        for (int k = 0; k < VPT; ++k) {
+            const uint32_t v = threadIdx.x + k * blockDim.x;
+            if (v < hv) {
+                float xf[8], rf[8];
+                unpack8<DT>(xv[k], xf);
+                unpack8<DT>(rv[k], rf);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    s[k][e] = xf[e] + rf[e];
+                    acc += s[k][e] * s[k][e];
+                }
+                store_vec<NTS>(r_out + row * sv.r_out_stride + v, pack8<DT>(s[k]));
+            }
+        }
+        const float total = block_sum(acc, partials[parity], nwaves);
+        const float scale = fast_rsqrt(total * inv_h + eps);
+#pragma unroll
+        for (int k = 0; k < VPT; ++k) {
+            const uint32_t v = threadIdx.x + k * blockDim.x;
+            if (v < hv) {
+                float w[8], y[8];
+                unpack8<DT>(wv[k], w);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) y[e] = (s[k][e] * scale) * w[e];
+                store_vec<NTS>(y_out + row * sv.y_stride + v, pack8<DT>(y));
+            }
+        }
+    }
+}
+
+template <int DT>
+__global__ __launch_bounds__(256) void fused_add_rmsnorm_strided_generic_kernel(uint16_t* y_out, uint16_t* r_out,
+                                                                                const uint16_t* x, const uint16_t* r,
+                                                                                const uint16_t* __restrict__ weight,
+                                                                                RowViews sv, int64_t T, int64_t H, float inv_h,
+                                                                                float eps)
+{
+    __shared__ float partials[2][16];
+    int parity = 0;
+    for (int64_t row = blockIdx.x; row < T; row += gridDim.x, parity ^= 1) {
+        const uint16_t* xr = x + row * sv.x_stride;
+        const uint16_t* rr = r + row * sv.r_stride;
+        float acc = 0.0f;
+        for (int64_t j = threadIdx.x; j < H; j += blockDim.x) {
+            float s = Storage<DT>::widen(xr[j]) + Storage<DT>::widen(rr[j]);
+            acc += s * s;
+        }
+        const float total = block_sum(acc, partials[parity], blockDim.x >> 6);
+        const float scale = fast_rsqrt(total * inv_h + eps);
+        for (int64_t j = threadIdx.x; j < H; j += blockDim.x) {
+            float s = Storage<DT>::widen(xr[j]) + Storage<DT>::widen(rr[j]);
+            r_out[row * sv.r_out_stride + j] = Storage<DT>::narrow(s);
+            y_out[row * sv.y_stride + j] = Storage<DT>::narrow((s * scale) * Storage<DT>::widen(weight[j]));
+        }
+    }
+}
+
 }  // namespace astra

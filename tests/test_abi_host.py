@@ -36,6 +36,7 @@ def test_every_declared_symbol_is_exported(A):
     assert {"astra_fused_add_rmsnorm", "astra_silu_and_mul", "astra_merge_attn_states_lse", "astra_status_string",
             "astra_stream_copy", "astra_plan_fused_add_rmsnorm", "astra_plan_silu_and_mul",
             "astra_plan_merge_attn_states_lse", "astra_plan_xcd_chunked", "astra_merge_attn_states_lse_kway",
+            "astra_fused_add_rmsnorm_strided",
             "astra_ablation_fused_add_rmsnorm", "astra_ablation_silu_and_mul", "astra_ablation_merge_attn_states_lse"} <= set(declared)
     for name in declared:
         assert hasattr(L, name), f"{name} declared in include/ but not exported"
@@ -192,6 +193,17 @@ def test_kway_validation_without_gpu(A):
     assert g(vo + 1, lo, vp, lp, 2, 1, 2, 8, 1) == 5 and g(vo, lo + 2, vp, lp, 2, 1, 2, 8, 1) == 5
     assert g(vp + 32, lo, vp, lp, 3, 1, 2, 8, 1) == 6                  # output inside the second part
     assert g(vo, lo, vp, lp, 2, 0, 2, 8, 1) == 0
+
+
+def test_strided_validation_without_gpu(A):
+    f = A.astra_fused_add_rmsnorm_strided
+    y, ro, x, r, w = 0x100000, 0x200000, 0x300000, 0x400000, 0x500000
+    assert f(0, 16, ro, 16, x, 16, r, 16, w, 4, 8, 1, 1e-6) == 1 and f(y, 16, ro, 16, x, 16, r, 16, 0, 4, 8, 1, 1e-6) == 1
+    assert f(y, 7, ro, 16, x, 16, r, 16, w, 4, 8, 1, 1e-6) == 2 and f(y, 16, ro, 16, x, 16, r, 1 << 62, w, 4, 8, 1, 1e-6) == 2
+    assert f(y, 16, ro, 16, x, 16, r, 16, w, 4, 8, 3, 1e-6) == 3 and f(y, 16, ro, 16, x, 16, r, 16, w, 4, 8, 1, float("nan")) == 4
+    assert f(y, 16, ro + 1, 16, x, 16, r, 16, w, 4, 8, 1, 1e-6) == 5
+    assert f(x, 32, ro, 16, x, 16, r, 16, w, 4, 8, 1, 1e-6) == 6 and f(y, 16, r + 2, 16, x, 16, r, 16, w, 4, 8, 1, 1e-6) == 6
+    assert f(x, 16, r, 16, x, 16, r, 16, w, 0, 8, 1, 1e-6) == 0          # in place, nothing to do
 
 
 def test_binding_refuses_cpu_tensors(A):
