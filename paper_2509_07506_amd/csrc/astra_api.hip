@@ -273,6 +273,52 @@ void launch_merge(const astra_launch_info_t& li, void* v_out, float* lse_out, co
         (uint32_t)(pairs * dvec), dvec, log2_dvec, make_fastdiv(dvec), li.log2_xcd_chunk);
 }
 
+// every part of the K-way input starts 16-byte aligned when the base is and head_dim % 8 == 0, which are the
+// fast-path conditions already
+template <int DT>
+void launch_merge_kway(const astra_launch_info_t& li, void* v_out, float* lse_out, const void* v_parts,
+                       const float* lse_parts, int64_t K, int64_t pairs, int64_t D, hipStream_t stream)
+{
+    if (li.path == ASTRA_PATH_GENERIC) {
+        merge_attn_states_lse_kway_generic_kernel<DT><<<dim3((uint32_t)li.grid), dim3(256), 0, stream>>>(
+            static_cast<uint16_t*>(v_out), lse_out, static_cast<const uint16_t*>(v_parts), lse_parts, (uint32_t)K, pairs, D);
+        return;
+    }
+    const uint32_t dvec = (uint32_t)(D / kVecElems);
+    const int log2_dvec = (dvec & (dvec - 1)) == 0 ? __builtin_ctz(dvec) : -1;
+    merge_attn_states_lse_kway_vec_kernel<DT, kKwayGroup, kNTLoad, kNTStore><<<dim3((uint32_t)li.grid), dim3(256), 0, stream>>>(
+        static_cast<u32x4*>(v_out), lse_out, static_cast<const u32x4*>(v_parts), lse_parts, (uint32_t)K,
+        (uint32_t)(pairs * dvec), (uint32_t)pairs, dvec, log2_dvec, make_fastdiv(dvec), li.log2_xcd_chunk);
+}
+
+template <int DT, int VPT>
+void launch_rmsnorm_strided_row(const astra_launch_info_t& li, void* y_out, void* r_out, const void* x, const void* r,
+                                const void* weight, const RowViews& ev, int64_t T, int64_t H, float eps, hipStream_t stream)
+{
+    const RowViews vv{ev.y_stride / kVecElems, ev.r_out_stride / kVecElems, ev.x_stride / kVecElems, ev.r_stride / kVecElems};
+    fused_add_rmsnorm_strided_row_kernel<DT, VPT, 1024, kNTLoad, kNTStore><<<dim3((uint32_t)li.grid), dim3(li.block), 0, stream>>>(
+        static_cast<u32x4*>(y_out), static_cast<u32x4*>(r_out), static_cast<const u32x4*>(x), static_cast<const u32x4*>(r),
+        static_cast<const u32x4*>(weight), vv, T, (uint32_t)(H / kVecElems), 1.0f / (float)H, eps, li.log2_xcd_chunk);
+}
+
+// `ev` holds the row strides in elements
+template <int DT>
+void launch_rmsnorm_strided(const astra_launch_info_t& li, void* y_out, void* r_out, const void* x, const void* r,
+                            const void* weight, const RowViews& ev, int64_t T, int64_t H, float eps, hipStream_t stream)
+{
+    if (li.path == ASTRA_PATH_GENERIC) {
+        fused_add_rmsnorm_strided_generic_kernel<DT><<<dim3((uint32_t)li.grid), dim3(256), 0, stream>>>(
+            static_cast<uint16_t*>(y_out), static_cast<uint16_t*>(r_out), static_cast<const uint16_t*>(x),
+            static_cast<const uint16_t*>(r), static_cast<const uint16_t*>(weight), ev, T, H, 1.0f / (float)H, eps);
+        return;
+    }
+    switch (li.vectors_per_lane) {
+        case 1: launch_rmsnorm_strided_row<DT, 1>(li, y_out, r_out, x, r, weight, ev, T, H, eps, stream); break;
+        case 2: launch_rmsnorm_strided_row<DT, 2>(li, y_out, r_out, x, r, weight, ev, T, H, eps, stream); break;
+        default: launch_rmsnorm_strided_row<DT, 4>(li, y_out, r_out, x, r, weight, ev, T, H, eps, stream); break;
+    }
+}
+
 }  // namespace
 
 // =======================================================================================================
@@ -462,22 +508,8 @@ astra_status_t astra_merge_attn_states_lse_kway(void* v_out, float* lse_out, con
         overlaps(lse_out, sbytes, v_out, vbytes))
         return ASTRA_ERR_ALIAS;
     if (T == 0) return ASTRA_OK;
-    // every part starts 16-byte aligned when the base is and head_dim % 8 == 0 (fast-path conditions)
-    const bool generic = li.path == ASTRA_PATH_GENERIC;
-    const uint32_t dvec = (uint32_t)(head_dim / kVecElems);
-    const int log2_dvec = (!generic && (dvec & (dvec - 1)) == 0) ? __builtin_ctz(dvec) : -1;
-#define ASTRA_LAUNCH_KWAY(DT)                                                                                          \
-    if (generic)                                                                                                       \
-        merge_attn_states_lse_kway_generic_kernel<DT><<<dim3((uint32_t)li.grid), dim3(256), 0, stream>>>(              \
-            static_cast<uint16_t*>(v_out), lse_out, static_cast<const uint16_t*>(v_parts), lse_parts, (uint32_t)K, pairs, \
-            head_dim);                                                                                                 \
-    else                                                                                                               \
-        merge_attn_states_lse_kway_vec_kernel<DT, kKwayGroup, kNTLoad, kNTStore><<<dim3((uint32_t)li.grid), dim3(256), 0, stream>>>( \
-            static_cast<u32x4*>(v_out), lse_out, static_cast<const u32x4*>(v_parts), lse_parts, (uint32_t)K,           \
-            (uint32_t)(pairs * dvec), (uint32_t)pairs, dvec, log2_dvec, make_fastdiv(dvec ? dvec : 1), li.log2_xcd_chunk)
-    if (dtype == ASTRA_BF16) { ASTRA_LAUNCH_KWAY(kBF16); }
-    else { ASTRA_LAUNCH_KWAY(kF16); }
-#undef ASTRA_LAUNCH_KWAY
+    if (dtype == ASTRA_BF16) launch_merge_kway<kBF16>(li, v_out, lse_out, v_parts, lse_parts, K, pairs, head_dim, stream);
+    else launch_merge_kway<kF16>(li, v_out, lse_out, v_parts, lse_parts, K, pairs, head_dim, stream);
     return after_launch();
 }
 
@@ -514,32 +546,9 @@ astra_status_t astra_fused_add_rmsnorm_strided(void* y_out, int64_t y_stride, vo
         overlaps(r_out, span[1], weight, H * 2))
         return ASTRA_ERR_ALIAS;
     if (T == 0) return ASTRA_OK;
-    const float inv_h = 1.0f / (float)H;
-#define ASTRA_LAUNCH_STRIDED(DT)                                                                                         \
-    if (li.path == ASTRA_PATH_GENERIC) {                                                                                 \
-        const RowViews sv{y_stride, r_out_stride, x_stride, r_stride};                                                   \
-        fused_add_rmsnorm_strided_generic_kernel<DT><<<dim3((uint32_t)li.grid), dim3(256), 0, stream>>>(                 \
-            static_cast<uint16_t*>(y_out), static_cast<uint16_t*>(r_out), static_cast<const uint16_t*>(x),               \
-            static_cast<const uint16_t*>(r), static_cast<const uint16_t*>(weight), sv, T, H, inv_h, eps);                \
-    } else {                                                                                                             \
-        const RowViews sv{y_stride / kVecElems, r_out_stride / kVecElems, x_stride / kVecElems, r_stride / kVecElems};   \
-        u32x4* yo = static_cast<u32x4*>(y_out);                                                                          \
-        u32x4* ro = static_cast<u32x4*>(r_out);                                                                          \
-        const u32x4* xi = static_cast<const u32x4*>(x);                                                                  \
-        const u32x4* ri = static_cast<const u32x4*>(r);                                                                  \
-        const u32x4* wi = static_cast<const u32x4*>(weight);                                                             \
-        const uint32_t hv = (uint32_t)(H / kVecElems);                                                                   \
-        const dim3 g((uint32_t)li.grid), b(li.block);                                                                    \
-        if (li.vectors_per_lane == 1)                                                                                    \
-            fused_add_rmsnorm_strided_row_kernel<DT, 1, 1024, kNTLoad, kNTStore><<<g, b, 0, stream>>>(yo, ro, xi, ri, wi, sv, T, hv, inv_h, eps, li.log2_xcd_chunk); \
-        else if (li.vectors_per_lane == 2)                                                                               \
-            fused_add_rmsnorm_strided_row_kernel<DT, 2, 1024, kNTLoad, kNTStore><<<g, b, 0, stream>>>(yo, ro, xi, ri, wi, sv, T, hv, inv_h, eps, li.log2_xcd_chunk); \
-        else                                                                                                             \
-            fused_add_rmsnorm_strided_row_kernel<DT, 4, 1024, kNTLoad, kNTStore><<<g, b, 0, stream>>>(yo, ro, xi, ri, wi, sv, T, hv, inv_h, eps, li.log2_xcd_chunk); \
-    }
-    if (dtype == ASTRA_BF16) { ASTRA_LAUNCH_STRIDED(kBF16) }
-    else { ASTRA_LAUNCH_STRIDED(kF16) }
-#undef ASTRA_LAUNCH_STRIDED
+    const RowViews views{y_stride, r_out_stride, x_stride, r_stride};
+    if (dtype == ASTRA_BF16) launch_rmsnorm_strided<kBF16>(li, y_out, r_out, x, r, weight, views, T, H, eps, stream);
+    else launch_rmsnorm_strided<kF16>(li, y_out, r_out, x, r, weight, views, T, H, eps, stream);
     return after_launch();
 }
 
