@@ -119,7 +119,7 @@ def test_rmsnorm_plans(A):
         assert p["block"] * p["vectors_per_lane"] * 8 >= H           # the whole row is register resident
         assert p["block"] * p["vectors_per_lane"] * 8 < 1.25 * H + 512
         assert T <= p["grid"] < T + (8 << lc) and (lc == 0 or p["grid"] % (8 << lc) == 0)
-        assert lc == 0 or T >= (32 << lc)                              # at least four chunks per XCD
+        assert lc == 0 or (T >= (64 << lc) and T >= 1024)              # small grids keep the plain launch order
         if T >= 4096:
             assert 128 * 1024 <= (H * 2) << lc <= 512 * 1024           # about 256 KiB per XCD run
     assert plan(4, 4100)["path"] == "generic" and plan(4, 4096, al=False)["path"] == "generic"
