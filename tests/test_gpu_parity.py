@@ -543,3 +543,46 @@ def test_graph_capture_and_replay(A):
         assert_storage_close(to_bits(so), s_ref, dt, f"replay {rep}: silu")
         assert_storage_close(to_bits(vo), vo_ref, dt, f"replay {rep}: v_out")
         assert_lse_close(lo.cpu().numpy(), lo_ref, f"replay {rep}: lse_out")
+
+
+@pytest.mark.parametrize("dt", ["bf16", "f16"])
+def test_non_finite_inputs_propagate_like_the_oracle(A, dt):
+    """inf and NaN operands are outside every benchmark config; the kernels follow the formulas literally, like
+    the oracle: NaN where the oracle has NaN, the same infinity where it has one, tolerance elsewhere."""
+    inf, nan = np.float32(np.inf), np.float32(np.nan)
+    # rmsnorm: a NaN row, a row with +inf, a row with -inf and +inf, a clean row
+    T, H = 4, 4096
+    x, r, w = workloads.rmsnorm_inputs(T, H, dt, np.random.default_rng(80))
+    x[0, 5] = workloads.to_bits(np.array([nan]), dt)[0]
+    x[1, 7] = workloads.to_bits(np.array([inf]), dt)[0]
+    x[2, 9] = workloads.to_bits(np.array([inf]), dt)[0]
+    r[2, 9] = workloads.to_bits(np.array([-inf]), dt)[0]
+    y, res = run_rmsnorm(A, x, r, w, 1e-6, dt)
+    y_ref, res_ref = O.fused_add_rmsnorm(x, r, w, 1e-6, dt)
+    fin = ~np.isnan(reference_f64.widen(res_ref, dt))
+    assert np.array_equal(res[fin], res_ref[fin]) and np.all(np.isnan(reference_f64.widen(res, dt)[~fin]))
+    assert_storage_close(y, y_ref, dt, "rmsnorm with non-finite operands")
+    # silu: x in {+inf, -inf, NaN}, g in {1, 0, inf, NaN}
+    d = 256
+    xs = np.zeros(d, np.float32)
+    gs = np.ones(d, np.float32)
+    k = 0
+    for xv in (inf, -inf, nan, 2.0, -3.0, 0.0):
+        for gv in (1.0, 0.0, inf, -inf, nan):
+            xs[k], gs[k] = xv, gv
+            k += 1
+    a = workloads.to_bits(np.concatenate([xs, gs]).reshape(1, 2 * d), dt)
+    assert_storage_close(run_silu(A, a, dt), O.silu_and_mul(a, dt), dt, "silu with non-finite operands")
+    # merge: NaN / +inf scores and non-finite values in live and in empty partitions
+    va, la, vb, lb = workloads.merge_inputs(8, 4, 64, dt, np.random.default_rng(81), empty_p=0.0)
+    la[0, 0] = nan
+    la[1, 0] = inf
+    lb[2, 0] = -inf
+    vb[2, 0, 3] = workloads.to_bits(np.array([nan]), dt)[0]       # garbage in an empty partition: 0 * NaN = NaN
+    va[3, 0, 4] = workloads.to_bits(np.array([inf]), dt)[0]
+    la[4, 0] = inf
+    lb[4, 0] = inf
+    vo, lo = run_merge(A, va, la, vb, lb, dt)
+    vo_ref, lo_ref = O.merge_attn_states_lse(va, la, vb, lb, dt)
+    assert_storage_close(vo, vo_ref, dt, "merge with non-finite operands")
+    assert_lse_close(lo, lo_ref, "merge lse with non-finite scores")
