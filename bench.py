@@ -348,8 +348,9 @@ def run_ablation(args):
     """The paper's experiment re-staged on MI355X: for each of the twelve Table-4 shapes, and for the three
     bandwidth-regime benchmark workloads, the time of the tuned kernel and of each variant with one of the
     paper's optimisations removed, the per-shape speedup sigma = t(variant) / t(tuned) and its geometric
-    mean per kernel and variant (the paper's Section 3.1 metric).  20 warm-up + 100 timed launches per
-    point (Section 4), one event pair around the 100; cold = rotating buffer sets, hot = one set."""
+    mean per kernel and variant (the paper's Section 3.1 metric).  20 warm-up launches, then 100 launches
+    captured in a HIP graph and replayed 5 times (Section 4's 20 + 100 protocol, without the host's per-call
+    cost); cold = rotating buffer sets, hot = one set."""
     import math
 
     import torch
@@ -365,17 +366,33 @@ def run_ablation(args):
     speedups = {}
 
     def timed(L, hot):
-        reps, warm = 100, 20
-        for k in range(warm):
-            L.launch(sh, 0 if hot else k)
+        # 100 launches captured into one HIP graph and replayed: no host call cost in the figure, which would
+        # otherwise floor every sub-5 us kernel at the ~4 us of a ctypes call
+        per_graph = 100
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            for k in range(20):
+                L.launch(side.cuda_stream, 0 if hot else k)
+        torch.cuda.current_stream().wait_stream(side)
         torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            cs = torch.cuda.current_stream().cuda_stream
+            for k in range(per_graph):
+                L.launch(cs, 0 if hot else 20 + k)
+        g.replay()
+        torch.cuda.synchronize()
+        reps = 5
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record(stream)
-        for k in range(reps):
-            L.launch(sh, 0 if hot else warm + k)
-        e1.record(stream)
+        e0.record()
+        for _ in range(reps):
+            g.replay()
+        e1.record()
         torch.cuda.synchronize()
-        return e0.elapsed_time(e1) * 1e3 / reps
+        us = e0.elapsed_time(e1) * 1e3 / (reps * per_graph)
+        del g
+        return us
 
     for n in names:
         c = workloads.case(n)
