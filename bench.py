@@ -43,6 +43,8 @@ def _to_dev(bits, dt):
     import numpy as np
     import torch
 
+    if dt == "f32":
+        return torch.from_numpy(np.ascontiguousarray(bits, np.float32)).cuda()
     tdt = {"bf16": torch.bfloat16, "f16": torch.float16}[dt]
     return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).view(tdt).cuda()
 
@@ -58,8 +60,8 @@ class Launcher:
         self.nsets = nsets
         v = variant  # 0 = the tuned kernel; otherwise an ablation variant (include/astra_ablation.h)
         dt = case.dtype
-        tdt = {"bf16": torch.bfloat16, "f16": torch.float16}[dt]
-        code = astra.ASTRA_BF16 if dt == "bf16" else astra.ASTRA_F16
+        tdt = {"bf16": torch.bfloat16, "f16": torch.float16, "f32": torch.float32}[dt]
+        code = {"bf16": astra.ASTRA_BF16, "f16": astra.ASTRA_F16, "f32": astra.ASTRA_F32}[dt]
         s = case.shape
 
         def pool(t):
@@ -81,7 +83,7 @@ class Launcher:
             else:
                 self.fn = lambda k, st: astra.astra_ablation_fused_add_rmsnorm(x0 + k * xs, r0 + k * rs, w0, T, H, code,
                                                                                eps, v, st)
-            self.plan = astra.astra_plan_fused_add_rmsnorm(T, H, True)[1].as_dict()
+            self.plan = astra.astra_plan_fused_add_rmsnorm(T, H, True, dtype=code)[1].as_dict()
         elif case.kernel == "silu":
             a = _to_dev(data[0], dt)
             ap, as_ = pool(a)
@@ -93,7 +95,7 @@ class Launcher:
                 self.fn = lambda k, st: astra.astra_silu_and_mul(o0 + k * os_, a0 + k * as_, T, d, code, st)
             else:
                 self.fn = lambda k, st: astra.astra_ablation_silu_and_mul(o0 + k * os_, a0 + k * as_, T, d, code, v, st)
-            self.plan = astra.astra_plan_silu_and_mul(T, d, True)[1].as_dict()
+            self.plan = astra.astra_plan_silu_and_mul(T, d, True, dtype=code)[1].as_dict()
         else:
             va, la, vb, lb = data
             va, vb = _to_dev(va, dt), _to_dev(vb, dt)
@@ -111,7 +113,7 @@ class Launcher:
                 self.fn = lambda k, st: astra.astra_ablation_merge_attn_states_lse(
                     p[0] + k * vs, p[1] + k * ls, p[2] + k * vs, p[3] + k * ls, p[4] + k * vs, p[5] + k * ls, T, NH, D, code, v,
                     st)
-            self.plan = astra.astra_plan_merge_attn_states_lse(T, NH, D, True)[1].as_dict()
+            self.plan = astra.astra_plan_merge_attn_states_lse(T, NH, D, True, dtype=code)[1].as_dict()
 
     def launch(self, stream_handle, k: int = 0):
         st = self.fn(k % self.nsets, stream_handle)
@@ -299,7 +301,9 @@ def run_sweep(args):
     torch.cuda.set_device(0)
     stream = torch.cuda.current_stream()
     sh = stream.cuda_stream
-    names = [n for n in sorted(workloads.CASES) if args.only is None or args.only in n]
+    # the benchmark's configs; the binary32-storage cases only when asked for (--only f32...)
+    pool = sorted(workloads.CASES) + (sorted(workloads.F32_CASES) if args.only and args.only.startswith("f32") else [])
+    names = [n for n in pool if args.only is None or args.only in n]
     for n in names:
         c = workloads.case(n)
         data = c.generate()

@@ -6,18 +6,19 @@
  * General rules for every entry point
  *   - All data pointers are DEVICE pointers (HIP global memory on the current device).  The caller owns
  *     every buffer; the library allocates nothing, keeps no state between calls and is re-entrant.
- *   - Tensors are dense, row-major, without strides.  16-bit tensors hold IEEE binary16 (ASTRA_F16) or
- *     bfloat16 (ASTRA_BF16) values; scores are IEEE binary32.
+ *   - Tensors are dense, row-major, without strides.  `dtype` names the storage type of the activation
+ *     tensors: IEEE binary16 (ASTRA_F16), bfloat16 (ASTRA_BF16) -- the types the serving workloads use --
+ *     or IEEE binary32 (ASTRA_F32, a convenience).  Scores are always IEEE binary32.
  *   - Arithmetic is binary32 inside the kernels; each stored 16-bit value is rounded once,
- *     round-to-nearest-even, subnormals preserved.
+ *     round-to-nearest-even, subnormals preserved; binary32 storage is written unrounded.
  *   - The work is enqueued on `stream` (NULL = the default stream) and the call returns without
  *     synchronising.
  *   - Errors are reported by return value only.  Arguments are validated, in the order
  *     null -> shape -> dtype -> eps -> alignment -> aliasing, before any HIP call is made, so a bad call
  *     never touches the device.  T == 0 is valid and does nothing.
- *   - Pointers must be aligned to their element size (2 bytes, scores 4 bytes).  The fast path needs
- *     16-byte aligned pointers and a row length that is a multiple of 8 elements; anything else is
- *     served by a slower element-wise path with the same results.
+ *   - Pointers must be aligned to their element size (2 or 4 bytes, scores 4 bytes).  The fast path needs
+ *     16-byte aligned pointers and a row length that is a multiple of 16 bytes (8 16-bit or 4 binary32
+ *     elements); anything else is served by a slower element-wise path with the same results.
  *   - Element counts (T*H, T*2d, T*num_heads*head_dim) may exceed 2^31; they must fit in int64.
  */
 #ifndef ASTRA_H
@@ -32,7 +33,7 @@ extern "C" {
 /* Same declaration as in the HIP runtime headers; repeating a typedef is legal in C11 and C++. */
 typedef struct ihipStream_t* hipStream_t;
 
-typedef enum { ASTRA_F16 = 0, ASTRA_BF16 = 1 } astra_dtype_t;
+typedef enum { ASTRA_F16 = 0, ASTRA_BF16 = 1, ASTRA_F32 = 2 } astra_dtype_t;
 
 typedef enum {
     ASTRA_OK = 0,

@@ -30,7 +30,8 @@ typedef enum {
     ASTRA_VARIANT_LIBM_EXP_DIVIDE = 4     /* silu_and_mul: library expf and an IEEE divide instead of v_exp_f32 / v_rcp_f32 */
 } astra_variant_t;
 
-#define ASTRA_ERR_VARIANT 8 /* astra_status_t value: variant not applicable to this operator or shape */
+#define ASTRA_ERR_VARIANT 8 /* astra_status_t value: variant not applicable to this operator, shape or storage type
+                               (the variants other than TUNED exist for the 16-bit types only) */
 
 astra_status_t astra_ablation_fused_add_rmsnorm(void* input, void* residual, const void* weight, int64_t T, int64_t H,
                                                 astra_dtype_t dtype, float eps, astra_variant_t variant,

@@ -28,12 +28,14 @@ typedef struct {
     int64_t grid;             /* workgroups launched (padded to a multiple of 8 * 2^log2_xcd_chunk) */
 } astra_launch_info_t;
 
-/* `aligned16` tells whether every tensor pointer of the call is 16-byte aligned (non-zero = yes).
- * Each function validates shapes like its operator does (ASTRA_ERR_SHAPE, ASTRA_ERR_NULL for `info`). */
-astra_status_t astra_plan_fused_add_rmsnorm(int64_t T, int64_t H, int aligned16, astra_launch_info_t* info);
-astra_status_t astra_plan_silu_and_mul(int64_t T, int64_t d, int aligned16, astra_launch_info_t* info);
-astra_status_t astra_plan_merge_attn_states_lse(int64_t T, int64_t num_heads, int64_t head_dim, int aligned16,
-                                                astra_launch_info_t* info);
+/* `dtype` is the storage type of the call, `aligned16` tells whether every tensor pointer of the call is
+ * 16-byte aligned (non-zero = yes).  Each function validates like its operator does (ASTRA_ERR_NULL for
+ * `info`, ASTRA_ERR_SHAPE, ASTRA_ERR_DTYPE). */
+astra_status_t astra_plan_fused_add_rmsnorm(int64_t T, int64_t H, astra_dtype_t dtype, int aligned16,
+                                            astra_launch_info_t* info);
+astra_status_t astra_plan_silu_and_mul(int64_t T, int64_t d, astra_dtype_t dtype, int aligned16, astra_launch_info_t* info);
+astra_status_t astra_plan_merge_attn_states_lse(int64_t T, int64_t num_heads, int64_t head_dim, astra_dtype_t dtype,
+                                                int aligned16, astra_launch_info_t* info);
 
 /* The map from workgroup index to work unit that the kernels apply when log2_xcd_chunk > 0 (the same
  * function the device code runs): workgroup b executes on XCD b % 8, and the workgroups of one XCD are

@@ -14,7 +14,7 @@
  * view as x (same pointer and stride) and r_out the very same view as r -- that is the in-place operator;
  * any other overlap between an output and an input or between the two outputs is ASTRA_ERR_ALIAS
  * (overlap is judged on the bounding byte ranges of the views).  The fast path needs 16-byte aligned
- * pointers and H and all strides multiples of 8; anything else takes the element-wise path.  Everything
+ * pointers and H and all strides multiples of 16 bytes (8 16-bit or 4 binary32 elements); anything else takes the element-wise path.  Everything
  * else -- ownership, stream, validation order, error codes -- is as in astra.h.
  */
 #ifndef ASTRA_STRIDED_H

@@ -15,8 +15,11 @@ import numpy as np
 
 
 def widen(bits: np.ndarray, dtype: str) -> np.ndarray:
-    """uint16 bit patterns -> float64 values (exact)."""
+    """Stored values -> float64 (exact): uint16 bit patterns for "f16"/"bf16", float32 arrays for "f32"."""
     bits = np.ascontiguousarray(bits)
+    if dtype == "f32":
+        assert bits.dtype == np.float32
+        return bits.astype(np.float64)
     assert bits.dtype == np.uint16
     if dtype == "bf16":
         return (bits.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)

@@ -17,6 +17,7 @@ import os
 
 ASTRA_F16 = 0
 ASTRA_BF16 = 1
+ASTRA_F32 = 2
 
 # include/astra_ablation.h
 ASTRA_VARIANT_TUNED = 0
@@ -82,9 +83,9 @@ def load_library() -> ctypes.CDLL:
     L.astra_status_string.argtypes = [i32]
     L.astra_status_string.restype = ctypes.c_char_p
     pinfo = ctypes.POINTER(LaunchInfo)
-    L.astra_plan_fused_add_rmsnorm.argtypes = [i64, i64, i32, pinfo]
-    L.astra_plan_silu_and_mul.argtypes = [i64, i64, i32, pinfo]
-    L.astra_plan_merge_attn_states_lse.argtypes = [i64, i64, i64, i32, pinfo]
+    L.astra_plan_fused_add_rmsnorm.argtypes = [i64, i64, i32, i32, pinfo]
+    L.astra_plan_silu_and_mul.argtypes = [i64, i64, i32, i32, pinfo]
+    L.astra_plan_merge_attn_states_lse.argtypes = [i64, i64, i64, i32, i32, pinfo]
     L.astra_plan_xcd_chunked.argtypes = [ctypes.c_uint32, i32]
     L.astra_plan_xcd_chunked.restype = ctypes.c_uint32
     for n in ("astra_fused_add_rmsnorm", "astra_silu_and_mul", "astra_merge_attn_states_lse", "astra_stream_copy",
@@ -152,16 +153,16 @@ def _plan(fn, *args):
     return st, info
 
 
-def astra_plan_fused_add_rmsnorm(T, H, aligned16=True):
-    return _plan(load_library().astra_plan_fused_add_rmsnorm, T, H, int(aligned16))
+def astra_plan_fused_add_rmsnorm(T, H, aligned16=True, dtype=ASTRA_BF16):
+    return _plan(load_library().astra_plan_fused_add_rmsnorm, T, H, dtype, int(aligned16))
 
 
-def astra_plan_silu_and_mul(T, d, aligned16=True):
-    return _plan(load_library().astra_plan_silu_and_mul, T, d, int(aligned16))
+def astra_plan_silu_and_mul(T, d, aligned16=True, dtype=ASTRA_BF16):
+    return _plan(load_library().astra_plan_silu_and_mul, T, d, dtype, int(aligned16))
 
 
-def astra_plan_merge_attn_states_lse(T, num_heads, head_dim, aligned16=True):
-    return _plan(load_library().astra_plan_merge_attn_states_lse, T, num_heads, head_dim, int(aligned16))
+def astra_plan_merge_attn_states_lse(T, num_heads, head_dim, aligned16=True, dtype=ASTRA_BF16):
+    return _plan(load_library().astra_plan_merge_attn_states_lse, T, num_heads, head_dim, dtype, int(aligned16))
 
 
 def astra_plan_xcd_chunked(workgroup: int, log2_chunk: int) -> int:
@@ -178,7 +179,9 @@ def _dtype_code(t) -> int:
         return ASTRA_BF16
     if t.dtype == torch.float16:
         return ASTRA_F16
-    raise TypeError(f"astra operators take float16 or bfloat16 tensors, got {t.dtype}")
+    if t.dtype == torch.float32:
+        return ASTRA_F32
+    raise TypeError(f"astra operators take float16, bfloat16 or float32 tensors, got {t.dtype}")
 
 
 def _check_gpu(*tensors):

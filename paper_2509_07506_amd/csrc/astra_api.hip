@@ -11,6 +11,7 @@
 
 #include <cstdint>
 #include <limits>
+#include <type_traits>
 
 #include "ablation_kernels.h"
 #include "fused_add_rmsnorm_kernels.h"
@@ -81,14 +82,27 @@ bool overlaps(const void* p, int64_t n, const void* q, int64_t m)
     return n > 0 && m > 0 && a < b + (uintptr_t)m && b < a + (uintptr_t)n;
 }
 
-bool valid_dtype(int dt) { return dt == ASTRA_F16 || dt == ASTRA_BF16; }
+bool valid_dtype(int dt) { return dt == ASTRA_F16 || dt == ASTRA_BF16 || dt == ASTRA_F32; }
+
+// bytes per storage element; anything that is not binary32 counts as 16-bit so that shape checks, which come
+// before the dtype check, are well defined for an invalid dtype too
+int elem_bytes(int dt) { return dt == ASTRA_F32 ? 4 : 2; }
+
+// calls f with the storage type as a compile-time constant
+template <class F>
+void for_dtype(astra_dtype_t dt, F&& f)
+{
+    if (dt == ASTRA_BF16) f(std::integral_constant<int, kBF16>{});
+    else if (dt == ASTRA_F16) f(std::integral_constant<int, kF16>{});
+    else f(std::integral_constant<int, kF32>{});
+}
 
 astra_status_t after_launch() { return hipGetLastError() == hipSuccess ? ASTRA_OK : ASTRA_ERR_LAUNCH; }
 
 int round_up(int v, int m) { return (v + m - 1) / m * m; }
 
 // ---- fused_add_rmsnorm plan -----------------------------------------------------------------------
-// The row lives in registers: hv = H/8 vectors spread over `block` lanes, `vpt` per lane.  Measured on
+// The row lives in registers: hv = H/N vectors (N = 16 / element size) spread over `block` lanes, `vpt` per lane.  Measured on
 // MI355X: rows of up to 1024 vectors (H <= 8192) are fastest with one vector per lane and the widest
 // workgroup, both for few rows (one dependent load-reduce-store chain per lane, the row's bytes
 // requested at once) and for many rows (finest interleaving of loads and stores; two 1024-lane
@@ -114,16 +128,17 @@ bool rmsnorm_row_plan(int64_t T, int64_t hv, RowPlan* plan)
     return true;
 }
 
-astra_status_t plan_rmsnorm(int64_t T, int64_t H, bool aligned16, astra_launch_info_t* info)
+astra_status_t plan_rmsnorm(int64_t T, int64_t H, int eb, bool aligned16, astra_launch_info_t* info)
 {
+    const int64_t ne = kVecBytes / eb;  // elements per 16-byte vector
     int64_t n;
-    if (T < 0 || H <= 0 || mul_overflows(T, H, &n) || n > std::numeric_limits<int64_t>::max() / 2) return ASTRA_ERR_SHAPE;
+    if (T < 0 || H <= 0 || mul_overflows(T, H, &n) || n > std::numeric_limits<int64_t>::max() / 4) return ASTRA_ERR_SHAPE;
     *info = astra_launch_info_t{ASTRA_PATH_NONE, 0, 0, 0, 0};
     if (T == 0) return ASTRA_OK;
     RowPlan rp;
-    if (aligned16 && H % kVecElems == 0 && rmsnorm_row_plan(T, H / kVecElems, &rp)) {
+    if (aligned16 && H % ne == 0 && rmsnorm_row_plan(T, H / ne, &rp)) {
         const int64_t rows = T < kMaxRowGrid ? T : kMaxRowGrid;
-        const int lc = fit_chunk_log2(rows, kRowChunkBytesLog2 - floor_log2(H * 2), kRowChunkMinRows);
+        const int lc = fit_chunk_log2(rows, kRowChunkBytesLog2 - floor_log2(H * eb), kRowChunkMinRows);
         *info = astra_launch_info_t{ASTRA_PATH_VECTOR, rp.block, rp.vpt, lc, T < kMaxRowGrid ? pad_grid(rows, lc) : rows};
     } else {
         *info = astra_launch_info_t{ASTRA_PATH_GENERIC, 256, 0, 0, T < kMaxGenericGrid ? T : kMaxGenericGrid};
@@ -131,17 +146,18 @@ astra_status_t plan_rmsnorm(int64_t T, int64_t H, bool aligned16, astra_launch_i
     return ASTRA_OK;
 }
 
-astra_status_t plan_silu(int64_t T, int64_t d, bool aligned16, astra_launch_info_t* info)
+astra_status_t plan_silu(int64_t T, int64_t d, int eb, bool aligned16, astra_launch_info_t* info)
 {
+    const int64_t ne = kVecBytes / eb;
     int64_t two_d, n;
     if (T < 0 || d <= 0 || mul_overflows(d, 2, &two_d) || mul_overflows(T, two_d, &n) ||
-        n > std::numeric_limits<int64_t>::max() / 2)
+        n > std::numeric_limits<int64_t>::max() / 4)
         return ASTRA_ERR_SHAPE;
     *info = astra_launch_info_t{ASTRA_PATH_NONE, 0, 0, 0, 0};
     if (T == 0) return ASTRA_OK;
-    const int64_t dv = d / kVecElems;
+    const int64_t dv = d / ne;
     // the input holds 2*T*dv vectors and is indexed with 32 bits
-    if (aligned16 && d % kVecElems == 0 && dv >= 32 && 2 * T * dv <= kMaxVecIndex) {
+    if (aligned16 && d % ne == 0 && dv >= 32 && 2 * T * dv <= kMaxVecIndex) {
         const int64_t span = 256 * kSiluUnroll;
         const int64_t blocks = (T * dv + span - 1) / span;
         const int lc = fit_chunk_log2(blocks, kFlatChunkLog2, kFlatChunkMinBlocks);
@@ -152,16 +168,17 @@ astra_status_t plan_silu(int64_t T, int64_t d, bool aligned16, astra_launch_info
     return ASTRA_OK;
 }
 
-astra_status_t plan_merge(int64_t T, int64_t NH, int64_t D, bool aligned16, astra_launch_info_t* info)
+astra_status_t plan_merge(int64_t T, int64_t NH, int64_t D, int eb, bool aligned16, astra_launch_info_t* info)
 {
+    const int64_t ne = kVecBytes / eb;
     int64_t pairs, n;
     if (T < 0 || NH <= 0 || D <= 0 || mul_overflows(T, NH, &pairs) || mul_overflows(pairs, D, &n) ||
         n > std::numeric_limits<int64_t>::max() / 4)
         return ASTRA_ERR_SHAPE;
     *info = astra_launch_info_t{ASTRA_PATH_NONE, 0, 0, 0, 0};
     if (T == 0) return ASTRA_OK;
-    const int64_t dvec = D / kVecElems;
-    if (aligned16 && D % kVecElems == 0 && pairs * dvec <= kMaxVecIndex) {
+    const int64_t dvec = D / ne;
+    if (aligned16 && D % ne == 0 && pairs * dvec <= kMaxVecIndex) {
         const int64_t span = 256 * kMergeUnroll;
         const int64_t blocks = (pairs * dvec + span - 1) / span;
         const int lc = fit_chunk_log2(blocks, kFlatChunkLog2, kFlatChunkMinBlocks);
@@ -181,33 +198,36 @@ void launch_rmsnorm_row(const astra_launch_info_t& li, void* input, void* residu
     fused_add_rmsnorm_row_kernel<DT, VPT, MAXT, kNTLoad, kNTStore, LDS_TREE>
         <<<dim3((uint32_t)li.grid), dim3(li.block), 0, stream>>>(
             static_cast<u32x4*>(input), static_cast<u32x4*>(residual), static_cast<const u32x4*>(weight), T,
-            (uint32_t)(H / kVecElems), 1.0f / (float)H, eps, li.log2_xcd_chunk);
+            (uint32_t)(H / Storage<DT>::kN), 1.0f / (float)H, eps, li.log2_xcd_chunk);
 }
 
 template <int DT>
 void launch_rmsnorm(const astra_launch_info_t& li, void* input, void* residual, const void* weight, int64_t T, int64_t H,
                     float eps, int variant, hipStream_t stream)
 {
-    if (variant == ASTRA_VARIANT_SCALAR_LOADS) {
-        // same decomposition as the tuned kernel (one workgroup per row, row in registers), 16-bit accesses
-        const int block = H >= 1024 ? 1024 : round_up((int)H, kWave);
-        fused_add_rmsnorm_scalar_kernel<DT, 16><<<dim3((uint32_t)(T < kMaxRowGrid ? T : kMaxRowGrid)), dim3(block), 0, stream>>>(
-            static_cast<uint16_t*>(input), static_cast<uint16_t*>(residual), static_cast<const uint16_t*>(weight), T,
-            (uint32_t)H, 1.0f / (float)H, eps);
-        return;
-    }
-    if (variant == ASTRA_VARIANT_LDS_TREE_REDUCTION) {
-        switch (li.vectors_per_lane) {
-            case 1: launch_rmsnorm_row<DT, 1, 1024, true>(li, input, residual, weight, T, H, eps, stream); break;
-            case 2: launch_rmsnorm_row<DT, 2, 1024, true>(li, input, residual, weight, T, H, eps, stream); break;
-            default: launch_rmsnorm_row<DT, 4, 1024, true>(li, input, residual, weight, T, H, eps, stream); break;
+    typedef typename Storage<DT>::elem_t E;
+    if constexpr (DT != kF32) {  // the ablation variants exist for the 16-bit storage types only
+        if (variant == ASTRA_VARIANT_SCALAR_LOADS) {
+            // same decomposition as the tuned kernel (one workgroup per row, row in registers), 16-bit accesses
+            const int block = H >= 1024 ? 1024 : round_up((int)H, kWave);
+            fused_add_rmsnorm_scalar_kernel<DT, 16>
+                <<<dim3((uint32_t)(T < kMaxRowGrid ? T : kMaxRowGrid)), dim3(block), 0, stream>>>(
+                    static_cast<uint16_t*>(input), static_cast<uint16_t*>(residual), static_cast<const uint16_t*>(weight), T,
+                    (uint32_t)H, 1.0f / (float)H, eps);
+            return;
         }
-        return;
+        if (variant == ASTRA_VARIANT_LDS_TREE_REDUCTION) {
+            switch (li.vectors_per_lane) {
+                case 1: launch_rmsnorm_row<DT, 1, 1024, true>(li, input, residual, weight, T, H, eps, stream); break;
+                case 2: launch_rmsnorm_row<DT, 2, 1024, true>(li, input, residual, weight, T, H, eps, stream); break;
+                default: launch_rmsnorm_row<DT, 4, 1024, true>(li, input, residual, weight, T, H, eps, stream); break;
+            }
+            return;
+        }
     }
     if (li.path == ASTRA_PATH_GENERIC) {
         fused_add_rmsnorm_generic_kernel<DT><<<dim3((uint32_t)li.grid), dim3(li.block), 0, stream>>>(
-            static_cast<uint16_t*>(input), static_cast<uint16_t*>(residual), static_cast<const uint16_t*>(weight), T, H,
-            1.0f / (float)H, eps);
+            static_cast<E*>(input), static_cast<E*>(residual), static_cast<const E*>(weight), T, H, 1.0f / (float)H, eps);
         return;
     }
     switch (li.vectors_per_lane) {
@@ -221,25 +241,28 @@ template <int DT>
 void launch_silu(const astra_launch_info_t& li, void* out, const void* in, int64_t T, int64_t d, int variant,
                  hipStream_t stream)
 {
-    if (variant == ASTRA_VARIANT_SCALAR_LOADS) {
-        const uint32_t n = (uint32_t)(T * d);
-        silu_and_mul_scalar_kernel<DT><<<dim3((n + 255u) / 256u), dim3(256), 0, stream>>>(
-            static_cast<uint16_t*>(out), static_cast<const uint16_t*>(in), n, (uint32_t)d, make_fastdiv((uint32_t)d));
-        return;
-    }
-    if (variant == ASTRA_VARIANT_LIBM_EXP_DIVIDE) {
-        const uint32_t dv = (uint32_t)(d / kVecElems);
-        silu_and_mul_vec_kernel<DT, kSiluUnroll, kNTLoad, kNTStore, true><<<dim3((uint32_t)li.grid), dim3(256), 0, stream>>>(
-            static_cast<u32x4*>(out), static_cast<const u32x4*>(in), (uint32_t)(T * dv), dv, make_fastdiv(dv),
-            li.log2_xcd_chunk);
-        return;
+    typedef typename Storage<DT>::elem_t E;
+    if constexpr (DT != kF32) {
+        if (variant == ASTRA_VARIANT_SCALAR_LOADS) {
+            const uint32_t n = (uint32_t)(T * d);
+            silu_and_mul_scalar_kernel<DT><<<dim3((n + 255u) / 256u), dim3(256), 0, stream>>>(
+                static_cast<uint16_t*>(out), static_cast<const uint16_t*>(in), n, (uint32_t)d, make_fastdiv((uint32_t)d));
+            return;
+        }
+        if (variant == ASTRA_VARIANT_LIBM_EXP_DIVIDE) {
+            const uint32_t dv = (uint32_t)(d / Storage<DT>::kN);
+            silu_and_mul_vec_kernel<DT, kSiluUnroll, kNTLoad, kNTStore, true><<<dim3((uint32_t)li.grid), dim3(256), 0, stream>>>(
+                static_cast<u32x4*>(out), static_cast<const u32x4*>(in), (uint32_t)(T * dv), dv, make_fastdiv(dv),
+                li.log2_xcd_chunk);
+            return;
+        }
     }
     if (li.path == ASTRA_PATH_GENERIC) {
         silu_and_mul_generic_kernel<DT><<<dim3((uint32_t)li.grid), dim3(li.block), 0, stream>>>(
-            static_cast<uint16_t*>(out), static_cast<const uint16_t*>(in), T, d);
+            static_cast<E*>(out), static_cast<const E*>(in), T, d);
         return;
     }
-    const uint32_t dv = (uint32_t)(d / kVecElems);
+    const uint32_t dv = (uint32_t)(d / Storage<DT>::kN);
     silu_and_mul_vec_kernel<DT, kSiluUnroll, kNTLoad, kNTStore><<<dim3((uint32_t)li.grid), dim3(256), 0, stream>>>(
         static_cast<u32x4*>(out), static_cast<const u32x4*>(in), (uint32_t)(T * dv), dv, make_fastdiv(dv), li.log2_xcd_chunk);
 }
@@ -248,29 +271,32 @@ template <int DT>
 void launch_merge(const astra_launch_info_t& li, void* v_out, float* lse_out, const void* v_a, const float* lse_a,
                   const void* v_b, const float* lse_b, int64_t pairs, int64_t D, int variant, hipStream_t stream)
 {
-    if (variant == ASTRA_VARIANT_SCALAR_LOADS) {
-        const uint32_t n = (uint32_t)(pairs * D);
-        merge_attn_states_lse_scalar_kernel<DT><<<dim3((n + 255u) / 256u), dim3(256), 0, stream>>>(
-            static_cast<uint16_t*>(v_out), lse_out, static_cast<const uint16_t*>(v_a), lse_a,
-            static_cast<const uint16_t*>(v_b), lse_b, n, (uint32_t)D, make_fastdiv((uint32_t)D));
-        return;
-    }
-    if (variant == ASTRA_VARIANT_UNHOISTED_WEIGHTS) {
-        const uint32_t dvec = (uint32_t)(D / kVecElems);
-        const int log2_dvec = (dvec & (dvec - 1)) == 0 ? __builtin_ctz(dvec) : -1;
-        merge_attn_states_lse_vec_kernel<DT, kMergeUnroll, kNTLoad, kNTStore, false>
-            <<<dim3((uint32_t)li.grid), dim3(256), 0, stream>>>(
-                static_cast<u32x4*>(v_out), lse_out, static_cast<const u32x4*>(v_a), lse_a, static_cast<const u32x4*>(v_b),
-                lse_b, (uint32_t)(pairs * dvec), dvec, log2_dvec, make_fastdiv(dvec), li.log2_xcd_chunk);
-        return;
+    typedef typename Storage<DT>::elem_t E;
+    if constexpr (DT != kF32) {
+        if (variant == ASTRA_VARIANT_SCALAR_LOADS) {
+            const uint32_t n = (uint32_t)(pairs * D);
+            merge_attn_states_lse_scalar_kernel<DT><<<dim3((n + 255u) / 256u), dim3(256), 0, stream>>>(
+                static_cast<uint16_t*>(v_out), lse_out, static_cast<const uint16_t*>(v_a), lse_a,
+                static_cast<const uint16_t*>(v_b), lse_b, n, (uint32_t)D, make_fastdiv((uint32_t)D));
+            return;
+        }
+        if (variant == ASTRA_VARIANT_UNHOISTED_WEIGHTS) {
+            const uint32_t dvec = (uint32_t)(D / Storage<DT>::kN);
+            const int log2_dvec = (dvec & (dvec - 1)) == 0 ? __builtin_ctz(dvec) : -1;
+            merge_attn_states_lse_vec_kernel<DT, kMergeUnroll, kNTLoad, kNTStore, false>
+                <<<dim3((uint32_t)li.grid), dim3(256), 0, stream>>>(
+                    static_cast<u32x4*>(v_out), lse_out, static_cast<const u32x4*>(v_a), lse_a,
+                    static_cast<const u32x4*>(v_b), lse_b, (uint32_t)(pairs * dvec), dvec, log2_dvec, make_fastdiv(dvec),
+                    li.log2_xcd_chunk);
+            return;
+        }
     }
     if (li.path == ASTRA_PATH_GENERIC) {
         merge_attn_states_lse_generic_kernel<DT><<<dim3((uint32_t)li.grid), dim3(li.block), 0, stream>>>(
-            static_cast<uint16_t*>(v_out), lse_out, static_cast<const uint16_t*>(v_a), lse_a,
-            static_cast<const uint16_t*>(v_b), lse_b, pairs, D);
+            static_cast<E*>(v_out), lse_out, static_cast<const E*>(v_a), lse_a, static_cast<const E*>(v_b), lse_b, pairs, D);
         return;
     }
-    const uint32_t dvec = (uint32_t)(D / kVecElems);
+    const uint32_t dvec = (uint32_t)(D / Storage<DT>::kN);
     int log2_dvec = -1;
     if ((dvec & (dvec - 1)) == 0) log2_dvec = __builtin_ctz(dvec);
     merge_attn_states_lse_vec_kernel<DT, kMergeUnroll, kNTLoad, kNTStore><<<dim3((uint32_t)li.grid), dim3(256), 0, stream>>>(
@@ -278,18 +304,19 @@ void launch_merge(const astra_launch_info_t& li, void* v_out, float* lse_out, co
         (uint32_t)(pairs * dvec), dvec, log2_dvec, make_fastdiv(dvec), li.log2_xcd_chunk);
 }
 
-// every part of the K-way input starts 16-byte aligned when the base is and head_dim % 8 == 0, which are the
-// fast-path conditions already
+// every part of the K-way input starts 16-byte aligned when the base is and head_dim is a whole number of
+// vectors, which are the fast-path conditions already
 template <int DT>
 void launch_merge_kway(const astra_launch_info_t& li, void* v_out, float* lse_out, const void* v_parts,
                        const float* lse_parts, int64_t K, int64_t pairs, int64_t D, hipStream_t stream)
 {
     if (li.path == ASTRA_PATH_GENERIC) {
+        typedef typename Storage<DT>::elem_t E;
         merge_attn_states_lse_kway_generic_kernel<DT><<<dim3((uint32_t)li.grid), dim3(256), 0, stream>>>(
-            static_cast<uint16_t*>(v_out), lse_out, static_cast<const uint16_t*>(v_parts), lse_parts, (uint32_t)K, pairs, D);
+            static_cast<E*>(v_out), lse_out, static_cast<const E*>(v_parts), lse_parts, (uint32_t)K, pairs, D);
         return;
     }
-    const uint32_t dvec = (uint32_t)(D / kVecElems);
+    const uint32_t dvec = (uint32_t)(D / Storage<DT>::kN);
     const int log2_dvec = (dvec & (dvec - 1)) == 0 ? __builtin_ctz(dvec) : -1;
     merge_attn_states_lse_kway_vec_kernel<DT, kKwayGroup, kNTLoad, kNTStore><<<dim3((uint32_t)li.grid), dim3(256), 0, stream>>>(
         static_cast<u32x4*>(v_out), lse_out, static_cast<const u32x4*>(v_parts), lse_parts, (uint32_t)K,
@@ -300,10 +327,11 @@ template <int DT, int VPT>
 void launch_rmsnorm_strided_row(const astra_launch_info_t& li, void* y_out, void* r_out, const void* x, const void* r,
                                 const void* weight, const RowViews& ev, int64_t T, int64_t H, float eps, hipStream_t stream)
 {
-    const RowViews vv{ev.y_stride / kVecElems, ev.r_out_stride / kVecElems, ev.x_stride / kVecElems, ev.r_stride / kVecElems};
+    constexpr int N = Storage<DT>::kN;
+    const RowViews vv{ev.y_stride / N, ev.r_out_stride / N, ev.x_stride / N, ev.r_stride / N};
     fused_add_rmsnorm_strided_row_kernel<DT, VPT, 1024, kNTLoad, kNTStore><<<dim3((uint32_t)li.grid), dim3(li.block), 0, stream>>>(
         static_cast<u32x4*>(y_out), static_cast<u32x4*>(r_out), static_cast<const u32x4*>(x), static_cast<const u32x4*>(r),
-        static_cast<const u32x4*>(weight), vv, T, (uint32_t)(H / kVecElems), 1.0f / (float)H, eps, li.log2_xcd_chunk);
+        static_cast<const u32x4*>(weight), vv, T, (uint32_t)(H / Storage<DT>::kN), 1.0f / (float)H, eps, li.log2_xcd_chunk);
 }
 
 // `ev` holds the row strides in elements
@@ -312,9 +340,10 @@ void launch_rmsnorm_strided(const astra_launch_info_t& li, void* y_out, void* r_
                             const void* weight, const RowViews& ev, int64_t T, int64_t H, float eps, hipStream_t stream)
 {
     if (li.path == ASTRA_PATH_GENERIC) {
+        typedef typename Storage<DT>::elem_t E;
         fused_add_rmsnorm_strided_generic_kernel<DT><<<dim3((uint32_t)li.grid), dim3(256), 0, stream>>>(
-            static_cast<uint16_t*>(y_out), static_cast<uint16_t*>(r_out), static_cast<const uint16_t*>(x),
-            static_cast<const uint16_t*>(r), static_cast<const uint16_t*>(weight), ev, T, H, 1.0f / (float)H, eps);
+            static_cast<E*>(y_out), static_cast<E*>(r_out), static_cast<const E*>(x), static_cast<const E*>(r),
+            static_cast<const E*>(weight), ev, T, H, 1.0f / (float)H, eps);
         return;
     }
     switch (li.vectors_per_lane) {
@@ -353,23 +382,27 @@ uint32_t astra_plan_xcd_chunked(uint32_t workgroup, int log2_chunk)
     return xcd_chunked(workgroup, log2_chunk);
 }
 
-astra_status_t astra_plan_fused_add_rmsnorm(int64_t T, int64_t H, int aligned16, astra_launch_info_t* info)
+astra_status_t astra_plan_fused_add_rmsnorm(int64_t T, int64_t H, astra_dtype_t dtype, int aligned16,
+                                            astra_launch_info_t* info)
 {
     if (!info) return ASTRA_ERR_NULL;
-    return plan_rmsnorm(T, H, aligned16 != 0, info);
+    const astra_status_t st = plan_rmsnorm(T, H, elem_bytes((int)dtype), aligned16 != 0, info);
+    return st == ASTRA_OK && !valid_dtype((int)dtype) ? ASTRA_ERR_DTYPE : st;
 }
 
-astra_status_t astra_plan_silu_and_mul(int64_t T, int64_t d, int aligned16, astra_launch_info_t* info)
+astra_status_t astra_plan_silu_and_mul(int64_t T, int64_t d, astra_dtype_t dtype, int aligned16, astra_launch_info_t* info)
 {
     if (!info) return ASTRA_ERR_NULL;
-    return plan_silu(T, d, aligned16 != 0, info);
+    const astra_status_t st = plan_silu(T, d, elem_bytes((int)dtype), aligned16 != 0, info);
+    return st == ASTRA_OK && !valid_dtype((int)dtype) ? ASTRA_ERR_DTYPE : st;
 }
 
-astra_status_t astra_plan_merge_attn_states_lse(int64_t T, int64_t num_heads, int64_t head_dim, int aligned16,
-                                                astra_launch_info_t* info)
+astra_status_t astra_plan_merge_attn_states_lse(int64_t T, int64_t num_heads, int64_t head_dim, astra_dtype_t dtype,
+                                                int aligned16, astra_launch_info_t* info)
 {
     if (!info) return ASTRA_ERR_NULL;
-    return plan_merge(T, num_heads, head_dim, aligned16 != 0, info);
+    const astra_status_t st = plan_merge(T, num_heads, head_dim, elem_bytes((int)dtype), aligned16 != 0, info);
+    return st == ASTRA_OK && !valid_dtype((int)dtype) ? ASTRA_ERR_DTYPE : st;
 }
 
 static astra_status_t run_fused_add_rmsnorm(void* input, void* residual, const void* weight, int64_t T, int64_t H,
@@ -378,23 +411,24 @@ static astra_status_t run_fused_add_rmsnorm(void* input, void* residual, const v
     if (!input || !residual || !weight) return ASTRA_ERR_NULL;
     astra_launch_info_t li;
     const bool a16 = aligned(input, 16) && aligned(residual, 16) && aligned(weight, 16);
-    astra_status_t st = plan_rmsnorm(T, H, a16, &li);
+    const int eb = elem_bytes((int)dtype);
+    astra_status_t st = plan_rmsnorm(T, H, eb, a16, &li);
     if (st != ASTRA_OK) return st;
     if (!valid_dtype((int)dtype)) return ASTRA_ERR_DTYPE;
     if (!(eps >= 0.0f)) return ASTRA_ERR_EPS;
-    if (!aligned(input, 2) || !aligned(residual, 2) || !aligned(weight, 2)) return ASTRA_ERR_ALIGN;
-    const int64_t bytes = T * H * 2;
-    if (overlaps(input, bytes, residual, bytes) || overlaps(input, bytes, weight, H * 2) ||
-        overlaps(residual, bytes, weight, H * 2))
+    if (!aligned(input, eb) || !aligned(residual, eb) || !aligned(weight, eb)) return ASTRA_ERR_ALIGN;
+    const int64_t bytes = T * H * eb;
+    if (overlaps(input, bytes, residual, bytes) || overlaps(input, bytes, weight, H * eb) ||
+        overlaps(residual, bytes, weight, H * eb))
         return ASTRA_ERR_ALIAS;
     if (variant != ASTRA_VARIANT_TUNED) {
+        if (dtype == ASTRA_F32) return (astra_status_t)ASTRA_ERR_VARIANT;
         if (variant != ASTRA_VARIANT_SCALAR_LOADS && variant != ASTRA_VARIANT_LDS_TREE_REDUCTION) return (astra_status_t)ASTRA_ERR_VARIANT;
         if (T > 0 && li.path != ASTRA_PATH_VECTOR) return (astra_status_t)ASTRA_ERR_VARIANT;
         if (variant == ASTRA_VARIANT_SCALAR_LOADS && H > 16384) return (astra_status_t)ASTRA_ERR_VARIANT;
     }
     if (T == 0) return ASTRA_OK;
-    if (dtype == ASTRA_BF16) launch_rmsnorm<kBF16>(li, input, residual, weight, T, H, eps, variant, stream);
-    else launch_rmsnorm<kF16>(li, input, residual, weight, T, H, eps, variant, stream);
+    for_dtype(dtype, [&](auto dt) { launch_rmsnorm<decltype(dt)::value>(li, input, residual, weight, T, H, eps, variant, stream); });
     return after_launch();
 }
 
@@ -416,19 +450,20 @@ static astra_status_t run_silu_and_mul(void* out, const void* input, int64_t T, 
 {
     if (!out || !input) return ASTRA_ERR_NULL;
     astra_launch_info_t li;
-    astra_status_t st = plan_silu(T, d, aligned(out, 16) && aligned(input, 16), &li);
+    const int eb = elem_bytes((int)dtype);
+    astra_status_t st = plan_silu(T, d, eb, aligned(out, 16) && aligned(input, 16), &li);
     if (st != ASTRA_OK) return st;
     if (!valid_dtype((int)dtype)) return ASTRA_ERR_DTYPE;
-    if (!aligned(out, 2) || !aligned(input, 2)) return ASTRA_ERR_ALIGN;
-    if (overlaps(out, T * d * 2, input, T * d * 4)) return ASTRA_ERR_ALIAS;
+    if (!aligned(out, eb) || !aligned(input, eb)) return ASTRA_ERR_ALIGN;
+    if (overlaps(out, T * d * eb, input, T * d * 2 * eb)) return ASTRA_ERR_ALIAS;
     if (variant != ASTRA_VARIANT_TUNED) {
+        if (dtype == ASTRA_F32) return (astra_status_t)ASTRA_ERR_VARIANT;
         if (variant != ASTRA_VARIANT_SCALAR_LOADS && variant != ASTRA_VARIANT_LIBM_EXP_DIVIDE) return (astra_status_t)ASTRA_ERR_VARIANT;
         if (T > 0 && li.path != ASTRA_PATH_VECTOR) return (astra_status_t)ASTRA_ERR_VARIANT;
         if (variant == ASTRA_VARIANT_SCALAR_LOADS && T * d >= (int64_t(1) << 32)) return (astra_status_t)ASTRA_ERR_VARIANT;
     }
     if (T == 0) return ASTRA_OK;
-    if (dtype == ASTRA_BF16) launch_silu<kBF16>(li, out, input, T, d, variant, stream);
-    else launch_silu<kF16>(li, out, input, T, d, variant, stream);
+    for_dtype(dtype, [&](auto dt) { launch_silu<decltype(dt)::value>(li, out, input, T, d, variant, stream); });
     return after_launch();
 }
 
@@ -450,15 +485,16 @@ static astra_status_t run_merge_attn_states_lse(void* v_out, float* lse_out, con
 {
     if (!v_out || !lse_out || !v_a || !lse_a || !v_b || !lse_b) return ASTRA_ERR_NULL;
     astra_launch_info_t li;
+    const int eb = elem_bytes((int)dtype);
     astra_status_t st =
-        plan_merge(T, num_heads, head_dim, aligned(v_out, 16) && aligned(v_a, 16) && aligned(v_b, 16), &li);
+        plan_merge(T, num_heads, head_dim, eb, aligned(v_out, 16) && aligned(v_a, 16) && aligned(v_b, 16), &li);
     if (st != ASTRA_OK) return st;
     if (!valid_dtype((int)dtype)) return ASTRA_ERR_DTYPE;
-    if (!aligned(v_out, 2) || !aligned(v_a, 2) || !aligned(v_b, 2) || !aligned(lse_out, 4) || !aligned(lse_a, 4) ||
+    if (!aligned(v_out, eb) || !aligned(v_a, eb) || !aligned(v_b, eb) || !aligned(lse_out, 4) || !aligned(lse_a, 4) ||
         !aligned(lse_b, 4))
         return ASTRA_ERR_ALIGN;
     const int64_t pairs = T * num_heads;
-    const int64_t vbytes = pairs * head_dim * 2, sbytes = pairs * 4;
+    const int64_t vbytes = pairs * head_dim * eb, sbytes = pairs * 4;
     if ((v_out != v_a && overlaps(v_out, vbytes, v_a, vbytes)) || (v_out != v_b && overlaps(v_out, vbytes, v_b, vbytes)) ||
         overlaps(lse_out, sbytes, lse_a, sbytes) || overlaps(lse_out, sbytes, lse_b, sbytes) ||
         overlaps(v_out, vbytes, lse_a, sbytes) || overlaps(v_out, vbytes, lse_b, sbytes) ||
@@ -466,13 +502,15 @@ static astra_status_t run_merge_attn_states_lse(void* v_out, float* lse_out, con
         overlaps(lse_out, sbytes, v_out, vbytes))
         return ASTRA_ERR_ALIAS;
     if (variant != ASTRA_VARIANT_TUNED) {
+        if (dtype == ASTRA_F32) return (astra_status_t)ASTRA_ERR_VARIANT;
         if (variant != ASTRA_VARIANT_SCALAR_LOADS && variant != ASTRA_VARIANT_UNHOISTED_WEIGHTS) return (astra_status_t)ASTRA_ERR_VARIANT;
         if (T > 0 && li.path != ASTRA_PATH_VECTOR) return (astra_status_t)ASTRA_ERR_VARIANT;
         if (variant == ASTRA_VARIANT_SCALAR_LOADS && pairs * head_dim >= (int64_t(1) << 32)) return (astra_status_t)ASTRA_ERR_VARIANT;
     }
     if (T == 0) return ASTRA_OK;
-    if (dtype == ASTRA_BF16) launch_merge<kBF16>(li, v_out, lse_out, v_a, lse_a, v_b, lse_b, pairs, head_dim, variant, stream);
-    else launch_merge<kF16>(li, v_out, lse_out, v_a, lse_a, v_b, lse_b, pairs, head_dim, variant, stream);
+    for_dtype(dtype, [&](auto dt) {
+        launch_merge<decltype(dt)::value>(li, v_out, lse_out, v_a, lse_a, v_b, lse_b, pairs, head_dim, variant, stream);
+    });
     return after_launch();
 }
 
@@ -499,22 +537,24 @@ astra_status_t astra_merge_attn_states_lse_kway(void* v_out, float* lse_out, con
 {
     if (!v_out || !lse_out || !v_parts || !lse_parts) return ASTRA_ERR_NULL;
     astra_launch_info_t li;
-    astra_status_t st = plan_merge(T, num_heads, head_dim, aligned(v_out, 16) && aligned(v_parts, 16), &li);
+    const int eb = elem_bytes((int)dtype);
+    astra_status_t st = plan_merge(T, num_heads, head_dim, eb, aligned(v_out, 16) && aligned(v_parts, 16), &li);
     if (st != ASTRA_OK) return st;
     const int64_t pairs = T * num_heads;
     int64_t part_elems = pairs * head_dim, all_elems;
     if (K < 1 || K > 65536 || mul_overflows(part_elems, K, &all_elems) || all_elems > std::numeric_limits<int64_t>::max() / 4)
         return ASTRA_ERR_SHAPE;
     if (!valid_dtype((int)dtype)) return ASTRA_ERR_DTYPE;
-    if (!aligned(v_out, 2) || !aligned(v_parts, 2) || !aligned(lse_out, 4) || !aligned(lse_parts, 4)) return ASTRA_ERR_ALIGN;
-    const int64_t vbytes = part_elems * 2, sbytes = pairs * 4;
+    if (!aligned(v_out, eb) || !aligned(v_parts, eb) || !aligned(lse_out, 4) || !aligned(lse_parts, 4)) return ASTRA_ERR_ALIGN;
+    const int64_t vbytes = part_elems * eb, sbytes = pairs * 4;
     if (overlaps(v_out, vbytes, v_parts, vbytes * K) || overlaps(v_out, vbytes, lse_parts, sbytes * K) ||
         overlaps(lse_out, sbytes, v_parts, vbytes * K) || overlaps(lse_out, sbytes, lse_parts, sbytes * K) ||
         overlaps(lse_out, sbytes, v_out, vbytes))
         return ASTRA_ERR_ALIAS;
     if (T == 0) return ASTRA_OK;
-    if (dtype == ASTRA_BF16) launch_merge_kway<kBF16>(li, v_out, lse_out, v_parts, lse_parts, K, pairs, head_dim, stream);
-    else launch_merge_kway<kF16>(li, v_out, lse_out, v_parts, lse_parts, K, pairs, head_dim, stream);
+    for_dtype(dtype, [&](auto dt) {
+        launch_merge_kway<decltype(dt)::value>(li, v_out, lse_out, v_parts, lse_parts, K, pairs, head_dim, stream);
+    });
     return after_launch();
 }
 
@@ -526,34 +566,36 @@ astra_status_t astra_fused_add_rmsnorm_strided(void* y_out, int64_t y_stride, vo
     if (!y_out || !r_out || !x || !r || !weight) return ASTRA_ERR_NULL;
     const int64_t strides[4] = {y_stride, r_out_stride, x_stride, r_stride};
     const void* const bases[4] = {y_out, r_out, x, r};
+    const int eb = elem_bytes((int)dtype);
     bool fast = aligned(weight, 16);
-    for (int i = 0; i < 4; ++i) fast = fast && aligned(bases[i], 16) && strides[i] % kVecElems == 0;
+    for (int i = 0; i < 4; ++i) fast = fast && aligned(bases[i], 16) && strides[i] % (kVecBytes / eb) == 0;
     astra_launch_info_t li;
-    astra_status_t st = plan_rmsnorm(T, H, fast, &li);
+    astra_status_t st = plan_rmsnorm(T, H, eb, fast, &li);
     if (st != ASTRA_OK) return st;
     int64_t span[4];  // bounding extent of each view in bytes
     for (int i = 0; i < 4; ++i) {
         int64_t rows_bytes;
         if (strides[i] < H || mul_overflows(T > 0 ? T - 1 : 0, strides[i], &rows_bytes) ||
-            rows_bytes > std::numeric_limits<int64_t>::max() / 4)
+            rows_bytes > std::numeric_limits<int64_t>::max() / 8)
             return ASTRA_ERR_SHAPE;
-        span[i] = T > 0 ? (rows_bytes + H) * 2 : 0;
+        span[i] = T > 0 ? (rows_bytes + H) * eb : 0;
     }
     if (!valid_dtype((int)dtype)) return ASTRA_ERR_DTYPE;
     if (!(eps >= 0.0f)) return ASTRA_ERR_EPS;
     for (int i = 0; i < 4; ++i)
-        if (!aligned(bases[i], 2)) return ASTRA_ERR_ALIGN;
-    if (!aligned(weight, 2)) return ASTRA_ERR_ALIGN;
+        if (!aligned(bases[i], eb)) return ASTRA_ERR_ALIGN;
+    if (!aligned(weight, eb)) return ASTRA_ERR_ALIGN;
     const bool y_in_place = (y_out == x && y_stride == x_stride), r_in_place = (r_out == r && r_out_stride == r_stride);
     if ((!y_in_place && overlaps(y_out, span[0], x, span[2])) || (!r_in_place && overlaps(r_out, span[1], r, span[3])) ||
         overlaps(y_out, span[0], r, span[3]) || overlaps(r_out, span[1], x, span[2]) ||
-        overlaps(y_out, span[0], r_out, span[1]) || overlaps(y_out, span[0], weight, H * 2) ||
-        overlaps(r_out, span[1], weight, H * 2))
+        overlaps(y_out, span[0], r_out, span[1]) || overlaps(y_out, span[0], weight, H * eb) ||
+        overlaps(r_out, span[1], weight, H * eb))
         return ASTRA_ERR_ALIAS;
     if (T == 0) return ASTRA_OK;
     const RowViews views{y_stride, r_out_stride, x_stride, r_stride};
-    if (dtype == ASTRA_BF16) launch_rmsnorm_strided<kBF16>(li, y_out, r_out, x, r, weight, views, T, H, eps, stream);
-    else launch_rmsnorm_strided<kF16>(li, y_out, r_out, x, r, weight, views, T, H, eps, stream);
+    for_dtype(dtype, [&](auto dt) {
+        launch_rmsnorm_strided<decltype(dt)::value>(li, y_out, r_out, x, r, weight, views, T, H, eps, stream);
+    });
     return after_launch();
 }
 

@@ -1,8 +1,8 @@
 // Device-side building blocks shared by the three gfx950 kernels: 16-byte vector access, 16-bit
 // storage-type conversion, wave64 and workgroup sum reductions, and the fast transcendental forms.
 //
-// gfx950 only.  A wavefront is 64 lanes; one lane moves 16 bytes (8 storage elements) per access so a
-// wave covers 1 KiB of contiguous memory per instruction.
+// gfx950 only.  A wavefront is 64 lanes; one lane moves 16 bytes (8 16-bit or 4 binary32 storage
+// elements) per access so a wave covers 1 KiB of contiguous memory per instruction.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -11,14 +11,14 @@
 namespace astra {
 
 constexpr int kWave = 64;
-constexpr int kVecElems = 8;  // 16-bit elements per 16-byte vector
+constexpr int kVecBytes = 16;
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 
-enum : int { kF16 = 0, kBF16 = 1 };
+enum : int { kF16 = 0, kBF16 = 1, kF32 = 2 };
 
 // ---------------------------------------------------------------------------------------------
 // global memory access.  Activations are touched exactly once, so they are moved with the
@@ -39,14 +39,18 @@ __device__ __forceinline__ void store_vec(u32x4* p, u32x4 v)
 }
 
 // ---------------------------------------------------------------------------------------------
-// storage types.  unpack2: one dword holding two 16-bit values -> two floats (exact).
-// pack2: two floats -> one dword, round-to-nearest-even (v_cvt_pk_bf16_f32 / v_cvt_pk_f16_f32).
+// storage types.  kN: elements per 16-byte vector; elem_t: the element as an integer or float word.
+// 16-bit types: unpack2 turns one dword holding two values into two floats (exact), pack2 turns two
+// floats into one dword, round-to-nearest-even (v_cvt_pk_bf16_f32 / v_cvt_pk_f16_f32).  binary32
+// storage needs no conversion at all.
 
 template <int DT>
 struct Storage;
 
 template <>
 struct Storage<kBF16> {
+    static constexpr int kN = 8;
+    typedef uint16_t elem_t;
     static __device__ __forceinline__ f32x2 unpack2(uint32_t w)
     {
         f32x2 r;
@@ -65,6 +69,8 @@ struct Storage<kBF16> {
 
 template <>
 struct Storage<kF16> {
+    static constexpr int kN = 8;
+    typedef uint16_t elem_t;
     static __device__ __forceinline__ f32x2 unpack2(uint32_t w)
     {
         return __builtin_convertvector(__builtin_bit_cast(f16x2, w), f32x2);
@@ -78,23 +84,46 @@ struct Storage<kF16> {
     static __device__ __forceinline__ uint16_t narrow(float f) { return __builtin_bit_cast(uint16_t, (_Float16)f); }
 };
 
+template <>
+struct Storage<kF32> {
+    static constexpr int kN = 4;
+    typedef float elem_t;
+    static __device__ __forceinline__ float widen(float f) { return f; }
+    static __device__ __forceinline__ float narrow(float f) { return f; }
+};
+
+// by-value helpers: the bit cast is applied to a plain scalar, never to a vector-element expression
+__device__ __forceinline__ float word_as_float(uint32_t w) { return __builtin_bit_cast(float, w); }
+__device__ __forceinline__ uint32_t float_as_word(float f) { return __builtin_bit_cast(uint32_t, f); }
+
+// one 16-byte vector <-> its Storage<DT>::kN values as floats
 template <int DT>
-__device__ __forceinline__ void unpack8(u32x4 v, float (&f)[8])
+__device__ __forceinline__ void unpack_vec(u32x4 v, float (&f)[Storage<DT>::kN])
 {
-    f32x2 a = Storage<DT>::unpack2(v.x), b = Storage<DT>::unpack2(v.y);
-    f32x2 c = Storage<DT>::unpack2(v.z), d = Storage<DT>::unpack2(v.w);
-    f[0] = a.x; f[1] = a.y; f[2] = b.x; f[3] = b.y;
-    f[4] = c.x; f[5] = c.y; f[6] = d.x; f[7] = d.y;
+    if constexpr (DT == kF32) {
+        f[0] = word_as_float(v.x); f[1] = word_as_float(v.y);
+        f[2] = word_as_float(v.z); f[3] = word_as_float(v.w);
+    } else {
+        f32x2 a = Storage<DT>::unpack2(v.x), b = Storage<DT>::unpack2(v.y);
+        f32x2 c = Storage<DT>::unpack2(v.z), d = Storage<DT>::unpack2(v.w);
+        f[0] = a.x; f[1] = a.y; f[2] = b.x; f[3] = b.y;
+        f[4] = c.x; f[5] = c.y; f[6] = d.x; f[7] = d.y;
+    }
 }
 
 template <int DT>
-__device__ __forceinline__ u32x4 pack8(const float (&f)[8])
+__device__ __forceinline__ u32x4 pack_vec(const float (&f)[Storage<DT>::kN])
 {
     u32x4 v;
-    v.x = Storage<DT>::pack2(f[0], f[1]);
-    v.y = Storage<DT>::pack2(f[2], f[3]);
-    v.z = Storage<DT>::pack2(f[4], f[5]);
-    v.w = Storage<DT>::pack2(f[6], f[7]);
+    if constexpr (DT == kF32) {
+        v.x = float_as_word(f[0]); v.y = float_as_word(f[1]);
+        v.z = float_as_word(f[2]); v.w = float_as_word(f[3]);
+    } else {
+        v.x = Storage<DT>::pack2(f[0], f[1]);
+        v.y = Storage<DT>::pack2(f[2], f[3]);
+        v.z = Storage<DT>::pack2(f[4], f[5]);
+        v.w = Storage<DT>::pack2(f[6], f[7]);
+    }
     return v;
 }
 

@@ -1,8 +1,8 @@
 // fused_add_rmsnorm for gfx950 -- paper Table 1, Kernel 2:
 //   y = (x + r) / sqrt(||x + r||^2 / H + eps) (.) w,  input <- y, residual <- x + r (both in place).
 //
-// One pass over HBM: a workgroup holds a whole row of binary32 sums in registers (VPT vectors of 8
-// per lane), so x and r are read once and each written once.  The sum of squares is reduced inside
+// One pass over HBM: a workgroup holds a whole row of binary32 sums in registers (VPT vectors of N = 8
+// 16-bit or 4 binary32 elements per lane), so x and r are read once and each written once.  The sum of squares is reduced inside
 // each wave with DPP (registers only) and across waves through one LDS float per wave and a single
 // barrier -- the register-first reduction of the paper's Fig. 3b, on 64-lane waves.
 #pragma once
@@ -11,7 +11,7 @@
 
 namespace astra {
 
-// Fast path: H % 8 == 0, 16-byte aligned pointers, hv = H/8 <= VPT * blockDim.x (VPT is 1, 2 or 4).
+// Fast path: H % N == 0, 16-byte aligned pointers, hv = H/N <= VPT * blockDim.x (VPT is 1, 2 or 4).
 // blockDim.x is a multiple of 64 and at most MAX_THREADS.  Lane `tid` owns vectors tid + k*blockDim.x.
 // A block walks rows r0, r0 + gridDim.x, ... (normally exactly one row), r0 = xcd_chunked(blockIdx.x).
 template <int DT, int VPT, int MAX_THREADS, bool NTL, bool NTS, bool LDS_TREE = false>
@@ -20,6 +20,7 @@ __global__ __launch_bounds__(MAX_THREADS) void fused_add_rmsnorm_row_kernel(u32x
                                                                             int64_t T, uint32_t hv, float inv_h, float eps,
                                                                             int log2_chunk)
 {
+    constexpr int N = Storage<DT>::kN;
     __shared__ float partials[2][16];
     __shared__ float tree[LDS_TREE ? 1024 : 1];  // ablation only
     const int nwaves = blockDim.x >> 6;
@@ -48,21 +49,21 @@ __global__ __launch_bounds__(MAX_THREADS) void fused_add_rmsnorm_row_kernel(u32x
             }
         }
 
-        float s[VPT][8];
+        float s[VPT][N];
         float acc = 0.0f;
 #pragma unroll
         for (int k = 0; k < VPT; ++k) {
             const uint32_t v = threadIdx.x + k * blockDim.x;
             if (v < hv) {
-                float x[8], r[8];
-                unpack8<DT>(xv[k], x);
-                unpack8<DT>(rv[k], r);
+                float x[N], r[N];
+                unpack_vec<DT>(xv[k], x);
+                unpack_vec<DT>(rv[k], r);
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
+                for (int e = 0; e < N; ++e) {
                     s[k][e] = x[e] + r[e];
                     acc += s[k][e] * s[k][e];
                 }
-                store_vec<NTS>(rrow + v, pack8<DT>(s[k]));
+                store_vec<NTS>(rrow + v, pack_vec<DT>(s[k]));
             }
         }
 
@@ -73,30 +74,32 @@ __global__ __launch_bounds__(MAX_THREADS) void fused_add_rmsnorm_row_kernel(u32x
         for (int k = 0; k < VPT; ++k) {
             const uint32_t v = threadIdx.x + k * blockDim.x;
             if (v < hv) {
-                float w[8], y[8];
-                unpack8<DT>(wv[k], w);
+                float w[N], y[N];
+                unpack_vec<DT>(wv[k], w);
 #pragma unroll
-                for (int e = 0; e < 8; ++e) y[e] = (s[k][e] * scale) * w[e];
-                store_vec<NTS>(xrow + v, pack8<DT>(y));
+                for (int e = 0; e < N; ++e) y[e] = (s[k][e] * scale) * w[e];
+                store_vec<NTS>(xrow + v, pack_vec<DT>(y));
             }
         }
     }
 }
 
-// Element-wise path for any H and 2-byte aligned pointers: two passes over the row.  The first pass
+// Element-wise path for any H and element-aligned pointers: two passes over the row.  The first pass
 // only reads (it needs the unrounded sums, so the residual cannot be written yet); the second
 // recomputes x + r, stores it and the normalised value.  Each element is read and written by the
 // same lane, so the in-place update is safe.
 template <int DT>
-__global__ __launch_bounds__(256) void fused_add_rmsnorm_generic_kernel(uint16_t* input, uint16_t* residual,
-                                                                        const uint16_t* __restrict__ weight, int64_t T,
-                                                                        int64_t H, float inv_h, float eps)
+__global__ __launch_bounds__(256) void fused_add_rmsnorm_generic_kernel(typename Storage<DT>::elem_t* input,
+                                                                        typename Storage<DT>::elem_t* residual,
+                                                                        const typename Storage<DT>::elem_t* __restrict__ weight,
+                                                                        int64_t T, int64_t H, float inv_h, float eps)
 {
+    typedef typename Storage<DT>::elem_t E;
     __shared__ float partials[2][16];
     int parity = 0;
     for (int64_t row = blockIdx.x; row < T; row += gridDim.x, parity ^= 1) {
-        uint16_t* x = input + row * H;
-        uint16_t* r = residual + row * H;
+        E* x = input + row * H;
+        E* r = residual + row * H;
         float acc = 0.0f;
         for (int64_t j = threadIdx.x; j < H; j += blockDim.x) {
             float s = Storage<DT>::widen(x[j]) + Storage<DT>::widen(r[j]);
@@ -128,6 +131,7 @@ __global__ __launch_bounds__(MAX_THREADS) void fused_add_rmsnorm_strided_row_ker
                                                                                     RowViews sv, int64_t T, uint32_t hv,
                                                                                     float inv_h, float eps, int log2_chunk)
 {
+    constexpr int N = Storage<DT>::kN;
     __shared__ float partials[2][16];
     const int nwaves = blockDim.x >> 6;
     const int64_t first_row = xcd_chunked(blockIdx.x, log2_chunk);
@@ -151,21 +155,21 @@ __global__ __launch_bounds__(MAX_THREADS) void fused_add_rmsnorm_strided_row_ker
                 rv[k] = load_vec<NTL>(rrow + v);
             }
         }
-        float s[VPT][8];
+        float s[VPT][N];
         float acc = 0.0f;
 #pragma unroll
         for (int k = 0; k < VPT; ++k) {
             const uint32_t v = threadIdx.x + k * blockDim.x;
             if (v < hv) {
-                float xf[8], rf[8];
-                unpack8<DT>(xv[k], xf);
-                unpack8<DT>(rv[k], rf);
+                float xf[N], rf[N];
+                unpack_vec<DT>(xv[k], xf);
+                unpack_vec<DT>(rv[k], rf);
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
+                for (int e = 0; e < N; ++e) {
                     s[k][e] = xf[e] + rf[e];
                     acc += s[k][e] * s[k][e];
                 }
-                store_vec<NTS>(r_out + row * sv.r_out_stride + v, pack8<DT>(s[k]));
+                store_vec<NTS>(r_out + row * sv.r_out_stride + v, pack_vec<DT>(s[k]));
             }
         }
         const float total = block_sum(acc, partials[parity], nwaves);
@@ -174,28 +178,28 @@ __global__ __launch_bounds__(MAX_THREADS) void fused_add_rmsnorm_strided_row_ker
         for (int k = 0; k < VPT; ++k) {
             const uint32_t v = threadIdx.x + k * blockDim.x;
             if (v < hv) {
-                float w[8], y[8];
-                unpack8<DT>(wv[k], w);
+                float w[N], y[N];
+                unpack_vec<DT>(wv[k], w);
 #pragma unroll
-                for (int e = 0; e < 8; ++e) y[e] = (s[k][e] * scale) * w[e];
-                store_vec<NTS>(y_out + row * sv.y_stride + v, pack8<DT>(y));
+                for (int e = 0; e < N; ++e) y[e] = (s[k][e] * scale) * w[e];
+                store_vec<NTS>(y_out + row * sv.y_stride + v, pack_vec<DT>(y));
             }
         }
     }
 }
 
 template <int DT>
-__global__ __launch_bounds__(256) void fused_add_rmsnorm_strided_generic_kernel(uint16_t* y_out, uint16_t* r_out,
-                                                                                const uint16_t* x, const uint16_t* r,
-                                                                                const uint16_t* __restrict__ weight,
-                                                                                RowViews sv, int64_t T, int64_t H, float inv_h,
-                                                                                float eps)
+__global__ __launch_bounds__(256) void fused_add_rmsnorm_strided_generic_kernel(
+    typename Storage<DT>::elem_t* y_out, typename Storage<DT>::elem_t* r_out, const typename Storage<DT>::elem_t* x,
+    const typename Storage<DT>::elem_t* r, const typename Storage<DT>::elem_t* __restrict__ weight, RowViews sv, int64_t T,
+    int64_t H, float inv_h, float eps)
 {
+    typedef typename Storage<DT>::elem_t E;
     __shared__ float partials[2][16];
     int parity = 0;
     for (int64_t row = blockIdx.x; row < T; row += gridDim.x, parity ^= 1) {
-        const uint16_t* xr = x + row * sv.x_stride;
-        const uint16_t* rr = r + row * sv.r_stride;
+        const E* xr = x + row * sv.x_stride;
+        const E* rr = r + row * sv.r_stride;
         float acc = 0.0f;
         for (int64_t j = threadIdx.x; j < H; j += blockDim.x) {
             float s = Storage<DT>::widen(xr[j]) + Storage<DT>::widen(rr[j]);

@@ -1,8 +1,8 @@
 // merge_attn_states_lse for gfx950 -- paper Table 1, Kernel 1:
 //   V_out = (e^Sa V_a + e^Sb V_b) / (e^Sa + e^Sb),  S_out = log(e^Sa + e^Sb).
 //
-// One lane owns one 16-byte vector (8 elements) of one (token, head) pair.  The two mixing weights
-// depend only on the pair, so a lane computes them once for its 8 elements (the hoisting of the
+// One lane owns one 16-byte vector (N = 8 16-bit or 4 binary32 elements) of one (token, head) pair.  The
+// two mixing weights depend only on the pair, so a lane computes them once for its N elements (the hoisting of the
 // paper's Fig. 2b); the lanes that share a pair read the same two scores from one cache line.
 // Per lane that is 4 transcendental ops against 48 bytes of traffic, far below the memory time.
 #pragma once
@@ -35,7 +35,7 @@ __device__ __forceinline__ MergeWeights merge_weights(float sa, float sb)
     return w;
 }
 
-// Fast path: head_dim % 8 == 0, 16-byte aligned v pointers.  Flat list of vectors, dvec = head_dim/8
+// Fast path: head_dim % N == 0, 16-byte aligned v pointers.  Flat list of vectors, dvec = head_dim/N
 // per pair.  The pair index is a shift when dvec is a power of two (LOG2_DVEC >= 0), otherwise a
 // multiply-high division.  v_out may alias v_a or v_b exactly: all loads of a lane precede its stores.
 // lse_out must not alias the input scores: the lanes of one pair can sit in different waves.
@@ -46,6 +46,7 @@ __global__ __launch_bounds__(BLOCK) void merge_attn_states_lse_vec_kernel(u32x4*
                                                                         uint32_t dvec, int log2_dvec, FastDiv by_dvec,
                                                                         int log2_chunk)
 {
+    constexpr int N = Storage<DT>::kN;
     const uint32_t first = xcd_chunked(blockIdx.x, log2_chunk) * (uint32_t(BLOCK) * UNROLL) + threadIdx.x;
     u32x4 av[UNROLL], bv[UNROLL];
     float sa[UNROLL], sb[UNROLL];
@@ -66,36 +67,37 @@ __global__ __launch_bounds__(BLOCK) void merge_attn_states_lse_vec_kernel(u32x4*
         const uint32_t i = first + uint32_t(BLOCK) * k;
         if (i < total_vecs) {
             const MergeWeights w = merge_weights(sa[k], sb[k]);
-            float a[8], b[8], o[8];
-            unpack8<DT>(av[k], a);
-            unpack8<DT>(bv[k], b);
+            float a[N], b[N], o[N];
+            unpack_vec<DT>(av[k], a);
+            unpack_vec<DT>(bv[k], b);
             if constexpr (HOIST) {
 #pragma unroll
-                for (int e = 0; e < 8; ++e) o[e] = w.a * a[e] + w.b * b[e];
+                for (int e = 0; e < N; ++e) o[e] = w.a * a[e] + w.b * b[e];
             } else {
                 // ablation only (the pattern of the paper's Fig. 2a): the weights are worked out again for
                 // every element.  The empty asm makes the score opaque so the compiler cannot merge the
-                // eight evaluations back into one.
+                // N evaluations back into one.
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
+                for (int e = 0; e < N; ++e) {
                     float s = sa[k];
                     asm volatile("" : "+v"(s));
                     const MergeWeights we = merge_weights(s, sb[k]);
                     o[e] = we.a * a[e] + we.b * b[e];
                 }
             }
-            store_vec<NTS>(v_out + i, pack8<DT>(o));
+            store_vec<NTS>(v_out + i, pack_vec<DT>(o));
             if (i == pair[k] * dvec) lse_out[pair[k]] = w.lse;  // first vector of the pair
         }
     }
 }
 
-// Element-wise path for any head_dim and 2-byte aligned pointers: one block per (token, head) pair.
+// Element-wise path for any head_dim and element-aligned pointers: one block per (token, head) pair.
 template <int DT>
-__global__ __launch_bounds__(256) void merge_attn_states_lse_generic_kernel(uint16_t* v_out, float* lse_out,
-                                                                            const uint16_t* v_a, const float* lse_a,
-                                                                            const uint16_t* v_b, const float* lse_b,
-                                                                            int64_t pairs, int64_t D)
+__global__ __launch_bounds__(256) void merge_attn_states_lse_generic_kernel(typename Storage<DT>::elem_t* v_out, float* lse_out,
+                                                                            const typename Storage<DT>::elem_t* v_a,
+                                                                            const float* lse_a,
+                                                                            const typename Storage<DT>::elem_t* v_b,
+                                                                            const float* lse_b, int64_t pairs, int64_t D)
 {
     for (int64_t p = blockIdx.x; p < pairs; p += gridDim.x) {
         const MergeWeights w = merge_weights(lse_a[p], lse_b[p]);
@@ -149,12 +151,15 @@ __global__ __launch_bounds__(256) void merge_attn_states_lse_kway_vec_kernel(u32
                                                                              uint32_t dvec, int log2_dvec, FastDiv by_dvec,
                                                                              int log2_chunk)
 {
+    constexpr int N = Storage<DT>::kN;
     const uint32_t i = xcd_chunked(blockIdx.x, log2_chunk) * 256u + threadIdx.x;
     if (i >= total_vecs) return;
     const uint32_t pair = log2_dvec >= 0 ? (i >> log2_dvec) : by_dvec.div(i);
     const float ninf = -__builtin_inff();
     float m = ninf, den = 0.0f;
-    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    float acc[N];
+#pragma unroll
+    for (int e = 0; e < N; ++e) acc[e] = 0.0f;
     for (uint32_t k0 = 0; k0 < K; k0 += G) {
         u32x4 pv[G];
         float s[G];
@@ -177,15 +182,15 @@ __global__ __launch_bounds__(256) void merge_attn_states_lse_kway_vec_kernel(u32
             const float rescale = fast_exp(m - mn);  // first live group: m = -inf, e^-inf = 0, sums are 0 anyway
             den *= rescale;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) acc[e] *= rescale;
+            for (int e = 0; e < N; ++e) acc[e] *= rescale;
 #pragma unroll
             for (int g = 0; g < G; ++g) {
                 const float w = fast_exp(s[g] - mn);
                 den += w;
-                float v[8];
-                unpack8<DT>(pv[g], v);
+                float v[N];
+                unpack_vec<DT>(pv[g], v);
 #pragma unroll
-                for (int e = 0; e < 8; ++e) acc[e] += w * v[e];
+                for (int e = 0; e < N; ++e) acc[e] += w * v[e];
             }
             m = mn;
         }
@@ -193,16 +198,16 @@ __global__ __launch_bounds__(256) void merge_attn_states_lse_kway_vec_kernel(u32
     const bool empty = (m == ninf);
     const float inv = empty ? 0.0f : fast_rcp(den);
 #pragma unroll
-    for (int e = 0; e < 8; ++e) acc[e] *= inv;
-    store_vec<NTS>(v_out + i, pack8<DT>(acc));
+    for (int e = 0; e < N; ++e) acc[e] *= inv;
+    store_vec<NTS>(v_out + i, pack_vec<DT>(acc));
     if (i == pair * dvec) lse_out[pair] = empty ? ninf : m + fast_log(den);
 }
 
-// Element-wise path for any head_dim and 2-byte aligned pointers: one block per (token, head) pair.
+// Element-wise path for any head_dim and element-aligned pointers: one block per (token, head) pair.
 template <int DT>
-__global__ __launch_bounds__(256) void merge_attn_states_lse_kway_generic_kernel(uint16_t* __restrict__ v_out,
+__global__ __launch_bounds__(256) void merge_attn_states_lse_kway_generic_kernel(typename Storage<DT>::elem_t* __restrict__ v_out,
                                                                                  float* __restrict__ lse_out,
-                                                                                 const uint16_t* __restrict__ v_parts,
+                                                                                 const typename Storage<DT>::elem_t* __restrict__ v_parts,
                                                                                  const float* __restrict__ lse_parts,
                                                                                  uint32_t K, int64_t pairs, int64_t D)
 {

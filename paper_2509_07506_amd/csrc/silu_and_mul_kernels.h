@@ -1,6 +1,7 @@
 // silu_and_mul for gfx950 -- paper Table 1, Kernel 3: out = SiLU(x) (.) g, SiLU(z) = z / (1 + e^-z).
 //
-// The operator is a pure stream: 2 input vectors and 1 output vector per 8 results, no reuse.  The
+// The operator is a pure stream: 2 input vectors and 1 output vector per N results (N = 8 for the
+// 16-bit storage types, 4 for binary32), no reuse.  The
 // fast kernel gives every lane 16-byte accesses and `UNROLL` independent vector pairs so that enough
 // bytes are in flight per CU, and keeps the transcendental cost at one v_exp_f32 and one v_rcp_f32
 // per element (the reciprocal-multiply form of the paper's Fig. 5b; the plain divide of Fig. 5a
@@ -21,8 +22,8 @@ __device__ __forceinline__ float silu_fast(float x)
 // point uses it (LIBM = true below).
 __device__ __forceinline__ float silu_libm(float x) { return x / (1.0f + expf(-x)); }
 
-// Fast path: d % 8 == 0 and 16-byte aligned pointers.  Work is the flat list of output vectors
-// (dv = d/8 per row); a block owns BLOCK*UNROLL consecutive ones.  The row of the block's first vector
+// Fast path: d % N == 0 and 16-byte aligned pointers.  Work is the flat list of output vectors
+// (dv = d/N per row); a block owns BLOCK*UNROLL consecutive ones.  The row of the block's first vector
 // comes from one scalar fast division; lanes then step to the next row when they run past the end
 // of a row (at most a few steps because the host only takes this path when dv >= 32).
 // For output vector (t, j):  x = in[t*2dv + j], g = in[t*2dv + dv + j], out index = t*dv + j.
@@ -31,6 +32,7 @@ __global__ __launch_bounds__(BLOCK) void silu_and_mul_vec_kernel(u32x4* __restri
                                                                uint32_t total_vecs, uint32_t dv, FastDiv by_dv,
                                                                int log2_chunk)
 {
+    constexpr int N = Storage<DT>::kN;
     constexpr uint32_t kSpan = uint32_t(BLOCK) * UNROLL;
     const uint32_t first = xcd_chunked(blockIdx.x, log2_chunk) * kSpan;
     if (first >= total_vecs) return;  // grid padding
@@ -57,24 +59,26 @@ __global__ __launch_bounds__(BLOCK) void silu_and_mul_vec_kernel(u32x4* __restri
 #pragma unroll
     for (int k = 0; k < UNROLL; ++k) {
         if (oidx[k] < total_vecs) {
-            float x[8], g[8], o[8];
-            unpack8<DT>(xv[k], x);
-            unpack8<DT>(gv[k], g);
+            float x[N], g[N], o[N];
+            unpack_vec<DT>(xv[k], x);
+            unpack_vec<DT>(gv[k], g);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) o[e] = (LIBM ? silu_libm(x[e]) : silu_fast(x[e])) * g[e];
-            store_vec<NTS>(out + oidx[k], pack8<DT>(o));
+            for (int e = 0; e < N; ++e) o[e] = (LIBM ? silu_libm(x[e]) : silu_fast(x[e])) * g[e];
+            store_vec<NTS>(out + oidx[k], pack_vec<DT>(o));
         }
     }
 }
 
-// Element-wise path for any d and any 2-byte aligned pointers: one block walks one row at a time.
+// Element-wise path for any d and any element-aligned pointers: one block walks one row at a time.
 template <int DT>
-__global__ __launch_bounds__(256) void silu_and_mul_generic_kernel(uint16_t* __restrict__ out,
-                                                                   const uint16_t* __restrict__ in, int64_t T, int64_t d)
+__global__ __launch_bounds__(256) void silu_and_mul_generic_kernel(typename Storage<DT>::elem_t* __restrict__ out,
+                                                                   const typename Storage<DT>::elem_t* __restrict__ in,
+                                                                   int64_t T, int64_t d)
 {
+    typedef typename Storage<DT>::elem_t E;
     for (int64_t t = blockIdx.x; t < T; t += gridDim.x) {
-        const uint16_t* row = in + t * 2 * d;
-        uint16_t* orow = out + t * d;
+        const E* row = in + t * 2 * d;
+        E* orow = out + t * d;
         for (int64_t j = threadIdx.x; j < d; j += blockDim.x) {
             float x = Storage<DT>::widen(row[j]);
             float g = Storage<DT>::widen(row[d + j]);

@@ -5,15 +5,21 @@ import torch
 from oracle import reference_f64
 from tests.util import LSE_ATOL, TOL, assert_bits_equal, close_mask
 
-TORCH_DT = {"bf16": torch.bfloat16, "f16": torch.float16}
+TORCH_DT = {"bf16": torch.bfloat16, "f16": torch.float16, "f32": torch.float32}
+CANARY32 = 0x7BCD7BCD  # a finite binary32 pattern
 
 
 def to_dev(bits: np.ndarray, dt: str) -> torch.Tensor:
-    """uint16 bit patterns -> GPU tensor of the storage type (bit-preserving)."""
+    """Stored values (uint16 bit patterns, or float32 for "f32") -> GPU tensor of the storage type (bit-preserving)."""
+    if dt == "f32":
+        return torch.from_numpy(np.ascontiguousarray(bits, np.float32)).cuda()
     return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).view(TORCH_DT[dt]).cuda()
 
 
 def to_bits(t: torch.Tensor) -> np.ndarray:
+    """GPU tensor -> what to_dev took: uint16 bit patterns, or the float32 values of a float32 tensor."""
+    if t.dtype == torch.float32:
+        return t.detach().cpu().contiguous().numpy()
     return t.detach().cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
 
 
@@ -21,6 +27,11 @@ def padded(bits: np.ndarray, dt: str, pad: int = 64, offset_elems: int = 0, cana
     """Uploads `bits` into the middle of a larger canary-filled buffer.  Returns (view, whole).
     `offset_elems` shifts the view by that many elements to break 16-byte alignment."""
     n = bits.size
+    if dt == "f32":
+        whole = torch.full((pad + offset_elems + n + pad,), CANARY32, dtype=torch.int32).view(torch.float32).cuda()
+        view = whole[pad + offset_elems: pad + offset_elems + n].view(bits.shape)
+        view.copy_(torch.from_numpy(np.ascontiguousarray(bits, np.float32)))
+        return view, whole
     whole = torch.full((pad + offset_elems + n + pad,), canary, dtype=torch.int16).view(TORCH_DT[dt]).cuda()
     view = whole[pad + offset_elems: pad + offset_elems + n].view(bits.shape)
     view.copy_(torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).view(TORCH_DT[dt]).view(bits.shape))
@@ -28,19 +39,23 @@ def padded(bits: np.ndarray, dt: str, pad: int = 64, offset_elems: int = 0, cana
 
 
 def canaries_intact(whole: torch.Tensor, n: int, pad: int = 64, offset_elems: int = 0, canary: int = 0x7BCD) -> bool:
-    w = whole.view(torch.int16).cpu().numpy().view(np.uint16)
+    if whole.dtype == torch.float32:
+        w = whole.view(torch.int32).cpu().numpy().view(np.uint32)
+        canary = CANARY32
+    else:
+        w = whole.view(torch.int16).cpu().numpy().view(np.uint16)
     lo = w[: pad + offset_elems]
     hi = w[pad + offset_elems + n:]
     return bool(np.all(lo == canary) and np.all(hi == canary))
 
 
 def assert_storage_close(got_bits, ref_bits, dt, what, chunk=1 << 24):
-    """Tolerance comparison of two 16-bit tensors.  Elements with identical bits are equal by
-    definition; only the differing ones are widened (numpy, float64) and compared."""
+    """Tolerance comparison of two stored tensors (uint16 bit patterns, or float32 arrays for "f32").  Elements
+    with identical bits are equal by definition; only the differing ones are widened (numpy, float64) and compared."""
     rtol, atol = TOL[dt]
     g = np.asarray(got_bits).reshape(-1)
     r = np.asarray(ref_bits).reshape(-1)
-    assert g.shape == r.shape, (what, g.shape, r.shape)
+    assert g.shape == r.shape and g.dtype == r.dtype, (what, g.shape, r.shape, g.dtype, r.dtype)
     nbad = 0
     ndiff = 0
     first = None
@@ -68,7 +83,7 @@ def assert_storage_close_to_real(got_bits, ref_real, dt, what):
     rtol, atol = TOL[dt]
     gv = reference_f64.widen(np.asarray(got_bits), dt)
     # a real value at or beyond (largest finite + half an ulp) of the storage type is stored as +-inf
-    limit = 65520.0 if dt == "f16" else float.fromhex("0x1.ffp127")
+    limit = {"f16": 65520.0, "bf16": float.fromhex("0x1.ffp127"), "f32": float.fromhex("0x1.ffffffp127")}[dt]
     ref_real = np.asarray(ref_real, np.float64)
     ref_real = np.where(np.abs(ref_real) >= limit, np.sign(ref_real) * np.inf, ref_real)
     ok = close_mask(gv, ref_real, rtol, atol)

@@ -53,7 +53,7 @@ def test_rmsnorm_validation_order(A):
     a, b, c = 0x10000, 0x20000, 0x30000          # never dereferenced: every call below fails validation
     assert f(0, b, c, 1, 8, 1, 1e-6) == 1 and f(a, 0, c, 1, 8, 1, 1e-6) == 1 and f(a, b, 0, 1, 8, 1, 1e-6) == 1
     assert f(a, b, c, -1, 8, 1, 1e-6) == 2 and f(a, b, c, 1, 0, 1, 1e-6) == 2 and f(a, b, c, 1 << 40, 1 << 40, 1, 1e-6) == 2
-    assert f(a, b, c, 1, 8, 2, 1e-6) == 3 and f(a, b, c, 1, 8, -1, 1e-6) == 3
+    assert f(a, b, c, 1, 8, 3, 1e-6) == 3 and f(a, b, c, 1, 8, -1, 1e-6) == 3
     assert f(a, b, c, 1, 8, 1, -1e-6) == 4 and f(a, b, c, 1, 8, 1, float("nan")) == 4
     assert f(a + 1, b, c, 1, 8, 1, 1e-6) == 5
     assert f(a, a + 8, c, 1, 8, 1, 1e-6) == 6 and f(a, b, a + 2, 1, 8, 1, 1e-6) == 6
@@ -65,6 +65,10 @@ def test_rmsnorm_validation_order(A):
     assert f(a + 1, a + 3, c, 1, 8, 1, 1.0) == 5
     # T == 0 is fine and launches nothing (works without a GPU)
     assert f(a, b, c, 0, 8, 1, 1e-6) == 0
+    # binary32 storage (dtype 2): 4-byte alignment, and extents counted in 4-byte elements
+    assert f(a + 2, b, c, 1, 8, 2, 1e-6) == 5 and f(a + 2, b, c, 0, 8, 1, 1e-6) == 0
+    assert f(a, a + 16, c, 1, 8, 2, 1e-6) == 6 and f(a, a + 32, c, 0, 8, 2, 1e-6) == 0
+    assert f(a, b, b + 4 * 8 * 4 - 4, 4, 8, 2, 1e-6) == 6      # weight inside the last residual row
 
 
 def test_silu_validation(A):
@@ -76,6 +80,7 @@ def test_silu_validation(A):
     assert f(a + 1, b, 1, 8, 1) == 5
     assert f(a, a + 16, 4, 8, 1) == 6 and f(a + 32, a, 4, 8, 1) == 6
     assert f(a, b, 0, 8, 0) == 0
+    assert f(a + 2, b, 1, 8, 2) == 5 and f(a, a + 16, 1, 8, 2) == 6   # binary32: out spans 32 bytes
 
 
 def test_merge_validation(A):
@@ -93,6 +98,8 @@ def test_merge_validation(A):
     assert f(vo, la, va, la, vb, lb, 4, 2, 8, 1) == 6              # lse_out on lse_a
     assert f(vo, lo, va, la, vb, lb, 0, 2, 8, 1) == 0
     assert f(va, lo, va, la, vb, lb, 0, 2, 8, 1) == 0              # exact aliasing of v_out and v_a is allowed
+    assert f(vo + 2, lo, va, la, vb, lb, 1, 2, 8, 2) == 5          # binary32 storage: 4-byte alignment
+    assert f(vo, lo, vo + 32, la, vb, lb, 1, 2, 8, 2) == 6          # 64-byte tensors 32 bytes apart
 
 
 def test_stream_copy_validation(A):
@@ -127,6 +134,30 @@ def test_rmsnorm_plans(A):
     big = plan(1 << 23, 64)                                            # row loop beyond the grid limit
     assert big["grid"] == 1 << 21 and big["grid"] % (8 << big["log2_xcd_chunk"]) == 0
     assert A.astra_plan_fused_add_rmsnorm(-1, 8, True)[0] == 2
+
+
+def test_binary32_plans(A):
+    """Four elements per 16-byte vector: the same geometry rules in vectors, twice the vectors per row."""
+    F32 = A.ASTRA_F32
+    p = A.astra_plan_fused_add_rmsnorm(8192, 4096, True, dtype=F32)[1].as_dict()
+    q = A.astra_plan_fused_add_rmsnorm(8192, 8192, True, dtype=A.ASTRA_BF16)[1].as_dict()
+    assert p == q                                                     # 16 KiB rows either way
+    for T, H in [(1, 8192), (600, 8192), (64, 16384), (4099, 5120)]:
+        p = A.astra_plan_fused_add_rmsnorm(T, H, True, dtype=F32)[1].as_dict()
+        assert p["path"] == "vector" and p["block"] * p["vectors_per_lane"] * 4 >= H and p["block"] <= 1024
+    assert A.astra_plan_fused_add_rmsnorm(4, 4098, True, dtype=F32)[1].as_dict()["path"] == "generic"   # H % 4 != 0
+    assert A.astra_plan_fused_add_rmsnorm(4, 4100, True, dtype=F32)[1].as_dict()["path"] == "vector"    # H % 4 == 0
+    assert A.astra_plan_fused_add_rmsnorm(4, 32768, True, dtype=F32)[1].as_dict()["path"] == "generic"  # > 4096 vectors
+    s = A.astra_plan_silu_and_mul(4096, 14336, True, dtype=F32)[1].as_dict()
+    assert s["path"] == "vector" and s["grid"] * 256 >= 4096 * 14336 // 4
+    assert A.astra_plan_silu_and_mul(3, 1410, True, dtype=F32)[1].as_dict()["path"] == "generic"
+    assert A.astra_plan_silu_and_mul(3, 1412, True, dtype=F32)[1].as_dict()["path"] == "vector"
+    m = A.astra_plan_merge_attn_states_lse(4096, 32, 128, True, dtype=F32)[1].as_dict()
+    assert m["path"] == "vector" and m["grid"] * 256 == 4096 * 32 * 32
+    assert A.astra_plan_merge_attn_states_lse(3, 5, 6, True, dtype=F32)[1].as_dict()["path"] == "generic"
+    assert A.astra_plan_merge_attn_states_lse(3, 5, 4, True, dtype=F32)[1].as_dict()["path"] == "vector"
+    assert A.astra_plan_merge_attn_states_lse(3, 5, 4, True, dtype=7)[0] == 3
+    assert A.astra_plan_merge_attn_states_lse(-3, 5, 4, True, dtype=7)[0] == 2                          # shape before dtype
 
 
 def test_silu_and_merge_plans(A):

@@ -1,8 +1,11 @@
 """Comparison helpers shared by the CPU and GPU tests (no operator arithmetic here)."""
 import numpy as np
 
-# tolerances fixed by the benchmark statement: (rtol, atol) per storage type, and the lse bound
-TOL = {"bf16": (1.6e-2, 1e-2), "f16": (2e-3, 1e-3)}
+# tolerances fixed by the benchmark statement: (rtol, atol) per storage type, and the lse bound.  The
+# binary32 storage type is not part of the benchmark; its bound comes from the arithmetic: the order of the
+# row sum (about sqrt(H) * 2^-24 relative on the mean square) and the hardware exp2 / rcp / rsq (about one
+# ulp each, with |x| * log2(e) * 2^-24 relative on e^x from rounding the exponent argument, |x| <= 100).
+TOL = {"bf16": (1.6e-2, 1e-2), "f16": (2e-3, 1e-3), "f32": (1e-4, 1e-6)}
 LSE_ATOL = 1e-4
 
 

@@ -4,6 +4,8 @@ This module serves both the tests/benchmark of the HIP library and the CPU oracl
 the operators' arithmetic: it only draws random numbers (numpy ``Generator(PCG64)``) and rounds them
 to the 16-bit storage type with the library casts of numpy (fp16) and torch (bf16), both
 round-to-nearest-even.  16-bit tensors are returned as ``uint16`` bit patterns, scores as ``float32``.
+Storage type ``"f32"`` (a boundary convenience, no benchmark config uses it) returns the ``float32``
+draws themselves.
 
 Distribution readings (where a benchmark config says N(mu, v), v is the variance):
   fused_add_rmsnorm  x ~ N(0,1); r ~ N(0,1) or N(0,4) (sigma 2); w ~ N(1, 0.1) (sigma sqrt(0.1))
@@ -23,9 +25,14 @@ def _rng(config: int, case: int, seed: int = 0) -> np.random.Generator:
     return np.random.Generator(np.random.PCG64(np.random.SeedSequence([seed, config, case])))
 
 
+ELEM_BYTES = {"f16": 2, "bf16": 2, "f32": 4}
+
+
 def to_bits(x: np.ndarray, dtype: str) -> np.ndarray:
-    """float32 array -> uint16 bit patterns of `dtype` via a library cast (RNE)."""
+    """float32 array -> uint16 bit patterns of `dtype` via a library cast (RNE); "f32" returns the array itself."""
     x = np.ascontiguousarray(x, np.float32)
+    if dtype == "f32":
+        return x
     if dtype == "f16":
         return x.astype(np.float16).view(np.uint16)
     if dtype == "bf16":
@@ -37,7 +44,7 @@ def to_bits(x: np.ndarray, dtype: str) -> np.ndarray:
 
 def _normal_bits(rng, n: int, dtype: str, mean: float = 0.0, std: float = 1.0, outlier_p: float = 0.0,
                  outlier_scale: float = 1.0) -> np.ndarray:
-    out = np.empty(n, np.uint16)
+    out = np.empty(n, np.float32 if dtype == "f32" else np.uint16)
     for lo in range(0, n, _CHUNK):
         m = min(_CHUNK, n - lo)
         z = rng.standard_normal(m, dtype=np.float32)
@@ -104,13 +111,14 @@ class Case:
         raise ValueError(self.kernel)
 
     def algorithmic_bytes(self) -> int:
-        """Bytes the operator itself must move in one pass (16-bit elements, float32 scores)."""
+        """Bytes the operator itself must move in one pass (elements of the storage type, float32 scores)."""
         s = self.shape
+        e = ELEM_BYTES[self.dtype]
         if self.kernel == "rmsnorm":
-            return 4 * s["T"] * s["H"] * 2 + s["H"] * 2
+            return 4 * s["T"] * s["H"] * e + s["H"] * e
         if self.kernel == "silu":
-            return 3 * s["T"] * s["d"] * 2
-        return 3 * s["T"] * s["NH"] * s["D"] * 2 + 3 * s["T"] * s["NH"] * 4
+            return 3 * s["T"] * s["d"] * e
+        return 3 * s["T"] * s["NH"] * s["D"] * e + 3 * s["T"] * s["NH"] * 4
 
     def tokens(self) -> int:
         return self.shape["T"]
@@ -165,9 +173,24 @@ def _paper_shape_cases():
     return out
 
 
+def _f32_cases():
+    """Bandwidth-regime shapes with binary32 storage (not benchmark configs: they exist to measure the
+    boundary's convenience storage type); value recipes as in the 16-bit configs of the same operator."""
+    return [
+        Case("f32_rmsnorm_T16384_H8192", "rmsnorm", 6, 0, "f32", {"T": 16384, "H": 8192}, eps=1e-5, r_std=2.0),
+        Case("f32_rmsnorm_T32768_H4096", "rmsnorm", 6, 1, "f32", {"T": 32768, "H": 4096}, eps=1e-5, r_std=2.0),
+        Case("f32_silu_T4096_d14336", "silu", 6, 2, "f32", {"T": 4096, "d": 14336}),
+        Case("f32_merge_T4096_NH32_D128", "merge", 6, 3, "f32", {"T": 4096, "NH": 32, "D": 128}),
+    ]
+
+
 CASES = {c.name: c for c in _cases()}
 PAPER_SHAPE_CASES = {c.name: c for c in _paper_shape_cases()}
+F32_CASES = {c.name: c for c in _f32_cases()}
 
 
 def case(name: str) -> Case:
-    return CASES[name] if name in CASES else PAPER_SHAPE_CASES[name]
+    for table in (CASES, PAPER_SHAPE_CASES, F32_CASES):
+        if name in table:
+            return table[name]
+    raise KeyError(name)
