@@ -1,0 +1,314 @@
+// Stand-alone check of the C ABI from a plain C++ host program: no Python, no PyTorch.  Device memory and the
+// stream come from the HIP runtime directly (hipMalloc / hipStreamCreate), the operators from libastra_hip.so,
+// the expectations from the CPU oracle library (test infrastructure).  Bars as everywhere: residual of
+// fused_add_rmsnorm bit-exact; other 16-bit outputs within rtol 1.6e-2 / atol 1e-2 (bf16), 2e-3 / 1e-3 (fp16);
+// binary32 storage within 1e-4 / 1e-6; lse within 1e-4.
+//
+// Build (done by __graft_entry__.build()):
+//   hipcc -O2 -std=c++17 -I include tests/c_abi/check_abi.cpp -o tests/c_abi/check_abi
+//         -L paper_2509_07506_amd -lastra_hip -L oracle -loracle -Wl,-rpath,... (both directories)
+// Exit status 0 and a final line "c_abi: all checks passed" on success.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdint>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <vector>
+
+#include "astra.h"
+#include "astra_kway.h"
+
+extern "C" {
+// oracle/astra_oracle.c
+float oracle_bf16_to_f32(uint16_t h);
+float oracle_f16_to_f32(uint16_t h);
+uint16_t oracle_f32_to_bf16(float f);
+uint16_t oracle_f32_to_f16(float f);
+void oracle_fused_add_rmsnorm(uint16_t* input, uint16_t* residual, const uint16_t* weight, int64_t T, int64_t H, int dtype,
+                              float eps);
+void oracle_fused_add_rmsnorm_f32(const float* x, const float* r, const float* w, int64_t T, int64_t H, float eps,
+                                  float* s_out, float* y_out);
+void oracle_silu_and_mul(uint16_t* out, const uint16_t* in, int64_t T, int64_t d, int dtype);
+void oracle_silu_and_mul_f32(float* out, const float* in, int64_t T, int64_t d);
+void oracle_merge_attn_states_lse(uint16_t* v_out, float* lse_out, const uint16_t* v_a, const float* lse_a,
+                                  const uint16_t* v_b, const float* lse_b, int64_t T, int64_t NH, int64_t D, int dtype);
+void oracle_merge_attn_states_lse_f32(float* v_out, float* lse_out, const float* v_a, const float* lse_a, const float* v_b,
+                                      const float* lse_b, int64_t T, int64_t NH, int64_t D);
+void oracle_merge_attn_states_lse_kway(uint16_t* v_out, float* lse_out, const uint16_t* v_parts, const float* lse_parts,
+                                       int64_t K, int64_t P, int64_t D, int dtype);
+}
+
+namespace {
+
+int g_failures = 0;
+
+#define HIP_OK(call)                                                                                 \
+    do {                                                                                             \
+        hipError_t e_ = (call);                                                                      \
+        if (e_ != hipSuccess) {                                                                      \
+            std::fprintf(stderr, "c_abi: %s failed: %s\n", #call, hipGetErrorString(e_));            \
+            std::exit(2);                                                                            \
+        }                                                                                            \
+    } while (0)
+
+void expect(bool ok, const char* what)
+{
+    if (!ok) {
+        ++g_failures;
+        std::printf("c_abi: FAILED %s\n", what);
+    }
+    std::fflush(stdout);
+}
+
+// splitmix64 -> roughly normal values (sum of four uniforms, variance 1)
+struct Rng {
+    uint64_t s;
+    uint64_t next()
+    {
+        uint64_t z = (s += 0x9E3779B97F4A7C15ull);
+        z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+        z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+        return z ^ (z >> 31);
+    }
+    float uniform() { return (float)(next() >> 40) * (1.0f / 16777216.0f); }
+    float normalish() { return (uniform() + uniform() + uniform() + uniform() - 2.0f) * 1.7320508f; }
+};
+
+float widen(uint16_t h, int dt) { return dt == ASTRA_BF16 ? oracle_bf16_to_f32(h) : oracle_f16_to_f32(h); }
+uint16_t narrow(float f, int dt) { return dt == ASTRA_BF16 ? oracle_f32_to_bf16(f) : oracle_f32_to_f16(f); }
+
+struct Tol {
+    double rtol, atol;
+};
+Tol tol_of(int dt) { return dt == ASTRA_BF16 ? Tol{1.6e-2, 1e-2} : dt == ASTRA_F16 ? Tol{2e-3, 1e-3} : Tol{1e-4, 1e-6}; }
+
+bool close(double got, double ref, Tol t)
+{
+    if (std::isnan(got) || std::isnan(ref)) return std::isnan(got) && std::isnan(ref);
+    if (std::isinf(got) || std::isinf(ref)) return got == ref;
+    return std::fabs(got - ref) <= t.atol + t.rtol * std::fabs(ref);
+}
+
+template <class E>
+double value_of(E e, int dt);
+template <>
+double value_of<uint16_t>(uint16_t e, int dt) { return widen(e, dt); }
+template <>
+double value_of<float>(float e, int) { return e; }
+
+template <class E>
+size_t count_far(const std::vector<E>& got, const std::vector<E>& ref, int dt)
+{
+    size_t bad = 0;
+    for (size_t i = 0; i < got.size(); ++i)
+        if (std::memcmp(&got[i], &ref[i], sizeof(E)) != 0 && !close(value_of(got[i], dt), value_of(ref[i], dt), tol_of(dt))) ++bad;
+    return bad;
+}
+
+size_t count_far_lse(const std::vector<float>& got, const std::vector<float>& ref)
+{
+    size_t bad = 0;
+    for (size_t i = 0; i < got.size(); ++i)
+        if (!close(got[i], ref[i], Tol{0.0, 1e-4})) ++bad;
+    return bad;
+}
+
+template <class E>
+E make_elem(float f, int dt);
+template <>
+uint16_t make_elem<uint16_t>(float f, int dt) { return narrow(f, dt); }
+template <>
+float make_elem<float>(float f, int) { return f; }
+
+template <class E>
+struct DevBuf {
+    E* p = nullptr;
+    size_t n = 0;
+    explicit DevBuf(size_t n_) : n(n_) { HIP_OK(hipMalloc((void**)&p, (n ? n : 1) * sizeof(E))); }
+    ~DevBuf() { (void)hipFree(p); }
+    void upload(const std::vector<E>& h, hipStream_t s) { HIP_OK(hipMemcpyAsync(p, h.data(), n * sizeof(E), hipMemcpyHostToDevice, s)); }
+    std::vector<E> download(hipStream_t s)
+    {
+        std::vector<E> h(n);
+        HIP_OK(hipMemcpyAsync(h.data(), p, n * sizeof(E), hipMemcpyDeviceToHost, s));
+        HIP_OK(hipStreamSynchronize(s));
+        return h;
+    }
+};
+
+template <class E>
+void check_rmsnorm(int dt, int64_t T, int64_t H, float eps, hipStream_t s)
+{
+    Rng g{uint64_t(1000 + dt * 97 + T * 31 + H)};
+    std::vector<E> x(T * H), r(T * H), w(H);
+    for (auto& v : x) v = make_elem<E>(g.normalish(), dt);
+    for (auto& v : r) v = make_elem<E>(2.0f * g.normalish(), dt);
+    for (auto& v : w) v = make_elem<E>(1.0f + 0.3f * g.normalish(), dt);
+    DevBuf<E> dx(x.size()), dr(r.size()), dw(w.size());
+    dx.upload(x, s);
+    dr.upload(r, s);
+    dw.upload(w, s);
+    astra_status_t st = astra_fused_add_rmsnorm(dx.p, dr.p, dw.p, T, H, (astra_dtype_t)dt, eps, s);
+    std::vector<E> y = dx.download(s), res = dr.download(s);
+    std::vector<E> y_ref, res_ref;
+    if constexpr (sizeof(E) == 2) {
+        y_ref = x;
+        res_ref = r;
+        oracle_fused_add_rmsnorm((uint16_t*)y_ref.data(), (uint16_t*)res_ref.data(), (const uint16_t*)w.data(), T, H, dt, eps);
+    } else {
+        y_ref.resize(x.size());
+        res_ref.resize(x.size());
+        oracle_fused_add_rmsnorm_f32((const float*)x.data(), (const float*)r.data(), (const float*)w.data(), T, H, eps,
+                                     (float*)res_ref.data(), (float*)y_ref.data());
+    }
+    char what[160];
+    std::snprintf(what, sizeof what, "fused_add_rmsnorm dtype=%d T=%lld H=%lld", dt, (long long)T, (long long)H);
+    const bool ok = st == ASTRA_OK && std::memcmp(res.data(), res_ref.data(), res.size() * sizeof(E)) == 0 &&
+                    count_far(y, y_ref, dt) == 0;
+    expect(ok, what);
+    if (ok) std::printf("c_abi: ok %s (residual bit-exact)\n", what);
+}
+
+template <class E>
+void check_silu(int dt, int64_t T, int64_t d, hipStream_t s)
+{
+    Rng g{uint64_t(2000 + dt * 97 + T * 31 + d)};
+    std::vector<E> in(T * 2 * d);
+    for (auto& v : in) {
+        float f = g.normalish();
+        if (g.uniform() < 1e-3f) f *= 20.0f;
+        v = make_elem<E>(f, dt);
+    }
+    DevBuf<E> din(in.size()), dout(T * d);
+    din.upload(in, s);
+    astra_status_t st = astra_silu_and_mul(dout.p, din.p, T, d, (astra_dtype_t)dt, s);
+    std::vector<E> out = dout.download(s), ref(T * d);
+    if constexpr (sizeof(E) == 2) oracle_silu_and_mul((uint16_t*)ref.data(), (const uint16_t*)in.data(), T, d, dt);
+    else oracle_silu_and_mul_f32((float*)ref.data(), (const float*)in.data(), T, d);
+    char what[160];
+    std::snprintf(what, sizeof what, "silu_and_mul dtype=%d T=%lld d=%lld", dt, (long long)T, (long long)d);
+    const bool ok = st == ASTRA_OK && count_far(out, ref, dt) == 0;
+    expect(ok, what);
+    if (ok) std::printf("c_abi: ok %s\n", what);
+}
+
+std::vector<float> make_scores(Rng& g, size_t n)
+{
+    std::vector<float> s(n);
+    for (auto& v : s) v = g.uniform() < 0.05f ? -INFINITY : -5.0f + 20.0f * g.uniform();
+    return s;
+}
+
+template <class E>
+void check_merge(int dt, int64_t T, int64_t NH, int64_t D, hipStream_t s)
+{
+    Rng g{uint64_t(3000 + dt * 97 + T * 31 + NH * 7 + D)};
+    const size_t P = T * NH;
+    std::vector<E> va(P * D), vb(P * D);
+    for (auto& v : va) v = make_elem<E>(g.normalish(), dt);
+    for (auto& v : vb) v = make_elem<E>(g.normalish(), dt);
+    std::vector<float> la = make_scores(g, P), lb = make_scores(g, P);
+    DevBuf<E> dva(va.size()), dvb(vb.size()), dvo(va.size());
+    DevBuf<float> dla(P), dlb(P), dlo(P);
+    dva.upload(va, s);
+    dvb.upload(vb, s);
+    dla.upload(la, s);
+    dlb.upload(lb, s);
+    astra_status_t st = astra_merge_attn_states_lse(dvo.p, dlo.p, dva.p, dla.p, dvb.p, dlb.p, T, NH, D, (astra_dtype_t)dt, s);
+    std::vector<E> vo = dvo.download(s), vo_ref(va.size());
+    std::vector<float> lo = dlo.download(s), lo_ref(P);
+    if constexpr (sizeof(E) == 2)
+        oracle_merge_attn_states_lse((uint16_t*)vo_ref.data(), lo_ref.data(), (const uint16_t*)va.data(), la.data(),
+                                     (const uint16_t*)vb.data(), lb.data(), T, NH, D, dt);
+    else
+        oracle_merge_attn_states_lse_f32((float*)vo_ref.data(), lo_ref.data(), (const float*)va.data(), la.data(),
+                                         (const float*)vb.data(), lb.data(), T, NH, D);
+    char what[160];
+    std::snprintf(what, sizeof what, "merge_attn_states_lse dtype=%d T=%lld NH=%lld D=%lld", dt, (long long)T, (long long)NH,
+                  (long long)D);
+    bool ok = st == ASTRA_OK && count_far(vo, vo_ref, dt) == 0 && count_far_lse(lo, lo_ref) == 0;
+    expect(ok, what);
+    if (ok) std::printf("c_abi: ok %s\n", what);
+
+    if constexpr (sizeof(E) == 2) {
+        // the same two states through the K-way entry point (K = 2, parts stacked)
+        std::vector<uint16_t> parts(2 * P * D);
+        std::memcpy(parts.data(), va.data(), P * D * 2);
+        std::memcpy(parts.data() + P * D, vb.data(), P * D * 2);
+        std::vector<float> lparts(2 * P);
+        std::memcpy(lparts.data(), la.data(), P * 4);
+        std::memcpy(lparts.data() + P, lb.data(), P * 4);
+        DevBuf<uint16_t> dparts(parts.size());
+        DevBuf<float> dlparts(lparts.size());
+        dparts.upload(parts, s);
+        dlparts.upload(lparts, s);
+        st = astra_merge_attn_states_lse_kway(dvo.p, dlo.p, dparts.p, dlparts.p, 2, T, NH, D, (astra_dtype_t)dt, s);
+        std::vector<uint16_t> kv = dvo.download(s), kv_ref(P * D);
+        std::vector<float> kl = dlo.download(s), kl_ref(P);
+        oracle_merge_attn_states_lse_kway(kv_ref.data(), kl_ref.data(), parts.data(), lparts.data(), 2, (int64_t)P, D, dt);
+        std::snprintf(what, sizeof what, "merge_attn_states_lse_kway K=2 dtype=%d T=%lld NH=%lld D=%lld", dt, (long long)T,
+                      (long long)NH, (long long)D);
+        ok = st == ASTRA_OK && count_far(kv, kv_ref, dt) == 0 && count_far_lse(kl, kl_ref) == 0;
+        expect(ok, what);
+        if (ok) std::printf("c_abi: ok %s\n", what);
+    }
+}
+
+void check_errors(hipStream_t s)
+{
+    DevBuf<uint16_t> a(4096), b(4096), c(4096);
+    expect(astra_fused_add_rmsnorm(nullptr, b.p, c.p, 1, 8, ASTRA_F16, 1e-6f, s) == ASTRA_ERR_NULL, "null pointer status");
+    expect(astra_fused_add_rmsnorm(a.p, b.p, c.p, -1, 8, ASTRA_F16, 1e-6f, s) == ASTRA_ERR_SHAPE, "shape status");
+    expect(astra_fused_add_rmsnorm(a.p, b.p, c.p, 1, 8, (astra_dtype_t)9, 1e-6f, s) == ASTRA_ERR_DTYPE, "dtype status");
+    expect(astra_fused_add_rmsnorm(a.p, b.p, c.p, 1, 8, ASTRA_F16, -1.0f, s) == ASTRA_ERR_EPS, "eps status");
+    expect(astra_fused_add_rmsnorm((char*)a.p + 1, b.p, c.p, 1, 8, ASTRA_F16, 1e-6f, s) == ASTRA_ERR_ALIGN, "alignment status");
+    expect(astra_fused_add_rmsnorm(a.p, a.p + 4, c.p, 1, 8, ASTRA_F16, 1e-6f, s) == ASTRA_ERR_ALIAS, "alias status");
+    expect(astra_silu_and_mul(a.p, a.p + 8, 2, 8, ASTRA_BF16, s) == ASTRA_ERR_ALIAS, "silu alias status");
+    expect(astra_fused_add_rmsnorm(a.p, b.p, c.p, 0, 8, ASTRA_F16, 1e-6f, s) == ASTRA_OK, "T == 0 is a no-op");
+    expect(std::strcmp(astra_status_string(ASTRA_OK), "ok") == 0, "status string");
+    HIP_OK(hipStreamSynchronize(s));
+    std::printf("c_abi: ok error statuses\n");
+}
+
+}  // namespace
+
+int main()
+{
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || ndev < 1) {
+        std::fprintf(stderr, "c_abi: no HIP device\n");
+        return 2;
+    }
+    HIP_OK(hipSetDevice(0));
+    hipStream_t s;
+    HIP_OK(hipStreamCreate(&s));  // a stream of the default priority that is not the null stream
+
+    check_errors(s);
+    for (int dt : {ASTRA_F16, ASTRA_BF16}) {
+        check_rmsnorm<uint16_t>(dt, 5, 4096, 1e-6f, s);
+        check_rmsnorm<uint16_t>(dt, 300, 8192, 1e-5f, s);
+        check_rmsnorm<uint16_t>(dt, 17, 5120, 1e-5f, s);
+        check_rmsnorm<uint16_t>(dt, 3, 100, 1e-5f, s);      // element-wise path
+        check_rmsnorm<uint16_t>(dt, 1100, 2048, 1e-5f, s);   // XCD-aware launch order
+        check_silu<uint16_t>(dt, 7, 1408, s);
+        check_silu<uint16_t>(dt, 130, 11008, s);
+        check_silu<uint16_t>(dt, 3, 100, s);
+        check_merge<uint16_t>(dt, 33, 40, 128, s);
+        check_merge<uint16_t>(dt, 5, 7, 36, s);
+    }
+    check_rmsnorm<float>(ASTRA_F32, 40, 8192, 1e-5f, s);
+    check_rmsnorm<float>(ASTRA_F32, 3, 6, 1e-5f, s);
+    check_silu<float>(ASTRA_F32, 9, 1412, s);
+    check_merge<float>(ASTRA_F32, 33, 8, 64, s);
+
+    HIP_OK(hipStreamSynchronize(s));
+    HIP_OK(hipStreamDestroy(s));
+    if (g_failures) {
+        std::printf("c_abi: %d check(s) FAILED\n", g_failures);
+        return 1;
+    }
+    std::printf("c_abi: all checks passed\n");
+    return 0;
+}
