@@ -135,6 +135,35 @@ def _load_traffic():
     return {}
 
 
+def _cpu_model():
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return None
+
+
+def _device_info():
+    """What the runtime reports about the GPU; the memory figures put the published 8 TB/s peak in context."""
+    import torch
+
+    p = torch.cuda.get_device_properties(0)
+    info = {"name": p.name, "compute_units": p.multi_processor_count, "memory_GiB": round(p.total_memory / 2**30, 1),
+            "gcn_arch": getattr(p, "gcnArchName", None)}
+    import paper_2509_07506_amd as astra
+
+    st, clk, width = astra.astra_device_memory_info(0)
+    if st == 0 and clk and width:
+        info["memory_clock_MHz"] = round(clk / 1e3, 1)
+        info["memory_bus_bits"] = int(width)
+        # HBM3E moves four bits per pin and reported clock (8 Gb/s per pin at 2000 MHz)
+        info["hbm_GBs_at_4_bits_per_pin_clock"] = round(4 * clk * 1e3 * width / 8 / 1e9, 1)
+    return info
+
+
 def cpu_baseline(cases, datas):
     """The oracle as it stands, on this host: all usable cores on the full step (best of 3 after one
     warm-up), and one thread on the first eighth of the rows of each workload."""
@@ -170,7 +199,7 @@ def cpu_baseline(cases, datas):
             "seconds_per_step": round(t_all, 4),
             "single_thread": {"value": round(total_bytes / 8 / t_one / 1e9, 3), "unit": "GB/s",
                               "sample": "first eighth of the rows of each workload, best of 2"},
-            "host_cores_visible": cores}
+            "host_cores_visible": cores, "cpu_model": _cpu_model()}
 
 
 def run_step_bench(args):
@@ -269,6 +298,7 @@ def run_step_bench(args):
                      "frac": round(dom["achieved_GBs"] / HBM_PEAK_GBS, 4), "traffic": dom["traffic"],
                      "avg_launch_us": dom["avg_us"]},
         "kernels": per_kernel,
+        "device": _device_info(),
     }
     # context only, not a target: what the paper itself reports for these kernels (its Tables 2 and 4)
     out["paper_context"] = {

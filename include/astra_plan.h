@@ -43,6 +43,11 @@ astra_status_t astra_plan_merge_attn_states_lse(int64_t T, int64_t num_heads, in
  * of 8 * 2^log2_chunk.  log2_chunk outside [0, 8] returns `workgroup` unchanged. */
 uint32_t astra_plan_xcd_chunked(uint32_t workgroup, int log2_chunk);
 
+/* What the HIP runtime reports about device `device`'s memory system: memory clock in kHz and bus width in
+ * bits (HBM3E moves four bits per pin and reported clock: bandwidth = 4 * clock * width / 8).  The only function of this
+ * header that calls the runtime.  ASTRA_ERR_NULL for a NULL output, ASTRA_ERR_LAUNCH if the query fails. */
+astra_status_t astra_device_memory_info(int device, int* memory_clock_khz, int* memory_bus_bits);
+
 #ifdef __cplusplus
 }
 #endif

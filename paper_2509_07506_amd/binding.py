@@ -86,6 +86,8 @@ def load_library() -> ctypes.CDLL:
     L.astra_plan_fused_add_rmsnorm.argtypes = [i64, i64, i32, i32, pinfo]
     L.astra_plan_silu_and_mul.argtypes = [i64, i64, i32, i32, pinfo]
     L.astra_plan_merge_attn_states_lse.argtypes = [i64, i64, i64, i32, i32, pinfo]
+    L.astra_device_memory_info.argtypes = [i32, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]
+    L.astra_device_memory_info.restype = i32
     L.astra_plan_xcd_chunked.argtypes = [ctypes.c_uint32, i32]
     L.astra_plan_xcd_chunked.restype = ctypes.c_uint32
     for n in ("astra_fused_add_rmsnorm", "astra_silu_and_mul", "astra_merge_attn_states_lse", "astra_stream_copy",
@@ -163,6 +165,13 @@ def astra_plan_silu_and_mul(T, d, aligned16=True, dtype=ASTRA_BF16):
 
 def astra_plan_merge_attn_states_lse(T, num_heads, head_dim, aligned16=True, dtype=ASTRA_BF16):
     return _plan(load_library().astra_plan_merge_attn_states_lse, T, num_heads, head_dim, dtype, int(aligned16))
+
+
+def astra_device_memory_info(device: int = 0):
+    """(status, memory clock in kHz, bus width in bits) as the HIP runtime reports them."""
+    clk, width = ctypes.c_int(0), ctypes.c_int(0)
+    st = load_library().astra_device_memory_info(int(device), ctypes.byref(clk), ctypes.byref(width))
+    return st, clk.value, width.value
 
 
 def astra_plan_xcd_chunked(workgroup: int, log2_chunk: int) -> int:

@@ -599,6 +599,17 @@ astra_status_t astra_fused_add_rmsnorm_strided(void* y_out, int64_t y_stride, vo
     return after_launch();
 }
 
+astra_status_t astra_device_memory_info(int device, int* memory_clock_khz, int* memory_bus_bits)
+{
+    if (!memory_clock_khz || !memory_bus_bits) return ASTRA_ERR_NULL;
+    if (hipDeviceGetAttribute(memory_clock_khz, hipDeviceAttributeMemoryClockRate, device) != hipSuccess ||
+        hipDeviceGetAttribute(memory_bus_bits, hipDeviceAttributeMemoryBusWidth, device) != hipSuccess) {
+        (void)hipGetLastError();  // leave no sticky error behind for the next call
+        return ASTRA_ERR_LAUNCH;
+    }
+    return ASTRA_OK;
+}
+
 astra_status_t astra_stream_copy(void* dst, const void* src, int64_t nbytes, hipStream_t stream)
 {
     if (!dst || !src) return ASTRA_ERR_NULL;

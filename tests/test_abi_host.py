@@ -35,7 +35,7 @@ def test_every_declared_symbol_is_exported(A):
     declared = _declared_functions()
     assert {"astra_fused_add_rmsnorm", "astra_silu_and_mul", "astra_merge_attn_states_lse", "astra_status_string",
             "astra_stream_copy", "astra_plan_fused_add_rmsnorm", "astra_plan_silu_and_mul",
-            "astra_plan_merge_attn_states_lse", "astra_plan_xcd_chunked", "astra_merge_attn_states_lse_kway",
+            "astra_plan_merge_attn_states_lse", "astra_plan_xcd_chunked", "astra_device_memory_info", "astra_merge_attn_states_lse_kway",
             "astra_fused_add_rmsnorm_strided",
             "astra_ablation_fused_add_rmsnorm", "astra_ablation_silu_and_mul", "astra_ablation_merge_attn_states_lse"} <= set(declared)
     for name in declared:
