@@ -12,7 +12,13 @@ BINARY = os.path.join(HERE, "check_abi")
 
 
 def build() -> str:
-    """Compiles check_abi.cpp with hipcc (host code only; needs the two libraries to be built already)."""
+    """Compiles check_abi.cpp with hipcc (host code only) against the two libraries, building them first if absent."""
+    import oracle
+    from paper_2509_07506_amd import build as hip_build
+
+    oracle.build()
+    if not os.path.exists(hip_build.LIB):
+        hip_build.build()
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     cmd = [hipcc, "-O2", "-std=c++17", "-Wall", "-Wextra", "-I", os.path.join(ROOT, "include"), SOURCE, "-o", BINARY,
            "-L", os.path.join(ROOT, "paper_2509_07506_amd"), "-lastra_hip", "-L", os.path.join(ROOT, "oracle"), "-loracle",
