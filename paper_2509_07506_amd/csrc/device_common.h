@@ -38,6 +38,10 @@ __device__ __forceinline__ void store_vec(u32x4* p, u32x4 v)
     else *p = v;
 }
 
+// Waits until every global load and store this wave has issued so far has completed (s_waitcnt vmcnt(0);
+// the LDS / scalar and export counters are left alone).  Used to pace a wave's second store behind its first.
+__device__ __forceinline__ void wait_vector_memory() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+
 // ---------------------------------------------------------------------------------------------
 // storage types.  kN: elements per 16-byte vector; elem_t: the element as an integer or float word.
 // 16-bit types: unpack2 turns one dword holding two values into two floats (exact), pack2 turns two

@@ -13,8 +13,14 @@ namespace astra {
 
 // Fast path: H % N == 0, 16-byte aligned pointers, hv = H/N <= VPT * blockDim.x (VPT is 1, 2 or 4).
 // blockDim.x is a multiple of 64 and at most MAX_THREADS.  Lane `tid` owns vectors tid + k*blockDim.x.
-// A block walks rows r0, r0 + gridDim.x, ... (normally exactly one row), r0 = xcd_chunked(blockIdx.x).
-template <int DT, int VPT, int MAX_THREADS, bool NTL, bool NTS, bool LDS_TREE = false>
+// ROW_LOOP = false: one row per workgroup, row = xcd_chunked(blockIdx.x) (the grid covers all rows).
+// ROW_LOOP = true:  a workgroup walks rows r0, r0 + gridDim.x, ... (only for more rows than the grid limit).
+// The two are separate instantiations on purpose: inside a loop the compiler hoists the unpacking of the
+// row-independent weight in front of the loop, and with it the wait for the weight load, so no workgroup would
+// request its activations before the weight has arrived -- measured 1-2 % slower for H <= 5120.
+// WEIGHT_FIRST asks for exactly that order explicitly (the host uses it for full 1024-lane workgroups only).
+template <int DT, int VPT, int MAX_THREADS, bool NTL, bool NTS, bool LDS_TREE = false, bool ROW_LOOP = false,
+          bool WEIGHT_FIRST = false>
 __global__ __launch_bounds__(MAX_THREADS) void fused_add_rmsnorm_row_kernel(u32x4* input, u32x4* residual,
                                                                             const u32x4* __restrict__ weight,
                                                                             int64_t T, uint32_t hv, float inv_h, float eps,
@@ -28,15 +34,22 @@ __global__ __launch_bounds__(MAX_THREADS) void fused_add_rmsnorm_row_kernel(u32x
     if (first_row >= T) return;  // grid padding; uniform for the whole workgroup
     int parity = 0;
 
-    // the weight does not depend on the row: fetch it once (L2 resident, shared by all blocks)
+    // the weight does not depend on the row: requested first (L2 resident, shared by all blocks), used last
     u32x4 wv[VPT];
 #pragma unroll
     for (int k = 0; k < VPT; ++k) {
         const uint32_t v = threadIdx.x + k * blockDim.x;
         if (v < hv) wv[k] = weight[v];
     }
+    if constexpr (WEIGHT_FIRST) {
+        // make the weight's arrival a precondition of requesting the activations (the empty asm consumes the
+        // registers, so the wait for the load is placed here)
+#pragma unroll
+        for (int k = 0; k < VPT; ++k) asm volatile("" : "+v"(wv[k]));
+    }
 
-    for (int64_t row = first_row; row < T; row += gridDim.x, parity ^= 1) {
+    int64_t row = first_row;
+    do {
         u32x4* xrow = input + row * hv;
         u32x4* rrow = residual + row * hv;
         u32x4 xv[VPT], rv[VPT];
@@ -69,6 +82,10 @@ __global__ __launch_bounds__(MAX_THREADS) void fused_add_rmsnorm_row_kernel(u32x
 
         const float total = LDS_TREE ? block_sum_lds_tree(acc, tree) : block_sum(acc, partials[parity], nwaves);
         const float scale = fast_rsqrt(total * inv_h + eps);
+        // The wave issues its second store only after its residual store has completed: measured 4-5 % faster than
+        // letting the two stores overlap for workgroups below 1024 lanes (85 vs 80 % of peak at H = 4096), no
+        // difference at 1024.  The weight-first form (1024 lanes) measured best without it.
+        if constexpr (!WEIGHT_FIRST) wait_vector_memory();
 
 #pragma unroll
         for (int k = 0; k < VPT; ++k) {
@@ -81,7 +98,9 @@ __global__ __launch_bounds__(MAX_THREADS) void fused_add_rmsnorm_row_kernel(u32x
                 store_vec<NTS>(xrow + v, pack_vec<DT>(y));
             }
         }
-    }
+        row += gridDim.x;
+        parity ^= 1;
+    } while (ROW_LOOP && row < T);
 }
 
 // Element-wise path for any H and element-aligned pointers: two passes over the row.  The first pass
@@ -118,13 +137,13 @@ __global__ __launch_bounds__(256) void fused_add_rmsnorm_generic_kernel(typename
 // ---------------------------------------------------------------------------------------------
 // Row-strided, out-of-place form: separate input and output views, each with its own row stride (in
 // vectors for the fast kernel, in elements for the element-wise one).  Same structure as the kernels
-// above; y_out == x and r_out == r (same strides) is the in-place operator.
+// above (ROW_LOOP as there); y_out == x and r_out == r (same strides) is the in-place operator.
 
 struct RowViews {
     int64_t y_stride, r_out_stride, x_stride, r_stride;
 };
 
-template <int DT, int VPT, int MAX_THREADS, bool NTL, bool NTS>
+template <int DT, int VPT, int MAX_THREADS, bool NTL, bool NTS, bool ROW_LOOP>
 __global__ __launch_bounds__(MAX_THREADS) void fused_add_rmsnorm_strided_row_kernel(u32x4* y_out, u32x4* r_out,
                                                                                     const u32x4* x, const u32x4* r,
                                                                                     const u32x4* __restrict__ weight,
@@ -143,7 +162,8 @@ __global__ __launch_bounds__(MAX_THREADS) void fused_add_rmsnorm_strided_row_ker
         const uint32_t v = threadIdx.x + k * blockDim.x;
         if (v < hv) wv[k] = weight[v];
     }
-    for (int64_t row = first_row; row < T; row += gridDim.x, parity ^= 1) {
+    int64_t row = first_row;
+    do {
         const u32x4* xrow = x + row * sv.x_stride;
         const u32x4* rrow = r + row * sv.r_stride;
         u32x4 xv[VPT], rv[VPT];
@@ -185,7 +205,9 @@ __global__ __launch_bounds__(MAX_THREADS) void fused_add_rmsnorm_strided_row_ker
                 store_vec<NTS>(y_out + row * sv.y_stride + v, pack_vec<DT>(y));
             }
         }
-    }
+        row += gridDim.x;
+        parity ^= 1;
+    } while (ROW_LOOP && row < T);
 }
 
 template <int DT>

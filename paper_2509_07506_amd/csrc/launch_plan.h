@@ -21,6 +21,7 @@ constexpr bool kNTStore = true;   // and on the once-written outputs
 constexpr int kSiluUnroll = 1;
 constexpr int kMergeUnroll = 1;
 constexpr int kCopyUnroll = 1;
+constexpr int kWeightFirstBlock = 1024;  // rmsnorm: workgroup width that waits for the weight before its activations
 constexpr int kKwayGroup = 4;     // partitions folded per step of the streaming K-way merge
 
 constexpr int64_t kMaxVecIndex = int64_t(1) << 31;  // 32-bit vector indices with head-room for the tail
@@ -91,25 +92,22 @@ inline void for_dtype(astra_dtype_t dt, F&& f)
 inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
 
 // ---- fused_add_rmsnorm plan -----------------------------------------------------------------------
-// The row lives in registers: hv = H/N vectors (N = 16 / element size) spread over `block` lanes, `vpt` per lane.  Measured on
-// MI355X: rows of up to 1024 vectors (H <= 8192) are fastest with one vector per lane and the widest
-// workgroup, both for few rows (one dependent load-reduce-store chain per lane, the row's bytes
-// requested at once) and for many rows (finest interleaving of loads and stores; two 1024-lane
-// workgroups fill a CU).  Longer rows take four vectors per lane when there are many rows (several
-// mid-sized workgroups per CU beat one huge one by 1-2 %) and two when there are few (more lanes per
-// row).  The block is the smallest multiple of 64 lanes that covers the row.
+// The row lives in registers: hv = H/N vectors (N = 16 / element size) spread over `block` lanes, `vpt` per lane.
+// Measured on MI355X: the fewest vectors per lane that fit the row in one workgroup are fastest, for few rows
+// (one dependent load-reduce-store chain per lane, the row's bytes requested at once) and for many rows (finest
+// interleaving of loads and stores): one vector per lane up to 1024 vectors (H <= 8192 in 16 bits; 81-85 % of
+// peak), two up to 2048 (78-79 %; four per lane in half-sized workgroups measured 74-75 % there), four up to
+// 4096.  The block is the smallest multiple of 64 lanes that covers the row.
 struct RowPlan {
     int vpt;
     int block;
 };
 
-constexpr int64_t kFewRows = 512;  // fewer rows than this cannot fill the chip twice over
-
-inline bool rmsnorm_row_plan(int64_t T, int64_t hv, RowPlan* plan)
+inline bool rmsnorm_row_plan(int64_t hv, RowPlan* plan)
 {
     int vpt;
     if (hv <= 1024) vpt = 1;
-    else if (hv <= 2048 && T < kFewRows) vpt = 2;
+    else if (hv <= 2048) vpt = 2;
     else if (hv <= 4096) vpt = 4;
     else return false;
     plan->vpt = vpt;
@@ -125,7 +123,7 @@ inline astra_status_t plan_rmsnorm(int64_t T, int64_t H, int eb, bool aligned16,
     *info = astra_launch_info_t{ASTRA_PATH_NONE, 0, 0, 0, 0};
     if (T == 0) return ASTRA_OK;
     RowPlan rp;
-    if (aligned16 && H % ne == 0 && rmsnorm_row_plan(T, H / ne, &rp)) {
+    if (aligned16 && H % ne == 0 && rmsnorm_row_plan(H / ne, &rp)) {
         const int64_t rows = T < kMaxRowGrid ? T : kMaxRowGrid;
         const int lc = fit_chunk_log2(rows, kRowChunkBytesLog2 - floor_log2(H * eb), kRowChunkMinRows);
         *info = astra_launch_info_t{ASTRA_PATH_VECTOR, rp.block, rp.vpt, lc, T < kMaxRowGrid ? pad_grid(rows, lc) : rows};
