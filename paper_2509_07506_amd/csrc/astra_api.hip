@@ -39,23 +39,25 @@ void launch_rmsnorm_row(const astra_launch_info_t& li, void* input, void* residu
     const dim3 grid((uint32_t)li.grid), block(li.block);
     const float inv_h = 1.0f / (float)H;
     if (li.grid < T) {  // more rows than the grid limit: workgroups walk several rows
-        fused_add_rmsnorm_row_kernel<DT, VPT, MAXT, kNTLoad, kNTStore, LDS_TREE, true>
+        fused_add_rmsnorm_row_kernel<DT, VPT, MAXT, kNTLoad, kNTStore, LDS_TREE, true, kPaceNone>
             <<<grid, block, 0, stream>>>(in, res, w, T, hv, inv_h, eps, li.log2_xcd_chunk);
         return;
     }
-    if constexpr (VPT == 1 && !LDS_TREE) {
-        // Full 1024-lane workgroups (two per CU) measured 0.9 % faster when a new workgroup holds its activation
-        // requests back until its weight has arrived (82.7 vs 81.9 % of peak at H = 8192); every narrower
-        // workgroup measured 2-4 % slower that way.  Only for grids that keep the chip busy for several rounds:
-        // for a few rows it would just add the weight's latency to the one dependent chain.
-        if (li.block == kWeightFirstBlock && T >= kRowChunkMinRows) {
-            fused_add_rmsnorm_row_kernel<DT, 1, MAXT, kNTLoad, kNTStore, false, false, true>
+    // the ablation's reduction variant is paced like the tuned kernel, so that the two differ in the reduction only
+    switch (rmsnorm_pace(T, hv, VPT)) {
+        case kPaceStoreGap:
+            fused_add_rmsnorm_row_kernel<DT, VPT, MAXT, kNTLoad, kNTStore, LDS_TREE, false, kPaceStoreGap>
                 <<<grid, block, 0, stream>>>(in, res, w, T, hv, inv_h, eps, li.log2_xcd_chunk);
             return;
-        }
+        case kPaceWeightFirst | kPaceXBeforeR:
+            fused_add_rmsnorm_row_kernel<DT, VPT, MAXT, kNTLoad, kNTStore, LDS_TREE, false, kPaceWeightFirst | kPaceXBeforeR>
+                <<<grid, block, 0, stream>>>(in, res, w, T, hv, inv_h, eps, li.log2_xcd_chunk);
+            return;
+        default:
+            fused_add_rmsnorm_row_kernel<DT, VPT, MAXT, kNTLoad, kNTStore, LDS_TREE, false, kPaceNone>
+                <<<grid, block, 0, stream>>>(in, res, w, T, hv, inv_h, eps, li.log2_xcd_chunk);
+            return;
     }
-    fused_add_rmsnorm_row_kernel<DT, VPT, MAXT, kNTLoad, kNTStore, LDS_TREE, false>
-        <<<grid, block, 0, stream>>>(in, res, w, T, hv, inv_h, eps, li.log2_xcd_chunk);
 }
 
 template <int DT>

@@ -38,6 +38,9 @@ __device__ __forceinline__ void store_vec(u32x4* p, u32x4 v)
     else *p = v;
 }
 
+// Request pacing of the fused_add_rmsnorm row kernel (a template parameter there, chosen by the host's launch plan)
+enum : int { kPaceNone = 0, kPaceWeightFirst = 1, kPaceXBeforeR = 2, kPaceStoreGap = 4 };
+
 // Waits until every global load and store this wave has issued so far has completed (s_waitcnt vmcnt(0);
 // the LDS / scalar and export counters are left alone).  Used to pace a wave's second store behind its first.
 __device__ __forceinline__ void wait_vector_memory() { __builtin_amdgcn_s_waitcnt(0x0F70); }

@@ -13,14 +13,29 @@ namespace astra {
 
 // Fast path: H % N == 0, 16-byte aligned pointers, hv = H/N <= VPT * blockDim.x (VPT is 1, 2 or 4).
 // blockDim.x is a multiple of 64 and at most MAX_THREADS.  Lane `tid` owns vectors tid + k*blockDim.x.
+//
 // ROW_LOOP = false: one row per workgroup, row = xcd_chunked(blockIdx.x) (the grid covers all rows).
 // ROW_LOOP = true:  a workgroup walks rows r0, r0 + gridDim.x, ... (only for more rows than the grid limit).
-// The two are separate instantiations on purpose: inside a loop the compiler hoists the unpacking of the
-// row-independent weight in front of the loop, and with it the wait for the weight load, so no workgroup would
-// request its activations before the weight has arrived -- measured 1-2 % slower for H <= 5120.
-// WEIGHT_FIRST asks for exactly that order explicitly (the host uses it for full 1024-lane workgroups only).
+//
+// PACE selects when a wave issues its memory requests.  The arithmetic is the same for every value; what changes
+// is how the requests of the thousands of resident waves interleave at the memory controllers, which is worth
+// 1-4 % of the streaming rate on MI355X (table in the host's launch plan).  Bits (device_common.h):
+//   kPaceWeightFirst  the weight must have arrived before the activations are requested
+//   kPaceXBeforeR     the x vectors must have arrived before the r vectors are requested
+//   kPaceStoreGap     the residual store must have completed before the output store is issued
+// With PACE = 0 every request goes out as early as possible: the shortest dependent chain, used for few rows.
+// The empty asm statements (`arrive`) consume the loaded registers at a chosen point, which fixes where the wait
+// for that load is placed; no instruction is emitted for them.  All loads are consumed before the arithmetic
+// starts, so the compiler has no reason to add a wait of its own later on.
+template <int VPT>
+__device__ __forceinline__ void arrive(u32x4 (&v)[VPT])
+{
+#pragma unroll
+    for (int k = 0; k < VPT; ++k) asm volatile("" : "+v"(v[k]));
+}
+
 template <int DT, int VPT, int MAX_THREADS, bool NTL, bool NTS, bool LDS_TREE = false, bool ROW_LOOP = false,
-          bool WEIGHT_FIRST = false>
+          int PACE = kPaceNone>
 __global__ __launch_bounds__(MAX_THREADS) void fused_add_rmsnorm_row_kernel(u32x4* input, u32x4* residual,
                                                                             const u32x4* __restrict__ weight,
                                                                             int64_t T, uint32_t hv, float inv_h, float eps,
@@ -39,14 +54,10 @@ __global__ __launch_bounds__(MAX_THREADS) void fused_add_rmsnorm_row_kernel(u32x
 #pragma unroll
     for (int k = 0; k < VPT; ++k) {
         const uint32_t v = threadIdx.x + k * blockDim.x;
+        wv[k] = u32x4{0u, 0u, 0u, 0u};
         if (v < hv) wv[k] = weight[v];
     }
-    if constexpr (WEIGHT_FIRST) {
-        // make the weight's arrival a precondition of requesting the activations (the empty asm consumes the
-        // registers, so the wait for the load is placed here)
-#pragma unroll
-        for (int k = 0; k < VPT; ++k) asm volatile("" : "+v"(wv[k]));
-    }
+    if constexpr ((PACE & kPaceWeightFirst) != 0) arrive<VPT>(wv);
 
     int64_t row = first_row;
     do {
@@ -56,11 +67,20 @@ __global__ __launch_bounds__(MAX_THREADS) void fused_add_rmsnorm_row_kernel(u32x
 #pragma unroll
         for (int k = 0; k < VPT; ++k) {
             const uint32_t v = threadIdx.x + k * blockDim.x;
-            if (v < hv) {
-                xv[k] = load_vec<NTL>(xrow + v);
-                rv[k] = load_vec<NTL>(rrow + v);
-            }
+            xv[k] = u32x4{0u, 0u, 0u, 0u};
+            if (v < hv) xv[k] = load_vec<NTL>(xrow + v);
         }
+        if constexpr ((PACE & kPaceXBeforeR) != 0) arrive<VPT>(xv);
+#pragma unroll
+        for (int k = 0; k < VPT; ++k) {
+            const uint32_t v = threadIdx.x + k * blockDim.x;
+            rv[k] = u32x4{0u, 0u, 0u, 0u};
+            if (v < hv) rv[k] = load_vec<NTL>(rrow + v);
+        }
+        // everything requested so far is consumed here, so the only later wait is the optional store gap
+        arrive<VPT>(xv);
+        arrive<VPT>(rv);
+        arrive<VPT>(wv);
 
         float s[VPT][N];
         float acc = 0.0f;
@@ -82,10 +102,7 @@ __global__ __launch_bounds__(MAX_THREADS) void fused_add_rmsnorm_row_kernel(u32x
 
         const float total = LDS_TREE ? block_sum_lds_tree(acc, tree) : block_sum(acc, partials[parity], nwaves);
         const float scale = fast_rsqrt(total * inv_h + eps);
-        // The wave issues its second store only after its residual store has completed: measured 4-5 % faster than
-        // letting the two stores overlap for workgroups below 1024 lanes (85 vs 80 % of peak at H = 4096), no
-        // difference at 1024.  The weight-first form (1024 lanes) measured best without it.
-        if constexpr (!WEIGHT_FIRST) wait_vector_memory();
+        if constexpr ((PACE & kPaceStoreGap) != 0) wait_vector_memory();
 
 #pragma unroll
         for (int k = 0; k < VPT; ++k) {

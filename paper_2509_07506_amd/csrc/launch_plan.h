@@ -21,7 +21,6 @@ constexpr bool kNTStore = true;   // and on the once-written outputs
 constexpr int kSiluUnroll = 1;
 constexpr int kMergeUnroll = 1;
 constexpr int kCopyUnroll = 1;
-constexpr int kWeightFirstBlock = 1024;  // rmsnorm: workgroup width that waits for the weight before its activations
 constexpr int kKwayGroup = 4;     // partitions folded per step of the streaming K-way merge
 
 constexpr int64_t kMaxVecIndex = int64_t(1) << 31;  // 32-bit vector indices with head-room for the tail
@@ -113,6 +112,26 @@ inline bool rmsnorm_row_plan(int64_t hv, RowPlan* plan)
     plan->vpt = vpt;
     plan->block = round_up((int)((hv + vpt - 1) / vpt), kWave);
     return true;
+}
+
+// When the waves of the row kernel issue their requests (fused_add_rmsnorm_kernels.h, PACE).  Few rows: nothing is
+// held back (the shortest dependent chain).  Streaming grids, measured on MI355X with T*H = 2^28 16-bit elements
+// (% of the 8 TB/s peak; "gap" = output store held until the residual store has completed, "w,x" = weight, then x,
+// then r requested one after the other; none / gap / w,x):
+//   one vector per lane    H=512 81.9/84.1/83.8   1024 81.5/83.0/82.7  1536 78.8/80.8/81.4  2048 81.5/82.5/83.6
+//                          2560 81.4/82.6/81.0    3072 80.0/80.6/80.2  4096 79.8/84.8/83.9  5120 83.1/83.2/75.6
+//                          6144 81.7/82.2/79.4    7168 82.3/81.8/81.4  8192 81.7/81.9/82.9
+//   two vectors per lane   10240 78.9/79.5/80.6   11008 78.7/78.5/79.0  12288 79.8/79.4/80.0  14336 79.0/79.0/80.3
+//                          16384 77.1/77.2/78.0
+//   four vectors per lane  20480 76.0/75.8/76.3   28672 76.0/76.2/71.1  32768 79.5/79.6/76.8
+// "gap" is never far from the best and has no bad case, so it is the default; "w,x" is taken where it measured
+// better: rows of 256 or 1024 vectors (4 KiB, 16 KiB) and all two-vector rows.  It is not used elsewhere because
+// it can lose 8 % (H = 5120).
+inline int rmsnorm_pace(int64_t T, int64_t hv, int vpt)
+{
+    if (T < kRowChunkMinRows) return kPaceNone;
+    if (vpt == 2 || (vpt == 1 && (hv == 256 || hv == 1024))) return kPaceWeightFirst | kPaceXBeforeR;
+    return kPaceStoreGap;
 }
 
 inline astra_status_t plan_rmsnorm(int64_t T, int64_t H, int eb, bool aligned16, astra_launch_info_t* info)
