@@ -135,6 +135,16 @@ def test_rmsnorm_tile_shapes(A, T, H, dt):
     check_rmsnorm(A, x, r, w, 1e-5, dt, f"rmsnorm T={T} H={H} {dt}")
 
 
+@pytest.mark.parametrize("T,H,dt", [(1100, 2048, "bf16"), (1030, 1032, "f16"), (1024, 8192, "f16"), (1025, 11008, "bf16"),
+                                    (1024, 16384, "f16"), (1030, 28672, "bf16"), (1100, 20000, "f16"), (2050, 512, "bf16")])
+def test_rmsnorm_streaming_grids(A, T, H, dt):
+    """From 1024 rows on the row kernel paces its requests (which wait goes where depends on the row length and on
+    the vectors per lane); the results must not depend on it."""
+    _say(f"[parity] rmsnorm streaming T={T} H={H} {dt} plan={A.astra_plan_fused_add_rmsnorm(T, H, True)[1].as_dict()}")
+    x, r, w = workloads.rmsnorm_inputs(T, H, dt, np.random.default_rng([11, T, H]), r_std=2.0)
+    check_rmsnorm(A, x, r, w, 1e-5, dt, f"rmsnorm T={T} H={H} {dt}")
+
+
 @pytest.mark.parametrize("dt", ["bf16", "f16"])
 @pytest.mark.parametrize("T,d", [(1, 256), (3, 264), (2, 512), (7, 1000), (33, 2048), (5, 4096), (19, 5120), (2, 12288),
                                  (1, 14336), (129, 3584)])
