@@ -26,7 +26,18 @@ typedef struct {
     int32_t vectors_per_lane; /* 16-byte vectors each lane keeps in flight (0 on the generic path) */
     int32_t log2_xcd_chunk;   /* workgroups an XCD runs back to back cover 2^this consecutive work units */
     int64_t grid;             /* workgroups launched (padded to a multiple of 8 * 2^log2_xcd_chunk) */
+    int32_t pace;             /* fused_add_rmsnorm fast path only: ASTRA_PACE_* bits, when a wave issues its requests */
+    int32_t reserved;         /* 0 */
 } astra_launch_info_t;
+
+/* Request pacing of the fused_add_rmsnorm row kernel.  Same arithmetic and bytes for every value; the order in time of
+ * a wave's requests changes the streaming rate by a few per cent, so the library picks it per shape from measurements. */
+enum {
+    ASTRA_PACE_NONE = 0,         /* every request as early as possible (few rows: shortest dependent chain) */
+    ASTRA_PACE_WEIGHT_FIRST = 1, /* the weight has arrived before the activations are requested */
+    ASTRA_PACE_X_BEFORE_R = 2,   /* x has arrived before r is requested */
+    ASTRA_PACE_STORE_GAP = 4     /* the residual store has completed before the output store is issued */
+};
 
 /* `dtype` is the storage type of the call, `aligned16` tells whether every tensor pointer of the call is
  * 16-byte aligned (non-zero = yes).  Each function validates like its operator does (ASTRA_ERR_NULL for

@@ -44,7 +44,7 @@ void launch_rmsnorm_row(const astra_launch_info_t& li, void* input, void* residu
         return;
     }
     // the ablation's reduction variant is paced like the tuned kernel, so that the two differ in the reduction only
-    switch (rmsnorm_pace(T, hv, VPT)) {
+    switch (li.pace) {
         case kPaceStoreGap:
             fused_add_rmsnorm_row_kernel<DT, VPT, MAXT, kNTLoad, kNTStore, LDS_TREE, false, kPaceStoreGap>
                 <<<grid, block, 0, stream>>>(in, res, w, T, hv, inv_h, eps, li.log2_xcd_chunk);

@@ -38,7 +38,8 @@ __device__ __forceinline__ void store_vec(u32x4* p, u32x4 v)
     else *p = v;
 }
 
-// Request pacing of the fused_add_rmsnorm row kernel (a template parameter there, chosen by the host's launch plan)
+// Request pacing of the fused_add_rmsnorm row kernel (a template parameter there, chosen by the host's launch plan;
+// the values are those of ASTRA_PACE_* in include/astra_plan.h)
 enum : int { kPaceNone = 0, kPaceWeightFirst = 1, kPaceXBeforeR = 2, kPaceStoreGap = 4 };
 
 // Waits until every global load and store this wave has issued so far has completed (s_waitcnt vmcnt(0);

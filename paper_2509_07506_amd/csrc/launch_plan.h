@@ -139,15 +139,16 @@ inline astra_status_t plan_rmsnorm(int64_t T, int64_t H, int eb, bool aligned16,
     const int64_t ne = kVecBytes / eb;  // elements per 16-byte vector
     int64_t n;
     if (T < 0 || H <= 0 || mul_overflows(T, H, &n) || n > std::numeric_limits<int64_t>::max() / 4) return ASTRA_ERR_SHAPE;
-    *info = astra_launch_info_t{ASTRA_PATH_NONE, 0, 0, 0, 0};
+    *info = astra_launch_info_t{ASTRA_PATH_NONE, 0, 0, 0, 0, 0, 0};
     if (T == 0) return ASTRA_OK;
     RowPlan rp;
     if (aligned16 && H % ne == 0 && rmsnorm_row_plan(H / ne, &rp)) {
         const int64_t rows = T < kMaxRowGrid ? T : kMaxRowGrid;
         const int lc = fit_chunk_log2(rows, kRowChunkBytesLog2 - floor_log2(H * eb), kRowChunkMinRows);
-        *info = astra_launch_info_t{ASTRA_PATH_VECTOR, rp.block, rp.vpt, lc, T < kMaxRowGrid ? pad_grid(rows, lc) : rows};
+        const int pace = T < kMaxRowGrid ? rmsnorm_pace(T, H / ne, rp.vpt) : kPaceNone;  // the row-loop kernel is not paced
+        *info = astra_launch_info_t{ASTRA_PATH_VECTOR, rp.block, rp.vpt, lc, T < kMaxRowGrid ? pad_grid(rows, lc) : rows, pace, 0};
     } else {
-        *info = astra_launch_info_t{ASTRA_PATH_GENERIC, 256, 0, 0, T < kMaxGenericGrid ? T : kMaxGenericGrid};
+        *info = astra_launch_info_t{ASTRA_PATH_GENERIC, 256, 0, 0, T < kMaxGenericGrid ? T : kMaxGenericGrid, 0, 0};
     }
     return ASTRA_OK;
 }
@@ -159,7 +160,7 @@ inline astra_status_t plan_silu(int64_t T, int64_t d, int eb, bool aligned16, as
     if (T < 0 || d <= 0 || mul_overflows(d, 2, &two_d) || mul_overflows(T, two_d, &n) ||
         n > std::numeric_limits<int64_t>::max() / 4)
         return ASTRA_ERR_SHAPE;
-    *info = astra_launch_info_t{ASTRA_PATH_NONE, 0, 0, 0, 0};
+    *info = astra_launch_info_t{ASTRA_PATH_NONE, 0, 0, 0, 0, 0, 0};
     if (T == 0) return ASTRA_OK;
     const int64_t dv = d / ne;
     // the input holds 2*T*dv vectors and is indexed with 32 bits
@@ -167,9 +168,9 @@ inline astra_status_t plan_silu(int64_t T, int64_t d, int eb, bool aligned16, as
         const int64_t span = 256 * kSiluUnroll;
         const int64_t blocks = (T * dv + span - 1) / span;
         const int lc = fit_chunk_log2(blocks, kFlatChunkLog2, kFlatChunkMinBlocks);
-        *info = astra_launch_info_t{ASTRA_PATH_VECTOR, 256, kSiluUnroll, lc, pad_grid(blocks, lc)};
+        *info = astra_launch_info_t{ASTRA_PATH_VECTOR, 256, kSiluUnroll, lc, pad_grid(blocks, lc), 0, 0};
     } else {
-        *info = astra_launch_info_t{ASTRA_PATH_GENERIC, 256, 0, 0, T < kMaxGenericGrid ? T : kMaxGenericGrid};
+        *info = astra_launch_info_t{ASTRA_PATH_GENERIC, 256, 0, 0, T < kMaxGenericGrid ? T : kMaxGenericGrid, 0, 0};
     }
     return ASTRA_OK;
 }
@@ -181,16 +182,16 @@ inline astra_status_t plan_merge(int64_t T, int64_t NH, int64_t D, int eb, bool 
     if (T < 0 || NH <= 0 || D <= 0 || mul_overflows(T, NH, &pairs) || mul_overflows(pairs, D, &n) ||
         n > std::numeric_limits<int64_t>::max() / 4)
         return ASTRA_ERR_SHAPE;
-    *info = astra_launch_info_t{ASTRA_PATH_NONE, 0, 0, 0, 0};
+    *info = astra_launch_info_t{ASTRA_PATH_NONE, 0, 0, 0, 0, 0, 0};
     if (T == 0) return ASTRA_OK;
     const int64_t dvec = D / ne;
     if (aligned16 && D % ne == 0 && pairs * dvec <= kMaxVecIndex) {
         const int64_t span = 256 * kMergeUnroll;
         const int64_t blocks = (pairs * dvec + span - 1) / span;
         const int lc = fit_chunk_log2(blocks, kFlatChunkLog2, kFlatChunkMinBlocks);
-        *info = astra_launch_info_t{ASTRA_PATH_VECTOR, 256, kMergeUnroll, lc, pad_grid(blocks, lc)};
+        *info = astra_launch_info_t{ASTRA_PATH_VECTOR, 256, kMergeUnroll, lc, pad_grid(blocks, lc), 0, 0};
     } else {
-        *info = astra_launch_info_t{ASTRA_PATH_GENERIC, 256, 0, 0, pairs < kMaxGenericGrid ? pairs : kMaxGenericGrid};
+        *info = astra_launch_info_t{ASTRA_PATH_GENERIC, 256, 0, 0, pairs < kMaxGenericGrid ? pairs : kMaxGenericGrid, 0, 0};
     }
     return ASTRA_OK;
 }

@@ -116,8 +116,10 @@ def test_rmsnorm_plans(A):
 
     assert plan(0, 4096)["path"] == "none"
     for T in (1, 8):                          # decode: widest block, one vector per lane, plain launch order
-        assert plan(T, 8192) == {"path": "vector", "block": 1024, "vectors_per_lane": 1, "log2_xcd_chunk": 0, "grid": T}
-    assert plan(16, 4096) == {"path": "vector", "block": 512, "vectors_per_lane": 1, "log2_xcd_chunk": 0, "grid": 16}
+        assert plan(T, 8192) == {"path": "vector", "block": 1024, "vectors_per_lane": 1, "log2_xcd_chunk": 0, "grid": T,
+                                 "pace": 0}
+    assert plan(16, 4096) == {"path": "vector", "block": 512, "vectors_per_lane": 1, "log2_xcd_chunk": 0, "grid": 16,
+                              "pace": 0}
     for T, H in [(8192, 8192), (32768, 8192), (4099, 5120), (4099, 7168), (1024, 4096), (512, 14336), (128, 11008),
                  (64, 8192), (257, 5120)]:
         p = plan(T, H)
@@ -134,6 +136,14 @@ def test_rmsnorm_plans(A):
     big = plan(1 << 23, 64)                                            # row loop beyond the grid limit
     assert big["grid"] == 1 << 21 and big["grid"] % (8 << big["log2_xcd_chunk"]) == 0
     assert A.astra_plan_fused_add_rmsnorm(-1, 8, True)[0] == 2
+    # request pacing: none for few rows and for the row-loop kernel, "store gap" (4) by default on streaming grids,
+    # weight-then-x-then-r (1 | 2) for 4 KiB / 16 KiB rows and for two-vector rows
+    assert plan(1023, 8192)["pace"] == 0 and big["pace"] == 0
+    assert plan(32768, 8192)["pace"] == 3 and plan(32768, 2048)["pace"] == 3 and plan(4096, 11008)["pace"] == 3
+    assert plan(32768, 4096)["pace"] == 4 and plan(4099, 5120)["pace"] == 4 and plan(2048, 28672)["pace"] == 4
+    assert plan(2048, 11008)["vectors_per_lane"] == 2 and plan(2048, 28672)["vectors_per_lane"] == 4
+    assert A.astra_plan_fused_add_rmsnorm(32768, 4096, True, dtype=A.ASTRA_F32)[1].as_dict()["pace"] == 3   # 16 KiB rows
+    assert A.astra_plan_silu_and_mul(4096, 14336, True)[1].as_dict()["pace"] == 0
 
 
 def test_binary32_plans(A):
