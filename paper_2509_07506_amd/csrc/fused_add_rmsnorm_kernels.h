@@ -2,9 +2,9 @@
 //   y = (x + r) / sqrt(||x + r||^2 / H + eps) (.) w,  input <- y, residual <- x + r (both in place).
 //
 // One pass over HBM: a workgroup holds a whole row of binary32 sums in registers (VPT vectors of N = 8
-// 16-bit or 4 binary32 elements per lane), so x and r are read once and each written once.  The sum of squares is reduced inside
-// each wave with DPP (registers only) and across waves through one LDS float per wave and a single
-// barrier -- the register-first reduction of the paper's Fig. 3b, on 64-lane waves.
+// 16-bit or 4 binary32 elements per lane), so x and r are read once and each written once.  The sum of
+// squares is reduced inside each wave with DPP (registers only) and across waves through one LDS float
+// per wave and a single barrier -- the register-first reduction of the paper's Fig. 3b, on 64-lane waves.
 #pragma once
 
 #include "device_common.h"
@@ -16,6 +16,7 @@ namespace astra {
 //
 // ROW_LOOP = false: one row per workgroup, row = xcd_chunked(blockIdx.x) (the grid covers all rows).
 // ROW_LOOP = true:  a workgroup walks rows r0, r0 + gridDim.x, ... (only for more rows than the grid limit).
+// They are separate instantiations so that the common single-row form carries no loop bookkeeping.
 //
 // PACE selects when a wave issues its memory requests.  The arithmetic is the same for every value; what changes
 // is how the requests of the thousands of resident waves interleave at the memory controllers, which is worth
