@@ -45,6 +45,8 @@ def test_rmsnorm_random_shapes(A):
     rng = np.random.default_rng(9001)
     for i in range(N_CASES):
         T, H = int(rng.integers(1, 70)), _row_len(rng, 20000)
+        if i % 4 == 3:
+            T = int(rng.integers(1024, 1300))      # streaming grids: the paced forms of the row kernel
         dt = _pick(rng, ["bf16", "f16"])
         eps = float(_pick(rng, [0.0, 1e-6, 1e-5, 1e-2]))
         print(f"[random] rmsnorm #{i} T={T} H={H} {dt} eps={eps}", flush=True)
