@@ -623,6 +623,27 @@ def run_ceiling(args):
     us = e0.elapsed_time(e1) * 1e3 / reps
     print(json.dumps({"case": "stream_copy_512MiB", "cache": "cold", "bytes": 2 * n, "batch_avg_us": round(us, 2),
                       "GBs": round(2 * n / us / 1e3, 1), "frac_of_peak": round(2 * n / us / 1e3 / HBM_PEAK_GBS, 4)}), flush=True)
+    # reference points from the vendor stack on the same buffers: the runtime's device-to-device copy (what
+    # Tensor.copy_ issues for a dense tensor), PyTorch's elementwise add (2 reads, 1 write) and fill (write only)
+    def timed(fn, nbytes, name):
+        for k in range(warm):
+            fn(k)
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(stream)
+        for k in range(reps):
+            fn(k)
+        b.record(stream)
+        torch.cuda.synchronize()
+        t = a.elapsed_time(b) * 1e3 / reps
+        print(json.dumps({"case": name, "cache": "cold", "bytes": nbytes, "batch_avg_us": round(t, 2),
+                          "GBs": round(nbytes / t / 1e3, 1), "frac_of_peak": round(nbytes / t / 1e3 / HBM_PEAK_GBS, 4)}), flush=True)
+
+    timed(lambda k: dst[k & 1].copy_(src[k & 1]), 2 * n, "vendor_copy_512MiB (Tensor.copy_)")
+    s16 = [t.view(torch.bfloat16) for t in src]
+    d16 = [t.view(torch.bfloat16) for t in dst]
+    timed(lambda k: torch.add(s16[0], s16[1], out=d16[k & 1]), 3 * n, "vendor_add_512MiB (torch.add, bf16)")
+    timed(lambda k: dst[k & 1].fill_(1), n, "vendor_fill_512MiB (Tensor.fill_)")
 
 
 def main():
