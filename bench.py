@@ -646,6 +646,77 @@ def run_ceiling(args):
     timed(lambda k: dst[k & 1].fill_(1), n, "vendor_fill_512MiB (Tensor.fill_)")
 
 
+def run_vs_eager(args):
+    """Context, not parity and not the headline: the three step workloads through this library and through the same
+    operators written with plain PyTorch tensor ops (binary32 arithmetic on bf16 storage, several kernels and
+    temporaries each) -- what a framework does without a fused kernel.  The paper's own comparison is against SGLang's
+    hand-written CUDA kernels, which are not available here."""
+    import torch
+    import torch.nn.functional as F
+
+    import paper_2509_07506_amd as astra
+    import workloads
+
+    astra.load_library()
+    torch.cuda.set_device(0)
+    stream = torch.cuda.current_stream()
+    sh = stream.cuda_stream
+
+    def timed(fn, reps=30, warm=5):
+        for _ in range(warm):
+            fn()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(stream)
+        for _ in range(reps):
+            fn()
+        b.record(stream)
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) * 1e3 / reps
+
+    for name in STEP_CASES:
+        c = workloads.case(name)
+        data = c.generate()
+        L = Launcher(astra, c, data, 1)
+        t_lib = timed(lambda: L.launch(sh))
+        if c.kernel == "rmsnorm":
+            x, r, w = (_to_dev(a, c.dtype) for a in data)
+            wf = w.float()
+
+            def eager():
+                s = x.float() + r.float()
+                r.copy_(s)
+                x.copy_(s * torch.rsqrt(s.pow(2).mean(-1, keepdim=True) + c.eps) * wf)
+        elif c.kernel == "silu":
+            a = _to_dev(data[0], c.dtype)
+            d = c.shape["d"]
+            out = torch.empty((c.shape["T"], d), dtype=a.dtype, device="cuda")
+
+            def eager():
+                out.copy_(F.silu(a[:, :d].float()) * a[:, d:].float())
+        else:
+            va, vb = _to_dev(data[0], c.dtype), _to_dev(data[2], c.dtype)
+            la, lb = torch.from_numpy(data[1]).cuda(), torch.from_numpy(data[3]).cuda()
+            vo, lo = torch.empty_like(va), torch.empty_like(la)
+
+            def eager():
+                m = torch.maximum(la, lb)
+                m0 = torch.where(torch.isneginf(m), torch.zeros_like(m), m)
+                ea, eb = torch.exp(la - m0), torch.exp(lb - m0)
+                den = ea + eb
+                safe = torch.where(den == 0, torch.ones_like(den), den)
+                vo.copy_((ea / safe).unsqueeze(-1) * va.float() + (eb / safe).unsqueeze(-1) * vb.float())
+                lo.copy_(torch.where(den == 0, m, m0 + torch.log(safe)))
+        t_eager = timed(eager)
+        b = c.algorithmic_bytes()
+        print(json.dumps({"case": name, "library_us": round(t_lib, 2), "library_GBs": round(b / t_lib / 1e3, 1),
+                          "pytorch_eager_us": round(t_eager, 2),
+                          "pytorch_eager_GBs_on_algorithmic_bytes": round(b / t_eager / 1e3, 1),
+                          "speedup_over_pytorch_eager": round(t_eager / t_lib, 2)}), flush=True)
+        del L
+        torch.cuda.empty_cache()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -659,6 +730,8 @@ def main():
     ap.add_argument("--ceiling", action="store_true", help="measure the streaming-copy ceiling of the machine")
     ap.add_argument("--kway", action="store_true", help="K-way merge vs a chain of two-way merges")
     ap.add_argument("--decode", action="store_true", help="decode-sized launches replayed from a HIP graph")
+    ap.add_argument("--vs-eager", action="store_true",
+                    help="context: the step workloads through this library and through plain PyTorch tensor ops")
     ap.add_argument("--ablation", action="store_true",
                     help="paper Table-4 shapes and the bandwidth workloads: tuned kernel vs each one-optimisation-removed variant")
     args = ap.parse_args()
@@ -666,7 +739,9 @@ def main():
         print("bench.py: this path runs on ONE GPU (row-independent kernels, no collectives); "
               "--gpus N with N > 1 is not supported", file=sys.stderr)
         sys.exit(2)
-    if args.decode:
+    if args.vs_eager:
+        run_vs_eager(args)
+    elif args.decode:
         run_decode(args)
     elif args.kway:
         run_kway(args)
