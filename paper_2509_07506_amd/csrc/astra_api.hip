@@ -122,8 +122,14 @@ void launch_silu(const astra_launch_info_t& li, void* out, const void* in, int64
         return;
     }
     const uint32_t dv = (uint32_t)(d / Storage<DT>::kN);
-    silu_and_mul_vec_kernel<DT, kSiluUnroll, kNTLoad, kNTStore><<<dim3((uint32_t)li.grid), dim3(256), 0, stream>>>(
-        static_cast<u32x4*>(out), static_cast<const u32x4*>(in), (uint32_t)(T * dv), dv, make_fastdiv(dv), li.log2_xcd_chunk);
+    if (dv < kSiluLaneDivBelow)
+        silu_and_mul_vec_kernel<DT, kSiluUnroll, kNTLoad, kNTStore, false, 256, true>
+            <<<dim3((uint32_t)li.grid), dim3(256), 0, stream>>>(static_cast<u32x4*>(out), static_cast<const u32x4*>(in),
+                                                                (uint32_t)(T * dv), dv, make_fastdiv(dv), li.log2_xcd_chunk);
+    else
+        silu_and_mul_vec_kernel<DT, kSiluUnroll, kNTLoad, kNTStore><<<dim3((uint32_t)li.grid), dim3(256), 0, stream>>>(
+            static_cast<u32x4*>(out), static_cast<const u32x4*>(in), (uint32_t)(T * dv), dv, make_fastdiv(dv),
+            li.log2_xcd_chunk);
 }
 
 template <int DT>

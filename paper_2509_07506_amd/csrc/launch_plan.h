@@ -21,6 +21,7 @@ constexpr bool kNTStore = true;   // and on the once-written outputs
 constexpr int kSiluUnroll = 1;
 constexpr int kMergeUnroll = 1;
 constexpr int kCopyUnroll = 1;
+constexpr int64_t kSiluLaneDivBelow = 32;  // silu rows shorter than this many vectors: each lane divides for itself
 constexpr int kKwayGroup = 4;     // partitions folded per step of the streaming K-way merge
 
 constexpr int64_t kMaxVecIndex = int64_t(1) << 31;  // 32-bit vector indices with head-room for the tail
@@ -164,7 +165,7 @@ inline astra_status_t plan_silu(int64_t T, int64_t d, int eb, bool aligned16, as
     if (T == 0) return ASTRA_OK;
     const int64_t dv = d / ne;
     // the input holds 2*T*dv vectors and is indexed with 32 bits
-    if (aligned16 && d % ne == 0 && dv >= 32 && 2 * T * dv <= kMaxVecIndex) {
+    if (aligned16 && d % ne == 0 && 2 * T * dv <= kMaxVecIndex) {  // rows under kSiluLaneDivBelow vectors: per-lane division
         const int64_t span = 256 * kSiluUnroll;
         const int64_t blocks = (T * dv + span - 1) / span;
         const int lc = fit_chunk_log2(blocks, kFlatChunkLog2, kFlatChunkMinBlocks);

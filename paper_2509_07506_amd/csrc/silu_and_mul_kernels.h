@@ -23,11 +23,12 @@ __device__ __forceinline__ float silu_fast(float x)
 __device__ __forceinline__ float silu_libm(float x) { return x / (1.0f + expf(-x)); }
 
 // Fast path: d % N == 0 and 16-byte aligned pointers.  Work is the flat list of output vectors
-// (dv = d/N per row); a block owns BLOCK*UNROLL consecutive ones.  The row of the block's first vector
-// comes from one scalar fast division; lanes then step to the next row when they run past the end
-// of a row (at most a few steps because the host only takes this path when dv >= 32).
-// For output vector (t, j):  x = in[t*2dv + j], g = in[t*2dv + dv + j], out index = t*dv + j.
-template <int DT, int UNROLL, bool NTL, bool NTS, bool LIBM = false, int BLOCK = 256>
+// (dv = d/N per row); a block owns BLOCK*UNROLL consecutive ones.  For output vector (t, j):
+//   x = in[t*2dv + j], g = in[t*2dv + dv + j], out index = t*dv + j.
+// LANE_DIV = false (rows of at least 32 vectors): the row of the block's first vector comes from one scalar
+// fast division; lanes then step to the next row when they run past the end of a row (a few steps at most).
+// LANE_DIV = true (short rows, e.g. a tensor-parallel slice of a small expert): every lane divides for itself.
+template <int DT, int UNROLL, bool NTL, bool NTS, bool LIBM = false, int BLOCK = 256, bool LANE_DIV = false>
 __global__ __launch_bounds__(BLOCK) void silu_and_mul_vec_kernel(u32x4* __restrict__ out, const u32x4* __restrict__ in,
                                                                uint32_t total_vecs, uint32_t dv, FastDiv by_dv,
                                                                int log2_chunk)
@@ -36,8 +37,11 @@ __global__ __launch_bounds__(BLOCK) void silu_and_mul_vec_kernel(u32x4* __restri
     constexpr uint32_t kSpan = uint32_t(BLOCK) * UNROLL;
     const uint32_t first = xcd_chunked(blockIdx.x, log2_chunk) * kSpan;
     if (first >= total_vecs) return;  // grid padding
-    const uint32_t t0 = by_dv.div(first);
-    const uint32_t j0 = first - t0 * dv;
+    uint32_t t0 = 0, j0 = 0;
+    if constexpr (!LANE_DIV) {
+        t0 = by_dv.div(first);
+        j0 = first - t0 * dv;
+    }
 
     u32x4 xv[UNROLL], gv[UNROLL];
     uint32_t oidx[UNROLL];
@@ -45,10 +49,17 @@ __global__ __launch_bounds__(BLOCK) void silu_and_mul_vec_kernel(u32x4* __restri
     for (int k = 0; k < UNROLL; ++k) {
         const uint32_t off = threadIdx.x + uint32_t(BLOCK) * k;
         oidx[k] = first + off;
-        uint32_t t = t0, j = j0 + off;
-        while (j >= dv) {
-            j -= dv;
-            ++t;
+        uint32_t t, j;
+        if constexpr (LANE_DIV) {
+            t = by_dv.div(oidx[k]);
+            j = oidx[k] - t * dv;
+        } else {
+            t = t0;
+            j = j0 + off;
+            while (j >= dv) {
+                j -= dv;
+                ++t;
+            }
         }
         if (oidx[k] < total_vecs) {
             const u32x4* px = in + (t * 2u * dv + j);  // the host keeps 2*T*dv within 32 bits

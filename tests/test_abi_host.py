@@ -179,7 +179,9 @@ def test_silu_and_merge_plans(A):
     assert p["grid"] % (8 << p["log2_xcd_chunk"]) == 0
     assert A.astra_plan_silu_and_mul(3, 100, True)[1].as_dict()["path"] == "generic"
     assert A.astra_plan_silu_and_mul(3, 1408, False)[1].as_dict()["path"] == "generic"
-    assert A.astra_plan_silu_and_mul(3, 128, True)[1].as_dict()["path"] == "generic"      # rows shorter than 32 vectors
+    assert A.astra_plan_silu_and_mul(3, 128, True)[1].as_dict()["path"] == "vector"       # short rows: per-lane division
+    assert A.astra_plan_silu_and_mul(1000, 8, True)[1].as_dict() == {"path": "vector", "block": 256, "vectors_per_lane": 1,
+                                                                     "log2_xcd_chunk": 0, "grid": 4, "pace": 0}
     assert A.astra_plan_silu_and_mul(1 << 20, 1 << 14, True)[1].as_dict()["path"] == "generic"  # beyond 32-bit vector indices
     small = A.astra_plan_silu_and_mul(3, 1408, True)[1].as_dict()
     assert small["log2_xcd_chunk"] == 0 and small["grid"] == 3                           # no padding for small grids

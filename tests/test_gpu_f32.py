@@ -89,7 +89,8 @@ def test_rmsnorm_unaligned_and_canaries(A):
         assert_bits_equal(u32(to_bits(wv)), u32(w), "weight untouched")
 
 
-@pytest.mark.parametrize("T,d", [(1, 128), (3, 1412), (257, 1408), (64, 8192), (700, 5120), (5, 130), (4, 7), (9, 96)])
+@pytest.mark.parametrize("T,d", [(1, 128), (3, 1412), (257, 1408), (64, 8192), (700, 5120), (5, 130), (4, 7), (9, 96),
+                                 (333, 4), (50, 88)])
 def test_silu_tiles(A, T, d):
     plan = A.astra_plan_silu_and_mul(T, d, True, dtype=A.ASTRA_F32)[1].as_dict()
     _say(f"[f32] silu T={T} d={d} plan={plan}")

@@ -147,7 +147,8 @@ def test_rmsnorm_streaming_grids(A, T, H, dt):
 
 @pytest.mark.parametrize("dt", ["bf16", "f16"])
 @pytest.mark.parametrize("T,d", [(1, 256), (3, 264), (2, 512), (7, 1000), (33, 2048), (5, 4096), (19, 5120), (2, 12288),
-                                 (1, 14336), (129, 3584)])
+                                 (1, 14336), (129, 3584),
+                                 (300, 8), (17, 64), (1000, 176), (5, 248), (4099, 24)])   # rows under 32 vectors
 def test_silu_tile_shapes(A, T, d, dt):
     _say(f"[parity] silu tiles T={T} d={d} {dt} plan={A.astra_plan_silu_and_mul(T, d, True)[1].as_dict()}")
     a = workloads.silu_inputs(T, d, dt, np.random.default_rng([2, T, d]))
