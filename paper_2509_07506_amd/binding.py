@@ -77,6 +77,10 @@ def load_library() -> ctypes.CDLL:
     L.astra_stream_copy.argtypes = [vp, vp, i64, vp]
     L.astra_fused_add_rmsnorm_strided.argtypes = [vp, i64, vp, i64, vp, i64, vp, i64, vp, i64, i64, i32, f32, vp]
     L.astra_fused_add_rmsnorm_strided.restype = i32
+    L.astra_silu_and_mul_strided.argtypes = [vp, i64, vp, i64, i64, i64, i32, vp]
+    L.astra_silu_and_mul_strided.restype = i32
+    L.astra_merge_attn_states_lse_strided.argtypes = [vp, i64, i64, vp, vp, i64, i64, vp, vp, i64, i64, vp, i64, i64, i64, i32, vp]
+    L.astra_merge_attn_states_lse_strided.restype = i32
     L.astra_merge_attn_states_lse_kway.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, i32, vp]
     L.astra_merge_attn_states_lse_kway.restype = i32
     L.astra_ablation_fused_add_rmsnorm.argtypes = [vp, vp, vp, i64, i64, i32, f32, i32, vp]
@@ -129,6 +133,16 @@ def astra_fused_add_rmsnorm_strided(y_out, y_stride, r_out, r_out_stride, x, x_s
                                     stream=None) -> int:
     return load_library().astra_fused_add_rmsnorm_strided(y_out, y_stride, r_out, r_out_stride, x, x_stride, r, r_stride,
                                                           weight, T, H, dtype, eps, stream)
+
+
+def astra_silu_and_mul_strided(out, out_stride, input_ptr, in_stride, T, d, dtype, stream=None) -> int:
+    return load_library().astra_silu_and_mul_strided(out, out_stride, input_ptr, in_stride, T, d, dtype, stream)
+
+
+def astra_merge_attn_states_lse_strided(v_out, out_ts, out_hs, lse_out, v_a, a_ts, a_hs, lse_a, v_b, b_ts, b_hs, lse_b, T,
+                                        num_heads, head_dim, dtype, stream=None) -> int:
+    return load_library().astra_merge_attn_states_lse_strided(v_out, out_ts, out_hs, lse_out, v_a, a_ts, a_hs, lse_a, v_b,
+                                                              b_ts, b_hs, lse_b, T, num_heads, head_dim, dtype, stream)
 
 
 def astra_merge_attn_states_lse_kway(v_out, lse_out, v_parts, lse_parts, K, T, num_heads, head_dim, dtype, stream=None) -> int:
@@ -293,6 +307,49 @@ def fused_add_rmsnorm_strided(y_out, r_out, x, r, weight, eps: float, stream=Non
                                          _stream(stream))
     if st:
         raise AstraError(st, "astra_fused_add_rmsnorm_strided")
+
+
+def silu_and_mul_strided(out, input, stream=None) -> None:
+    """out[T,d] <- silu(input[:, :d]) * input[:, d:] for 2-D tensors whose rows are dense but may be strided views."""
+    for t in (out, input):
+        if not t.is_cuda:
+            raise ValueError("astra operators run on GPU tensors only (there is no CPU path)")
+    T, two_d = input.shape
+    d = two_d // 2
+    if two_d % 2 or out.shape != (T, d) or out.dtype != input.dtype or (two_d > 1 and input.stride(1) != 1) or \
+            (d > 1 and out.stride(1) != 1):
+        raise ValueError("silu_and_mul_strided: input [T,2d] and out [T,d] of one dtype with unit column stride expected")
+    if T == 0:
+        return
+    st = astra_silu_and_mul_strided(out.data_ptr(), out.stride(0) if T > 1 else d, input.data_ptr(),
+                                    input.stride(0) if T > 1 else two_d, T, d, _dtype_code(input), _stream(stream))
+    if st:
+        raise AstraError(st, "astra_silu_and_mul_strided")
+
+
+def merge_attn_states_lse_strided(v_out, lse_out, v_a, lse_a, v_b, lse_b, stream=None) -> None:
+    """Merge for value tensors [T,NH,D] that are strided views (dense along D); scores dense [T,NH] float32."""
+    import torch
+
+    for t in (v_out, lse_out, v_a, lse_a, v_b, lse_b):
+        if not t.is_cuda:
+            raise ValueError("astra operators run on GPU tensors only (there is no CPU path)")
+    T, NH, D = v_a.shape
+    for t in (v_out, v_a, v_b):
+        if t.shape != (T, NH, D) or t.dtype != v_a.dtype or (D > 1 and t.stride(2) != 1):
+            raise ValueError("merge_attn_states_lse_strided: v tensors [T,NH,D] of one dtype, dense along D, expected")
+    for s in (lse_a, lse_b, lse_out):
+        if s.shape != (T, NH) or s.dtype != torch.float32 or not s.is_contiguous():
+            raise ValueError("merge_attn_states_lse_strided: lse tensors [T,NH] float32, dense, expected")
+    if T == 0:
+        return
+    hs = lambda t: t.stride(1) if NH > 1 else D
+    ts = lambda t: t.stride(0) if T > 1 else (NH - 1) * hs(t) + D
+    st = astra_merge_attn_states_lse_strided(v_out.data_ptr(), ts(v_out), hs(v_out), lse_out.data_ptr(), v_a.data_ptr(),
+                                             ts(v_a), hs(v_a), lse_a.data_ptr(), v_b.data_ptr(), ts(v_b), hs(v_b),
+                                             lse_b.data_ptr(), T, NH, D, _dtype_code(v_a), _stream(stream))
+    if st:
+        raise AstraError(st, "astra_merge_attn_states_lse_strided")
 
 
 def stream_copy(dst, src, stream=None) -> None:

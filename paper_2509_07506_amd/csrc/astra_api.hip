@@ -474,6 +474,105 @@ astra_status_t astra_fused_add_rmsnorm_strided(void* y_out, int64_t y_stride, vo
     return after_launch();
 }
 
+astra_status_t astra_silu_and_mul_strided(void* out, int64_t out_stride, const void* input, int64_t in_stride, int64_t T,
+                                          int64_t d, astra_dtype_t dtype, hipStream_t stream)
+{
+    if (!out || !input) return ASTRA_ERR_NULL;
+    const int eb = elem_bytes((int)dtype);
+    const int64_t ne = kVecBytes / eb;
+    const bool fast = aligned(out, 16) && aligned(input, 16) && out_stride % ne == 0 && in_stride % ne == 0;
+    astra_launch_info_t li;
+    astra_status_t st = plan_silu(T, d, eb, fast, &li);
+    if (st != ASTRA_OK) return st;
+    int64_t out_rows, in_rows;
+    if (out_stride < d || in_stride < 2 * d || mul_overflows(T > 0 ? T - 1 : 0, out_stride, &out_rows) ||
+        mul_overflows(T > 0 ? T - 1 : 0, in_stride, &in_rows) || out_rows > std::numeric_limits<int64_t>::max() / 8 ||
+        in_rows > std::numeric_limits<int64_t>::max() / 8)
+        return ASTRA_ERR_SHAPE;
+    if (!valid_dtype((int)dtype)) return ASTRA_ERR_DTYPE;
+    if (!aligned(out, eb) || !aligned(input, eb)) return ASTRA_ERR_ALIGN;
+    const int64_t out_span = T > 0 ? (out_rows + d) * eb : 0, in_span = T > 0 ? (in_rows + 2 * d) * eb : 0;
+    if (overlaps(out, out_span, input, in_span)) return ASTRA_ERR_ALIAS;
+    if (T == 0) return ASTRA_OK;
+    for_dtype(dtype, [&](auto dtc) {
+        constexpr int DT = decltype(dtc)::value;
+        typedef typename Storage<DT>::elem_t E;
+        if (li.path == ASTRA_PATH_GENERIC) {
+            silu_and_mul_strided_generic_kernel<DT><<<dim3((uint32_t)li.grid), dim3(256), 0, stream>>>(
+                static_cast<E*>(out), out_stride, static_cast<const E*>(input), in_stride, T, d);
+        } else {
+            const uint32_t dv = (uint32_t)(d / Storage<DT>::kN);
+            silu_and_mul_strided_vec_kernel<DT, kNTLoad, kNTStore><<<dim3((uint32_t)li.grid), dim3(256), 0, stream>>>(
+                static_cast<u32x4*>(out), out_stride / Storage<DT>::kN, static_cast<const u32x4*>(input),
+                in_stride / Storage<DT>::kN, (uint32_t)(T * dv), dv, make_fastdiv(dv), li.log2_xcd_chunk);
+        }
+    });
+    return after_launch();
+}
+
+astra_status_t astra_merge_attn_states_lse_strided(void* v_out, int64_t out_token_stride, int64_t out_head_stride,
+                                                   float* lse_out, const void* v_a, int64_t a_token_stride,
+                                                   int64_t a_head_stride, const float* lse_a, const void* v_b,
+                                                   int64_t b_token_stride, int64_t b_head_stride, const float* lse_b,
+                                                   int64_t T, int64_t num_heads, int64_t head_dim, astra_dtype_t dtype,
+                                                   hipStream_t stream)
+{
+    if (!v_out || !lse_out || !v_a || !lse_a || !v_b || !lse_b) return ASTRA_ERR_NULL;
+    const int eb = elem_bytes((int)dtype);
+    const int64_t ne = kVecBytes / eb;
+    const int64_t ts[3] = {out_token_stride, a_token_stride, b_token_stride};
+    const int64_t hs[3] = {out_head_stride, a_head_stride, b_head_stride};
+    const void* const bases[3] = {v_out, v_a, v_b};
+    bool fast = true;
+    for (int i = 0; i < 3; ++i) fast = fast && aligned(bases[i], 16) && ts[i] % ne == 0 && hs[i] % ne == 0;
+    astra_launch_info_t li;
+    astra_status_t st = plan_merge(T, num_heads, head_dim, eb, fast, &li);
+    if (st != ASTRA_OK) return st;
+    int64_t span[3];  // bounding extent of each value view in bytes
+    for (int i = 0; i < 3; ++i) {
+        int64_t heads_ext, tok_ext, total;
+        if (hs[i] < head_dim || mul_overflows(num_heads - 1, hs[i], &heads_ext) ||
+            __builtin_add_overflow(heads_ext, head_dim, &heads_ext) || ts[i] < heads_ext ||
+            mul_overflows(T > 0 ? T - 1 : 0, ts[i], &tok_ext) || __builtin_add_overflow(tok_ext, heads_ext, &total) ||
+            total > std::numeric_limits<int64_t>::max() / 8)
+            return ASTRA_ERR_SHAPE;
+        span[i] = T > 0 ? total * eb : 0;
+    }
+    if (!valid_dtype((int)dtype)) return ASTRA_ERR_DTYPE;
+    for (int i = 0; i < 3; ++i)
+        if (!aligned(bases[i], eb)) return ASTRA_ERR_ALIGN;
+    if (!aligned(lse_out, 4) || !aligned(lse_a, 4) || !aligned(lse_b, 4)) return ASTRA_ERR_ALIGN;
+    const int64_t pairs = T * num_heads, sbytes = pairs * 4;
+    const bool out_is_a = (v_out == v_a && ts[0] == ts[1] && hs[0] == hs[1]);
+    const bool out_is_b = (v_out == v_b && ts[0] == ts[2] && hs[0] == hs[2]);
+    if ((!out_is_a && overlaps(v_out, span[0], v_a, span[1])) || (!out_is_b && overlaps(v_out, span[0], v_b, span[2])) ||
+        overlaps(lse_out, sbytes, lse_a, sbytes) || overlaps(lse_out, sbytes, lse_b, sbytes) ||
+        overlaps(v_out, span[0], lse_a, sbytes) || overlaps(v_out, span[0], lse_b, sbytes) ||
+        overlaps(lse_out, sbytes, v_a, span[1]) || overlaps(lse_out, sbytes, v_b, span[2]) ||
+        overlaps(lse_out, sbytes, v_out, span[0]))
+        return ASTRA_ERR_ALIAS;
+    if (T == 0) return ASTRA_OK;
+    for_dtype(dtype, [&](auto dtc) {
+        constexpr int DT = decltype(dtc)::value;
+        constexpr int N = Storage<DT>::kN;
+        typedef typename Storage<DT>::elem_t E;
+        if (li.path == ASTRA_PATH_GENERIC) {
+            const ValueStrides vs{ts[0], hs[0], ts[1], hs[1], ts[2], hs[2]};
+            merge_attn_states_lse_strided_generic_kernel<DT><<<dim3((uint32_t)li.grid), dim3(256), 0, stream>>>(
+                static_cast<E*>(v_out), lse_out, static_cast<const E*>(v_a), lse_a, static_cast<const E*>(v_b), lse_b, vs, pairs,
+                num_heads, head_dim);
+        } else {
+            const ValueStrides vs{ts[0] / N, hs[0] / N, ts[1] / N, hs[1] / N, ts[2] / N, hs[2] / N};
+            const uint32_t dvec = (uint32_t)(head_dim / N);
+            merge_attn_states_lse_strided_vec_kernel<DT, kNTLoad, kNTStore><<<dim3((uint32_t)li.grid), dim3(256), 0, stream>>>(
+                static_cast<u32x4*>(v_out), lse_out, static_cast<const u32x4*>(v_a), lse_a, static_cast<const u32x4*>(v_b),
+                lse_b, vs, (uint32_t)(pairs * dvec), dvec, make_fastdiv(dvec), make_fastdiv((uint32_t)num_heads),
+                (uint32_t)num_heads, li.log2_xcd_chunk);
+        }
+    });
+    return after_launch();
+}
+
 astra_status_t astra_device_memory_info(int device, int* memory_clock_khz, int* memory_bus_bits)
 {
     if (!memory_clock_khz || !memory_bus_bits) return ASTRA_ERR_NULL;

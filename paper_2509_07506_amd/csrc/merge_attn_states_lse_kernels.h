@@ -111,6 +111,57 @@ __global__ __launch_bounds__(256) void merge_attn_states_lse_generic_kernel(type
 }
 
 // ---------------------------------------------------------------------------------------------
+// Strided views of the value tensors: element (t, h, k) of a tensor lives at t*token_stride + h*head_stride + k
+// (strides in vectors for the fast kernel, in elements for the element-wise one); the scores stay dense [T, NH].
+// One lane per output vector; pair, token and head from per-lane fast divisions; 64-bit offsets.
+
+struct ValueStrides {
+    int64_t out_token, out_head, a_token, a_head, b_token, b_head;
+};
+
+template <int DT, bool NTL, bool NTS>
+__global__ __launch_bounds__(256) void merge_attn_states_lse_strided_vec_kernel(u32x4* v_out, float* lse_out, const u32x4* v_a,
+                                                                                const float* lse_a, const u32x4* v_b,
+                                                                                const float* lse_b, ValueStrides vs,
+                                                                                uint32_t total_vecs, uint32_t dvec,
+                                                                                FastDiv by_dvec, FastDiv by_heads,
+                                                                                uint32_t heads, int log2_chunk)
+{
+    constexpr int N = Storage<DT>::kN;
+    const uint32_t i = xcd_chunked(blockIdx.x, log2_chunk) * 256u + threadIdx.x;
+    if (i >= total_vecs) return;
+    const uint32_t pair = by_dvec.div(i), jv = i - pair * dvec;
+    const uint32_t t = by_heads.div(pair), h = pair - t * heads;
+    const u32x4 av = load_vec<NTL>(v_a + ((int64_t)t * vs.a_token + (int64_t)h * vs.a_head + jv));
+    const u32x4 bv = load_vec<NTL>(v_b + ((int64_t)t * vs.b_token + (int64_t)h * vs.b_head + jv));
+    const MergeWeights w = merge_weights(lse_a[pair], lse_b[pair]);
+    float a[N], b[N], o[N];
+    unpack_vec<DT>(av, a);
+    unpack_vec<DT>(bv, b);
+#pragma unroll
+    for (int e = 0; e < N; ++e) o[e] = w.a * a[e] + w.b * b[e];
+    store_vec<NTS>(v_out + ((int64_t)t * vs.out_token + (int64_t)h * vs.out_head + jv), pack_vec<DT>(o));
+    if (jv == 0) lse_out[pair] = w.lse;
+}
+
+template <int DT>
+__global__ __launch_bounds__(256) void merge_attn_states_lse_strided_generic_kernel(
+    typename Storage<DT>::elem_t* v_out, float* lse_out, const typename Storage<DT>::elem_t* v_a, const float* lse_a,
+    const typename Storage<DT>::elem_t* v_b, const float* lse_b, ValueStrides vs, int64_t pairs, int64_t heads, int64_t D)
+{
+    for (int64_t p = blockIdx.x; p < pairs; p += gridDim.x) {
+        const int64_t t = p / heads, h = p - t * heads;
+        const MergeWeights w = merge_weights(lse_a[p], lse_b[p]);
+        const typename Storage<DT>::elem_t* pa = v_a + t * vs.a_token + h * vs.a_head;
+        const typename Storage<DT>::elem_t* pb = v_b + t * vs.b_token + h * vs.b_head;
+        typename Storage<DT>::elem_t* po = v_out + t * vs.out_token + h * vs.out_head;
+        for (int64_t k = threadIdx.x; k < D; k += blockDim.x)
+            po[k] = Storage<DT>::narrow(w.a * Storage<DT>::widen(pa[k]) + w.b * Storage<DT>::widen(pb[k]));
+        if (threadIdx.x == 0) lse_out[p] = w.lse;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // K-way merge: V_out = sum_k e^(S_k) V_k / sum_k e^(S_k), S_out = log sum_k e^(S_k).
 // kway_stats is the plain three-pass evaluation used by the element-wise path.
 

@@ -98,4 +98,46 @@ __global__ __launch_bounds__(256) void silu_and_mul_generic_kernel(typename Stor
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Row-strided views: input row t starts in_stride vectors (elements for the element-wise kernel) after row
+// t-1, likewise the output.  One lane per output vector, row and column from a per-lane fast division,
+// 64-bit offsets (a strided view has no 32-bit bound on its extent).
+
+template <int DT, bool NTL, bool NTS>
+__global__ __launch_bounds__(256) void silu_and_mul_strided_vec_kernel(u32x4* __restrict__ out, int64_t out_stride,
+                                                                       const u32x4* __restrict__ in, int64_t in_stride,
+                                                                       uint32_t total_vecs, uint32_t dv, FastDiv by_dv,
+                                                                       int log2_chunk)
+{
+    constexpr int N = Storage<DT>::kN;
+    const uint32_t o = xcd_chunked(blockIdx.x, log2_chunk) * 256u + threadIdx.x;
+    if (o >= total_vecs) return;
+    const uint32_t t = by_dv.div(o);
+    const uint32_t j = o - t * dv;
+    const u32x4* px = in + ((int64_t)t * in_stride + j);
+    const u32x4 xv = load_vec<NTL>(px);
+    const u32x4 gv = load_vec<NTL>(px + dv);
+    float x[N], g[N], r[N];
+    unpack_vec<DT>(xv, x);
+    unpack_vec<DT>(gv, g);
+#pragma unroll
+    for (int e = 0; e < N; ++e) r[e] = silu_fast(x[e]) * g[e];
+    store_vec<NTS>(out + ((int64_t)t * out_stride + j), pack_vec<DT>(r));
+}
+
+template <int DT>
+__global__ __launch_bounds__(256) void silu_and_mul_strided_generic_kernel(typename Storage<DT>::elem_t* __restrict__ out,
+                                                                           int64_t out_stride,
+                                                                           const typename Storage<DT>::elem_t* __restrict__ in,
+                                                                           int64_t in_stride, int64_t T, int64_t d)
+{
+    typedef typename Storage<DT>::elem_t E;
+    for (int64_t t = blockIdx.x; t < T; t += gridDim.x) {
+        const E* row = in + t * in_stride;
+        E* orow = out + t * out_stride;
+        for (int64_t j = threadIdx.x; j < d; j += blockDim.x)
+            orow[j] = Storage<DT>::narrow(silu_fast(Storage<DT>::widen(row[j])) * Storage<DT>::widen(row[d + j]));
+    }
+}
+
 }  // namespace astra

@@ -36,7 +36,7 @@ def test_every_declared_symbol_is_exported(A):
     assert {"astra_fused_add_rmsnorm", "astra_silu_and_mul", "astra_merge_attn_states_lse", "astra_status_string",
             "astra_stream_copy", "astra_plan_fused_add_rmsnorm", "astra_plan_silu_and_mul",
             "astra_plan_merge_attn_states_lse", "astra_plan_xcd_chunked", "astra_device_memory_info", "astra_merge_attn_states_lse_kway",
-            "astra_fused_add_rmsnorm_strided",
+            "astra_fused_add_rmsnorm_strided", "astra_silu_and_mul_strided", "astra_merge_attn_states_lse_strided",
             "astra_ablation_fused_add_rmsnorm", "astra_ablation_silu_and_mul", "astra_ablation_merge_attn_states_lse"} <= set(declared)
     for name in declared:
         assert hasattr(L, name), f"{name} declared in include/ but not exported"
@@ -100,6 +100,38 @@ def test_merge_validation(A):
     assert f(va, lo, va, la, vb, lb, 0, 2, 8, 1) == 0              # exact aliasing of v_out and v_a is allowed
     assert f(vo + 2, lo, va, la, vb, lb, 1, 2, 8, 2) == 5          # binary32 storage: 4-byte alignment
     assert f(vo, lo, vo + 32, la, vb, lb, 1, 2, 8, 2) == 6          # 64-byte tensors 32 bytes apart
+
+
+def test_strided_silu_and_merge_validation(A):
+    f = A.astra_silu_and_mul_strided
+    a, b = 0x10000, 0x40000
+    assert f(0, 8, b, 16, 1, 8, 1) == 1 and f(a, 8, 0, 16, 1, 8, 1) == 1
+    assert f(a, 7, b, 16, 2, 8, 1) == 2 and f(a, 8, b, 15, 2, 8, 1) == 2 and f(a, 8, b, 16, -1, 8, 1) == 2
+    assert f(a, 1 << 61, b, 1 << 61, 8, 8, 1) == 2                      # extent overflows
+    assert f(a, 8, b, 16, 2, 8, 9) == 3
+    assert f(a + 1, 8, b, 16, 2, 8, 1) == 5
+    assert f(a, 8, a + 24, 16, 2, 8, 1) == 6                            # out rows [a, a+32) meet input [a+24, ...)
+    assert f(a, 64, a + 64, 64, 2, 8, 1) == 6                           # interleaved views: bounding ranges overlap
+    assert f(a, 8, b, 16, 0, 8, 1) == 0
+    g = A.astra_merge_attn_states_lse_strided
+    vo, lo, va, la, vb, lb = 0x100000, 0x200000, 0x300000, 0x400000, 0x500000, 0x600000
+
+    def call(T=2, NH=2, D=8, dt=1, **kw):
+        p = dict(vo=vo, ots=16, ohs=8, lo=lo, va=va, ats=16, ahs=8, la=la, vb=vb, bts=16, bhs=8, lb=lb)
+        p.update(kw)
+        return g(p["vo"], p["ots"], p["ohs"], p["lo"], p["va"], p["ats"], p["ahs"], p["la"], p["vb"], p["bts"], p["bhs"],
+                 p["lb"], T, NH, D, dt)
+
+    for key in ("vo", "lo", "va", "la", "vb", "lb"):
+        assert call(**{key: 0}) == 1
+    assert call(T=-1) == 2 and call(NH=0) == 2 and call(ahs=7) == 2 and call(ats=15) == 2 and call(ots=1 << 61) == 2
+    assert call(dt=5) == 3
+    assert call(va=va + 1) == 5 and call(lo=lo + 2) == 5
+    assert call(va=vo + 8) == 6                                          # v_out partly on v_a
+    assert call(T=0, va=vo) == 0                                         # same view, nothing to do
+    assert call(va=vo, ats=32) == 6                                      # same pointer but another stride: not the same view
+    assert call(lo=la) == 6
+    assert call(T=0) == 0
 
 
 def test_stream_copy_validation(A):
