@@ -303,6 +303,7 @@ def run_step_bench(args):
             "tokens_per_s": round(c.tokens() / (avg * 1e-3), 1),
             "back_to_back_us": None if c.kernel not in batch_us else round(batch_us[c.kernel], 3),
             "back_to_back_GBs": None if c.kernel not in batch_us else round(b / batch_us[c.kernel] / 1e3, 1),
+            "back_to_back_frac_of_peak": None if c.kernel not in batch_us else round(b / batch_us[c.kernel] / 1e3 / HBM_PEAK_GBS, 4),
             "traffic": (traffic.get(c.name) or {}).get("total_bytes"),
             "traffic_detail": traffic.get(c.name),
         }
