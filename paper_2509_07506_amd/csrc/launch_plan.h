@@ -116,22 +116,28 @@ inline bool rmsnorm_row_plan(int64_t hv, RowPlan* plan)
 }
 
 // When the waves of the row kernel issue their requests (fused_add_rmsnorm_kernels.h, PACE).  Few rows: nothing is
-// held back (the shortest dependent chain).  Streaming grids, measured on MI355X with T*H = 2^28 16-bit elements
-// (% of the 8 TB/s peak; "gap" = output store held until the residual store has completed, "w,x" = weight, then x,
-// then r requested one after the other; none / gap / w,x):
-//   one vector per lane    H=512 81.9/84.1/83.8   1024 81.5/83.0/82.7  1536 78.8/80.8/81.4  2048 81.5/82.5/83.6
-//                          2560 81.4/82.6/81.0    3072 80.0/80.6/80.2  4096 79.8/84.8/83.9  5120 83.1/83.2/75.6
-//                          6144 81.7/82.2/79.4    7168 82.3/81.8/81.4  8192 81.7/81.9/82.9
-//   two vectors per lane   10240 78.9/79.5/80.6   11008 78.7/78.5/79.0  12288 79.8/79.4/80.0  14336 79.0/79.0/80.3
-//                          16384 77.1/77.2/78.0
-//   four vectors per lane  20480 76.0/75.8/76.3   28672 76.0/76.2/71.1  32768 79.5/79.6/76.8
-// "gap" is never far from the best and has no bad case, so it is the default; "w,x" is taken where it measured
-// better: rows of 256 or 1024 vectors (4 KiB, 16 KiB) and all two-vector rows.  It is not used elsewhere because
-// it can lose 8 % (H = 5120).
+// held back (the shortest dependent chain).  Streaming grids: measured on MI355X with T*H = 2^28 16-bit elements,
+// microseconds per launch averaged over 16 placements of x and r inside one 6 GiB allocation (10 for the two-vector
+// rows), worst placement in brackets; "gap" = output store held until the residual store has completed, "x" = x
+// arrived before r is requested, "w,x" = weight, then x, then r one after the other:
+//                 none        gap         x           w,x
+//   H =  2048   342 (362)   328 (346)   326 (337)   323 (339)
+//   H =  4096   337 (349)   320 (338)   322 (325)   320 (326)
+//   H =  5120   326 (331)   326 (332)   332 (335)   355 (358)
+//   H =  6144   329 (334)   329 (334)   332 (339)   340 (346)
+//   H =  8192   331 (342)   329 (332)   325 (332)   323 (329)
+//   H = 11008   342 (345)   342 (345)   344 (347)   336 (340)     two vectors per lane
+//   H = 16384   347 (353)   346 (351)   338 (341)   345 (350)     two vectors per lane
+// (floor at 8 TB/s: 268 us).  "gap" is never far from the best and has no bad case, so it is the default (it also
+// measured best or equal for H = 512 ... 1536, 2560 ... 3584, 7168 and for four vectors per lane); "w,x" is taken
+// where it measured better -- rows of 256, 512 or 1024 vectors (4, 8, 16 KiB) and two-vector rows -- except rows of
+// 2048 vectors, which take "x".  Serialising x and r can lose 8 % on rows that are not a power of two (H = 5120),
+// so it is not used outside the measured cases.
 inline int rmsnorm_pace(int64_t T, int64_t hv, int vpt)
 {
     if (T < kRowChunkMinRows) return kPaceNone;
-    if (vpt == 2 || (vpt == 1 && (hv == 256 || hv == 1024))) return kPaceWeightFirst | kPaceXBeforeR;
+    if (vpt == 1 && (hv == 256 || hv == 512 || hv == 1024)) return kPaceWeightFirst | kPaceXBeforeR;
+    if (vpt == 2) return hv == 2048 ? kPaceXBeforeR : (kPaceWeightFirst | kPaceXBeforeR);
     return kPaceStoreGap;
 }
 
