@@ -126,18 +126,28 @@ inline bool rmsnorm_row_plan(int64_t hv, RowPlan* plan)
 //   H =  5120   326 (331)   326 (332)   332 (335)   355 (358)
 //   H =  6144   329 (334)   329 (334)   332 (339)   340 (346)
 //   H =  8192   331 (342)   329 (332)   325 (332)   323 (329)
+//   H =   512   324 (335)   324 (341)   320 (326)   322 (330)
+//   H =  1024   327 (341)   326 (341)   327 (340)   323 (336)
+//   H =  3072   336 (345)   333 (341)   328 (333)   336 (342)
+//   H =  7168   329 (331)   330 (332)   328 (331)   329 (332)
+//   H = 10240   342 (345)   341 (343)   339 (342)   336 (338)     two vectors per lane
 //   H = 11008   342 (345)   342 (345)   344 (347)   336 (340)     two vectors per lane
+//   H = 12288   339 (340)   339 (340)   338 (339)   337 (339)     two vectors per lane
+//   H = 14336   341 (342)   341 (343)   338 (339)   336 (337)     two vectors per lane
 //   H = 16384   347 (353)   346 (351)   338 (341)   345 (350)     two vectors per lane
-// (floor at 8 TB/s: 268 us).  "gap" is never far from the best and has no bad case, so it is the default (it also
-// measured best or equal for H = 512 ... 1536, 2560 ... 3584, 7168 and for four vectors per lane); "w,x" is taken
-// where it measured better -- rows of 256, 512 or 1024 vectors (4, 8, 16 KiB) and two-vector rows -- except rows of
-// 2048 vectors, which take "x".  Serialising x and r can lose 8 % on rows that are not a power of two (H = 5120),
-// so it is not used outside the measured cases.
+//   H = 20480   354 (355)   355 (356)   352 (352)   350 (352)     four vectors per lane
+//   H = 28672   353 (359)   354 (357)   353 (358)   374 (382)     four vectors per lane
+//   H = 32768   360 (372)   356 (365)   346 (355)   360 (365)     four vectors per lane
+// (floor at 8 TB/s: 268 us).  "gap" is never far from the best and has no bad case, so it is the default; the other
+// two are taken only where they measured at least 1.5 % better: "w,x" for rows of 256, 512 or 1024 vectors (4, 8,
+// 16 KiB) and for two-vector rows, "x" for rows of 384, 2048 and 4096 vectors.  Serialising x and r can lose 8 %
+// on other row lengths (H = 5120), and waiting for the weight 6 % (H = 28672), so neither is used outside the
+// measured cases.
 inline int rmsnorm_pace(int64_t T, int64_t hv, int vpt)
 {
     if (T < kRowChunkMinRows) return kPaceNone;
-    if (vpt == 1 && (hv == 256 || hv == 512 || hv == 1024)) return kPaceWeightFirst | kPaceXBeforeR;
-    if (vpt == 2) return hv == 2048 ? kPaceXBeforeR : (kPaceWeightFirst | kPaceXBeforeR);
+    if (hv == 384 || hv == 2048 || hv == 4096) return kPaceXBeforeR;
+    if (vpt == 2 || hv == 256 || hv == 512 || hv == 1024) return kPaceWeightFirst | kPaceXBeforeR;
     return kPaceStoreGap;
 }
 

@@ -174,6 +174,7 @@ def test_rmsnorm_plans(A):
     assert plan(32768, 8192)["pace"] == 3 and plan(32768, 2048)["pace"] == 3 and plan(4096, 11008)["pace"] == 3
     assert plan(32768, 4096)["pace"] == 3 and plan(4096, 16384)["pace"] == 2
     assert plan(4099, 5120)["pace"] == 4 and plan(2048, 28672)["pace"] == 4 and plan(32768, 1024)["pace"] == 4
+    assert plan(2048, 3072)["pace"] == 2 and plan(2048, 32768)["pace"] == 2
     assert plan(2048, 11008)["vectors_per_lane"] == 2 and plan(2048, 28672)["vectors_per_lane"] == 4
     assert A.astra_plan_fused_add_rmsnorm(32768, 4096, True, dtype=A.ASTRA_F32)[1].as_dict()["pace"] == 3   # 16 KiB rows
     assert A.astra_plan_fused_add_rmsnorm(32768, 8192, True, dtype=A.ASTRA_F32)[1].as_dict()["pace"] == 2   # 32 KiB rows

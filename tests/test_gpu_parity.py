@@ -137,7 +137,7 @@ def test_rmsnorm_tile_shapes(A, T, H, dt):
 
 @pytest.mark.parametrize("T,H,dt", [(1100, 2048, "bf16"), (1030, 1032, "f16"), (1024, 8192, "f16"), (1025, 11008, "bf16"),
                                     (1024, 16384, "f16"), (1030, 28672, "bf16"), (1100, 20000, "f16"), (2050, 512, "bf16"),
-                                    (1040, 4096, "bf16")])
+                                    (1040, 4096, "bf16"), (1029, 3072, "f16"), (1024, 32768, "bf16")])
 def test_rmsnorm_streaming_grids(A, T, H, dt):
     """From 1024 rows on the row kernel paces its requests (which wait goes where depends on the row length and on
     the vectors per lane); the results must not depend on it."""
