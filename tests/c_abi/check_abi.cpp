@@ -19,6 +19,8 @@
 
 #include "astra.h"
 #include "astra_kway.h"
+#include "astra_plan.h"
+#include "astra_strided.h"
 
 extern "C" {
 // oracle/astra_oracle.c
@@ -256,6 +258,104 @@ void check_merge(int dt, int64_t T, int64_t NH, int64_t D, hipStream_t s)
     }
 }
 
+// the strided entry points on padded views (rows / heads further apart than their length), 16-bit storage
+void check_strided(int dt, hipStream_t s)
+{
+    // silu_and_mul: T rows of 2d, input row stride 2d + 16, output row stride d + 8
+    {
+        const int64_t T = 37, d = 1408, is = 2 * d + 16, os = d + 8;
+        Rng g{uint64_t(4000 + dt)};
+        std::vector<uint16_t> dense(T * 2 * d), in(T * is, narrow(7.0f, dt));
+        for (auto& v : dense) v = narrow(g.normalish(), dt);
+        for (int64_t t = 0; t < T; ++t) std::memcpy(&in[t * is], &dense[t * 2 * d], 2 * d * 2);
+        DevBuf<uint16_t> din(in.size()), dout(T * os);
+        std::vector<uint16_t> out_init(T * os, narrow(9.0f, dt));
+        din.upload(in, s);
+        dout.upload(out_init, s);
+        astra_status_t st = astra_silu_and_mul_strided(dout.p, os, din.p, is, T, d, (astra_dtype_t)dt, s);
+        std::vector<uint16_t> out = dout.download(s), ref(T * d), got(T * d);
+        oracle_silu_and_mul(ref.data(), dense.data(), T, d, dt);
+        bool gaps = true;
+        for (int64_t t = 0; t < T; ++t) {
+            std::memcpy(&got[t * d], &out[t * os], d * 2);
+            for (int64_t j = d; j < os; ++j) gaps = gaps && out[t * os + j] == narrow(9.0f, dt);
+        }
+        char what[120];
+        std::snprintf(what, sizeof what, "silu_and_mul_strided dtype=%d", dt);
+        const bool ok = st == ASTRA_OK && gaps && count_far(got, ref, dt) == 0;
+        expect(ok, what);
+        if (ok) std::printf("c_abi: ok %s (gaps untouched)\n", what);
+    }
+    // merge: heads of 128 values inside 192-wide head slots for v_a, dense v_b, 136-wide slots for the output
+    {
+        const int64_t T = 21, NH = 8, D = 128, ha = 192, ho = 136;
+        const size_t P = T * NH;
+        Rng g{uint64_t(5000 + dt)};
+        std::vector<uint16_t> va(P * D), vb(P * D), wa(P * ha, narrow(7.0f, dt));
+        for (auto& v : va) v = narrow(g.normalish(), dt);
+        for (auto& v : vb) v = narrow(g.normalish(), dt);
+        for (size_t p = 0; p < P; ++p) std::memcpy(&wa[p * ha], &va[p * D], D * 2);
+        std::vector<float> la = make_scores(g, P), lb = make_scores(g, P);
+        DevBuf<uint16_t> dwa(wa.size()), dvb(vb.size()), dvo(P * ho);
+        DevBuf<float> dla(P), dlb(P), dlo(P);
+        std::vector<uint16_t> out_init(P * ho, narrow(9.0f, dt));
+        dwa.upload(wa, s);
+        dvb.upload(vb, s);
+        dvo.upload(out_init, s);
+        dla.upload(la, s);
+        dlb.upload(lb, s);
+        astra_status_t st = astra_merge_attn_states_lse_strided(dvo.p, NH * ho, ho, dlo.p, dwa.p, NH * ha, ha, dla.p, dvb.p, NH * D,
+                                                                D, dlb.p, T, NH, D, (astra_dtype_t)dt, s);
+        std::vector<uint16_t> out = dvo.download(s), got(P * D), ref(P * D);
+        std::vector<float> lo = dlo.download(s), lo_ref(P);
+        oracle_merge_attn_states_lse(ref.data(), lo_ref.data(), va.data(), la.data(), vb.data(), lb.data(), T, NH, D, dt);
+        bool gaps = true;
+        for (size_t p = 0; p < P; ++p) {
+            std::memcpy(&got[p * D], &out[p * ho], D * 2);
+            for (int64_t j = D; j < ho; ++j) gaps = gaps && out[p * ho + j] == narrow(9.0f, dt);
+        }
+        char what[120];
+        std::snprintf(what, sizeof what, "merge_attn_states_lse_strided dtype=%d", dt);
+        const bool ok = st == ASTRA_OK && gaps && count_far(got, ref, dt) == 0 && count_far_lse(lo, lo_ref) == 0;
+        expect(ok, what);
+        if (ok) std::printf("c_abi: ok %s (gaps untouched)\n", what);
+    }
+    // fused_add_rmsnorm out of place on dense views equals the in-place oracle
+    {
+        const int64_t T = 19, H = 4096;
+        Rng g{uint64_t(6000 + dt)};
+        std::vector<uint16_t> x(T * H), r(T * H), w(H);
+        for (auto& v : x) v = narrow(g.normalish(), dt);
+        for (auto& v : r) v = narrow(2.0f * g.normalish(), dt);
+        for (auto& v : w) v = narrow(1.0f + 0.3f * g.normalish(), dt);
+        DevBuf<uint16_t> dx(x.size()), dr(r.size()), dw(w.size()), dy(x.size()), dro(r.size());
+        dx.upload(x, s);
+        dr.upload(r, s);
+        dw.upload(w, s);
+        astra_status_t st = astra_fused_add_rmsnorm_strided(dy.p, H, dro.p, H, dx.p, H, dr.p, H, dw.p, T, H, (astra_dtype_t)dt, 1e-6f, s);
+        std::vector<uint16_t> y = dy.download(s), res = dro.download(s), x_after = dx.download(s), y_ref = x, res_ref = r;
+        oracle_fused_add_rmsnorm(y_ref.data(), res_ref.data(), w.data(), T, H, dt, 1e-6f);
+        char what[120];
+        std::snprintf(what, sizeof what, "fused_add_rmsnorm_strided dtype=%d", dt);
+        const bool ok = st == ASTRA_OK && res == res_ref && x_after == x && count_far(y, y_ref, dt) == 0;
+        expect(ok, what);
+        if (ok) std::printf("c_abi: ok %s (inputs untouched, residual bit-exact)\n", what);
+    }
+}
+
+void check_host_queries()
+{
+    astra_launch_info_t li;
+    expect(astra_plan_fused_add_rmsnorm(32768, 8192, ASTRA_BF16, 1, &li) == ASTRA_OK && li.path == ASTRA_PATH_VECTOR &&
+               li.block == 1024 && li.grid == 32768,
+           "plan of the headline rmsnorm shape");
+    expect(astra_plan_silu_and_mul(3, 100, ASTRA_F16, 1, &li) == ASTRA_OK && li.path == ASTRA_PATH_GENERIC, "plan of an odd silu shape");
+    expect(astra_plan_merge_attn_states_lse(0, 4, 64, ASTRA_F16, 1, &li) == ASTRA_OK && li.path == ASTRA_PATH_NONE, "plan of an empty merge");
+    int clk = 0, bits = 0;
+    expect(astra_device_memory_info(0, &clk, &bits) == ASTRA_OK && clk > 0 && bits > 0, "device memory info");
+    std::printf("c_abi: ok host queries (memory clock %d kHz, bus %d bits)\n", clk, bits);
+}
+
 void check_errors(hipStream_t s)
 {
     DevBuf<uint16_t> a(4096), b(4096), c(4096);
@@ -286,7 +386,9 @@ int main()
     HIP_OK(hipStreamCreate(&s));  // a stream of the default priority that is not the null stream
 
     check_errors(s);
+    check_host_queries();
     for (int dt : {ASTRA_F16, ASTRA_BF16}) {
+        check_strided(dt, s);
         check_rmsnorm<uint16_t>(dt, 5, 4096, 1e-6f, s);
         check_rmsnorm<uint16_t>(dt, 300, 8192, 1e-5f, s);
         check_rmsnorm<uint16_t>(dt, 17, 5120, 1e-5f, s);

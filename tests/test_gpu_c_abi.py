@@ -24,4 +24,4 @@ def test_c_program_passes_all_checks():
     assert r.returncode == 0, f"check_abi exit status {r.returncode}"
     lines = r.stdout.strip().splitlines()
     assert lines[-1] == "c_abi: all checks passed"
-    assert sum(1 for l in lines if l.startswith("c_abi: ok ")) == 29 and not any("FAILED" in l for l in lines)
+    assert sum(1 for l in lines if l.startswith("c_abi: ok ")) == 36 and not any("FAILED" in l for l in lines)
