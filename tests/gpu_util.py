@@ -85,7 +85,7 @@ def assert_storage_close_to_real(got_bits, ref_real, dt, what):
     # a real value at or beyond (largest finite + half an ulp) of the storage type is stored as +-inf
     limit = {"f16": 65520.0, "bf16": float.fromhex("0x1.ffp127"), "f32": float.fromhex("0x1.ffffffp127")}[dt]
     ref_real = np.asarray(ref_real, np.float64)
-    ref_real = np.where(np.abs(ref_real) >= limit, np.sign(ref_real) * np.inf, ref_real)
+    ref_real = np.where(np.abs(ref_real) >= limit, np.copysign(np.inf, ref_real), ref_real)
     ok = close_mask(gv, ref_real, rtol, atol)
     if not ok.all():
         bad = np.argwhere(~ok)
