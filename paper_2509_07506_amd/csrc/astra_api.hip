@@ -28,38 +28,45 @@ astra_status_t after_launch() { return hipGetLastError() == hipSuccess ? ASTRA_O
 
 // ---- launches ---------------------------------------------------------------------------------------
 
-template <int DT, int VPT, int MAXT, bool LDS_TREE = false>
+// Launches the row kernel for one plan.  STRIDED = false: `input` / `residual` are updated in place and `y_out`, `r_out`,
+// `views` are ignored; STRIDED = true: x = `input`, r = `residual` are read through `views` (strides in vectors) and
+// the results go to y_out / r_out.  The ablation's reduction variant (LDS_TREE) is paced like the tuned kernel, so
+// that the two differ in the reduction only.
+template <int DT, int VPT, int MAXT, bool LDS_TREE = false, bool STRIDED = false>
 void launch_rmsnorm_row(const astra_launch_info_t& li, void* input, void* residual, const void* weight, int64_t T,
-                        int64_t H, float eps, hipStream_t stream)
+                        int64_t H, float eps, hipStream_t stream, void* y_out = nullptr, void* r_out = nullptr,
+                        RowViews views = RowViews{0, 0, 0, 0})
 {
     const uint32_t hv = (uint32_t)(H / Storage<DT>::kN);
     u32x4* const in = static_cast<u32x4*>(input);
     u32x4* const res = static_cast<u32x4*>(residual);
     const u32x4* const w = static_cast<const u32x4*>(weight);
+    u32x4* const yo = static_cast<u32x4*>(y_out);
+    u32x4* const ro = static_cast<u32x4*>(r_out);
     const dim3 grid((uint32_t)li.grid), block(li.block);
     const float inv_h = 1.0f / (float)H;
+    const int lc = li.log2_xcd_chunk;
     if (li.grid < T) {  // more rows than the grid limit: workgroups walk several rows
-        fused_add_rmsnorm_row_kernel<DT, VPT, MAXT, kNTLoad, kNTStore, LDS_TREE, true, kPaceNone>
-            <<<grid, block, 0, stream>>>(in, res, w, T, hv, inv_h, eps, li.log2_xcd_chunk);
+        fused_add_rmsnorm_row_kernel<DT, VPT, MAXT, kNTLoad, kNTStore, LDS_TREE, true, kPaceNone, STRIDED>
+            <<<grid, block, 0, stream>>>(in, res, w, T, hv, inv_h, eps, lc, yo, ro, views);
         return;
     }
-    // the ablation's reduction variant is paced like the tuned kernel, so that the two differ in the reduction only
     switch (li.pace) {
         case kPaceStoreGap:
-            fused_add_rmsnorm_row_kernel<DT, VPT, MAXT, kNTLoad, kNTStore, LDS_TREE, false, kPaceStoreGap>
-                <<<grid, block, 0, stream>>>(in, res, w, T, hv, inv_h, eps, li.log2_xcd_chunk);
+            fused_add_rmsnorm_row_kernel<DT, VPT, MAXT, kNTLoad, kNTStore, LDS_TREE, false, kPaceStoreGap, STRIDED>
+                <<<grid, block, 0, stream>>>(in, res, w, T, hv, inv_h, eps, lc, yo, ro, views);
             return;
         case kPaceWeightFirst | kPaceXBeforeR:
-            fused_add_rmsnorm_row_kernel<DT, VPT, MAXT, kNTLoad, kNTStore, LDS_TREE, false, kPaceWeightFirst | kPaceXBeforeR>
-                <<<grid, block, 0, stream>>>(in, res, w, T, hv, inv_h, eps, li.log2_xcd_chunk);
+            fused_add_rmsnorm_row_kernel<DT, VPT, MAXT, kNTLoad, kNTStore, LDS_TREE, false, kPaceWeightFirst | kPaceXBeforeR, STRIDED>
+                <<<grid, block, 0, stream>>>(in, res, w, T, hv, inv_h, eps, lc, yo, ro, views);
             return;
         case kPaceXBeforeR:
-            fused_add_rmsnorm_row_kernel<DT, VPT, MAXT, kNTLoad, kNTStore, LDS_TREE, false, kPaceXBeforeR>
-                <<<grid, block, 0, stream>>>(in, res, w, T, hv, inv_h, eps, li.log2_xcd_chunk);
+            fused_add_rmsnorm_row_kernel<DT, VPT, MAXT, kNTLoad, kNTStore, LDS_TREE, false, kPaceXBeforeR, STRIDED>
+                <<<grid, block, 0, stream>>>(in, res, w, T, hv, inv_h, eps, lc, yo, ro, views);
             return;
         default:
-            fused_add_rmsnorm_row_kernel<DT, VPT, MAXT, kNTLoad, kNTStore, LDS_TREE, false, kPaceNone>
-                <<<grid, block, 0, stream>>>(in, res, w, T, hv, inv_h, eps, li.log2_xcd_chunk);
+            fused_add_rmsnorm_row_kernel<DT, VPT, MAXT, kNTLoad, kNTStore, LDS_TREE, false, kPaceNone, STRIDED>
+                <<<grid, block, 0, stream>>>(in, res, w, T, hv, inv_h, eps, lc, yo, ro, views);
             return;
     }
 }
@@ -192,27 +199,6 @@ void launch_merge_kway(const astra_launch_info_t& li, void* v_out, float* lse_ou
         (uint32_t)(pairs * dvec), (uint32_t)pairs, dvec, log2_dvec, make_fastdiv(dvec), li.log2_xcd_chunk);
 }
 
-template <int DT, int VPT>
-void launch_rmsnorm_strided_row(const astra_launch_info_t& li, void* y_out, void* r_out, const void* x, const void* r,
-                                const void* weight, const RowViews& ev, int64_t T, int64_t H, float eps, hipStream_t stream)
-{
-    constexpr int N = Storage<DT>::kN;
-    const RowViews vv{ev.y_stride / N, ev.r_out_stride / N, ev.x_stride / N, ev.r_stride / N};
-    const uint32_t hv = (uint32_t)(H / N);
-    if (li.grid >= T)
-        fused_add_rmsnorm_strided_row_kernel<DT, VPT, 1024, kNTLoad, kNTStore, false>
-            <<<dim3((uint32_t)li.grid), dim3(li.block), 0, stream>>>(
-                static_cast<u32x4*>(y_out), static_cast<u32x4*>(r_out), static_cast<const u32x4*>(x),
-                static_cast<const u32x4*>(r), static_cast<const u32x4*>(weight), vv, T, hv, 1.0f / (float)H, eps,
-                li.log2_xcd_chunk);
-    else
-        fused_add_rmsnorm_strided_row_kernel<DT, VPT, 1024, kNTLoad, kNTStore, true>
-            <<<dim3((uint32_t)li.grid), dim3(li.block), 0, stream>>>(
-                static_cast<u32x4*>(y_out), static_cast<u32x4*>(r_out), static_cast<const u32x4*>(x),
-                static_cast<const u32x4*>(r), static_cast<const u32x4*>(weight), vv, T, hv, 1.0f / (float)H, eps,
-                li.log2_xcd_chunk);
-}
-
 // `ev` holds the row strides in elements
 template <int DT>
 void launch_rmsnorm_strided(const astra_launch_info_t& li, void* y_out, void* r_out, const void* x, const void* r,
@@ -225,10 +211,14 @@ void launch_rmsnorm_strided(const astra_launch_info_t& li, void* y_out, void* r_
             static_cast<const E*>(weight), ev, T, H, 1.0f / (float)H, eps);
         return;
     }
+    constexpr int N = Storage<DT>::kN;
+    const RowViews vv{ev.y_stride / N, ev.r_out_stride / N, ev.x_stride / N, ev.r_stride / N};
+    void* const xin = const_cast<void*>(x);  // read only when STRIDED
+    void* const rin = const_cast<void*>(r);
     switch (li.vectors_per_lane) {
-        case 1: launch_rmsnorm_strided_row<DT, 1>(li, y_out, r_out, x, r, weight, ev, T, H, eps, stream); break;
-        case 2: launch_rmsnorm_strided_row<DT, 2>(li, y_out, r_out, x, r, weight, ev, T, H, eps, stream); break;
-        default: launch_rmsnorm_strided_row<DT, 4>(li, y_out, r_out, x, r, weight, ev, T, H, eps, stream); break;
+        case 1: launch_rmsnorm_row<DT, 1, 1024, false, true>(li, xin, rin, weight, T, H, eps, stream, y_out, r_out, vv); break;
+        case 2: launch_rmsnorm_row<DT, 2, 1024, false, true>(li, xin, rin, weight, T, H, eps, stream, y_out, r_out, vv); break;
+        default: launch_rmsnorm_row<DT, 4, 1024, false, true>(li, xin, rin, weight, T, H, eps, stream, y_out, r_out, vv); break;
     }
 }
 

@@ -35,12 +35,21 @@ __device__ __forceinline__ void arrive(u32x4 (&v)[VPT])
     for (int k = 0; k < VPT; ++k) asm volatile("" : "+v"(v[k]));
 }
 
+// STRIDED = false: dense in-place operator; `input` and `residual` are read and overwritten, `views`, `y_out` and
+// `r_out` are not looked at.  STRIDED = true: rows of x (= `input`), r (= `residual`), y_out and r_out start
+// views.*_stride vectors apart and the results go to y_out / r_out (which may be the input views themselves).
+struct RowViews {
+    int64_t y_stride, r_out_stride, x_stride, r_stride;
+};
+
 template <int DT, int VPT, int MAX_THREADS, bool NTL, bool NTS, bool LDS_TREE = false, bool ROW_LOOP = false,
-          int PACE = kPaceNone>
+          int PACE = kPaceNone, bool STRIDED = false>
 __global__ __launch_bounds__(MAX_THREADS) void fused_add_rmsnorm_row_kernel(u32x4* input, u32x4* residual,
                                                                             const u32x4* __restrict__ weight,
                                                                             int64_t T, uint32_t hv, float inv_h, float eps,
-                                                                            int log2_chunk)
+                                                                            int log2_chunk, u32x4* y_out = nullptr,
+                                                                            u32x4* r_out = nullptr,
+                                                                            RowViews views = RowViews{0, 0, 0, 0})
 {
     constexpr int N = Storage<DT>::kN;
     __shared__ float partials[2][16];
@@ -62,8 +71,10 @@ __global__ __launch_bounds__(MAX_THREADS) void fused_add_rmsnorm_row_kernel(u32x
 
     int64_t row = first_row;
     do {
-        u32x4* xrow = input + row * hv;
-        u32x4* rrow = residual + row * hv;
+        const u32x4* xrow = input + row * (STRIDED ? views.x_stride : (int64_t)hv);
+        const u32x4* rrow = residual + row * (STRIDED ? views.r_stride : (int64_t)hv);
+        u32x4* yrow = STRIDED ? y_out + row * views.y_stride : input + row * hv;
+        u32x4* sumrow = STRIDED ? r_out + row * views.r_out_stride : residual + row * hv;
         u32x4 xv[VPT], rv[VPT];
 #pragma unroll
         for (int k = 0; k < VPT; ++k) {
@@ -97,7 +108,7 @@ __global__ __launch_bounds__(MAX_THREADS) void fused_add_rmsnorm_row_kernel(u32x
                     s[k][e] = x[e] + r[e];
                     acc += s[k][e] * s[k][e];
                 }
-                store_vec<NTS>(rrow + v, pack_vec<DT>(s[k]));
+                store_vec<NTS>(sumrow + v, pack_vec<DT>(s[k]));
             }
         }
 
@@ -113,7 +124,7 @@ __global__ __launch_bounds__(MAX_THREADS) void fused_add_rmsnorm_row_kernel(u32x
                 unpack_vec<DT>(wv[k], w);
 #pragma unroll
                 for (int e = 0; e < N; ++e) y[e] = (s[k][e] * scale) * w[e];
-                store_vec<NTS>(xrow + v, pack_vec<DT>(y));
+                store_vec<NTS>(yrow + v, pack_vec<DT>(y));
             }
         }
         row += gridDim.x;
@@ -153,80 +164,8 @@ __global__ __launch_bounds__(256) void fused_add_rmsnorm_generic_kernel(typename
 }
 
 // ---------------------------------------------------------------------------------------------
-// Row-strided, out-of-place form: separate input and output views, each with its own row stride (in
-// vectors for the fast kernel, in elements for the element-wise one).  Same structure as the kernels
-// above (ROW_LOOP as there); y_out == x and r_out == r (same strides) is the in-place operator.
-
-struct RowViews {
-    int64_t y_stride, r_out_stride, x_stride, r_stride;
-};
-
-template <int DT, int VPT, int MAX_THREADS, bool NTL, bool NTS, bool ROW_LOOP>
-__global__ __launch_bounds__(MAX_THREADS) void fused_add_rmsnorm_strided_row_kernel(u32x4* y_out, u32x4* r_out,
-                                                                                    const u32x4* x, const u32x4* r,
-                                                                                    const u32x4* __restrict__ weight,
-                                                                                    RowViews sv, int64_t T, uint32_t hv,
-                                                                                    float inv_h, float eps, int log2_chunk)
-{
-    constexpr int N = Storage<DT>::kN;
-    __shared__ float partials[2][16];
-    const int nwaves = blockDim.x >> 6;
-    const int64_t first_row = xcd_chunked(blockIdx.x, log2_chunk);
-    if (first_row >= T) return;
-    int parity = 0;
-    u32x4 wv[VPT];
-#pragma unroll
-    for (int k = 0; k < VPT; ++k) {
-        const uint32_t v = threadIdx.x + k * blockDim.x;
-        if (v < hv) wv[k] = weight[v];
-    }
-    int64_t row = first_row;
-    do {
-        const u32x4* xrow = x + row * sv.x_stride;
-        const u32x4* rrow = r + row * sv.r_stride;
-        u32x4 xv[VPT], rv[VPT];
-#pragma unroll
-        for (int k = 0; k < VPT; ++k) {
-            const uint32_t v = threadIdx.x + k * blockDim.x;
-            if (v < hv) {
-                xv[k] = load_vec<NTL>(xrow + v);
-                rv[k] = load_vec<NTL>(rrow + v);
-            }
-        }
-        float s[VPT][N];
-        float acc = 0.0f;
-#pragma unroll
-        for (int k = 0; k < VPT; ++k) {
-            const uint32_t v = threadIdx.x + k * blockDim.x;
-            if (v < hv) {
-                float xf[N], rf[N];
-                unpack_vec<DT>(xv[k], xf);
-                unpack_vec<DT>(rv[k], rf);
-#pragma unroll
-                for (int e = 0; e < N; ++e) {
-                    s[k][e] = xf[e] + rf[e];
-                    acc += s[k][e] * s[k][e];
-                }
-                store_vec<NTS>(r_out + row * sv.r_out_stride + v, pack_vec<DT>(s[k]));
-            }
-        }
-        const float total = block_sum(acc, partials[parity], nwaves);
-        const float scale = fast_rsqrt(total * inv_h + eps);
-#pragma unroll
-        for (int k = 0; k < VPT; ++k) {
-            const uint32_t v = threadIdx.x + k * blockDim.x;
-            if (v < hv) {
-                float w[N], y[N];
-                unpack_vec<DT>(wv[k], w);
-#pragma unroll
-                for (int e = 0; e < N; ++e) y[e] = (s[k][e] * scale) * w[e];
-                store_vec<NTS>(y_out + row * sv.y_stride + v, pack_vec<DT>(y));
-            }
-        }
-        row += gridDim.x;
-        parity ^= 1;
-    } while (ROW_LOOP && row < T);
-}
+// Row-strided, out-of-place form, element-wise path (the fast path is the row kernel above with STRIDED = true):
+// separate input and output views, each with its own row stride in elements.
 
 template <int DT>
 __global__ __launch_bounds__(256) void fused_add_rmsnorm_strided_generic_kernel(
