@@ -115,8 +115,8 @@ inline bool rmsnorm_row_plan(int64_t hv, RowPlan* plan)
     return true;
 }
 
-// When the waves of the row kernel issue their requests (fused_add_rmsnorm_kernels.h, PACE).  Few rows: nothing is
-// held back (the shortest dependent chain).  Streaming grids: measured on MI355X with T*H = 2^28 16-bit elements,
+// When the waves of the row kernel issue their requests (fused_add_rmsnorm_kernels.h, PACE).  Streaming grids (three
+// rounds of resident workgroups or more; smaller grids further down): measured on MI355X with T*H = 2^28 16-bit elements,
 // microseconds per launch averaged over 16 placements of x and r inside one 6 GiB allocation (10 for the two-vector
 // rows), worst placement in brackets; "gap" = output store held until the residual store has completed, "x" = x
 // arrived before r is requested, "w,x" = weight, then x, then r one after the other:
@@ -140,15 +140,71 @@ inline bool rmsnorm_row_plan(int64_t hv, RowPlan* plan)
 //   H = 32768   360 (372)   356 (365)   346 (355)   360 (365)     four vectors per lane
 // (floor at 8 TB/s: 268 us).  "gap" is never far from the best and has no bad case, so it is the default; the other
 // two are taken only where they measured at least 1.5 % better: "w,x" for rows of 256, 512 or 1024 vectors (4, 8,
-// 16 KiB) and for two-vector rows, "x" for rows of 384, 2048 and 4096 vectors.  Serialising x and r can lose 8 %
-// on other row lengths (H = 5120), and waiting for the weight 6 % (H = 28672), so neither is used outside the
-// measured cases.
-inline int rmsnorm_pace(int64_t T, int64_t hv, int vpt)
+// 16 KiB) and for two-vector rows, "x" for rows of 384, 2048 and 4096 vectors, and for 896 (H = 7168: level here,
+// 1-2 % better than the others on grids of 3 to 16 rounds).  Serialising x and r can lose 8 % on other row lengths
+// (H = 5120), and waiting for the weight 6 % (H = 28672), so neither is used outside the measured cases.
+// Rows measured later in the same way, same columns: H = 1536: 341 (351), 337 (347), 333 (340), 330 (334);
+// H = 2560: 331 (337), 328 (338), 322 (328), 334 (336); H = 7680: 332 (340), 332 (335), 332 (336), 330 (332); H = 3584,
+// 4608 and 6656 level within 1 %.  "x" is taken for 192, 320 and 960 vectors as well (1-2.5 % better than "none"
+// and "gap" on grids of 3 to 16 rounds too).
+// The gap lengthens every workgroup's life by one store round trip, which the end of the grid pays once: about a
+// microsecond whatever the size (H = 1024: 23.5 against 22.5 at T = 16384, 84.0 against 82.6 at T = 65536), so under
+// kGapMinRounds rounds of resident workgroups the default is "none".
+constexpr int kGapMinRounds = 32;
+
+inline int rmsnorm_stream_pace(int64_t hv, int vpt, bool long_grid)
 {
-    if (T < kRowChunkMinRows) return kPaceNone;
-    if (hv == 384 || hv == 2048 || hv == 4096) return kPaceXBeforeR;
+    if (hv == 192 || hv == 320 || hv == 384 || hv == 896 || hv == 960 || hv == 2048 || hv == 4096) return kPaceXBeforeR;
     if (vpt == 2 || hv == 256 || hv == 512 || hv == 1024) return kPaceWeightFirst | kPaceXBeforeR;
-    return kPaceStoreGap;
+    return long_grid ? kPaceStoreGap : kPaceNone;
+}
+
+// Grids of a few rounds.  Time is a staircase in n = ceil(T / 256), the most rows any of the 256 compute units
+// gets, and what decides the best variant is how many bytes of x and r one compute unit has requested at once,
+// n * (row bytes) * 2 (measured on MI355X for 16 row lengths from 1024 to 16384 16-bit elements, T in steps of
+// 5 % of a round, two placements of x and r; microseconds per launch, cold):
+//   * under 48 KiB per compute unit nothing is held back (the shortest dependent chain);
+//   * from there up to three rounds of resident workgroups, "x" (x arrived before r is requested) is 10-18 %
+//     faster where the compute units are just full (T = 1024, H = 4096: 6.6 against 7.7; T = 2048, H = 2048: 6.3
+//     against 7.6; T = 768, H = 8192: 10.5 against 11.5) and within +-5 % elsewhere;
+//   * rows that no longer fit at once (n above the resident workgroups per compute unit: 64 KiB requested) but
+//     stay within 88 KiB per compute unit run 10-17 % faster in half-sized workgroups with two vectors per lane,
+//     all resident at once (T = 1280, H = 4096: 7.8 against 9.1; T = 1024, H = 5120: 7.7 against 9.2; T = 1536,
+//     H = 3072: 7.0 against 8.4; T = 2560, H = 2048: 7.8 against 8.9); past 88 KiB they are 3-9 % slower.
+//     Workgroups of 5 and 10 waves hold one fewer per compute unit than their lane count allows (the step in the
+//     measured times comes one row earlier), so H = 2560 and H = 5120 switch one row earlier;
+//   * from three rounds on, the streaming policy above.
+constexpr int kCus = 256;
+constexpr int64_t kPaceMinBytesPerCu = 48 << 10;
+constexpr int64_t kHalfBlockMaxBytesPerCu = 88 << 10;
+constexpr int kStreamingRounds = 3;
+
+inline int resident_row_blocks(int block)
+{
+    const int by_lanes = 2048 / block;
+    return (block == 320 || block == 640) ? by_lanes - 1 : by_lanes;
+}
+
+// vectors per lane, lanes and pacing of the row kernel for T rows of hv vectors (row_bytes each)
+inline bool rmsnorm_row_policy(int64_t T, int64_t hv, int64_t row_bytes, RowPlan* plan, int* pace)
+{
+    if (!rmsnorm_row_plan(hv, plan)) return false;
+    const int64_t n = (T + kCus - 1) / kCus;
+    const int64_t resident = resident_row_blocks(plan->block);
+    // n * row_bytes * 2 without overflow: the comparisons only matter below 2^17
+    const int64_t per_cu = n > (int64_t(1) << 20) ? std::numeric_limits<int64_t>::max() : n * row_bytes * 2;
+    if (per_cu < kPaceMinBytesPerCu) {
+        *pace = kPaceNone;
+    } else if (plan->vpt == 1 && plan->block >= 2 * kWave && n > resident && per_cu <= kHalfBlockMaxBytesPerCu) {
+        plan->vpt = 2;
+        plan->block = round_up((int)((hv + 1) / 2), kWave);
+        *pace = kPaceXBeforeR;
+    } else if (n < kStreamingRounds * resident) {
+        *pace = kPaceXBeforeR;
+    } else {
+        *pace = rmsnorm_stream_pace(hv, plan->vpt, n >= kGapMinRounds * resident);
+    }
+    return true;
 }
 
 inline astra_status_t plan_rmsnorm(int64_t T, int64_t H, int eb, bool aligned16, astra_launch_info_t* info)
@@ -159,10 +215,11 @@ inline astra_status_t plan_rmsnorm(int64_t T, int64_t H, int eb, bool aligned16,
     *info = astra_launch_info_t{ASTRA_PATH_NONE, 0, 0, 0, 0, 0, 0};
     if (T == 0) return ASTRA_OK;
     RowPlan rp;
-    if (aligned16 && H % ne == 0 && rmsnorm_row_plan(H / ne, &rp)) {
+    int pace = kPaceNone;
+    if (aligned16 && H % ne == 0 && rmsnorm_row_policy(T, H / ne, H * eb, &rp, &pace)) {
         const int64_t rows = T < kMaxRowGrid ? T : kMaxRowGrid;
         const int lc = fit_chunk_log2(rows, kRowChunkBytesLog2 - floor_log2(H * eb), kRowChunkMinRows);
-        const int pace = T < kMaxRowGrid ? rmsnorm_pace(T, H / ne, rp.vpt) : kPaceNone;  // the row-loop kernel is not paced
+        if (T >= kMaxRowGrid) pace = kPaceNone;  // the row-loop kernel is not paced
         *info = astra_launch_info_t{ASTRA_PATH_VECTOR, rp.block, rp.vpt, lc, T < kMaxRowGrid ? pad_grid(rows, lc) : rows, pace, 0};
     } else {
         *info = astra_launch_info_t{ASTRA_PATH_GENERIC, 256, 0, 0, T < kMaxGenericGrid ? T : kMaxGenericGrid, 0, 0};

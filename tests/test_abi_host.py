@@ -168,14 +168,31 @@ def test_rmsnorm_plans(A):
     big = plan(1 << 23, 64)                                            # row loop beyond the grid limit
     assert big["grid"] == 1 << 21 and big["grid"] % (8 << big["log2_xcd_chunk"]) == 0
     assert A.astra_plan_fused_add_rmsnorm(-1, 8, True)[0] == 2
-    # request pacing: none for few rows and for the row-loop kernel, "store gap" (4) by default on streaming grids,
-    # weight-then-x-then-r (1 | 2) for 4 KiB / 16 KiB rows and for two-vector rows
-    assert plan(1023, 8192)["pace"] == 0 and big["pace"] == 0
+    # request pacing: none while a compute unit requests under 48 KiB at once and for the row-loop kernel; on streaming
+    # grids (three rounds or more) "store gap" (4) by default on long grids, weight-then-x-then-r (1 | 2) for 4 KiB / 16 KiB rows and
+    # for two-vector rows, x-then-r (2) for some row lengths
+    assert plan(255, 8192)["pace"] == 0 and plan(512, 4096)["pace"] == 0 and big["pace"] == 0
     assert plan(32768, 8192)["pace"] == 3 and plan(32768, 2048)["pace"] == 3 and plan(4096, 11008)["pace"] == 3
     assert plan(32768, 4096)["pace"] == 3 and plan(4096, 16384)["pace"] == 2
-    assert plan(4099, 5120)["pace"] == 4 and plan(2048, 28672)["pace"] == 4 and plan(32768, 1024)["pace"] == 4
+    assert plan(32768, 5120)["pace"] == 4 and plan(16384, 28672)["pace"] == 4 and plan(1 << 20, 1024)["pace"] == 4
+    # ... but only where the gap's extra microsecond at the end of the grid is small change (32 rounds or more)
+    assert plan(4099, 5120)["pace"] == 0 and plan(2048, 28672)["pace"] == 0 and plan(32768, 1024)["pace"] == 0
     assert plan(2048, 3072)["pace"] == 2 and plan(2048, 32768)["pace"] == 2
     assert plan(2048, 11008)["vectors_per_lane"] == 2 and plan(2048, 28672)["vectors_per_lane"] == 4
+    assert plan(4099, 7168)["pace"] == 2
+    # grids of under three rounds: x-then-r once a compute unit requests 48 KiB at once ...
+    for T, H in [(1023, 8192), (512, 8192), (768, 8192), (1024, 4096), (2048, 4096), (2048, 2048), (1024, 7168)]:
+        p = plan(T, H)
+        assert p["pace"] == 2 and p["vectors_per_lane"] == 1, (T, H)
+    # ... and half-sized workgroups with two vectors per lane where the rows no longer fit at once but stay within
+    # 88 KiB per compute unit
+    for T, H, block in [(1280, 4096, 256), (1024, 5120, 320), (768, 5120, 320), (1536, 3072, 192), (2560, 2048, 128),
+                        (768, 6144, 384), (600, 7168, 448), (5000, 1024, 64)]:
+        p = plan(T, H)
+        assert (p["vectors_per_lane"], p["block"], p["pace"]) == (2, block, 2), (T, H, p)
+    for T, H in [(1024, 4096), (1536, 4096), (1024, 8192), (768, 8192), (3072, 2048), (512, 5120), (1280, 5120)]:
+        assert plan(T, H)["vectors_per_lane"] == 1, (T, H)
+    assert A.astra_plan_fused_add_rmsnorm(1280, 2048, True, dtype=A.ASTRA_F32)[1].as_dict()["vectors_per_lane"] == 2
     assert A.astra_plan_fused_add_rmsnorm(32768, 4096, True, dtype=A.ASTRA_F32)[1].as_dict()["pace"] == 3   # 16 KiB rows
     assert A.astra_plan_fused_add_rmsnorm(32768, 8192, True, dtype=A.ASTRA_F32)[1].as_dict()["pace"] == 2   # 32 KiB rows
     assert A.astra_plan_silu_and_mul(4096, 14336, True)[1].as_dict()["pace"] == 0
