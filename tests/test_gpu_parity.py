@@ -139,8 +139,8 @@ def test_rmsnorm_tile_shapes(A, T, H, dt):
                                     (1024, 16384, "f16"), (1030, 28672, "bf16"), (1100, 20000, "f16"), (2050, 512, "bf16"),
                                     (1040, 4096, "bf16"), (1029, 3072, "f16"), (1024, 32768, "bf16")])
 def test_rmsnorm_streaming_grids(A, T, H, dt):
-    """From 1024 rows on the row kernel paces its requests (which wait goes where depends on the row length and on
-    the vectors per lane); the results must not depend on it."""
+    """On larger grids the row kernel paces its requests (which wait goes where depends on the row length, the
+    vectors per lane and the grid size); the results must not depend on it."""
     _say(f"[parity] rmsnorm streaming T={T} H={H} {dt} plan={A.astra_plan_fused_add_rmsnorm(T, H, True)[1].as_dict()}")
     x, r, w = workloads.rmsnorm_inputs(T, H, dt, np.random.default_rng([11, T, H]), r_std=2.0)
     check_rmsnorm(A, x, r, w, 1e-5, dt, f"rmsnorm T={T} H={H} {dt}")
