@@ -46,6 +46,9 @@ def _gaps_intact(whole, col0, H):
     (7, 4096, (4096 + 64, 4096 + 8, 8192, 4096 + 128), 0),        # fast path: strides and offsets multiples of 8
     (300, 5120, (5120 + 8, 5120 + 8, 5120 + 8, 5120 + 8), 8),
     (33, 11008, (11008 + 16, 11008, 11008 + 24, 22016), 0),        # long rows (4 vectors per lane)
+    (1280, 4096, (4096 + 8, 4096 + 16, 4096 + 8, 4096), 0),        # half-sized workgroups, two vectors per lane
+    (700, 8192, (8192 + 8, 8192, 8192 + 8, 8192 + 8), 8),          # x requested before r
+    (1100, 2048, (2048 + 64, 2048 + 8, 2048, 2048 + 8), 0),        # launch order in chunks
     (5, 4096, (4096 + 3, 4096 + 8, 4096 + 8, 4096 + 8), 0),        # odd stride: element-wise path
     (5, 4100, (4100 + 4, 4100, 4111, 4100 + 1), 1),                # odd everything
     (1, 4096, (4096, 4096, 4096, 4096), 0),
