@@ -173,6 +173,10 @@ inline int rmsnorm_stream_pace(int64_t hv, int vpt, bool long_grid)
 //     H = 3072: 7.0 against 8.4; T = 2560, H = 2048: 7.8 against 8.9); past 88 KiB they are 3-9 % slower.
 //     Workgroups of 5 and 10 waves hold one fewer per compute unit than their lane count allows (the step in the
 //     measured times comes one row earlier), so H = 2560 and H = 5120 switch one row earlier;
+//   * two-vector rows of 20 KiB or more that fill the compute units exactly (n = 2: two 640- to 1024-lane workgroups
+//     each) are faster with four vectors per lane in half-sized workgroups, half as many waves with the same bytes
+//     requested: T = 512: H = 14336 10.9 against 12.0, H = 12288 9.2 against 10.3, H = 16384 12.9 against 13.2;
+//     T = 307: level to 5 %; 18 KiB rows (H = 9216) lose 0-5 % and n = 1 or n = 3 gain nothing, so only there;
 //   * from three rounds on, the streaming policy above.
 constexpr int kCus = 256;
 constexpr int64_t kPaceMinBytesPerCu = 48 << 10;
@@ -198,6 +202,10 @@ inline bool rmsnorm_row_policy(int64_t T, int64_t hv, int64_t row_bytes, RowPlan
     } else if (plan->vpt == 1 && plan->block >= 2 * kWave && n > resident && per_cu <= kHalfBlockMaxBytesPerCu) {
         plan->vpt = 2;
         plan->block = round_up((int)((hv + 1) / 2), kWave);
+        *pace = kPaceXBeforeR;
+    } else if (plan->vpt == 2 && hv >= 1280 && n == 2) {
+        plan->vpt = 4;
+        plan->block = round_up((int)((hv + 3) / 4), kWave);
         *pace = kPaceXBeforeR;
     } else if (n < kStreamingRounds * resident) {
         *pace = kPaceXBeforeR;

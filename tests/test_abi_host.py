@@ -192,6 +192,12 @@ def test_rmsnorm_plans(A):
         assert (p["vectors_per_lane"], p["block"], p["pace"]) == (2, block, 2), (T, H, p)
     for T, H in [(1024, 4096), (1536, 4096), (1024, 8192), (768, 8192), (3072, 2048), (512, 5120), (1280, 5120)]:
         assert plan(T, H)["vectors_per_lane"] == 1, (T, H)
+    # two-vector rows that fill the compute units exactly: four vectors per lane in half-sized workgroups
+    for T, H, block in [(512, 14336, 448), (300, 12288, 384), (512, 16384, 512), (400, 10240, 320)]:
+        p = plan(T, H)
+        assert (p["vectors_per_lane"], p["block"], p["pace"]) == (4, block, 2), (T, H, p)
+    for T, H in [(256, 14336), (513, 14336), (512, 9216), (1024, 16384)]:
+        assert plan(T, H)["vectors_per_lane"] == 2, (T, H)
     assert A.astra_plan_fused_add_rmsnorm(1280, 2048, True, dtype=A.ASTRA_F32)[1].as_dict()["vectors_per_lane"] == 2
     assert A.astra_plan_fused_add_rmsnorm(32768, 4096, True, dtype=A.ASTRA_F32)[1].as_dict()["pace"] == 3   # 16 KiB rows
     assert A.astra_plan_fused_add_rmsnorm(32768, 8192, True, dtype=A.ASTRA_F32)[1].as_dict()["pace"] == 2   # 32 KiB rows

@@ -150,11 +150,13 @@ def test_rmsnorm_streaming_grids(A, T, H, dt):
                                              (1537, 3072, "f16", 2, 2), (2560, 2048, "bf16", 2, 2), (5000, 1024, "f16", 2, 2),
                                              (700, 5000, "bf16", 2, 2), (760, 6136, "f16", 2, 2),
                                              (768, 8192, "bf16", 1, 2), (1024, 4096, "f16", 1, 2), (2047, 2048, "bf16", 1, 2),
-                                             (500, 7168, "f16", 1, 2), (1100, 7680, "bf16", 1, 2), (2000, 5120, "f16", 1, 0)])
+                                             (500, 7168, "f16", 1, 2), (1100, 7680, "bf16", 1, 2), (2000, 5120, "f16", 1, 0),
+                                             (512, 14336, "f16", 4, 2), (300, 12288, "bf16", 4, 2), (500, 11000, "bf16", 4, 2)])
 def test_rmsnorm_grids_of_few_rounds(A, T, H, dt, vpt, pace):
     """Grids of one to three rounds of resident workgroups: x is requested before r, and rows that just no longer fit
     at once go to half-sized workgroups with two vectors per lane (also where the last vector of a lane falls off
-    the end of the row); the results must not depend on any of it."""
+    the end of the row), two-vector rows that fill the machine exactly to four; the results must not depend on any
+    of it."""
     plan = A.astra_plan_fused_add_rmsnorm(T, H, True)[1].as_dict()
     _say(f"[parity] rmsnorm few rounds T={T} H={H} {dt} plan={plan}")
     assert (plan["vectors_per_lane"], plan["pace"]) == (vpt, pace)
