@@ -591,6 +591,52 @@ def run_decode(args):
         torch.cuda.empty_cache()
 
 
+def run_prefill(args):
+    """Prefill-chunk shapes (workloads.PREFILL_CASES: T of 512 to 4096 at LLaMA-7B/13B/70B dimensions) replayed from
+    a HIP graph, cold: every graph holds 100 launches rotating over enough buffer sets that one rotation moves at
+    least 1 GiB; microseconds per launch averaged over 10 replays."""
+    import torch
+
+    import paper_2509_07506_amd as astra
+    import workloads
+
+    astra.load_library()
+    torch.cuda.set_device(0)
+    per_graph, reps = 100, 10
+    for n in sorted(workloads.PREFILL_CASES, key=lambda s: (s.split("_")[1], workloads.case(s).algorithmic_bytes())):
+        c = workloads.case(n)
+        nsets = min(per_graph, max(2, -(-(1 << 30) // c.algorithmic_bytes()) + 1))
+        L = Launcher(astra, c, c.generate(), nsets)
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            for k in range(nsets):
+                L.launch(side.cuda_stream, k)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            sh = torch.cuda.current_stream().cuda_stream
+            for k in range(per_graph):
+                L.launch(sh, k)
+        for _ in range(2):
+            g.replay()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / (reps * per_graph)
+        gbs = c.algorithmic_bytes() / us / 1e3
+        print(json.dumps({"case": n, "mode": "hip graph replay, cold", "buffer_sets": nsets, "us_per_launch": round(us, 2),
+                          "bytes": c.algorithmic_bytes(), "GBs": round(gbs, 1), "frac_of_peak": round(gbs / HBM_PEAK_GBS, 4),
+                          "launch": L.plan}), flush=True)
+        del g, L
+        torch.cuda.empty_cache()
+
+
 def run_ceiling(args):
     """Streaming ceiling of this machine with the operators' access pattern: astra_stream_copy over
     512 MiB, alternating between two source/destination pairs (2 GiB footprint, so always cold)."""
@@ -731,6 +777,7 @@ def main():
     ap.add_argument("--ceiling", action="store_true", help="measure the streaming-copy ceiling of the machine")
     ap.add_argument("--kway", action="store_true", help="K-way merge vs a chain of two-way merges")
     ap.add_argument("--decode", action="store_true", help="decode-sized launches replayed from a HIP graph")
+    ap.add_argument("--prefill", action="store_true", help="prefill-chunk shapes replayed from a HIP graph, cold")
     ap.add_argument("--vs-eager", action="store_true",
                     help="context: the step workloads through this library and through plain PyTorch tensor ops")
     ap.add_argument("--ablation", action="store_true",
@@ -742,6 +789,8 @@ def main():
         sys.exit(2)
     if args.vs_eager:
         run_vs_eager(args)
+    elif args.prefill:
+        run_prefill(args)
     elif args.decode:
         run_decode(args)
     elif args.kway:

@@ -184,13 +184,36 @@ def _f32_cases():
     ]
 
 
+def _prefill_cases():
+    """Prefill-chunk shapes (some hundreds to a few thousand tokens) at the dimensions of the models the paper names
+    for its shape selection (Section 6.1: LLaMA-7B, 13B and 70B): hidden 4096 / 5120 / 8192, intermediate 11008 /
+    13824 / 28672, 32 / 40 / 64 heads of 128.  Not benchmark configs: they exist to measure the grids of one to a
+    few rounds of resident workgroups; value recipes as in the benchmark configs of the same operator."""
+    out = []
+    k = 0
+    for H in (4096, 5120, 8192):
+        for T in (512, 1024, 2048, 4096):
+            out.append(Case(f"pf_rmsnorm_T{T}_H{H}_bf16", "rmsnorm", 7, k, "bf16", {"T": T, "H": H}, eps=1e-5, r_std=2.0))
+            k += 1
+    for d in (11008, 13824, 28672):
+        for T in (512, 2048):
+            out.append(Case(f"pf_silu_T{T}_d{d}_bf16", "silu", 7, k, "bf16", {"T": T, "d": d}))
+            k += 1
+    for NH in (32, 40, 64):
+        for T in (512, 2048):
+            out.append(Case(f"pf_merge_T{T}_NH{NH}_D128_bf16", "merge", 7, k, "bf16", {"T": T, "NH": NH, "D": 128}))
+            k += 1
+    return out
+
+
 CASES = {c.name: c for c in _cases()}
 PAPER_SHAPE_CASES = {c.name: c for c in _paper_shape_cases()}
 F32_CASES = {c.name: c for c in _f32_cases()}
+PREFILL_CASES = {c.name: c for c in _prefill_cases()}
 
 
 def case(name: str) -> Case:
-    for table in (CASES, PAPER_SHAPE_CASES, F32_CASES):
+    for table in (CASES, PAPER_SHAPE_CASES, F32_CASES, PREFILL_CASES):
         if name in table:
             return table[name]
     raise KeyError(name)
