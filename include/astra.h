@@ -18,8 +18,10 @@
  *     never touches the device.  T == 0 is valid and does nothing.
  *   - Pointers must be aligned to their element size (2 or 4 bytes, scores 4 bytes).  The fast path needs
  *     16-byte aligned pointers and a row length that is a multiple of 16 bytes (8 16-bit or 4 binary32
- *     elements); anything else is served by a slower element-wise path that computes the same thing (equal up
- *     to the order of binary32 roundings; the residual of fused_add_rmsnorm is bit-identical on both paths).
+ *     elements); anything else is served by slower paths that compute the same thing (16-byte accesses at
+ *     element alignment with the last, partial vector of a row element by element; plain element-wise kernels
+ *     for rows of more than 4096 vectors and inputs beyond 2^31 vectors).  Equal up to the order of binary32
+ *     roundings; the residual of fused_add_rmsnorm is bit-identical on every path.
  *   - Element counts (T*H, T*2d, T*num_heads*head_dim) may exceed 2^31; they must fit in int64.
  */
 #ifndef ASTRA_H

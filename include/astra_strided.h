@@ -21,7 +21,7 @@
  * any other overlap between an output and an input or between the two outputs is ASTRA_ERR_ALIAS
  * (overlap is judged on the bounding byte ranges of the views).  The fast path needs 16-byte aligned
  * pointers and H and all strides multiples of 16 bytes (8 16-bit or 4 binary32 elements); anything else takes the
- * element-wise path.
+ * ragged path of astra_fused_add_rmsnorm (rows of up to 4096 vectors) or the element-wise path.
  */
 #ifndef ASTRA_STRIDED_H
 #define ASTRA_STRIDED_H

@@ -44,7 +44,7 @@ class LaunchInfo(ctypes.Structure):
                 ("reserved", ctypes.c_int32)]
 
     def as_dict(self):
-        return {"path": {0: "none", 1: "vector", 2: "generic"}[self.path], "block": self.block,
+        return {"path": {0: "none", 1: "vector", 2: "generic", 3: "ragged"}[self.path], "block": self.block,
                 "vectors_per_lane": self.vectors_per_lane, "log2_xcd_chunk": self.log2_xcd_chunk, "grid": self.grid,
                 "pace": self.pace}
 

@@ -71,6 +71,32 @@ void launch_rmsnorm_row(const astra_launch_info_t& li, void* input, void* residu
     }
 }
 
+// `ev` holds the row strides in elements; in place: y_out = x, r_out = r
+template <int DT>
+void launch_rmsnorm_ragged(const astra_launch_info_t& li, void* y_out, void* r_out, const void* x, const void* r,
+                           const void* weight, const RowViews& ev, int64_t T, int64_t H, float eps, hipStream_t stream)
+{
+    typedef typename Storage<DT>::elem_t E;
+    const dim3 grid((uint32_t)li.grid), block(li.block);
+    const float inv_h = 1.0f / (float)H;
+    E* const y = static_cast<E*>(y_out);
+    E* const ro = static_cast<E*>(r_out);
+    const E* const xi = static_cast<const E*>(x);
+    const E* const ri = static_cast<const E*>(r);
+    const E* const w = static_cast<const E*>(weight);
+    switch (li.vectors_per_lane) {
+        case 1:
+            fused_add_rmsnorm_ragged_row_kernel<DT, 1, kNTLoad, kNTStore><<<grid, block, 0, stream>>>(y, ro, xi, ri, w, ev, T, H, inv_h, eps);
+            break;
+        case 2:
+            fused_add_rmsnorm_ragged_row_kernel<DT, 2, kNTLoad, kNTStore><<<grid, block, 0, stream>>>(y, ro, xi, ri, w, ev, T, H, inv_h, eps);
+            break;
+        default:
+            fused_add_rmsnorm_ragged_row_kernel<DT, 4, kNTLoad, kNTStore><<<grid, block, 0, stream>>>(y, ro, xi, ri, w, ev, T, H, inv_h, eps);
+            break;
+    }
+}
+
 template <int DT>
 void launch_rmsnorm(const astra_launch_info_t& li, void* input, void* residual, const void* weight, int64_t T, int64_t H,
                     float eps, int variant, hipStream_t stream)
@@ -98,6 +124,10 @@ void launch_rmsnorm(const astra_launch_info_t& li, void* input, void* residual, 
     if (li.path == ASTRA_PATH_GENERIC) {
         fused_add_rmsnorm_generic_kernel<DT><<<dim3((uint32_t)li.grid), dim3(li.block), 0, stream>>>(
             static_cast<E*>(input), static_cast<E*>(residual), static_cast<const E*>(weight), T, H, 1.0f / (float)H, eps);
+        return;
+    }
+    if (li.path == ASTRA_PATH_RAGGED) {
+        launch_rmsnorm_ragged<DT>(li, input, residual, input, residual, weight, RowViews{H, H, H, H}, T, H, eps, stream);
         return;
     }
     switch (li.vectors_per_lane) {
@@ -130,6 +160,12 @@ void launch_silu(const astra_launch_info_t& li, void* out, const void* in, int64
     if (li.path == ASTRA_PATH_GENERIC) {
         silu_and_mul_generic_kernel<DT><<<dim3((uint32_t)li.grid), dim3(li.block), 0, stream>>>(
             static_cast<E*>(out), static_cast<const E*>(in), T, d);
+        return;
+    }
+    if (li.path == ASTRA_PATH_RAGGED) {
+        const uint32_t dvr = (uint32_t)((d + Storage<DT>::kN - 1) / Storage<DT>::kN);
+        silu_and_mul_ragged_kernel<DT, kNTLoad, kNTStore><<<dim3((uint32_t)li.grid), dim3(256), 0, stream>>>(
+            static_cast<E*>(out), static_cast<const E*>(in), (uint32_t)(T * dvr), dvr, d, make_fastdiv(dvr));
         return;
     }
     const uint32_t dv = (uint32_t)(d / Storage<DT>::kN);
@@ -172,6 +208,13 @@ void launch_merge(const astra_launch_info_t& li, void* v_out, float* lse_out, co
             static_cast<E*>(v_out), lse_out, static_cast<const E*>(v_a), lse_a, static_cast<const E*>(v_b), lse_b, pairs, D);
         return;
     }
+    if (li.path == ASTRA_PATH_RAGGED) {
+        const uint32_t dvr = (uint32_t)((D + Storage<DT>::kN - 1) / Storage<DT>::kN);
+        merge_attn_states_lse_ragged_kernel<DT, kNTLoad, kNTStore><<<dim3((uint32_t)li.grid), dim3(256), 0, stream>>>(
+            static_cast<E*>(v_out), lse_out, static_cast<const E*>(v_a), lse_a, static_cast<const E*>(v_b), lse_b,
+            (uint32_t)(pairs * dvr), dvr, D, make_fastdiv(dvr));
+        return;
+    }
     const uint32_t dvec = (uint32_t)(D / Storage<DT>::kN);
     int log2_dvec = -1;
     if ((dvec & (dvec - 1)) == 0) log2_dvec = __builtin_ctz(dvec);
@@ -209,6 +252,10 @@ void launch_rmsnorm_strided(const astra_launch_info_t& li, void* y_out, void* r_
         fused_add_rmsnorm_strided_generic_kernel<DT><<<dim3((uint32_t)li.grid), dim3(256), 0, stream>>>(
             static_cast<E*>(y_out), static_cast<E*>(r_out), static_cast<const E*>(x), static_cast<const E*>(r),
             static_cast<const E*>(weight), ev, T, H, 1.0f / (float)H, eps);
+        return;
+    }
+    if (li.path == ASTRA_PATH_RAGGED) {
+        launch_rmsnorm_ragged<DT>(li, y_out, r_out, x, r, weight, ev, T, H, eps, stream);
         return;
     }
     constexpr int N = Storage<DT>::kN;
@@ -407,7 +454,7 @@ astra_status_t astra_merge_attn_states_lse_kway(void* v_out, float* lse_out, con
     if (!v_out || !lse_out || !v_parts || !lse_parts) return ASTRA_ERR_NULL;
     astra_launch_info_t li;
     const int eb = elem_bytes((int)dtype);
-    astra_status_t st = plan_merge(T, num_heads, head_dim, eb, aligned(v_out, 16) && aligned(v_parts, 16), &li);
+    astra_status_t st = plan_merge(T, num_heads, head_dim, eb, aligned(v_out, 16) && aligned(v_parts, 16), &li, false);
     if (st != ASTRA_OK) return st;
     const int64_t pairs = T * num_heads;
     int64_t part_elems = pairs * head_dim, all_elems;
@@ -476,7 +523,7 @@ astra_status_t astra_silu_and_mul_strided(void* out, int64_t out_stride, const v
     const int64_t ne = kVecBytes / eb;
     const bool fast = aligned(out, 16) && aligned(input, 16) && out_stride % ne == 0 && in_stride % ne == 0;
     astra_launch_info_t li;
-    astra_status_t st = plan_silu(T, d, eb, fast, &li);
+    astra_status_t st = plan_silu(T, d, eb, fast, &li, false);
     if (st != ASTRA_OK) return st;
     int64_t out_rows, in_rows;
     if (out_stride < d || in_stride < 2 * d || mul_overflows(T > 0 ? T - 1 : 0, out_stride, &out_rows) ||
@@ -520,7 +567,7 @@ astra_status_t astra_merge_attn_states_lse_strided(void* v_out, int64_t out_toke
     bool fast = true;
     for (int i = 0; i < 3; ++i) fast = fast && aligned(bases[i], 16) && ts[i] % ne == 0 && hs[i] % ne == 0;
     astra_launch_info_t li;
-    astra_status_t st = plan_merge(T, num_heads, head_dim, eb, fast, &li);
+    astra_status_t st = plan_merge(T, num_heads, head_dim, eb, fast, &li, false);
     if (st != ASTRA_OK) return st;
     int64_t span[3];  // bounding extent of each value view in bytes
     for (int i = 0; i < 3; ++i) {

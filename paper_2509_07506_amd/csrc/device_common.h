@@ -147,6 +147,63 @@ __device__ __forceinline__ float fast_rcp(float x) { return __builtin_amdgcn_rcp
 __device__ __forceinline__ float fast_rsqrt(float x) { return __builtin_amdgcn_rsqf(x); }
 
 // ---------------------------------------------------------------------------------------------
+// kN elements at element alignment (the "ragged" kernels: row lengths that are no multiple of a vector,
+// pointers that are only element aligned).  A 16-byte global access needs no 16-byte alignment on this
+// target (code objects for the HSA runtime run with unaligned access mode on, and the compiler itself turns
+// a 16-byte copy from a 2-byte-aligned address into one 128-bit instruction), so a full vector is still one
+// instruction; measured it streams at 91-95 % of the aligned rate.  The last, partial vector of a row is
+// touched element by element and never past `count`.
+
+typedef u32x4 u32x4_align2 __attribute__((aligned(2)));
+typedef u32x4 u32x4_align4 __attribute__((aligned(4)));
+
+template <int DT>
+struct ElemAlignedVec {
+    typedef u32x4_align2 type;
+};
+template <>
+struct ElemAlignedVec<kF32> {
+    typedef u32x4_align4 type;
+};
+
+// f[0, count) <- p[0, count) widened, f[count, kN) <- 0; 1 <= count <= kN
+template <int DT, bool NT>
+__device__ __forceinline__ void load_elems(const typename Storage<DT>::elem_t* p, int count, float (&f)[Storage<DT>::kN])
+{
+    constexpr int N = Storage<DT>::kN;
+    typedef typename ElemAlignedVec<DT>::type V;
+    if (count == N) {
+        u32x4 v;
+        if constexpr (NT) v = __builtin_nontemporal_load(reinterpret_cast<const V*>(p));
+        else v = *reinterpret_cast<const V*>(p);
+        unpack_vec<DT>(v, f);
+    } else {
+#pragma unroll
+        for (int e = 0; e < N; ++e) {
+            f[e] = 0.0f;
+            if (e < count) f[e] = Storage<DT>::widen(p[e]);
+        }
+    }
+}
+
+// p[0, count) <- f[0, count) narrowed; nothing past count is written
+template <int DT, bool NT>
+__device__ __forceinline__ void store_elems(typename Storage<DT>::elem_t* p, int count, const float (&f)[Storage<DT>::kN])
+{
+    constexpr int N = Storage<DT>::kN;
+    typedef typename ElemAlignedVec<DT>::type V;
+    if (count == N) {
+        const u32x4 v = pack_vec<DT>(f);
+        if constexpr (NT) __builtin_nontemporal_store(v, reinterpret_cast<V*>(p));
+        else *reinterpret_cast<V*>(p) = v;
+    } else {
+#pragma unroll
+        for (int e = 0; e < N; ++e)
+            if (e < count) p[e] = Storage<DT>::narrow(f[e]);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // index arithmetic
 
 // n / d for a 32-bit n and a fixed divisor d >= 1, as a multiply-high and two shifts (Granlund and

@@ -132,6 +132,73 @@ __global__ __launch_bounds__(MAX_THREADS) void fused_add_rmsnorm_row_kernel(u32x
     } while (ROW_LOOP && row < T);
 }
 
+// ---------------------------------------------------------------------------------------------
+// Ragged path: any H of up to 4096 vectors (the last vector of a row possibly partial), pointers and row strides only
+// element aligned; in place (y_out = x, r_out = r, strides H) or out of place.  One workgroup per row, rows
+// gridDim.x apart, the row in registers as in the row kernel above; full vectors are 16-byte accesses at element
+// alignment, the partial one goes element by element (zeros beyond the row, which add nothing to the sum).
+// A lane loads its elements of x and r before it stores to the same positions, so exact aliasing of an
+// output with an input is safe.  `sv` holds the row strides in elements.
+template <int DT, int VPT, bool NTL, bool NTS>
+__global__ __launch_bounds__(1024) void fused_add_rmsnorm_ragged_row_kernel(
+    typename Storage<DT>::elem_t* y_out, typename Storage<DT>::elem_t* r_out, const typename Storage<DT>::elem_t* x,
+    const typename Storage<DT>::elem_t* r, const typename Storage<DT>::elem_t* __restrict__ weight, RowViews sv, int64_t T,
+    int64_t H, float inv_h, float eps)
+{
+    constexpr int N = Storage<DT>::kN;
+    __shared__ float partials[2][16];
+    const int nwaves = blockDim.x >> 6;
+    int parity = 0;
+
+    int64_t e0[VPT];
+    int count[VPT];  // elements of this lane's k-th vector that lie inside the row: 0 .. N
+    u32x4 wv[VPT];
+#pragma unroll
+    for (int k = 0; k < VPT; ++k) {
+        e0[k] = (int64_t)(threadIdx.x + k * blockDim.x) * N;
+        count[k] = H - e0[k] >= N ? N : (H > e0[k] ? (int)(H - e0[k]) : 0);
+        float w[N] = {};
+        if (count[k] > 0) load_elems<DT, false>(weight + e0[k], count[k], w);
+        wv[k] = pack_vec<DT>(w);  // widening and narrowing again is exact
+    }
+
+    for (int64_t row = blockIdx.x; row < T; row += gridDim.x, parity ^= 1) {
+        const typename Storage<DT>::elem_t* xr = x + row * sv.x_stride;
+        const typename Storage<DT>::elem_t* rr = r + row * sv.r_stride;
+        typename Storage<DT>::elem_t* yr = y_out + row * sv.y_stride;
+        typename Storage<DT>::elem_t* sr = r_out + row * sv.r_out_stride;
+        float s[VPT][N];
+        float acc = 0.0f;
+#pragma unroll
+        for (int k = 0; k < VPT; ++k) {
+            if (count[k] > 0) {
+                float a[N], b[N];
+                load_elems<DT, NTL>(xr + e0[k], count[k], a);
+                load_elems<DT, NTL>(rr + e0[k], count[k], b);
+#pragma unroll
+                for (int e = 0; e < N; ++e) {
+                    s[k][e] = a[e] + b[e];
+                    acc += s[k][e] * s[k][e];
+                }
+                store_elems<DT, NTS>(sr + e0[k], count[k], s[k]);
+            }
+        }
+        const float total = block_sum(acc, partials[parity], nwaves);
+        const float scale = fast_rsqrt(total * inv_h + eps);
+#pragma unroll
+        for (int k = 0; k < VPT; ++k) {
+            if (count[k] > 0) {
+                float w[N], y[N];
+                unpack_vec<DT>(wv[k], w);
+#pragma unroll
+                for (int e = 0; e < N; ++e) y[e] = (s[k][e] * scale) * w[e];
+                store_elems<DT, NTS>(yr + e0[k], count[k], y);
+            }
+        }
+    }
+}
+
+
 // Element-wise path for any H and element-aligned pointers: two passes over the row.  The first pass
 // only reads (it needs the unrounded sums, so the residual cannot be written yet); the second
 // recomputes x + r, stores it and the normalised value.  Each element is read and written by the

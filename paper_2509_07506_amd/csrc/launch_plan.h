@@ -229,13 +229,19 @@ inline astra_status_t plan_rmsnorm(int64_t T, int64_t H, int eb, bool aligned16,
         const int lc = fit_chunk_log2(rows, kRowChunkBytesLog2 - floor_log2(H * eb), kRowChunkMinRows);
         if (T >= kMaxRowGrid) pace = kPaceNone;  // the row-loop kernel is not paced
         *info = astra_launch_info_t{ASTRA_PATH_VECTOR, rp.block, rp.vpt, lc, T < kMaxRowGrid ? pad_grid(rows, lc) : rows, pace, 0};
+    } else if (rmsnorm_row_plan((H + ne - 1) / ne, &rp)) {
+        // rows that are no whole number of vectors, or pointers that are only element aligned: the row still lives in
+        // registers, with 16-byte accesses at element alignment (workgroups walk rows beyond the grid limit)
+        *info = astra_launch_info_t{ASTRA_PATH_RAGGED, rp.block, rp.vpt, 0, T < kMaxRowGrid ? T : kMaxRowGrid, 0, 0};
     } else {
         *info = astra_launch_info_t{ASTRA_PATH_GENERIC, 256, 0, 0, T < kMaxGenericGrid ? T : kMaxGenericGrid, 0, 0};
     }
     return ASTRA_OK;
 }
 
-inline astra_status_t plan_silu(int64_t T, int64_t d, int eb, bool aligned16, astra_launch_info_t* info)
+// `ragged_ok`: the caller has a ragged kernel for inputs the vector path does not take (the dense entry points do)
+inline astra_status_t plan_silu(int64_t T, int64_t d, int eb, bool aligned16, astra_launch_info_t* info,
+                                bool ragged_ok = true)
 {
     const int64_t ne = kVecBytes / eb;
     int64_t two_d, n;
@@ -251,13 +257,16 @@ inline astra_status_t plan_silu(int64_t T, int64_t d, int eb, bool aligned16, as
         const int64_t blocks = (T * dv + span - 1) / span;
         const int lc = fit_chunk_log2(blocks, kFlatChunkLog2, kFlatChunkMinBlocks);
         *info = astra_launch_info_t{ASTRA_PATH_VECTOR, 256, kSiluUnroll, lc, pad_grid(blocks, lc), 0, 0};
+    } else if (ragged_ok && T * ((d + ne - 1) / ne) <= kMaxVecIndex) {  // no overflow: T * d is below 2^61
+        *info = astra_launch_info_t{ASTRA_PATH_RAGGED, 256, 1, 0, (T * ((d + ne - 1) / ne) + 255) / 256, 0, 0};
     } else {
         *info = astra_launch_info_t{ASTRA_PATH_GENERIC, 256, 0, 0, T < kMaxGenericGrid ? T : kMaxGenericGrid, 0, 0};
     }
     return ASTRA_OK;
 }
 
-inline astra_status_t plan_merge(int64_t T, int64_t NH, int64_t D, int eb, bool aligned16, astra_launch_info_t* info)
+inline astra_status_t plan_merge(int64_t T, int64_t NH, int64_t D, int eb, bool aligned16, astra_launch_info_t* info,
+                                 bool ragged_ok = true)
 {
     const int64_t ne = kVecBytes / eb;
     int64_t pairs, n;
@@ -272,6 +281,8 @@ inline astra_status_t plan_merge(int64_t T, int64_t NH, int64_t D, int eb, bool 
         const int64_t blocks = (pairs * dvec + span - 1) / span;
         const int lc = fit_chunk_log2(blocks, kFlatChunkLog2, kFlatChunkMinBlocks);
         *info = astra_launch_info_t{ASTRA_PATH_VECTOR, 256, kMergeUnroll, lc, pad_grid(blocks, lc), 0, 0};
+    } else if (ragged_ok && pairs * ((D + ne - 1) / ne) <= kMaxVecIndex) {
+        *info = astra_launch_info_t{ASTRA_PATH_RAGGED, 256, 1, 0, (pairs * ((D + ne - 1) / ne) + 255) / 256, 0, 0};
     } else {
         *info = astra_launch_info_t{ASTRA_PATH_GENERIC, 256, 0, 0, pairs < kMaxGenericGrid ? pairs : kMaxGenericGrid, 0, 0};
     }

@@ -91,7 +91,36 @@ __global__ __launch_bounds__(BLOCK) void merge_attn_states_lse_vec_kernel(u32x4*
     }
 }
 
-// Element-wise path for any head_dim and element-aligned pointers: one block per (token, head) pair.
+// Ragged path: any head_dim, value pointers only element aligned.  A pair is dvec = ceil(D/N) vectors, the last
+// one possibly partial; one lane per vector, pair and position from a per-lane fast division, 64-bit element
+// offsets.  Full vectors are 16-byte accesses at element alignment, the partial one goes element by element.
+// v_out may alias v_a or v_b exactly (a lane loads before it stores, and no two lanes share an element).
+template <int DT, bool NTL, bool NTS>
+__global__ __launch_bounds__(256) void merge_attn_states_lse_ragged_kernel(typename Storage<DT>::elem_t* v_out, float* lse_out,
+                                                                           const typename Storage<DT>::elem_t* v_a,
+                                                                           const float* lse_a,
+                                                                           const typename Storage<DT>::elem_t* v_b,
+                                                                           const float* lse_b, uint32_t total_vecs,
+                                                                           uint32_t dvec, int64_t D, FastDiv by_dvec)
+{
+    constexpr int N = Storage<DT>::kN;
+    const uint32_t i = blockIdx.x * 256u + threadIdx.x;
+    if (i >= total_vecs) return;
+    const uint32_t pair = by_dvec.div(i), jv = i - pair * dvec;
+    const int64_t e0 = (int64_t)jv * N;
+    const int count = D - e0 < N ? (int)(D - e0) : N;
+    const int64_t base = (int64_t)pair * D + e0;
+    float a[N], b[N], o[N];
+    load_elems<DT, NTL>(v_a + base, count, a);
+    load_elems<DT, NTL>(v_b + base, count, b);
+    const MergeWeights w = merge_weights(lse_a[pair], lse_b[pair]);
+#pragma unroll
+    for (int e = 0; e < N; ++e) o[e] = w.a * a[e] + w.b * b[e];
+    store_elems<DT, NTS>(v_out + base, count, o);
+    if (jv == 0) lse_out[pair] = w.lse;
+}
+
+// Element-wise path (inputs too large for the ragged kernel's 32-bit vector index): one block per (token, head) pair.
 template <int DT>
 __global__ __launch_bounds__(256) void merge_attn_states_lse_generic_kernel(typename Storage<DT>::elem_t* v_out, float* lse_out,
                                                                             const typename Storage<DT>::elem_t* v_a,

@@ -163,8 +163,13 @@ def test_rmsnorm_plans(A):
         assert lc == 0 or (T >= (64 << lc) and T >= 1024)              # small grids keep the plain launch order
         if T >= 4096:
             assert 128 * 1024 <= (H * 2) << lc <= 512 * 1024           # about 256 KiB per XCD run
-    assert plan(4, 4100)["path"] == "generic" and plan(4, 4096, al=False)["path"] == "generic"
-    assert plan(4, 65536)["path"] == "generic"
+    # rows that are no whole number of vectors, pointers that are only element aligned: ragged path, row in registers
+    assert plan(4, 4100) == {"path": "ragged", "block": 576, "vectors_per_lane": 1, "log2_xcd_chunk": 0, "grid": 4, "pace": 0}
+    assert plan(4, 4096, al=False)["path"] == "ragged" and plan(9, 32767)["path"] == "ragged" and plan(3, 1)["path"] == "ragged"
+    assert plan(4, 11009)["vectors_per_lane"] == 2 and plan(4, 32767)["vectors_per_lane"] == 4
+    assert plan(1 << 22, 100) == {"path": "ragged", "block": 64, "vectors_per_lane": 1, "log2_xcd_chunk": 0, "grid": 1 << 21,
+                                  "pace": 0}
+    assert plan(4, 65536)["path"] == "generic" and plan(4, 32769)["path"] == "generic"   # more than 4096 vectors
     big = plan(1 << 23, 64)                                            # row loop beyond the grid limit
     assert big["grid"] == 1 << 21 and big["grid"] % (8 << big["log2_xcd_chunk"]) == 0
     assert A.astra_plan_fused_add_rmsnorm(-1, 8, True)[0] == 2
@@ -213,16 +218,16 @@ def test_binary32_plans(A):
     for T, H in [(1, 8192), (600, 8192), (64, 16384), (4099, 5120)]:
         p = A.astra_plan_fused_add_rmsnorm(T, H, True, dtype=F32)[1].as_dict()
         assert p["path"] == "vector" and p["block"] * p["vectors_per_lane"] * 4 >= H and p["block"] <= 1024
-    assert A.astra_plan_fused_add_rmsnorm(4, 4098, True, dtype=F32)[1].as_dict()["path"] == "generic"   # H % 4 != 0
+    assert A.astra_plan_fused_add_rmsnorm(4, 4098, True, dtype=F32)[1].as_dict()["path"] == "ragged"    # H % 4 != 0
     assert A.astra_plan_fused_add_rmsnorm(4, 4100, True, dtype=F32)[1].as_dict()["path"] == "vector"    # H % 4 == 0
     assert A.astra_plan_fused_add_rmsnorm(4, 32768, True, dtype=F32)[1].as_dict()["path"] == "generic"  # > 4096 vectors
     s = A.astra_plan_silu_and_mul(4096, 14336, True, dtype=F32)[1].as_dict()
     assert s["path"] == "vector" and s["grid"] * 256 >= 4096 * 14336 // 4
-    assert A.astra_plan_silu_and_mul(3, 1410, True, dtype=F32)[1].as_dict()["path"] == "generic"
+    assert A.astra_plan_silu_and_mul(3, 1410, True, dtype=F32)[1].as_dict()["path"] == "ragged"
     assert A.astra_plan_silu_and_mul(3, 1412, True, dtype=F32)[1].as_dict()["path"] == "vector"
     m = A.astra_plan_merge_attn_states_lse(4096, 32, 128, True, dtype=F32)[1].as_dict()
     assert m["path"] == "vector" and m["grid"] * 256 == 4096 * 32 * 32
-    assert A.astra_plan_merge_attn_states_lse(3, 5, 6, True, dtype=F32)[1].as_dict()["path"] == "generic"
+    assert A.astra_plan_merge_attn_states_lse(3, 5, 6, True, dtype=F32)[1].as_dict()["path"] == "ragged"
     assert A.astra_plan_merge_attn_states_lse(3, 5, 4, True, dtype=F32)[1].as_dict()["path"] == "vector"
     assert A.astra_plan_merge_attn_states_lse(3, 5, 4, True, dtype=7)[0] == 3
     assert A.astra_plan_merge_attn_states_lse(-3, 5, 4, True, dtype=7)[0] == 2                          # shape before dtype
@@ -235,18 +240,23 @@ def test_silu_and_merge_plans(A):
     assert st == 0 and p["path"] == "vector"
     assert work <= p["grid"] * p["block"] * p["vectors_per_lane"] < work + (8 << p["log2_xcd_chunk"]) * 256
     assert p["grid"] % (8 << p["log2_xcd_chunk"]) == 0
-    assert A.astra_plan_silu_and_mul(3, 100, True)[1].as_dict()["path"] == "generic"
-    assert A.astra_plan_silu_and_mul(3, 1408, False)[1].as_dict()["path"] == "generic"
+    assert A.astra_plan_silu_and_mul(3, 100, True)[1].as_dict() == {"path": "ragged", "block": 256, "vectors_per_lane": 1,
+                                                                    "log2_xcd_chunk": 0, "grid": 1, "pace": 0}   # 3 * 13 vectors
+    assert A.astra_plan_silu_and_mul(3, 1408, False)[1].as_dict()["path"] == "ragged"
+    assert A.astra_plan_silu_and_mul(1 << 20, (1 << 14) + 1, True)[1].as_dict()["path"] == "generic"
     assert A.astra_plan_silu_and_mul(3, 128, True)[1].as_dict()["path"] == "vector"       # short rows: per-lane division
     assert A.astra_plan_silu_and_mul(1000, 8, True)[1].as_dict() == {"path": "vector", "block": 256, "vectors_per_lane": 1,
                                                                      "log2_xcd_chunk": 0, "grid": 4, "pace": 0}
-    assert A.astra_plan_silu_and_mul(1 << 20, 1 << 14, True)[1].as_dict()["path"] == "generic"  # beyond 32-bit vector indices
+    # the input's 2^32 vectors are beyond the vector kernel's 32-bit index; the ragged kernel indexes the 2^31 output vectors
+    assert A.astra_plan_silu_and_mul(1 << 20, 1 << 14, True)[1].as_dict()["path"] == "ragged"
     small = A.astra_plan_silu_and_mul(3, 1408, True)[1].as_dict()
     assert small["log2_xcd_chunk"] == 0 and small["grid"] == 3                           # no padding for small grids
     st, i = A.astra_plan_merge_attn_states_lse(4096, 32, 128, True)
     p = i.as_dict()
     assert st == 0 and p["path"] == "vector" and p["grid"] * p["block"] * p["vectors_per_lane"] == 4096 * 32 * 16
-    assert A.astra_plan_merge_attn_states_lse(3, 5, 4, True)[1].as_dict()["path"] == "generic"
+    assert A.astra_plan_merge_attn_states_lse(3, 5, 4, True)[1].as_dict()["path"] == "ragged"
+    assert A.astra_plan_merge_attn_states_lse(3, 5, 72, False)[1].as_dict()["path"] == "ragged"
+    assert A.astra_plan_merge_attn_states_lse(1 << 24, 64, 129, True)[1].as_dict()["path"] == "generic"   # 2^30 * 17 vectors
     assert A.astra_plan_merge_attn_states_lse(3, 5, 72, True)[1].as_dict()["path"] == "vector"
     assert A.astra_plan_merge_attn_states_lse(0, 5, 72, True)[1].as_dict()["path"] == "none"
 

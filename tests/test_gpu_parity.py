@@ -184,20 +184,22 @@ def test_merge_tile_shapes(A, T, NH, D, dt):
 
 
 # ---------------------------------------------------------------------------------------------------
-# element-wise path: odd row lengths and pointers that are only 2-byte aligned; canaries around buffers
+# ragged and element-wise paths: odd row lengths and pointers that are only 2-byte aligned; canaries around buffers
 
 @pytest.mark.parametrize("dt", ["bf16", "f16"])
 @pytest.mark.parametrize("T,H,off", [(3, 4100, 0), (2, 4097, 0), (5, 1, 0), (4, 7, 0), (3, 4096, 1), (2, 8192, 3), (3, 333, 5),
+                                     (2, 8, 1), (5, 9, 0), (3, 15, 7), (257, 5124, 0), (300, 11009, 0), (33, 32767, 1),
+                                     (1030, 4098, 3), (600, 16383, 5), (40, 32761, 0),
                                      (2, 70000, 0), (1, 65536, 0)])
-def test_rmsnorm_generic_path_and_canaries(A, T, H, off, dt):
-    _say(f"[parity] rmsnorm generic T={T} H={H} offset={off} {dt}")
+def test_rmsnorm_ragged_and_generic_paths_and_canaries(A, T, H, off, dt):
+    _say(f"[parity] rmsnorm ragged/generic T={T} H={H} offset={off} {dt}")
     x, r, w = workloads.rmsnorm_inputs(T, H, dt, np.random.default_rng([4, T, H, off]), r_std=2.0)
     xd, xw = padded(x, dt, offset_elems=off)
     rd, rw = padded(r, dt, offset_elems=off)
     wd, ww = padded(w, dt, offset_elems=off)
     aligned = all(t.data_ptr() % 16 == 0 for t in (xd, rd, wd))
     st, info = A.astra_plan_fused_add_rmsnorm(T, H, aligned)
-    assert info.as_dict()["path"] == "generic"
+    assert info.as_dict()["path"] == ("ragged" if -(-H // 8) <= 4096 else "generic")
     A.fused_add_rmsnorm(xd, rd, wd, 1e-5)
     torch.cuda.synchronize()
     y_ref, res_ref = O.fused_add_rmsnorm(x, r, w, 1e-5, dt)
@@ -225,7 +227,8 @@ def test_rmsnorm_vector_path_canaries(A, T, H, dt):
 
 @pytest.mark.parametrize("dt", ["bf16", "f16"])
 @pytest.mark.parametrize("T,d,off", [(3, 100, 0), (2, 1412, 0), (5, 1, 0), (4, 2049, 0), (3, 1408, 1), (2, 248, 0), (3, 11008, 2),
-                                     (4, 1408, 0), (257, 11008, 0)])
+                                     (4, 1408, 0), (257, 11008, 0),
+                                     (300, 11009, 0), (1000, 7, 3), (257, 1410, 5), (64, 8, 1), (129, 13825, 0), (50, 11012, 7)])
 def test_silu_paths_and_canaries(A, T, d, off, dt):
     _say(f"[parity] silu T={T} d={d} offset={off} {dt}")
     a = workloads.silu_inputs(T, d, dt, np.random.default_rng([6, T, d, off]))
@@ -241,7 +244,8 @@ def test_silu_paths_and_canaries(A, T, d, off, dt):
 
 @pytest.mark.parametrize("dt", ["bf16", "f16"])
 @pytest.mark.parametrize("T,NH,D,off", [(3, 5, 4, 0), (2, 3, 100, 0), (5, 2, 1, 0), (3, 4, 128, 1), (2, 40, 64, 3), (4, 40, 256, 0),
-                                        (257, 40, 64, 0), (3, 6, 72, 0)])
+                                        (257, 40, 64, 0), (3, 6, 72, 0),
+                                        (257, 40, 129, 0), (100, 7, 132, 5), (300, 32, 7, 0), (65, 40, 128, 1), (33, 5, 9, 3)])
 def test_merge_paths_and_canaries(A, T, NH, D, off, dt):
     _say(f"[parity] merge T={T} NH={NH} D={D} offset={off} {dt}")
     va, la, vb, lb = workloads.merge_inputs(T, NH, D, dt, np.random.default_rng([7, T, NH, D, off]), empty_p=0.15)
