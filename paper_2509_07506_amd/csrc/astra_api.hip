@@ -165,7 +165,7 @@ void launch_silu(const astra_launch_info_t& li, void* out, const void* in, int64
     if (li.path == ASTRA_PATH_RAGGED) {
         const uint32_t dvr = (uint32_t)((d + Storage<DT>::kN - 1) / Storage<DT>::kN);
         silu_and_mul_ragged_kernel<DT, kNTLoad, kNTStore><<<dim3((uint32_t)li.grid), dim3(256), 0, stream>>>(
-            static_cast<E*>(out), static_cast<const E*>(in), (uint32_t)(T * dvr), dvr, d, make_fastdiv(dvr));
+            static_cast<E*>(out), d, static_cast<const E*>(in), 2 * d, (uint32_t)(T * dvr), dvr, d, make_fastdiv(dvr));
         return;
     }
     const uint32_t dv = (uint32_t)(d / Storage<DT>::kN);
@@ -523,7 +523,7 @@ astra_status_t astra_silu_and_mul_strided(void* out, int64_t out_stride, const v
     const int64_t ne = kVecBytes / eb;
     const bool fast = aligned(out, 16) && aligned(input, 16) && out_stride % ne == 0 && in_stride % ne == 0;
     astra_launch_info_t li;
-    astra_status_t st = plan_silu(T, d, eb, fast, &li, false);
+    astra_status_t st = plan_silu(T, d, eb, fast, &li);
     if (st != ASTRA_OK) return st;
     int64_t out_rows, in_rows;
     if (out_stride < d || in_stride < 2 * d || mul_overflows(T > 0 ? T - 1 : 0, out_stride, &out_rows) ||
@@ -541,6 +541,11 @@ astra_status_t astra_silu_and_mul_strided(void* out, int64_t out_stride, const v
         if (li.path == ASTRA_PATH_GENERIC) {
             silu_and_mul_strided_generic_kernel<DT><<<dim3((uint32_t)li.grid), dim3(256), 0, stream>>>(
                 static_cast<E*>(out), out_stride, static_cast<const E*>(input), in_stride, T, d);
+        } else if (li.path == ASTRA_PATH_RAGGED) {
+            const uint32_t dvr = (uint32_t)((d + Storage<DT>::kN - 1) / Storage<DT>::kN);
+            silu_and_mul_ragged_kernel<DT, kNTLoad, kNTStore><<<dim3((uint32_t)li.grid), dim3(256), 0, stream>>>(
+                static_cast<E*>(out), out_stride, static_cast<const E*>(input), in_stride, (uint32_t)(T * dvr), dvr, d,
+                make_fastdiv(dvr));
         } else {
             const uint32_t dv = (uint32_t)(d / Storage<DT>::kN);
             silu_and_mul_strided_vec_kernel<DT, kNTLoad, kNTStore><<<dim3((uint32_t)li.grid), dim3(256), 0, stream>>>(
@@ -567,7 +572,7 @@ astra_status_t astra_merge_attn_states_lse_strided(void* v_out, int64_t out_toke
     bool fast = true;
     for (int i = 0; i < 3; ++i) fast = fast && aligned(bases[i], 16) && ts[i] % ne == 0 && hs[i] % ne == 0;
     astra_launch_info_t li;
-    astra_status_t st = plan_merge(T, num_heads, head_dim, eb, fast, &li, false);
+    astra_status_t st = plan_merge(T, num_heads, head_dim, eb, fast, &li);
     if (st != ASTRA_OK) return st;
     int64_t span[3];  // bounding extent of each value view in bytes
     for (int i = 0; i < 3; ++i) {
@@ -602,6 +607,13 @@ astra_status_t astra_merge_attn_states_lse_strided(void* v_out, int64_t out_toke
             merge_attn_states_lse_strided_generic_kernel<DT><<<dim3((uint32_t)li.grid), dim3(256), 0, stream>>>(
                 static_cast<E*>(v_out), lse_out, static_cast<const E*>(v_a), lse_a, static_cast<const E*>(v_b), lse_b, vs, pairs,
                 num_heads, head_dim);
+        } else if (li.path == ASTRA_PATH_RAGGED) {
+            const ValueStrides vs{ts[0], hs[0], ts[1], hs[1], ts[2], hs[2]};
+            const uint32_t dvr = (uint32_t)((head_dim + N - 1) / N);
+            merge_attn_states_lse_ragged_kernel<DT, kNTLoad, kNTStore, true><<<dim3((uint32_t)li.grid), dim3(256), 0, stream>>>(
+                static_cast<E*>(v_out), lse_out, static_cast<const E*>(v_a), lse_a, static_cast<const E*>(v_b), lse_b,
+                (uint32_t)(pairs * dvr), dvr, head_dim, make_fastdiv(dvr), vs, make_fastdiv((uint32_t)num_heads),
+                (uint32_t)num_heads);
         } else {
             const ValueStrides vs{ts[0] / N, hs[0] / N, ts[1] / N, hs[1] / N, ts[2] / N, hs[2] / N};
             const uint32_t dvec = (uint32_t)(head_dim / N);

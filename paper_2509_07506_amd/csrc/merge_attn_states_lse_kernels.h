@@ -91,17 +91,21 @@ __global__ __launch_bounds__(BLOCK) void merge_attn_states_lse_vec_kernel(u32x4*
     }
 }
 
-// Ragged path: any head_dim, value pointers only element aligned.  A pair is dvec = ceil(D/N) vectors, the last
-// one possibly partial; one lane per vector, pair and position from a per-lane fast division, 64-bit element
-// offsets.  Full vectors are 16-byte accesses at element alignment, the partial one goes element by element.
-// v_out may alias v_a or v_b exactly (a lane loads before it stores, and no two lanes share an element).
-template <int DT, bool NTL, bool NTS>
-__global__ __launch_bounds__(256) void merge_attn_states_lse_ragged_kernel(typename Storage<DT>::elem_t* v_out, float* lse_out,
-                                                                           const typename Storage<DT>::elem_t* v_a,
-                                                                           const float* lse_a,
-                                                                           const typename Storage<DT>::elem_t* v_b,
-                                                                           const float* lse_b, uint32_t total_vecs,
-                                                                           uint32_t dvec, int64_t D, FastDiv by_dvec)
+// Strides of the value tensors of a strided call: element (t, h, k) lives at t*token + h*head + k
+struct ValueStrides {
+    int64_t out_token, out_head, a_token, a_head, b_token, b_head;
+};
+
+// Ragged path: any head_dim, value pointers (and, STRIDED, token and head strides) only element aligned.  A pair is
+// dvec = ceil(D/N) vectors, the last one possibly partial; one lane per vector, pair and position from a per-lane
+// fast division, 64-bit element offsets.  Full vectors are 16-byte accesses at element alignment, the partial one
+// goes element by element.  v_out may alias v_a or v_b exactly (a lane loads before it stores, and no two lanes
+// share an element).  STRIDED = false: dense [pairs, D] tensors, `vs`, `by_heads` and `heads` are not looked at.
+template <int DT, bool NTL, bool NTS, bool STRIDED = false>
+__global__ __launch_bounds__(256) void merge_attn_states_lse_ragged_kernel(
+    typename Storage<DT>::elem_t* v_out, float* lse_out, const typename Storage<DT>::elem_t* v_a, const float* lse_a,
+    const typename Storage<DT>::elem_t* v_b, const float* lse_b, uint32_t total_vecs, uint32_t dvec, int64_t D,
+    FastDiv by_dvec, ValueStrides vs = ValueStrides{0, 0, 0, 0, 0, 0}, FastDiv by_heads = FastDiv{0, 0, 0}, uint32_t heads = 1)
 {
     constexpr int N = Storage<DT>::kN;
     const uint32_t i = blockIdx.x * 256u + threadIdx.x;
@@ -109,14 +113,22 @@ __global__ __launch_bounds__(256) void merge_attn_states_lse_ragged_kernel(typen
     const uint32_t pair = by_dvec.div(i), jv = i - pair * dvec;
     const int64_t e0 = (int64_t)jv * N;
     const int count = D - e0 < N ? (int)(D - e0) : N;
-    const int64_t base = (int64_t)pair * D + e0;
+    int64_t oa, ob, oo;
+    if constexpr (STRIDED) {
+        const uint32_t t = by_heads.div(pair), h = pair - t * heads;
+        oa = (int64_t)t * vs.a_token + (int64_t)h * vs.a_head + e0;
+        ob = (int64_t)t * vs.b_token + (int64_t)h * vs.b_head + e0;
+        oo = (int64_t)t * vs.out_token + (int64_t)h * vs.out_head + e0;
+    } else {
+        oa = ob = oo = (int64_t)pair * D + e0;
+    }
     float a[N], b[N], o[N];
-    load_elems<DT, NTL>(v_a + base, count, a);
-    load_elems<DT, NTL>(v_b + base, count, b);
+    load_elems<DT, NTL>(v_a + oa, count, a);
+    load_elems<DT, NTL>(v_b + ob, count, b);
     const MergeWeights w = merge_weights(lse_a[pair], lse_b[pair]);
 #pragma unroll
     for (int e = 0; e < N; ++e) o[e] = w.a * a[e] + w.b * b[e];
-    store_elems<DT, NTS>(v_out + base, count, o);
+    store_elems<DT, NTS>(v_out + oo, count, o);
     if (jv == 0) lse_out[pair] = w.lse;
 }
 
@@ -141,12 +153,8 @@ __global__ __launch_bounds__(256) void merge_attn_states_lse_generic_kernel(type
 
 // ---------------------------------------------------------------------------------------------
 // Strided views of the value tensors: element (t, h, k) of a tensor lives at t*token_stride + h*head_stride + k
-// (strides in vectors for the fast kernel, in elements for the element-wise one); the scores stay dense [T, NH].
+// (strides in vectors for the fast kernel, in elements for the ragged and the element-wise one); the scores stay dense [T, NH].
 // One lane per output vector; pair, token and head from per-lane fast divisions; 64-bit offsets.
-
-struct ValueStrides {
-    int64_t out_token, out_head, a_token, a_head, b_token, b_head;
-};
 
 template <int DT, bool NTL, bool NTS>
 __global__ __launch_bounds__(256) void merge_attn_states_lse_strided_vec_kernel(u32x4* v_out, float* lse_out, const u32x4* v_a,

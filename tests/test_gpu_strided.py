@@ -49,8 +49,10 @@ def _gaps_intact(whole, col0, H):
     (1280, 4096, (4096 + 8, 4096 + 16, 4096 + 8, 4096), 0),        # half-sized workgroups, two vectors per lane
     (700, 8192, (8192 + 8, 8192, 8192 + 8, 8192 + 8), 8),          # x requested before r
     (1100, 2048, (2048 + 64, 2048 + 8, 2048, 2048 + 8), 0),        # launch order in chunks
-    (5, 4096, (4096 + 3, 4096 + 8, 4096 + 8, 4096 + 8), 0),        # odd stride: element-wise path
+    (5, 4096, (4096 + 3, 4096 + 8, 4096 + 8, 4096 + 8), 0),        # odd stride: ragged path
     (5, 4100, (4100 + 4, 4100, 4111, 4100 + 1), 1),                # odd everything
+    (270, 5124, (5124 + 5, 5124 + 1, 5124, 5124 + 3), 3),
+    (3, 33000, (33000 + 1, 33000, 33000 + 7, 33000), 0),           # more than 4096 vectors: element-wise path
     (1, 4096, (4096, 4096, 4096, 4096), 0),
 ])
 def test_strided_out_of_place(A, T, H, strides, col0, dt):
@@ -116,8 +118,9 @@ from tests.gpu_util import assert_lse_close  # noqa: E402
     (9, 1408, 2 * 1408 + 64, 1408 + 8, 0),          # fast path
     (300, 5120, 2 * 5120 + 8, 5120 + 16, 8),
     (1100, 176, 2 * 176 + 24, 176 + 8, 0),          # short rows
-    (5, 1408, 2 * 1408 + 3, 1408 + 8, 0),           # odd stride: element-wise path
+    (5, 1408, 2 * 1408 + 3, 1408 + 8, 0),           # odd stride: ragged path
     (4, 100, 2 * 100 + 1, 100 + 7, 1),              # odd everything
+    (270, 1411, 2 * 1411 + 5, 1411 + 3, 3),
     (1, 4096, 2 * 4096, 4096, 0),
 ])
 def test_silu_strided(A, T, d, in_stride, out_stride, col0, dt):
@@ -162,8 +165,9 @@ def _gaps_intact3(whole, NH, D, head_stride, col0):
     (33, 8, 128, (192, 128, 136), 64, 0),            # fast path: head_dim slices of wider heads
     (300, 40, 64, (64, 72, 64), 0, 8),
     (5, 7, 72, (80, 72, 96), 16, 0),                 # head_dim not a power of two
-    (6, 4, 128, (131, 128, 128), 0, 0),              # odd head stride: element-wise path
+    (6, 4, 128, (131, 128, 128), 0, 0),              # odd head stride: ragged path
     (3, 5, 36, (40, 37, 36), 3, 1),                  # odd everything
+    (70, 9, 100, (103, 100, 109), 5, 3),
     (1, 1, 256, (256, 256, 256), 0, 0),
 ])
 def test_merge_strided(A, T, NH, D, head_strides, token_pad, col0, dt):
