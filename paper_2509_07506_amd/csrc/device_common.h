@@ -166,6 +166,15 @@ struct ElemAlignedVec<kF32> {
     typedef u32x4_align4 type;
 };
 
+// one whole vector at element alignment
+template <int DT, bool NT>
+__device__ __forceinline__ u32x4 load_vec_elem_aligned(const typename Storage<DT>::elem_t* p)
+{
+    typedef typename ElemAlignedVec<DT>::type V;
+    if constexpr (NT) return __builtin_nontemporal_load(reinterpret_cast<const V*>(p));
+    else return *reinterpret_cast<const V*>(p);
+}
+
 // f[0, count) <- p[0, count) widened, f[count, kN) <- 0; 1 <= count <= kN
 template <int DT, bool NT>
 __device__ __forceinline__ void load_elems(const typename Storage<DT>::elem_t* p, int count, float (&f)[Storage<DT>::kN])
@@ -178,10 +187,12 @@ __device__ __forceinline__ void load_elems(const typename Storage<DT>::elem_t* p
         else v = *reinterpret_cast<const V*>(p);
         unpack_vec<DT>(v, f);
     } else {
+        // branch-free: every lane reads inside [0, count) (the index is clamped), so the loads are independent of
+        // each other and go out together; a conditional load per element would wait for memory count times
 #pragma unroll
         for (int e = 0; e < N; ++e) {
-            f[e] = 0.0f;
-            if (e < count) f[e] = Storage<DT>::widen(p[e]);
+            const float v = Storage<DT>::widen(p[e < count ? e : count - 1]);
+            f[e] = e < count ? v : 0.0f;
         }
     }
 }

@@ -133,12 +133,12 @@ __global__ __launch_bounds__(MAX_THREADS) void fused_add_rmsnorm_row_kernel(u32x
 }
 
 // ---------------------------------------------------------------------------------------------
-// Ragged path: any H of up to 4096 vectors (the last vector of a row possibly partial), pointers and row strides only
+// Ragged path: any H of up to 4096 whole vectors plus a tail of fewer than N elements, pointers and row strides only
 // element aligned; in place (y_out = x, r_out = r, strides H) or out of place.  One workgroup per row, rows
-// gridDim.x apart, the row in registers as in the row kernel above; full vectors are 16-byte accesses at element
-// alignment, the partial one goes element by element (zeros beyond the row, which add nothing to the sum).
-// A lane loads its elements of x and r before it stores to the same positions, so exact aliasing of an
-// output with an input is safe.  `sv` holds the row strides in elements.
+// gridDim.x apart, the whole vectors in registers as in the row kernel above, as 16-byte accesses at element
+// alignment; the tail goes element by element in the workgroup's last lane (which has the fewest vectors), so it
+// costs no extra wave.  A lane loads its elements of x and r before it stores to the same positions, so exact
+// aliasing of an output with an input is safe.  `sv` holds the row strides in elements.
 template <int DT, int VPT, bool NTL, bool NTS>
 __global__ __launch_bounds__(1024) void fused_add_rmsnorm_ragged_row_kernel(
     typename Storage<DT>::elem_t* y_out, typename Storage<DT>::elem_t* r_out, const typename Storage<DT>::elem_t* x,
@@ -149,57 +149,96 @@ __global__ __launch_bounds__(1024) void fused_add_rmsnorm_ragged_row_kernel(
     __shared__ float partials[2][16];
     const int nwaves = blockDim.x >> 6;
     int parity = 0;
+    const int64_t whole = H / N;      // whole vectors per row
+    const int64_t tail0 = whole * N;  // first element of the tail
+    const int tail = threadIdx.x == blockDim.x - 1 ? (int)(H - tail0) : 0;  // tail elements this lane handles
 
-    int64_t e0[VPT];
-    int count[VPT];  // elements of this lane's k-th vector that lie inside the row: 0 .. N
+    bool live[VPT];
     u32x4 wv[VPT];
 #pragma unroll
     for (int k = 0; k < VPT; ++k) {
-        e0[k] = (int64_t)(threadIdx.x + k * blockDim.x) * N;
-        count[k] = H - e0[k] >= N ? N : (H > e0[k] ? (int)(H - e0[k]) : 0);
+        const int64_t v = threadIdx.x + k * blockDim.x;
+        live[k] = v < whole;
         float w[N] = {};
-        if (count[k] > 0) load_elems<DT, false>(weight + e0[k], count[k], w);
+        if (live[k]) load_elems<DT, false>(weight + v * N, N, w);
         wv[k] = pack_vec<DT>(w);  // widening and narrowing again is exact
     }
+    float wt[N] = {};
+    if (tail > 0) load_elems<DT, false>(weight + tail0, tail, wt);
 
     for (int64_t row = blockIdx.x; row < T; row += gridDim.x, parity ^= 1) {
         const typename Storage<DT>::elem_t* xr = x + row * sv.x_stride;
         const typename Storage<DT>::elem_t* rr = r + row * sv.r_stride;
         typename Storage<DT>::elem_t* yr = y_out + row * sv.y_stride;
         typename Storage<DT>::elem_t* sr = r_out + row * sv.r_out_stride;
+        // every request of the row first (whole vectors, then the tail with clamped indices, so that nothing waits
+        // in between), then the arithmetic
+        u32x4 xa[VPT], ra[VPT];
+#pragma unroll
+        for (int k = 0; k < VPT; ++k) {
+            xa[k] = ra[k] = u32x4{0u, 0u, 0u, 0u};
+            if (live[k]) {
+                const int64_t e0 = (int64_t)(threadIdx.x + k * blockDim.x) * N;
+                xa[k] = load_vec_elem_aligned<DT, NTL>(xr + e0);
+                ra[k] = load_vec_elem_aligned<DT, NTL>(rr + e0);
+            }
+        }
+        float st[N] = {};
+        if (tail > 0) {
+            typename Storage<DT>::elem_t xt[N], rt[N];
+#pragma unroll
+            for (int e = 0; e < N; ++e) {
+                const int idx = e < tail ? e : tail - 1;
+                xt[e] = xr[tail0 + idx];
+                rt[e] = rr[tail0 + idx];
+            }
+#pragma unroll
+            for (int e = 0; e < N; ++e) st[e] = e < tail ? Storage<DT>::widen(xt[e]) + Storage<DT>::widen(rt[e]) : 0.0f;
+        }
         float s[VPT][N];
         float acc = 0.0f;
 #pragma unroll
         for (int k = 0; k < VPT; ++k) {
-            if (count[k] > 0) {
+            if (live[k]) {
                 float a[N], b[N];
-                load_elems<DT, NTL>(xr + e0[k], count[k], a);
-                load_elems<DT, NTL>(rr + e0[k], count[k], b);
+                unpack_vec<DT>(xa[k], a);
+                unpack_vec<DT>(ra[k], b);
 #pragma unroll
                 for (int e = 0; e < N; ++e) {
                     s[k][e] = a[e] + b[e];
                     acc += s[k][e] * s[k][e];
                 }
-                store_elems<DT, NTS>(sr + e0[k], count[k], s[k]);
+                store_elems<DT, NTS>(sr + (int64_t)(threadIdx.x + k * blockDim.x) * N, N, s[k]);
             }
+        }
+        if (tail > 0) {
+#pragma unroll
+            for (int e = 0; e < N; ++e) acc += st[e] * st[e];  // zeros beyond the row add nothing
+            store_elems<DT, NTS>(sr + tail0, tail, st);
         }
         const float total = block_sum(acc, partials[parity], nwaves);
         const float scale = fast_rsqrt(total * inv_h + eps);
 #pragma unroll
         for (int k = 0; k < VPT; ++k) {
-            if (count[k] > 0) {
+            if (live[k]) {
+                const int64_t e0 = (int64_t)(threadIdx.x + k * blockDim.x) * N;
                 float w[N], y[N];
                 unpack_vec<DT>(wv[k], w);
 #pragma unroll
                 for (int e = 0; e < N; ++e) y[e] = (s[k][e] * scale) * w[e];
-                store_elems<DT, NTS>(yr + e0[k], count[k], y);
+                store_elems<DT, NTS>(yr + e0, N, y);
             }
+        }
+        if (tail > 0) {
+            float y[N];
+#pragma unroll
+            for (int e = 0; e < N; ++e) y[e] = (st[e] * scale) * wt[e];
+            store_elems<DT, NTS>(yr + tail0, tail, y);
         }
     }
 }
 
-
-// Element-wise path for any H and element-aligned pointers: two passes over the row.  The first pass
+// Element-wise path (rows of more than 4096 vectors), any H and element-aligned pointers: two passes over the row.  The first pass
 // only reads (it needs the unrounded sums, so the residual cannot be written yet); the second
 // recomputes x + r, stores it and the normalised value.  Each element is read and written by the
 // same lane, so the in-place update is safe.

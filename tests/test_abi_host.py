@@ -164,12 +164,14 @@ def test_rmsnorm_plans(A):
         if T >= 4096:
             assert 128 * 1024 <= (H * 2) << lc <= 512 * 1024           # about 256 KiB per XCD run
     # rows that are no whole number of vectors, pointers that are only element aligned: ragged path, row in registers
-    assert plan(4, 4100) == {"path": "ragged", "block": 576, "vectors_per_lane": 1, "log2_xcd_chunk": 0, "grid": 4, "pace": 0}
+    # (lanes for the whole vectors; the tail of fewer than 8 elements rides in the last lane)
+    assert plan(4, 4100) == {"path": "ragged", "block": 512, "vectors_per_lane": 1, "log2_xcd_chunk": 0, "grid": 4, "pace": 0}
     assert plan(4, 4096, al=False)["path"] == "ragged" and plan(9, 32767)["path"] == "ragged" and plan(3, 1)["path"] == "ragged"
     assert plan(4, 11009)["vectors_per_lane"] == 2 and plan(4, 32767)["vectors_per_lane"] == 4
     assert plan(1 << 22, 100) == {"path": "ragged", "block": 64, "vectors_per_lane": 1, "log2_xcd_chunk": 0, "grid": 1 << 21,
                                   "pace": 0}
-    assert plan(4, 65536)["path"] == "generic" and plan(4, 32769)["path"] == "generic"   # more than 4096 vectors
+    assert plan(4, 32775)["path"] == "ragged" and plan(4, 8199)["vectors_per_lane"] == 1
+    assert plan(4, 65536)["path"] == "generic" and plan(4, 32776)["path"] == "generic"   # more than 4096 vectors
     big = plan(1 << 23, 64)                                            # row loop beyond the grid limit
     assert big["grid"] == 1 << 21 and big["grid"] % (8 << big["log2_xcd_chunk"]) == 0
     assert A.astra_plan_fused_add_rmsnorm(-1, 8, True)[0] == 2
