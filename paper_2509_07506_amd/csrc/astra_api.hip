@@ -84,16 +84,18 @@ void launch_rmsnorm_ragged(const astra_launch_info_t& li, void* y_out, void* r_o
     const E* const xi = static_cast<const E*>(x);
     const E* const ri = static_cast<const E*>(r);
     const E* const w = static_cast<const E*>(weight);
+    auto go = [&](auto vpt, auto with_tail) {
+        fused_add_rmsnorm_ragged_row_kernel<DT, decltype(vpt)::value, decltype(with_tail)::value, kNTLoad, kNTStore>
+            <<<grid, block, 0, stream>>>(y, ro, xi, ri, w, ev, T, H, inv_h, eps, li.log2_xcd_chunk);
+    };
+    auto with_vpt = [&](auto vpt) {
+        if (H % Storage<DT>::kN != 0) go(vpt, std::true_type{});
+        else go(vpt, std::false_type{});  // only the pointers or strides are unaligned: no tail code at all
+    };
     switch (li.vectors_per_lane) {
-        case 1:
-            fused_add_rmsnorm_ragged_row_kernel<DT, 1, kNTLoad, kNTStore><<<grid, block, 0, stream>>>(y, ro, xi, ri, w, ev, T, H, inv_h, eps);
-            break;
-        case 2:
-            fused_add_rmsnorm_ragged_row_kernel<DT, 2, kNTLoad, kNTStore><<<grid, block, 0, stream>>>(y, ro, xi, ri, w, ev, T, H, inv_h, eps);
-            break;
-        default:
-            fused_add_rmsnorm_ragged_row_kernel<DT, 4, kNTLoad, kNTStore><<<grid, block, 0, stream>>>(y, ro, xi, ri, w, ev, T, H, inv_h, eps);
-            break;
+        case 1: with_vpt(std::integral_constant<int, 1>{}); break;
+        case 2: with_vpt(std::integral_constant<int, 2>{}); break;
+        default: with_vpt(std::integral_constant<int, 4>{}); break;
     }
 }
 

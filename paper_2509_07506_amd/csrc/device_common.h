@@ -175,42 +175,48 @@ __device__ __forceinline__ u32x4 load_vec_elem_aligned(const typename Storage<DT
     else return *reinterpret_cast<const V*>(p);
 }
 
-// f[0, count) <- p[0, count) widened, f[count, kN) <- 0; 1 <= count <= kN
+// Elements [e0, e0 + count) of a row of `len` elements, 1 <= count <= kN, e0 + count <= len, into f.  Returns the
+// position `shift` of element e0 in f: element e0 + i sits in f[shift + i]; the other positions of f hold
+// other elements of the row (or repeats) and must be ignored.
+//   count == kN           one 16-byte access at e0, shift 0;
+//   count < kN <= len     (the partial last vector of a row: e0 + count == len) the whole vector that ends at the
+//                         row end, one 16-byte access, shift kN - count; the positions before `shift` belong to the
+//                         neighbouring lane and are only read;
+//   len < kN              element loads with the index clamped into the row (independent of each other, so they go
+//                         out together; a guarded load per element would wait for memory count times), shift 0.
 template <int DT, bool NT>
-__device__ __forceinline__ void load_elems(const typename Storage<DT>::elem_t* p, int count, float (&f)[Storage<DT>::kN])
+__device__ __forceinline__ int load_row_elems(const typename Storage<DT>::elem_t* row, int64_t len, int64_t e0, int count,
+                                              float (&f)[Storage<DT>::kN])
 {
     constexpr int N = Storage<DT>::kN;
-    typedef typename ElemAlignedVec<DT>::type V;
     if (count == N) {
-        u32x4 v;
-        if constexpr (NT) v = __builtin_nontemporal_load(reinterpret_cast<const V*>(p));
-        else v = *reinterpret_cast<const V*>(p);
-        unpack_vec<DT>(v, f);
-    } else {
-        // branch-free: every lane reads inside [0, count) (the index is clamped), so the loads are independent of
-        // each other and go out together; a conditional load per element would wait for memory count times
-#pragma unroll
-        for (int e = 0; e < N; ++e) {
-            const float v = Storage<DT>::widen(p[e < count ? e : count - 1]);
-            f[e] = e < count ? v : 0.0f;
-        }
+        unpack_vec<DT>(load_vec_elem_aligned<DT, NT>(row + e0), f);
+        return 0;
     }
+    if (len >= N) {
+        unpack_vec<DT>(load_vec_elem_aligned<DT, NT>(row + (len - N)), f);
+        return N - count;
+    }
+#pragma unroll
+    for (int e = 0; e < N; ++e) f[e] = Storage<DT>::widen(row[e0 + (e < count ? e : count - 1)]);
+    return 0;
 }
 
-// p[0, count) <- f[0, count) narrowed; nothing past count is written
+// row[e0 + i] <- f[shift + i] narrowed for 0 <= i < count; nothing else is written
 template <int DT, bool NT>
-__device__ __forceinline__ void store_elems(typename Storage<DT>::elem_t* p, int count, const float (&f)[Storage<DT>::kN])
+__device__ __forceinline__ void store_row_elems(typename Storage<DT>::elem_t* row, int64_t e0, int count, int shift,
+                                                const float (&f)[Storage<DT>::kN])
 {
     constexpr int N = Storage<DT>::kN;
     typedef typename ElemAlignedVec<DT>::type V;
     if (count == N) {
         const u32x4 v = pack_vec<DT>(f);
-        if constexpr (NT) __builtin_nontemporal_store(v, reinterpret_cast<V*>(p));
-        else *reinterpret_cast<V*>(p) = v;
+        if constexpr (NT) __builtin_nontemporal_store(v, reinterpret_cast<V*>(row + e0));
+        else *reinterpret_cast<V*>(row + e0) = v;
     } else {
 #pragma unroll
-        for (int e = 0; e < N; ++e)
-            if (e < count) p[e] = Storage<DT>::narrow(f[e]);
+        for (int p = 0; p < N; ++p)
+            if (p >= shift && p < shift + count) row[e0 + (p - shift)] = Storage<DT>::narrow(f[p]);
     }
 }
 

@@ -133,73 +133,65 @@ __global__ __launch_bounds__(MAX_THREADS) void fused_add_rmsnorm_row_kernel(u32x
 }
 
 // ---------------------------------------------------------------------------------------------
-// Ragged path: any H of up to 4096 whole vectors plus a tail of fewer than N elements, pointers and row strides only
-// element aligned; in place (y_out = x, r_out = r, strides H) or out of place.  One workgroup per row, rows
-// gridDim.x apart, the whole vectors in registers as in the row kernel above, as 16-byte accesses at element
-// alignment; the tail goes element by element in the workgroup's last lane (which has the fewest vectors), so it
-// costs no extra wave.  A lane loads its elements of x and r before it stores to the same positions, so exact
-// aliasing of an output with an input is safe.  `sv` holds the row strides in elements.
-template <int DT, int VPT, bool NTL, bool NTS>
+// Ragged path: any H of 1 to 4096 whole vectors plus (TAIL) a tail of fewer than N elements, pointers and row strides
+// only element aligned; in place (y_out = x, r_out = r, strides H) or out of place.  One workgroup per row in the
+// XCD-aware order, rows gridDim.x apart, the whole vectors in registers as in the row kernel above, as 16-byte
+// accesses at element alignment.  The tail rides in the workgroup's last lane (which has the fewest vectors, so it
+// costs no extra wave) as the whole vector that ends at the row end, of which only the last `tail` positions are
+// summed and stored; every request of a row is issued before the first is used.  A lane loads
+// its elements of x and r before it stores to the same positions, so exact aliasing of an output with an input is
+// safe.  `sv` holds the row strides in elements.
+template <int DT, int VPT, bool TAIL, bool NTL, bool NTS>
 __global__ __launch_bounds__(1024) void fused_add_rmsnorm_ragged_row_kernel(
     typename Storage<DT>::elem_t* y_out, typename Storage<DT>::elem_t* r_out, const typename Storage<DT>::elem_t* x,
     const typename Storage<DT>::elem_t* r, const typename Storage<DT>::elem_t* __restrict__ weight, RowViews sv, int64_t T,
-    int64_t H, float inv_h, float eps)
+    int64_t H, float inv_h, float eps, int log2_chunk)
 {
     constexpr int N = Storage<DT>::kN;
     __shared__ float partials[2][16];
     const int nwaves = blockDim.x >> 6;
     int parity = 0;
-    const int64_t whole = H / N;      // whole vectors per row
-    const int64_t tail0 = whole * N;  // first element of the tail
-    const int tail = threadIdx.x == blockDim.x - 1 ? (int)(H - tail0) : 0;  // tail elements this lane handles
+    const int64_t first_row = xcd_chunked(blockIdx.x, log2_chunk);
+    if (first_row >= T) return;  // grid padding; uniform for the whole workgroup
+    const uint32_t whole = (uint32_t)(H / N);  // whole vectors per row
+    const uint32_t tail0 = whole * N;          // first element of the tail
+    const int tail = TAIL && threadIdx.x == blockDim.x - 1 ? (int)(H - tail0) : 0;  // tail elements this lane handles
 
-    bool live[VPT];
-    u32x4 wv[VPT];
+    u32x4 wv[VPT], wt = u32x4{0u, 0u, 0u, 0u};
 #pragma unroll
     for (int k = 0; k < VPT; ++k) {
-        const int64_t v = threadIdx.x + k * blockDim.x;
-        live[k] = v < whole;
-        float w[N] = {};
-        if (live[k]) load_elems<DT, false>(weight + v * N, N, w);
-        wv[k] = pack_vec<DT>(w);  // widening and narrowing again is exact
+        const uint32_t v = threadIdx.x + k * blockDim.x;
+        wv[k] = u32x4{0u, 0u, 0u, 0u};
+        if (v < whole) wv[k] = load_vec_elem_aligned<DT, false>(weight + v * N);
     }
-    float wt[N] = {};
-    if (tail > 0) load_elems<DT, false>(weight + tail0, tail, wt);
+    if (TAIL && tail > 0) wt = load_vec_elem_aligned<DT, false>(weight + (H - N));  // the vector that ends at the row end
 
-    for (int64_t row = blockIdx.x; row < T; row += gridDim.x, parity ^= 1) {
+    for (int64_t row = first_row; row < T; row += gridDim.x, parity ^= 1) {
         const typename Storage<DT>::elem_t* xr = x + row * sv.x_stride;
         const typename Storage<DT>::elem_t* rr = r + row * sv.r_stride;
         typename Storage<DT>::elem_t* yr = y_out + row * sv.y_stride;
         typename Storage<DT>::elem_t* sr = r_out + row * sv.r_out_stride;
-        // every request of the row first (whole vectors, then the tail with clamped indices, so that nothing waits
-        // in between), then the arithmetic
-        u32x4 xa[VPT], ra[VPT];
+        u32x4 xa[VPT], ra[VPT], xt = u32x4{0u, 0u, 0u, 0u}, rt = u32x4{0u, 0u, 0u, 0u};
 #pragma unroll
         for (int k = 0; k < VPT; ++k) {
+            const uint32_t v = threadIdx.x + k * blockDim.x;
             xa[k] = ra[k] = u32x4{0u, 0u, 0u, 0u};
-            if (live[k]) {
-                const int64_t e0 = (int64_t)(threadIdx.x + k * blockDim.x) * N;
-                xa[k] = load_vec_elem_aligned<DT, NTL>(xr + e0);
-                ra[k] = load_vec_elem_aligned<DT, NTL>(rr + e0);
+            if (v < whole) {
+                xa[k] = load_vec_elem_aligned<DT, NTL>(xr + v * N);
+                ra[k] = load_vec_elem_aligned<DT, NTL>(rr + v * N);
             }
         }
-        float st[N] = {};
-        if (tail > 0) {
-            typename Storage<DT>::elem_t xt[N], rt[N];
-#pragma unroll
-            for (int e = 0; e < N; ++e) {
-                const int idx = e < tail ? e : tail - 1;
-                xt[e] = xr[tail0 + idx];
-                rt[e] = rr[tail0 + idx];
-            }
-#pragma unroll
-            for (int e = 0; e < N; ++e) st[e] = e < tail ? Storage<DT>::widen(xt[e]) + Storage<DT>::widen(rt[e]) : 0.0f;
+        if (TAIL && tail > 0) {
+            xt = load_vec_elem_aligned<DT, NTL>(xr + (H - N));
+            rt = load_vec_elem_aligned<DT, NTL>(rr + (H - N));
         }
-        float s[VPT][N];
+
+        float s[VPT][N], st[TAIL ? N : 1];
         float acc = 0.0f;
 #pragma unroll
         for (int k = 0; k < VPT; ++k) {
-            if (live[k]) {
+            const uint32_t v = threadIdx.x + k * blockDim.x;
+            if (v < whole) {
                 float a[N], b[N];
                 unpack_vec<DT>(xa[k], a);
                 unpack_vec<DT>(ra[k], b);
@@ -208,32 +200,43 @@ __global__ __launch_bounds__(1024) void fused_add_rmsnorm_ragged_row_kernel(
                     s[k][e] = a[e] + b[e];
                     acc += s[k][e] * s[k][e];
                 }
-                store_elems<DT, NTS>(sr + (int64_t)(threadIdx.x + k * blockDim.x) * N, N, s[k]);
+                store_row_elems<DT, NTS>(sr, (int64_t)v * N, N, 0, s[k]);
             }
         }
-        if (tail > 0) {
+        if constexpr (TAIL) {
+            if (tail > 0) {
+                float a[N], b[N];
+                unpack_vec<DT>(xt, a);
+                unpack_vec<DT>(rt, b);
 #pragma unroll
-            for (int e = 0; e < N; ++e) acc += st[e] * st[e];  // zeros beyond the row add nothing
-            store_elems<DT, NTS>(sr + tail0, tail, st);
+                for (int e = 0; e < N; ++e) {
+                    st[e] = e >= N - tail ? a[e] + b[e] : 0.0f;  // the other positions belong to the neighbouring lane
+                    acc += st[e] * st[e];
+                }
+                store_row_elems<DT, NTS>(sr, tail0, tail, N - tail, st);
+            }
         }
         const float total = block_sum(acc, partials[parity], nwaves);
         const float scale = fast_rsqrt(total * inv_h + eps);
 #pragma unroll
         for (int k = 0; k < VPT; ++k) {
-            if (live[k]) {
-                const int64_t e0 = (int64_t)(threadIdx.x + k * blockDim.x) * N;
+            const uint32_t v = threadIdx.x + k * blockDim.x;
+            if (v < whole) {
                 float w[N], y[N];
                 unpack_vec<DT>(wv[k], w);
 #pragma unroll
                 for (int e = 0; e < N; ++e) y[e] = (s[k][e] * scale) * w[e];
-                store_elems<DT, NTS>(yr + e0, N, y);
+                store_row_elems<DT, NTS>(yr, (int64_t)v * N, N, 0, y);
             }
         }
-        if (tail > 0) {
-            float y[N];
+        if constexpr (TAIL) {
+            if (tail > 0) {
+                float w[N], y[N];
+                unpack_vec<DT>(wt, w);
 #pragma unroll
-            for (int e = 0; e < N; ++e) y[e] = (st[e] * scale) * wt[e];
-            store_elems<DT, NTS>(yr + tail0, tail, y);
+                for (int e = 0; e < N; ++e) y[e] = (st[e] * scale) * w[e];
+                store_row_elems<DT, NTS>(yr, tail0, tail, N - tail, y);
+            }
         }
     }
 }

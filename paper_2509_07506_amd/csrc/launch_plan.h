@@ -229,11 +229,13 @@ inline astra_status_t plan_rmsnorm(int64_t T, int64_t H, int eb, bool aligned16,
         const int lc = fit_chunk_log2(rows, kRowChunkBytesLog2 - floor_log2(H * eb), kRowChunkMinRows);
         if (T >= kMaxRowGrid) pace = kPaceNone;  // the row-loop kernel is not paced
         *info = astra_launch_info_t{ASTRA_PATH_VECTOR, rp.block, rp.vpt, lc, T < kMaxRowGrid ? pad_grid(rows, lc) : rows, pace, 0};
-    } else if (rmsnorm_row_plan(H >= ne ? H / ne : 1, &rp)) {
+    } else if (H >= ne && rmsnorm_row_plan(H / ne, &rp)) {
         // rows that are no whole number of vectors, or pointers that are only element aligned: the row still lives in
-        // registers, with 16-byte accesses at element alignment; lanes for the whole vectors, the tail rides in the
-        // last lane (workgroups walk rows beyond the grid limit)
-        *info = astra_launch_info_t{ASTRA_PATH_RAGGED, rp.block, rp.vpt, 0, T < kMaxRowGrid ? T : kMaxRowGrid, 0, 0};
+        // registers, with 16-byte accesses at element alignment; lanes for the whole vectors (at least one), the tail
+        // rides in the last lane (workgroups walk rows beyond the grid limit)
+        const int64_t rows = T < kMaxRowGrid ? T : kMaxRowGrid;
+        const int lc = fit_chunk_log2(rows, kRowChunkBytesLog2 - floor_log2(H * eb), kRowChunkMinRows);
+        *info = astra_launch_info_t{ASTRA_PATH_RAGGED, rp.block, rp.vpt, lc, T < kMaxRowGrid ? pad_grid(rows, lc) : rows, 0, 0};
     } else {
         *info = astra_launch_info_t{ASTRA_PATH_GENERIC, 256, 0, 0, T < kMaxGenericGrid ? T : kMaxGenericGrid, 0, 0};
     }

@@ -98,9 +98,9 @@ struct ValueStrides {
 
 // Ragged path: any head_dim, value pointers (and, STRIDED, token and head strides) only element aligned.  A pair is
 // dvec = ceil(D/N) vectors, the last one possibly partial; one lane per vector, pair and position from a per-lane
-// fast division, 64-bit element offsets.  Full vectors are 16-byte accesses at element alignment, the partial one
-// goes element by element.  v_out may alias v_a or v_b exactly (a lane loads before it stores, and no two lanes
-// share an element).  STRIDED = false: dense [pairs, D] tensors, `vs`, `by_heads` and `heads` are not looked at.
+// fast division, 64-bit element offsets.  Full vectors are 16-byte accesses at element alignment; the partial one
+// reads the whole vector that ends at the end of the pair and stores its own elements one by one.  v_out may alias
+// v_a or v_b exactly (a lane loads before it stores; what it reads of its neighbour's elements it ignores).  STRIDED = false: dense [pairs, D] tensors, `vs`, `by_heads` and `heads` are not looked at.
 template <int DT, bool NTL, bool NTS, bool STRIDED = false>
 __global__ __launch_bounds__(256) void merge_attn_states_lse_ragged_kernel(
     typename Storage<DT>::elem_t* v_out, float* lse_out, const typename Storage<DT>::elem_t* v_a, const float* lse_a,
@@ -113,22 +113,22 @@ __global__ __launch_bounds__(256) void merge_attn_states_lse_ragged_kernel(
     const uint32_t pair = by_dvec.div(i), jv = i - pair * dvec;
     const int64_t e0 = (int64_t)jv * N;
     const int count = D - e0 < N ? (int)(D - e0) : N;
-    int64_t oa, ob, oo;
+    int64_t oa, ob, oo;  // where the pair's head_dim elements start
     if constexpr (STRIDED) {
         const uint32_t t = by_heads.div(pair), h = pair - t * heads;
-        oa = (int64_t)t * vs.a_token + (int64_t)h * vs.a_head + e0;
-        ob = (int64_t)t * vs.b_token + (int64_t)h * vs.b_head + e0;
-        oo = (int64_t)t * vs.out_token + (int64_t)h * vs.out_head + e0;
+        oa = (int64_t)t * vs.a_token + (int64_t)h * vs.a_head;
+        ob = (int64_t)t * vs.b_token + (int64_t)h * vs.b_head;
+        oo = (int64_t)t * vs.out_token + (int64_t)h * vs.out_head;
     } else {
-        oa = ob = oo = (int64_t)pair * D + e0;
+        oa = ob = oo = (int64_t)pair * D;
     }
     float a[N], b[N], o[N];
-    load_elems<DT, NTL>(v_a + oa, count, a);
-    load_elems<DT, NTL>(v_b + ob, count, b);
+    const int shift = load_row_elems<DT, NTL>(v_a + oa, D, e0, count, a);
+    load_row_elems<DT, NTL>(v_b + ob, D, e0, count, b);
     const MergeWeights w = merge_weights(lse_a[pair], lse_b[pair]);
 #pragma unroll
-    for (int e = 0; e < N; ++e) o[e] = w.a * a[e] + w.b * b[e];
-    store_elems<DT, NTS>(v_out + oo, count, o);
+    for (int e = 0; e < N; ++e) o[e] = w.a * a[e] + w.b * b[e];  // positions outside [shift, shift + count) are not stored
+    store_row_elems<DT, NTS>(v_out + oo, e0, count, shift, o);
     if (jv == 0) lse_out[pair] = w.lse;
 }
 

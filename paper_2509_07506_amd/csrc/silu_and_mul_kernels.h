@@ -82,8 +82,8 @@ __global__ __launch_bounds__(BLOCK) void silu_and_mul_vec_kernel(u32x4* __restri
 
 // Ragged path: any d, pointers and row strides only element aligned (dense tensors: out_stride = d, in_stride = 2d).
 // A row is dv = ceil(d/N) vectors, the last one possibly partial; one lane per vector, row and column from a
-// per-lane fast division, 64-bit element offsets.  Full vectors are 16-byte accesses at element alignment, the
-// partial one goes element by element.
+// per-lane fast division, 64-bit element offsets.  Full vectors are 16-byte accesses at element alignment; the
+// partial one reads the whole vector that ends at the row end and stores its own elements one by one.
 template <int DT, bool NTL, bool NTS>
 __global__ __launch_bounds__(256) void silu_and_mul_ragged_kernel(typename Storage<DT>::elem_t* __restrict__ out,
                                                                   int64_t out_stride,
@@ -97,13 +97,13 @@ __global__ __launch_bounds__(256) void silu_and_mul_ragged_kernel(typename Stora
     const uint32_t t = by_dv.div(i), j = i - t * dv;
     const int64_t e0 = (int64_t)j * N;
     const int count = d - e0 < N ? (int)(d - e0) : N;
-    const typename Storage<DT>::elem_t* px = in + (int64_t)t * in_stride + e0;
+    const typename Storage<DT>::elem_t* xrow = in + (int64_t)t * in_stride;  // the gate row follows d elements later
     float x[N], g[N], o[N];
-    load_elems<DT, NTL>(px, count, x);
-    load_elems<DT, NTL>(px + d, count, g);
+    const int shift = load_row_elems<DT, NTL>(xrow, d, e0, count, x);
+    load_row_elems<DT, NTL>(xrow + d, d, e0, count, g);
 #pragma unroll
-    for (int e = 0; e < N; ++e) o[e] = silu_fast(x[e]) * g[e];
-    store_elems<DT, NTS>(out + (int64_t)t * out_stride + e0, count, o);
+    for (int e = 0; e < N; ++e) o[e] = silu_fast(x[e]) * g[e];  // positions outside [shift, shift + count) are not stored
+    store_row_elems<DT, NTS>(out + (int64_t)t * out_stride, e0, count, shift, o);
 }
 
 // Element-wise path (inputs too large for the ragged kernel's 32-bit vector index): one block walks one row at a time.

@@ -166,10 +166,13 @@ def test_rmsnorm_plans(A):
     # rows that are no whole number of vectors, pointers that are only element aligned: ragged path, row in registers
     # (lanes for the whole vectors; the tail of fewer than 8 elements rides in the last lane)
     assert plan(4, 4100) == {"path": "ragged", "block": 512, "vectors_per_lane": 1, "log2_xcd_chunk": 0, "grid": 4, "pace": 0}
-    assert plan(4, 4096, al=False)["path"] == "ragged" and plan(9, 32767)["path"] == "ragged" and plan(3, 1)["path"] == "ragged"
+    assert plan(4, 4096, al=False)["path"] == "ragged" and plan(9, 32767)["path"] == "ragged" and plan(3, 8)["path"] == "vector" and plan(3, 9)["path"] == "ragged"
+    assert plan(3, 1)["path"] == "generic" and plan(3, 7)["path"] == "generic"          # not one whole vector in a row
     assert plan(4, 11009)["vectors_per_lane"] == 2 and plan(4, 32767)["vectors_per_lane"] == 4
-    assert plan(1 << 22, 100) == {"path": "ragged", "block": 64, "vectors_per_lane": 1, "log2_xcd_chunk": 0, "grid": 1 << 21,
+    assert plan(1 << 22, 100) == {"path": "ragged", "block": 64, "vectors_per_lane": 1, "log2_xcd_chunk": 8, "grid": 1 << 21,
                                   "pace": 0}
+    p = plan(4099, 5124)
+    assert p["path"] == "ragged" and p["log2_xcd_chunk"] == 5 and p["grid"] == 4352 and p["block"] == 640
     assert plan(4, 32775)["path"] == "ragged" and plan(4, 8199)["vectors_per_lane"] == 1
     assert plan(4, 65536)["path"] == "generic" and plan(4, 32776)["path"] == "generic"   # more than 4096 vectors
     big = plan(1 << 23, 64)                                            # row loop beyond the grid limit

@@ -66,7 +66,7 @@ def check_rmsnorm(A, x, r, w, eps, what):
 def test_rmsnorm_tiles(A, T, H):
     plan = A.astra_plan_fused_add_rmsnorm(T, H, True, dtype=A.ASTRA_F32)[1].as_dict()
     _say(f"[f32] rmsnorm T={T} H={H} plan={plan}")
-    assert plan["path"] == ("generic" if H > 16384 else "vector" if H % 4 == 0 else "ragged")
+    assert plan["path"] == ("generic" if H > 16384 or H < 4 else "vector" if H % 4 == 0 else "ragged")
     x, r, w = workloads.rmsnorm_inputs(T, H, DT, _rng(1, T, H), r_std=2.0)
     check_rmsnorm(A, x, r, w, 1e-5, f"rmsnorm f32 T={T} H={H}")
 

@@ -199,7 +199,7 @@ def test_rmsnorm_ragged_and_generic_paths_and_canaries(A, T, H, off, dt):
     wd, ww = padded(w, dt, offset_elems=off)
     aligned = all(t.data_ptr() % 16 == 0 for t in (xd, rd, wd))
     st, info = A.astra_plan_fused_add_rmsnorm(T, H, aligned)
-    assert info.as_dict()["path"] == ("ragged" if H // 8 <= 4096 else "generic")
+    assert info.as_dict()["path"] == ("ragged" if 1 <= H // 8 <= 4096 else "generic")
     A.fused_add_rmsnorm(xd, rd, wd, 1e-5)
     torch.cuda.synchronize()
     y_ref, res_ref = O.fused_add_rmsnorm(x, r, w, 1e-5, dt)
