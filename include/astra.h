@@ -19,8 +19,8 @@
  *   - Pointers must be aligned to their element size (2 or 4 bytes, scores 4 bytes).  The fast path needs
  *     16-byte aligned pointers and a row length that is a multiple of 16 bytes (8 16-bit or 4 binary32
  *     elements); anything else is served by slower paths that compute the same thing (16-byte accesses at
- *     element alignment with the last, partial vector of a row element by element; plain element-wise kernels
- *     for rows of more than 4096 vectors and inputs beyond 2^31 vectors).  Equal up to the order of binary32
+ *     element alignment, the partial last vector of a row stored element by element; plain element-wise kernels
+ *     for fused_add_rmsnorm rows of more than 4096 vectors or less than one and for inputs beyond 2^31 vectors).  Equal up to the order of binary32
  *     roundings; the residual of fused_add_rmsnorm is bit-identical on every path.
  *   - Element counts (T*H, T*2d, T*num_heads*head_dim) may exceed 2^31; they must fit in int64.
  */

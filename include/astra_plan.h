@@ -17,7 +17,8 @@ extern "C" {
 typedef enum {
     ASTRA_PATH_NONE = 0,    /* nothing to launch (T == 0) */
     ASTRA_PATH_VECTOR = 1,  /* 16-byte-per-lane fast path */
-    ASTRA_PATH_GENERIC = 2, /* element-wise path: rows of more than 4096 vectors, inputs beyond the 32-bit vector index */
+    ASTRA_PATH_GENERIC = 2, /* element-wise path: rmsnorm rows of more than 4096 vectors or less than one, inputs beyond
+                               the 32-bit vector index */
     ASTRA_PATH_RAGGED = 3   /* row lengths that are no whole number of vectors, or pointers that are only element
                                aligned: 16-byte accesses at element alignment, the partial last vector element-wise */
 } astra_path_t;
