@@ -20,7 +20,8 @@
  * partitions empty give V_out = 0 and S_out = -inf.  K = 2 computes what astra_merge_attn_states_lse
  * computes on the two slices.  Outputs must not overlap inputs (ASTRA_ERR_ALIAS).  K must be in
  * [1, 65536] (ASTRA_ERR_SHAPE otherwise).  Everything else -- ownership, stream, validation order,
- * alignment rules, the element-wise path for a head_dim that is not a whole number of 16-byte vectors or unaligned pointers -- is as in astra.h.
+ * alignment rules, the slower paths for a head_dim that is not a whole number of 16-byte vectors or for pointers that
+ * are only element aligned -- is as in astra.h.
  */
 #ifndef ASTRA_KWAY_H
 #define ASTRA_KWAY_H

@@ -237,6 +237,15 @@ void launch_merge_kway(const astra_launch_info_t& li, void* v_out, float* lse_ou
             static_cast<E*>(v_out), lse_out, static_cast<const E*>(v_parts), lse_parts, (uint32_t)K, pairs, D);
         return;
     }
+    if (li.path == ASTRA_PATH_RAGGED) {
+        typedef typename Storage<DT>::elem_t E;
+        const uint32_t dvr = (uint32_t)((D + Storage<DT>::kN - 1) / Storage<DT>::kN);
+        merge_attn_states_lse_kway_ragged_kernel<DT, kKwayGroup, kNTLoad, kNTStore>
+            <<<dim3((uint32_t)li.grid), dim3(256), 0, stream>>>(static_cast<E*>(v_out), lse_out, static_cast<const E*>(v_parts),
+                                                                lse_parts, (uint32_t)K, (uint32_t)(pairs * dvr), pairs, dvr, D,
+                                                                make_fastdiv(dvr));
+        return;
+    }
     const uint32_t dvec = (uint32_t)(D / Storage<DT>::kN);
     const int log2_dvec = (dvec & (dvec - 1)) == 0 ? __builtin_ctz(dvec) : -1;
     merge_attn_states_lse_kway_vec_kernel<DT, kKwayGroup, kNTLoad, kNTStore><<<dim3((uint32_t)li.grid), dim3(256), 0, stream>>>(
@@ -456,7 +465,7 @@ astra_status_t astra_merge_attn_states_lse_kway(void* v_out, float* lse_out, con
     if (!v_out || !lse_out || !v_parts || !lse_parts) return ASTRA_ERR_NULL;
     astra_launch_info_t li;
     const int eb = elem_bytes((int)dtype);
-    astra_status_t st = plan_merge(T, num_heads, head_dim, eb, aligned(v_out, 16) && aligned(v_parts, 16), &li, false);
+    astra_status_t st = plan_merge(T, num_heads, head_dim, eb, aligned(v_out, 16) && aligned(v_parts, 16), &li);
     if (st != ASTRA_OK) return st;
     const int64_t pairs = T * num_heads;
     int64_t part_elems = pairs * head_dim, all_elems;

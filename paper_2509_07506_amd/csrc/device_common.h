@@ -185,21 +185,33 @@ __device__ __forceinline__ u32x4 load_vec_elem_aligned(const typename Storage<DT
 //   len < kN              element loads with the index clamped into the row (independent of each other, so they go
 //                         out together; a guarded load per element would wait for memory count times), shift 0.
 template <int DT, bool NT>
-__device__ __forceinline__ int load_row_elems(const typename Storage<DT>::elem_t* row, int64_t len, int64_t e0, int count,
-                                              float (&f)[Storage<DT>::kN])
+__device__ __forceinline__ u32x4 load_row_vec(const typename Storage<DT>::elem_t* row, int64_t len, int64_t e0, int count,
+                                              int* shift)
 {
     constexpr int N = Storage<DT>::kN;
     if (count == N) {
-        unpack_vec<DT>(load_vec_elem_aligned<DT, NT>(row + e0), f);
-        return 0;
+        *shift = 0;
+        return load_vec_elem_aligned<DT, NT>(row + e0);
     }
     if (len >= N) {
-        unpack_vec<DT>(load_vec_elem_aligned<DT, NT>(row + (len - N)), f);
-        return N - count;
+        *shift = N - count;
+        return load_vec_elem_aligned<DT, NT>(row + (len - N));
     }
+    float f[N];
 #pragma unroll
     for (int e = 0; e < N; ++e) f[e] = Storage<DT>::widen(row[e0 + (e < count ? e : count - 1)]);
-    return 0;
+    *shift = 0;
+    return pack_vec<DT>(f);  // widening and narrowing again is exact
+}
+
+// the same, unpacked
+template <int DT, bool NT>
+__device__ __forceinline__ int load_row_elems(const typename Storage<DT>::elem_t* row, int64_t len, int64_t e0, int count,
+                                              float (&f)[Storage<DT>::kN])
+{
+    int shift;
+    unpack_vec<DT>(load_row_vec<DT, NT>(row, len, e0, count, &shift), f);
+    return shift;
 }
 
 // row[e0 + i] <- f[shift + i] narrowed for 0 <= i < count; nothing else is written

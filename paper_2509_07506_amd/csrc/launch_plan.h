@@ -242,9 +242,7 @@ inline astra_status_t plan_rmsnorm(int64_t T, int64_t H, int eb, bool aligned16,
     return ASTRA_OK;
 }
 
-// `ragged_ok`: the caller has a ragged kernel for inputs the vector path does not take (the dense entry points do)
-inline astra_status_t plan_silu(int64_t T, int64_t d, int eb, bool aligned16, astra_launch_info_t* info,
-                                bool ragged_ok = true)
+inline astra_status_t plan_silu(int64_t T, int64_t d, int eb, bool aligned16, astra_launch_info_t* info)
 {
     const int64_t ne = kVecBytes / eb;
     int64_t two_d, n;
@@ -260,7 +258,7 @@ inline astra_status_t plan_silu(int64_t T, int64_t d, int eb, bool aligned16, as
         const int64_t blocks = (T * dv + span - 1) / span;
         const int lc = fit_chunk_log2(blocks, kFlatChunkLog2, kFlatChunkMinBlocks);
         *info = astra_launch_info_t{ASTRA_PATH_VECTOR, 256, kSiluUnroll, lc, pad_grid(blocks, lc), 0, 0};
-    } else if (ragged_ok && T * ((d + ne - 1) / ne) <= kMaxVecIndex) {  // no overflow: T * d is below 2^61
+    } else if (T * ((d + ne - 1) / ne) <= kMaxVecIndex) {  // no overflow: T * d is below 2^61
         *info = astra_launch_info_t{ASTRA_PATH_RAGGED, 256, 1, 0, (T * ((d + ne - 1) / ne) + 255) / 256, 0, 0};
     } else {
         *info = astra_launch_info_t{ASTRA_PATH_GENERIC, 256, 0, 0, T < kMaxGenericGrid ? T : kMaxGenericGrid, 0, 0};
@@ -268,8 +266,7 @@ inline astra_status_t plan_silu(int64_t T, int64_t d, int eb, bool aligned16, as
     return ASTRA_OK;
 }
 
-inline astra_status_t plan_merge(int64_t T, int64_t NH, int64_t D, int eb, bool aligned16, astra_launch_info_t* info,
-                                 bool ragged_ok = true)
+inline astra_status_t plan_merge(int64_t T, int64_t NH, int64_t D, int eb, bool aligned16, astra_launch_info_t* info)
 {
     const int64_t ne = kVecBytes / eb;
     int64_t pairs, n;
@@ -284,7 +281,7 @@ inline astra_status_t plan_merge(int64_t T, int64_t NH, int64_t D, int eb, bool 
         const int64_t blocks = (pairs * dvec + span - 1) / span;
         const int lc = fit_chunk_log2(blocks, kFlatChunkLog2, kFlatChunkMinBlocks);
         *info = astra_launch_info_t{ASTRA_PATH_VECTOR, 256, kMergeUnroll, lc, pad_grid(blocks, lc), 0, 0};
-    } else if (ragged_ok && pairs * ((D + ne - 1) / ne) <= kMaxVecIndex) {
+    } else if (pairs * ((D + ne - 1) / ne) <= kMaxVecIndex) {
         *info = astra_launch_info_t{ASTRA_PATH_RAGGED, 256, 1, 0, (pairs * ((D + ne - 1) / ne) + 255) / 256, 0, 0};
     } else {
         *info = astra_launch_info_t{ASTRA_PATH_GENERIC, 256, 0, 0, pairs < kMaxGenericGrid ? pairs : kMaxGenericGrid, 0, 0};

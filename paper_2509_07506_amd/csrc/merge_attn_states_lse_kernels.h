@@ -291,7 +291,71 @@ __global__ __launch_bounds__(256) void merge_attn_states_lse_kway_vec_kernel(u32
     if (i == pair * dvec) lse_out[pair] = empty ? ninf : m + fast_log(den);
 }
 
-// Element-wise path for any head_dim and element-aligned pointers: one block per (token, head) pair.
+// Ragged path of the K-way merge: any head_dim, value pointers only element aligned.  The streaming form above with
+// dvec = ceil(D/N) vectors per pair; a partial last vector is read as the whole vector that ends at the end of the
+// pair (the same positions for every part) and only its own elements are stored.
+template <int DT, int G, bool NTL, bool NTS>
+__global__ __launch_bounds__(256) void merge_attn_states_lse_kway_ragged_kernel(
+    typename Storage<DT>::elem_t* __restrict__ v_out, float* __restrict__ lse_out,
+    const typename Storage<DT>::elem_t* __restrict__ v_parts, const float* __restrict__ lse_parts, uint32_t K,
+    uint32_t total_vecs, int64_t pairs, uint32_t dvec, int64_t D, FastDiv by_dvec)
+{
+    constexpr int N = Storage<DT>::kN;
+    const uint32_t i = blockIdx.x * 256u + threadIdx.x;
+    if (i >= total_vecs) return;
+    const uint32_t pair = by_dvec.div(i), jv = i - pair * dvec;
+    const int64_t e0 = (int64_t)jv * N;
+    const int count = D - e0 < N ? (int)(D - e0) : N;
+    const float ninf = -__builtin_inff();
+    float m = ninf, den = 0.0f;
+    float acc[N];
+#pragma unroll
+    for (int e = 0; e < N; ++e) acc[e] = 0.0f;
+    int shift = 0;
+    for (uint32_t k0 = 0; k0 < K; k0 += G) {
+        u32x4 pv[G];
+        float s[G];
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            const uint32_t k = k0 + g;
+            if (k < K) {
+                pv[g] = load_row_vec<DT, NTL>(v_parts + ((int64_t)k * pairs + pair) * D, D, e0, count, &shift);
+                s[g] = lse_parts[(int64_t)k * pairs + pair];
+            } else {
+                pv[g] = u32x4{0u, 0u, 0u, 0u};
+                s[g] = ninf;
+            }
+        }
+        float gm = s[0];
+#pragma unroll
+        for (int g = 1; g < G; ++g) gm = fmaxf(gm, s[g]);
+        const float mn = fmaxf(m, gm);
+        if (mn != ninf) {
+            const float rescale = fast_exp(m - mn);
+            den *= rescale;
+#pragma unroll
+            for (int e = 0; e < N; ++e) acc[e] *= rescale;
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                const float w = fast_exp(s[g] - mn);
+                den += w;
+                float v[N];
+                unpack_vec<DT>(pv[g], v);
+#pragma unroll
+                for (int e = 0; e < N; ++e) acc[e] += w * v[e];
+            }
+            m = mn;
+        }
+    }
+    const bool empty = (m == ninf);
+    const float inv = empty ? 0.0f : fast_rcp(den);
+#pragma unroll
+    for (int e = 0; e < N; ++e) acc[e] *= inv;
+    store_row_elems<DT, NTS>(v_out + (int64_t)pair * D, e0, count, shift, acc);
+    if (jv == 0) lse_out[pair] = empty ? ninf : m + fast_log(den);
+}
+
+// Element-wise path (inputs beyond the ragged kernel's 32-bit vector index): one block per (token, head) pair.
 template <int DT>
 __global__ __launch_bounds__(256) void merge_attn_states_lse_kway_generic_kernel(typename Storage<DT>::elem_t* __restrict__ v_out,
                                                                                  float* __restrict__ lse_out,
