@@ -9,8 +9,8 @@
  *
  * Arguments, layouts, ownership and validation are exactly those of the corresponding function in
  * astra.h.  In addition: a variant that does not apply to the operator, or a shape outside what the
- * variant supports (all need 16-byte aligned pointers and rows that are a multiple of 8 elements, i.e.
- * the fast path; scalar-load variants need fewer than 2^32 elements and, for rmsnorm, H <= 16384),
+ * variant supports (variants 1 to 4 need 16-byte aligned pointers and rows that are a multiple of 8 elements,
+ * i.e. the fast path; scalar-load variants need fewer than 2^32 elements and, for rmsnorm, H <= 16384),
  * returns ASTRA_ERR_VARIANT and does nothing.
  */
 #ifndef ASTRA_ABLATION_H
@@ -27,11 +27,14 @@ typedef enum {
     ASTRA_VARIANT_SCALAR_LOADS = 1,       /* all three: one 16-bit element per load/store instead of 128-bit vectors */
     ASTRA_VARIANT_LDS_TREE_REDUCTION = 2, /* fused_add_rmsnorm: LDS tree with a barrier per step instead of DPP + one LDS float per wave */
     ASTRA_VARIANT_UNHOISTED_WEIGHTS = 3,  /* merge_attn_states_lse: mixing weights recomputed for every element */
-    ASTRA_VARIANT_LIBM_EXP_DIVIDE = 4     /* silu_and_mul: library expf and an IEEE divide instead of v_exp_f32 / v_rcp_f32 */
+    ASTRA_VARIANT_LIBM_EXP_DIVIDE = 4,    /* silu_and_mul: library expf and an IEEE divide instead of v_exp_f32 / v_rcp_f32 */
+    ASTRA_VARIANT_ELEMENT_WISE = 5        /* all three: the plain element-wise kernels that astra.h keeps for inputs beyond the
+                                             limits of its other paths, here on any valid input (every storage type, any
+                                             row length and alignment), so that they can be checked and timed at ordinary sizes */
 } astra_variant_t;
 
 #define ASTRA_ERR_VARIANT 8 /* astra_status_t value: variant not applicable to this operator, shape or storage type
-                               (the variants other than TUNED exist for the 16-bit types only) */
+                               (variants 1 to 4 exist for the 16-bit types only) */
 
 astra_status_t astra_ablation_fused_add_rmsnorm(void* input, void* residual, const void* weight, int64_t T, int64_t H,
                                                 astra_dtype_t dtype, float eps, astra_variant_t variant,

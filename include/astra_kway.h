@@ -19,7 +19,8 @@
  * That equals the definition up to binary32 rounding.  A single non-empty partition is returned unchanged; all
  * partitions empty give V_out = 0 and S_out = -inf.  K = 2 computes what astra_merge_attn_states_lse
  * computes on the two slices.  Outputs must not overlap inputs (ASTRA_ERR_ALIAS).  K must be in
- * [1, 65536] (ASTRA_ERR_SHAPE otherwise).  Everything else -- ownership, stream, validation order,
+ * [1, 65536] and the output must hold at most 2^31 16-byte vectors, counting a partial last vector of a pair as
+ * one (ASTRA_ERR_SHAPE otherwise).  Everything else -- ownership, stream, validation order,
  * alignment rules, the slower paths for a head_dim that is not a whole number of 16-byte vectors or for pointers that
  * are only element aligned -- is as in astra.h.
  */

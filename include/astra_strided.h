@@ -3,8 +3,9 @@
  * of larger buffers.  Arithmetic, rounding, ownership, stream and validation order are those of astra.h; strides
  * are in elements; a stride smaller than the extent it has to span is ASTRA_ERR_SHAPE; overlap is judged on the
  * bounding byte ranges of the views.  The fast path needs 16-byte aligned pointers and row lengths and strides
- * that are multiples of 16 bytes; anything else takes the ragged or the element-wise path of astra.h (same results
- * up to the order of binary32 roundings).
+ * that are multiples of 16 bytes; anything else takes the ragged path of astra.h (same results up to the order of
+ * binary32 roundings).  The silu_and_mul and merge_attn_states_lse views may hold at most 2^31 16-byte output
+ * vectors, counting a partial last vector of a row as one (ASTRA_ERR_SHAPE otherwise).
  *
  * fused_add_rmsnorm (Kernel 2: y = (x+r)/sqrt(||x+r||^2/H + eps) (.) w) on row-strided views, with the results
  * written somewhere else than the operands if wanted.  Same arithmetic and rounding as astra_fused_add_rmsnorm (residual = one binary32 add rounded

@@ -25,6 +25,7 @@ ASTRA_VARIANT_SCALAR_LOADS = 1
 ASTRA_VARIANT_LDS_TREE_REDUCTION = 2
 ASTRA_VARIANT_UNHOISTED_WEIGHTS = 3
 ASTRA_VARIANT_LIBM_EXP_DIVIDE = 4
+ASTRA_VARIANT_ELEMENT_WISE = 5
 ASTRA_ERR_VARIANT = 8
 
 _PKG = os.path.dirname(os.path.abspath(__file__))

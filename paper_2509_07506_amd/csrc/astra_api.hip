@@ -231,12 +231,6 @@ template <int DT>
 void launch_merge_kway(const astra_launch_info_t& li, void* v_out, float* lse_out, const void* v_parts,
                        const float* lse_parts, int64_t K, int64_t pairs, int64_t D, hipStream_t stream)
 {
-    if (li.path == ASTRA_PATH_GENERIC) {
-        typedef typename Storage<DT>::elem_t E;
-        merge_attn_states_lse_kway_generic_kernel<DT><<<dim3((uint32_t)li.grid), dim3(256), 0, stream>>>(
-            static_cast<E*>(v_out), lse_out, static_cast<const E*>(v_parts), lse_parts, (uint32_t)K, pairs, D);
-        return;
-    }
     if (li.path == ASTRA_PATH_RAGGED) {
         typedef typename Storage<DT>::elem_t E;
         const uint32_t dvr = (uint32_t)((D + Storage<DT>::kN - 1) / Storage<DT>::kN);
@@ -348,7 +342,9 @@ static astra_status_t run_fused_add_rmsnorm(void* input, void* residual, const v
     if (overlaps(input, bytes, residual, bytes) || overlaps(input, bytes, weight, H * eb) ||
         overlaps(residual, bytes, weight, H * eb))
         return ASTRA_ERR_ALIAS;
-    if (variant != ASTRA_VARIANT_TUNED) {
+    if (variant == ASTRA_VARIANT_ELEMENT_WISE) {
+        li = astra_launch_info_t{T > 0 ? ASTRA_PATH_GENERIC : ASTRA_PATH_NONE, 256, 0, 0, T < kMaxGenericGrid ? T : kMaxGenericGrid, 0, 0};
+    } else if (variant != ASTRA_VARIANT_TUNED) {
         if (dtype == ASTRA_F32) return (astra_status_t)ASTRA_ERR_VARIANT;
         if (variant != ASTRA_VARIANT_SCALAR_LOADS && variant != ASTRA_VARIANT_LDS_TREE_REDUCTION) return (astra_status_t)ASTRA_ERR_VARIANT;
         if (T > 0 && li.path != ASTRA_PATH_VECTOR) return (astra_status_t)ASTRA_ERR_VARIANT;
@@ -383,7 +379,9 @@ static astra_status_t run_silu_and_mul(void* out, const void* input, int64_t T, 
     if (!valid_dtype((int)dtype)) return ASTRA_ERR_DTYPE;
     if (!aligned(out, eb) || !aligned(input, eb)) return ASTRA_ERR_ALIGN;
     if (overlaps(out, T * d * eb, input, T * d * 2 * eb)) return ASTRA_ERR_ALIAS;
-    if (variant != ASTRA_VARIANT_TUNED) {
+    if (variant == ASTRA_VARIANT_ELEMENT_WISE) {
+        li = astra_launch_info_t{T > 0 ? ASTRA_PATH_GENERIC : ASTRA_PATH_NONE, 256, 0, 0, T < kMaxGenericGrid ? T : kMaxGenericGrid, 0, 0};
+    } else if (variant != ASTRA_VARIANT_TUNED) {
         if (dtype == ASTRA_F32) return (astra_status_t)ASTRA_ERR_VARIANT;
         if (variant != ASTRA_VARIANT_SCALAR_LOADS && variant != ASTRA_VARIANT_LIBM_EXP_DIVIDE) return (astra_status_t)ASTRA_ERR_VARIANT;
         if (T > 0 && li.path != ASTRA_PATH_VECTOR) return (astra_status_t)ASTRA_ERR_VARIANT;
@@ -428,7 +426,9 @@ static astra_status_t run_merge_attn_states_lse(void* v_out, float* lse_out, con
         overlaps(lse_out, sbytes, v_a, vbytes) || overlaps(lse_out, sbytes, v_b, vbytes) ||
         overlaps(lse_out, sbytes, v_out, vbytes))
         return ASTRA_ERR_ALIAS;
-    if (variant != ASTRA_VARIANT_TUNED) {
+    if (variant == ASTRA_VARIANT_ELEMENT_WISE) {
+        li = astra_launch_info_t{T > 0 ? ASTRA_PATH_GENERIC : ASTRA_PATH_NONE, 256, 0, 0, pairs < kMaxGenericGrid ? pairs : kMaxGenericGrid, 0, 0};
+    } else if (variant != ASTRA_VARIANT_TUNED) {
         if (dtype == ASTRA_F32) return (astra_status_t)ASTRA_ERR_VARIANT;
         if (variant != ASTRA_VARIANT_SCALAR_LOADS && variant != ASTRA_VARIANT_UNHOISTED_WEIGHTS) return (astra_status_t)ASTRA_ERR_VARIANT;
         if (T > 0 && li.path != ASTRA_PATH_VECTOR) return (astra_status_t)ASTRA_ERR_VARIANT;
@@ -467,6 +467,7 @@ astra_status_t astra_merge_attn_states_lse_kway(void* v_out, float* lse_out, con
     const int eb = elem_bytes((int)dtype);
     astra_status_t st = plan_merge(T, num_heads, head_dim, eb, aligned(v_out, 16) && aligned(v_parts, 16), &li);
     if (st != ASTRA_OK) return st;
+    if (li.path == ASTRA_PATH_GENERIC) return ASTRA_ERR_SHAPE;  // more than 2^31 output vectors
     const int64_t pairs = T * num_heads;
     int64_t part_elems = pairs * head_dim, all_elems;
     if (K < 1 || K > 65536 || mul_overflows(part_elems, K, &all_elems) || all_elems > std::numeric_limits<int64_t>::max() / 4)
@@ -536,6 +537,7 @@ astra_status_t astra_silu_and_mul_strided(void* out, int64_t out_stride, const v
     astra_launch_info_t li;
     astra_status_t st = plan_silu(T, d, eb, fast, &li);
     if (st != ASTRA_OK) return st;
+    if (li.path == ASTRA_PATH_GENERIC) return ASTRA_ERR_SHAPE;  // more than 2^31 output vectors
     int64_t out_rows, in_rows;
     if (out_stride < d || in_stride < 2 * d || mul_overflows(T > 0 ? T - 1 : 0, out_stride, &out_rows) ||
         mul_overflows(T > 0 ? T - 1 : 0, in_stride, &in_rows) || out_rows > std::numeric_limits<int64_t>::max() / 8 ||
@@ -549,10 +551,7 @@ astra_status_t astra_silu_and_mul_strided(void* out, int64_t out_stride, const v
     for_dtype(dtype, [&](auto dtc) {
         constexpr int DT = decltype(dtc)::value;
         typedef typename Storage<DT>::elem_t E;
-        if (li.path == ASTRA_PATH_GENERIC) {
-            silu_and_mul_strided_generic_kernel<DT><<<dim3((uint32_t)li.grid), dim3(256), 0, stream>>>(
-                static_cast<E*>(out), out_stride, static_cast<const E*>(input), in_stride, T, d);
-        } else if (li.path == ASTRA_PATH_RAGGED) {
+        if (li.path == ASTRA_PATH_RAGGED) {
             const uint32_t dvr = (uint32_t)((d + Storage<DT>::kN - 1) / Storage<DT>::kN);
             silu_and_mul_ragged_kernel<DT, kNTLoad, kNTStore><<<dim3((uint32_t)li.grid), dim3(256), 0, stream>>>(
                 static_cast<E*>(out), out_stride, static_cast<const E*>(input), in_stride, (uint32_t)(T * dvr), dvr, d,
@@ -585,6 +584,7 @@ astra_status_t astra_merge_attn_states_lse_strided(void* v_out, int64_t out_toke
     astra_launch_info_t li;
     astra_status_t st = plan_merge(T, num_heads, head_dim, eb, fast, &li);
     if (st != ASTRA_OK) return st;
+    if (li.path == ASTRA_PATH_GENERIC) return ASTRA_ERR_SHAPE;  // more than 2^31 output vectors
     int64_t span[3];  // bounding extent of each value view in bytes
     for (int i = 0; i < 3; ++i) {
         int64_t heads_ext, tok_ext, total;
@@ -613,12 +613,7 @@ astra_status_t astra_merge_attn_states_lse_strided(void* v_out, int64_t out_toke
         constexpr int DT = decltype(dtc)::value;
         constexpr int N = Storage<DT>::kN;
         typedef typename Storage<DT>::elem_t E;
-        if (li.path == ASTRA_PATH_GENERIC) {
-            const ValueStrides vs{ts[0], hs[0], ts[1], hs[1], ts[2], hs[2]};
-            merge_attn_states_lse_strided_generic_kernel<DT><<<dim3((uint32_t)li.grid), dim3(256), 0, stream>>>(
-                static_cast<E*>(v_out), lse_out, static_cast<const E*>(v_a), lse_a, static_cast<const E*>(v_b), lse_b, vs, pairs,
-                num_heads, head_dim);
-        } else if (li.path == ASTRA_PATH_RAGGED) {
+        if (li.path == ASTRA_PATH_RAGGED) {
             const ValueStrides vs{ts[0], hs[0], ts[1], hs[1], ts[2], hs[2]};
             const uint32_t dvr = (uint32_t)((head_dim + N - 1) / N);
             merge_attn_states_lse_ragged_kernel<DT, kNTLoad, kNTStore, true><<<dim3((uint32_t)li.grid), dim3(256), 0, stream>>>(

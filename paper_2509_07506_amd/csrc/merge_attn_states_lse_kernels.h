@@ -181,47 +181,8 @@ __global__ __launch_bounds__(256) void merge_attn_states_lse_strided_vec_kernel(
     if (jv == 0) lse_out[pair] = w.lse;
 }
 
-template <int DT>
-__global__ __launch_bounds__(256) void merge_attn_states_lse_strided_generic_kernel(
-    typename Storage<DT>::elem_t* v_out, float* lse_out, const typename Storage<DT>::elem_t* v_a, const float* lse_a,
-    const typename Storage<DT>::elem_t* v_b, const float* lse_b, ValueStrides vs, int64_t pairs, int64_t heads, int64_t D)
-{
-    for (int64_t p = blockIdx.x; p < pairs; p += gridDim.x) {
-        const int64_t t = p / heads, h = p - t * heads;
-        const MergeWeights w = merge_weights(lse_a[p], lse_b[p]);
-        const typename Storage<DT>::elem_t* pa = v_a + t * vs.a_token + h * vs.a_head;
-        const typename Storage<DT>::elem_t* pb = v_b + t * vs.b_token + h * vs.b_head;
-        typename Storage<DT>::elem_t* po = v_out + t * vs.out_token + h * vs.out_head;
-        for (int64_t k = threadIdx.x; k < D; k += blockDim.x)
-            po[k] = Storage<DT>::narrow(w.a * Storage<DT>::widen(pa[k]) + w.b * Storage<DT>::widen(pb[k]));
-        if (threadIdx.x == 0) lse_out[p] = w.lse;
-    }
-}
-
 // ---------------------------------------------------------------------------------------------
 // K-way merge: V_out = sum_k e^(S_k) V_k / sum_k e^(S_k), S_out = log sum_k e^(S_k).
-// kway_stats is the plain three-pass evaluation used by the element-wise path.
-
-struct KwayStats {
-    float m0;   // maximum score (0 when every partition is empty)
-    float inv;  // 1 / sum_k e^(S_k - m0)   (0 when every partition is empty)
-    float lse;
-};
-
-__device__ __forceinline__ KwayStats kway_stats(const float* lse_parts, uint32_t K, size_t pairs, size_t pair)
-{
-    const float ninf = -__builtin_inff();
-    float m = ninf;
-    for (uint32_t k = 0; k < K; ++k) m = fmaxf(m, lse_parts[k * pairs + pair]);
-    const bool empty = (m == ninf);
-    KwayStats st;
-    st.m0 = empty ? 0.0f : m;
-    float den = 0.0f;
-    for (uint32_t k = 0; k < K; ++k) den += fast_exp(lse_parts[k * pairs + pair] - st.m0);
-    st.inv = empty ? 0.0f : fast_rcp(den);
-    st.lse = empty ? ninf : m + fast_log(den);
-    return st;
-}
 
 // Fast path: one lane per output vector; part k of vector i lives at v_parts[k * total_vecs + i].
 // Streaming form: the parts are taken in groups of G.  All G scores and G vectors of a group are
@@ -353,28 +314,6 @@ __global__ __launch_bounds__(256) void merge_attn_states_lse_kway_ragged_kernel(
     for (int e = 0; e < N; ++e) acc[e] *= inv;
     store_row_elems<DT, NTS>(v_out + (int64_t)pair * D, e0, count, shift, acc);
     if (jv == 0) lse_out[pair] = empty ? ninf : m + fast_log(den);
-}
-
-// Element-wise path (inputs beyond the ragged kernel's 32-bit vector index): one block per (token, head) pair.
-template <int DT>
-__global__ __launch_bounds__(256) void merge_attn_states_lse_kway_generic_kernel(typename Storage<DT>::elem_t* __restrict__ v_out,
-                                                                                 float* __restrict__ lse_out,
-                                                                                 const typename Storage<DT>::elem_t* __restrict__ v_parts,
-                                                                                 const float* __restrict__ lse_parts,
-                                                                                 uint32_t K, int64_t pairs, int64_t D)
-{
-    for (int64_t p = blockIdx.x; p < pairs; p += gridDim.x) {
-        const KwayStats st = kway_stats(lse_parts, K, (size_t)pairs, (size_t)p);
-        for (int64_t j = threadIdx.x; j < D; j += blockDim.x) {
-            float acc = 0.0f;
-            for (uint32_t k = 0; k < K; ++k) {
-                const float w = fast_exp(lse_parts[(size_t)k * pairs + p] - st.m0) * st.inv;
-                acc += w * Storage<DT>::widen(v_parts[((size_t)k * pairs + p) * D + j]);
-            }
-            v_out[p * D + j] = Storage<DT>::narrow(acc);
-        }
-        if (threadIdx.x == 0) lse_out[p] = st.lse;
-    }
 }
 
 }  // namespace astra

@@ -126,7 +126,7 @@ __global__ __launch_bounds__(256) void silu_and_mul_generic_kernel(typename Stor
 
 // ---------------------------------------------------------------------------------------------
 // Row-strided views: input row t starts in_stride vectors (elements for the element-wise kernel) after row
-// t-1, likewise the output.  One lane per output vector, row and column from a per-lane fast division,
+// t-1, likewise the output (views with odd strides or extents take the ragged kernel above).  One lane per output vector, row and column from a per-lane fast division,
 // 64-bit offsets (a strided view has no 32-bit bound on its extent).
 
 template <int DT, bool NTL, bool NTS>
@@ -149,21 +149,6 @@ __global__ __launch_bounds__(256) void silu_and_mul_strided_vec_kernel(u32x4* __
 #pragma unroll
     for (int e = 0; e < N; ++e) r[e] = silu_fast(x[e]) * g[e];
     store_vec<NTS>(out + ((int64_t)t * out_stride + j), pack_vec<DT>(r));
-}
-
-template <int DT>
-__global__ __launch_bounds__(256) void silu_and_mul_strided_generic_kernel(typename Storage<DT>::elem_t* __restrict__ out,
-                                                                           int64_t out_stride,
-                                                                           const typename Storage<DT>::elem_t* __restrict__ in,
-                                                                           int64_t in_stride, int64_t T, int64_t d)
-{
-    typedef typename Storage<DT>::elem_t E;
-    for (int64_t t = blockIdx.x; t < T; t += gridDim.x) {
-        const E* row = in + t * in_stride;
-        E* orow = out + t * out_stride;
-        for (int64_t j = threadIdx.x; j < d; j += blockDim.x)
-            orow[j] = Storage<DT>::narrow(silu_fast(Storage<DT>::widen(row[j])) * Storage<DT>::widen(row[d + j]));
-    }
 }
 
 }  // namespace astra

@@ -113,6 +113,8 @@ def test_strided_silu_and_merge_validation(A):
     assert f(a, 8, a + 24, 16, 2, 8, 1) == 6                            # out rows [a, a+32) meet input [a+24, ...)
     assert f(a, 64, a + 64, 64, 2, 8, 1) == 6                           # interleaved views: bounding ranges overlap
     assert f(a, 8, b, 16, 0, 8, 1) == 0
+    big_d = (1 << 14) + 8                                               # 2049 vectors per row, 2^20 rows: over 2^31 vectors
+    assert f(a, big_d, b, 2 * big_d, 1 << 20, big_d, 1) == 2
     g = A.astra_merge_attn_states_lse_strided
     vo, lo, va, la, vb, lb = 0x100000, 0x200000, 0x300000, 0x400000, 0x500000, 0x600000
 
@@ -132,6 +134,7 @@ def test_strided_silu_and_merge_validation(A):
     assert call(va=vo, ats=32) == 6                                      # same pointer but another stride: not the same view
     assert call(lo=la) == 6
     assert call(T=0) == 0
+    assert call(T=1 << 24, NH=64, D=136, ots=64 * 136, ohs=136, ats=64 * 136, ahs=136, bts=64 * 136, bhs=136) == 2   # 2^30 pairs x 17 vectors
 
 
 def test_stream_copy_validation(A):
@@ -309,6 +312,7 @@ def test_kway_validation_without_gpu(A):
     assert g(vo + 1, lo, vp, lp, 2, 1, 2, 8, 1) == 5 and g(vo, lo + 2, vp, lp, 2, 1, 2, 8, 1) == 5
     assert g(vp + 32, lo, vp, lp, 3, 1, 2, 8, 1) == 6                  # output inside the second part
     assert g(vo, lo, vp, lp, 2, 0, 2, 8, 1) == 0
+    assert g(vo, lo, vp, lp, 2, 1 << 24, 64, 136, 1) == 2             # 2^30 pairs x 17 vectors: over 2^31 output vectors
 
 
 def test_strided_validation_without_gpu(A):

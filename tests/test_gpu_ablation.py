@@ -114,6 +114,23 @@ def test_merge_variants_edge_shapes(A, T, NH, D, dt):
         _merge(A, *m, dt, v)
 
 
+@pytest.mark.parametrize("dt", ["bf16", "f16"])
+def test_element_wise_variant_on_any_input(A, dt):
+    """ASTRA_VARIANT_ELEMENT_WISE: the plain element-wise kernels, which astra.h itself only takes for inputs beyond
+    the limits of its other paths, on fast-path, ragged and long-row shapes."""
+    v = A.ASTRA_VARIANT_ELEMENT_WISE
+    for T, H in [(3, 8), (5, 523), (7, 5120), (40, 8192), (2, 70000), (300, 4099), (4, 1)]:
+        print(f"[ablation] element-wise rmsnorm T={T} H={H} {dt}", flush=True)
+        x, r, w = workloads.rmsnorm_inputs(T, H, dt, np.random.default_rng([34, T, H]), r_std=2.0)
+        _rmsnorm(A, x, r, w, 1e-5, dt, v)
+    for T, d in [(1, 256), (3, 263), (19, 5120), (257, 1409), (5, 1)]:
+        print(f"[ablation] element-wise silu T={T} d={d} {dt}", flush=True)
+        _silu(A, workloads.silu_inputs(T, d, dt, np.random.default_rng([35, T, d])), dt, v)
+    for T, NH, D in [(1, 1, 8), (7, 3, 75), (257, 40, 64), (33, 32, 128), (5, 2, 1)]:
+        print(f"[ablation] element-wise merge T={T} NH={NH} D={D} {dt}", flush=True)
+        _merge(A, *workloads.merge_inputs(T, NH, D, dt, np.random.default_rng([36, T, NH, D]), empty_p=0.15), dt, v)
+
+
 def test_variant_validation_on_device(A):
     buf = torch.zeros(1 << 16, dtype=torch.float16, device="cuda")
     p = buf.data_ptr()

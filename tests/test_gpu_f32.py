@@ -206,3 +206,34 @@ def test_ablation_variants_are_16_bit_only(A):
                                             A.ASTRA_VARIANT_TUNED, None)
     torch.cuda.synchronize()
     assert st == 0
+
+
+def test_element_wise_variant(A):
+    """ASTRA_VARIANT_ELEMENT_WISE (include/astra_ablation.h) also takes binary32 storage."""
+    v, code, st = A.ASTRA_VARIANT_ELEMENT_WISE, A.ASTRA_F32, torch.cuda.current_stream().cuda_stream
+    for T, H in [(5, 516), (33, 4099), (2, 40000)]:
+        x, r, w = workloads.rmsnorm_inputs(T, H, DT, _rng(20, T, H), r_std=2.0)
+        xd, rd, wd = to_dev(x, DT), to_dev(r, DT), to_dev(w, DT)
+        assert A.astra_ablation_fused_add_rmsnorm(xd.data_ptr(), rd.data_ptr(), wd.data_ptr(), T, H, code, 1e-5, v, st) == 0
+        torch.cuda.synchronize()
+        s_ref, y_ref = O.fused_add_rmsnorm_f32(x, r, w, 1e-5)
+        assert_bits_equal(u32(to_bits(rd)), u32(s_ref), "element-wise rmsnorm: residual (bit-exact)")
+        assert_storage_close(to_bits(xd), y_ref, DT, "element-wise rmsnorm: normalised output")
+    for T, d in [(7, 1412), (3, 101)]:
+        a = workloads.silu_inputs(T, d, DT, _rng(21, T, d))
+        ad = to_dev(a, DT)
+        out = torch.empty((T, d), dtype=torch.float32, device="cuda")
+        assert A.astra_ablation_silu_and_mul(out.data_ptr(), ad.data_ptr(), T, d, code, v, st) == 0
+        torch.cuda.synchronize()
+        assert_storage_close(to_bits(out), O.silu_and_mul_f32(a), DT, "element-wise silu")
+    for T, NH, D in [(9, 8, 128), (5, 7, 37)]:
+        va, la, vb, lb = workloads.merge_inputs(T, NH, D, DT, _rng(22, T, NH, D), empty_p=0.1)
+        vad, vbd = to_dev(va, DT), to_dev(vb, DT)
+        lad, lbd = torch.from_numpy(la).cuda(), torch.from_numpy(lb).cuda()
+        vo, lo = torch.empty_like(vad), torch.empty_like(lad)
+        assert A.astra_ablation_merge_attn_states_lse(vo.data_ptr(), lo.data_ptr(), vad.data_ptr(), lad.data_ptr(), vbd.data_ptr(),
+                                                      lbd.data_ptr(), T, NH, D, code, v, st) == 0
+        torch.cuda.synchronize()
+        vo_ref, lo_ref = O.merge_attn_states_lse_f32(va, la, vb, lb)
+        assert_storage_close(to_bits(vo), vo_ref, DT, "element-wise merge: v_out")
+        assert_lse_close(lo.cpu().numpy(), lo_ref, "element-wise merge: lse_out")
