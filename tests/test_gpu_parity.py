@@ -480,11 +480,12 @@ def test_rmsnorm_beyond_2_31_elements(A):
     assert _all_tiles_equal(xd, B) and _all_tiles_equal(rd, B), "rows beyond the first tile differ"
 
 
-def test_rmsnorm_more_rows_than_the_grid_limit(A):
-    dt, B, H = "f16", 256, 8
-    T = (1 << 21) + 259                                   # the row kernel launches at most 2^21 workgroups
+@pytest.mark.parametrize("H,path", [(8, "vector"), (12, "ragged")])
+def test_rmsnorm_more_rows_than_the_grid_limit(A, H, path):
+    dt, B = "f16", 256
+    T = (1 << 21) + 259                                   # the row kernels launch at most 2^21 workgroups
     st, info = A.astra_plan_fused_add_rmsnorm(T, H, True)
-    assert info.as_dict()["grid"] == 1 << 21
+    assert info.as_dict()["grid"] == 1 << 21 and info.as_dict()["path"] == path
     x, r, w = workloads.rmsnorm_inputs(B, H, dt, np.random.default_rng(51))
     reps = -(-T // B)
     xd = _tile_rows(to_dev(x, dt), reps)[:T].contiguous()
