@@ -19,6 +19,8 @@ taken inside the timed region on the launch stream; `kernels` carries the same f
     python bench.py --ablation       # paper Table-4 shapes: tuned vs one-optimisation-removed variants
     python bench.py --kway           # K-way merge vs a chain of two-way merges
     python bench.py --decode         # decode-sized launches replayed from a HIP graph
+    python bench.py --prefill        # prefill-chunk shapes (T 512..4096, LLaMA dimensions) from a HIP graph, cold
+    python bench.py --vs-eager       # the step's three workloads written with plain PyTorch tensor ops, for context
 """
 from __future__ import annotations
 
