@@ -21,6 +21,7 @@ taken inside the timed region on the launch stream; `kernels` carries the same f
     python bench.py --decode         # decode-sized launches replayed from a HIP graph
     python bench.py --prefill        # prefill-chunk shapes (T 512..4096, LLaMA dimensions) from a HIP graph, cold
     python bench.py --vs-eager       # the step's three workloads written with plain PyTorch tensor ops, for context
+    python bench.py --ragged         # odd row lengths: ragged kernels vs vector and element-wise kernels
 """
 from __future__ import annotations
 
@@ -639,6 +640,55 @@ def run_prefill(args):
         torch.cuda.empty_cache()
 
 
+def run_ragged(args):
+    """Row lengths that are no whole number of 16-byte vectors: the ragged kernels against the vector kernels on the
+    nearest aligned shape and against the plain element-wise kernels (ASTRA_VARIANT_ELEMENT_WISE) on the same shape.
+    T = 16384, bf16; 5 warm-up + 50 launches between one HIP-event pair, alternating over two buffer sets (every set
+    is larger than the last-level cache, so the figures are cold)."""
+    import torch
+
+    import paper_2509_07506_amd as astra
+    import workloads
+
+    astra.load_library()
+    torch.cuda.set_device(0)
+    stream = torch.cuda.current_stream()
+    sh = stream.cuda_stream
+    T = 16384
+    trios = [("rmsnorm", {"T": T, "H": 5120}, {"T": T, "H": 5124}), ("rmsnorm", {"T": T, "H": 5120}, {"T": T, "H": 5121}),
+             ("rmsnorm", {"T": T, "H": 8192}, {"T": T, "H": 8196}),
+             ("silu", {"T": T, "d": 11008}, {"T": T, "d": 11012}), ("silu", {"T": T, "d": 11008}, {"T": T, "d": 11009}),
+             ("merge", {"T": T, "NH": 40, "D": 128}, {"T": T, "NH": 40, "D": 132}),
+             ("merge", {"T": T, "NH": 40, "D": 128}, {"T": T, "NH": 40, "D": 129})]
+
+    def timed(L, reps=50, warm=5):
+        for k in range(warm):
+            L.launch(sh, k % L.nsets)
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(stream)
+        for k in range(reps):
+            L.launch(sh, k % L.nsets)
+        b.record(stream)
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) * 1e3 / reps
+
+    for i, (kernel, aligned_shape, odd_shape) in enumerate(trios):
+        out = {"kernel": kernel}
+        for label, shape, variant in (("vector", aligned_shape, 0), ("ragged", odd_shape, 0),
+                                      ("element_wise", odd_shape, astra.ASTRA_VARIANT_ELEMENT_WISE)):
+            c = workloads.Case(f"odd_{kernel}_{i}_{label}", kernel, 8, i, "bf16", shape, eps=1e-5, r_std=2.0)
+            L = Launcher(astra, c, c.generate(), 2, variant)
+            us = timed(L)
+            out[label] = {"shape": shape, "path": L.plan["path"] if variant == 0 else "generic", "us": round(us, 2),
+                          "GBs": round(c.algorithmic_bytes() / us / 1e3, 1)}
+            del L
+            torch.cuda.empty_cache()
+        out["ragged_over_element_wise"] = round(out["element_wise"]["us"] / out["ragged"]["us"], 2)
+        out["ragged_frac_of_vector_rate"] = round(out["ragged"]["GBs"] / out["vector"]["GBs"], 3)
+        print(json.dumps(out), flush=True)
+
+
 def run_ceiling(args):
     """Streaming ceiling of this machine with the operators' access pattern: astra_stream_copy over
     512 MiB, alternating between two source/destination pairs (2 GiB footprint, so always cold)."""
@@ -780,6 +830,7 @@ def main():
     ap.add_argument("--kway", action="store_true", help="K-way merge vs a chain of two-way merges")
     ap.add_argument("--decode", action="store_true", help="decode-sized launches replayed from a HIP graph")
     ap.add_argument("--prefill", action="store_true", help="prefill-chunk shapes replayed from a HIP graph, cold")
+    ap.add_argument("--ragged", action="store_true", help="odd row lengths: ragged vs vector vs element-wise kernels")
     ap.add_argument("--vs-eager", action="store_true",
                     help="context: the step workloads through this library and through plain PyTorch tensor ops")
     ap.add_argument("--ablation", action="store_true",
@@ -793,6 +844,8 @@ def main():
         run_vs_eager(args)
     elif args.prefill:
         run_prefill(args)
+    elif args.ragged:
+        run_ragged(args)
     elif args.decode:
         run_decode(args)
     elif args.kway:
