@@ -30,7 +30,7 @@ typedef struct {
     int32_t log2_xcd_chunk;   /* workgroups an XCD runs back to back cover 2^this consecutive work units */
     int64_t grid;             /* workgroups launched (padded to a multiple of 8 * 2^log2_xcd_chunk) */
     int32_t pace;             /* fused_add_rmsnorm fast path only: ASTRA_PACE_* bits, when a wave issues its requests */
-    int32_t reserved;         /* 0 */
+    int32_t rows_per_block;   /* fused_add_rmsnorm on rows of at most 32 vectors: rows one workgroup handles; otherwise 0 */
 } astra_launch_info_t;
 
 /* Request pacing of the fused_add_rmsnorm row kernel.  Same arithmetic and bytes for every value; the order in time of

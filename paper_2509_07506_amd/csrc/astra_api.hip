@@ -71,6 +71,36 @@ void launch_rmsnorm_row(const astra_launch_info_t& li, void* input, void* residu
     }
 }
 
+// rows of at most 32 vectors, 256 / G rows per workgroup; `views` (strides in vectors) only when STRIDED
+template <int DT, bool STRIDED>
+void launch_rmsnorm_short(const astra_launch_info_t& li, void* input, void* residual, const void* weight, int64_t T, int64_t H,
+                          float eps, hipStream_t stream, void* y_out = nullptr, void* r_out = nullptr,
+                          const RowViews& views = RowViews{0, 0, 0, 0})
+{
+    const uint32_t hv = (uint32_t)(H / Storage<DT>::kN);
+    u32x4* const in = static_cast<u32x4*>(input);
+    u32x4* const res = static_cast<u32x4*>(residual);
+    const u32x4* const w = static_cast<const u32x4*>(weight);
+    u32x4* const yo = static_cast<u32x4*>(y_out);
+    u32x4* const ro = static_cast<u32x4*>(r_out);
+    const dim3 grid((uint32_t)li.grid), block(256);
+    const float inv_h = 1.0f / (float)H;
+    switch (256 / li.rows_per_block) {
+        case 8:
+            fused_add_rmsnorm_short_row_kernel<DT, 8, kNTLoad, kNTStore, STRIDED>
+                <<<grid, block, 0, stream>>>(in, res, w, T, hv, inv_h, eps, li.log2_xcd_chunk, yo, ro, views);
+            break;
+        case 16:
+            fused_add_rmsnorm_short_row_kernel<DT, 16, kNTLoad, kNTStore, STRIDED>
+                <<<grid, block, 0, stream>>>(in, res, w, T, hv, inv_h, eps, li.log2_xcd_chunk, yo, ro, views);
+            break;
+        default:
+            fused_add_rmsnorm_short_row_kernel<DT, 32, kNTLoad, kNTStore, STRIDED>
+                <<<grid, block, 0, stream>>>(in, res, w, T, hv, inv_h, eps, li.log2_xcd_chunk, yo, ro, views);
+            break;
+    }
+}
+
 // `ev` holds the row strides in elements; in place: y_out = x, r_out = r
 template <int DT>
 void launch_rmsnorm_ragged(const astra_launch_info_t& li, void* y_out, void* r_out, const void* x, const void* r,
@@ -130,6 +160,10 @@ void launch_rmsnorm(const astra_launch_info_t& li, void* input, void* residual, 
     }
     if (li.path == ASTRA_PATH_RAGGED) {
         launch_rmsnorm_ragged<DT>(li, input, residual, input, residual, weight, RowViews{H, H, H, H}, T, H, eps, stream);
+        return;
+    }
+    if (li.rows_per_block > 0) {
+        launch_rmsnorm_short<DT, false>(li, input, residual, weight, T, H, eps, stream);
         return;
     }
     switch (li.vectors_per_lane) {
@@ -267,6 +301,10 @@ void launch_rmsnorm_strided(const astra_launch_info_t& li, void* y_out, void* r_
     const RowViews vv{ev.y_stride / N, ev.r_out_stride / N, ev.x_stride / N, ev.r_stride / N};
     void* const xin = const_cast<void*>(x);  // read only when STRIDED
     void* const rin = const_cast<void*>(r);
+    if (li.rows_per_block > 0) {
+        launch_rmsnorm_short<DT, true>(li, xin, rin, weight, T, H, eps, stream, y_out, r_out, vv);
+        return;
+    }
     switch (li.vectors_per_lane) {
         case 1: launch_rmsnorm_row<DT, 1, 1024, false, true>(li, xin, rin, weight, T, H, eps, stream, y_out, r_out, vv); break;
         case 2: launch_rmsnorm_row<DT, 2, 1024, false, true>(li, xin, rin, weight, T, H, eps, stream, y_out, r_out, vv); break;
@@ -333,7 +371,7 @@ static astra_status_t run_fused_add_rmsnorm(void* input, void* residual, const v
     astra_launch_info_t li;
     const bool a16 = aligned(input, 16) && aligned(residual, 16) && aligned(weight, 16);
     const int eb = elem_bytes((int)dtype);
-    astra_status_t st = plan_rmsnorm(T, H, eb, a16, &li);
+    astra_status_t st = plan_rmsnorm(T, H, eb, a16, &li, variant == ASTRA_VARIANT_TUNED);
     if (st != ASTRA_OK) return st;
     if (!valid_dtype((int)dtype)) return ASTRA_ERR_DTYPE;
     if (!(eps >= 0.0f)) return ASTRA_ERR_EPS;

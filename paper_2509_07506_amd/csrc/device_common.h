@@ -306,6 +306,26 @@ __device__ __forceinline__ float wave_sum(float v)
     return (r0 + r1) + (r2 + r3);
 }
 
+// Sum over each aligned group of G = 8, 16 or 32 consecutive lanes; every lane gets its group's sum.  The same DPP
+// steps as wave_sum, stopped early; for 32 lanes the two 16-lane row sums are combined through the scalar unit.
+template <int G>
+__device__ __forceinline__ float group_sum(float v)
+{
+    static_assert(G == 8 || G == 16 || G == 32, "group of 8, 16 or 32 lanes");
+    v += dpp_move<0xB1>(v);   // quad_perm [1,0,3,2]
+    v += dpp_move<0x4E>(v);   // quad_perm [2,3,0,1]
+    v += dpp_move<0x141>(v);  // row_half_mirror
+    if constexpr (G == 8) return v;
+    v += dpp_move<0x140>(v);  // row_mirror
+    if constexpr (G == 16) return v;
+    int iv = __builtin_bit_cast(int, v);
+    float r0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 0));
+    float r1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 16));
+    float r2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 32));
+    float r3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 48));
+    return (threadIdx.x & 32u) ? r2 + r3 : r0 + r1;
+}
+
 // Sum over a workgroup of `nwaves` full waves (blockDim.x == nwaves * 64, at most 16 waves).  One LDS
 // float per wave and one barrier; every lane then adds the partials in the same order.  `lds` must
 // hold 16 floats and must not be reused before the next barrier of the caller.

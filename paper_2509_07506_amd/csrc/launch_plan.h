@@ -215,7 +215,13 @@ inline bool rmsnorm_row_policy(int64_t T, int64_t hv, int64_t row_bytes, RowPlan
     return true;
 }
 
-inline astra_status_t plan_rmsnorm(int64_t T, int64_t H, int eb, bool aligned16, astra_launch_info_t* info)
+// Rows of at most kShortRowVecs vectors share a workgroup (fused_add_rmsnorm_short_row_kernel): lanes per row
+constexpr int64_t kShortRowVecs = 32;
+inline int short_row_group(int64_t hv) { return hv <= 8 ? 8 : hv <= 16 ? 16 : 32; }
+
+// `short_rows`: the caller can launch the short-row kernel (the ablation variants, which restage the row kernel, cannot)
+inline astra_status_t plan_rmsnorm(int64_t T, int64_t H, int eb, bool aligned16, astra_launch_info_t* info,
+                                   bool short_rows = true)
 {
     const int64_t ne = kVecBytes / eb;  // elements per 16-byte vector
     int64_t n;
@@ -224,7 +230,13 @@ inline astra_status_t plan_rmsnorm(int64_t T, int64_t H, int eb, bool aligned16,
     if (T == 0) return ASTRA_OK;
     RowPlan rp;
     int pace = kPaceNone;
-    if (aligned16 && H % ne == 0 && rmsnorm_row_policy(T, H / ne, H * eb, &rp, &pace)) {
+    const int64_t short_rows_per_block = 256 / short_row_group(H / ne);
+    if (short_rows && aligned16 && H % ne == 0 && H / ne <= kShortRowVecs &&
+        (T + short_rows_per_block - 1) / short_rows_per_block <= kMaxRowGrid) {
+        const int64_t blocks = (T + short_rows_per_block - 1) / short_rows_per_block;
+        const int lc = fit_chunk_log2(blocks, kFlatChunkLog2, kFlatChunkMinBlocks);  // a workgroup streams 4 KiB, like the flat kernels
+        *info = astra_launch_info_t{ASTRA_PATH_VECTOR, 256, 1, lc, pad_grid(blocks, lc), kPaceNone, (int32_t)short_rows_per_block};
+    } else if (aligned16 && H % ne == 0 && rmsnorm_row_policy(T, H / ne, H * eb, &rp, &pace)) {
         const int64_t rows = T < kMaxRowGrid ? T : kMaxRowGrid;
         const int lc = fit_chunk_log2(rows, kRowChunkBytesLog2 - floor_log2(H * eb), kRowChunkMinRows);
         if (T >= kMaxRowGrid) pace = kPaceNone;  // the row-loop kernel is not paced

@@ -178,8 +178,16 @@ def test_rmsnorm_plans(A):
     assert p["path"] == "ragged" and p["log2_xcd_chunk"] == 5 and p["grid"] == 4352 and p["block"] == 640
     assert plan(4, 32775)["path"] == "ragged" and plan(4, 8199)["vectors_per_lane"] == 1
     assert plan(4, 65536)["path"] == "generic" and plan(4, 32776)["path"] == "generic"   # more than 4096 vectors
-    big = plan(1 << 23, 64)                                            # row loop beyond the grid limit
+    big = plan(1 << 23, 264)                                           # row loop beyond the grid limit
     assert big["grid"] == 1 << 21 and big["grid"] % (8 << big["log2_xcd_chunk"]) == 0
+    # rows of at most 32 vectors share a workgroup: 8, 16 or 32 lanes per row, 256-lane workgroups
+    assert plan(1 << 23, 64) == {"path": "vector", "block": 256, "vectors_per_lane": 1, "log2_xcd_chunk": 8, "grid": 1 << 18,
+                                 "pace": 0, "rows_per_block": 32}
+    assert plan(1000, 128)["rows_per_block"] == 16 and plan(1000, 128)["grid"] == 63 and plan(1000, 136)["rows_per_block"] == 8
+    assert plan(5, 256)["rows_per_block"] == 8 and plan(5, 256)["grid"] == 1 and "rows_per_block" not in plan(5, 264)
+    assert "rows_per_block" not in plan(5, 260) and plan(5, 260)["path"] == "ragged"
+    assert plan(1 << 26, 8)["rows_per_block"] == 32 and plan(1 << 26, 8)["grid"] == 1 << 21
+    assert "rows_per_block" not in plan((1 << 26) + 1, 8) and plan((1 << 26) + 1, 8)["block"] == 64   # beyond the grid limit: row loop
     assert A.astra_plan_fused_add_rmsnorm(-1, 8, True)[0] == 2
     # request pacing: none while a compute unit requests under 48 KiB at once and for the row-loop kernel; on streaming
     # grids (three rounds or more) "store gap" (4) by default on long grids, weight-then-x-then-r (1 | 2) for 4 KiB / 16 KiB rows and

@@ -146,6 +146,19 @@ def test_rmsnorm_streaming_grids(A, T, H, dt):
     check_rmsnorm(A, x, r, w, 1e-5, dt, f"rmsnorm T={T} H={H} {dt}")
 
 
+@pytest.mark.parametrize("dt", ["bf16", "f16"])
+@pytest.mark.parametrize("T,H,rows", [(1, 8, 32), (7, 16, 32), (33, 24, 32), (1000, 64, 32), (5000, 72, 16), (257, 128, 16),
+                                      (4099, 136, 8), (65, 200, 8), (3, 256, 8), (100000, 128, 16)])
+def test_rmsnorm_short_rows_share_a_workgroup(A, T, H, rows, dt):
+    """Rows of at most 32 vectors: 8, 16 or 32 lanes per row, several rows per workgroup, the sum inside the wave;
+    ragged last workgroups and rows that leave lanes of their group idle included."""
+    plan = A.astra_plan_fused_add_rmsnorm(T, H, True)[1].as_dict()
+    _say(f"[parity] rmsnorm short rows T={T} H={H} {dt} plan={plan}")
+    assert plan.get("rows_per_block") == rows and plan["block"] == 256
+    x, r, w = workloads.rmsnorm_inputs(T, H, dt, np.random.default_rng([13, T, H]), r_std=2.0)
+    check_rmsnorm(A, x, r, w, 1e-5, dt, f"rmsnorm T={T} H={H} {dt}")
+
+
 @pytest.mark.parametrize("T,H,dt,vpt,pace", [(1280, 4096, "bf16", 2, 2), (1024, 5120, "f16", 2, 2), (600, 7168, "bf16", 2, 2),
                                              (1537, 3072, "f16", 2, 2), (2560, 2048, "bf16", 2, 2), (5000, 1024, "f16", 2, 2),
                                              (700, 5000, "bf16", 2, 2), (760, 6136, "f16", 2, 2),
@@ -480,7 +493,7 @@ def test_rmsnorm_beyond_2_31_elements(A):
     assert _all_tiles_equal(xd, B) and _all_tiles_equal(rd, B), "rows beyond the first tile differ"
 
 
-@pytest.mark.parametrize("H,path", [(8, "vector"), (12, "ragged")])
+@pytest.mark.parametrize("H,path", [(264, "vector"), (12, "ragged")])
 def test_rmsnorm_more_rows_than_the_grid_limit(A, H, path):
     dt, B = "f16", 256
     T = (1 << 21) + 259                                   # the row kernels launch at most 2^21 workgroups
