@@ -46,7 +46,8 @@ typedef enum {
     ASTRA_ERR_EPS = 4,    /* eps is negative or NaN */
     ASTRA_ERR_ALIGN = 5,  /* a pointer is not aligned to its element size */
     ASTRA_ERR_ALIAS = 6,  /* an output overlaps an input it must not overlap */
-    ASTRA_ERR_LAUNCH = 7  /* the HIP runtime refused the kernel launch */
+    ASTRA_ERR_LAUNCH = 7, /* the HIP runtime refused the kernel launch */
+    ASTRA_ERR_VARIANT = 8 /* astra_ablation.h only: the variant does not apply to this operator, shape or storage type */
 } astra_status_t;
 
 /*

@@ -33,8 +33,8 @@ typedef enum {
                                              row length and alignment), so that they can be checked and timed at ordinary sizes */
 } astra_variant_t;
 
-#define ASTRA_ERR_VARIANT 8 /* astra_status_t value: variant not applicable to this operator, shape or storage type
-                               (variants 1 to 4 exist for the 16-bit types only) */
+/* ASTRA_ERR_VARIANT (astra.h): variant not applicable to this operator, shape or storage type (variants 1 to 4 exist
+ * for the 16-bit types only). */
 
 astra_status_t astra_ablation_fused_add_rmsnorm(void* input, void* residual, const void* weight, int64_t T, int64_t H,
                                                 astra_dtype_t dtype, float eps, astra_variant_t variant,

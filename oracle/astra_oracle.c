@@ -262,8 +262,24 @@ void oracle_merge_weights_f32(float sa, float sb, float* a, float* b, float* s_o
     }
 }
 
+/* One element of the blend a * va + b * vb (two products and one sum).  A term whose weight is exactly zero is
+   left out, its value is not looked at: an empty partition (score -inf) stands for attention over no keys, whose
+   value vector is undefined, and Table 1's weighted mean over the union of the key sets does not depend on it.
+   So one empty side returns the other side's term alone, whatever the empty side's buffer holds. */
+static float blend2(float a, float va, float b, float vb)
+{
+    if (a == 0.0f && b == 0.0f) return 0.0f;
+    if (a == 0.0f) return b * vb;
+    if (b == 0.0f) return a * va;
+    {
+        float pa = a * va;
+        float pb = b * vb;
+        return pa + pb;
+    }
+}
+
 /* v_a, v_b, v_out: [T, NH, D] 16-bit patterns of `dtype`; lse_a, lse_b, lse_out: [T, NH] binary32.
-   v_out = RNE(a * v_a + b * v_b) with two products and one sum. */
+   v_out = RNE(a * v_a + b * v_b), zero-weight terms left out (blend2). */
 void oracle_merge_attn_states_lse(uint16_t* v_out, float* lse_out, const uint16_t* v_a, const float* lse_a,
                                   const uint16_t* v_b, const float* lse_b, int64_t T, int64_t NH, int64_t D,
                                   int dtype)
@@ -273,11 +289,8 @@ void oracle_merge_attn_states_lse(uint16_t* v_out, float* lse_out, const uint16_
         float a, b, s;
         oracle_merge_weights_f32(lse_a[p], lse_b[p], &a, &b, &s);
         lse_out[p] = s;
-        for (int64_t k = 0; k < D; ++k) {
-            float pa = a * widen(v_a[p * D + k], dtype);
-            float pb = b * widen(v_b[p * D + k], dtype);
-            v_out[p * D + k] = narrow(pa + pb, dtype);
-        }
+        for (int64_t k = 0; k < D; ++k)
+            v_out[p * D + k] = narrow(blend2(a, widen(v_a[p * D + k], dtype), b, widen(v_b[p * D + k], dtype)), dtype);
     }
 }
 
@@ -286,7 +299,8 @@ void oracle_merge_attn_states_lse(uint16_t* v_out, float* lse_out, const uint16_
    evaluated with m = max_k S_k subtracted from every score.  The paper defines only K = 2; this is the
    same expression with more terms (merging is associative, so it equals any chain of two-way merges up
    to rounding).  v_parts: [K, P, D] patterns (P = T*NH pairs), lse_parts: [K, P] binary32.
-   Terms are accumulated in the order k = 0, 1, ..., K-1.  All scores -inf: V_out = 0, S_out = -inf. */
+   Terms are accumulated in the order k = 0, 1, ..., K-1; a term whose weight is exactly zero is left out, as in
+   blend2.  All scores -inf: V_out = 0, S_out = -inf. */
 void oracle_merge_attn_states_lse_kway(uint16_t* v_out, float* lse_out, const uint16_t* v_parts,
                                        const float* lse_parts, int64_t K, int64_t P, int64_t D, int dtype)
 {
@@ -306,7 +320,7 @@ void oracle_merge_attn_states_lse_kway(uint16_t* v_out, float* lse_out, const ui
             float acc = 0.0f;
             for (int64_t k = 0; k < K; ++k) {
                 float a = expf(lse_parts[k * P + p] - m) / den;
-                acc += a * widen(v_parts[(k * P + p) * D + j], dtype);
+                if (a != 0.0f) acc += a * widen(v_parts[(k * P + p) * D + j], dtype);
             }
             v_out[p * D + j] = narrow(acc, dtype);
         }
@@ -321,10 +335,6 @@ void oracle_merge_attn_states_lse_f32(float* v_out, float* lse_out, const float*
         float a, b, s;
         oracle_merge_weights_f32(lse_a[p], lse_b[p], &a, &b, &s);
         lse_out[p] = s;
-        for (int64_t k = 0; k < D; ++k) {
-            float pa = a * v_a[p * D + k];
-            float pb = b * v_b[p * D + k];
-            v_out[p * D + k] = pa + pb;
-        }
+        for (int64_t k = 0; k < D; ++k) v_out[p * D + k] = blend2(a, v_a[p * D + k], b, v_b[p * D + k]);
     }
 }

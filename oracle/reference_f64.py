@@ -56,7 +56,8 @@ def silu_and_mul(in_bits, dtype: str) -> np.ndarray:
 def merge_attn_states_lse(va_bits, lse_a, vb_bits, lse_b, dtype: str):
     """Kernel 1.  Returns (v_out float64 [T,NH,D], lse_out float64 [T,NH]).
 
-    Both scores -inf: v_out = 0, lse_out = -inf.
+    Both scores -inf: v_out = 0, lse_out = -inf.  A side whose weight is exactly zero (an empty partition) is left
+    out of the blend whatever its values are.
     """
     va = widen(va_bits, dtype)
     vb = widen(vb_bits, dtype)
@@ -72,8 +73,10 @@ def merge_attn_states_lse(va_bits, lse_a, vb_bits, lse_b, dtype: str):
         a = np.where(empty, 0.0, ea / den)
         b = np.where(empty, 0.0, eb / den)
         s_out = np.where(empty, -np.inf, m0 + np.log(den))
-    v_out = a[..., None] * va + b[..., None] * vb
-    return v_out, s_out
+    # a term whose weight is exactly zero is left out: its values are not looked at
+    ta = a[..., None] * np.where(a[..., None] == 0.0, 0.0, va)
+    tb = b[..., None] * np.where(b[..., None] == 0.0, 0.0, vb)
+    return ta + tb, s_out
 
 
 def merge_attn_states_lse_kway(v_parts_bits, lse_parts, dtype: str):
@@ -89,4 +92,5 @@ def merge_attn_states_lse_kway(v_parts_bits, lse_parts, dtype: str):
     with np.errstate(divide="ignore", invalid="ignore"):
         a = np.where(empty, 0.0, e / den)
         s_out = np.where(empty, -np.inf, m0 + np.log(den))
-    return (a[..., None] * v).sum(axis=0), s_out
+    live = (a != 0.0)[..., None]  # zero-weight parts are left out, their values not looked at
+    return (a[..., None] * np.where(live, v, 0.0)).sum(axis=0), s_out

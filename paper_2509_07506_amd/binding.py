@@ -55,17 +55,18 @@ def library_path() -> str:
 
 
 def load_library() -> ctypes.CDLL:
-    """Loads the built library.  Builds it first only when no built library exists at all."""
+    """Loads the built library.  Builds it first when none is built, or when the built one does not come from the
+    sources as they are now (so that tests and benchmarks never check or time an outdated binary)."""
     global _lib
     if _lib is not None:
         return _lib
-    if not os.path.exists(_LIB_PATH):
-        from . import build as _build
+    from . import build as _build
 
+    if _build.is_stale():
         try:
             _build.build()
         except Exception as e:  # no silent fallback: the product path needs the HIP library
-            raise RuntimeError(f"astra HIP library is not built and building it failed: {e}") from e
+            raise RuntimeError(f"astra HIP library is missing or older than its sources and building it failed: {e}") from e
     # PyTorch ships its own HIP runtime; load it first so that this library binds to the same runtime as
     # the streams and device buffers it is handed (two HIP runtimes in one process do not share streams).
     import torch  # noqa: F401

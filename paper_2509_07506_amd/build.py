@@ -1,6 +1,7 @@
 """Builds the astra HIP library for gfx950 with hipcc (cross-compiles without a GPU)."""
 from __future__ import annotations
 
+import hashlib
 import os
 import subprocess
 
@@ -8,6 +9,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libastra_hip.so")
+STAMP = LIB + ".sha256"  # digest of the sources and flags the library was built from
 SOURCES = [os.path.join(CSRC, "astra_api.hip")]
 
 HIPCC_FLAGS = [
@@ -25,16 +27,31 @@ def sources_and_headers():
     return deps
 
 
+def source_digest() -> str:
+    """SHA-256 over the compiler flags and every source and header the library is built from (names and contents)."""
+    h = hashlib.sha256(" ".join(HIPCC_FLAGS).encode())
+    for p in sources_and_headers():
+        h.update(os.path.relpath(p, ROOT).encode())
+        with open(p, "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
+
+
 def is_stale() -> bool:
-    if not os.path.exists(LIB):
+    """True when no library is built, or the built one does not come from the sources as they are now (judged by
+    content, not by file times, so a copied or checked-out tree is not mistaken for a changed one)."""
+    if not os.path.exists(LIB) or not os.path.exists(STAMP):
         return True
-    t = os.path.getmtime(LIB)
-    return any(os.path.getmtime(p) > t for p in sources_and_headers())
+    with open(STAMP) as f:
+        return f.read().strip() != source_digest()
 
 
 def build(verbose: bool = False) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     cmd = [hipcc, *HIPCC_FLAGS, "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-o", LIB, *SOURCES]
+    digest = source_digest()
+    if os.path.exists(STAMP):
+        os.remove(STAMP)
     if verbose:
         print(" ".join(cmd), flush=True)
     r = subprocess.run(cmd, capture_output=True, text=True)
@@ -42,6 +59,8 @@ def build(verbose: bool = False) -> str:
         raise RuntimeError("hipcc failed:\n" + r.stdout + r.stderr)
     if verbose and r.stderr.strip():
         print(r.stderr)
+    with open(STAMP, "w") as f:
+        f.write(digest + "\n")
     return LIB
 
 

@@ -181,7 +181,7 @@ void launch_silu(const astra_launch_info_t& li, void* out, const void* in, int64
     if constexpr (DT != kF32) {
         if (variant == ASTRA_VARIANT_SCALAR_LOADS) {
             const uint32_t n = (uint32_t)(T * d);
-            silu_and_mul_scalar_kernel<DT><<<dim3((n + 255u) / 256u), dim3(256), 0, stream>>>(
+            silu_and_mul_scalar_kernel<DT><<<dim3((uint32_t)(((uint64_t)n + 255u) / 256u)), dim3(256), 0, stream>>>(
                 static_cast<uint16_t*>(out), static_cast<const uint16_t*>(in), n, (uint32_t)d, make_fastdiv((uint32_t)d));
             return;
         }
@@ -223,7 +223,7 @@ void launch_merge(const astra_launch_info_t& li, void* v_out, float* lse_out, co
     if constexpr (DT != kF32) {
         if (variant == ASTRA_VARIANT_SCALAR_LOADS) {
             const uint32_t n = (uint32_t)(pairs * D);
-            merge_attn_states_lse_scalar_kernel<DT><<<dim3((n + 255u) / 256u), dim3(256), 0, stream>>>(
+            merge_attn_states_lse_scalar_kernel<DT><<<dim3((uint32_t)(((uint64_t)n + 255u) / 256u)), dim3(256), 0, stream>>>(
                 static_cast<uint16_t*>(v_out), lse_out, static_cast<const uint16_t*>(v_a), lse_a,
                 static_cast<const uint16_t*>(v_b), lse_b, n, (uint32_t)D, make_fastdiv((uint32_t)D));
             return;
@@ -330,8 +330,8 @@ const char* astra_status_string(astra_status_t status)
         case ASTRA_ERR_ALIGN: return "pointer not aligned to its element size";
         case ASTRA_ERR_ALIAS: return "output overlaps an input";
         case ASTRA_ERR_LAUNCH: return "kernel launch failed";
+        case ASTRA_ERR_VARIANT: return "ablation variant not applicable to this operator or shape";
     }
-    if ((int)status == ASTRA_ERR_VARIANT) return "ablation variant not applicable to this operator or shape";
     return "unknown status";
 }
 
@@ -383,10 +383,10 @@ static astra_status_t run_fused_add_rmsnorm(void* input, void* residual, const v
     if (variant == ASTRA_VARIANT_ELEMENT_WISE) {
         li = astra_launch_info_t{T > 0 ? ASTRA_PATH_GENERIC : ASTRA_PATH_NONE, 256, 0, 0, T < kMaxGenericGrid ? T : kMaxGenericGrid, 0, 0};
     } else if (variant != ASTRA_VARIANT_TUNED) {
-        if (dtype == ASTRA_F32) return (astra_status_t)ASTRA_ERR_VARIANT;
-        if (variant != ASTRA_VARIANT_SCALAR_LOADS && variant != ASTRA_VARIANT_LDS_TREE_REDUCTION) return (astra_status_t)ASTRA_ERR_VARIANT;
-        if (T > 0 && li.path != ASTRA_PATH_VECTOR) return (astra_status_t)ASTRA_ERR_VARIANT;
-        if (variant == ASTRA_VARIANT_SCALAR_LOADS && H > 16384) return (astra_status_t)ASTRA_ERR_VARIANT;
+        if (dtype == ASTRA_F32) return ASTRA_ERR_VARIANT;
+        if (variant != ASTRA_VARIANT_SCALAR_LOADS && variant != ASTRA_VARIANT_LDS_TREE_REDUCTION) return ASTRA_ERR_VARIANT;
+        if (T > 0 && li.path != ASTRA_PATH_VECTOR) return ASTRA_ERR_VARIANT;
+        if (variant == ASTRA_VARIANT_SCALAR_LOADS && H > 16384) return ASTRA_ERR_VARIANT;
     }
     if (T == 0) return ASTRA_OK;
     for_dtype(dtype, [&](auto dt) { launch_rmsnorm<decltype(dt)::value>(li, input, residual, weight, T, H, eps, variant, stream); });
@@ -420,10 +420,10 @@ static astra_status_t run_silu_and_mul(void* out, const void* input, int64_t T, 
     if (variant == ASTRA_VARIANT_ELEMENT_WISE) {
         li = astra_launch_info_t{T > 0 ? ASTRA_PATH_GENERIC : ASTRA_PATH_NONE, 256, 0, 0, T < kMaxGenericGrid ? T : kMaxGenericGrid, 0, 0};
     } else if (variant != ASTRA_VARIANT_TUNED) {
-        if (dtype == ASTRA_F32) return (astra_status_t)ASTRA_ERR_VARIANT;
-        if (variant != ASTRA_VARIANT_SCALAR_LOADS && variant != ASTRA_VARIANT_LIBM_EXP_DIVIDE) return (astra_status_t)ASTRA_ERR_VARIANT;
-        if (T > 0 && li.path != ASTRA_PATH_VECTOR) return (astra_status_t)ASTRA_ERR_VARIANT;
-        if (variant == ASTRA_VARIANT_SCALAR_LOADS && T * d >= (int64_t(1) << 32)) return (astra_status_t)ASTRA_ERR_VARIANT;
+        if (dtype == ASTRA_F32) return ASTRA_ERR_VARIANT;
+        if (variant != ASTRA_VARIANT_SCALAR_LOADS && variant != ASTRA_VARIANT_LIBM_EXP_DIVIDE) return ASTRA_ERR_VARIANT;
+        if (T > 0 && li.path != ASTRA_PATH_VECTOR) return ASTRA_ERR_VARIANT;
+        if (variant == ASTRA_VARIANT_SCALAR_LOADS && T * d >= (int64_t(1) << 32)) return ASTRA_ERR_VARIANT;
     }
     if (T == 0) return ASTRA_OK;
     for_dtype(dtype, [&](auto dt) { launch_silu<decltype(dt)::value>(li, out, input, T, d, variant, stream); });
@@ -467,10 +467,10 @@ static astra_status_t run_merge_attn_states_lse(void* v_out, float* lse_out, con
     if (variant == ASTRA_VARIANT_ELEMENT_WISE) {
         li = astra_launch_info_t{T > 0 ? ASTRA_PATH_GENERIC : ASTRA_PATH_NONE, 256, 0, 0, pairs < kMaxGenericGrid ? pairs : kMaxGenericGrid, 0, 0};
     } else if (variant != ASTRA_VARIANT_TUNED) {
-        if (dtype == ASTRA_F32) return (astra_status_t)ASTRA_ERR_VARIANT;
-        if (variant != ASTRA_VARIANT_SCALAR_LOADS && variant != ASTRA_VARIANT_UNHOISTED_WEIGHTS) return (astra_status_t)ASTRA_ERR_VARIANT;
-        if (T > 0 && li.path != ASTRA_PATH_VECTOR) return (astra_status_t)ASTRA_ERR_VARIANT;
-        if (variant == ASTRA_VARIANT_SCALAR_LOADS && pairs * head_dim >= (int64_t(1) << 32)) return (astra_status_t)ASTRA_ERR_VARIANT;
+        if (dtype == ASTRA_F32) return ASTRA_ERR_VARIANT;
+        if (variant != ASTRA_VARIANT_SCALAR_LOADS && variant != ASTRA_VARIANT_UNHOISTED_WEIGHTS) return ASTRA_ERR_VARIANT;
+        if (T > 0 && li.path != ASTRA_PATH_VECTOR) return ASTRA_ERR_VARIANT;
+        if (variant == ASTRA_VARIANT_SCALAR_LOADS && pairs * head_dim >= (int64_t(1) << 32)) return ASTRA_ERR_VARIANT;
     }
     if (T == 0) return ASTRA_OK;
     for_dtype(dtype, [&](auto dt) {

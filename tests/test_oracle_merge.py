@@ -93,6 +93,38 @@ def test_one_sided_empty_returns_the_other_bit_exactly(oracle, dt):
     assert np.array_equal(vo, a) and np.array_equal(lo.view(np.uint32), sa.view(np.uint32))
 
 
+@pytest.mark.parametrize("dt", ["bf16", "f16"])
+def test_garbage_in_an_empty_partition_is_never_looked_at(oracle, dt):
+    """The merged result is attention over the union of the key sets; a partition with no keys (score -inf) has
+    no value vector, so whatever its buffer holds -- NaN, inf, anything -- must not reach the output, and the
+    other side comes back bit for bit (including a negative zero)."""
+    a, sa, b, sb = _rand_case(6, 3, 32, 12, dt)
+    sa = np.where(np.isneginf(sa), np.float32(0.25), sa)
+    a[0, 0, :4] = workloads.to_bits(np.array([-0.0, 0.0, -1.0, 3.0], np.float32), dt)
+    sb_empty = np.full_like(sb, -np.inf)
+    for junk in (np.nan, np.inf, -np.inf):
+        g = b.copy()
+        g[...] = workloads.to_bits(np.array([junk], np.float32), dt)[0]
+        for vo, lo in (oracle.merge_attn_states_lse(a, sa, g, sb_empty, dt), oracle.merge_attn_states_lse(g, sb_empty, a, sa, dt)):
+            assert np.array_equal(vo, a) and np.array_equal(lo.view(np.uint32), sa.view(np.uint32))
+    # the all-binary32 and the float64 forms
+    af = reference_f64.widen(a, dt).astype(np.float32)
+    gf = np.full_like(af, np.nan)
+    vo, lo = oracle.merge_attn_states_lse_f32(af, sa, gf, sb_empty)
+    assert np.array_equal(vo.view(np.uint32), af.view(np.uint32))
+    vo, lo = oracle.merge_attn_states_lse_f32(gf, sb_empty, af, sa)
+    assert np.array_equal(vo.view(np.uint32), af.view(np.uint32))
+    v64, _ = reference_f64.merge_attn_states_lse(a, sa, workloads.to_bits(gf, dt), sb_empty, dt)
+    assert np.array_equal(v64, reference_f64.widen(a, dt))
+    # both sides empty, both full of garbage: still 0 and -inf
+    vo, lo = oracle.merge_attn_states_lse(workloads.to_bits(gf, dt), sb_empty, workloads.to_bits(gf, dt), sb_empty, dt)
+    assert np.all((vo & 0x7FFF) == 0) and np.all(np.isneginf(lo))
+    # a weight that underflows to exactly zero (scores more than 104 apart) leaves its side out as well
+    far = (sa - np.float32(200.0)).astype(np.float32)
+    vo, _ = oracle.merge_attn_states_lse(a, sa, workloads.to_bits(gf, dt), far, dt)
+    assert np.array_equal(vo, a)
+
+
 def test_both_empty_gives_zero_and_minus_inf(oracle):
     dt = "bf16"
     a, _, b, _ = _rand_case(2, 2, 8, 3, dt)

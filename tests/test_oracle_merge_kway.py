@@ -100,3 +100,31 @@ def test_dominant_partition_wins_exactly(oracle):
     s[2] = 30.0
     vo, lo = oracle.merge_attn_states_lse_kway(v, s, "bf16")
     assert np.array_equal(vo, v[2]) and np.all(lo == 30.0)
+
+
+@pytest.mark.parametrize("dt", ["bf16", "f16"])
+def test_garbage_in_empty_partitions_is_never_looked_at(oracle, dt):
+    """partitions with score -inf hold no keys: whatever their value buffers contain stays out of the result"""
+    rng = np.random.default_rng(6)
+    K, T, NH, D = 5, 3, 2, 16
+    parts = [workloads.merge_inputs(T, NH, D, dt, rng, empty_p=0.0)[:2] for _ in range(K)]
+    v = np.stack([p[0] for p in parts])
+    s = np.stack([p[1] for p in parts])
+    s[1] = -np.inf
+    s[3] = -np.inf
+    clean_v, clean_l = oracle.merge_attn_states_lse_kway(v, s, dt)
+    for junk in (np.nan, np.inf, -np.inf):
+        g = v.copy()
+        g[1] = workloads.to_bits(np.array([junk], np.float32), dt)[0]
+        g[3] = workloads.to_bits(np.array([junk], np.float32), dt)[0]
+        vo, lo = oracle.merge_attn_states_lse_kway(g, s, dt)
+        assert np.array_equal(vo, clean_v) and np.array_equal(lo.view(np.uint32), clean_l.view(np.uint32))
+        v64, _ = reference_f64.merge_attn_states_lse_kway(g, s, dt)
+        assert np.all(np.isfinite(v64))
+    # a single live partition comes back bit for bit
+    s1 = np.full_like(s, -np.inf)
+    s1[2] = s[2]
+    g = np.full_like(v, workloads.to_bits(np.array([np.nan], np.float32), dt)[0])
+    g[2] = v[2]
+    vo, lo = oracle.merge_attn_states_lse_kway(g, s1, dt)
+    assert np.array_equal(vo & 0x7FFF, v[2] & 0x7FFF) and np.array_equal(lo.view(np.uint32), s[2].view(np.uint32))

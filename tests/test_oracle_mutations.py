@@ -36,6 +36,9 @@ MUTANTS = [
     ("kway_unnormalised", "float a = expf(lse_parts[k * P + p] - m) / den;", "float a = expf(lse_parts[k * P + p] - m);", "test_oracle_merge_kway.py"),
     ("kway_part_stride_wrong", "acc += a * widen(v_parts[(k * P + p) * D + j], dtype);", "acc += a * widen(v_parts[(p * K + k) * D + j], dtype);", "test_oracle_merge_kway.py"),
     ("kway_lse_drops_max", "lse_out[p] = m + logf(den);", "lse_out[p] = logf(den);", "test_oracle_merge_kway.py"),
+    ("merge_empty_side_leaks", "if (a == 0.0f) return b * vb;", "if (0) return b * vb;", "test_oracle_merge.py"),
+    ("merge_both_empty_leaks", "if (a == 0.0f && b == 0.0f) return 0.0f;", "", "test_oracle_merge.py"),
+    ("kway_empty_part_leaks", "if (a != 0.0f) acc += a * widen(", "acc += a * widen(", "test_oracle_merge_kway.py"),
     ("merge_log_of_sum_of_scores", "float wb = expf(sb - m);", "float wb = expf(sb + m);", "test_oracle_merge.py"),
     ("bf16_truncates", "return (uint16_t)(sign | shr_rne(mag, 16));", "return (uint16_t)(sign | (mag >> 16));", "test_oracle_convert.py"),
     ("f16_flushes_subnormals", "if (e < 101u) return (uint16_t)sign;", "if (e < 113u) return (uint16_t)sign;", "test_oracle_convert.py"),
