@@ -41,7 +41,7 @@ __global__ __launch_bounds__(256) void merge_attn_states_lse_scalar_kernel(uint1
     const MergeWeights w = merge_weights(lse_a[p], lse_b[p]);
     const float a = Storage<DT>::widen(v_a[i]);
     const float b = Storage<DT>::widen(v_b[i]);
-    v_out[i] = Storage<DT>::narrow(w.a * a + w.b * b);
+    v_out[i] = Storage<DT>::narrow(blend(w, a, b));
     if (i == p * D) lse_out[p] = w.lse;
 }
 
@@ -70,7 +70,7 @@ __global__ __launch_bounds__(1024) void fused_add_rmsnorm_scalar_kernel(uint16_t
             }
         }
         const float total = block_sum(acc, partials[parity], blockDim.x >> 6);
-        const float scale = fast_rsqrt(total * inv_h + eps);
+        const float scale = rsqrt_full_range(total * inv_h + eps);
 #pragma unroll
         for (int k = 0; k < EPT; ++k) {
             const uint32_t j = threadIdx.x + k * blockDim.x;

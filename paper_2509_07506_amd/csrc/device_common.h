@@ -146,6 +146,16 @@ __device__ __forceinline__ float fast_log(float x) { return __builtin_amdgcn_log
 __device__ __forceinline__ float fast_rcp(float x) { return __builtin_amdgcn_rcpf(x); }
 __device__ __forceinline__ float fast_rsqrt(float x) { return __builtin_amdgcn_rsqf(x); }
 
+// 1/sqrt(x) for every x >= 0.  The hardware op reads a subnormal argument as zero and would return inf; arguments
+// below 2^-100 are scaled by 2^64 first and the result by 2^32 (exact powers of two), so a row whose mean square is
+// that small (eps = 0 or tiny, |x + r| around 1e-19 or less) still gets a finite scale.  x = 0 gives inf.
+__device__ __forceinline__ float rsqrt_full_range(float x)
+{
+    const bool tiny = x < 0x1p-100f;
+    const float r = fast_rsqrt(tiny ? x * 0x1p+64f : x);
+    return tiny ? r * 0x1p+32f : r;
+}
+
 // ---------------------------------------------------------------------------------------------
 // kN elements at element alignment (the "ragged" kernels: row lengths that are no multiple of a vector,
 // pointers that are only element aligned).  A 16-byte global access needs no 16-byte alignment on this
@@ -341,25 +351,25 @@ __device__ __forceinline__ float block_sum(float v, float* lds, int nwaves)
     return total;
 }
 
-// Ablation only -- the reduction of the paper's Fig. 3a: every lane writes its value to LDS, then a
-// tree halves the number of active lanes per step with a barrier after each step.  `lds` holds 1024
-// floats; blockDim.x is a multiple of 64 (not necessarily a power of two: the first step folds the
-// part above the largest power of two onto the bottom).
-__device__ __forceinline__ float block_sum_lds_tree(float v, float* lds)
+// Ablation only: the workgroup sum with the register-level step taken out again, to measure what reducing in
+// registers first is worth (the paper's Fig. 3 compares a shared-memory-only reduction with a shuffle-first one).
+// Same two levels as block_sum -- per wave, then across waves -- but the per-wave level goes through LDS: every lane
+// stores its value and each 64-lane segment is halved six times with a workgroup barrier before every halving; the
+// segment sums are then added by every lane in wave order, as in block_sum.  `lds` holds blockDim.x floats
+// (blockDim.x a multiple of 64, at most 1024) and is free again on return.
+__device__ __forceinline__ float block_sum_lds_only(float v, float* lds, int nwaves)
 {
-    const uint32_t t = threadIdx.x, n = blockDim.x;
-    uint32_t p = 1;
-    while (p * 2 <= n) p *= 2;  // largest power of two <= n
+    const uint32_t t = threadIdx.x, lane = t & 63u;
     lds[t] = v;
-    __syncthreads();
-    if (t + p < n) lds[t] += lds[t + p];
-    __syncthreads();
-    for (uint32_t off = p / 2; off > 0; off >>= 1) {
-        if (t < off) lds[t] += lds[t + off];
+#pragma unroll
+    for (uint32_t width = 32; width >= 1; width >>= 1) {
         __syncthreads();
+        if (lane < width) lds[t] += lds[t + width];  // lanes >= width are only read in this step
     }
-    const float total = lds[0];
-    __syncthreads();  // lds is reused by the next row
+    __syncthreads();
+    float total = lds[0];
+    for (int w = 1; w < nwaves; ++w) total += lds[64 * w];
+    __syncthreads();  // the next row overwrites lds
     return total;
 }
 

@@ -112,8 +112,8 @@ __global__ __launch_bounds__(MAX_THREADS) void fused_add_rmsnorm_row_kernel(u32x
             }
         }
 
-        const float total = LDS_TREE ? block_sum_lds_tree(acc, tree) : block_sum(acc, partials[parity], nwaves);
-        const float scale = fast_rsqrt(total * inv_h + eps);
+        const float total = LDS_TREE ? block_sum_lds_only(acc, tree, nwaves) : block_sum(acc, partials[parity], nwaves);
+        const float scale = rsqrt_full_range(total * inv_h + eps);
         if constexpr ((PACE & kPaceStoreGap) != 0) wait_vector_memory();
 
 #pragma unroll
@@ -168,7 +168,7 @@ __global__ __launch_bounds__(256) void fused_add_rmsnorm_short_row_kernel(u32x4*
     }
     if (live) store_vec<NTS>(STRIDED ? r_out + (row * views.r_out_stride + v) : residual + ro, pack_vec<DT>(s));
     const float total = group_sum<G>(acc);
-    const float scale = fast_rsqrt(total * inv_h + eps);
+    const float scale = rsqrt_full_range(total * inv_h + eps);
     float w[N], y[N];
     unpack_vec<DT>(wv, w);
 #pragma unroll
@@ -261,7 +261,7 @@ __global__ __launch_bounds__(1024) void fused_add_rmsnorm_ragged_row_kernel(
             }
         }
         const float total = block_sum(acc, partials[parity], nwaves);
-        const float scale = fast_rsqrt(total * inv_h + eps);
+        const float scale = rsqrt_full_range(total * inv_h + eps);
 #pragma unroll
         for (int k = 0; k < VPT; ++k) {
             const uint32_t v = threadIdx.x + k * blockDim.x;
@@ -307,7 +307,7 @@ __global__ __launch_bounds__(256) void fused_add_rmsnorm_generic_kernel(typename
             acc += s * s;
         }
         const float total = block_sum(acc, partials[parity], blockDim.x >> 6);
-        const float scale = fast_rsqrt(total * inv_h + eps);
+        const float scale = rsqrt_full_range(total * inv_h + eps);
         for (int64_t j = threadIdx.x; j < H; j += blockDim.x) {
             float s = Storage<DT>::widen(x[j]) + Storage<DT>::widen(r[j]);
             r[j] = Storage<DT>::narrow(s);
@@ -338,7 +338,7 @@ __global__ __launch_bounds__(256) void fused_add_rmsnorm_strided_generic_kernel(
             acc += s * s;
         }
         const float total = block_sum(acc, partials[parity], blockDim.x >> 6);
-        const float scale = fast_rsqrt(total * inv_h + eps);
+        const float scale = rsqrt_full_range(total * inv_h + eps);
         for (int64_t j = threadIdx.x; j < H; j += blockDim.x) {
             float s = Storage<DT>::widen(xr[j]) + Storage<DT>::widen(rr[j]);
             r_out[row * sv.r_out_stride + j] = Storage<DT>::narrow(s);

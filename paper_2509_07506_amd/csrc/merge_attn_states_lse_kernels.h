@@ -35,6 +35,18 @@ __device__ __forceinline__ MergeWeights merge_weights(float sa, float sb)
     return w;
 }
 
+// One element of the blend a*va + b*vb.  A term whose weight is exactly zero is left out and its value not looked
+// at: an empty partition (score -inf) has no value vector, so NaN or inf left in its buffer must not reach the
+// output, and one empty side returns the other side's value bit for bit.  The sum is one fused multiply-add in
+// every kernel, so all paths give the same bits.  The selects cost three v_cndmask per element, far below the
+// memory time.
+__device__ __forceinline__ float blend(const MergeWeights& w, float va, float vb)
+{
+    const float pa = w.a * va, pb = w.b * vb;
+    const float both = __builtin_fmaf(w.a, va, pb);
+    return w.a == 0.0f ? (w.b == 0.0f ? 0.0f : pb) : (w.b == 0.0f ? pa : both);
+}
+
 // Fast path: head_dim % N == 0, 16-byte aligned v pointers.  Flat list of vectors, dvec = head_dim/N
 // per pair.  The pair index is a shift when dvec is a power of two (LOG2_DVEC >= 0), otherwise a
 // multiply-high division.  v_out may alias v_a or v_b exactly: all loads of a lane precede its stores.
@@ -72,7 +84,7 @@ __global__ __launch_bounds__(BLOCK) void merge_attn_states_lse_vec_kernel(u32x4*
             unpack_vec<DT>(bv[k], b);
             if constexpr (HOIST) {
 #pragma unroll
-                for (int e = 0; e < N; ++e) o[e] = w.a * a[e] + w.b * b[e];
+                for (int e = 0; e < N; ++e) o[e] = blend(w, a[e], b[e]);
             } else {
                 // ablation only (the pattern of the paper's Fig. 2a): the weights are worked out again for
                 // every element.  The empty asm makes the score opaque so the compiler cannot merge the
@@ -82,7 +94,7 @@ __global__ __launch_bounds__(BLOCK) void merge_attn_states_lse_vec_kernel(u32x4*
                     float s = sa[k];
                     asm volatile("" : "+v"(s));
                     const MergeWeights we = merge_weights(s, sb[k]);
-                    o[e] = we.a * a[e] + we.b * b[e];
+                    o[e] = blend(we, a[e], b[e]);
                 }
             }
             store_vec<NTS>(v_out + i, pack_vec<DT>(o));
@@ -127,7 +139,7 @@ __global__ __launch_bounds__(256) void merge_attn_states_lse_ragged_kernel(
     load_row_elems<DT, NTL>(v_b + ob, D, e0, count, b);
     const MergeWeights w = merge_weights(lse_a[pair], lse_b[pair]);
 #pragma unroll
-    for (int e = 0; e < N; ++e) o[e] = w.a * a[e] + w.b * b[e];  // positions outside [shift, shift + count) are not stored
+    for (int e = 0; e < N; ++e) o[e] = blend(w, a[e], b[e]);  // positions outside [shift, shift + count) are not stored
     store_row_elems<DT, NTS>(v_out + oo, e0, count, shift, o);
     if (jv == 0) lse_out[pair] = w.lse;
 }
@@ -145,7 +157,7 @@ __global__ __launch_bounds__(256) void merge_attn_states_lse_generic_kernel(type
         for (int64_t k = threadIdx.x; k < D; k += blockDim.x) {
             float a = Storage<DT>::widen(v_a[p * D + k]);
             float b = Storage<DT>::widen(v_b[p * D + k]);
-            v_out[p * D + k] = Storage<DT>::narrow(w.a * a + w.b * b);
+            v_out[p * D + k] = Storage<DT>::narrow(blend(w, a, b));
         }
         if (threadIdx.x == 0) lse_out[p] = w.lse;
     }
@@ -176,7 +188,7 @@ __global__ __launch_bounds__(256) void merge_attn_states_lse_strided_vec_kernel(
     unpack_vec<DT>(av, a);
     unpack_vec<DT>(bv, b);
 #pragma unroll
-    for (int e = 0; e < N; ++e) o[e] = w.a * a[e] + w.b * b[e];
+    for (int e = 0; e < N; ++e) o[e] = blend(w, a[e], b[e]);
     store_vec<NTS>(v_out + ((int64_t)t * vs.out_token + (int64_t)h * vs.out_head + jv), pack_vec<DT>(o));
     if (jv == 0) lse_out[pair] = w.lse;
 }
@@ -239,7 +251,7 @@ __global__ __launch_bounds__(256) void merge_attn_states_lse_kway_vec_kernel(u32
                 float v[N];
                 unpack_vec<DT>(pv[g], v);
 #pragma unroll
-                for (int e = 0; e < N; ++e) acc[e] += w * v[e];
+                for (int e = 0; e < N; ++e) acc[e] = w == 0.0f ? acc[e] : __builtin_fmaf(w, v[e], acc[e]);  // empty parts are not looked at
             }
             m = mn;
         }
@@ -303,7 +315,7 @@ __global__ __launch_bounds__(256) void merge_attn_states_lse_kway_ragged_kernel(
                 float v[N];
                 unpack_vec<DT>(pv[g], v);
 #pragma unroll
-                for (int e = 0; e < N; ++e) acc[e] += w * v[e];
+                for (int e = 0; e < N; ++e) acc[e] = w == 0.0f ? acc[e] : __builtin_fmaf(w, v[e], acc[e]);  // empty parts are not looked at
             }
             m = mn;
         }

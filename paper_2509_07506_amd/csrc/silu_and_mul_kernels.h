@@ -12,15 +12,19 @@
 
 namespace astra {
 
-__device__ __forceinline__ float silu_fast(float x)
+// SiLU(x) = x * 1/(1 + e^-x).  LIBM = false (every kernel of the library): e^-x as one hardware 2^(-x log2 e) and the
+// reciprocal as one hardware v_rcp_f32.  x << 0: 2^(+big) = inf, 1/inf = 0, x * 0 = -0, the limit value.
+// LIBM = true (ablation entry point only): the same expression with the library expf and an IEEE-rounded divide,
+// the costlier pair that the paper's Fig. 5 measures against the fast one.
+template <bool LIBM>
+__device__ __forceinline__ float silu_form(float x)
 {
-    // x * 1/(1 + 2^(-x log2 e)).  x << 0: 2^(+big) = inf, 1/inf = 0, x * 0 = -0, the limit value.
-    return x * fast_rcp(1.0f + __builtin_amdgcn_exp2f(x * -kLog2e));
+    const float e = LIBM ? expf(-x) : __builtin_amdgcn_exp2f(x * -kLog2e);
+    const float inv = LIBM ? 1.0f / (1.0f + e) : fast_rcp(1.0f + e);
+    return x * inv;
 }
 
-// The plain form of the paper's Fig. 5a: library expf and an IEEE divide.  Only the ablation entry
-// point uses it (LIBM = true below).
-__device__ __forceinline__ float silu_libm(float x) { return x / (1.0f + expf(-x)); }
+__device__ __forceinline__ float silu_fast(float x) { return silu_form<false>(x); }
 
 // Fast path: d % N == 0 and 16-byte aligned pointers.  Work is the flat list of output vectors
 // (dv = d/N per row); a block owns BLOCK*UNROLL consecutive ones.  For output vector (t, j):
@@ -74,7 +78,7 @@ __global__ __launch_bounds__(BLOCK) void silu_and_mul_vec_kernel(u32x4* __restri
             unpack_vec<DT>(xv[k], x);
             unpack_vec<DT>(gv[k], g);
 #pragma unroll
-            for (int e = 0; e < N; ++e) o[e] = (LIBM ? silu_libm(x[e]) : silu_fast(x[e])) * g[e];
+            for (int e = 0; e < N; ++e) o[e] = silu_form<LIBM>(x[e]) * g[e];
             store_vec<NTS>(out + oidx[k], pack_vec<DT>(o));
         }
     }

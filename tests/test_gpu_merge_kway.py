@@ -108,3 +108,30 @@ def test_kway_validation(A):
     assert g(p, q, p + 8192, q + 1024, 3, 0, 2, 8, A.ASTRA_F16, None) == 0
     torch.cuda.synchronize()
     assert bool((buf == 0).all()) and bool((f == 0).all())
+
+
+@pytest.mark.parametrize("dt", ["bf16", "f16", "f32"])
+@pytest.mark.parametrize("K,D", [(2, 128), (5, 128), (9, 64), (5, 100), (6, 132)])
+def test_kway_never_looks_at_an_empty_partition(A, K, D, dt):
+    """NaN / inf in the value buffers of partitions whose score is -inf stay out of the result (vector and ragged paths)"""
+    print(f"[kway empty] K={K} D={D} {dt}", flush=True)
+    T, NH = 19, 4
+    v, s = _inputs(K, T, NH, D, dt, 3, empty_p=0.0)
+    clean_v = v.copy()
+    s[1::2] = -np.inf                                                    # every second partition empty ...
+    v[1::2] = workloads.to_bits(np.array([np.nan], np.float32), dt)[0]   # ... and full of NaN
+    s[:, 0, 0] = -np.inf
+    v[:, 0, 0] = workloads.to_bits(np.array([np.inf], np.float32), dt)[0]  # one pair with nothing live at all
+    clean_v[1::2] = 0
+    clean_v[:, 0, 0] = 0
+    vo, lo = _run(A, v, s, dt)
+    w = reference_f64.widen(vo, dt)
+    assert np.all(np.isfinite(w)) and np.all(w[0, 0] == 0) and np.isneginf(lo[0, 0])
+    if dt == "f32":
+        v64, l64 = reference_f64.merge_attn_states_lse_kway(clean_v, s, dt)
+        assert_storage_close_to_real(vo, v64, dt, "v_out vs float64")
+        assert_lse_close(lo, l64, "lse_out")
+    else:
+        vo_ref, lo_ref = O.merge_attn_states_lse_kway(v, s, dt)
+        assert_storage_close(vo, vo_ref, dt, "v_out")
+        assert_lse_close(lo, lo_ref, "lse_out")

@@ -331,6 +331,36 @@ def test_rmsnorm_special_rows(A, dt):
         assert sub.sum() > 100, "expected fp16-subnormal residuals in the tiny row"
 
 
+@pytest.mark.parametrize("dt", ["bf16", "f32"])
+@pytest.mark.parametrize("H", [4096, 64, 4100, 40000])
+def test_rmsnorm_rows_whose_mean_square_is_subnormal(A, dt, H):
+    """|x + r| around 1e-20 with eps = 0: the mean square (about 1e-40) is a binary32 subnormal, which the hardware
+    reciprocal square root alone would read as zero.  The scale must stay finite and y close to the oracle's, on the
+    row, short-row, ragged and element-wise kernels.  (fp16 cannot hold such values.)"""
+    _say(f"[tiny rows] {dt} H={H}")
+    T = 5
+    rng = np.random.default_rng([13, H])
+    x = workloads.to_bits((rng.standard_normal((T, H)) * 1e-20).astype(np.float32), dt)
+    r = workloads.to_bits((rng.standard_normal((T, H)) * 1e-20).astype(np.float32), dt)
+    w = workloads.to_bits((1.0 + 0.3 * rng.standard_normal(H)).astype(np.float32), dt)
+    x[1], r[1] = x[1] * 0, r[1] * 0
+    x[1, 0] = workloads.to_bits(np.array([3e-22], np.float32), dt)[0]      # mean square far below the subnormal range
+    for eps in (0.0, 1e-42):
+        y, res = run_rmsnorm(A, x, r, w, eps, dt)
+        if dt == "f32":
+            res_ref, y_ref = O.fused_add_rmsnorm_f32(x, r, w, eps)
+        else:
+            y_ref, res_ref = O.fused_add_rmsnorm(x, r, w, eps, dt)
+        assert_bits_equal(res, res_ref, "residual")
+        yw, yr = reference_f64.widen(y, dt), reference_f64.widen(y_ref, dt)
+        rows = [0, 2, 3, 4]                                                # row 1: a total that underflows to 0 in
+        assert np.all(np.isfinite(yw[rows])), "scale must stay finite"     # binary32 gives inf * s in both forms
+        # the squares are subnormal (about 16 significant bits), so compare with the 16-bit bar for both storage types
+        np.testing.assert_allclose(yw[rows], yr[rows], rtol=1.6e-2, atol=1e-2)
+        y64, _ = reference_f64.fused_add_rmsnorm(x[rows], r[rows], w, eps, dt)
+        np.testing.assert_allclose(yw[rows], y64, rtol=1.6e-2, atol=1e-2)
+
+
 @pytest.mark.parametrize("dt", ["bf16", "f16"])
 def test_silu_special_values(A, dt):
     xs = np.array([0.0, -0.0, 1.0, -1.0, -1.2784645, 20.0, 88.0, 100.0, -20.0, -87.0, -88.0, -89.0, -100.0, -200.0, 3e4, -3e4,
@@ -373,6 +403,59 @@ def test_merge_empty_partitions_and_symmetry(A, dt):
     vo2, lo2 = run_merge(A, vb, lb, va, la, dt)
     assert_storage_close(vo2, vo, dt, "symmetry v_out")
     assert np.array_equal(lo2.view(np.uint32), lo.view(np.uint32))
+
+
+@pytest.mark.parametrize("dt", ["bf16", "f16", "f32"])
+@pytest.mark.parametrize("D,offset,variant", [(128, 0, 0), (64, 0, 0), (100, 0, 0), (129, 0, 0), (128, 1, 0), (128, 0, 5),
+                                              (128, 0, 1), (128, 0, 3)])
+def test_merge_never_looks_at_an_empty_partition(A, dt, D, offset, variant):
+    """NaN / inf left in the value buffer of a partition whose score is -inf must not reach the output: the other
+    side comes back bit for bit (a negative zero included) on every path -- vector, ragged (odd head_dim, pointer
+    offset by one element), element-wise and the ablation variants."""
+    if dt == "f32" and variant in (1, 3):
+        pytest.skip("ablation variants exist for the 16-bit types only")
+    if dt == "f32" and D == 129:
+        D = 130
+    _say(f"[merge empty] {dt} D={D} offset={offset} variant={variant}")
+    T, NH = 37, 6
+    va, la, vb, lb = workloads.merge_inputs(T, NH, D, dt, np.random.default_rng([12, D]), empty_p=0.0)
+    nan_bits = workloads.to_bits(np.array([np.nan], np.float32), dt)[0]
+    inf_bits = workloads.to_bits(np.array([np.inf], np.float32), dt)[0]
+    va[0, 0, :2] = workloads.to_bits(np.array([-0.0, 0.0], np.float32), dt)
+    lb[:, 0] = -np.inf
+    vb[:, 0] = nan_bits            # side b empty and full of NaN
+    la[:, 1] = -np.inf
+    va[:, 1] = inf_bits            # side a empty and full of +inf
+    la[:, 2] = -np.inf
+    lb[:, 2] = -np.inf
+    va[:, 2] = nan_bits
+    vb[:, 2] = inf_bits            # both empty, both garbage
+    la[:, 3] = 12.0
+    lb[:, 3] = -150.0
+    vb[:, 3] = nan_bits            # weight underflows to exactly zero
+    vad, _ = padded(va, dt, offset_elems=offset)
+    vbd, _ = padded(vb, dt, offset_elems=offset)
+    vod, whole = padded(np.zeros_like(va), dt, offset_elems=offset)
+    lad, lbd = torch.from_numpy(la).cuda(), torch.from_numpy(lb).cuda()
+    lod = torch.empty_like(lad)
+    code = {"bf16": A.ASTRA_BF16, "f16": A.ASTRA_F16, "f32": A.ASTRA_F32}[dt]
+    args = (vod.data_ptr(), lod.data_ptr(), vad.data_ptr(), lad.data_ptr(), vbd.data_ptr(), lbd.data_ptr(), T, NH, D, code)
+    st = A.astra_merge_attn_states_lse(*args, None) if variant == 0 else A.astra_ablation_merge_attn_states_lse(*args, variant, None)
+    if variant in (1, 3) and (D % 8 or offset):
+        assert st == A.ASTRA_ERR_VARIANT
+        return
+    assert st == 0
+    torch.cuda.synchronize()
+    vo, lo = to_bits(vod), lod.cpu().numpy()
+    as_bits = (lambda a: a.view(np.uint32)) if dt == "f32" else (lambda a: a)
+    assert np.array_equal(as_bits(vo[:, 0]), as_bits(va[:, 0])) and np.array_equal(lo[:, 0], la[:, 0])
+    assert np.array_equal(as_bits(vo[:, 1]), as_bits(vb[:, 1])) and np.array_equal(lo[:, 1], lb[:, 1])
+    assert np.all(reference_f64.widen(vo[:, 2], dt) == 0) and np.all(np.isneginf(lo[:, 2]))
+    assert np.array_equal(as_bits(vo[:, 3]), as_bits(va[:, 3])) and np.all(lo[:, 3] == 12.0)
+    vo_ref, lo_ref = (O.merge_attn_states_lse_f32 if dt == "f32" else lambda *a: O.merge_attn_states_lse(*a, dt))(va, la, vb, lb)
+    assert_storage_close(vo, vo_ref, dt, "merge with garbage in empty partitions")
+    assert_lse_close(lo, lo_ref, "lse")
+    assert canaries_intact(whole, va.size, offset_elems=offset)
 
 
 @pytest.mark.parametrize("dt", ["bf16", "f16"])
@@ -626,7 +709,7 @@ def test_non_finite_inputs_propagate_like_the_oracle(A, dt):
     la[0, 0] = nan
     la[1, 0] = inf
     lb[2, 0] = -inf
-    vb[2, 0, 3] = workloads.to_bits(np.array([nan]), dt)[0]       # garbage in an empty partition: 0 * NaN = NaN
+    vb[2, 0, 3] = workloads.to_bits(np.array([nan]), dt)[0]       # garbage in an empty partition: never looked at
     va[3, 0, 4] = workloads.to_bits(np.array([inf]), dt)[0]
     la[4, 0] = inf
     lb[4, 0] = inf
