@@ -31,6 +31,10 @@ typedef struct {
     int64_t grid;             /* workgroups launched (padded to a multiple of 8 * 2^log2_xcd_chunk) */
     int32_t pace;             /* fused_add_rmsnorm fast path only: ASTRA_PACE_* bits, when a wave issues its requests */
     int32_t rows_per_block;   /* fused_add_rmsnorm on rows of at most 32 vectors: rows one workgroup handles; otherwise 0 */
+    int32_t access_bytes;     /* bytes one lane moves per access on the vector path: 16, or 8 for small silu_and_mul problems;
+                                 0 on the other paths */
+    int32_t non_temporal;     /* 1: activations are moved with the non-temporal hint (streaming sizes); 0: plain cached
+                                 accesses (small silu_and_mul / merge problems, where the launch ends sooner with them) */
 } astra_launch_info_t;
 
 /* Request pacing of the fused_add_rmsnorm row kernel.  Same arithmetic and bytes for every value; the order in time of

@@ -42,12 +42,14 @@ class AstraError(RuntimeError):
 class LaunchInfo(ctypes.Structure):
     _fields_ = [("path", ctypes.c_int32), ("block", ctypes.c_int32), ("vectors_per_lane", ctypes.c_int32),
                 ("log2_xcd_chunk", ctypes.c_int32), ("grid", ctypes.c_int64), ("pace", ctypes.c_int32),
-                ("rows_per_block", ctypes.c_int32)]
+                ("rows_per_block", ctypes.c_int32), ("access_bytes", ctypes.c_int32), ("non_temporal", ctypes.c_int32)]
 
     def as_dict(self):
         return {"path": {0: "none", 1: "vector", 2: "generic", 3: "ragged"}[self.path], "block": self.block,
                 "vectors_per_lane": self.vectors_per_lane, "log2_xcd_chunk": self.log2_xcd_chunk, "grid": self.grid,
-                "pace": self.pace, **({"rows_per_block": self.rows_per_block} if self.rows_per_block else {})}
+                "pace": self.pace, **({"rows_per_block": self.rows_per_block} if self.rows_per_block else {}),
+                **({"access_bytes": self.access_bytes} if self.access_bytes not in (0, 16) else {}),
+                **({"non_temporal": 0} if self.path in (1, 3) and not self.non_temporal else {})}
 
 
 def library_path() -> str:

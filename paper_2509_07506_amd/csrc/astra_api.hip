@@ -187,9 +187,12 @@ void launch_silu(const astra_launch_info_t& li, void* out, const void* in, int64
         }
         if (variant == ASTRA_VARIANT_LIBM_EXP_DIVIDE) {
             const uint32_t dv = (uint32_t)(d / Storage<DT>::kN);
-            silu_and_mul_vec_kernel<DT, kSiluUnroll, kNTLoad, kNTStore, true><<<dim3((uint32_t)li.grid), dim3(256), 0, stream>>>(
-                static_cast<u32x4*>(out), static_cast<const u32x4*>(in), (uint32_t)(T * dv), dv, make_fastdiv(dv),
-                li.log2_xcd_chunk);
+            for_flat_block(li.block, [&](auto bc) {
+                constexpr int B = decltype(bc)::value;
+                silu_and_mul_vec_kernel<DT, kSiluUnroll, kNTLoad, kNTStore, true, B><<<dim3((uint32_t)li.grid), dim3(B), 0, stream>>>(
+                    static_cast<u32x4*>(out), static_cast<const u32x4*>(in), (uint32_t)(T * dv), dv, make_fastdiv(dv),
+                    li.log2_xcd_chunk);
+            });
             return;
         }
     }
@@ -205,14 +208,22 @@ void launch_silu(const astra_launch_info_t& li, void* out, const void* in, int64
         return;
     }
     const uint32_t dv = (uint32_t)(d / Storage<DT>::kN);
-    if (dv < kSiluLaneDivBelow)
-        silu_and_mul_vec_kernel<DT, kSiluUnroll, kNTLoad, kNTStore, false, 256, true>
-            <<<dim3((uint32_t)li.grid), dim3(256), 0, stream>>>(static_cast<u32x4*>(out), static_cast<const u32x4*>(in),
-                                                                (uint32_t)(T * dv), dv, make_fastdiv(dv), li.log2_xcd_chunk);
-    else
-        silu_and_mul_vec_kernel<DT, kSiluUnroll, kNTLoad, kNTStore><<<dim3((uint32_t)li.grid), dim3(256), 0, stream>>>(
-            static_cast<u32x4*>(out), static_cast<const u32x4*>(in), (uint32_t)(T * dv), dv, make_fastdiv(dv),
-            li.log2_xcd_chunk);
+    if (li.access_bytes == kVecBytes / 2) {  // small problem: half a vector per lane, plain accesses
+        silu_and_mul_small_kernel<DT><<<dim3((uint32_t)li.grid), dim3(256), 0, stream>>>(
+            static_cast<u32x2*>(out), static_cast<const u32x2*>(in), (uint32_t)(2 * T * dv), 2 * dv, make_fastdiv(2 * dv));
+        return;
+    }
+    for_flat_block(li.block, [&](auto bc) {
+        constexpr int B = decltype(bc)::value;
+        if (dv < kSiluLaneDivBelow)
+            silu_and_mul_vec_kernel<DT, kSiluUnroll, kNTLoad, kNTStore, false, B, true>
+                <<<dim3((uint32_t)li.grid), dim3(B), 0, stream>>>(static_cast<u32x4*>(out), static_cast<const u32x4*>(in),
+                                                                  (uint32_t)(T * dv), dv, make_fastdiv(dv), li.log2_xcd_chunk);
+        else
+            silu_and_mul_vec_kernel<DT, kSiluUnroll, kNTLoad, kNTStore, false, B><<<dim3((uint32_t)li.grid), dim3(B), 0, stream>>>(
+                static_cast<u32x4*>(out), static_cast<const u32x4*>(in), (uint32_t)(T * dv), dv, make_fastdiv(dv),
+                li.log2_xcd_chunk);
+    });
 }
 
 template <int DT>
@@ -231,11 +242,14 @@ void launch_merge(const astra_launch_info_t& li, void* v_out, float* lse_out, co
         if (variant == ASTRA_VARIANT_UNHOISTED_WEIGHTS) {
             const uint32_t dvec = (uint32_t)(D / Storage<DT>::kN);
             const int log2_dvec = (dvec & (dvec - 1)) == 0 ? __builtin_ctz(dvec) : -1;
-            merge_attn_states_lse_vec_kernel<DT, kMergeUnroll, kNTLoad, kNTStore, false>
-                <<<dim3((uint32_t)li.grid), dim3(256), 0, stream>>>(
-                    static_cast<u32x4*>(v_out), lse_out, static_cast<const u32x4*>(v_a), lse_a,
-                    static_cast<const u32x4*>(v_b), lse_b, (uint32_t)(pairs * dvec), dvec, log2_dvec, make_fastdiv(dvec),
-                    li.log2_xcd_chunk);
+            for_flat_block(li.block, [&](auto bc) {
+                constexpr int B = decltype(bc)::value;
+                merge_attn_states_lse_vec_kernel<DT, kMergeUnroll, kNTLoad, kNTStore, false, B>
+                    <<<dim3((uint32_t)li.grid), dim3(B), 0, stream>>>(
+                        static_cast<u32x4*>(v_out), lse_out, static_cast<const u32x4*>(v_a), lse_a,
+                        static_cast<const u32x4*>(v_b), lse_b, (uint32_t)(pairs * dvec), dvec, log2_dvec, make_fastdiv(dvec),
+                        li.log2_xcd_chunk);
+            });
             return;
         }
     }
@@ -254,9 +268,19 @@ void launch_merge(const astra_launch_info_t& li, void* v_out, float* lse_out, co
     const uint32_t dvec = (uint32_t)(D / Storage<DT>::kN);
     int log2_dvec = -1;
     if ((dvec & (dvec - 1)) == 0) log2_dvec = __builtin_ctz(dvec);
-    merge_attn_states_lse_vec_kernel<DT, kMergeUnroll, kNTLoad, kNTStore><<<dim3((uint32_t)li.grid), dim3(256), 0, stream>>>(
-        static_cast<u32x4*>(v_out), lse_out, static_cast<const u32x4*>(v_a), lse_a, static_cast<const u32x4*>(v_b), lse_b,
-        (uint32_t)(pairs * dvec), dvec, log2_dvec, make_fastdiv(dvec), li.log2_xcd_chunk);
+    for_flat_block(li.block, [&](auto bc) {
+        constexpr int B = decltype(bc)::value;
+        auto go = [&](auto nt) {
+            constexpr bool NT = decltype(nt)::value;
+            merge_attn_states_lse_vec_kernel<DT, kMergeUnroll, kNTLoad && NT, kNTStore && NT, true, B>
+                <<<dim3((uint32_t)li.grid), dim3(B), 0, stream>>>(static_cast<u32x4*>(v_out), lse_out,
+                                                                  static_cast<const u32x4*>(v_a), lse_a,
+                                                                  static_cast<const u32x4*>(v_b), lse_b, (uint32_t)(pairs * dvec),
+                                                                  dvec, log2_dvec, make_fastdiv(dvec), li.log2_xcd_chunk);
+        };
+        if (li.non_temporal) go(std::true_type{});
+        else go(std::false_type{});  // small problems: plain cached accesses
+    });
 }
 
 // every part of the K-way input starts 16-byte aligned when the base is and head_dim is a whole number of
@@ -381,7 +405,7 @@ static astra_status_t run_fused_add_rmsnorm(void* input, void* residual, const v
         overlaps(residual, bytes, weight, H * eb))
         return ASTRA_ERR_ALIAS;
     if (variant == ASTRA_VARIANT_ELEMENT_WISE) {
-        li = astra_launch_info_t{T > 0 ? ASTRA_PATH_GENERIC : ASTRA_PATH_NONE, 256, 0, 0, T < kMaxGenericGrid ? T : kMaxGenericGrid, 0, 0};
+        li = launch_info(T > 0 ? ASTRA_PATH_GENERIC : ASTRA_PATH_NONE, 256, 0, 0, T < kMaxGenericGrid ? T : kMaxGenericGrid, 0, 0);
     } else if (variant != ASTRA_VARIANT_TUNED) {
         if (dtype == ASTRA_F32) return ASTRA_ERR_VARIANT;
         if (variant != ASTRA_VARIANT_SCALAR_LOADS && variant != ASTRA_VARIANT_LDS_TREE_REDUCTION) return ASTRA_ERR_VARIANT;
@@ -418,7 +442,7 @@ static astra_status_t run_silu_and_mul(void* out, const void* input, int64_t T, 
     if (!aligned(out, eb) || !aligned(input, eb)) return ASTRA_ERR_ALIGN;
     if (overlaps(out, T * d * eb, input, T * d * 2 * eb)) return ASTRA_ERR_ALIAS;
     if (variant == ASTRA_VARIANT_ELEMENT_WISE) {
-        li = astra_launch_info_t{T > 0 ? ASTRA_PATH_GENERIC : ASTRA_PATH_NONE, 256, 0, 0, T < kMaxGenericGrid ? T : kMaxGenericGrid, 0, 0};
+        li = launch_info(T > 0 ? ASTRA_PATH_GENERIC : ASTRA_PATH_NONE, 256, 0, 0, T < kMaxGenericGrid ? T : kMaxGenericGrid, 0, 0);
     } else if (variant != ASTRA_VARIANT_TUNED) {
         if (dtype == ASTRA_F32) return ASTRA_ERR_VARIANT;
         if (variant != ASTRA_VARIANT_SCALAR_LOADS && variant != ASTRA_VARIANT_LIBM_EXP_DIVIDE) return ASTRA_ERR_VARIANT;
@@ -465,7 +489,7 @@ static astra_status_t run_merge_attn_states_lse(void* v_out, float* lse_out, con
         overlaps(lse_out, sbytes, v_out, vbytes))
         return ASTRA_ERR_ALIAS;
     if (variant == ASTRA_VARIANT_ELEMENT_WISE) {
-        li = astra_launch_info_t{T > 0 ? ASTRA_PATH_GENERIC : ASTRA_PATH_NONE, 256, 0, 0, pairs < kMaxGenericGrid ? pairs : kMaxGenericGrid, 0, 0};
+        li = launch_info(T > 0 ? ASTRA_PATH_GENERIC : ASTRA_PATH_NONE, 256, 0, 0, pairs < kMaxGenericGrid ? pairs : kMaxGenericGrid, 0, 0);
     } else if (variant != ASTRA_VARIANT_TUNED) {
         if (dtype == ASTRA_F32) return ASTRA_ERR_VARIANT;
         if (variant != ASTRA_VARIANT_SCALAR_LOADS && variant != ASTRA_VARIANT_UNHOISTED_WEIGHTS) return ASTRA_ERR_VARIANT;
@@ -503,7 +527,7 @@ astra_status_t astra_merge_attn_states_lse_kway(void* v_out, float* lse_out, con
     if (!v_out || !lse_out || !v_parts || !lse_parts) return ASTRA_ERR_NULL;
     astra_launch_info_t li;
     const int eb = elem_bytes((int)dtype);
-    astra_status_t st = plan_merge(T, num_heads, head_dim, eb, aligned(v_out, 16) && aligned(v_parts, 16), &li);
+    astra_status_t st = plan_merge(T, num_heads, head_dim, eb, aligned(v_out, 16) && aligned(v_parts, 16), &li, true);
     if (st != ASTRA_OK) return st;
     if (li.path == ASTRA_PATH_GENERIC) return ASTRA_ERR_SHAPE;  // more than 2^31 output vectors
     const int64_t pairs = T * num_heads;
@@ -573,7 +597,7 @@ astra_status_t astra_silu_and_mul_strided(void* out, int64_t out_stride, const v
     const int64_t ne = kVecBytes / eb;
     const bool fast = aligned(out, 16) && aligned(input, 16) && out_stride % ne == 0 && in_stride % ne == 0;
     astra_launch_info_t li;
-    astra_status_t st = plan_silu(T, d, eb, fast, &li);
+    astra_status_t st = plan_silu(T, d, eb, fast, &li, true);
     if (st != ASTRA_OK) return st;
     if (li.path == ASTRA_PATH_GENERIC) return ASTRA_ERR_SHAPE;  // more than 2^31 output vectors
     int64_t out_rows, in_rows;
@@ -620,7 +644,7 @@ astra_status_t astra_merge_attn_states_lse_strided(void* v_out, int64_t out_toke
     bool fast = true;
     for (int i = 0; i < 3; ++i) fast = fast && aligned(bases[i], 16) && ts[i] % ne == 0 && hs[i] % ne == 0;
     astra_launch_info_t li;
-    astra_status_t st = plan_merge(T, num_heads, head_dim, eb, fast, &li);
+    astra_status_t st = plan_merge(T, num_heads, head_dim, eb, fast, &li, true);
     if (st != ASTRA_OK) return st;
     if (li.path == ASTRA_PATH_GENERIC) return ASTRA_ERR_SHAPE;  // more than 2^31 output vectors
     int64_t span[3];  // bounding extent of each value view in bytes

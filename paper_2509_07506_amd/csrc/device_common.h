@@ -14,6 +14,7 @@ constexpr int kWave = 64;
 constexpr int kVecBytes = 16;
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
@@ -131,6 +132,31 @@ __device__ __forceinline__ u32x4 pack_vec(const float (&f)[Storage<DT>::kN])
         v.y = Storage<DT>::pack2(f[2], f[3]);
         v.z = Storage<DT>::pack2(f[4], f[5]);
         v.w = Storage<DT>::pack2(f[6], f[7]);
+    }
+    return v;
+}
+
+// half a vector (8 bytes: 4 16-bit or 2 binary32 elements), for the small-problem kernels
+template <int DT>
+__device__ __forceinline__ void unpack_half_vec(u32x2 v, float (&f)[Storage<DT>::kN / 2])
+{
+    if constexpr (DT == kF32) {
+        f[0] = word_as_float(v.x); f[1] = word_as_float(v.y);
+    } else {
+        f32x2 a = Storage<DT>::unpack2(v.x), b = Storage<DT>::unpack2(v.y);
+        f[0] = a.x; f[1] = a.y; f[2] = b.x; f[3] = b.y;
+    }
+}
+
+template <int DT>
+__device__ __forceinline__ u32x2 pack_half_vec(const float (&f)[Storage<DT>::kN / 2])
+{
+    u32x2 v;
+    if constexpr (DT == kF32) {
+        v.x = float_as_word(f[0]); v.y = float_as_word(f[1]);
+    } else {
+        v.x = Storage<DT>::pack2(f[0], f[1]);
+        v.y = Storage<DT>::pack2(f[2], f[3]);
     }
     return v;
 }

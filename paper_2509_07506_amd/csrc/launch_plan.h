@@ -91,6 +91,33 @@ inline void for_dtype(astra_dtype_t dt, F&& f)
 
 inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
 
+// a launch description; the vector and ragged paths move 16 bytes per lane with the non-temporal hint unless said otherwise
+inline astra_launch_info_t launch_info(int path, int block, int vpt, int lc, int64_t grid, int pace, int rows_per_block,
+                                       int access_bytes = -1, int non_temporal = -1)
+{
+    const bool wide = (path == ASTRA_PATH_VECTOR || path == ASTRA_PATH_RAGGED);
+    astra_launch_info_t li;
+    li.path = path;
+    li.block = block;
+    li.vectors_per_lane = vpt;
+    li.log2_xcd_chunk = lc;
+    li.grid = grid;
+    li.pace = pace;
+    li.rows_per_block = rows_per_block;
+    li.access_bytes = access_bytes >= 0 ? access_bytes : (wide ? kVecBytes : 0);
+    li.non_temporal = non_temporal >= 0 ? non_temporal : (wide ? 1 : 0);
+    return li;
+}
+
+// calls f with the workgroup width of a flat kernel (64, 128 or 256 lanes) as a compile-time constant
+template <class F>
+inline void for_flat_block(int block, F&& f)
+{
+    if (block == 64) f(std::integral_constant<int, 64>{});
+    else if (block == 128) f(std::integral_constant<int, 128>{});
+    else f(std::integral_constant<int, 256>{});
+}
+
 // ---- fused_add_rmsnorm plan -----------------------------------------------------------------------
 // The row lives in registers: hv = H/N vectors (N = 16 / element size) spread over `block` lanes, `vpt` per lane.
 // Measured on MI355X: the fewest vectors per lane that fit the row in one workgroup are fastest, for few rows
@@ -226,7 +253,7 @@ inline astra_status_t plan_rmsnorm(int64_t T, int64_t H, int eb, bool aligned16,
     const int64_t ne = kVecBytes / eb;  // elements per 16-byte vector
     int64_t n;
     if (T < 0 || H <= 0 || mul_overflows(T, H, &n) || n > std::numeric_limits<int64_t>::max() / 4) return ASTRA_ERR_SHAPE;
-    *info = astra_launch_info_t{ASTRA_PATH_NONE, 0, 0, 0, 0, 0, 0};
+    *info = launch_info(ASTRA_PATH_NONE, 0, 0, 0, 0, 0, 0);
     if (T == 0) return ASTRA_OK;
     RowPlan rp;
     int pace = kPaceNone;
@@ -235,68 +262,100 @@ inline astra_status_t plan_rmsnorm(int64_t T, int64_t H, int eb, bool aligned16,
         (T + short_rows_per_block - 1) / short_rows_per_block <= kMaxRowGrid) {
         const int64_t blocks = (T + short_rows_per_block - 1) / short_rows_per_block;
         const int lc = fit_chunk_log2(blocks, kFlatChunkLog2, kFlatChunkMinBlocks);  // a workgroup streams 4 KiB, like the flat kernels
-        *info = astra_launch_info_t{ASTRA_PATH_VECTOR, 256, 1, lc, pad_grid(blocks, lc), kPaceNone, (int32_t)short_rows_per_block};
+        *info = launch_info(ASTRA_PATH_VECTOR, 256, 1, lc, pad_grid(blocks, lc), kPaceNone, (int32_t)short_rows_per_block);
     } else if (aligned16 && H % ne == 0 && rmsnorm_row_policy(T, H / ne, H * eb, &rp, &pace)) {
         const int64_t rows = T < kMaxRowGrid ? T : kMaxRowGrid;
         const int lc = fit_chunk_log2(rows, kRowChunkBytesLog2 - floor_log2(H * eb), kRowChunkMinRows);
         if (T >= kMaxRowGrid) pace = kPaceNone;  // the row-loop kernel is not paced
-        *info = astra_launch_info_t{ASTRA_PATH_VECTOR, rp.block, rp.vpt, lc, T < kMaxRowGrid ? pad_grid(rows, lc) : rows, pace, 0};
+        *info = launch_info(ASTRA_PATH_VECTOR, rp.block, rp.vpt, lc, T < kMaxRowGrid ? pad_grid(rows, lc) : rows, pace, 0);
     } else if (H >= ne && rmsnorm_row_plan(H / ne, &rp)) {
         // rows that are no whole number of vectors, or pointers that are only element aligned: the row still lives in
         // registers, with 16-byte accesses at element alignment; lanes for the whole vectors (at least one), the tail
         // rides in the last lane (workgroups walk rows beyond the grid limit)
         const int64_t rows = T < kMaxRowGrid ? T : kMaxRowGrid;
         const int lc = fit_chunk_log2(rows, kRowChunkBytesLog2 - floor_log2(H * eb), kRowChunkMinRows);
-        *info = astra_launch_info_t{ASTRA_PATH_RAGGED, rp.block, rp.vpt, lc, T < kMaxRowGrid ? pad_grid(rows, lc) : rows, 0, 0};
+        *info = launch_info(ASTRA_PATH_RAGGED, rp.block, rp.vpt, lc, T < kMaxRowGrid ? pad_grid(rows, lc) : rows, 0, 0);
     } else {
-        *info = astra_launch_info_t{ASTRA_PATH_GENERIC, 256, 0, 0, T < kMaxGenericGrid ? T : kMaxGenericGrid, 0, 0};
+        *info = launch_info(ASTRA_PATH_GENERIC, 256, 0, 0, T < kMaxGenericGrid ? T : kMaxGenericGrid, 0, 0);
     }
     return ASTRA_OK;
 }
 
-inline astra_status_t plan_silu(int64_t T, int64_t d, int eb, bool aligned16, astra_launch_info_t* info)
+// Lanes per workgroup of the flat kernels (silu_and_mul, merge_attn_states_lse fast paths) for `vecs` output vectors.
+// Measured on MI355X by HIP-graph replay, cold, 16 bytes per lane throughout (narrower accesses never won):
+//   * streaming grids (4096 or more 256-lane workgroups): single-wave workgroups are 1.5-3 % faster (silu T=4096
+//     d=14336: 53.6 against 54.4 us; merge T=4096 32x128: 17.9 against 18.5; T=32768: 128.0 against 129.7) -- a wave
+//     slot is handed on as soon as its own wave has finished instead of when all four of a workgroup have;
+//   * fewer workgroups than compute units (33 to 255 of 256 lanes): 128 lanes spread the work over twice as many
+//     compute units (silu T=16 d=12288: 2.06 against 2.14 us; T=32 d=5120: 2.06 against 2.13);
+//   * everything else: 256 lanes (up to 32 workgroups: 1.79 against 1.95 us; 2048 workgroups: 5.9 against 6.1).
+// Small flat problems (fewer than this many output vectors, about 1.5 MiB moved) use plain cached accesses, and
+// silu_and_mul 8 bytes per lane: see silu_and_mul_small_kernel.  merge_attn_states_lse, same measurement: T=1 40x256
+// 1.76 us against 2.04 non-temporal, T=16 32x128 1.94 against 2.04, and from T=64 32x128 (2^15 vectors) on 2.25
+// non-temporal against 2.51 plain.
+constexpr int64_t kSmallFlatVecs = int64_t(1) << 15;
+
+inline int flat_block(int64_t vecs)
+{
+    const int64_t blocks256 = (vecs + 255) / 256;
+    if (blocks256 >= kFlatChunkMinBlocks) return 64;
+    if (blocks256 > 32 && blocks256 < kCus) return 128;
+    return 256;
+}
+
+// `wide_only`: the caller's kernel exists with 256-lane workgroups only (strided views)
+inline astra_status_t plan_silu(int64_t T, int64_t d, int eb, bool aligned16, astra_launch_info_t* info, bool wide_only = false)
 {
     const int64_t ne = kVecBytes / eb;
     int64_t two_d, n;
     if (T < 0 || d <= 0 || mul_overflows(d, 2, &two_d) || mul_overflows(T, two_d, &n) ||
         n > std::numeric_limits<int64_t>::max() / 4)
         return ASTRA_ERR_SHAPE;
-    *info = astra_launch_info_t{ASTRA_PATH_NONE, 0, 0, 0, 0, 0, 0};
+    *info = launch_info(ASTRA_PATH_NONE, 0, 0, 0, 0, 0, 0);
     if (T == 0) return ASTRA_OK;
     const int64_t dv = d / ne;
     // the input holds 2*T*dv vectors and is indexed with 32 bits
     if (aligned16 && d % ne == 0 && 2 * T * dv <= kMaxVecIndex) {  // rows under kSiluLaneDivBelow vectors: per-lane division
-        const int64_t span = 256 * kSiluUnroll;
+        if (!wide_only && T * dv < kSmallFlatVecs) {  // half a vector per lane, plain accesses
+            *info = launch_info(ASTRA_PATH_VECTOR, 256, 1, 0, (2 * T * dv + 255) / 256, 0, 0, kVecBytes / 2, 0);
+            return ASTRA_OK;
+        }
+        const int block = wide_only ? 256 : flat_block(T * dv);
+        const int64_t span = block * kSiluUnroll;
         const int64_t blocks = (T * dv + span - 1) / span;
-        const int lc = fit_chunk_log2(blocks, kFlatChunkLog2, kFlatChunkMinBlocks);
-        *info = astra_launch_info_t{ASTRA_PATH_VECTOR, 256, kSiluUnroll, lc, pad_grid(blocks, lc), 0, 0};
+        const int lc = fit_chunk_log2(blocks, kFlatChunkLog2, kFlatChunkMinBlocks * (256 / block));
+        *info = launch_info(ASTRA_PATH_VECTOR, block, kSiluUnroll, lc, pad_grid(blocks, lc), 0, 0);
     } else if (T * ((d + ne - 1) / ne) <= kMaxVecIndex) {  // no overflow: T * d is below 2^61
-        *info = astra_launch_info_t{ASTRA_PATH_RAGGED, 256, 1, 0, (T * ((d + ne - 1) / ne) + 255) / 256, 0, 0};
+        *info = launch_info(ASTRA_PATH_RAGGED, 256, 1, 0, (T * ((d + ne - 1) / ne) + 255) / 256, 0, 0);
     } else {
-        *info = astra_launch_info_t{ASTRA_PATH_GENERIC, 256, 0, 0, T < kMaxGenericGrid ? T : kMaxGenericGrid, 0, 0};
+        *info = launch_info(ASTRA_PATH_GENERIC, 256, 0, 0, T < kMaxGenericGrid ? T : kMaxGenericGrid, 0, 0);
     }
     return ASTRA_OK;
 }
 
-inline astra_status_t plan_merge(int64_t T, int64_t NH, int64_t D, int eb, bool aligned16, astra_launch_info_t* info)
+// `wide_only`: the caller's kernel exists with 256-lane workgroups only (strided views, K-way merge)
+inline astra_status_t plan_merge(int64_t T, int64_t NH, int64_t D, int eb, bool aligned16, astra_launch_info_t* info,
+                                 bool wide_only = false)
 {
     const int64_t ne = kVecBytes / eb;
     int64_t pairs, n;
     if (T < 0 || NH <= 0 || D <= 0 || mul_overflows(T, NH, &pairs) || mul_overflows(pairs, D, &n) ||
         n > std::numeric_limits<int64_t>::max() / 4)
         return ASTRA_ERR_SHAPE;
-    *info = astra_launch_info_t{ASTRA_PATH_NONE, 0, 0, 0, 0, 0, 0};
+    *info = launch_info(ASTRA_PATH_NONE, 0, 0, 0, 0, 0, 0);
     if (T == 0) return ASTRA_OK;
     const int64_t dvec = D / ne;
     if (aligned16 && D % ne == 0 && pairs * dvec <= kMaxVecIndex) {
-        const int64_t span = 256 * kMergeUnroll;
+        const int block = wide_only ? 256 : flat_block(pairs * dvec);
+        const int64_t span = block * kMergeUnroll;
         const int64_t blocks = (pairs * dvec + span - 1) / span;
-        const int lc = fit_chunk_log2(blocks, kFlatChunkLog2, kFlatChunkMinBlocks);
-        *info = astra_launch_info_t{ASTRA_PATH_VECTOR, 256, kMergeUnroll, lc, pad_grid(blocks, lc), 0, 0};
+        const int lc = fit_chunk_log2(blocks, kFlatChunkLog2, kFlatChunkMinBlocks * (256 / block));
+        *info = launch_info(ASTRA_PATH_VECTOR, block, kMergeUnroll, lc, pad_grid(blocks, lc), 0, 0, kVecBytes,
+                            !wide_only && pairs * dvec < kSmallFlatVecs ? 0 : 1);
     } else if (pairs * ((D + ne - 1) / ne) <= kMaxVecIndex) {
-        *info = astra_launch_info_t{ASTRA_PATH_RAGGED, 256, 1, 0, (pairs * ((D + ne - 1) / ne) + 255) / 256, 0, 0};
+        *info = launch_info(ASTRA_PATH_RAGGED, 256, 1, 0, (pairs * ((D + ne - 1) / ne) + 255) / 256, 0, 0);
     } else {
-        *info = astra_launch_info_t{ASTRA_PATH_GENERIC, 256, 0, 0, pairs < kMaxGenericGrid ? pairs : kMaxGenericGrid, 0, 0};
+        *info = launch_info(ASTRA_PATH_GENERIC, 256, 0, 0, pairs < kMaxGenericGrid ? pairs : kMaxGenericGrid, 0, 0);
     }
     return ASTRA_OK;
 }

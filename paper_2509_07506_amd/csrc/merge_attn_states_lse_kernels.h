@@ -47,6 +47,27 @@ __device__ __forceinline__ float blend(const MergeWeights& w, float va, float vb
     return w.a == 0.0f ? (w.b == 0.0f ? 0.0f : pb) : (w.b == 0.0f ? pa : both);
 }
 
+// The same for one 16-byte vector of each side, with fewer instructions: the weighted sum is formed for all N
+// elements (one multiply and one fused multiply-add each), then the packed result is replaced as a whole when a
+// weight is zero -- by the other side's vector unchanged (its weight is then exactly 1: e^0 / (1 + 0)), or by zero
+// when both weights are zero.  Equal to blend() element by element for every finite live value.
+template <int DT>
+__device__ __forceinline__ u32x4 blend_vec(const MergeWeights& w, u32x4 av, u32x4 bv)
+{
+    constexpr int N = Storage<DT>::kN;
+    float a[N], b[N], o[N];
+    unpack_vec<DT>(av, a);
+    unpack_vec<DT>(bv, b);
+#pragma unroll
+    for (int e = 0; e < N; ++e) o[e] = __builtin_fmaf(w.a, a[e], w.b * b[e]);
+    u32x4 r = pack_vec<DT>(o);
+    const bool a0 = (w.a == 0.0f), b0 = (w.b == 0.0f);
+    const u32x4 other = a0 ? bv : av;
+    r = (a0 != b0) ? other : r;
+    r = (a0 && b0) ? u32x4{0u, 0u, 0u, 0u} : r;
+    return r;
+}
+
 // Fast path: head_dim % N == 0, 16-byte aligned v pointers.  Flat list of vectors, dvec = head_dim/N
 // per pair.  The pair index is a shift when dvec is a power of two (LOG2_DVEC >= 0), otherwise a
 // multiply-high division.  v_out may alias v_a or v_b exactly: all loads of a lane precede its stores.
@@ -79,13 +100,12 @@ __global__ __launch_bounds__(BLOCK) void merge_attn_states_lse_vec_kernel(u32x4*
         const uint32_t i = first + uint32_t(BLOCK) * k;
         if (i < total_vecs) {
             const MergeWeights w = merge_weights(sa[k], sb[k]);
-            float a[N], b[N], o[N];
-            unpack_vec<DT>(av[k], a);
-            unpack_vec<DT>(bv[k], b);
             if constexpr (HOIST) {
-#pragma unroll
-                for (int e = 0; e < N; ++e) o[e] = blend(w, a[e], b[e]);
+                store_vec<NTS>(v_out + i, blend_vec<DT>(w, av[k], bv[k]));
             } else {
+                float a[N], b[N], o[N];
+                unpack_vec<DT>(av[k], a);
+                unpack_vec<DT>(bv[k], b);
                 // ablation only (the pattern of the paper's Fig. 2a): the weights are worked out again for
                 // every element.  The empty asm makes the score opaque so the compiler cannot merge the
                 // N evaluations back into one.
@@ -96,8 +116,8 @@ __global__ __launch_bounds__(BLOCK) void merge_attn_states_lse_vec_kernel(u32x4*
                     const MergeWeights we = merge_weights(s, sb[k]);
                     o[e] = blend(we, a[e], b[e]);
                 }
+                store_vec<NTS>(v_out + i, pack_vec<DT>(o));
             }
-            store_vec<NTS>(v_out + i, pack_vec<DT>(o));
             if (i == pair[k] * dvec) lse_out[pair[k]] = w.lse;  // first vector of the pair
         }
     }
@@ -184,12 +204,7 @@ __global__ __launch_bounds__(256) void merge_attn_states_lse_strided_vec_kernel(
     const u32x4 av = load_vec<NTL>(v_a + ((int64_t)t * vs.a_token + (int64_t)h * vs.a_head + jv));
     const u32x4 bv = load_vec<NTL>(v_b + ((int64_t)t * vs.b_token + (int64_t)h * vs.b_head + jv));
     const MergeWeights w = merge_weights(lse_a[pair], lse_b[pair]);
-    float a[N], b[N], o[N];
-    unpack_vec<DT>(av, a);
-    unpack_vec<DT>(bv, b);
-#pragma unroll
-    for (int e = 0; e < N; ++e) o[e] = blend(w, a[e], b[e]);
-    store_vec<NTS>(v_out + ((int64_t)t * vs.out_token + (int64_t)h * vs.out_head + jv), pack_vec<DT>(o));
+    store_vec<NTS>(v_out + ((int64_t)t * vs.out_token + (int64_t)h * vs.out_head + jv), blend_vec<DT>(w, av, bv));
     if (jv == 0) lse_out[pair] = w.lse;
 }
 
@@ -249,9 +264,10 @@ __global__ __launch_bounds__(256) void merge_attn_states_lse_kway_vec_kernel(u32
                 const float w = fast_exp(s[g] - mn);
                 den += w;
                 float v[N];
-                unpack_vec<DT>(pv[g], v);
+                // a part with weight zero (an empty partition) is not looked at: its vector is read as zeros
+                unpack_vec<DT>(w == 0.0f ? u32x4{0u, 0u, 0u, 0u} : pv[g], v);
 #pragma unroll
-                for (int e = 0; e < N; ++e) acc[e] = w == 0.0f ? acc[e] : __builtin_fmaf(w, v[e], acc[e]);  // empty parts are not looked at
+                for (int e = 0; e < N; ++e) acc[e] = __builtin_fmaf(w, v[e], acc[e]);
             }
             m = mn;
         }
@@ -313,9 +329,10 @@ __global__ __launch_bounds__(256) void merge_attn_states_lse_kway_ragged_kernel(
                 const float w = fast_exp(s[g] - mn);
                 den += w;
                 float v[N];
-                unpack_vec<DT>(pv[g], v);
+                // a part with weight zero (an empty partition) is not looked at: its vector is read as zeros
+                unpack_vec<DT>(w == 0.0f ? u32x4{0u, 0u, 0u, 0u} : pv[g], v);
 #pragma unroll
-                for (int e = 0; e < N; ++e) acc[e] = w == 0.0f ? acc[e] : __builtin_fmaf(w, v[e], acc[e]);  // empty parts are not looked at
+                for (int e = 0; e < N; ++e) acc[e] = __builtin_fmaf(w, v[e], acc[e]);
             }
             m = mn;
         }

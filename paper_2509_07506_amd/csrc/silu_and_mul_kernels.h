@@ -84,6 +84,31 @@ __global__ __launch_bounds__(BLOCK) void silu_and_mul_vec_kernel(u32x4* __restri
     }
 }
 
+// Small problems (fewer than 2^15 output vectors, about 1.5 MiB moved: decode-sized launches, bound by launch latency
+// and one memory round trip).  Two differences from the streaming kernel, both measured on MI355X by HIP-graph replay
+// on the paper's Table 4 shapes, cold: plain (cached) accesses instead of non-temporal ones -- the kernel ends as soon
+// as its stores are in the L2, 0.10-0.17 us sooner -- and 8 bytes per lane, which spreads the work over twice as many
+// lanes and compute units (T=32 d=5120: 1.97 us against 2.08 with 16 bytes per lane, 2.14 non-temporal; T=16
+// d=12288: 1.98 / 2.09 / 2.15).  From 2^15 vectors on non-temporal wins again (T=64 d=8192: 2.29 against 2.47).
+// Work is the flat list of half vectors, dh = 2 * d / N per row; every lane divides for itself.
+template <int DT>
+__global__ __launch_bounds__(256) void silu_and_mul_small_kernel(u32x2* __restrict__ out, const u32x2* __restrict__ in,
+                                                                 uint32_t total_halves, uint32_t dh, FastDiv by_dh)
+{
+    constexpr int M = Storage<DT>::kN / 2;
+    const uint32_t o = blockIdx.x * 256u + threadIdx.x;
+    if (o >= total_halves) return;
+    const uint32_t t = by_dh.div(o), j = o - t * dh;
+    const u32x2* px = in + (t * 2u * dh + j);  // below 2^17 half vectors in all
+    const u32x2 xv = px[0], gv = px[dh];
+    float x[M], g[M], r[M];
+    unpack_half_vec<DT>(xv, x);
+    unpack_half_vec<DT>(gv, g);
+#pragma unroll
+    for (int e = 0; e < M; ++e) r[e] = silu_fast(x[e]) * g[e];
+    out[o] = pack_half_vec<DT>(r);
+}
+
 // Ragged path: any d, pointers and row strides only element aligned (dense tensors: out_stride = d, in_stride = 2d).
 // A row is dv = ceil(d/N) vectors, the last one possibly partial; one lane per vector, row and column from a
 // per-lane fast division, 64-bit element offsets.  Full vectors are 16-byte accesses at element alignment; the

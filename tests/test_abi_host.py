@@ -238,11 +238,11 @@ def test_binary32_plans(A):
     assert A.astra_plan_fused_add_rmsnorm(4, 4100, True, dtype=F32)[1].as_dict()["path"] == "vector"    # H % 4 == 0
     assert A.astra_plan_fused_add_rmsnorm(4, 32768, True, dtype=F32)[1].as_dict()["path"] == "generic"  # > 4096 vectors
     s = A.astra_plan_silu_and_mul(4096, 14336, True, dtype=F32)[1].as_dict()
-    assert s["path"] == "vector" and s["grid"] * 256 >= 4096 * 14336 // 4
+    assert s["path"] == "vector" and s["block"] == 64 and s["grid"] * s["block"] >= 4096 * 14336 // 4
     assert A.astra_plan_silu_and_mul(3, 1410, True, dtype=F32)[1].as_dict()["path"] == "ragged"
     assert A.astra_plan_silu_and_mul(3, 1412, True, dtype=F32)[1].as_dict()["path"] == "vector"
     m = A.astra_plan_merge_attn_states_lse(4096, 32, 128, True, dtype=F32)[1].as_dict()
-    assert m["path"] == "vector" and m["grid"] * 256 == 4096 * 32 * 32
+    assert m["path"] == "vector" and m["block"] == 64 and m["grid"] * m["block"] == 4096 * 32 * 32
     assert A.astra_plan_merge_attn_states_lse(3, 5, 6, True, dtype=F32)[1].as_dict()["path"] == "ragged"
     assert A.astra_plan_merge_attn_states_lse(3, 5, 4, True, dtype=F32)[1].as_dict()["path"] == "vector"
     assert A.astra_plan_merge_attn_states_lse(3, 5, 4, True, dtype=7)[0] == 3
@@ -262,14 +262,30 @@ def test_silu_and_merge_plans(A):
     assert A.astra_plan_silu_and_mul(1 << 20, (1 << 14) + 1, True)[1].as_dict()["path"] == "generic"
     assert A.astra_plan_silu_and_mul(3, 128, True)[1].as_dict()["path"] == "vector"       # short rows: per-lane division
     assert A.astra_plan_silu_and_mul(1000, 8, True)[1].as_dict() == {"path": "vector", "block": 256, "vectors_per_lane": 1,
-                                                                     "log2_xcd_chunk": 0, "grid": 4, "pace": 0}
+                                                                     "log2_xcd_chunk": 0, "grid": 8, "pace": 0,
+                                                                     "access_bytes": 8, "non_temporal": 0}   # small: half vectors
     # the input's 2^32 vectors are beyond the vector kernel's 32-bit index; the ragged kernel indexes the 2^31 output vectors
     assert A.astra_plan_silu_and_mul(1 << 20, 1 << 14, True)[1].as_dict()["path"] == "ragged"
     small = A.astra_plan_silu_and_mul(3, 1408, True)[1].as_dict()
-    assert small["log2_xcd_chunk"] == 0 and small["grid"] == 3                           # no padding for small grids
+    assert small["log2_xcd_chunk"] == 0 and small["grid"] == 5                           # 3 * 352 half vectors, no padding for small grids
     st, i = A.astra_plan_merge_attn_states_lse(4096, 32, 128, True)
     p = i.as_dict()
     assert st == 0 and p["path"] == "vector" and p["grid"] * p["block"] * p["vectors_per_lane"] == 4096 * 32 * 16
+    # workgroup width of the flat kernels: one wave on streaming grids, 128 lanes when 256-lane workgroups would be
+    # fewer than the compute units (but more than 32), 256 lanes otherwise; the grid always covers the work
+    for T, d, block in [(64, 8192, 256), (100, 4096, 128), (128, 11008, 256), (2048, 11008, 64)]:
+        q = A.astra_plan_silu_and_mul(T, d, True)[1].as_dict()
+        assert q["block"] == block and "access_bytes" not in q and "non_temporal" not in q, (T, d, q)
+        assert T * d // 8 <= q["grid"] * block < T * d // 8 + max(block, (8 << q["log2_xcd_chunk"]) * block), (T, d, q)
+    # small problems (under 2^15 output vectors): plain accesses; silu_and_mul with half a vector per lane
+    for T, d in [(1, 8), (16, 4096), (32, 5120), (16, 12288), (63, 4160)]:
+        q = A.astra_plan_silu_and_mul(T, d, True)[1].as_dict()
+        assert q["access_bytes"] == 8 and q["non_temporal"] == 0 and q["block"] == 256 and q["log2_xcd_chunk"] == 0, (T, d, q)
+        assert T * d // 4 <= q["grid"] * 256 < T * d // 4 + 256
+    assert "access_bytes" not in A.astra_plan_silu_and_mul(64, 4096, True)[1].as_dict()        # exactly 2^15 vectors: streaming form
+    for T, block, nt in [(1, 256, 0), (16, 256, 0), (63, 128, 0), (64, 128, 1), (200, 256, 1), (1024, 256, 1), (2048, 64, 1), (32768, 64, 1)]:
+        q = A.astra_plan_merge_attn_states_lse(T, 32, 128, True)[1].as_dict()
+        assert q["block"] == block and q.get("non_temporal", 1) == nt and "access_bytes" not in q, (T, q)
     assert A.astra_plan_merge_attn_states_lse(3, 5, 4, True)[1].as_dict()["path"] == "ragged"
     assert A.astra_plan_merge_attn_states_lse(3, 5, 72, False)[1].as_dict()["path"] == "ragged"
     assert A.astra_plan_merge_attn_states_lse(1 << 24, 64, 129, True)[1].as_dict()["path"] == "generic"   # 2^30 * 17 vectors
