@@ -22,6 +22,8 @@ taken inside the timed region on the launch stream; `kernels` carries the same f
     python bench.py --prefill        # prefill-chunk shapes (T 512..4096, LLaMA dimensions) from a HIP graph, cold
     python bench.py --vs-eager       # the step's three workloads written with plain PyTorch tensor ops, for context
     python bench.py --ragged         # odd row lengths: ragged kernels vs vector and element-wise kernels
+    python bench.py --fit            # t = a + bytes/BW over a T sweep: fixed cost per launch and streaming rate, kernels and probes
+    python bench.py --pacing         # fused_add_rmsnorm request pacing A/B over buffer placements (the launch policy's table)
 """
 from __future__ import annotations
 
@@ -124,6 +126,92 @@ class Launcher:
             raise RuntimeError(f"{self.case.name}: astra status {st}")
 
 
+def cold_sets(working_set_bytes: int, cap: int = 4096) -> int:
+    """Buffer sets to rotate over so that no launch finds its operands in the 256 MB last-level cache: at least
+    1 GiB per rotation, at least two sets; one set when a single set already exceeds 512 MiB."""
+    if working_set_bytes > (512 << 20):
+        return 1
+    return min(cap, max(2, -(-(1 << 30) // max(working_set_bytes, 1)) + 1))
+
+
+PROBE_OF = {"rmsnorm": ("update2", 4, 4), "silu": ("read2_write1", 3, 3), "merge": ("read2_write1", 3, 3)}  # mode, code, streams
+
+
+class Probe:
+    """astra_stream_probe with the traffic mix and the bytes per stream of a workload's operator (the small extra
+    streams -- the rmsnorm weight, the merge scores -- are left out: the probe is priced on its own bytes)."""
+
+    def __init__(self, astra, case, nsets: int):
+        import torch
+
+        s = case.shape
+        eb = 4 if case.dtype == "f32" else 2
+        per_stream = {"rmsnorm": lambda: s["T"] * s["H"], "silu": lambda: s["T"] * s["d"],
+                      "merge": lambda: s["T"] * s["NH"] * s["D"]}[case.kernel]() * eb
+        self.nbytes = -(-per_stream // 16) * 16
+        self.mode_name, self.mode, self.streams = PROBE_OF[case.kernel]
+        self.bytes = self.nbytes * self.streams
+        self.nsets = nsets
+        self.stride = -(-self.nbytes // 256) * 256
+        self.bufs = [torch.zeros(nsets * self.stride, dtype=torch.uint8, device="cuda") for _ in range(3)]
+        self.astra = astra
+
+    def launch(self, stream_handle, k: int = 0):
+        o = (k % self.nsets) * self.stride
+        a, b, c = (t.data_ptr() + o for t in self.bufs)
+        st = self.astra.astra_stream_probe(a, b, c, self.nbytes, self.mode, stream_handle)
+        if st != 0:
+            raise RuntimeError(f"astra_stream_probe: status {st}")
+
+
+def batch_us(launch, stream, sh, reps: int, warm: int = 5) -> float:
+    """Microseconds per launch of `reps` launches enqueued back to back between ONE HIP-event pair (no per-launch
+    events: dispatch + kernel)."""
+    import torch
+
+    for k in range(warm):
+        launch(sh, k)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record(stream)
+    for k in range(reps):
+        launch(sh, warm + k)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e3 / reps
+
+
+def graph_us(launch, per_graph: int, reps: int, warm_sets: int) -> float:
+    """Microseconds per launch of `per_graph` launches captured into one HIP graph and replayed `reps` times: no
+    host call cost in the figure."""
+    import torch
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        for k in range(warm_sets):
+            launch(side.cuda_stream, k)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        cs = torch.cuda.current_stream().cuda_stream
+        for k in range(per_graph):
+            launch(cs, k)
+    for _ in range(2):
+        g.replay()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        g.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    us = e0.elapsed_time(e1) * 1e3 / (reps * per_graph)
+    del g
+    return us
+
+
 def _median(v):
     v = sorted(v)
     n = len(v)
@@ -136,6 +224,17 @@ def _load_traffic():
         with open(p) as f:
             return json.load(f)
     return {}
+
+
+def traffic_for(traffic: dict, case_name: str, plan: dict):
+    """The committed counter figures of a workload, or None when they were taken on another launch geometry than
+    the library plans now (a kernel or policy change since the counters were collected makes them stale)."""
+    t = traffic.get(case_name)
+    if not t:
+        return None, "no counter figures committed for this workload"
+    if t.get("launch") != plan:
+        return None, f"stale: counters were collected on launch {t.get('launch')}, the library now plans {plan}"
+    return t, None
 
 
 def _cpu_model():
@@ -205,6 +304,36 @@ def cpu_baseline(cases, datas):
             "host_cores_visible": cores, "cpu_model": _cpu_model()}
 
 
+def cpu_case_baseline(case, data):
+    """The oracle on one workload, on this host's cores (at most 16 threads, OpenMP over rows): one warm-up pass, then
+    one timed pass for workloads of 100 MB or more and the best of five below.  A baseline, not a target."""
+    import oracle
+
+    cores = len(os.sched_getaffinity(0))
+    used = oracle.set_threads(min(cores, 16))
+
+    def one():
+        t0 = time.perf_counter()
+        if case.kernel == "rmsnorm":
+            if case.dtype == "f32":
+                oracle.fused_add_rmsnorm_f32(data[0], data[1], data[2], case.eps)
+            else:
+                oracle.fused_add_rmsnorm(data[0], data[1], data[2], case.eps, case.dtype)
+        elif case.kernel == "silu":
+            (oracle.silu_and_mul_f32 if case.dtype == "f32" else lambda a: oracle.silu_and_mul(a, case.dtype))(data[0])
+        elif case.dtype == "f32":
+            oracle.merge_attn_states_lse_f32(*data)
+        else:
+            oracle.merge_attn_states_lse(*data, case.dtype)
+        return time.perf_counter() - t0
+
+    one()
+    b = case.algorithmic_bytes()
+    t = one() if b >= 100e6 else min(one() for _ in range(5))
+    return {"us": round(t * 1e6, 1), "GBs": round(b / t / 1e9, 3), "tokens_per_s": round(case.tokens() / t, 1), "cores": used,
+            "kind": "oracle", "passes": 1 if b >= 100e6 else 5}
+
+
 def run_step_bench(args):
     import torch
 
@@ -268,25 +397,22 @@ def run_step_bench(args):
         extra()
     torch.cuda.synchronize()
 
-    # Second view, outside the timed steps: each kernel launched 50 times back to back between ONE event pair,
-    # rotating over 3 buffer sets (cold).  An event pair around every single launch costs about 3 us of event and
-    # dispatch gap, which matters for the 17-54 us kernels; this figure has no per-launch events.
-    batch_us = {}
+    # The figure each kernel is held to, outside the timed steps: 50 launches back to back between ONE event pair
+    # (dispatch + kernel, no per-launch events), rotating over enough buffer sets that every launch is cold.  An event
+    # pair around every single launch costs about 3 us of event and dispatch gap, which matters for the 17-54 us
+    # kernels; that figure is kept as the labelled extra `event_pair`.  Beside it, the same-traffic probe: the bytes
+    # of the operator moved by a kernel that does nothing else, same geometry, same protocol, same process.
+    batch, probe = {}, {}
     if not args.with_copy:
         for c, d in zip(cases, datas):
-            nsets = 1 if c.algorithmic_bytes() > (512 << 20) else 3
+            nsets = cold_sets(c.algorithmic_bytes())
             Lb = Launcher(astra, c, d, nsets)
-            for k in range(5):
-                Lb.launch(sh, k)
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            torch.cuda.synchronize()
-            e0.record(stream)
-            for k in range(50):
-                Lb.launch(sh, k)
-            e1.record(stream)
-            torch.cuda.synchronize()
-            batch_us[c.kernel] = e0.elapsed_time(e1) * 1e3 / 50
+            batch[c.kernel] = batch_us(Lb.launch, stream, sh, 50)
             del Lb
+            torch.cuda.empty_cache()
+            P = Probe(astra, c, nsets)
+            probe[c.kernel] = (P, batch_us(P.launch, stream, sh, 50))
+            P.bufs = None
             torch.cuda.empty_cache()
 
     traffic = _load_traffic()
@@ -298,20 +424,30 @@ def run_step_bench(args):
             d_ms = [ev[k][i].elapsed_time(ev[k][i + 1]) for k in range(K)]
         avg = sum(d_ms) / K
         b = c.algorithmic_bytes()
-        per_kernel[c.kernel] = {
-            "workload": c.name, "kernel": KERNEL_NAMES[c.kernel], "launch": L.plan, "algorithmic_bytes": b,
-            "events": "timed region" if i == dom_i else "separate pass of the same step, an event pair around every launch",
+        us = batch.get(c.kernel)
+        t, why = traffic_for(traffic, c.name, L.plan)
+        r = {"workload": c.name, "kernel": KERNEL_NAMES[c.kernel], "launch": L.plan, "algorithmic_bytes": b}
+        if us is not None:
+            P, pus = probe[c.kernel]
+            r.update({
+                "us": round(us, 3), "achieved_GBs": round(b / us / 1e3, 1), "frac_of_peak": round(b / us / 1e3 / HBM_PEAK_GBS, 4),
+                "tokens_per_s": round(c.tokens() / (us * 1e-6), 1),
+                "how": "50 launches back to back between one HIP-event pair, cold (rotating buffer sets): dispatch + kernel",
+                "same_traffic_probe": {"mode": P.mode_name, "bytes": P.bytes, "us": round(pus, 3),
+                                       "GBs": round(P.bytes / pus / 1e3, 1),
+                                       "frac_of_peak": round(P.bytes / pus / 1e3 / HBM_PEAK_GBS, 4)},
+                "rate_vs_probe": round((b / us) / (P.bytes / pus), 4)})
+        r["event_pair"] = {
+            "note": "timed region" if i == dom_i else "separate pass of the same step; an event pair around one launch spans "
+                    "about 3 us of event and dispatch gap",
             "avg_us": round(avg * 1e3, 3), "median_us": round(_median(d_ms) * 1e3, 3), "min_us": round(min(d_ms) * 1e3, 3),
-            "achieved_GBs": round(b / (avg * 1e-3) / 1e9, 1), "frac_of_peak": round(b / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-            "tokens_per_s": round(c.tokens() / (avg * 1e-3), 1),
-            "back_to_back_us": None if c.kernel not in batch_us else round(batch_us[c.kernel], 3),
-            "back_to_back_GBs": None if c.kernel not in batch_us else round(b / batch_us[c.kernel] / 1e3, 1),
-            "back_to_back_frac_of_peak": None if c.kernel not in batch_us else round(b / batch_us[c.kernel] / 1e3 / HBM_PEAK_GBS, 4),
-            "traffic": (traffic.get(c.name) or {}).get("total_bytes"),
-            "traffic_detail": traffic.get(c.name),
-        }
+            "GBs": round(b / (avg * 1e-3) / 1e9, 1), "frac_of_peak": round(b / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+        r["traffic"] = t["total_bytes"] if t else None
+        r["traffic_detail"] = t if t else {"unavailable": why}
+        per_kernel[c.kernel] = r
     total_bytes = sum(c.algorithmic_bytes() for c in cases)
-    dom = max(per_kernel.values(), key=lambda r: r["avg_us"])
+    dom = per_kernel[cases[dom_i].kernel]
+    dom_e = dom["event_pair"]
     out = {
         "metric": METRIC, "value": round(total_bytes / wall * K / 1e9, 1), "unit": "GB/s", "n_gpus": 1, "steps": K,
         "warmup": args.warmup, "ms_per_step": round(wall / K * 1e3, 4), "higher_is_better": True, "scaling": "weak",
@@ -319,9 +455,10 @@ def run_step_bench(args):
         "config": {"workload": "+".join(STEP_CASES), "storage_dtype": "bf16", "bytes_per_step": total_bytes,
                    "cache": "cold (a step streams ~2.6 GB through a 256 MB last-level cache)"},
         "roofline": {"bound": "hbm", "kernel": dom["kernel"], "workload": dom["workload"],
-                     "achieved": dom["achieved_GBs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(dom["achieved_GBs"] / HBM_PEAK_GBS, 4), "traffic": dom["traffic"],
-                     "avg_launch_us": dom["avg_us"]},
+                     "achieved": dom_e["GBs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(dom_e["GBs"] / HBM_PEAK_GBS, 4), "traffic": dom["traffic"],
+                     "avg_launch_us": dom_e["avg_us"],
+                     "how": "algorithmic bytes / average of the HIP-event durations of this kernel inside the timed region"},
         "kernels": per_kernel,
         "device": _device_info(),
     }
@@ -363,8 +500,9 @@ def run_sweep(args):
         c = workloads.case(n)
         data = c.generate()
         ws = c.algorithmic_bytes()
-        nsets = 1 if ws > (512 << 20) else min(4096, max(2, -(-(1 << 30) // max(ws, 1)) + 1))
+        nsets = cold_sets(ws)
         L = Launcher(astra, c, data, nsets)
+        cpu = None if args.no_cpu else cpu_case_baseline(c, data)
         for hot in (False, True):
             reps, warm = 100, 20
             pick = (lambda k: 0) if hot else (lambda k: k)
@@ -385,14 +523,14 @@ def run_sweep(args):
                 L.launch(sh, pick(warm + k))
             e1.record(stream)
             torch.cuda.synchronize()
-            batch_us = e0.elapsed_time(e1) * 1e3 / reps
+            b_us = e0.elapsed_time(e1) * 1e3 / reps
             med = _median(d) * 1e-3
             print(json.dumps({"case": n, "cache": "hot" if hot else "cold", "buffer_sets": 1 if hot else nsets,
                               "rotation_bytes": ws * (1 if hot else nsets),
                               "launch": L.plan, "bytes": ws, "median_us": round(med * 1e6, 2),
-                              "min_us": round(min(d) * 1e3, 2), "batch_avg_us": round(batch_us, 2),
+                              "min_us": round(min(d) * 1e3, 2), "batch_avg_us": round(b_us, 2),
                               "GBs": round(ws / med / 1e9, 1), "frac_of_peak": round(ws / med / 1e9 / HBM_PEAK_GBS, 4),
-                              "tokens_per_s": round(c.tokens() / med, 1)}), flush=True)
+                              "tokens_per_s": round(c.tokens() / med, 1), "cpu_baseline": cpu}), flush=True)
         del L
         torch.cuda.empty_cache()
 
@@ -689,6 +827,206 @@ def run_ragged(args):
         print(json.dumps(out), flush=True)
 
 
+def _device_launcher(astra, kernel, shape, nsets, variant=0, arena=None, offsets=None):
+    """Launch closure on device-generated data (values do not matter for timing): `nsets` independent buffer sets.
+    `arena`/`offsets` (fused_add_rmsnorm only): place x and r at the given byte offsets of one existing allocation."""
+    import torch
+
+    code = astra.ASTRA_BF16
+    if kernel == "rmsnorm":
+        T, H = shape["T"], shape["H"]
+        n = T * H
+        w = (1.0 + 0.3 * torch.randn(H, device="cuda")).to(torch.bfloat16)
+        if arena is None:
+            x = torch.randn(nsets * n, device="cuda").to(torch.bfloat16)
+            r = (2.0 * torch.randn(nsets * n, device="cuda")).to(torch.bfloat16)
+            x0, r0 = x.data_ptr(), r.data_ptr()
+        else:
+            x0, r0 = arena.data_ptr() + offsets[0], arena.data_ptr() + offsets[1]
+            x = r = arena
+        keep = (x, r, w)
+        w0 = w.data_ptr()
+        if variant:
+            fn = lambda sh, k: astra.astra_ablation_fused_add_rmsnorm(x0 + (k % nsets) * n * 2, r0 + (k % nsets) * n * 2, w0, T, H,
+                                                                     code, 1e-5, variant, sh)
+        else:
+            fn = lambda sh, k: astra.astra_fused_add_rmsnorm(x0 + (k % nsets) * n * 2, r0 + (k % nsets) * n * 2, w0, T, H, code,
+                                                             1e-5, sh)
+        plan = astra.astra_plan_fused_add_rmsnorm(T, H, True)[1].as_dict()
+        nbytes = 4 * n * 2 + H * 2
+    elif kernel == "silu":
+        T, d = shape["T"], shape["d"]
+        a = torch.randn(nsets * T * 2 * d, device="cuda").to(torch.bfloat16)
+        o = torch.empty(nsets * T * d, dtype=torch.bfloat16, device="cuda")
+        keep = (a, o)
+        a0, o0 = a.data_ptr(), o.data_ptr()
+        fn = lambda sh, k: astra.astra_silu_and_mul(o0 + (k % nsets) * T * d * 2, a0 + (k % nsets) * T * d * 4, T, d, code, sh)
+        plan = astra.astra_plan_silu_and_mul(T, d, True)[1].as_dict()
+        nbytes = 3 * T * d * 2
+    else:
+        T, NH, D = shape["T"], shape["NH"], shape["D"]
+        n, p = T * NH * D, T * NH
+        va = torch.randn(nsets * n, device="cuda").to(torch.bfloat16)
+        vb = torch.randn(nsets * n, device="cuda").to(torch.bfloat16)
+        vo = torch.empty(nsets * n, dtype=torch.bfloat16, device="cuda")
+        la = torch.rand(nsets * p, device="cuda") * 20 - 5
+        lb = torch.rand(nsets * p, device="cuda") * 20 - 5
+        lo = torch.empty(nsets * p, dtype=torch.float32, device="cuda")
+        keep = (va, vb, vo, la, lb, lo)
+        q = [t.data_ptr() for t in (vo, lo, va, la, vb, lb)]
+        fn = lambda sh, k: astra.astra_merge_attn_states_lse(q[0] + (k % nsets) * n * 2, q[1] + (k % nsets) * p * 4,
+                                                             q[2] + (k % nsets) * n * 2, q[3] + (k % nsets) * p * 4,
+                                                             q[4] + (k % nsets) * n * 2, q[5] + (k % nsets) * p * 4, T, NH, D, code, sh)
+        plan = astra.astra_plan_merge_attn_states_lse(T, NH, D, True)[1].as_dict()
+        nbytes = 3 * n * 2 + 3 * p * 4
+
+    def launch(sh, k=0):
+        st = fn(sh, k)
+        if st != 0:
+            raise RuntimeError(f"{kernel} {shape}: astra status {st}")
+
+    return launch, plan, nbytes, keep
+
+
+def _fit_line(points):
+    """least squares t = a + bytes / BW over (bytes, us) points; returns (a in us, BW in GB/s, worst residual in us)"""
+    n = len(points)
+    sx = sum(b for b, _ in points)
+    sy = sum(t for _, t in points)
+    sxx = sum(b * b for b, _ in points)
+    sxy = sum(b * t for b, t in points)
+    slope = (n * sxy - sx * sy) / (n * sxx - sx * sx)
+    a = (sy - slope * sx) / n
+    return a, 1e-3 / slope, max(abs(t - (a + slope * b)) for b, t in points)
+
+
+def run_fit(args):
+    """Fixed cost per launch and streaming rate of each operator at its headline row length: microseconds per launch
+    (HIP-graph replay, cold) over a sweep of T, and the least-squares line t = a + bytes / BW through the points of
+    60 MB and more.  The same for astra_stream_probe with the operator's traffic mix at the same bytes per stream, and
+    for an empty kernel launch: what the machine itself takes for such a launch."""
+    import types
+
+    import torch
+
+    import paper_2509_07506_amd as astra
+
+    astra.load_library()
+    torch.cuda.set_device(0)
+    sweeps = [("rmsnorm", "H", 8192, [256, 512, 1024, 2048, 4096, 8192, 16384, 32768]),
+              ("silu", "d", 14336, [64, 128, 256, 512, 1024, 2048, 4096, 8192]),
+              ("merge", None, None, [512, 1024, 2048, 4096, 8192, 16384, 32768, 65536])]
+    # the floor: a launch that moves 16 bytes
+    tiny = torch.zeros(64, dtype=torch.uint8, device="cuda")
+    floor_us = graph_us(lambda sh, k: astra.astra_stream_probe(None, None, tiny.data_ptr(), 16, astra.ASTRA_PROBE_WRITE1, sh), 200, 10, 1)
+    print(json.dumps({"series": "launch_floor", "what": "astra_stream_probe writing 16 bytes, HIP-graph replay", "us": round(floor_us, 3)}),
+          flush=True)
+    for kernel, dim, val, Ts in sweeps:
+        pts, ppts = [], []
+        for T in Ts:
+            shape = {"T": T, dim: val} if dim else {"T": T, "NH": 32, "D": 128}
+            per_stream = T * (val if dim else 32 * 128) * 2
+            ws = per_stream * (4 if kernel == "rmsnorm" else 3)
+            per_graph = 20 if ws > (200 << 20) else 100
+            nsets = min(per_graph, cold_sets(ws))
+            launch, plan, nbytes, keep = _device_launcher(astra, kernel, shape, nsets)
+            us = graph_us(launch, per_graph, 5, nsets)
+            del keep, launch
+            torch.cuda.empty_cache()
+            case = types.SimpleNamespace(kernel=kernel, dtype="bf16", shape=shape if dim else shape)
+            P = Probe(astra, case, nsets)
+            pus = graph_us(P.launch, per_graph, 5, nsets)
+            pbytes, mode = P.bytes, P.mode_name
+            P.bufs = None
+            del P
+            torch.cuda.empty_cache()
+            pts.append((nbytes, us))
+            ppts.append((pbytes, pus))
+            print(json.dumps({"series": kernel, "shape": shape, "bytes": nbytes, "us": round(us, 3), "GBs": round(nbytes / us / 1e3, 1),
+                              "frac_of_peak": round(nbytes / us / 1e3 / HBM_PEAK_GBS, 4), "launch": plan,
+                              "probe": {"mode": mode, "bytes": pbytes, "us": round(pus, 3), "GBs": round(pbytes / pus / 1e3, 1),
+                                        "frac_of_peak": round(pbytes / pus / 1e3 / HBM_PEAK_GBS, 4)},
+                              "rate_vs_probe": round((nbytes / us) / (pbytes / pus), 4)}), flush=True)
+        for name, series in ((kernel, pts), (kernel + "_probe", ppts)):
+            big = [q for q in series if q[0] >= 60e6]
+            a, bw, worst = _fit_line(big)
+            print(json.dumps({"fit": name, "points": len(big), "fixed_us": round(a, 3), "streaming_GBs": round(bw, 1),
+                              "streaming_frac_of_peak": round(bw / HBM_PEAK_GBS, 4), "worst_residual_us": round(worst, 3),
+                              "launch_floor_us": round(floor_us, 3)}), flush=True)
+
+
+PACE_ROWS = (512, 1024, 1536, 2048, 2560, 3072, 4096, 5120, 6144, 7168, 7680, 8192, 10240, 11008, 12288, 14336, 16384, 20480, 28672,
+             32768)
+
+
+def run_pacing(args):
+    """A/B of the request pacing of fused_add_rmsnorm (include/astra_plan.h, ASTRA_PACE_*): for every row length of
+    PACE_ROWS at T*H = 2^28 (bf16, 2.1 GB moved per launch), the four forced paces (include/astra_ablation.h) and the
+    library's own choice, each on the same 12 placements of x and r inside one 6 GiB allocation, in one process:
+    microseconds per launch (2 warm-up + 10 launches between one event pair), mean and worst over the placements."""
+    import torch
+
+    import paper_2509_07506_amd as astra
+
+    astra.load_library()
+    torch.cuda.set_device(0)
+    stream = torch.cuda.current_stream()
+    sh = stream.cuda_stream
+    arena = torch.empty(6 << 30, dtype=torch.uint8, device="cuda")
+    arena.view(torch.bfloat16).normal_()
+    MiB = 1 << 20
+    placements = [(i * 96 * MiB, 2560 * MiB + j * 164 * MiB) for i in (0, 1, 2) for j in (0, 1, 2, 3)]   # 512 MiB tensors
+    variants = (("none", astra.ASTRA_VARIANT_PACE_NONE), ("gap", astra.ASTRA_VARIANT_PACE_STORE_GAP),
+                ("x", astra.ASTRA_VARIANT_PACE_X_BEFORE_R), ("w,x", astra.ASTRA_VARIANT_PACE_WEIGHT_X_R), ("policy", 0))
+    rows = [int(h) for h in args.rows.split(",")] if args.rows else PACE_ROWS
+    for H in rows:
+        T = (1 << 28) // H
+        res = {name: [] for name, _ in variants}
+        for off in placements:
+            for name, v in variants:
+                launch, plan, nbytes, keep = _device_launcher(astra, "rmsnorm", {"T": T, "H": H}, 1, v, arena, off)
+                res[name].append(batch_us(launch, stream, sh, 10, 2))
+        pace_names = {0: "none", 4: "gap", 2: "x", 3: "w,x"}
+        out = {"H": H, "T": T, "bytes": nbytes, "placements": len(placements), "policy_pace": pace_names.get(plan["pace"], plan["pace"]),
+               "vectors_per_lane": plan["vectors_per_lane"], "block": plan["block"]}
+        # paired with the default pace on the same placement: a special case is worth having only if it wins on
+        # (nearly) every placement, not merely on average
+        default = "gap" if T >= 32 * 256 * max(1, 2048 // plan["block"]) else "none"
+        out["default"] = default
+        for name, v in res.items():
+            gains = [d - t for d, t in zip(res[default], v)]
+            out[name] = {"mean_us": round(sum(v) / len(v), 2), "worst_us": round(max(v), 2), "best_us": round(min(v), 2),
+                         "mean_gain_over_default_us": round(sum(gains) / len(gains), 2),
+                         "placements_faster_than_default": sum(g > 0 for g in gains),
+                         "us": [round(t, 1) for t in v]}
+        print(json.dumps(out), flush=True)
+
+
+def run_pacing_few_rounds(args):
+    """The same A/B on grids of one to a few rounds of resident workgroups (prefill chunks), where the launch policy
+    asks for "x before r" once a compute unit requests 48 KiB at once: forced "none", forced "x" and the library's
+    choice, HIP-graph replay, cold (buffer sets rotate), microseconds per launch.  The geometry (lanes, vectors per
+    lane) is the policy's in all three columns; only the pace differs."""
+    import torch
+
+    import paper_2509_07506_amd as astra
+
+    astra.load_library()
+    torch.cuda.set_device(0)
+    for H in (2048, 3072, 4096, 5120, 7168, 8192):
+        for T in (256, 512, 768, 1024, 1280, 1536, 2048, 2560, 3072, 4096):
+            ws = 4 * T * H * 2
+            nsets = min(100, cold_sets(ws))
+            out = {"H": H, "T": T, "bytes": ws + 2 * H}
+            for name, v in (("none", astra.ASTRA_VARIANT_PACE_NONE), ("x", astra.ASTRA_VARIANT_PACE_X_BEFORE_R), ("policy", 0)):
+                launch, plan, nbytes, keep = _device_launcher(astra, "rmsnorm", {"T": T, "H": H}, nsets, v)
+                out[name + "_us"] = round(graph_us(launch, 100, 5, nsets), 3)
+                del keep, launch
+                torch.cuda.empty_cache()
+            out["policy_plan"] = {k: plan[k] for k in ("block", "vectors_per_lane", "pace")}
+            print(json.dumps(out), flush=True)
+
+
 def run_ceiling(args):
     """Streaming ceiling of this machine with the operators' access pattern: astra_stream_copy over
     512 MiB, alternating between two source/destination pairs (2 GiB footprint, so always cold)."""
@@ -833,6 +1171,10 @@ def main():
     ap.add_argument("--ragged", action="store_true", help="odd row lengths: ragged vs vector vs element-wise kernels")
     ap.add_argument("--vs-eager", action="store_true",
                     help="context: the step workloads through this library and through plain PyTorch tensor ops")
+    ap.add_argument("--fit", action="store_true", help="fixed cost per launch and streaming rate: T sweeps of kernels and probes")
+    ap.add_argument("--pacing", action="store_true", help="fused_add_rmsnorm request pacing A/B over buffer placements")
+    ap.add_argument("--few-rounds", action="store_true", help="with --pacing: grids of one to a few rounds (prefill chunks) instead")
+    ap.add_argument("--rows", default=None, help="with --pacing: comma-separated row lengths instead of the full list")
     ap.add_argument("--ablation", action="store_true",
                     help="paper Table-4 shapes and the bandwidth workloads: tuned kernel vs each one-optimisation-removed variant")
     args = ap.parse_args()
@@ -840,7 +1182,13 @@ def main():
         print("bench.py: this path runs on ONE GPU (row-independent kernels, no collectives); "
               "--gpus N with N > 1 is not supported", file=sys.stderr)
         sys.exit(2)
-    if args.vs_eager:
+    if args.fit:
+        run_fit(args)
+    elif args.pacing and args.few_rounds:
+        run_pacing_few_rounds(args)
+    elif args.pacing:
+        run_pacing(args)
+    elif args.vs_eager:
         run_vs_eager(args)
     elif args.prefill:
         run_prefill(args)

@@ -104,6 +104,24 @@ astra_status_t astra_merge_attn_states_lse(void* v_out, float* lse_out, const vo
  */
 astra_status_t astra_stream_copy(void* dst, const void* src, int64_t nbytes, hipStream_t stream);
 
+/*
+ * Measurement aid, not one of the paper's operators: moves `nbytes` bytes per stream with the traffic mix of an
+ * operator and none of its arithmetic, with the launch geometry the operators use, so that an operator's time can be
+ * set against what the machine does for the same bytes.  a, b, c: device buffers of nbytes each, 16-byte aligned,
+ * pairwise disjoint, nbytes a multiple of 16; a buffer the mode does not touch may be NULL.
+ */
+typedef enum {
+    ASTRA_PROBE_COPY = 0,         /* c <- a: one read stream, one write stream */
+    ASTRA_PROBE_READ2 = 1,        /* a and b are read, nothing is written */
+    ASTRA_PROBE_WRITE1 = 2,       /* c is written */
+    ASTRA_PROBE_READ2_WRITE1 = 3, /* c <- a ^ b: the mix of silu_and_mul and merge_attn_states_lse */
+    ASTRA_PROBE_UPDATE2 = 4       /* a <- a ^ b, b <- a + b, in place: the mix of fused_add_rmsnorm */
+} astra_probe_t;
+
+/* Errors: ASTRA_ERR_NULL (a buffer the mode uses is NULL), ASTRA_ERR_SHAPE (nbytes < 0, not a multiple of 16, more than
+ * 2^31 vectors, or an unknown mode), ASTRA_ERR_ALIGN, ASTRA_ERR_ALIAS, ASTRA_ERR_LAUNCH. */
+astra_status_t astra_stream_probe(void* a, void* b, void* c, int64_t nbytes, astra_probe_t mode, hipStream_t stream);
+
 /* Static, NUL-terminated description of a status code. */
 const char* astra_status_string(astra_status_t status);
 

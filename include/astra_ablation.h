@@ -28,9 +28,17 @@ typedef enum {
     ASTRA_VARIANT_LDS_TREE_REDUCTION = 2, /* fused_add_rmsnorm: LDS tree with a barrier per step instead of DPP + one LDS float per wave */
     ASTRA_VARIANT_UNHOISTED_WEIGHTS = 3,  /* merge_attn_states_lse: mixing weights recomputed for every element */
     ASTRA_VARIANT_LIBM_EXP_DIVIDE = 4,    /* silu_and_mul: library expf and an IEEE divide instead of v_exp_f32 / v_rcp_f32 */
-    ASTRA_VARIANT_ELEMENT_WISE = 5        /* all three: the plain element-wise kernels that astra.h keeps for inputs beyond the
+    ASTRA_VARIANT_ELEMENT_WISE = 5,       /* all three: the plain element-wise kernels that astra.h keeps for inputs beyond the
                                              limits of its other paths, here on any valid input (every storage type, any
                                              row length and alignment), so that they can be checked and timed at ordinary sizes */
+    /* fused_add_rmsnorm only, every storage type: the tuned row kernel with its request pacing (ASTRA_PACE_* in
+       astra_plan.h) forced instead of chosen by the launch policy, so that the policy's table can be re-measured.
+       Same arithmetic and results as the tuned kernel.  ASTRA_ERR_VARIANT unless the shape runs one row per workgroup
+       on the 16-byte path (rows of at most 4096 vectors, 16-byte aligned, fewer than 2^21 rows). */
+    ASTRA_VARIANT_PACE_NONE = 6,          /* every request as early as possible */
+    ASTRA_VARIANT_PACE_STORE_GAP = 7,     /* output store held until the residual store has completed */
+    ASTRA_VARIANT_PACE_X_BEFORE_R = 8,    /* x arrived before r is requested */
+    ASTRA_VARIANT_PACE_WEIGHT_X_R = 9     /* weight, then x, then r, one after the other */
 } astra_variant_t;
 
 /* ASTRA_ERR_VARIANT (astra.h): variant not applicable to this operator, shape or storage type (variants 1 to 4 exist

@@ -26,6 +26,10 @@ ASTRA_VARIANT_LDS_TREE_REDUCTION = 2
 ASTRA_VARIANT_UNHOISTED_WEIGHTS = 3
 ASTRA_VARIANT_LIBM_EXP_DIVIDE = 4
 ASTRA_VARIANT_ELEMENT_WISE = 5
+ASTRA_VARIANT_PACE_NONE = 6
+ASTRA_VARIANT_PACE_STORE_GAP = 7
+ASTRA_VARIANT_PACE_X_BEFORE_R = 8
+ASTRA_VARIANT_PACE_WEIGHT_X_R = 9
 ASTRA_ERR_VARIANT = 8
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
@@ -79,6 +83,8 @@ def load_library() -> ctypes.CDLL:
     L.astra_silu_and_mul.argtypes = [vp, vp, i64, i64, i32, vp]
     L.astra_merge_attn_states_lse.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, i32, vp]
     L.astra_stream_copy.argtypes = [vp, vp, i64, vp]
+    L.astra_stream_probe.argtypes = [vp, vp, vp, i64, i32, vp]
+    L.astra_stream_probe.restype = i32
     L.astra_fused_add_rmsnorm_strided.argtypes = [vp, i64, vp, i64, vp, i64, vp, i64, vp, i64, i64, i32, f32, vp]
     L.astra_fused_add_rmsnorm_strided.restype = i32
     L.astra_silu_and_mul_strided.argtypes = [vp, i64, vp, i64, i64, i64, i32, vp]
@@ -131,6 +137,13 @@ def astra_merge_attn_states_lse(v_out, lse_out, v_a, lse_a, v_b, lse_b, T, num_h
 
 def astra_stream_copy(dst, src, nbytes, stream=None) -> int:
     return load_library().astra_stream_copy(dst, src, nbytes, stream)
+
+
+ASTRA_PROBE_COPY, ASTRA_PROBE_READ2, ASTRA_PROBE_WRITE1, ASTRA_PROBE_READ2_WRITE1, ASTRA_PROBE_UPDATE2 = range(5)
+
+
+def astra_stream_probe(a, b, c, nbytes, mode, stream=None) -> int:
+    return load_library().astra_stream_probe(a, b, c, nbytes, mode, stream)
 
 
 def astra_fused_add_rmsnorm_strided(y_out, y_stride, r_out, r_out_stride, x, x_stride, r, r_stride, weight, T, H, dtype, eps,

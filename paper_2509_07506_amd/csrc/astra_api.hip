@@ -406,6 +406,12 @@ static astra_status_t run_fused_add_rmsnorm(void* input, void* residual, const v
         return ASTRA_ERR_ALIAS;
     if (variant == ASTRA_VARIANT_ELEMENT_WISE) {
         li = launch_info(T > 0 ? ASTRA_PATH_GENERIC : ASTRA_PATH_NONE, 256, 0, 0, T < kMaxGenericGrid ? T : kMaxGenericGrid, 0, 0);
+    } else if (variant >= ASTRA_VARIANT_PACE_NONE && variant <= ASTRA_VARIANT_PACE_WEIGHT_X_R) {
+        // the tuned row kernel with a forced pace: only where the plan launches it with one row per workgroup
+        if (T > 0 && (li.path != ASTRA_PATH_VECTOR || li.rows_per_block != 0 || li.grid < T)) return ASTRA_ERR_VARIANT;
+        static const int forced[4] = {kPaceNone, kPaceStoreGap, kPaceXBeforeR, kPaceWeightFirst | kPaceXBeforeR};
+        li.pace = forced[variant - ASTRA_VARIANT_PACE_NONE];
+        variant = ASTRA_VARIANT_TUNED;
     } else if (variant != ASTRA_VARIANT_TUNED) {
         if (dtype == ASTRA_F32) return ASTRA_ERR_VARIANT;
         if (variant != ASTRA_VARIANT_SCALAR_LOADS && variant != ASTRA_VARIANT_LDS_TREE_REDUCTION) return ASTRA_ERR_VARIANT;
@@ -718,6 +724,40 @@ astra_status_t astra_stream_copy(void* dst, const void* src, int64_t nbytes, hip
     const int lc = fit_chunk_log2(blocks, kFlatChunkLog2, kFlatChunkMinBlocks);
     stream_copy_kernel<kCopyUnroll, kNTLoad, kNTStore><<<dim3((uint32_t)pad_grid(blocks, lc)), dim3(256), 0, stream>>>(
         static_cast<u32x4*>(dst), static_cast<const u32x4*>(src), (uint32_t)nvec, lc);
+    return after_launch();
+}
+
+astra_status_t astra_stream_probe(void* a, void* b, void* c, int64_t nbytes, astra_probe_t mode, hipStream_t stream)
+{
+    const int m = (int)mode;
+    if (m < ASTRA_PROBE_COPY || m > ASTRA_PROBE_UPDATE2) return ASTRA_ERR_SHAPE;
+    const bool use_a = (m != ASTRA_PROBE_WRITE1), use_b = (m == ASTRA_PROBE_READ2 || m == ASTRA_PROBE_READ2_WRITE1 || m == ASTRA_PROBE_UPDATE2);
+    const bool use_c = (m == ASTRA_PROBE_COPY || m == ASTRA_PROBE_WRITE1 || m == ASTRA_PROBE_READ2_WRITE1);
+    if ((use_a && !a) || (use_b && !b) || (use_c && !c)) return ASTRA_ERR_NULL;
+    if (nbytes < 0 || nbytes % 16 != 0 || nbytes / 16 > kMaxVecIndex) return ASTRA_ERR_SHAPE;
+    if ((use_a && !aligned(a, 16)) || (use_b && !aligned(b, 16)) || (use_c && !aligned(c, 16))) return ASTRA_ERR_ALIGN;
+    if ((use_a && use_b && overlaps(a, nbytes, b, nbytes)) || (use_a && use_c && overlaps(a, nbytes, c, nbytes)) ||
+        (use_b && use_c && overlaps(b, nbytes, c, nbytes)))
+        return ASTRA_ERR_ALIAS;
+    if (nbytes == 0) return ASTRA_OK;
+    const int64_t nvec = nbytes / 16;
+    const int block = flat_block(nvec);
+    const int64_t blocks = (nvec + block - 1) / block;
+    const int lc = fit_chunk_log2(blocks, kFlatChunkLog2, kFlatChunkMinBlocks * (256 / block));
+    const dim3 grid((uint32_t)pad_grid(blocks, lc));
+    u32x4* const pa = static_cast<u32x4*>(a);
+    u32x4* const pb = static_cast<u32x4*>(b);
+    u32x4* const pc = static_cast<u32x4*>(c);
+    for_flat_block(block, [&](auto bc) {
+        constexpr int B = decltype(bc)::value;
+        switch (m) {
+            case ASTRA_PROBE_COPY: stream_probe_kernel<0, B><<<grid, dim3(B), 0, stream>>>(pa, pb, pc, (uint32_t)nvec, lc); break;
+            case ASTRA_PROBE_READ2: stream_probe_kernel<1, B><<<grid, dim3(B), 0, stream>>>(pa, pb, pc, (uint32_t)nvec, lc); break;
+            case ASTRA_PROBE_WRITE1: stream_probe_kernel<2, B><<<grid, dim3(B), 0, stream>>>(pa, pb, pc, (uint32_t)nvec, lc); break;
+            case ASTRA_PROBE_READ2_WRITE1: stream_probe_kernel<3, B><<<grid, dim3(B), 0, stream>>>(pa, pb, pc, (uint32_t)nvec, lc); break;
+            default: stream_probe_kernel<4, B><<<grid, dim3(B), 0, stream>>>(pa, pb, pc, (uint32_t)nvec, lc); break;
+        }
+    });
     return after_launch();
 }
 

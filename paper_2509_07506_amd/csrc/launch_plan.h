@@ -142,47 +142,39 @@ inline bool rmsnorm_row_plan(int64_t hv, RowPlan* plan)
     return true;
 }
 
-// When the waves of the row kernel issue their requests (fused_add_rmsnorm_kernels.h, PACE).  Streaming grids (three
-// rounds of resident workgroups or more; smaller grids further down): measured on MI355X with T*H = 2^28 16-bit elements,
-// microseconds per launch averaged over 16 placements of x and r inside one 6 GiB allocation (10 for the two-vector
-// rows), worst placement in brackets; "gap" = output store held until the residual store has completed, "x" = x
-// arrived before r is requested, "w,x" = weight, then x, then r one after the other:
-//                 none        gap         x           w,x
-//   H =  2048   342 (362)   328 (346)   326 (337)   323 (339)
-//   H =  4096   337 (349)   320 (338)   322 (325)   320 (326)
-//   H =  5120   326 (331)   326 (332)   332 (335)   355 (358)
-//   H =  6144   329 (334)   329 (334)   332 (339)   340 (346)
-//   H =  8192   331 (342)   329 (332)   325 (332)   323 (329)
-//   H =   512   324 (335)   324 (341)   320 (326)   322 (330)
-//   H =  1024   327 (341)   326 (341)   327 (340)   323 (336)
-//   H =  3072   336 (345)   333 (341)   328 (333)   336 (342)
-//   H =  7168   329 (331)   330 (332)   328 (331)   329 (332)
-//   H = 10240   342 (345)   341 (343)   339 (342)   336 (338)     two vectors per lane
-//   H = 11008   342 (345)   342 (345)   344 (347)   336 (340)     two vectors per lane
-//   H = 12288   339 (340)   339 (340)   338 (339)   337 (339)     two vectors per lane
-//   H = 14336   341 (342)   341 (343)   338 (339)   336 (337)     two vectors per lane
-//   H = 16384   347 (353)   346 (351)   338 (341)   345 (350)     two vectors per lane
-//   H = 20480   354 (355)   355 (356)   352 (352)   350 (352)     four vectors per lane
-//   H = 28672   353 (359)   354 (357)   353 (358)   374 (382)     four vectors per lane
-//   H = 32768   360 (372)   356 (365)   346 (355)   360 (365)     four vectors per lane
-// (floor at 8 TB/s: 268 us).  "gap" is never far from the best and has no bad case, so it is the default; the other
-// two are taken only where they measured at least 1.5 % better: "w,x" for rows of 256, 512 or 1024 vectors (4, 8,
-// 16 KiB) and for two-vector rows, "x" for rows of 384, 2048 and 4096 vectors, and for 896 (H = 7168: level here,
-// 1-2 % better than the others on grids of 3 to 16 rounds).  Serialising x and r can lose 8 % on other row lengths
-// (H = 5120), and waiting for the weight 6 % (H = 28672), so neither is used outside the measured cases.
-// Rows measured later in the same way, same columns: H = 1536: 341 (351), 337 (347), 333 (340), 330 (334);
-// H = 2560: 331 (337), 328 (338), 322 (328), 334 (336); H = 7680: 332 (340), 332 (335), 332 (336), 330 (332); H = 3584,
-// 4608 and 6656 level within 1 %.  "x" is taken for 192, 320 and 960 vectors as well (1-2.5 % better than "none"
-// and "gap" on grids of 3 to 16 rounds too).
-// The gap lengthens every workgroup's life by one store round trip, which the end of the grid pays once: about a
-// microsecond whatever the size (H = 1024: 23.5 against 22.5 at T = 16384, 84.0 against 82.6 at T = 65536), so under
-// kGapMinRounds rounds of resident workgroups the default is "none".
+// When the waves of the row kernel issue their requests (fused_add_rmsnorm_kernels.h, PACE), streaming grids (three
+// rounds of resident workgroups or more; smaller grids further down).  "gap" = output store held until the residual
+// store has completed, "x" = x arrived before r is requested, "w,x" = weight, then x, then r one after the other.
+// The table below is what `bench.py --pacing` measures (T*H = 2^28 16-bit elements, every pace forced through the
+// ablation entry point on the same 12 placements of x and r inside one allocation, one process): mean microseconds
+// per launch, and in brackets the mean gain over "gap" and on how many of the 12 placements the pace beat "gap".
+// The same code moves by 1-5 % with the placement alone, so a row length gets a pace of its own only if that pace
+// beat the default on at least 11 of the 12 placements and by at least 1.5 % on average; everything else takes the
+// default.  Rows kept (H in 16-bit elements):
+//   H =  1024   gap 331.1   w,x 322.7 (+8.4, 12/12)
+//   H =  1536   gap 339.4   w,x 330.3 (+9.2, 12/12)
+//   H =  2048   gap 331.1   w,x 325.1 (+6.0, 11/12)
+//   H =  2560   gap 333.0   x   324.6 (+8.4, 12/12)
+//   H =  3072   gap 335.5   x   329.6 (+5.9, 12/12)
+//   H =  8192   gap 331.2   w,x 324.6 (+6.6, 11/12)
+//   H = 14336   gap 346.0   w,x 338.1 (+7.8, 12/12)     two vectors per lane
+//   H = 16384   gap 345.2   x   339.0 (+6.2, 12/12)     two vectors per lane
+// Rows measured and left at the default (best alternative): H = 512 x +3.6 (9/12); 4096 w,x +0.7 (5/12); 5120 none +0.1;
+// 6144 none -0.3; 7168 x +3.0 (10/12); 7680 w,x +3.8 (11/12, 1.1 %); 10240 w,x +3.6 (9/12); 11008 w,x +2.7 (10/12);
+// 12288 w,x +4.2 (12/12, 1.2 %); 20480 x +2.4; 28672 x +0.9; 32768 x +4.2 (10/12).  A forced pace can also lose a lot:
+// "w,x" costs 28 us (8 %) at H = 5120 and 25 us at H = 28672, "x" 5 us at H = 5120, which is why there is no blanket
+// rule.  (floor at 8 TB/s: 268 us.)
+// Default: "gap" against "none" is 2-12 us better for rows of 1536 to 4096 elements and level elsewhere.  The gap
+// lengthens every workgroup's life by one store round trip, which the end of the grid pays once: about a microsecond
+// whatever the size (H = 1024: 23.5 against 22.5 at T = 16384, 84.0 against 82.6 at T = 65536), so under kGapMinRounds
+// rounds of resident workgroups the default is "none".
 constexpr int kGapMinRounds = 32;
 
-inline int rmsnorm_stream_pace(int64_t hv, int vpt, bool long_grid)
+inline int rmsnorm_stream_pace(int64_t hv, bool long_grid)
 {
-    if (hv == 192 || hv == 320 || hv == 384 || hv == 896 || hv == 960 || hv == 2048 || hv == 4096) return kPaceXBeforeR;
-    if (vpt == 2 || hv == 256 || hv == 512 || hv == 1024) return kPaceWeightFirst | kPaceXBeforeR;
+    // keys are row lengths in 16-byte vectors: H / 8 for the 16-bit storage types the table was measured with
+    if (hv == 320 || hv == 384 || hv == 2048) return kPaceXBeforeR;
+    if (hv == 128 || hv == 192 || hv == 256 || hv == 1024 || hv == 1792) return kPaceWeightFirst | kPaceXBeforeR;
     return long_grid ? kPaceStoreGap : kPaceNone;
 }
 
@@ -237,7 +229,7 @@ inline bool rmsnorm_row_policy(int64_t T, int64_t hv, int64_t row_bytes, RowPlan
     } else if (n < kStreamingRounds * resident) {
         *pace = kPaceXBeforeR;
     } else {
-        *pace = rmsnorm_stream_pace(hv, plan->vpt, n >= kGapMinRounds * resident);
+        *pace = rmsnorm_stream_pace(hv, n >= kGapMinRounds * resident);
     }
     return true;
 }

@@ -190,17 +190,18 @@ def test_rmsnorm_plans(A):
     assert "rows_per_block" not in plan((1 << 26) + 1, 8) and plan((1 << 26) + 1, 8)["block"] == 64   # beyond the grid limit: row loop
     assert A.astra_plan_fused_add_rmsnorm(-1, 8, True)[0] == 2
     # request pacing: none while a compute unit requests under 48 KiB at once and for the row-loop kernel; on streaming
-    # grids (three rounds or more) "store gap" (4) by default on long grids, weight-then-x-then-r (1 | 2) for 4 KiB / 16 KiB rows and
-    # for two-vector rows, x-then-r (2) for some row lengths
+    # grids (three rounds or more) "store gap" (4) by default on long grids, and a pace of its own for the row lengths that
+    # beat the default on nearly every buffer placement (bench.py --pacing): weight-then-x-then-r (1 | 2), x-then-r (2)
     assert plan(255, 8192)["pace"] == 0 and plan(512, 4096)["pace"] == 0 and big["pace"] == 0
-    assert plan(32768, 8192)["pace"] == 3 and plan(32768, 2048)["pace"] == 3 and plan(4096, 11008)["pace"] == 3
-    assert plan(32768, 4096)["pace"] == 3 and plan(4096, 16384)["pace"] == 2
-    assert plan(32768, 5120)["pace"] == 4 and plan(16384, 28672)["pace"] == 4 and plan(1 << 20, 1024)["pace"] == 4
-    # ... but only where the gap's extra microsecond at the end of the grid is small change (32 rounds or more)
-    assert plan(4099, 5120)["pace"] == 0 and plan(2048, 28672)["pace"] == 0 and plan(32768, 1024)["pace"] == 0
-    assert plan(2048, 3072)["pace"] == 2 and plan(2048, 32768)["pace"] == 2
+    for T, H, pace in [(32768, 8192, 3), (32768, 2048, 3), (32768, 1024, 3), (32768, 1536, 3), (4096, 14336, 3),
+                       (32768, 2560, 2), (32768, 3072, 2), (4096, 16384, 2),
+                       (32768, 4096, 4), (32768, 5120, 4), (32768, 7168, 4), (32768, 7680, 4), (32768, 11008, 4), (32768, 12288, 4),
+                       (32768, 10240, 4), (16384, 28672, 4), (16384, 32768, 4), (1 << 20, 512, 4)]:
+        assert plan(T, H)["pace"] == pace, (T, H, plan(T, H))
+    # ... the gap only where its extra microsecond at the end of the grid is small change (32 rounds or more)
+    assert plan(4099, 5120)["pace"] == 0 and plan(2048, 28672)["pace"] == 0 and plan(4099, 7168)["pace"] == 0
+    assert plan(2048, 3072)["pace"] == 2 and plan(2048, 32768)["pace"] == 0
     assert plan(2048, 11008)["vectors_per_lane"] == 2 and plan(2048, 28672)["vectors_per_lane"] == 4
-    assert plan(4099, 7168)["pace"] == 2
     # grids of under three rounds: x-then-r once a compute unit requests 48 KiB at once ...
     for T, H in [(1023, 8192), (512, 8192), (768, 8192), (1024, 4096), (2048, 4096), (2048, 2048), (1024, 7168)]:
         p = plan(T, H)
@@ -356,3 +357,32 @@ def test_binding_refuses_cpu_tensors(A):
     x = torch.zeros((2, 64), dtype=torch.bfloat16)
     with pytest.raises(ValueError):
         A.fused_add_rmsnorm(x, x.clone(), torch.ones(64, dtype=torch.bfloat16), 1e-6)
+
+
+def test_stream_probe_validation(A):
+    f = A.astra_stream_probe
+    a, b, c = 0x10000, 0x20000, 0x30000          # never dereferenced: every call below fails validation or moves nothing
+    assert f(a, b, c, 16, 5) == 2 and f(a, b, c, 16, -1) == 2                       # unknown mode
+    assert f(0, b, c, 16, A.ASTRA_PROBE_COPY) == 1 and f(a, 0, 0, 16, A.ASTRA_PROBE_COPY) == 1
+    assert f(a, 0, c, 16, A.ASTRA_PROBE_READ2) == 1 and f(a, b, 0, 16, A.ASTRA_PROBE_READ2_WRITE1) == 1
+    assert f(0, 0, 0, 16, A.ASTRA_PROBE_WRITE1) == 1 and f(a, 0, 0, 16, A.ASTRA_PROBE_UPDATE2) == 1
+    assert f(a, b, c, -16, 0) == 2 and f(a, b, c, 24, 0) == 2 and f(a, b, c, (1 << 35) + 16, 0) == 2
+    assert f(a + 8, b, c, 16, 0) == 5 and f(a, b + 4, c, 16, 3) == 5 and f(a, b, c + 2, 16, 2) == 5
+    assert f(a, b, a + 16, 64, 0) == 6 and f(a, a, c, 64, 3) == 6 and f(a, b, b, 64, 3) == 6 and f(a, a + 32, 0, 64, 4) == 6
+    assert f(a, 0, c, 0, 0) == 0 and f(0, 0, c, 0, 2) == 0 and f(a, b, 0, 0, 1) == 0    # nothing to move
+    # buffers a mode does not use are not looked at
+    assert f(a, 1, c, 0, A.ASTRA_PROBE_COPY) == 0 and f(3, 5, c, 0, A.ASTRA_PROBE_WRITE1) == 0
+
+
+def test_pace_variants_validate_like_the_operator(A):
+    f = A.astra_ablation_fused_add_rmsnorm
+    a, b, c = 1 << 40, 2 << 40, 3 << 40          # never dereferenced
+    for v in (A.ASTRA_VARIANT_PACE_NONE, A.ASTRA_VARIANT_PACE_STORE_GAP, A.ASTRA_VARIANT_PACE_X_BEFORE_R, A.ASTRA_VARIANT_PACE_WEIGHT_X_R):
+        assert f(0, b, c, 1, 8, 1, 1e-6, v) == 1 and f(a, b, c, -1, 8, 1, 1e-6, v) == 2 and f(a, b, c, 1, 8, 7, 1e-6, v) == 3
+        assert f(a, b, c, 1, 8, 1, -1.0, v) == 4 and f(a + 1, b, c, 1, 8, 1, 1e-6, v) == 5 and f(a, a, c, 1, 8, 1, 1e-6, v) == 6
+        assert f(a, b, c, 0, 8, 1, 1e-6, v) == 0                                          # T == 0: nothing to do
+        assert f(a + 2, b, c, 4, 4096, 1, 1e-6, v) == A.ASTRA_ERR_VARIANT                 # ragged path: no row kernel to pace
+        assert f(a, b, c, 4, 4100, 1, 1e-6, v) == A.ASTRA_ERR_VARIANT
+        assert f(a, b, c, 4, 40000, 1, 1e-6, v) == A.ASTRA_ERR_VARIANT                    # element-wise path
+        assert f(a, b, c, 1 << 22, 264, 1, 1e-6, v) == A.ASTRA_ERR_VARIANT                # row loop beyond the grid limit
+    assert f(a, b, c, 4, 4096, 1, 1e-6, 10) == A.ASTRA_ERR_VARIANT and f(a, b, c, 4, 4096, 1, 1e-6, -1) == A.ASTRA_ERR_VARIANT

@@ -53,6 +53,36 @@ def test_committed_traffic_matches_algorithmic_bytes():
         assert os.path.exists(os.path.join(ROOT, t["source"]))
 
 
+def test_committed_traffic_was_counted_on_the_geometry_the_library_plans_now():
+    """The counter figures bench.py reports are a committed file; they name the kernel instantiation and the launch
+    geometry they were collected on.  When a kernel or policy change makes the library plan something else for the
+    benchmark workloads, the figures are stale: bench.py then reports traffic null, and this test fails until the
+    counters are collected again."""
+    import paper_2509_07506_amd as astra
+
+    with open(os.path.join(ROOT, "profiles", "hbm_traffic.json")) as f:
+        traffic = json.load(f)
+    sys.path.insert(0, ROOT)
+    import bench
+
+    for name, t in traffic.items():
+        c = workloads.case(name)
+        s = c.shape
+        if c.kernel == "rmsnorm":
+            st, info = astra.astra_plan_fused_add_rmsnorm(s["T"], s["H"], True)
+        elif c.kernel == "silu":
+            st, info = astra.astra_plan_silu_and_mul(s["T"], s["d"], True)
+        else:
+            st, info = astra.astra_plan_merge_attn_states_lse(s["T"], s["NH"], s["D"], True)
+        assert st == 0
+        assert t["launch"] == info.as_dict(), f"{name}: counters were collected on {t['launch']}, the library plans {info.as_dict()}"
+        assert bench.KERNEL_NAMES[c.kernel] in t["kernel"]
+        got, why = bench.traffic_for(traffic, name, info.as_dict())
+        assert got is t and why is None
+        stale, why = bench.traffic_for(traffic, name, dict(info.as_dict(), block=info.block * 2))
+        assert stale is None and "stale" in why
+
+
 def test_median():
     sys.path.insert(0, ROOT)
     import bench

@@ -142,3 +142,60 @@ def test_variant_validation_on_device(A):
     assert A.astra_ablation_silu_and_mul(p, p + 65536, 2, 512, A.ASTRA_F16, 99, None) == E
     torch.cuda.synchronize()
     assert bool((buf == 0).all())
+
+
+@pytest.mark.parametrize("dt", ["bf16", "f16"])
+@pytest.mark.parametrize("T,H", [(3, 4096), (700, 2048), (1100, 5120), (300, 8192), (65, 10240), (20, 20480), (1500, 512)])
+def test_forced_pacing_gives_the_tuned_kernels_bits(A, T, H, dt):
+    """The pace-forcing variants run the tuned row kernel with another order of memory requests: same arithmetic, so
+    the same bits as astra_fused_add_rmsnorm, and the oracle's bars."""
+    print(f"[pace] T={T} H={H} {dt}", flush=True)
+    x, r, w = workloads.rmsnorm_inputs(T, H, dt, np.random.default_rng([31, T, H]), r_std=2.0)
+    xd, rd, wd = to_dev(x, dt), to_dev(r, dt), to_dev(w, dt)
+    A.fused_add_rmsnorm(xd, rd, wd, 1e-5)
+    torch.cuda.synchronize()
+    y0, r0 = to_bits(xd), to_bits(rd)
+    for v in (A.ASTRA_VARIANT_PACE_NONE, A.ASTRA_VARIANT_PACE_STORE_GAP, A.ASTRA_VARIANT_PACE_X_BEFORE_R, A.ASTRA_VARIANT_PACE_WEIGHT_X_R):
+        _rmsnorm(A, x, r, w, 1e-5, dt, v)          # against the oracle
+        xd, rd = to_dev(x, dt), to_dev(r, dt)
+        st = A.astra_ablation_fused_add_rmsnorm(xd.data_ptr(), rd.data_ptr(), wd.data_ptr(), T, H, _code(A, dt), 1e-5, v,
+                                                torch.cuda.current_stream().cuda_stream)
+        assert st == 0
+        torch.cuda.synchronize()
+        assert np.array_equal(to_bits(xd), y0) and np.array_equal(to_bits(rd), r0), f"variant {v} differs from the tuned kernel"
+
+
+def test_stream_probes_move_what_they_say(A):
+    """astra_stream_probe: results of every mode on sizes around the workgroup and grid-padding edges; untouched
+    buffers stay untouched."""
+    s = torch.cuda.current_stream().cuda_stream
+    for nvec in (1, 63, 64, 257, 4096 * 256 + 5, 70000):
+        n = nvec * 16
+        g = torch.Generator(device="cpu").manual_seed(nvec)
+        a0 = torch.randint(-2**31, 2**31 - 1, (nvec * 4,), dtype=torch.int32, generator=g)
+        b0 = torch.randint(-2**31, 2**31 - 1, (nvec * 4,), dtype=torch.int32, generator=g)
+        pad = 64
+        def dev(t):
+            whole = torch.full((pad + t.numel() + pad,), 0x5A5A5A5A, dtype=torch.int32, device="cuda")
+            whole[pad:pad + t.numel()] = t.cuda()
+            return whole, whole[pad:pad + t.numel()]
+        def edges_ok(whole):
+            return bool((whole[:pad] == 0x5A5A5A5A).all() and (whole[-pad:] == 0x5A5A5A5A).all())
+        for mode in range(5):
+            (aw, a), (bw, b), (cw, c) = dev(a0), dev(b0), dev(torch.zeros_like(a0))
+            st = A.astra_stream_probe(a.data_ptr(), b.data_ptr(), c.data_ptr(), n, mode, s)
+            assert st == 0, (nvec, mode, st)
+            torch.cuda.synchronize()
+            ah, bh, ch = a.cpu(), b.cpu(), c.cpu()
+            if mode == A.ASTRA_PROBE_COPY:
+                assert torch.equal(ch, a0) and torch.equal(ah, a0) and torch.equal(bh, b0)
+            elif mode == A.ASTRA_PROBE_READ2:
+                assert torch.equal(ah, a0) and torch.equal(bh, b0) and not ch.any()
+            elif mode == A.ASTRA_PROBE_WRITE1:
+                assert torch.equal(ch.view(-1, 4), torch.arange(nvec, dtype=torch.int32).view(-1, 1).expand(-1, 4))
+                assert torch.equal(ah, a0) and torch.equal(bh, b0)
+            elif mode == A.ASTRA_PROBE_READ2_WRITE1:
+                assert torch.equal(ch, a0 ^ b0) and torch.equal(ah, a0) and torch.equal(bh, b0)
+            else:
+                assert torch.equal(ah, a0 ^ b0) and torch.equal(bh, a0 + b0) and not ch.any()
+            assert edges_ok(aw) and edges_ok(bw) and edges_ok(cw)
