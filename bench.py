@@ -58,11 +58,12 @@ class Launcher:
     """Device buffers of one workload (optionally `nsets` independent copies, used round-robin so that no
     launch re-reads cache-resident bytes) and a closure that enqueues its kernel on a given stream."""
 
-    def __init__(self, astra, case, data, nsets: int = 1, variant: int = 0):
+    def __init__(self, astra, case, data, nsets: int = 1, variant: int = 0, offset_elems: int = 0):
         import torch
 
         self.case = case
         self.nsets = nsets
+        off = offset_elems  # every activation tensor starts this many elements past a 256-byte boundary
         v = variant  # 0 = the tuned kernel; otherwise an ablation variant (include/astra_ablation.h)
         dt = case.dtype
         tdt = {"bf16": torch.bfloat16, "f16": torch.float16, "f32": torch.float32}[dt]
@@ -73,8 +74,8 @@ class Launcher:
             # [nsets, ...] copies of one tensor, each copy 256-byte aligned
             n = t.numel()
             stride = -(-n * t.element_size() // 256) * 256 // t.element_size()
-            p = torch.empty(nsets * stride, dtype=t.dtype, device="cuda")
-            p.view(nsets, stride)[:, :n] = t.reshape(1, n)
+            p = torch.empty(nsets * stride + 64, dtype=t.dtype, device="cuda")
+            p[:nsets * stride].view(nsets, stride)[:, :n] = t.reshape(1, n)
             return p, stride * t.element_size()
 
         if case.kernel == "rmsnorm":
@@ -82,25 +83,25 @@ class Launcher:
             (xp, xs), (rp, rs) = pool(x), pool(r)
             self.bufs = (xp, rp, w)
             T, H, eps = s["T"], s["H"], case.eps
-            x0, r0, w0 = xp.data_ptr(), rp.data_ptr(), w.data_ptr()
+            x0, r0, w0 = xp.data_ptr() + off * x.element_size(), rp.data_ptr() + off * x.element_size(), w.data_ptr()
             if v == 0:
                 self.fn = lambda k, st: astra.astra_fused_add_rmsnorm(x0 + k * xs, r0 + k * rs, w0, T, H, code, eps, st)
             else:
                 self.fn = lambda k, st: astra.astra_ablation_fused_add_rmsnorm(x0 + k * xs, r0 + k * rs, w0, T, H, code,
                                                                                eps, v, st)
-            self.plan = astra.astra_plan_fused_add_rmsnorm(T, H, True, dtype=code)[1].as_dict()
+            self.plan = astra.astra_plan_fused_add_rmsnorm(T, H, 2 if off % (16 // x.element_size()) else 1, dtype=code)[1].as_dict()
         elif case.kernel == "silu":
             a = _to_dev(data[0], dt)
             ap, as_ = pool(a)
             op, os_ = pool(torch.empty((s["T"], s["d"]), dtype=tdt, device="cuda"))
             self.bufs = (ap, op)
             T, d = s["T"], s["d"]
-            a0, o0 = ap.data_ptr(), op.data_ptr()
+            a0, o0 = ap.data_ptr() + off * a.element_size(), op.data_ptr() + off * a.element_size()
             if v == 0:
                 self.fn = lambda k, st: astra.astra_silu_and_mul(o0 + k * os_, a0 + k * as_, T, d, code, st)
             else:
                 self.fn = lambda k, st: astra.astra_ablation_silu_and_mul(o0 + k * os_, a0 + k * as_, T, d, code, v, st)
-            self.plan = astra.astra_plan_silu_and_mul(T, d, True, dtype=code)[1].as_dict()
+            self.plan = astra.astra_plan_silu_and_mul(T, d, 0 if off % (16 // a.element_size()) else 1, dtype=code)[1].as_dict()
         else:
             va, la, vb, lb = data
             va, vb = _to_dev(va, dt), _to_dev(vb, dt)
@@ -109,7 +110,8 @@ class Launcher:
             (lap, ls), (lbp, _), (lop, _) = pool(la), pool(lb), pool(torch.empty_like(la))
             self.bufs = (vap, vbp, vop, lap, lbp, lop)
             T, NH, D = s["T"], s["NH"], s["D"]
-            p = [t.data_ptr() for t in (vop, lop, vap, lap, vbp, lbp)]
+            vo = off * va.element_size()  # the value tensors are offset, the scores are not
+            p = [vop.data_ptr() + vo, lop.data_ptr(), vap.data_ptr() + vo, lap.data_ptr(), vbp.data_ptr() + vo, lbp.data_ptr()]
             if v == 0:
                 self.fn = lambda k, st: astra.astra_merge_attn_states_lse(p[0] + k * vs, p[1] + k * ls, p[2] + k * vs,
                                                                           p[3] + k * ls, p[4] + k * vs, p[5] + k * ls, T, NH,
@@ -118,7 +120,7 @@ class Launcher:
                 self.fn = lambda k, st: astra.astra_ablation_merge_attn_states_lse(
                     p[0] + k * vs, p[1] + k * ls, p[2] + k * vs, p[3] + k * ls, p[4] + k * vs, p[5] + k * ls, T, NH, D, code, v,
                     st)
-            self.plan = astra.astra_plan_merge_attn_states_lse(T, NH, D, True, dtype=code)[1].as_dict()
+            self.plan = astra.astra_plan_merge_attn_states_lse(T, NH, D, 2 if off % (16 // va.element_size()) else 1, dtype=code)[1].as_dict()
 
     def launch(self, stream_handle, k: int = 0):
         st = self.fn(k % self.nsets, stream_handle)
@@ -813,17 +815,20 @@ def run_ragged(args):
 
     for i, (kernel, aligned_shape, odd_shape) in enumerate(trios):
         out = {"kernel": kernel}
-        for label, shape, variant in (("vector", aligned_shape, 0), ("ragged", odd_shape, 0),
-                                      ("element_wise", odd_shape, astra.ASTRA_VARIANT_ELEMENT_WISE)):
+        # "odd": the odd row length on 16-byte aligned tensors; "offset": the aligned row length with every activation
+        # tensor one element off the 16-byte grid (all of them alike)
+        for label, shape, variant, off in (("vector", aligned_shape, 0, 0), ("odd", odd_shape, 0, 0), ("offset", aligned_shape, 0, 1),
+                                           ("element_wise", odd_shape, astra.ASTRA_VARIANT_ELEMENT_WISE, 0)):
             c = workloads.Case(f"odd_{kernel}_{i}_{label}", kernel, 8, i, "bf16", shape, eps=1e-5, r_std=2.0)
-            L = Launcher(astra, c, c.generate(), 2, variant)
+            L = Launcher(astra, c, c.generate(), 2, variant, offset_elems=off)
             us = timed(L)
             out[label] = {"shape": shape, "path": L.plan["path"] if variant == 0 else "generic", "us": round(us, 2),
                           "GBs": round(c.algorithmic_bytes() / us / 1e3, 1)}
             del L
             torch.cuda.empty_cache()
-        out["ragged_over_element_wise"] = round(out["element_wise"]["us"] / out["ragged"]["us"], 2)
-        out["ragged_frac_of_vector_rate"] = round(out["ragged"]["GBs"] / out["vector"]["GBs"], 3)
+        out["odd_over_element_wise"] = round(out["element_wise"]["us"] / out["odd"]["us"], 2)
+        out["odd_frac_of_vector_rate"] = round(out["odd"]["GBs"] / out["vector"]["GBs"], 3)
+        out["offset_frac_of_vector_rate"] = round(out["offset"]["GBs"] / out["vector"]["GBs"], 3)
         print(json.dumps(out), flush=True)
 
 

@@ -19,8 +19,14 @@ typedef enum {
     ASTRA_PATH_VECTOR = 1,  /* 16-byte-per-lane fast path */
     ASTRA_PATH_GENERIC = 2, /* element-wise path: rmsnorm rows of more than 4096 vectors or less than one, inputs beyond
                                the 32-bit vector index */
-    ASTRA_PATH_RAGGED = 3   /* row lengths that are no whole number of vectors, or pointers that are only element
-                               aligned: 16-byte accesses at element alignment, the partial last vector element-wise */
+    ASTRA_PATH_RAGGED = 3,  /* row lengths that are no whole number of vectors, or pointers that are only element
+                               aligned, the tensors of the call at unrelated offsets into the 16-byte grid: 16-byte
+                               accesses at element alignment, the partial last vector element-wise */
+    ASTRA_PATH_PHASED = 4   /* the same row lengths and pointers, but the activation tensors of the call in step with
+                               each other (congruent modulo 16 bytes -- every dense call on 16-byte aligned tensors is):
+                               lanes own the 16-byte aligned chunks of memory a row covers, so all interior accesses are
+                               aligned; the partial chunk at a row end element-wise.  fused_add_rmsnorm and
+                               merge_attn_states_lse; runs at the vector path's rate */
 } astra_path_t;
 
 typedef struct {
@@ -46,9 +52,10 @@ enum {
     ASTRA_PACE_STORE_GAP = 4     /* the residual store has completed before the output store is issued */
 };
 
-/* `dtype` is the storage type of the call, `aligned16` tells whether every tensor pointer of the call is
- * 16-byte aligned (non-zero = yes).  Each function validates like its operator does (ASTRA_ERR_NULL for
- * `info`, ASTRA_ERR_SHAPE, ASTRA_ERR_DTYPE). */
+/* `dtype` is the storage type of the call.  `aligned16` tells how the tensor pointers of the call sit on the 16-byte
+ * grid: 1 = every pointer is 16-byte aligned; 2 = not, but the activation tensors (input and residual; v_a, v_b and
+ * v_out) are congruent modulo 16 bytes; 0 = element alignment only.  Each function validates like its operator does
+ * (ASTRA_ERR_NULL for `info`, ASTRA_ERR_SHAPE, ASTRA_ERR_DTYPE). */
 astra_status_t astra_plan_fused_add_rmsnorm(int64_t T, int64_t H, astra_dtype_t dtype, int aligned16,
                                             astra_launch_info_t* info);
 astra_status_t astra_plan_silu_and_mul(int64_t T, int64_t d, astra_dtype_t dtype, int aligned16, astra_launch_info_t* info);

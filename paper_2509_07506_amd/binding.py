@@ -49,11 +49,11 @@ class LaunchInfo(ctypes.Structure):
                 ("rows_per_block", ctypes.c_int32), ("access_bytes", ctypes.c_int32), ("non_temporal", ctypes.c_int32)]
 
     def as_dict(self):
-        return {"path": {0: "none", 1: "vector", 2: "generic", 3: "ragged"}[self.path], "block": self.block,
+        return {"path": {0: "none", 1: "vector", 2: "generic", 3: "ragged", 4: "phased"}[self.path], "block": self.block,
                 "vectors_per_lane": self.vectors_per_lane, "log2_xcd_chunk": self.log2_xcd_chunk, "grid": self.grid,
                 "pace": self.pace, **({"rows_per_block": self.rows_per_block} if self.rows_per_block else {}),
                 **({"access_bytes": self.access_bytes} if self.access_bytes not in (0, 16) else {}),
-                **({"non_temporal": 0} if self.path in (1, 3) and not self.non_temporal else {})}
+                **({"non_temporal": 0} if self.path in (1, 3, 4) and not self.non_temporal else {})}
 
 
 def library_path() -> str:

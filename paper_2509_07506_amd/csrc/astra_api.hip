@@ -26,6 +26,9 @@ using namespace astra;
 
 astra_status_t after_launch() { return hipGetLastError() == hipSuccess ? ASTRA_OK : ASTRA_ERR_LAUNCH; }
 
+// the `aligned16` argument of the astra_plan_* functions as an alignment class
+int plan_align(int aligned16) { return aligned16 == 2 ? kAlignPhased : (aligned16 != 0 ? kAlign16 : kAlignNone); }
+
 // ---- launches ---------------------------------------------------------------------------------------
 
 // Launches the row kernel for one plan.  STRIDED = false: `input` / `residual` are updated in place and `y_out`, `r_out`,
@@ -119,6 +122,15 @@ void launch_rmsnorm_ragged(const astra_launch_info_t& li, void* y_out, void* r_o
             <<<grid, block, 0, stream>>>(y, ro, xi, ri, w, ev, T, H, inv_h, eps, li.log2_xcd_chunk);
     };
     auto with_vpt = [&](auto vpt) {
+        if (li.path == ASTRA_PATH_PHASED) {  // all four views in step: aligned chunks
+            if (li.grid < T)  // more rows than the grid limit: workgroups walk several rows
+                fused_add_rmsnorm_phased_row_kernel<DT, decltype(vpt)::value, kNTLoad, kNTStore, true>
+                    <<<grid, block, 0, stream>>>(y, ro, xi, ri, w, ev, T, H, inv_h, eps, li.log2_xcd_chunk);
+            else
+                fused_add_rmsnorm_phased_row_kernel<DT, decltype(vpt)::value, kNTLoad, kNTStore, false>
+                    <<<grid, block, 0, stream>>>(y, ro, xi, ri, w, ev, T, H, inv_h, eps, li.log2_xcd_chunk);
+            return;
+        }
         if (H % Storage<DT>::kN != 0) go(vpt, std::true_type{});
         else go(vpt, std::false_type{});  // only the pointers or strides are unaligned: no tail code at all
     };
@@ -158,7 +170,7 @@ void launch_rmsnorm(const astra_launch_info_t& li, void* input, void* residual, 
             static_cast<E*>(input), static_cast<E*>(residual), static_cast<const E*>(weight), T, H, 1.0f / (float)H, eps);
         return;
     }
-    if (li.path == ASTRA_PATH_RAGGED) {
+    if (li.path == ASTRA_PATH_RAGGED || li.path == ASTRA_PATH_PHASED) {
         launch_rmsnorm_ragged<DT>(li, input, residual, input, residual, weight, RowViews{H, H, H, H}, T, H, eps, stream);
         return;
     }
@@ -265,6 +277,15 @@ void launch_merge(const astra_launch_info_t& li, void* v_out, float* lse_out, co
             (uint32_t)(pairs * dvr), dvr, D, make_fastdiv(dvr));
         return;
     }
+    if (li.path == ASTRA_PATH_PHASED) {  // the three value tensors share one phase (the plan made sure): aligned chunks
+        constexpr int N = Storage<DT>::kN;
+        const int phase = (int)((reinterpret_cast<uintptr_t>(v_a) / sizeof(E)) & (N - 1));
+        const int64_t n = pairs * D;
+        merge_attn_states_lse_phased_kernel<DT, kNTLoad, kNTStore><<<dim3((uint32_t)li.grid), dim3(256), 0, stream>>>(
+            static_cast<E*>(v_out), lse_out, static_cast<const E*>(v_a), lse_a, static_cast<const E*>(v_b), lse_b, (uint32_t)n,
+            (uint32_t)D, make_fastdiv((uint32_t)D), (uint32_t)((n + phase + N - 1) / N), phase, li.log2_xcd_chunk);
+        return;
+    }
     const uint32_t dvec = (uint32_t)(D / Storage<DT>::kN);
     int log2_dvec = -1;
     if ((dvec & (dvec - 1)) == 0) log2_dvec = __builtin_ctz(dvec);
@@ -317,7 +338,7 @@ void launch_rmsnorm_strided(const astra_launch_info_t& li, void* y_out, void* r_
             static_cast<const E*>(weight), ev, T, H, 1.0f / (float)H, eps);
         return;
     }
-    if (li.path == ASTRA_PATH_RAGGED) {
+    if (li.path == ASTRA_PATH_RAGGED || li.path == ASTRA_PATH_PHASED) {
         launch_rmsnorm_ragged<DT>(li, y_out, r_out, x, r, weight, ev, T, H, eps, stream);
         return;
     }
@@ -369,14 +390,14 @@ astra_status_t astra_plan_fused_add_rmsnorm(int64_t T, int64_t H, astra_dtype_t 
                                             astra_launch_info_t* info)
 {
     if (!info) return ASTRA_ERR_NULL;
-    const astra_status_t st = plan_rmsnorm(T, H, elem_bytes((int)dtype), aligned16 != 0, info);
+    const astra_status_t st = plan_rmsnorm(T, H, elem_bytes((int)dtype), plan_align(aligned16), info);
     return st == ASTRA_OK && !valid_dtype((int)dtype) ? ASTRA_ERR_DTYPE : st;
 }
 
 astra_status_t astra_plan_silu_and_mul(int64_t T, int64_t d, astra_dtype_t dtype, int aligned16, astra_launch_info_t* info)
 {
     if (!info) return ASTRA_ERR_NULL;
-    const astra_status_t st = plan_silu(T, d, elem_bytes((int)dtype), aligned16 != 0, info);
+    const astra_status_t st = plan_silu(T, d, elem_bytes((int)dtype), plan_align(aligned16), info);
     return st == ASTRA_OK && !valid_dtype((int)dtype) ? ASTRA_ERR_DTYPE : st;
 }
 
@@ -384,7 +405,7 @@ astra_status_t astra_plan_merge_attn_states_lse(int64_t T, int64_t num_heads, in
                                                 int aligned16, astra_launch_info_t* info)
 {
     if (!info) return ASTRA_ERR_NULL;
-    const astra_status_t st = plan_merge(T, num_heads, head_dim, elem_bytes((int)dtype), aligned16 != 0, info);
+    const astra_status_t st = plan_merge(T, num_heads, head_dim, elem_bytes((int)dtype), plan_align(aligned16), info);
     return st == ASTRA_OK && !valid_dtype((int)dtype) ? ASTRA_ERR_DTYPE : st;
 }
 
@@ -393,9 +414,8 @@ static astra_status_t run_fused_add_rmsnorm(void* input, void* residual, const v
 {
     if (!input || !residual || !weight) return ASTRA_ERR_NULL;
     astra_launch_info_t li;
-    const bool a16 = aligned(input, 16) && aligned(residual, 16) && aligned(weight, 16);
     const int eb = elem_bytes((int)dtype);
-    astra_status_t st = plan_rmsnorm(T, H, eb, a16, &li, variant == ASTRA_VARIANT_TUNED);
+    astra_status_t st = plan_rmsnorm(T, H, eb, align_class(input, residual), &li, variant == ASTRA_VARIANT_TUNED, aligned(weight, 16));
     if (st != ASTRA_OK) return st;
     if (!valid_dtype((int)dtype)) return ASTRA_ERR_DTYPE;
     if (!(eps >= 0.0f)) return ASTRA_ERR_EPS;
@@ -442,7 +462,7 @@ static astra_status_t run_silu_and_mul(void* out, const void* input, int64_t T, 
     if (!out || !input) return ASTRA_ERR_NULL;
     astra_launch_info_t li;
     const int eb = elem_bytes((int)dtype);
-    astra_status_t st = plan_silu(T, d, eb, aligned(out, 16) && aligned(input, 16), &li);
+    astra_status_t st = plan_silu(T, d, eb, aligned(out, 16) && aligned(input, 16) ? kAlign16 : kAlignNone, &li);
     if (st != ASTRA_OK) return st;
     if (!valid_dtype((int)dtype)) return ASTRA_ERR_DTYPE;
     if (!aligned(out, eb) || !aligned(input, eb)) return ASTRA_ERR_ALIGN;
@@ -480,7 +500,7 @@ static astra_status_t run_merge_attn_states_lse(void* v_out, float* lse_out, con
     astra_launch_info_t li;
     const int eb = elem_bytes((int)dtype);
     astra_status_t st =
-        plan_merge(T, num_heads, head_dim, eb, aligned(v_out, 16) && aligned(v_a, 16) && aligned(v_b, 16), &li);
+        plan_merge(T, num_heads, head_dim, eb, align_class(v_out, v_a, v_b), &li);
     if (st != ASTRA_OK) return st;
     if (!valid_dtype((int)dtype)) return ASTRA_ERR_DTYPE;
     if (!aligned(v_out, eb) || !aligned(v_a, eb) || !aligned(v_b, eb) || !aligned(lse_out, 4) || !aligned(lse_a, 4) ||
@@ -533,7 +553,7 @@ astra_status_t astra_merge_attn_states_lse_kway(void* v_out, float* lse_out, con
     if (!v_out || !lse_out || !v_parts || !lse_parts) return ASTRA_ERR_NULL;
     astra_launch_info_t li;
     const int eb = elem_bytes((int)dtype);
-    astra_status_t st = plan_merge(T, num_heads, head_dim, eb, aligned(v_out, 16) && aligned(v_parts, 16), &li, true);
+    astra_status_t st = plan_merge(T, num_heads, head_dim, eb, aligned(v_out, 16) && aligned(v_parts, 16) ? kAlign16 : kAlignNone, &li, true);
     if (st != ASTRA_OK) return st;
     if (li.path == ASTRA_PATH_GENERIC) return ASTRA_ERR_SHAPE;  // more than 2^31 output vectors
     const int64_t pairs = T * num_heads;
@@ -563,10 +583,14 @@ astra_status_t astra_fused_add_rmsnorm_strided(void* y_out, int64_t y_stride, vo
     const int64_t strides[4] = {y_stride, r_out_stride, x_stride, r_stride};
     const void* const bases[4] = {y_out, r_out, x, r};
     const int eb = elem_bytes((int)dtype);
-    bool fast = aligned(weight, 16);
-    for (int i = 0; i < 4; ++i) fast = fast && aligned(bases[i], 16) && strides[i] % (kVecBytes / eb) == 0;
+    // every view on the 16-byte grid, or at least all four in step with each other in every row
+    int ac = align_class(y_out, r_out, x, r);
+    for (int i = 0; i < 4; ++i) {
+        if (ac == kAlign16 && strides[i] % (kVecBytes / eb) != 0) ac = kAlignPhased;
+        if ((strides[i] - strides[0]) % (kVecBytes / eb) != 0) ac = kAlignNone;
+    }
     astra_launch_info_t li;
-    astra_status_t st = plan_rmsnorm(T, H, eb, fast, &li);
+    astra_status_t st = plan_rmsnorm(T, H, eb, ac, &li, true, aligned(weight, 16));
     if (st != ASTRA_OK) return st;
     int64_t span[4];  // bounding extent of each view in bytes
     for (int i = 0; i < 4; ++i) {
@@ -603,7 +627,7 @@ astra_status_t astra_silu_and_mul_strided(void* out, int64_t out_stride, const v
     const int64_t ne = kVecBytes / eb;
     const bool fast = aligned(out, 16) && aligned(input, 16) && out_stride % ne == 0 && in_stride % ne == 0;
     astra_launch_info_t li;
-    astra_status_t st = plan_silu(T, d, eb, fast, &li, true);
+    astra_status_t st = plan_silu(T, d, eb, fast ? kAlign16 : kAlignNone, &li, true);
     if (st != ASTRA_OK) return st;
     if (li.path == ASTRA_PATH_GENERIC) return ASTRA_ERR_SHAPE;  // more than 2^31 output vectors
     int64_t out_rows, in_rows;
@@ -650,7 +674,7 @@ astra_status_t astra_merge_attn_states_lse_strided(void* v_out, int64_t out_toke
     bool fast = true;
     for (int i = 0; i < 3; ++i) fast = fast && aligned(bases[i], 16) && ts[i] % ne == 0 && hs[i] % ne == 0;
     astra_launch_info_t li;
-    astra_status_t st = plan_merge(T, num_heads, head_dim, eb, fast, &li, true);
+    astra_status_t st = plan_merge(T, num_heads, head_dim, eb, fast ? kAlign16 : kAlignNone, &li, true);
     if (st != ASTRA_OK) return st;
     if (li.path == ASTRA_PATH_GENERIC) return ASTRA_ERR_SHAPE;  // more than 2^31 output vectors
     int64_t span[3];  // bounding extent of each value view in bytes

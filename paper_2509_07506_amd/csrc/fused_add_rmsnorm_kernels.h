@@ -177,6 +177,133 @@ __global__ __launch_bounds__(256) void fused_add_rmsnorm_short_row_kernel(u32x4*
 }
 
 // ---------------------------------------------------------------------------------------------
+// Phased path: rows that do not start on the 16-byte grid (H no whole number of vectors, so the phase changes from row
+// to row, or pointers offset by some elements), with x, r, y_out and r_out all at the SAME phase in every row (the
+// host checks: pointers congruent modulo 16 bytes, row strides congruent modulo a vector -- true for every dense in
+// place call on 16-byte aligned tensors).  A row is cut into the 16-byte aligned chunks of memory it covers: lane c
+// owns chunk c, i.e. row elements [c*N - phase, c*N - phase + N), and moves it with aligned 16-byte accesses exactly
+// like the fast path.  The chunk at either end of the row can be partial (it also holds elements of the neighbouring
+// row, which another workgroup is updating).
+//
+// What decides the speed here is the NUMBER of memory instructions a workgroup issues, not their bytes: on MI355X a
+// streaming kernel pays about as much for a 2-byte store of one lane as for a 1 KiB store of a whole wave (measured:
+// T=16384, H=4096 one element off the grid -- 84 us with the partial chunks left out, 112-131 us with them loaded and
+// stored element by element or in 8/4/2-byte pieces, i.e. with 16-40 more instructions per row on top of 45).  So:
+//   * a partial chunk is LOADED whole, with the same instruction as every other chunk, and the positions outside the
+//     row are cleared in registers (they are bytes of the neighbouring row or, at the ends of a tensor, at most 14
+//     bytes outside it -- an aligned 16-byte access lies inside one page, so it cannot fault);
+//   * its elements are STORED by the first 16 lanes of the workgroup, one element per lane (lane j < N: position j of
+//     the first chunk, lane N + j: position j of the last chunk), so that the whole boundary costs one element-wide
+//     store instruction per output and one element-wide weight load: the two owner lanes hand the unrounded sums to
+//     those lanes through LDS (written before the reduction's barrier, read after it).
+// That is 3 memory instructions per row more than the fast path.  The weight is indexed by row position, so its
+// 16-byte loads are at element alignment (it is cache resident).  One workgroup per row in the XCD-aware order;
+// ROW_LOOP as in the row kernel; VPT chunks per lane; VPT * blockDim.x >= the most chunks a row can cover.
+template <int DT, int VPT, bool NTL, bool NTS, bool ROW_LOOP = false>
+__global__ __launch_bounds__(1024) void fused_add_rmsnorm_phased_row_kernel(
+    typename Storage<DT>::elem_t* y_out, typename Storage<DT>::elem_t* r_out, const typename Storage<DT>::elem_t* x,
+    const typename Storage<DT>::elem_t* r, const typename Storage<DT>::elem_t* __restrict__ weight, RowViews sv, int64_t T,
+    int64_t H, float inv_h, float eps, int log2_chunk)
+{
+    typedef typename Storage<DT>::elem_t E;
+    constexpr int N = Storage<DT>::kN;
+    __shared__ float partials[2][16];
+    __shared__ float edge[2][2 * N];  // unrounded sums of the first chunk [0, N) and of the last chunk [N, 2N)
+    const int nwaves = blockDim.x >> 6;
+    int parity = 0;
+    const int64_t first_row = xcd_chunked(blockIdx.x, log2_chunk);
+    if (first_row >= T) return;  // grid padding; uniform for the whole workgroup
+    const int len = (int)H;      // at most 4096 vectors
+
+    int64_t row = first_row;
+    do {
+        const E* xr = x + row * sv.x_stride;
+        const E* rr = r + row * sv.r_stride;
+        E* yr = y_out + row * sv.y_stride;
+        E* sr = r_out + row * sv.r_out_stride;
+        const int phase = phase_of<DT>(xr);           // the same for rr, yr and sr; uniform
+        const int last = (phase + len - 1) / N;       // index of the row's last chunk; uniform
+        const bool head_cut = phase != 0, tail_cut = (phase + len) % N != 0;
+
+        // the boundary elements' weights, one per lane of the first 16 (requested first, like the weight vectors)
+        const int j = (int)threadIdx.x;
+        const int edge_e = j < N ? j - phase : last * N - phase + (j - N);  // row element of this lane's boundary position
+        const bool edge_lane = j < 2 * N && edge_e >= 0 && edge_e < len && (j < N ? head_cut : tail_cut);  // H >= N: the two chunks differ
+        float edge_w = 0.0f;
+        if (edge_lane) edge_w = Storage<DT>::widen(weight[edge_e]);
+
+        u32x4 xa[VPT], ra[VPT], wa[VPT];
+        int e0[VPT];
+        bool whole[VPT], cut[VPT];
+#pragma unroll
+        for (int k = 0; k < VPT; ++k) {
+            const int c = (int)(threadIdx.x + k * blockDim.x);
+            e0[k] = c * N - phase;  // first row element of the chunk (negative for chunk 0 when phase > 0)
+            whole[k] = e0[k] >= 0 && e0[k] + N <= len;
+            cut[k] = !whole[k] && c <= last;
+            wa[k] = u32x4{0u, 0u, 0u, 0u};
+            if (whole[k]) wa[k] = load_vec_elem_aligned<DT, false>(weight + e0[k]);
+        }
+#pragma unroll
+        for (int k = 0; k < VPT; ++k) {
+            xa[k] = ra[k] = u32x4{0u, 0u, 0u, 0u};
+            if (whole[k] || cut[k]) {  // one aligned access, also for a partial chunk
+                xa[k] = load_vec<NTL>(reinterpret_cast<const u32x4*>(xr + e0[k]));
+                ra[k] = load_vec<NTL>(reinterpret_cast<const u32x4*>(rr + e0[k]));
+            }
+        }
+
+        float s[VPT][N];
+        float acc = 0.0f;
+#pragma unroll
+        for (int k = 0; k < VPT; ++k) {
+            float a[N], b[N];
+            unpack_vec<DT>(xa[k], a);
+            unpack_vec<DT>(ra[k], b);
+            if (cut[k]) {  // clear the positions that belong to the neighbouring row
+#pragma unroll
+                for (int e = 0; e < N; ++e) {
+                    const bool mine = e0[k] + e >= 0 && e0[k] + e < len;
+                    a[e] = mine ? a[e] : 0.0f;
+                    b[e] = mine ? b[e] : 0.0f;
+                }
+            }
+#pragma unroll
+            for (int e = 0; e < N; ++e) {
+                s[k][e] = a[e] + b[e];
+                acc += s[k][e] * s[k][e];
+            }
+            if (whole[k]) store_vec<NTS>(reinterpret_cast<u32x4*>(sr + e0[k]), pack_vec<DT>(s[k]));
+            if (cut[k]) {
+                float* slot = edge[parity] + (e0[k] < 0 ? 0 : N);  // first chunk, or last chunk
+#pragma unroll
+                for (int e = 0; e < N; ++e) slot[e] = s[k][e];
+            }
+        }
+        const float total = block_sum(acc, partials[parity], nwaves);
+        if (nwaves == 1) __syncthreads();  // block_sum has no barrier of its own then; the boundary sums pass through LDS
+        const float scale = rsqrt_full_range(total * inv_h + eps);
+#pragma unroll
+        for (int k = 0; k < VPT; ++k) {
+            if (whole[k]) {
+                float w[N], y[N];
+                unpack_vec<DT>(wa[k], w);
+#pragma unroll
+                for (int e = 0; e < N; ++e) y[e] = (s[k][e] * scale) * w[e];
+                store_vec<NTS>(reinterpret_cast<u32x4*>(yr + e0[k]), pack_vec<DT>(y));
+            }
+        }
+        if (edge_lane) {  // the boundary elements, one per lane: a single store instruction per output
+            const float se = edge[parity][j];
+            sr[edge_e] = Storage<DT>::narrow(se);
+            yr[edge_e] = Storage<DT>::narrow((se * scale) * edge_w);
+        }
+        row += gridDim.x;
+        parity ^= 1;
+    } while (ROW_LOOP && row < T);
+}
+
+// ---------------------------------------------------------------------------------------------
 // Ragged path: any H of 1 to 4096 whole vectors plus (TAIL) a tail of fewer than N elements, pointers and row strides
 // only element aligned; in place (y_out = x, r_out = r, strides H) or out of place.  One workgroup per row in the
 // XCD-aware order, rows gridDim.x apart, the whole vectors in registers as in the row kernel above, as 16-byte

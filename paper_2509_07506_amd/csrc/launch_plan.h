@@ -73,6 +73,22 @@ inline bool overlaps(const void* p, int64_t n, const void* q, int64_t m)
     return n > 0 && m > 0 && a < b + (uintptr_t)m && b < a + (uintptr_t)n;
 }
 
+// How the tensor pointers of a call sit on the 16-byte grid (the `aligned16` argument of the plan functions):
+//   kAlignNone   element alignment only, the tensors' offsets into the grid unrelated
+//   kAlign16     every pointer (and row stride) a multiple of 16 bytes
+//   kAlignPhased the activation tensors congruent modulo 16 bytes (and their row strides congruent modulo a vector):
+//                they share one phase in every row, so they can be cut into the same aligned chunks
+enum : int { kAlignNone = 0, kAlign16 = 1, kAlignPhased = 2 };
+
+template <class... P>
+inline int align_class(const void* first, P... rest)
+{
+    const uintptr_t ph = reinterpret_cast<uintptr_t>(first) & 15u;
+    bool same = true;
+    for (const void* p : {static_cast<const void*>(rest)...}) same = same && ((reinterpret_cast<uintptr_t>(p) & 15u) == ph);
+    return !same ? kAlignNone : (ph == 0 ? kAlign16 : kAlignPhased);
+}
+
 inline bool valid_dtype(int dt) { return dt == ASTRA_F16 || dt == ASTRA_BF16 || dt == ASTRA_F32; }
 
 // bytes per storage element; anything that is not binary32 counts as 16-bit so that shape checks, which come
@@ -95,7 +111,7 @@ inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
 inline astra_launch_info_t launch_info(int path, int block, int vpt, int lc, int64_t grid, int pace, int rows_per_block,
                                        int access_bytes = -1, int non_temporal = -1)
 {
-    const bool wide = (path == ASTRA_PATH_VECTOR || path == ASTRA_PATH_RAGGED);
+    const bool wide = (path == ASTRA_PATH_VECTOR || path == ASTRA_PATH_RAGGED || path == ASTRA_PATH_PHASED);
     astra_launch_info_t li;
     li.path = path;
     li.block = block;
@@ -239,9 +255,11 @@ constexpr int64_t kShortRowVecs = 32;
 inline int short_row_group(int64_t hv) { return hv <= 8 ? 8 : hv <= 16 ? 16 : 32; }
 
 // `short_rows`: the caller can launch the short-row kernel (the ablation variants, which restage the row kernel, cannot)
-inline astra_status_t plan_rmsnorm(int64_t T, int64_t H, int eb, bool aligned16, astra_launch_info_t* info,
-                                   bool short_rows = true)
+inline astra_status_t plan_rmsnorm(int64_t T, int64_t H, int eb, int align, astra_launch_info_t* info,
+                                   bool short_rows = true, bool weight16 = true)
 {
+    // the fast path also needs the weight on the 16-byte grid; the phased path does not
+    const bool aligned16 = (align == kAlign16) && weight16;
     const int64_t ne = kVecBytes / eb;  // elements per 16-byte vector
     int64_t n;
     if (T < 0 || H <= 0 || mul_overflows(T, H, &n) || n > std::numeric_limits<int64_t>::max() / 4) return ASTRA_ERR_SHAPE;
@@ -260,6 +278,12 @@ inline astra_status_t plan_rmsnorm(int64_t T, int64_t H, int eb, bool aligned16,
         const int lc = fit_chunk_log2(rows, kRowChunkBytesLog2 - floor_log2(H * eb), kRowChunkMinRows);
         if (T >= kMaxRowGrid) pace = kPaceNone;  // the row-loop kernel is not paced
         *info = launch_info(ASTRA_PATH_VECTOR, rp.block, rp.vpt, lc, T < kMaxRowGrid ? pad_grid(rows, lc) : rows, pace, 0);
+    } else if (align != kAlignNone && H >= ne && rmsnorm_row_plan((H + 2 * ne - 2) / ne, &rp)) {
+        // rows or pointers off the 16-byte grid, but x, r and the outputs in step with each other: lanes own the aligned
+        // chunks of memory a row covers, at most floor((H + 2N - 2) / N) of them (fused_add_rmsnorm_phased_row_kernel)
+        const int64_t rows = T < kMaxRowGrid ? T : kMaxRowGrid;
+        const int lc = fit_chunk_log2(rows, kRowChunkBytesLog2 - floor_log2(H * eb), kRowChunkMinRows);
+        *info = launch_info(ASTRA_PATH_PHASED, rp.block, rp.vpt, lc, T < kMaxRowGrid ? pad_grid(rows, lc) : rows, 0, 0);
     } else if (H >= ne && rmsnorm_row_plan(H / ne, &rp)) {
         // rows that are no whole number of vectors, or pointers that are only element aligned: the row still lives in
         // registers, with 16-byte accesses at element alignment; lanes for the whole vectors (at least one), the tail
@@ -296,8 +320,9 @@ inline int flat_block(int64_t vecs)
 }
 
 // `wide_only`: the caller's kernel exists with 256-lane workgroups only (strided views)
-inline astra_status_t plan_silu(int64_t T, int64_t d, int eb, bool aligned16, astra_launch_info_t* info, bool wide_only = false)
+inline astra_status_t plan_silu(int64_t T, int64_t d, int eb, int align, astra_launch_info_t* info, bool wide_only = false)
 {
+    const bool aligned16 = (align == kAlign16);  // x and g sit d elements apart: no common phase when d is no whole number of vectors
     const int64_t ne = kVecBytes / eb;
     int64_t two_d, n;
     if (T < 0 || d <= 0 || mul_overflows(d, 2, &two_d) || mul_overflows(T, two_d, &n) ||
@@ -326,9 +351,10 @@ inline astra_status_t plan_silu(int64_t T, int64_t d, int eb, bool aligned16, as
 }
 
 // `wide_only`: the caller's kernel exists with 256-lane workgroups only (strided views, K-way merge)
-inline astra_status_t plan_merge(int64_t T, int64_t NH, int64_t D, int eb, bool aligned16, astra_launch_info_t* info,
+inline astra_status_t plan_merge(int64_t T, int64_t NH, int64_t D, int eb, int align, astra_launch_info_t* info,
                                  bool wide_only = false)
 {
+    const bool aligned16 = (align == kAlign16);
     const int64_t ne = kVecBytes / eb;
     int64_t pairs, n;
     if (T < 0 || NH <= 0 || D <= 0 || mul_overflows(T, NH, &pairs) || mul_overflows(pairs, D, &n) ||
@@ -344,6 +370,12 @@ inline astra_status_t plan_merge(int64_t T, int64_t NH, int64_t D, int eb, bool 
         const int lc = fit_chunk_log2(blocks, kFlatChunkLog2, kFlatChunkMinBlocks * (256 / block));
         *info = launch_info(ASTRA_PATH_VECTOR, block, kMergeUnroll, lc, pad_grid(blocks, lc), 0, 0, kVecBytes,
                             !wide_only && pairs * dvec < kSmallFlatVecs ? 0 : 1);
+    } else if (!wide_only && align != kAlignNone && D >= ne && n < (int64_t(1) << 32)) {
+        // head_dim or pointers off the 16-byte grid, the three dense value tensors in step with each other: one lane per
+        // aligned chunk of the flat tensors, at most one more chunk than whole vectors (merge_attn_states_lse_phased_kernel)
+        const int64_t blocks = ((n + ne - 1) / ne + 1 + 255) / 256;
+        const int lc = fit_chunk_log2(blocks, kFlatChunkLog2, kFlatChunkMinBlocks);
+        *info = launch_info(ASTRA_PATH_PHASED, 256, 1, lc, pad_grid(blocks, lc), 0, 0);
     } else if (pairs * ((D + ne - 1) / ne) <= kMaxVecIndex) {
         *info = launch_info(ASTRA_PATH_RAGGED, 256, 1, 0, (pairs * ((D + ne - 1) / ne) + 255) / 256, 0, 0);
     } else {

@@ -164,6 +164,51 @@ __global__ __launch_bounds__(256) void merge_attn_states_lse_ragged_kernel(
     if (jv == 0) lse_out[pair] = w.lse;
 }
 
+// Phased path: head_dim no whole number of vectors (or pointers offset by some elements), with v_a, v_b and v_out dense
+// and congruent modulo 16 bytes, and head_dim >= N.  The three value tensors are then flat arrays at one common phase,
+// and the work is the list of 16-byte aligned chunks of memory they cover: lane c owns flat elements
+// [c*N - phase, c*N - phase + N), moved with aligned 16-byte accesses exactly like the fast path; only the first and
+// the last chunk of the whole tensor can be partial (element by element).  A chunk can straddle the end of a (token,
+// head) pair -- at most one, since head_dim >= N -- so a lane evaluates the weights of the pair of its first and of
+// its last element and takes, per element, those of the pair the element belongs to; the lane that holds a pair's
+// first element stores that pair's S_out.  (An unaligned 16-byte access per lane, as in the ragged kernel above,
+// costs 25-30 % of the streaming rate on MI355X.)
+template <int DT, bool NTL, bool NTS>
+__global__ __launch_bounds__(256) void merge_attn_states_lse_phased_kernel(
+    typename Storage<DT>::elem_t* v_out, float* lse_out, const typename Storage<DT>::elem_t* v_a, const float* lse_a,
+    const typename Storage<DT>::elem_t* v_b, const float* lse_b, uint32_t n_elems, uint32_t D, FastDiv by_D,
+    uint32_t total_chunks, int phase, int log2_chunk)
+{
+    constexpr int N = Storage<DT>::kN;
+    const uint32_t c = xcd_chunked(blockIdx.x, log2_chunk) * 256u + threadIdx.x;
+    if (c >= total_chunks) return;
+    const int64_t e0 = (int64_t)c * N - phase;  // first flat element of the chunk; negative only for chunk 0
+    const bool whole = e0 >= 0 && e0 + N <= (int64_t)n_elems;
+    const uint32_t first = e0 < 0 ? 0u : (uint32_t)e0;
+    const uint32_t last = e0 + N <= (int64_t)n_elems ? (uint32_t)(e0 + N - 1) : n_elems - 1u;
+    const uint32_t p0 = by_D.div(first), p1 = by_D.div(last);
+    u32x4 av, bv;
+    if (whole) {
+        av = load_vec<NTL>(reinterpret_cast<const u32x4*>(v_a + e0));
+        bv = load_vec<NTL>(reinterpret_cast<const u32x4*>(v_b + e0));
+    } else {
+        av = load_chunk_partial<DT>(v_a, n_elems, e0);
+        bv = load_chunk_partial<DT>(v_b, n_elems, e0);
+    }
+    const MergeWeights w0 = merge_weights(lse_a[p0], lse_b[p0]);
+    const MergeWeights w1 = merge_weights(lse_a[p1], lse_b[p1]);
+    const int64_t turn = (int64_t)(p0 + 1u) * D - e0;  // chunk positions from `turn` on belong to pair p1
+    float a[N], b[N], o[N];
+    unpack_vec<DT>(av, a);
+    unpack_vec<DT>(bv, b);
+#pragma unroll
+    for (int i = 0; i < N; ++i) o[i] = blend(i < turn ? w0 : w1, a[i], b[i]);
+    if (whole) store_vec<NTS>(reinterpret_cast<u32x4*>(v_out + e0), pack_vec<DT>(o));
+    else store_chunk_partial<DT>(v_out, n_elems, e0, o);
+    if (first == p0 * D) lse_out[p0] = w0.lse;  // the chunk holds the first element of pair p0 ...
+    if (p1 != p0) lse_out[p1] = w1.lse;         // ... and that of p1 whenever it reaches into p1
+}
+
 // Element-wise path (inputs too large for the ragged kernel's 32-bit vector index): one block per (token, head) pair.
 template <int DT>
 __global__ __launch_bounds__(256) void merge_attn_states_lse_generic_kernel(typename Storage<DT>::elem_t* v_out, float* lse_out,

@@ -166,18 +166,30 @@ def test_rmsnorm_plans(A):
         assert lc == 0 or (T >= (64 << lc) and T >= 1024)              # small grids keep the plain launch order
         if T >= 4096:
             assert 128 * 1024 <= (H * 2) << lc <= 512 * 1024           # about 256 KiB per XCD run
-    # rows that are no whole number of vectors, pointers that are only element aligned: ragged path, row in registers
-    # (lanes for the whole vectors; the tail of fewer than 8 elements rides in the last lane)
-    assert plan(4, 4100) == {"path": "ragged", "block": 512, "vectors_per_lane": 1, "log2_xcd_chunk": 0, "grid": 4, "pace": 0}
-    assert plan(4, 4096, al=False)["path"] == "ragged" and plan(9, 32767)["path"] == "ragged" and plan(3, 8)["path"] == "vector" and plan(3, 9)["path"] == "ragged"
-    assert plan(3, 1)["path"] == "generic" and plan(3, 7)["path"] == "generic"          # not one whole vector in a row
-    assert plan(4, 11009)["vectors_per_lane"] == 2 and plan(4, 32767)["vectors_per_lane"] == 4
-    assert plan(1 << 22, 100) == {"path": "ragged", "block": 64, "vectors_per_lane": 1, "log2_xcd_chunk": 8, "grid": 1 << 21,
-                                  "pace": 0}
+    # rows that are no whole number of vectors on tensors that are in step with each other (16-byte aligned, al=1, or all
+    # offset alike, al=2): phased path -- lanes own the aligned chunks a row covers, at most floor((H + 14) / 8)
+    assert plan(4, 4100) == {"path": "phased", "block": 576, "vectors_per_lane": 1, "log2_xcd_chunk": 0, "grid": 4, "pace": 0}
+    assert plan(4, 4096, al=2) == {"path": "phased", "block": 576, "vectors_per_lane": 1, "log2_xcd_chunk": 0, "grid": 4, "pace": 0}
+    assert plan(9, 32750)["path"] == "phased" and plan(3, 8)["path"] == "vector" and plan(3, 9)["path"] == "phased"
+    assert plan(3, 8, al=2)["path"] == "phased" and plan(4, 8185)["block"] == 1024 and plan(4, 8186)["vectors_per_lane"] == 2
+    assert plan(4, 32761)["path"] == "phased" and plan(4, 32762)["path"] == "ragged"       # one chunk more than 4096: old form
     p = plan(4099, 5124)
+    assert p["path"] == "phased" and p["log2_xcd_chunk"] == 5 and p["grid"] == 4352 and p["block"] == 704
+    # tensors at unrelated offsets into the 16-byte grid (al=0): ragged path, row in registers (lanes for the whole
+    # vectors; the tail of fewer than 8 elements rides in the last lane)
+    assert plan(4, 4100, al=0) == {"path": "ragged", "block": 512, "vectors_per_lane": 1, "log2_xcd_chunk": 0, "grid": 4, "pace": 0}
+    assert plan(4, 4096, al=0)["path"] == "ragged" and plan(9, 32767, al=0)["path"] == "ragged" and plan(3, 9, al=0)["path"] == "ragged"
+    assert plan(3, 8, al=0)["path"] == "ragged"
+    for al in (0, 1, 2):
+        assert plan(3, 1, al)["path"] == "generic" and plan(3, 7, al)["path"] == "generic"      # not one whole vector in a row
+        assert plan(4, 65536 + (al != 1), al)["path"] == "generic" and plan(4, 32776, al)["path"] == "generic"   # more than 4096 vectors
+    assert plan(4, 11009, al=0)["vectors_per_lane"] == 2 and plan(4, 32767, al=0)["vectors_per_lane"] == 4
+    assert plan(1 << 22, 100, al=0) == {"path": "ragged", "block": 64, "vectors_per_lane": 1, "log2_xcd_chunk": 8, "grid": 1 << 21,
+                                        "pace": 0}
+    assert plan(1 << 22, 100)["path"] == "phased" and plan(1 << 22, 100)["grid"] == 1 << 21
+    p = plan(4099, 5124, al=0)
     assert p["path"] == "ragged" and p["log2_xcd_chunk"] == 5 and p["grid"] == 4352 and p["block"] == 640
-    assert plan(4, 32775)["path"] == "ragged" and plan(4, 8199)["vectors_per_lane"] == 1
-    assert plan(4, 65536)["path"] == "generic" and plan(4, 32776)["path"] == "generic"   # more than 4096 vectors
+    assert plan(4, 32775, al=0)["path"] == "ragged" and plan(4, 8199, al=0)["vectors_per_lane"] == 1
     big = plan(1 << 23, 264)                                           # row loop beyond the grid limit
     assert big["grid"] == 1 << 21 and big["grid"] % (8 << big["log2_xcd_chunk"]) == 0
     # rows of at most 32 vectors share a workgroup: 8, 16 or 32 lanes per row, 256-lane workgroups
@@ -185,7 +197,7 @@ def test_rmsnorm_plans(A):
                                  "pace": 0, "rows_per_block": 32}
     assert plan(1000, 128)["rows_per_block"] == 16 and plan(1000, 128)["grid"] == 63 and plan(1000, 136)["rows_per_block"] == 8
     assert plan(5, 256)["rows_per_block"] == 8 and plan(5, 256)["grid"] == 1 and "rows_per_block" not in plan(5, 264)
-    assert "rows_per_block" not in plan(5, 260) and plan(5, 260)["path"] == "ragged"
+    assert "rows_per_block" not in plan(5, 260) and plan(5, 260)["path"] == "phased" and plan(5, 260, al=0)["path"] == "ragged"
     assert plan(1 << 26, 8)["rows_per_block"] == 32 and plan(1 << 26, 8)["grid"] == 1 << 21
     assert "rows_per_block" not in plan((1 << 26) + 1, 8) and plan((1 << 26) + 1, 8)["block"] == 64   # beyond the grid limit: row loop
     assert A.astra_plan_fused_add_rmsnorm(-1, 8, True)[0] == 2
@@ -235,7 +247,8 @@ def test_binary32_plans(A):
     for T, H in [(1, 8192), (600, 8192), (64, 16384), (4099, 5120)]:
         p = A.astra_plan_fused_add_rmsnorm(T, H, True, dtype=F32)[1].as_dict()
         assert p["path"] == "vector" and p["block"] * p["vectors_per_lane"] * 4 >= H and p["block"] <= 1024
-    assert A.astra_plan_fused_add_rmsnorm(4, 4098, True, dtype=F32)[1].as_dict()["path"] == "ragged"    # H % 4 != 0
+    assert A.astra_plan_fused_add_rmsnorm(4, 4098, True, dtype=F32)[1].as_dict()["path"] == "phased"    # H % 4 != 0
+    assert A.astra_plan_fused_add_rmsnorm(4, 4098, 0, dtype=F32)[1].as_dict()["path"] == "ragged"
     assert A.astra_plan_fused_add_rmsnorm(4, 4100, True, dtype=F32)[1].as_dict()["path"] == "vector"    # H % 4 == 0
     assert A.astra_plan_fused_add_rmsnorm(4, 32768, True, dtype=F32)[1].as_dict()["path"] == "generic"  # > 4096 vectors
     s = A.astra_plan_silu_and_mul(4096, 14336, True, dtype=F32)[1].as_dict()
@@ -244,7 +257,9 @@ def test_binary32_plans(A):
     assert A.astra_plan_silu_and_mul(3, 1412, True, dtype=F32)[1].as_dict()["path"] == "vector"
     m = A.astra_plan_merge_attn_states_lse(4096, 32, 128, True, dtype=F32)[1].as_dict()
     assert m["path"] == "vector" and m["block"] == 64 and m["grid"] * m["block"] == 4096 * 32 * 32
-    assert A.astra_plan_merge_attn_states_lse(3, 5, 6, True, dtype=F32)[1].as_dict()["path"] == "ragged"
+    assert A.astra_plan_merge_attn_states_lse(3, 5, 6, True, dtype=F32)[1].as_dict()["path"] == "phased"
+    assert A.astra_plan_merge_attn_states_lse(3, 5, 6, 0, dtype=F32)[1].as_dict()["path"] == "ragged"
+    assert A.astra_plan_merge_attn_states_lse(3, 5, 3, True, dtype=F32)[1].as_dict()["path"] == "ragged"     # head_dim under one vector
     assert A.astra_plan_merge_attn_states_lse(3, 5, 4, True, dtype=F32)[1].as_dict()["path"] == "vector"
     assert A.astra_plan_merge_attn_states_lse(3, 5, 4, True, dtype=7)[0] == 3
     assert A.astra_plan_merge_attn_states_lse(-3, 5, 4, True, dtype=7)[0] == 2                          # shape before dtype
@@ -287,8 +302,13 @@ def test_silu_and_merge_plans(A):
     for T, block, nt in [(1, 256, 0), (16, 256, 0), (63, 128, 0), (64, 128, 1), (200, 256, 1), (1024, 256, 1), (2048, 64, 1), (32768, 64, 1)]:
         q = A.astra_plan_merge_attn_states_lse(T, 32, 128, True)[1].as_dict()
         assert q["block"] == block and q.get("non_temporal", 1) == nt and "access_bytes" not in q, (T, q)
-    assert A.astra_plan_merge_attn_states_lse(3, 5, 4, True)[1].as_dict()["path"] == "ragged"
+    assert A.astra_plan_merge_attn_states_lse(3, 5, 4, True)[1].as_dict()["path"] == "ragged"                 # head_dim under one vector
     assert A.astra_plan_merge_attn_states_lse(3, 5, 72, False)[1].as_dict()["path"] == "ragged"
+    # head_dim or pointers off the 16-byte grid, value tensors in step with each other: aligned chunks of the flat tensors
+    q = A.astra_plan_merge_attn_states_lse(257, 40, 129, True)[1].as_dict()
+    assert q["path"] == "phased" and q["block"] == 256 and q["grid"] * 256 >= (257 * 40 * 129 + 7) // 8 + 1
+    assert A.astra_plan_merge_attn_states_lse(3, 5, 72, 2)[1].as_dict()["path"] == "phased"
+    assert A.astra_plan_merge_attn_states_lse(1 << 16, 512, 129, True)[1].as_dict()["path"] == "ragged"       # 2^32 elements and more
     assert A.astra_plan_merge_attn_states_lse(1 << 24, 64, 129, True)[1].as_dict()["path"] == "generic"   # 2^30 * 17 vectors
     assert A.astra_plan_merge_attn_states_lse(3, 5, 72, True)[1].as_dict()["path"] == "vector"
     assert A.astra_plan_merge_attn_states_lse(0, 5, 72, True)[1].as_dict()["path"] == "none"

@@ -63,11 +63,11 @@ def check_rmsnorm(A, x, r, w, eps, what):
                                  (1000, 32), (333, 68), (50, 128),             # short rows: several rows per workgroup
                                  (9, 16384), (520, 11008), (1024, 4096), (1050, 2048), (1030, 6144),  # last three: paced grids
                                  (2, 32768),                                     # beyond 4096 vectors: element-wise path
-                                 (7, 4099), (3, 6), (300, 2050)])                # H % 4 != 0: ragged path
+                                 (7, 4099), (3, 6), (300, 2050)])                # H % 4 != 0: phased path (aligned chunks)
 def test_rmsnorm_tiles(A, T, H):
     plan = A.astra_plan_fused_add_rmsnorm(T, H, True, dtype=A.ASTRA_F32)[1].as_dict()
     _say(f"[f32] rmsnorm T={T} H={H} plan={plan}")
-    assert plan["path"] == ("generic" if H > 16384 or H < 4 else "vector" if H % 4 == 0 else "ragged")
+    assert plan["path"] == ("generic" if H > 16384 or H < 4 else "vector" if H % 4 == 0 else "phased")
     x, r, w = workloads.rmsnorm_inputs(T, H, DT, _rng(1, T, H), r_std=2.0)
     check_rmsnorm(A, x, r, w, 1e-5, f"rmsnorm f32 T={T} H={H}")
 
@@ -135,7 +135,7 @@ def run_merge(A, va, la, vb, lb):
 def test_merge_tiles(A, T, NH, D):
     plan = A.astra_plan_merge_attn_states_lse(T, NH, D, True, dtype=A.ASTRA_F32)[1].as_dict()
     _say(f"[f32] merge T={T} NH={NH} D={D} plan={plan}")
-    assert plan["path"] == ("vector" if D % 4 == 0 else "ragged")
+    assert plan["path"] == ("vector" if D % 4 == 0 else "phased" if D >= 4 else "ragged")
     va, la, vb, lb = workloads.merge_inputs(T, NH, D, DT, _rng(4, T, NH, D), empty_p=0.1)
     vo, lo = run_merge(A, va, la, vb, lb)
     vo_ref, lo_ref = O.merge_attn_states_lse_f32(va, la, vb, lb)

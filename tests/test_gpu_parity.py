@@ -210,9 +210,9 @@ def test_rmsnorm_ragged_and_generic_paths_and_canaries(A, T, H, off, dt):
     xd, xw = padded(x, dt, offset_elems=off)
     rd, rw = padded(r, dt, offset_elems=off)
     wd, ww = padded(w, dt, offset_elems=off)
-    aligned = all(t.data_ptr() % 16 == 0 for t in (xd, rd, wd))
-    st, info = A.astra_plan_fused_add_rmsnorm(T, H, aligned)
-    assert info.as_dict()["path"] == ("ragged" if 1 <= H // 8 <= 4096 else "generic")
+    # x and r carry the same offset, so they are in step with each other: the phased kernel (aligned chunks)
+    st, info = A.astra_plan_fused_add_rmsnorm(T, H, 1 if off == 0 else 2)
+    assert info.as_dict()["path"] == ("generic" if H < 8 or H // 8 > 4096 else "phased" if (H + 14) // 8 <= 4096 else "ragged")
     A.fused_add_rmsnorm(xd, rd, wd, 1e-5)
     torch.cuda.synchronize()
     y_ref, res_ref = O.fused_add_rmsnorm(x, r, w, 1e-5, dt)
@@ -220,6 +220,27 @@ def test_rmsnorm_ragged_and_generic_paths_and_canaries(A, T, H, off, dt):
     assert_storage_close(to_bits(xd), y_ref, dt, "normalised output")
     assert canaries_intact(xw, x.size, offset_elems=off) and canaries_intact(rw, r.size, offset_elems=off)
     assert canaries_intact(ww, w.size, offset_elems=off) and np.array_equal(to_bits(wd), w)
+
+
+@pytest.mark.parametrize("dt", ["bf16", "f16"])
+@pytest.mark.parametrize("T,H,offs", [(3, 4100, (0, 1, 0)), (5, 4096, (1, 0, 0)), (4, 4097, (3, 6, 1)), (300, 5124, (2, 5, 7)),
+                                      (7, 9, (0, 4, 0)), (257, 11009, (1, 2, 3)), (33, 32767, (7, 0, 2)), (600, 16383, (4, 0, 0)),
+                                      (1030, 2056, (0, 0, 3)), (3, 8, (1, 2, 0))])
+def test_rmsnorm_tensors_at_unrelated_offsets(A, T, H, offs, dt):
+    """x, r and the weight each at an offset of its own into the 16-byte grid: the ragged kernel (16-byte accesses at
+    element alignment) when x and r are out of step, the phased one with an offset weight when only the weight is."""
+    _say(f"[parity] rmsnorm mixed offsets T={T} H={H} offsets={offs} {dt}")
+    x, r, w = workloads.rmsnorm_inputs(T, H, dt, np.random.default_rng([14, T, H]), r_std=2.0)
+    xd, xw = padded(x, dt, offset_elems=offs[0])
+    rd, rw = padded(r, dt, offset_elems=offs[1])
+    wd, ww = padded(w, dt, offset_elems=offs[2])
+    A.fused_add_rmsnorm(xd, rd, wd, 1e-5)
+    torch.cuda.synchronize()
+    y_ref, res_ref = O.fused_add_rmsnorm(x, r, w, 1e-5, dt)
+    assert_bits_equal(to_bits(rd), res_ref, "residual (bit-exact)")
+    assert_storage_close(to_bits(xd), y_ref, dt, "normalised output")
+    assert canaries_intact(xw, x.size, offset_elems=offs[0]) and canaries_intact(rw, r.size, offset_elems=offs[1])
+    assert canaries_intact(ww, w.size, offset_elems=offs[2]) and np.array_equal(to_bits(wd), w)
 
 
 @pytest.mark.parametrize("dt", ["bf16", "f16"])
@@ -278,6 +299,59 @@ def test_merge_paths_and_canaries(A, T, NH, D, off, dt):
     edge = lo_whole.cpu().numpy()
     assert np.all(edge[:pad] == 1234.5) and np.all(edge[pad + T * NH:] == 1234.5)
     assert np.array_equal(to_bits(vad), va) and np.array_equal(to_bits(vbd), vb)
+
+
+@pytest.mark.parametrize("dt", ["bf16", "f16"])
+@pytest.mark.parametrize("T,NH,D,offs", [(3, 5, 100, (0, 1, 0)), (65, 40, 128, (1, 0, 0)), (257, 40, 129, (2, 5, 7)), (33, 5, 9, (0, 0, 3)),
+                                         (100, 7, 132, (4, 4, 0)), (9, 3, 8, (1, 1, 2))])
+def test_merge_tensors_at_unrelated_offsets(A, T, NH, D, offs, dt):
+    """v_a, v_b and v_out each at an offset of its own into the 16-byte grid: the ragged kernel"""
+    _say(f"[parity] merge mixed offsets T={T} NH={NH} D={D} offsets={offs} {dt}")
+    va, la, vb, lb = workloads.merge_inputs(T, NH, D, dt, np.random.default_rng([15, T, NH, D]), empty_p=0.15)
+    vad, vaw = padded(va, dt, offset_elems=offs[0])
+    vbd, vbw = padded(vb, dt, offset_elems=offs[1])
+    vod, vow = padded(np.full(va.shape, 0x1234, np.uint16), dt, offset_elems=offs[2])
+    lad, lbd = torch.from_numpy(la).cuda(), torch.from_numpy(lb).cuda()
+    lod = torch.empty_like(lad)
+    A.merge_attn_states_lse(vod, lod, vad, lad, vbd, lbd)
+    torch.cuda.synchronize()
+    vo_ref, lo_ref = O.merge_attn_states_lse(va, la, vb, lb, dt)
+    assert_storage_close(to_bits(vod), vo_ref, dt, "v_out")
+    assert_lse_close(lod.cpu().numpy(), lo_ref, "lse_out")
+    assert canaries_intact(vow, va.size, offset_elems=offs[2])
+    assert np.array_equal(to_bits(vad), va) and np.array_equal(to_bits(vbd), vb)
+
+
+@pytest.mark.parametrize("dt", ["bf16", "f16"])
+@pytest.mark.parametrize("T,NH,D,off", [(1, 1, 8, 1), (1, 1, 9, 0), (2, 3, 15, 7), (1000, 8, 129, 0), (4099, 40, 65, 3), (300, 5, 1000, 5),
+                                        (64, 4, 257, 0), (7, 1, 2049, 2)])
+def test_merge_phased_path_pair_boundaries(A, T, NH, D, off, dt):
+    """the phased kernel's chunks straddle pair boundaries at every position; S_out must come from the right lane, and
+    empty pairs next to live ones must not bleed into each other"""
+    _say(f"[parity] merge phased T={T} NH={NH} D={D} offset={off} {dt}")
+    st, info = A.astra_plan_merge_attn_states_lse(T, NH, D, 1 if off == 0 else 2)
+    assert info.as_dict()["path"] == ("phased" if (D % 8 or off) else "vector")
+    va, la, vb, lb = workloads.merge_inputs(T, NH, D, dt, np.random.default_rng([16, T, NH, D]), empty_p=0.3)
+    vad, vaw = padded(va, dt, offset_elems=off)
+    vbd, vbw = padded(vb, dt, offset_elems=off)
+    vod, vow = padded(np.full(va.shape, 0x1234, np.uint16), dt, offset_elems=off)
+    pad = 16
+    lo_whole = torch.full((pad + T * NH + pad,), 1234.5, dtype=torch.float32, device="cuda")
+    lod = lo_whole[pad:pad + T * NH].view(T, NH)
+    lad, lbd = torch.from_numpy(la).cuda(), torch.from_numpy(lb).cuda()
+    A.merge_attn_states_lse(vod, lod, vad, lad, vbd, lbd)
+    torch.cuda.synchronize()
+    vo_ref, lo_ref = O.merge_attn_states_lse(va, la, vb, lb, dt)
+    assert_storage_close(to_bits(vod), vo_ref, dt, "v_out")
+    assert_lse_close(lod.cpu().numpy(), lo_ref, "lse_out")
+    assert canaries_intact(vow, va.size, offset_elems=off)
+    edge = lo_whole.cpu().numpy()
+    assert np.all(edge[:pad] == 1234.5) and np.all(edge[pad + T * NH:] == 1234.5)
+    # in place on v_a
+    A.merge_attn_states_lse(vad, lod, vad, lad, vbd, lbd)
+    torch.cuda.synchronize()
+    assert_storage_close(to_bits(vad), vo_ref, dt, "v_out in place on v_a")
+    assert canaries_intact(vaw, va.size, offset_elems=off)
 
 
 # ---------------------------------------------------------------------------------------------------
@@ -576,7 +650,7 @@ def test_rmsnorm_beyond_2_31_elements(A):
     assert _all_tiles_equal(xd, B) and _all_tiles_equal(rd, B), "rows beyond the first tile differ"
 
 
-@pytest.mark.parametrize("H,path", [(264, "vector"), (12, "ragged")])
+@pytest.mark.parametrize("H,path", [(264, "vector"), (12, "phased")])
 def test_rmsnorm_more_rows_than_the_grid_limit(A, H, path):
     dt, B = "f16", 256
     T = (1 << 21) + 259                                   # the row kernels launch at most 2^21 workgroups
