@@ -41,7 +41,12 @@ extern "C" {
 /* Same declaration as in the HIP runtime headers; repeating a typedef is legal in C11 and C++. */
 typedef struct ihipStream_t* hipStream_t;
 
-typedef enum { ASTRA_F16 = 0, ASTRA_BF16 = 1, ASTRA_F32 = 2 } astra_dtype_t;
+/* Every enumeration of this interface also lists the two ends of the 32-bit integer range.  They are not values to
+ * pass: they make every int a representable value of the type, so that a call with an unknown code is a well-defined
+ * input in C and in C++ alike, which the library answers with an error code. */
+#define ASTRA_ENUM_SPANS_INT32(prefix) prefix##_INT32_MIN_ = -0x7fffffff - 1, prefix##_INT32_MAX_ = 0x7fffffff
+
+typedef enum { ASTRA_F16 = 0, ASTRA_BF16 = 1, ASTRA_F32 = 2, ASTRA_ENUM_SPANS_INT32(ASTRA_DTYPE) } astra_dtype_t;
 
 typedef enum {
     ASTRA_OK = 0,
@@ -52,7 +57,8 @@ typedef enum {
     ASTRA_ERR_ALIGN = 5,  /* a pointer is not aligned to its element size */
     ASTRA_ERR_ALIAS = 6,  /* an output overlaps an input it must not overlap */
     ASTRA_ERR_LAUNCH = 7, /* the HIP runtime refused the kernel launch */
-    ASTRA_ERR_VARIANT = 8 /* astra_ablation.h only: the variant does not apply to this operator, shape or storage type */
+    ASTRA_ERR_VARIANT = 8, /* astra_ablation.h only: the variant does not apply to this operator, shape or storage type */
+    ASTRA_ENUM_SPANS_INT32(ASTRA_STATUS)
 } astra_status_t;
 
 /*
@@ -120,7 +126,8 @@ typedef enum {
     ASTRA_PROBE_READ2 = 1,        /* a and b are read, nothing is written */
     ASTRA_PROBE_WRITE1 = 2,       /* c is written */
     ASTRA_PROBE_READ2_WRITE1 = 3, /* c <- a ^ b: the mix of silu_and_mul and merge_attn_states_lse */
-    ASTRA_PROBE_UPDATE2 = 4       /* a <- a ^ b, b <- a + b, in place: the mix of fused_add_rmsnorm */
+    ASTRA_PROBE_UPDATE2 = 4,      /* a <- a ^ b, b <- a + b, in place: the mix of fused_add_rmsnorm */
+    ASTRA_ENUM_SPANS_INT32(ASTRA_PROBE)
 } astra_probe_t;
 
 /* Errors: ASTRA_ERR_NULL (a buffer the mode uses is NULL), ASTRA_ERR_SHAPE (nbytes < 0, not a multiple of 16, more than

@@ -38,7 +38,8 @@ typedef enum {
     ASTRA_VARIANT_PACE_NONE = 6,          /* every request as early as possible */
     ASTRA_VARIANT_PACE_STORE_GAP = 7,     /* output store held until the residual store has completed */
     ASTRA_VARIANT_PACE_X_BEFORE_R = 8,    /* x arrived before r is requested */
-    ASTRA_VARIANT_PACE_WEIGHT_X_R = 9     /* weight, then x, then r, one after the other */
+    ASTRA_VARIANT_PACE_WEIGHT_X_R = 9,    /* weight, then x, then r, one after the other */
+    ASTRA_ENUM_SPANS_INT32(ASTRA_VARIANT)
 } astra_variant_t;
 
 /* ASTRA_ERR_VARIANT (astra.h): variant not applicable to this operator, shape or storage type (variants 1 to 4 exist

@@ -376,6 +376,7 @@ const char* astra_status_string(astra_status_t status)
         case ASTRA_ERR_ALIAS: return "output overlaps an input";
         case ASTRA_ERR_LAUNCH: return "kernel launch failed";
         case ASTRA_ERR_VARIANT: return "ablation variant not applicable to this operator or shape";
+        default: break;
     }
     return "unknown status";
 }
@@ -587,7 +588,7 @@ astra_status_t astra_fused_add_rmsnorm_strided(void* y_out, int64_t y_stride, vo
     int ac = align_class(y_out, r_out, x, r);
     for (int i = 0; i < 4; ++i) {
         if (ac == kAlign16 && strides[i] % (kVecBytes / eb) != 0) ac = kAlignPhased;
-        if ((strides[i] - strides[0]) % (kVecBytes / eb) != 0) ac = kAlignNone;
+        if (strides[i] % (kVecBytes / eb) != strides[0] % (kVecBytes / eb)) ac = kAlignNone;  // (no difference of strides: it could overflow)
     }
     astra_launch_info_t li;
     astra_status_t st = plan_rmsnorm(T, H, eb, ac, &li, true, aligned(weight, 16));

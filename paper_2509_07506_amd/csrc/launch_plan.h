@@ -70,7 +70,9 @@ inline bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintp
 inline bool overlaps(const void* p, int64_t n, const void* q, int64_t m)
 {
     const uintptr_t a = reinterpret_cast<uintptr_t>(p), b = reinterpret_cast<uintptr_t>(q);
-    return n > 0 && m > 0 && a < b + (uintptr_t)m && b < a + (uintptr_t)n;
+    if (n <= 0 || m <= 0) return false;
+    if ((uintptr_t)n > ~a || (uintptr_t)m > ~b) return true;  // an extent that wraps around the address space is no tensor: refuse it
+    return a < b + (uintptr_t)m && b < a + (uintptr_t)n;
 }
 
 // How the tensor pointers of a call sit on the 16-byte grid (the `aligned16` argument of the plan functions):
@@ -262,7 +264,10 @@ inline astra_status_t plan_rmsnorm(int64_t T, int64_t H, int eb, int align, astr
     const bool aligned16 = (align == kAlign16) && weight16;
     const int64_t ne = kVecBytes / eb;  // elements per 16-byte vector
     int64_t n;
-    if (T < 0 || H <= 0 || mul_overflows(T, H, &n) || n > std::numeric_limits<int64_t>::max() / 4) return ASTRA_ERR_SHAPE;
+    // (the row length is bounded on its own as well: with T == 0 the product says nothing, and H * 4 bytes must not overflow)
+    if (T < 0 || H <= 0 || H > std::numeric_limits<int64_t>::max() / 4 || mul_overflows(T, H, &n) ||
+        n > std::numeric_limits<int64_t>::max() / 4)
+        return ASTRA_ERR_SHAPE;
     *info = launch_info(ASTRA_PATH_NONE, 0, 0, 0, 0, 0, 0);
     if (T == 0) return ASTRA_OK;
     RowPlan rp;

@@ -55,6 +55,8 @@ def test_rmsnorm_validation_order(A):
     assert f(a, b, c, -1, 8, 1, 1e-6) == 2 and f(a, b, c, 1, 0, 1, 1e-6) == 2 and f(a, b, c, 1 << 40, 1 << 40, 1, 1e-6) == 2
     assert f(a, b, c, 1, 8, 3, 1e-6) == 3 and f(a, b, c, 1, 8, -1, 1e-6) == 3
     assert f(a, b, c, 1, 8, 1, -1e-6) == 4 and f(a, b, c, 1, 8, 1, float("nan")) == 4
+    assert f(a, b, c, 0, 1 << 62, 1, 1e-6) == 2                       # the row length is bounded on its own, also when T == 0
+    assert f((1 << 64) - 0x1000, b, c, 64, 4096, 1, 1e-6) == 6        # a tensor that wraps around the address space is refused
     assert f(a + 1, b, c, 1, 8, 1, 1e-6) == 5
     assert f(a, a + 8, c, 1, 8, 1, 1e-6) == 6 and f(a, b, a + 2, 1, 8, 1, 1e-6) == 6
     # precedence: null before shape before dtype before eps before alignment before aliasing
