@@ -62,6 +62,8 @@ def lib() -> ctypes.CDLL:
         L.oracle_merge_attn_states_lse_f32.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64]
         L.oracle_merge_attn_states_lse_kway.argtypes = [vp, vp, vp, vp, i64, i64, i64, i32]
         L.oracle_merge_attn_states_lse_kway.restype = None
+        L.oracle_merge_attn_states_lse_kway_f32.argtypes = [vp, vp, vp, vp, i64, i64, i64]
+        L.oracle_merge_attn_states_lse_kway_f32.restype = None
         for name in ("oracle_widen_array", "oracle_narrow_array", "oracle_set_threads", "oracle_fused_add_rmsnorm_f32",
                      "oracle_fused_add_rmsnorm", "oracle_silu_and_mul", "oracle_silu_and_mul_f32",
                      "oracle_merge_weights_f32", "oracle_merge_attn_states_lse", "oracle_merge_attn_states_lse_f32"):
@@ -206,4 +208,15 @@ def merge_attn_states_lse_kway(v_parts_bits, lse_parts, dtype: str):
     vo = np.empty((T, NH, D), np.uint16)
     lo = np.empty((T, NH), np.float32)
     lib().oracle_merge_attn_states_lse_kway(_ptr(vo), _ptr(lo), _ptr(v), _ptr(l), K, T * NH, D, DTYPES[dtype])
+    return vo, lo
+
+
+def merge_attn_states_lse_kway_f32(v_parts, lse_parts):
+    """All-float32 K-way merge.  v_parts [K,T,NH,D] float32, lse_parts [K,T,NH] float32 -> (v_out, lse_out) float32."""
+    v, l = _f32(v_parts), _f32(lse_parts)
+    K, T, NH, D = v.shape
+    assert l.shape == (K, T, NH)
+    vo = np.empty((T, NH, D), np.float32)
+    lo = np.empty((T, NH), np.float32)
+    lib().oracle_merge_attn_states_lse_kway_f32(_ptr(vo), _ptr(lo), _ptr(v), _ptr(l), K, T * NH, D)
     return vo, lo

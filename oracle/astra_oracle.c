@@ -327,6 +327,33 @@ void oracle_merge_attn_states_lse_kway(uint16_t* v_out, float* lse_out, const ui
     }
 }
 
+/* All-binary32 form of the K-way merge: the same three passes (maximum, denominator, weighted sum in the order
+   k = 0 .. K-1, zero-weight terms left out) on float values; v_parts [K, P, D], lse_parts [K, P]. */
+void oracle_merge_attn_states_lse_kway_f32(float* v_out, float* lse_out, const float* v_parts, const float* lse_parts,
+                                           int64_t K, int64_t P, int64_t D)
+{
+    for (int64_t p = 0; p < P; ++p) {
+        float top = -INFINITY;
+        for (int64_t k = 0; k < K; ++k) top = fmaxf(top, lse_parts[k * P + p]);
+        if (top == -INFINITY) { /* every partition empty */
+            lse_out[p] = -INFINITY;
+            for (int64_t j = 0; j < D; ++j) v_out[p * D + j] = 0.0f;
+            continue;
+        }
+        float total = 0.0f;
+        for (int64_t k = 0; k < K; ++k) total += expf(lse_parts[k * P + p] - top);
+        lse_out[p] = top + logf(total);
+        for (int64_t j = 0; j < D; ++j) {
+            float sum = 0.0f;
+            for (int64_t k = 0; k < K; ++k) {
+                float wgt = expf(lse_parts[k * P + p] - top) / total;
+                if (wgt != 0.0f) sum += wgt * v_parts[(k * P + p) * D + j];
+            }
+            v_out[p * D + j] = sum;
+        }
+    }
+}
+
 /* All-binary32 form. */
 void oracle_merge_attn_states_lse_f32(float* v_out, float* lse_out, const float* v_a, const float* lse_a,
                                       const float* v_b, const float* lse_b, int64_t T, int64_t NH, int64_t D)

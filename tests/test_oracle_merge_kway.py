@@ -128,3 +128,38 @@ def test_garbage_in_empty_partitions_is_never_looked_at(oracle, dt):
     g[2] = v[2]
     vo, lo = oracle.merge_attn_states_lse_kway(g, s1, dt)
     assert np.array_equal(vo & 0x7FFF, v[2] & 0x7FFF) and np.array_equal(lo.view(np.uint32), s[2].view(np.uint32))
+
+
+def test_binary32_form_is_the_same_operator(oracle):
+    """the all-binary32 K-way oracle: attention over the union of K key sets (float64 brute force), K = 2 equal to the
+    all-binary32 two-way oracle bit for bit, and equal to the 16-bit oracle on values the 16-bit type holds exactly"""
+    rng = np.random.default_rng(7)
+    D = 8
+    for K in (1, 2, 3, 6):
+        for trial in range(4):
+            q = rng.standard_normal(D) * 2
+            sizes = rng.integers(1, 6, K)
+            Ks = [rng.standard_normal((n, D)) for n in sizes]
+            Vs = [rng.standard_normal((n, D)) for n in sizes]
+            parts = [_attention(q, k, v) for k, v in zip(Ks, Vs)]
+            vu, su = _attention(q, np.concatenate(Ks), np.concatenate(Vs))
+            v_parts = np.stack([p[0] for p in parts]).reshape(K, 1, 1, D).astype(np.float32)
+            s_parts = np.array([p[1] for p in parts], np.float32).reshape(K, 1, 1)
+            vo, lo = oracle.merge_attn_states_lse_kway_f32(v_parts, s_parts)
+            np.testing.assert_allclose(vo[0, 0], vu, rtol=0, atol=3e-6)
+            np.testing.assert_allclose(lo[0, 0], su, rtol=0, atol=3e-6)
+    va, la, vb, lb = workloads.merge_inputs(11, 3, 24, "f32", np.random.default_rng(8), empty_p=0.2)
+    v2, l2 = oracle.merge_attn_states_lse_f32(va, la, vb, lb)
+    vk, lk = oracle.merge_attn_states_lse_kway_f32(np.stack([va, vb]), np.stack([la, lb]))
+    assert np.array_equal(np.abs(vk).view(np.uint32), np.abs(v2).view(np.uint32)) and np.array_equal(lk.view(np.uint32), l2.view(np.uint32))
+    # against the 16-bit form: same arithmetic before the final rounding
+    v16, s16 = np.stack([workloads.merge_inputs(5, 2, 16, "bf16", rng, empty_p=0.2)[0] for _ in range(4)]), rng.uniform(-5, 15, (4, 5, 2)).astype(np.float32)
+    s16[1, 0, 0] = -np.inf
+    vo16, lo16 = oracle.merge_attn_states_lse_kway(v16, s16, "bf16")
+    vo32, lo32 = oracle.merge_attn_states_lse_kway_f32(reference_f64.widen(v16, "bf16").astype(np.float32), s16)
+    assert np.array_equal(workloads.to_bits(vo32, "bf16") & 0x7FFF, vo16 & 0x7FFF) and np.array_equal(lo32.view(np.uint32), lo16.view(np.uint32))
+    # garbage in empty partitions
+    g = np.stack([va, np.full_like(va, np.nan)])
+    vo, lo = oracle.merge_attn_states_lse_kway_f32(g, np.stack([la, np.full_like(la, -np.inf)]))
+    live = ~np.isneginf(la)
+    assert np.array_equal(vo[live].view(np.uint32), va[live].view(np.uint32)) and np.all(vo[~live] == 0)

@@ -39,6 +39,9 @@ MUTANTS = [
     ("merge_empty_side_leaks", "if (a == 0.0f) return b * vb;", "if (0) return b * vb;", "test_oracle_merge.py"),
     ("merge_both_empty_leaks", "if (a == 0.0f && b == 0.0f) return 0.0f;", "", "test_oracle_merge.py"),
     ("kway_empty_part_leaks", "if (a != 0.0f) acc += a * widen(", "acc += a * widen(", "test_oracle_merge_kway.py"),
+    ("kway_f32_unnormalised", "float wgt = expf(lse_parts[k * P + p] - top) / total;", "float wgt = expf(lse_parts[k * P + p] - top);", "test_oracle_merge_kway.py"),
+    ("kway_f32_empty_part_leaks", "if (wgt != 0.0f) sum += wgt * v_parts[", "sum += wgt * v_parts[", "test_oracle_merge_kway.py"),
+    ("kway_f32_no_empty_guard", "if (top == -INFINITY) { /* every partition empty */", "if (0) {", "test_oracle_merge_kway.py"),
     ("merge_log_of_sum_of_scores", "float wb = expf(sb - m);", "float wb = expf(sb + m);", "test_oracle_merge.py"),
     ("bf16_truncates", "return (uint16_t)(sign | shr_rne(mag, 16));", "return (uint16_t)(sign | (mag >> 16));", "test_oracle_convert.py"),
     ("f16_flushes_subnormals", "if (e < 101u) return (uint16_t)sign;", "if (e < 113u) return (uint16_t)sign;", "test_oracle_convert.py"),
