@@ -3,8 +3,8 @@
 The oracle's all-binary32 forms (``oracle_*_f32``, pinned by the same closed forms as the 16-bit forms) take
 and return float32 arrays; the float64 definitions bound both.  Bars: the residual of fused_add_rmsnorm is
 bit-exact (one binary32 add, stored unrounded); every other output within rtol 1e-4 / atol 1e-6 (derived
-from the arithmetic in tests/util.py); lse within 1e-4.  The K-way merge has no binary32 C form: it is
-compared with the float64 definition and, at K = 2, with the two-way oracle.
+from the arithmetic in tests/util.py); lse within 1e-4.  The K-way merge is compared with its own binary32 oracle,
+with the float64 definition and, at K = 2, with the two-way oracle.
 """
 import os
 
@@ -165,6 +165,9 @@ def test_merge_kway(A, K, T, NH, D):
     lo = torch.empty((T, NH), dtype=torch.float32, device="cuda")
     A.merge_attn_states_lse_kway(vo, lo, vd, sd)
     torch.cuda.synchronize()
+    vref, lref = O.merge_attn_states_lse_kway_f32(v, s)
+    assert_storage_close(to_bits(vo), vref, DT, "kway f32 v_out vs the binary32 oracle")
+    assert_lse_close(lo.cpu().numpy(), lref, "kway f32 lse vs the binary32 oracle")
     v64, l64 = reference_f64.merge_attn_states_lse_kway(v, s, DT)
     assert_storage_close_to_real(to_bits(vo), v64, DT, "kway f32 v_out vs float64")
     assert_lse_close(lo.cpu().numpy(), l64, "kway f32 lse vs float64")
