@@ -348,6 +348,9 @@ __device__ __forceinline__ void store_chunk_pieces(u32x4* chunk, int lo, int hi,
     }
 }
 
+// the unit in which the memory system moves data: a wave's 64 x 16 bytes are eight whole lines when line aligned
+constexpr int kLineBytes = 128;
+
 // position of an element pointer on the 16-byte grid, in elements (0 .. N-1)
 template <int DT>
 __device__ __forceinline__ int phase_of(const typename Storage<DT>::elem_t* p)

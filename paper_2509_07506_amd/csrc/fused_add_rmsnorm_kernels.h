@@ -180,10 +180,15 @@ __global__ __launch_bounds__(256) void fused_add_rmsnorm_short_row_kernel(u32x4*
 // Phased path: rows that do not start on the 16-byte grid (H no whole number of vectors, so the phase changes from row
 // to row, or pointers offset by some elements), with x, r, y_out and r_out all at the SAME phase in every row (the
 // host checks: pointers congruent modulo 16 bytes, row strides congruent modulo a vector -- true for every dense in
-// place call on 16-byte aligned tensors).  A row is cut into the 16-byte aligned chunks of memory it covers: lane c
-// owns chunk c, i.e. row elements [c*N - phase, c*N - phase + N), and moves it with aligned 16-byte accesses exactly
-// like the fast path.  The chunk at either end of the row can be partial (it also holds elements of the neighbouring
-// row, which another workgroup is updating).
+// place call on 16-byte aligned tensors).  A row is cut into the 16-byte aligned chunks of memory it covers, counted
+// from the start of the 128-byte line the row begins in: lane c owns chunk c of that line-aligned run, i.e. row elements
+// [c*N - phase, c*N - phase + N) with phase = elements between the line start and the row start (up to 128 bytes' worth;
+// the chunks before the row stay idle), and moves it with aligned 16-byte accesses exactly like the fast path.  Counting
+// from the line rather than from the row's first chunk keeps every wave's 1 KiB access on whole 128-byte lines, which
+// measured 3-7 points of the HBM peak faster for row lengths that are no multiple of the vector (T=16384, bf16:
+// H=8196 70.9 -> 78.2 %, H=11012 71.1 -> 78.0 %, H=4100 76.1 -> 79.5 %, H=5124 74.5 -> 77.5 %; the fast path on the
+// neighbouring aligned H: 78.7-81.4 %).  The chunk at either end of the row can be partial (it also holds elements of
+// the neighbouring row, which another workgroup is updating).
 //
 // What decides the speed here is the NUMBER of memory instructions a workgroup issues, not their bytes: on MI355X a
 // streaming kernel pays about as much for a 2-byte store of one lane as for a 1 KiB store of a whole wave (measured:
@@ -198,7 +203,8 @@ __global__ __launch_bounds__(256) void fused_add_rmsnorm_short_row_kernel(u32x4*
 //     those lanes through LDS (written before the reduction's barrier, read after it).
 // That is 3 memory instructions per row more than the fast path.  The weight is indexed by row position, so its
 // 16-byte loads are at element alignment (it is cache resident).  One workgroup per row in the XCD-aware order;
-// ROW_LOOP as in the row kernel; VPT chunks per lane; VPT * blockDim.x >= the most chunks a row can cover.
+// ROW_LOOP as in the row kernel; VPT chunks per lane; VPT * blockDim.x >= the most chunk slots a row can need,
+// ceil((128 / sizeof(element) - 1 + H) / N).
 template <int DT, int VPT, bool NTL, bool NTS, bool ROW_LOOP = false>
 __global__ __launch_bounds__(1024) void fused_add_rmsnorm_phased_row_kernel(
     typename Storage<DT>::elem_t* y_out, typename Storage<DT>::elem_t* r_out, const typename Storage<DT>::elem_t* x,
@@ -221,13 +227,15 @@ __global__ __launch_bounds__(1024) void fused_add_rmsnorm_phased_row_kernel(
         const E* rr = r + row * sv.r_stride;
         E* yr = y_out + row * sv.y_stride;
         E* sr = r_out + row * sv.r_out_stride;
-        const int phase = phase_of<DT>(xr);           // the same for rr, yr and sr; uniform
+        // elements from the start of the enclosing 128-byte line to the row start; modulo N the same for rr, yr, sr
+        const int phase = (int)((reinterpret_cast<uintptr_t>(xr) & (kLineBytes - 1)) / sizeof(E));
+        const int first = phase / N;                  // index of the row's first chunk; uniform
         const int last = (phase + len - 1) / N;       // index of the row's last chunk; uniform
-        const bool head_cut = phase != 0, tail_cut = (phase + len) % N != 0;
+        const bool head_cut = phase % N != 0, tail_cut = (phase + len) % N != 0;
 
         // the boundary elements' weights, one per lane of the first 16 (requested first, like the weight vectors)
         const int j = (int)threadIdx.x;
-        const int edge_e = j < N ? j - phase : last * N - phase + (j - N);  // row element of this lane's boundary position
+        const int edge_e = (j < N ? first * N + j : last * N + (j - N)) - phase;  // row element of this lane's boundary position
         const bool edge_lane = j < 2 * N && edge_e >= 0 && edge_e < len && (j < N ? head_cut : tail_cut);  // H >= N: the two chunks differ
         float edge_w = 0.0f;
         if (edge_lane) edge_w = Storage<DT>::widen(weight[edge_e]);
@@ -240,7 +248,7 @@ __global__ __launch_bounds__(1024) void fused_add_rmsnorm_phased_row_kernel(
             const int c = (int)(threadIdx.x + k * blockDim.x);
             e0[k] = c * N - phase;  // first row element of the chunk (negative for chunk 0 when phase > 0)
             whole[k] = e0[k] >= 0 && e0[k] + N <= len;
-            cut[k] = !whole[k] && c <= last;
+            cut[k] = !whole[k] && c >= first && c <= last;
             wa[k] = u32x4{0u, 0u, 0u, 0u};
             if (whole[k]) wa[k] = load_vec_elem_aligned<DT, false>(weight + e0[k]);
         }

@@ -283,9 +283,10 @@ inline astra_status_t plan_rmsnorm(int64_t T, int64_t H, int eb, int align, astr
         const int lc = fit_chunk_log2(rows, kRowChunkBytesLog2 - floor_log2(H * eb), kRowChunkMinRows);
         if (T >= kMaxRowGrid) pace = kPaceNone;  // the row-loop kernel is not paced
         *info = launch_info(ASTRA_PATH_VECTOR, rp.block, rp.vpt, lc, T < kMaxRowGrid ? pad_grid(rows, lc) : rows, pace, 0);
-    } else if (align != kAlignNone && H >= ne && rmsnorm_row_plan((H + 2 * ne - 2) / ne, &rp)) {
+    } else if (align != kAlignNone && H >= ne && rmsnorm_row_plan((H + kLineBytes / eb - 1 + ne - 1) / ne, &rp)) {
         // rows or pointers off the 16-byte grid, but x, r and the outputs in step with each other: lanes own the aligned
-        // chunks of memory a row covers, at most floor((H + 2N - 2) / N) of them (fused_add_rmsnorm_phased_row_kernel)
+        // chunks of memory a row covers, counted from the start of the 128-byte line the row begins in: at most
+        // ceil((128 / eb - 1 + H) / N) chunk slots (fused_add_rmsnorm_phased_row_kernel)
         const int64_t rows = T < kMaxRowGrid ? T : kMaxRowGrid;
         const int lc = fit_chunk_log2(rows, kRowChunkBytesLog2 - floor_log2(H * eb), kRowChunkMinRows);
         *info = launch_info(ASTRA_PATH_PHASED, rp.block, rp.vpt, lc, T < kMaxRowGrid ? pad_grid(rows, lc) : rows, 0, 0);

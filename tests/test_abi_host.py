@@ -169,12 +169,13 @@ def test_rmsnorm_plans(A):
         if T >= 4096:
             assert 128 * 1024 <= (H * 2) << lc <= 512 * 1024           # about 256 KiB per XCD run
     # rows that are no whole number of vectors on tensors that are in step with each other (16-byte aligned, al=1, or all
-    # offset alike, al=2): phased path -- lanes own the aligned chunks a row covers, at most floor((H + 14) / 8)
+    # offset alike, al=2): phased path -- lanes own the aligned chunks a row covers, counted from the start of the 128-byte
+    # line the row begins in: at most floor((H + 63 + 7) / 8) chunk slots
     assert plan(4, 4100) == {"path": "phased", "block": 576, "vectors_per_lane": 1, "log2_xcd_chunk": 0, "grid": 4, "pace": 0}
     assert plan(4, 4096, al=2) == {"path": "phased", "block": 576, "vectors_per_lane": 1, "log2_xcd_chunk": 0, "grid": 4, "pace": 0}
-    assert plan(9, 32750)["path"] == "phased" and plan(3, 8)["path"] == "vector" and plan(3, 9)["path"] == "phased"
-    assert plan(3, 8, al=2)["path"] == "phased" and plan(4, 8185)["block"] == 1024 and plan(4, 8186)["vectors_per_lane"] == 2
-    assert plan(4, 32761)["path"] == "phased" and plan(4, 32762)["path"] == "ragged"       # one chunk more than 4096: old form
+    assert plan(9, 32700)["path"] == "phased" and plan(3, 8)["path"] == "vector" and plan(3, 9)["path"] == "phased"
+    assert plan(3, 8, al=2)["path"] == "phased" and plan(4, 8129)["block"] == 1024 and plan(4, 8130)["vectors_per_lane"] == 2
+    assert plan(4, 32705)["path"] == "phased" and plan(4, 32706)["path"] == "ragged"       # one chunk slot more than 4096: old form
     p = plan(4099, 5124)
     assert p["path"] == "phased" and p["log2_xcd_chunk"] == 5 and p["grid"] == 4352 and p["block"] == 704
     # tensors at unrelated offsets into the 16-byte grid (al=0): ragged path, row in registers (lanes for the whole

@@ -76,7 +76,7 @@ def test_rmsnorm_unaligned_and_canaries(A):
     T, H = 33, 1032
     x, r, w = workloads.rmsnorm_inputs(T, H, DT, _rng(2))
     s_ref, y_ref = O.fused_add_rmsnorm_f32(x, r, w, 1e-6)
-    for off in (0, 1):                                   # 16-byte aligned; shifted by one element (4-byte aligned)
+    for off in (0, 1, 6, 31):       # 16-byte aligned; shifted by one element (4-byte aligned); by more than a vector
         _say(f"[f32] rmsnorm canaries offset={off}")
         xv, xw = padded(x, DT, offset_elems=off)
         rv, rw = padded(r, DT, offset_elems=off)

@@ -203,7 +203,9 @@ def test_merge_tile_shapes(A, T, NH, D, dt):
 @pytest.mark.parametrize("T,H,off", [(3, 4100, 0), (2, 4097, 0), (5, 1, 0), (4, 7, 0), (3, 4096, 1), (2, 8192, 3), (3, 333, 5),
                                      (2, 8, 1), (5, 9, 0), (3, 15, 7), (257, 5124, 0), (300, 11009, 0), (33, 32767, 1),
                                      (1030, 4098, 3), (600, 16383, 5), (40, 32761, 0), (7, 32775, 0), (300, 8199, 1),
-                                     (2, 70000, 0), (1, 65536, 0)])
+                                     (2, 70000, 0), (1, 65536, 0),
+                                     # offsets beyond one vector: the row starts in the middle of a 128-byte line
+                                     (70, 4097, 9), (3, 4096, 37), (130, 1001, 63), (40, 32705, 0), (5, 32705, 63), (3, 8, 57)])
 def test_rmsnorm_ragged_and_generic_paths_and_canaries(A, T, H, off, dt):
     _say(f"[parity] rmsnorm ragged/generic T={T} H={H} offset={off} {dt}")
     x, r, w = workloads.rmsnorm_inputs(T, H, dt, np.random.default_rng([4, T, H, off]), r_std=2.0)
@@ -212,7 +214,7 @@ def test_rmsnorm_ragged_and_generic_paths_and_canaries(A, T, H, off, dt):
     wd, ww = padded(w, dt, offset_elems=off)
     # x and r carry the same offset, so they are in step with each other: the phased kernel (aligned chunks)
     st, info = A.astra_plan_fused_add_rmsnorm(T, H, 1 if off == 0 else 2)
-    assert info.as_dict()["path"] == ("generic" if H < 8 or H // 8 > 4096 else "phased" if (H + 14) // 8 <= 4096 else "ragged")
+    assert info.as_dict()["path"] == ("generic" if H < 8 or H // 8 > 4096 else "phased" if (H + 63 + 7) // 8 <= 4096 else "ragged")
     A.fused_add_rmsnorm(xd, rd, wd, 1e-5)
     torch.cuda.synchronize()
     y_ref, res_ref = O.fused_add_rmsnorm(x, r, w, 1e-5, dt)
