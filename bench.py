@@ -101,7 +101,7 @@ class Launcher:
                 self.fn = lambda k, st: astra.astra_silu_and_mul(o0 + k * os_, a0 + k * as_, T, d, code, st)
             else:
                 self.fn = lambda k, st: astra.astra_ablation_silu_and_mul(o0 + k * os_, a0 + k * as_, T, d, code, v, st)
-            self.plan = astra.astra_plan_silu_and_mul(T, d, 0 if off % (16 // a.element_size()) else 1, dtype=code)[1].as_dict()
+            self.plan = astra.astra_plan_silu_and_mul(T, d, 2 if off % (16 // a.element_size()) else 1, dtype=code)[1].as_dict()
         else:
             va, la, vb, lb = data
             va, vb = _to_dev(va, dt), _to_dev(vb, dt)

@@ -21,7 +21,8 @@
  *     elements); anything else is served by other paths that compute the same thing: when the activation tensors of
  *     a call are in step with each other (congruent modulo 16 bytes, as all 16-byte aligned dense tensors are),
  *     fused_add_rmsnorm and merge_attn_states_lse work on the 16-byte aligned chunks of memory the rows cover, at
- *     nearly the fast path's rate; otherwise 16-byte accesses at element alignment; plain element-wise kernels for
+ *     nearly the fast path's rate, and so does silu_and_mul when d is a whole number of vectors (with any other d
+ *     its two input halves are out of step with each other); otherwise 16-byte accesses at element alignment; plain element-wise kernels for
  *     fused_add_rmsnorm rows of more than 4096 vectors or less than one and for inputs beyond 2^31 vectors.  Equal up
  *     to the order of binary32 roundings; the residual of fused_add_rmsnorm is bit-identical on every path.
  *   - Nothing outside a tensor is ever written.  The chunked paths READ whole 16-byte aligned chunks, so at the two

@@ -25,8 +25,9 @@ typedef enum {
     ASTRA_PATH_PHASED = 4   /* the same row lengths and pointers, but the activation tensors of the call in step with
                                each other (congruent modulo 16 bytes -- every dense call on 16-byte aligned tensors is):
                                lanes own the 16-byte aligned chunks of memory a row covers, so all interior accesses are
-                               aligned; the partial chunk at a row end element-wise.  fused_add_rmsnorm and
-                               merge_attn_states_lse; runs at the vector path's rate */
+                               aligned; the partial chunk at a row end element-wise.  fused_add_rmsnorm,
+                               merge_attn_states_lse, and silu_and_mul with offset pointers and d a whole number of
+                               vectors; runs at nearly the vector path's rate */
 } astra_path_t;
 
 typedef struct {
@@ -53,8 +54,8 @@ enum {
 };
 
 /* `dtype` is the storage type of the call.  `aligned16` tells how the tensor pointers of the call sit on the 16-byte
- * grid: 1 = every pointer is 16-byte aligned; 2 = not, but the activation tensors (input and residual; v_a, v_b and
- * v_out) are congruent modulo 16 bytes; 0 = element alignment only.  Each function validates like its operator does
+ * grid: 1 = every pointer is 16-byte aligned; 2 = not, but the activation tensors (input and residual; input and out;
+ * v_a, v_b and v_out) are congruent modulo 16 bytes; 0 = element alignment only.  Each function validates like its operator does
  * (ASTRA_ERR_NULL for `info`, ASTRA_ERR_SHAPE, ASTRA_ERR_DTYPE). */
 astra_status_t astra_plan_fused_add_rmsnorm(int64_t T, int64_t H, astra_dtype_t dtype, int aligned16,
                                             astra_launch_info_t* info);

@@ -213,6 +213,18 @@ void launch_silu(const astra_launch_info_t& li, void* out, const void* in, int64
             static_cast<E*>(out), static_cast<const E*>(in), T, d);
         return;
     }
+    if (li.path == ASTRA_PATH_PHASED) {  // x, g and the output all start `phase` elements past the 16-byte grid in every row
+        constexpr int N = Storage<DT>::kN;
+        const int phase = (int)((reinterpret_cast<uintptr_t>(out) & 15u) / sizeof(E));
+        const uint32_t chunks = (uint32_t)((T * d + phase + N - 1) / N);
+        for_flat_block(li.block, [&](auto bc) {
+            constexpr int B = decltype(bc)::value;
+            silu_and_mul_phased_kernel<DT, kNTLoad, kNTStore, B><<<dim3((uint32_t)li.grid), dim3(B), 0, stream>>>(
+                static_cast<E*>(out), static_cast<const E*>(in), (uint32_t)T, (uint32_t)d, make_fastdiv((uint32_t)d), chunks,
+                phase, li.log2_xcd_chunk);
+        });
+        return;
+    }
     if (li.path == ASTRA_PATH_RAGGED) {
         const uint32_t dvr = (uint32_t)((d + Storage<DT>::kN - 1) / Storage<DT>::kN);
         silu_and_mul_ragged_kernel<DT, kNTLoad, kNTStore><<<dim3((uint32_t)li.grid), dim3(256), 0, stream>>>(
@@ -463,7 +475,7 @@ static astra_status_t run_silu_and_mul(void* out, const void* input, int64_t T, 
     if (!out || !input) return ASTRA_ERR_NULL;
     astra_launch_info_t li;
     const int eb = elem_bytes((int)dtype);
-    astra_status_t st = plan_silu(T, d, eb, aligned(out, 16) && aligned(input, 16) ? kAlign16 : kAlignNone, &li);
+    astra_status_t st = plan_silu(T, d, eb, align_class(out, input), &li);
     if (st != ASTRA_OK) return st;
     if (!valid_dtype((int)dtype)) return ASTRA_ERR_DTYPE;
     if (!aligned(out, eb) || !aligned(input, eb)) return ASTRA_ERR_ALIGN;

@@ -328,7 +328,7 @@ inline int flat_block(int64_t vecs)
 // `wide_only`: the caller's kernel exists with 256-lane workgroups only (strided views)
 inline astra_status_t plan_silu(int64_t T, int64_t d, int eb, int align, astra_launch_info_t* info, bool wide_only = false)
 {
-    const bool aligned16 = (align == kAlign16);  // x and g sit d elements apart: no common phase when d is no whole number of vectors
+    const bool aligned16 = (align == kAlign16);
     const int64_t ne = kVecBytes / eb;
     int64_t two_d, n;
     if (T < 0 || d <= 0 || mul_overflows(d, 2, &two_d) || mul_overflows(T, two_d, &n) ||
@@ -348,6 +348,14 @@ inline astra_status_t plan_silu(int64_t T, int64_t d, int eb, int align, astra_l
         const int64_t blocks = (T * dv + span - 1) / span;
         const int lc = fit_chunk_log2(blocks, kFlatChunkLog2, kFlatChunkMinBlocks * (256 / block));
         *info = launch_info(ASTRA_PATH_VECTOR, block, kSiluUnroll, lc, pad_grid(blocks, lc), 0, 0);
+    } else if (!wide_only && align == kAlignPhased && d % ne == 0 && T * d <= kMaxVecIndex) {
+        // input and output offset from the 16-byte grid alike: the aligned chunks the output covers, one more than
+        // its vectors (silu_and_mul_phased_kernel); flat output elements are indexed with 32 bits
+        const int64_t chunks = T * dv + 1;
+        const int block = flat_block(chunks);
+        const int64_t blocks = (chunks + block - 1) / block;
+        const int lc = fit_chunk_log2(blocks, kFlatChunkLog2, kFlatChunkMinBlocks * (256 / block));
+        *info = launch_info(ASTRA_PATH_PHASED, block, 1, lc, pad_grid(blocks, lc), 0, 0);
     } else if (T * ((d + ne - 1) / ne) <= kMaxVecIndex) {  // no overflow: T * d is below 2^61
         *info = launch_info(ASTRA_PATH_RAGGED, 256, 1, 0, (T * ((d + ne - 1) / ne) + 255) / 256, 0, 0);
     } else {

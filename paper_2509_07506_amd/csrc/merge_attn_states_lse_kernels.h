@@ -241,7 +241,6 @@ __global__ __launch_bounds__(256) void merge_attn_states_lse_strided_vec_kernel(
                                                                                 FastDiv by_dvec, FastDiv by_heads,
                                                                                 uint32_t heads, int log2_chunk)
 {
-    constexpr int N = Storage<DT>::kN;
     const uint32_t i = xcd_chunked(blockIdx.x, log2_chunk) * 256u + threadIdx.x;
     if (i >= total_vecs) return;
     const uint32_t pair = by_dvec.div(i), jv = i - pair * dvec;

@@ -278,6 +278,15 @@ def test_silu_and_merge_plans(A):
     assert A.astra_plan_silu_and_mul(3, 100, True)[1].as_dict() == {"path": "ragged", "block": 256, "vectors_per_lane": 1,
                                                                     "log2_xcd_chunk": 0, "grid": 1, "pace": 0}   # 3 * 13 vectors
     assert A.astra_plan_silu_and_mul(3, 1408, False)[1].as_dict()["path"] == "ragged"
+    # input and output offset from the 16-byte grid alike, d a whole number of vectors: aligned chunks of the output, one
+    # more than its vectors
+    ph = A.astra_plan_silu_and_mul(4096, 14336, 2)[1].as_dict()
+    assert ph == {"path": "phased", "block": 64, "vectors_per_lane": 1, "log2_xcd_chunk": 8, "grid": 114688 + 2048, "pace": 0}
+    assert A.astra_plan_silu_and_mul(3, 1408, 2)[1].as_dict() == {"path": "phased", "block": 256, "vectors_per_lane": 1,
+                                                                  "log2_xcd_chunk": 0, "grid": 3, "pace": 0}
+    assert A.astra_plan_silu_and_mul(3, 1410, 2)[1].as_dict()["path"] == "ragged"          # the two halves of a row out of step
+    assert A.astra_plan_silu_and_mul(1 << 17, 1 << 14, 2)[1].as_dict()["path"] == "phased"  # 2^31 output elements: the most
+    assert A.astra_plan_silu_and_mul((1 << 17) + 1, 1 << 14, 2)[1].as_dict()["path"] == "ragged"
     assert A.astra_plan_silu_and_mul(1 << 20, (1 << 14) + 1, True)[1].as_dict()["path"] == "generic"
     assert A.astra_plan_silu_and_mul(3, 128, True)[1].as_dict()["path"] == "vector"       # short rows: per-lane division
     assert A.astra_plan_silu_and_mul(1000, 8, True)[1].as_dict() == {"path": "vector", "block": 256, "vectors_per_lane": 1,

@@ -264,17 +264,38 @@ def test_rmsnorm_vector_path_canaries(A, T, H, dt):
 @pytest.mark.parametrize("dt", ["bf16", "f16"])
 @pytest.mark.parametrize("T,d,off", [(3, 100, 0), (2, 1412, 0), (5, 1, 0), (4, 2049, 0), (3, 1408, 1), (2, 248, 0), (3, 11008, 2),
                                      (4, 1408, 0), (257, 11008, 0),
-                                     (300, 11009, 0), (1000, 7, 3), (257, 1410, 5), (64, 8, 1), (129, 13825, 0), (50, 11012, 7)])
+                                     (300, 11009, 0), (1000, 7, 3), (257, 1410, 5), (64, 8, 1), (129, 13825, 0), (50, 11012, 7),
+                                     # d a whole number of vectors behind offset pointers: aligned chunks of the output, one
+                                     # per row across the row end (every chunk when d = 8)
+                                     (1, 8, 7), (1, 16, 3), (2, 8, 4), (513, 1408, 4), (1030, 64, 5), (257, 11008, 6),
+                                     (40, 14336, 9), (3, 24, 15)])
 def test_silu_paths_and_canaries(A, T, d, off, dt):
     _say(f"[parity] silu T={T} d={d} offset={off} {dt}")
     a = workloads.silu_inputs(T, d, dt, np.random.default_rng([6, T, d, off]))
     ad, aw = padded(a, dt, offset_elems=off)
     out_init = np.full((T, d), 0x1234, np.uint16)
     od, ow = padded(out_init, dt, offset_elems=off)
+    st, info = A.astra_plan_silu_and_mul(T, d, 1 if off % 8 == 0 else 2)
+    assert info.as_dict()["path"] == ("vector" if d % 8 == 0 and off % 8 == 0 else "phased" if d % 8 == 0 else "ragged")
     A.silu_and_mul(od, ad)
     torch.cuda.synchronize()
     assert_storage_close(to_bits(od), O.silu_and_mul(a, dt), dt, "out")
     assert canaries_intact(ow, T * d, offset_elems=off) and canaries_intact(aw, a.size, offset_elems=off)
+    assert np.array_equal(to_bits(ad), a)
+
+
+@pytest.mark.parametrize("dt", ["bf16", "f16"])
+@pytest.mark.parametrize("T,d,off_in,off_out", [(5, 1408, 1, 2), (300, 11008, 0, 3), (64, 8, 5, 0), (33, 1416, 7, 7)])
+def test_silu_input_and_output_at_unrelated_offsets(A, T, d, off_in, off_out, dt):
+    """input and output out of step with each other: 16-byte accesses at element alignment (the last case is in step)"""
+    _say(f"[parity] silu T={T} d={d} offsets in={off_in} out={off_out} {dt}")
+    a = workloads.silu_inputs(T, d, dt, np.random.default_rng([66, T, d, off_in, off_out]))
+    ad, aw = padded(a, dt, offset_elems=off_in)
+    od, ow = padded(np.full((T, d), 0x1234, np.uint16), dt, offset_elems=off_out)
+    A.silu_and_mul(od, ad)
+    torch.cuda.synchronize()
+    assert_storage_close(to_bits(od), O.silu_and_mul(a, dt), dt, "out")
+    assert canaries_intact(ow, T * d, offset_elems=off_out) and canaries_intact(aw, a.size, offset_elems=off_in)
     assert np.array_equal(to_bits(ad), a)
 
 
