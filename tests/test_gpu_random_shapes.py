@@ -129,3 +129,55 @@ def test_merge_kway_random_shapes(A):
         vo_ref, lo_ref = O.merge_attn_states_lse_kway(v, s, dt)
         assert_storage_close(to_bits(vo), vo_ref, dt, f"#{i} v_out")
         assert_lse_close(lo.cpu().numpy(), lo_ref, f"#{i} lse_out")
+
+
+def test_random_shapes_behind_random_element_offsets(A):
+    """every activation tensor of a call starts the same random number of elements (0 to 70: beyond a vector, beyond a
+    128-byte line) into a canary-filled buffer: the chunked paths with rows that start anywhere in a line"""
+    from tests.gpu_util import canaries_intact, padded
+
+    rng = np.random.default_rng(9006)
+    for i in range(N_CASES):
+        dt = _pick(rng, ["bf16", "f16"])
+        off = int(rng.integers(0, 71))
+        kind = i % 3
+        if kind == 0:
+            T, H = int(rng.integers(1, 300)), _row_len(rng, 12000)
+            print(f"[random] offset rmsnorm #{i} T={T} H={H} off={off} {dt}", flush=True)
+            x, r, w = workloads.rmsnorm_inputs(T, H, dt, rng, r_std=2.0)
+            (xd, xw), (rd, rw), (wd, ww) = (padded(t, dt, offset_elems=off) for t in (x, r, w))
+            A.fused_add_rmsnorm(xd, rd, wd, 1e-5)
+            torch.cuda.synchronize()
+            y_ref, res_ref = O.fused_add_rmsnorm(x, r, w, 1e-5, dt)
+            assert_bits_equal(to_bits(rd), res_ref, f"#{i} residual")
+            assert_storage_close(to_bits(xd), y_ref, dt, f"#{i} y")
+            assert canaries_intact(xw, x.size, offset_elems=off) and canaries_intact(rw, r.size, offset_elems=off)
+            assert canaries_intact(ww, w.size, offset_elems=off) and np.array_equal(to_bits(wd), w)
+        elif kind == 1:
+            T, d = int(rng.integers(1, 300)), _row_len(rng, 12000)
+            print(f"[random] offset silu #{i} T={T} d={d} off={off} {dt}", flush=True)
+            a = workloads.silu_inputs(T, d, dt, rng)
+            ad, aw = padded(a, dt, offset_elems=off)
+            od, ow = padded(np.full((T, d), 0x1234, np.uint16), dt, offset_elems=off)
+            A.silu_and_mul(od, ad)
+            torch.cuda.synchronize()
+            assert_storage_close(to_bits(od), O.silu_and_mul(a, dt), dt, f"#{i} silu")
+            assert canaries_intact(ow, T * d, offset_elems=off) and canaries_intact(aw, a.size, offset_elems=off)
+            assert np.array_equal(to_bits(ad), a)
+        else:
+            T, NH = int(rng.integers(1, 60)), int(rng.integers(1, 48))
+            D = int(_pick(rng, [8, 16, 64, 72, 128, 256, 4, 100, 1, 129, 132, 24]))
+            print(f"[random] offset merge #{i} T={T} NH={NH} D={D} off={off} {dt}", flush=True)
+            va, la, vb, lb = workloads.merge_inputs(T, NH, D, dt, rng, empty_p=0.05)
+            (vad, vaw), (vbd, vbw) = padded(va, dt, offset_elems=off), padded(vb, dt, offset_elems=off)
+            vo, vow = padded(np.full((T, NH, D), 0x1234, np.uint16), dt, offset_elems=off)
+            lad, lbd = torch.from_numpy(la).cuda(), torch.from_numpy(lb).cuda()
+            lo = torch.empty_like(lad)
+            A.merge_attn_states_lse(vo, lo, vad, lad, vbd, lbd)
+            torch.cuda.synchronize()
+            vo_ref, lo_ref = O.merge_attn_states_lse(va, la, vb, lb, dt)
+            assert_storage_close(to_bits(vo), vo_ref, dt, f"#{i} v_out")
+            assert_lse_close(lo.cpu().numpy(), lo_ref, f"#{i} lse_out")
+            assert canaries_intact(vow, va.size, offset_elems=off) and canaries_intact(vaw, va.size, offset_elems=off)
+            assert canaries_intact(vbw, vb.size, offset_elems=off)
+            assert np.array_equal(to_bits(vad), va) and np.array_equal(to_bits(vbd), vb)
