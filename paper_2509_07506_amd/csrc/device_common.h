@@ -300,63 +300,8 @@ __device__ __forceinline__ void store_chunk_partial(typename Storage<DT>::elem_t
     }
 }
 
-// The same two operations with as few memory instructions as possible.  `chunk` is the 16-byte aligned address of the
-// chunk, [lo, hi) the chunk positions that belong to the row (0 <= lo < hi <= N, not the whole chunk).
-// Load: the whole aligned chunk in one access.  The positions outside [lo, hi) are bytes of the neighbouring row or,
-// at the two ends of a tensor, up to 14 bytes outside it; an aligned 16-byte access lies inside one page, so it cannot
-// fault, and those positions are cleared before use.
-template <int DT, bool NT>
-__device__ __forceinline__ u32x4 load_chunk_masked(const u32x4* chunk, int lo, int hi)
-{
-    constexpr int N = Storage<DT>::kN;
-    const u32x4 v = load_vec<NT>(chunk);
-    uint32_t w[4] = {v.x, v.y, v.z, v.w};
-    if constexpr (DT == kF32) {
-#pragma unroll
-        for (int p = 0; p < N; ++p) w[p] = (p >= lo && p < hi) ? w[p] : 0u;
-    } else {
-#pragma unroll
-        for (int p = 0; p < N; p += 2) {
-            const uint32_t keep = ((p >= lo && p < hi) ? 0x0000ffffu : 0u) | ((p + 1 >= lo && p + 1 < hi) ? 0xffff0000u : 0u);
-            w[p / 2] &= keep;
-        }
-    }
-    return u32x4{w[0], w[1], w[2], w[3]};
-}
-
-// Store: positions [lo, hi) of the packed chunk `v` as the fewest aligned pieces of 8, 4 and (16-bit types) 2 bytes --
-// at most three per side instead of one store per element; nothing outside [lo, hi) is written.  A piece is written
-// if it lies inside [lo, hi) and the aligned piece of twice its size that contains it does not.
-template <int DT>
-__device__ __forceinline__ void store_chunk_pieces(u32x4* chunk, int lo, int hi, u32x4 v)
-{
-    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-    auto in = [&](int pos, int size) { return lo <= pos && pos + size <= hi; };  // positions in elements
-    constexpr int kPerDword = (DT == kF32) ? 1 : 2;                              // elements per 32-bit word
-    uint32_t* const d = reinterpret_cast<uint32_t*>(chunk);
-#pragma unroll
-    for (int q = 0; q < 2; ++q)  // 8-byte pieces: dwords 2q, 2q+1
-        if (in(2 * q * kPerDword, 2 * kPerDword)) *reinterpret_cast<u32x2*>(d + 2 * q) = u32x2{w[2 * q], w[2 * q + 1]};
-#pragma unroll
-    for (int q = 0; q < 4; ++q)  // 4-byte pieces
-        if (in(q * kPerDword, kPerDword) && !in((q & ~1) * kPerDword, 2 * kPerDword)) d[q] = w[q];
-    if constexpr (DT != kF32) {
-        uint16_t* const h = reinterpret_cast<uint16_t*>(chunk);
-#pragma unroll
-        for (int p = 0; p < 8; ++p)  // 2-byte pieces
-            if (in(p, 1) && !in(p & ~1, 2)) h[p] = (uint16_t)(p & 1 ? w[p / 2] >> 16 : w[p / 2] & 0xffffu);
-    }
-}
-
 // the unit in which the memory system moves data: a wave's 64 x 16 bytes are eight whole lines when line aligned
 constexpr int kLineBytes = 128;
-
-// position of an element pointer on the 16-byte grid, in elements (0 .. N-1)
-template <int DT>
-__device__ __forceinline__ int phase_of(const typename Storage<DT>::elem_t* p)
-{
-    return (int)((reinterpret_cast<uintptr_t>(p) / sizeof(typename Storage<DT>::elem_t)) & (Storage<DT>::kN - 1));
-}
 
 // ---------------------------------------------------------------------------------------------
 // index arithmetic
