@@ -106,6 +106,36 @@ def test_silu_tiles(A, T, d):
     assert_bits_equal(u32(to_bits(ad)), u32(a), "input untouched")
 
 
+@pytest.mark.parametrize("T,d,off", [(3, 1412, 1), (257, 1408, 3), (5, 4, 2), (64, 8192, 5), (9, 96, 33), (7, 130, 1)])
+def test_silu_and_merge_behind_offset_pointers(A, T, d, off):
+    """binary32 tensors that start `off` elements into a canary-filled buffer, all of a call alike: the chunked paths
+    with four elements per chunk (silu needs d % 4 == 0 for it; the last case runs at element alignment)"""
+    plan = A.astra_plan_silu_and_mul(T, d, 2 if off % 4 else 1, dtype=A.ASTRA_F32)[1].as_dict()
+    _say(f"[f32] silu offset T={T} d={d} off={off} plan={plan}")
+    assert plan["path"] == ("ragged" if d % 4 else "phased" if off % 4 else "vector")
+    a = workloads.silu_inputs(T, d, DT, _rng(31, T, d, off))
+    ad, aw = padded(a, DT, offset_elems=off)
+    od, ow = padded(np.zeros((T, d), np.float32), DT, offset_elems=off)
+    A.silu_and_mul(od, ad)
+    torch.cuda.synchronize()
+    assert_storage_close(to_bits(od), O.silu_and_mul_f32(a), DT, "silu f32 offset")
+    assert canaries_intact(ow, T * d, offset_elems=off) and canaries_intact(aw, a.size, offset_elems=off)
+    assert_bits_equal(u32(to_bits(ad)), u32(a), "input untouched")
+    # the same shape as a merge: T x 3 pairs of d elements
+    va, la, vb, lb = workloads.merge_inputs(T, 3, d, DT, _rng(32, T, d, off), empty_p=0.1)
+    (vad, vaw), (vbd, vbw) = padded(va, DT, offset_elems=off), padded(vb, DT, offset_elems=off)
+    vo, vow = padded(np.zeros((T, 3, d), np.float32), DT, offset_elems=off)
+    lad, lbd = torch.from_numpy(la).cuda(), torch.from_numpy(lb).cuda()
+    lo = torch.empty_like(lad)
+    A.merge_attn_states_lse(vo, lo, vad, lad, vbd, lbd)
+    torch.cuda.synchronize()
+    vo_ref, lo_ref = O.merge_attn_states_lse_f32(va, la, vb, lb)
+    assert_storage_close(to_bits(vo), vo_ref, DT, "merge f32 offset v_out")
+    assert_lse_close(lo.cpu().numpy(), lo_ref, "merge f32 offset lse")
+    assert canaries_intact(vow, va.size, offset_elems=off) and canaries_intact(vaw, va.size, offset_elems=off)
+    assert canaries_intact(vbw, vb.size, offset_elems=off)
+
+
 def test_silu_special_values(A):
     d = 128
     xs = np.array([0.0, -0.0, 1.0, -1.0, 20.0, -20.0, 88.0, -88.0, -89.0, -104.0, 3e38, -3e38, 1e-40, -1e-40, 100.0,
