@@ -333,9 +333,12 @@ void launch_merge_kway(const astra_launch_info_t& li, void* v_out, float* lse_ou
     }
     const uint32_t dvec = (uint32_t)(D / Storage<DT>::kN);
     const int log2_dvec = (dvec & (dvec - 1)) == 0 ? __builtin_ctz(dvec) : -1;
-    merge_attn_states_lse_kway_vec_kernel<DT, kKwayGroup, kNTLoad, kNTStore><<<dim3((uint32_t)li.grid), dim3(256), 0, stream>>>(
-        static_cast<u32x4*>(v_out), lse_out, static_cast<const u32x4*>(v_parts), lse_parts, (uint32_t)K,
-        (uint32_t)(pairs * dvec), (uint32_t)pairs, dvec, log2_dvec, make_fastdiv(dvec), li.log2_xcd_chunk);
+    for_flat_block(li.block, [&](auto bc) {
+        constexpr int B = decltype(bc)::value;
+        merge_attn_states_lse_kway_vec_kernel<DT, kKwayGroup, kNTLoad, kNTStore, B><<<dim3((uint32_t)li.grid), dim3(B), 0, stream>>>(
+            static_cast<u32x4*>(v_out), lse_out, static_cast<const u32x4*>(v_parts), lse_parts, (uint32_t)K,
+            (uint32_t)(pairs * dvec), (uint32_t)pairs, dvec, log2_dvec, make_fastdiv(dvec), li.log2_xcd_chunk);
+    });
 }
 
 // `ev` holds the row strides in elements
@@ -566,8 +569,11 @@ astra_status_t astra_merge_attn_states_lse_kway(void* v_out, float* lse_out, con
     if (!v_out || !lse_out || !v_parts || !lse_parts) return ASTRA_ERR_NULL;
     astra_launch_info_t li;
     const int eb = elem_bytes((int)dtype);
-    astra_status_t st = plan_merge(T, num_heads, head_dim, eb, aligned(v_out, 16) && aligned(v_parts, 16) ? kAlign16 : kAlignNone, &li, true);
+    const int align = aligned(v_out, 16) && aligned(v_parts, 16) ? kAlign16 : kAlignNone;
+    astra_status_t st = plan_merge(T, num_heads, head_dim, eb, align, &li, true);
     if (st != ASTRA_OK) return st;
+    // the fast kernel exists for every workgroup width of the flat grids; the ragged one with 256 lanes only
+    if (li.path == ASTRA_PATH_VECTOR) plan_merge(T, num_heads, head_dim, eb, align, &li, false);
     if (li.path == ASTRA_PATH_GENERIC) return ASTRA_ERR_SHAPE;  // more than 2^31 output vectors
     const int64_t pairs = T * num_heads;
     int64_t part_elems = pairs * head_dim, all_elems;

@@ -364,7 +364,7 @@ inline astra_status_t plan_silu(int64_t T, int64_t d, int eb, int align, astra_l
     return ASTRA_OK;
 }
 
-// `wide_only`: the caller's kernel exists with 256-lane workgroups only (strided views, K-way merge)
+// `wide_only`: the caller's kernel exists with 256-lane workgroups only (strided views, the ragged K-way merge)
 inline astra_status_t plan_merge(int64_t T, int64_t NH, int64_t D, int eb, int align, astra_launch_info_t* info,
                                  bool wide_only = false)
 {

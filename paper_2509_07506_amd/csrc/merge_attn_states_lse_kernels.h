@@ -262,8 +262,8 @@ __global__ __launch_bounds__(256) void merge_attn_states_lse_strided_vec_kernel(
 // denominator and running accumulators that are rescaled by e^(m_old - m_new) whenever the maximum
 // grows.  Equal to the definition up to binary32 rounding; a three-pass form (maximum, denominator,
 // weights) measured 10-14 % slower because every pass waits on memory again.
-template <int DT, int G, bool NTL, bool NTS>
-__global__ __launch_bounds__(256) void merge_attn_states_lse_kway_vec_kernel(u32x4* __restrict__ v_out,
+template <int DT, int G, bool NTL, bool NTS, int BLOCK = 256>
+__global__ __launch_bounds__(BLOCK) void merge_attn_states_lse_kway_vec_kernel(u32x4* __restrict__ v_out,
                                                                              float* __restrict__ lse_out,
                                                                              const u32x4* __restrict__ v_parts,
                                                                              const float* __restrict__ lse_parts,
@@ -272,7 +272,7 @@ __global__ __launch_bounds__(256) void merge_attn_states_lse_kway_vec_kernel(u32
                                                                              int log2_chunk)
 {
     constexpr int N = Storage<DT>::kN;
-    const uint32_t i = xcd_chunked(blockIdx.x, log2_chunk) * 256u + threadIdx.x;
+    const uint32_t i = xcd_chunked(blockIdx.x, log2_chunk) * uint32_t(BLOCK) + threadIdx.x;
     if (i >= total_vecs) return;
     const uint32_t pair = log2_dvec >= 0 ? (i >> log2_dvec) : by_dvec.div(i);
     const float ninf = -__builtin_inff();
