@@ -406,7 +406,7 @@ astra_status_t astra_plan_fused_add_rmsnorm(int64_t T, int64_t H, astra_dtype_t 
                                             astra_launch_info_t* info)
 {
     if (!info) return ASTRA_ERR_NULL;
-    const astra_status_t st = plan_rmsnorm(T, H, elem_bytes((int)dtype), plan_align(aligned16), info);
+    const astra_status_t st = plan_rmsnorm(T, H, elem_bytes((int)dtype), plan_align(aligned16), info, true, true, true);
     return st == ASTRA_OK && !valid_dtype((int)dtype) ? ASTRA_ERR_DTYPE : st;
 }
 
@@ -431,7 +431,8 @@ static astra_status_t run_fused_add_rmsnorm(void* input, void* residual, const v
     if (!input || !residual || !weight) return ASTRA_ERR_NULL;
     astra_launch_info_t li;
     const int eb = elem_bytes((int)dtype);
-    astra_status_t st = plan_rmsnorm(T, H, eb, align_class(input, residual), &li, variant == ASTRA_VARIANT_TUNED, aligned(weight, 16));
+    astra_status_t st = plan_rmsnorm(T, H, eb, align_class(input, residual), &li, variant == ASTRA_VARIANT_TUNED, aligned(weight, 16),
+                                     variant == ASTRA_VARIANT_TUNED);
     if (st != ASTRA_OK) return st;
     if (!valid_dtype((int)dtype)) return ASTRA_ERR_DTYPE;
     if (!(eps >= 0.0f)) return ASTRA_ERR_EPS;

@@ -108,7 +108,7 @@ __global__ __launch_bounds__(MAX_THREADS) void fused_add_rmsnorm_row_kernel(u32x
                     s[k][e] = x[e] + r[e];
                     acc += s[k][e] * s[k][e];
                 }
-                store_vec<NTS>(sumrow + v, pack_vec<DT>(s[k]));
+                store_row_vec_in_place<NTS>(sumrow, hv, v, pack_vec<DT>(s[k]));
             }
         }
 
@@ -124,7 +124,7 @@ __global__ __launch_bounds__(MAX_THREADS) void fused_add_rmsnorm_row_kernel(u32x
                 unpack_vec<DT>(wv[k], w);
 #pragma unroll
                 for (int e = 0; e < N; ++e) y[e] = (s[k][e] * scale) * w[e];
-                store_vec<NTS>(yrow + v, pack_vec<DT>(y));
+                store_row_vec_in_place<NTS>(yrow, hv, v, pack_vec<DT>(y));
             }
         }
         row += gridDim.x;

@@ -256,9 +256,20 @@ inline bool rmsnorm_row_policy(int64_t T, int64_t hv, int64_t row_bytes, RowPlan
 constexpr int64_t kShortRowVecs = 32;
 inline int short_row_group(int64_t hv) { return hv <= 8 ? 8 : hv <= 16 ? 16 : 32; }
 
+// Rows of whole vectors that are no whole number of 128-byte lines (H * eb % 128 != 0) start in the middle of a line,
+// so the waves of the fast kernel straddle nine lines instead of eight; the phased kernel counts its chunks from the
+// line start and keeps every wave access on whole lines.  Measured on MI355X, T=16384, bf16, fast -> phased kernel:
+// H=2056 75.1 -> 76.2 % of the HBM peak, H=4104 77.7 -> 79.4 %, H=4128 79.1 -> 79.7 %, H=5128 78.0 -> 79.1 %,
+// H=8200 73.9 -> 78.3 %, H=8224 76.2 -> 77.5 %, H=11016 73.9 -> 77.5 %; H=1032 71.8 -> 71.3 %, hence the lower limit.
+// Streaming grids only (32 rows per compute unit or more): shorter grids keep the fast kernel with its request pacing.
+constexpr int64_t kLineGridMinRowBytes = 4096;
+constexpr int64_t kLineGridMinRows = 32 * kCus;
+
 // `short_rows`: the caller can launch the short-row kernel (the ablation variants, which restage the row kernel, cannot)
+// `line_grid`: dense rows in place, any kernel allowed (the tuned dense operator): rows that are no whole number of
+// 128-byte lines go to the phased kernel
 inline astra_status_t plan_rmsnorm(int64_t T, int64_t H, int eb, int align, astra_launch_info_t* info,
-                                   bool short_rows = true, bool weight16 = true)
+                                   bool short_rows = true, bool weight16 = true, bool line_grid = false)
 {
     // the fast path also needs the weight on the 16-byte grid; the phased path does not
     const bool aligned16 = (align == kAlign16) && weight16;
@@ -278,6 +289,10 @@ inline astra_status_t plan_rmsnorm(int64_t T, int64_t H, int eb, int align, astr
         const int64_t blocks = (T + short_rows_per_block - 1) / short_rows_per_block;
         const int lc = fit_chunk_log2(blocks, kFlatChunkLog2, kFlatChunkMinBlocks);  // a workgroup streams 4 KiB, like the flat kernels
         *info = launch_info(ASTRA_PATH_VECTOR, 256, 1, lc, pad_grid(blocks, lc), kPaceNone, (int32_t)short_rows_per_block);
+    } else if (line_grid && align == kAlign16 && H % ne == 0 && (H * eb) % kLineBytes != 0 && H * eb >= kLineGridMinRowBytes &&
+               T >= kLineGridMinRows && T < kMaxRowGrid && rmsnorm_row_plan((H + kLineBytes / eb - 1 + ne - 1) / ne, &rp)) {
+        const int lc = fit_chunk_log2(T, kRowChunkBytesLog2 - floor_log2(H * eb), kRowChunkMinRows);
+        *info = launch_info(ASTRA_PATH_PHASED, rp.block, rp.vpt, lc, pad_grid(T, lc), 0, 0);
     } else if (aligned16 && H % ne == 0 && rmsnorm_row_policy(T, H / ne, H * eb, &rp, &pace)) {
         const int64_t rows = T < kMaxRowGrid ? T : kMaxRowGrid;
         const int lc = fit_chunk_log2(rows, kRowChunkBytesLog2 - floor_log2(H * eb), kRowChunkMinRows);

@@ -178,6 +178,14 @@ def test_rmsnorm_plans(A):
     assert plan(4, 32705)["path"] == "phased" and plan(4, 32706)["path"] == "ragged"       # one chunk slot more than 4096: old form
     p = plan(4099, 5124)
     assert p["path"] == "phased" and p["log2_xcd_chunk"] == 5 and p["grid"] == 4352 and p["block"] == 704
+    # rows of whole vectors that are no whole number of 128-byte lines (from 4 KiB on): the same kernel, whose waves stay on
+    # whole lines; below 4 KiB and for whole lines the fast kernel
+    # (streaming grids only: 32 rows per compute unit or more)
+    assert plan(8192, 4104) == {"path": "phased", "block": 576, "vectors_per_lane": 1, "log2_xcd_chunk": 5, "grid": 8192, "pace": 0}
+    assert plan(8192, 8200)["path"] == "phased" and plan(8192, 8200)["vectors_per_lane"] == 2
+    assert plan(8192, 2056)["path"] == "phased" and plan(8192, 2040)["path"] == "vector" and plan(8192, 1032)["path"] == "vector"
+    assert plan(8192, 4160)["path"] == "vector" and plan(8192, 32712)["path"] == "vector"  # 65 lines; too long for the line grid
+    assert plan(8191, 4104)["path"] == "vector" and plan(4, 8200)["path"] == "vector"
     # tensors at unrelated offsets into the 16-byte grid (al=0): ragged path, row in registers (lanes for the whole
     # vectors; the tail of fewer than 8 elements rides in the last lane)
     assert plan(4, 4100, al=0) == {"path": "ragged", "block": 512, "vectors_per_lane": 1, "log2_xcd_chunk": 0, "grid": 4, "pace": 0}
@@ -252,7 +260,9 @@ def test_binary32_plans(A):
         assert p["path"] == "vector" and p["block"] * p["vectors_per_lane"] * 4 >= H and p["block"] <= 1024
     assert A.astra_plan_fused_add_rmsnorm(4, 4098, True, dtype=F32)[1].as_dict()["path"] == "phased"    # H % 4 != 0
     assert A.astra_plan_fused_add_rmsnorm(4, 4098, 0, dtype=F32)[1].as_dict()["path"] == "ragged"
-    assert A.astra_plan_fused_add_rmsnorm(4, 4100, True, dtype=F32)[1].as_dict()["path"] == "vector"    # H % 4 == 0
+    assert A.astra_plan_fused_add_rmsnorm(4, 4128, True, dtype=F32)[1].as_dict()["path"] == "vector"    # H % 4 == 0, whole lines
+    assert A.astra_plan_fused_add_rmsnorm(4, 4100, True, dtype=F32)[1].as_dict()["path"] == "vector"
+    assert A.astra_plan_fused_add_rmsnorm(8192, 4100, True, dtype=F32)[1].as_dict()["path"] == "phased"  # H % 4 == 0, no whole lines
     assert A.astra_plan_fused_add_rmsnorm(4, 32768, True, dtype=F32)[1].as_dict()["path"] == "generic"  # > 4096 vectors
     s = A.astra_plan_silu_and_mul(4096, 14336, True, dtype=F32)[1].as_dict()
     assert s["path"] == "vector" and s["block"] == 64 and s["grid"] * s["block"] >= 4096 * 14336 // 4

@@ -205,7 +205,9 @@ def test_merge_tile_shapes(A, T, NH, D, dt):
                                      (1030, 4098, 3), (600, 16383, 5), (40, 32761, 0), (7, 32775, 0), (300, 8199, 1),
                                      (2, 70000, 0), (1, 65536, 0),
                                      # offsets beyond one vector: the row starts in the middle of a 128-byte line
-                                     (70, 4097, 9), (3, 4096, 37), (130, 1001, 63), (40, 32705, 0), (5, 32705, 63), (3, 8, 57)])
+                                     (70, 4097, 9), (3, 4096, 37), (130, 1001, 63), (40, 32705, 0), (5, 32705, 63), (3, 8, 57),
+                                     # whole vectors but no whole 128-byte lines, aligned tensors: the same kernel
+                                     (5, 4104, 0), (300, 8200, 0), (130, 11016, 0), (70, 2056, 0), (8200, 2056, 0), (8192, 4104, 0)])
 def test_rmsnorm_ragged_and_generic_paths_and_canaries(A, T, H, off, dt):
     _say(f"[parity] rmsnorm ragged/generic T={T} H={H} offset={off} {dt}")
     x, r, w = workloads.rmsnorm_inputs(T, H, dt, np.random.default_rng([4, T, H, off]), r_std=2.0)
@@ -214,7 +216,10 @@ def test_rmsnorm_ragged_and_generic_paths_and_canaries(A, T, H, off, dt):
     wd, ww = padded(w, dt, offset_elems=off)
     # x and r carry the same offset, so they are in step with each other: the phased kernel (aligned chunks)
     st, info = A.astra_plan_fused_add_rmsnorm(T, H, 1 if off == 0 else 2)
-    assert info.as_dict()["path"] == ("generic" if H < 8 or H // 8 > 4096 else "phased" if (H + 63 + 7) // 8 <= 4096 else "ragged")
+    if H % 8 or off:
+        assert info.as_dict()["path"] == ("generic" if H < 8 or H // 8 > 4096 else "phased" if (H + 63 + 7) // 8 <= 4096 else "ragged")
+    else:  # aligned tensors, rows of whole vectors
+        assert info.as_dict()["path"] == ("generic" if H // 8 > 4096 else "phased" if T >= 8192 and H * 2 % 128 else "vector")
     A.fused_add_rmsnorm(xd, rd, wd, 1e-5)
     torch.cuda.synchronize()
     y_ref, res_ref = O.fused_add_rmsnorm(x, r, w, 1e-5, dt)
