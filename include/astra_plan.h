@@ -27,7 +27,9 @@ typedef enum {
                                lanes own the 16-byte aligned chunks of memory a row covers, so all interior accesses are
                                aligned; the partial chunk at a row end element-wise.  fused_add_rmsnorm,
                                merge_attn_states_lse, and silu_and_mul with offset pointers and d a whole number of
-                               vectors; runs at nearly the vector path's rate */
+                               vectors; runs at nearly the vector path's rate.  fused_add_rmsnorm also takes it for
+                               16-byte aligned rows of whole vectors that are no whole number of 128-byte lines, on
+                               streaming grids: its chunks are counted from the line, so its waves stay on whole lines */
 } astra_path_t;
 
 typedef struct {

@@ -25,6 +25,8 @@ namespace astra {
 //   kPaceXBeforeR     the x vectors must have arrived before the r vectors are requested
 //   kPaceStoreGap     the residual store must have completed before the output store is issued
 // With PACE = 0 every request goes out as early as possible: the shortest dependent chain, used for few rows.
+// Both results go out through store_row_vec_in_place (device_common.h): non-temporal, and at device scope when the
+// row begins and ends on 128-byte lines.
 // The empty asm statements (`arrive`) consume the loaded registers at a chosen point, which fixes where the wait
 // for that load is placed; no instruction is emitted for them.  All loads are consumed before the arithmetic
 // starts, so the compiler has no reason to add a wait of its own later on.
