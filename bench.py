@@ -21,7 +21,7 @@ taken inside the timed region on the launch stream; `kernels` carries the same f
     python bench.py --decode         # decode-sized launches replayed from a HIP graph
     python bench.py --prefill        # prefill-chunk shapes (T 512..4096, LLaMA dimensions) from a HIP graph, cold
     python bench.py --vs-eager       # the step's three workloads written with plain PyTorch tensor ops, for context
-    python bench.py --ragged         # odd row lengths: ragged kernels vs vector and element-wise kernels
+    python bench.py --ragged         # odd row lengths and offset pointers: chunked kernels vs vector and element-wise kernels
     python bench.py --fit            # t = a + bytes/BW over a T sweep: fixed cost per launch and streaming rate, kernels and probes
     python bench.py --pacing         # fused_add_rmsnorm request pacing A/B over buffer placements (the launch policy's table)
 """
@@ -781,8 +781,9 @@ def run_prefill(args):
 
 
 def run_ragged(args):
-    """Row lengths that are no whole number of 16-byte vectors: the ragged kernels against the vector kernels on the
-    nearest aligned shape and against the plain element-wise kernels (ASTRA_VARIANT_ELEMENT_WISE) on the same shape.
+    """Row lengths that are no whole number of 16-byte vectors, and offset pointers: what the library runs on them (the
+    kernels that work on aligned chunks of memory) against the vector kernels on the nearest aligned shape and against
+    the plain element-wise kernels (ASTRA_VARIANT_ELEMENT_WISE) on the same shape.
     T = 16384, bf16; 5 warm-up + 50 launches between one HIP-event pair, alternating over two buffer sets (every set
     is larger than the last-level cache, so the figures are cold)."""
     import torch
@@ -1173,7 +1174,7 @@ def main():
     ap.add_argument("--kway", action="store_true", help="K-way merge vs a chain of two-way merges")
     ap.add_argument("--decode", action="store_true", help="decode-sized launches replayed from a HIP graph")
     ap.add_argument("--prefill", action="store_true", help="prefill-chunk shapes replayed from a HIP graph, cold")
-    ap.add_argument("--ragged", action="store_true", help="odd row lengths: ragged vs vector vs element-wise kernels")
+    ap.add_argument("--ragged", action="store_true", help="odd row lengths and offset pointers: chunked vs vector vs element-wise kernels")
     ap.add_argument("--vs-eager", action="store_true",
                     help="context: the step workloads through this library and through plain PyTorch tensor ops")
     ap.add_argument("--fit", action="store_true", help="fixed cost per launch and streaming rate: T sweeps of kernels and probes")

@@ -18,16 +18,18 @@
  *     never touches the device.  T == 0 is valid and does nothing.
  *   - Pointers must be aligned to their element size (2 or 4 bytes, scores 4 bytes).  The fast path needs
  *     16-byte aligned pointers and a row length that is a multiple of 16 bytes (8 16-bit or 4 binary32
- *     elements); anything else is served by other paths that compute the same thing: when the activation tensors of
- *     a call are in step with each other (congruent modulo 16 bytes, as all 16-byte aligned dense tensors are),
- *     fused_add_rmsnorm and merge_attn_states_lse work on the 16-byte aligned chunks of memory the rows cover, at
- *     nearly the fast path's rate, and so does silu_and_mul when d is a whole number of vectors (with any other d
- *     its two input halves are out of step with each other); otherwise 16-byte accesses at element alignment; plain element-wise kernels for
- *     fused_add_rmsnorm rows of more than 4096 vectors or less than one and for inputs beyond 2^31 vectors.  Equal up
- *     to the order of binary32 roundings; the residual of fused_add_rmsnorm is bit-identical on every path.
- *   - Nothing outside a tensor is ever written.  The chunked paths READ whole 16-byte aligned chunks, so at the two
- *     ends of a tensor that does not start or end on the 16-byte grid they read up to 14 bytes outside it; such a
- *     read stays inside the 16-byte aligned block (hence the page) that holds the tensor's first or last element.
+ *     elements); anything else is served by other paths that compute the same thing.  The usual one works on the
+ *     16-byte aligned chunks of memory the OUTPUT covers, at nearly the fast path's rate: silu_and_mul and
+ *     merge_attn_states_lse for any element-aligned dense tensors with rows (d, head_dim) of at least one vector,
+ *     fused_add_rmsnorm when its activation tensors are in step with each other (congruent modulo 16 bytes, as all
+ *     16-byte aligned dense tensors are).  Otherwise 16-byte accesses at element alignment (fused_add_rmsnorm tensors
+ *     out of step, rows under one vector), and plain element-wise kernels for fused_add_rmsnorm rows of more than 4096
+ *     vectors or less than one and for inputs beyond 2^31 vectors.  Equal up to the order of binary32 roundings; the
+ *     residual of fused_add_rmsnorm is bit-identical on every path.
+ *   - Nothing outside a tensor is ever written.  One path READS outside: the chunked path of fused_add_rmsnorm loads
+ *     whole 16-byte aligned chunks, so at the two ends of a tensor that does not start or end on the 16-byte grid it
+ *     reads up to 14 bytes outside it; such a read stays inside the 16-byte aligned block (hence the page) that holds
+ *     the tensor's first or last element.
  *   - Element counts (T*H, T*2d, T*num_heads*head_dim) may exceed 2^31; they must fit in int64.
  */
 #ifndef ASTRA_H

@@ -19,15 +19,17 @@ typedef enum {
     ASTRA_PATH_VECTOR = 1,  /* 16-byte-per-lane fast path */
     ASTRA_PATH_GENERIC = 2, /* element-wise path: rmsnorm rows of more than 4096 vectors or less than one, inputs beyond
                                the 32-bit vector index */
-    ASTRA_PATH_RAGGED = 3,  /* row lengths that are no whole number of vectors, or pointers that are only element
-                               aligned, the tensors of the call at unrelated offsets into the 16-byte grid: 16-byte
-                               accesses at element alignment, the partial last vector element-wise */
-    ASTRA_PATH_PHASED = 4   /* the same row lengths and pointers, but the activation tensors of the call in step with
-                               each other (congruent modulo 16 bytes -- every dense call on 16-byte aligned tensors is):
-                               lanes own the 16-byte aligned chunks of memory a row covers, so all interior accesses are
-                               aligned; the partial chunk at a row end element-wise.  fused_add_rmsnorm,
-                               merge_attn_states_lse, and silu_and_mul with offset pointers and d a whole number of
-                               vectors; runs at nearly the vector path's rate.  fused_add_rmsnorm also takes it for
+    ASTRA_PATH_RAGGED = 3,  /* 16-byte accesses at element alignment, loads and stores alike, the partial last vector of a row
+                               element-wise: fused_add_rmsnorm with its activation tensors at unrelated offsets into the
+                               16-byte grid; silu_and_mul and merge_attn_states_lse with rows (d, head_dim) under one
+                               vector, row-strided views, or more than 2^31 (2^32) elements */
+    ASTRA_PATH_PHASED = 4   /* row lengths that are no whole number of vectors, or pointers that are only element aligned:
+                               lanes own the 16-byte aligned chunks of memory the output covers, so every store is an
+                               aligned one (the partial chunk at an end element-wise); runs at nearly the vector path's
+                               rate.  silu_and_mul and merge_attn_states_lse: any dense tensors with rows of at least
+                               one vector, loads at element alignment.  fused_add_rmsnorm (in place, so loads and stores
+                               share their chunks): activation tensors in step with each other (congruent modulo 16
+                               bytes -- every dense call on 16-byte aligned tensors is); it also takes this path for
                                16-byte aligned rows of whole vectors that are no whole number of 128-byte lines, on
                                streaming grids: its chunks are counted from the line, so its waves stay on whole lines */
 } astra_path_t;
@@ -57,7 +59,8 @@ enum {
 
 /* `dtype` is the storage type of the call.  `aligned16` tells how the tensor pointers of the call sit on the 16-byte
  * grid: 1 = every pointer is 16-byte aligned; 2 = not, but the activation tensors (input and residual; input and out;
- * v_a, v_b and v_out) are congruent modulo 16 bytes; 0 = element alignment only.  Each function validates like its operator does
+ * v_a, v_b and v_out) are congruent modulo 16 bytes; 0 = element alignment only (1 against the rest decides for
+ * silu_and_mul and merge_attn_states_lse, 2 against 0 matters to fused_add_rmsnorm only).  Each function validates like its operator does
  * (ASTRA_ERR_NULL for `info`, ASTRA_ERR_SHAPE, ASTRA_ERR_DTYPE). */
 astra_status_t astra_plan_fused_add_rmsnorm(int64_t T, int64_t H, astra_dtype_t dtype, int aligned16,
                                             astra_launch_info_t* info);

@@ -213,7 +213,7 @@ void launch_silu(const astra_launch_info_t& li, void* out, const void* in, int64
             static_cast<E*>(out), static_cast<const E*>(in), T, d);
         return;
     }
-    if (li.path == ASTRA_PATH_PHASED) {  // x, g and the output all start `phase` elements past the 16-byte grid in every row
+    if (li.path == ASTRA_PATH_PHASED) {  // the aligned chunks of the output, `phase` elements past the 16-byte grid
         constexpr int N = Storage<DT>::kN;
         const int phase = (int)((reinterpret_cast<uintptr_t>(out) & 15u) / sizeof(E));
         const uint32_t chunks = (uint32_t)((T * d + phase + N - 1) / N);
@@ -289,9 +289,9 @@ void launch_merge(const astra_launch_info_t& li, void* v_out, float* lse_out, co
             (uint32_t)(pairs * dvr), dvr, D, make_fastdiv(dvr));
         return;
     }
-    if (li.path == ASTRA_PATH_PHASED) {  // the three value tensors share one phase (the plan made sure): aligned chunks
+    if (li.path == ASTRA_PATH_PHASED) {  // the aligned chunks of the output
         constexpr int N = Storage<DT>::kN;
-        const int phase = (int)((reinterpret_cast<uintptr_t>(v_a) / sizeof(E)) & (N - 1));
+        const int phase = (int)((reinterpret_cast<uintptr_t>(v_out) / sizeof(E)) & (N - 1));
         const int64_t n = pairs * D;
         merge_attn_states_lse_phased_kernel<DT, kNTLoad, kNTStore><<<dim3((uint32_t)li.grid), dim3(256), 0, stream>>>(
             static_cast<E*>(v_out), lse_out, static_cast<const E*>(v_a), lse_a, static_cast<const E*>(v_b), lse_b, (uint32_t)n,

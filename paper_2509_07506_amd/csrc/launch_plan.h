@@ -372,10 +372,11 @@ inline astra_status_t plan_silu(int64_t T, int64_t d, int eb, int align, astra_l
         const int64_t blocks = (T * dv + span - 1) / span;
         const int lc = fit_chunk_log2(blocks, kFlatChunkLog2, kFlatChunkMinBlocks * (256 / block));
         *info = launch_info(ASTRA_PATH_VECTOR, block, kSiluUnroll, lc, pad_grid(blocks, lc), 0, 0);
-    } else if (!wide_only && align == kAlignPhased && d % ne == 0 && T * d <= kMaxVecIndex) {
-        // input and output offset from the 16-byte grid alike: the aligned chunks the output covers, one more than
-        // its vectors (silu_and_mul_phased_kernel); flat output elements are indexed with 32 bits
-        const int64_t chunks = T * dv + 1;
+    } else if (!wide_only && d >= ne && T * d <= kMaxVecIndex) {
+        // any other dense call with rows of at least one vector: the aligned chunks of memory the output covers, at
+        // most one more than ceil(T * d / N) (silu_and_mul_phased_kernel: aligned stores, loads at element
+        // alignment); flat output elements are indexed with 32 bits
+        const int64_t chunks = (T * d + ne - 1) / ne + 1;
         const int block = flat_block(chunks);
         const int64_t blocks = (chunks + block - 1) / block;
         const int lc = fit_chunk_log2(blocks, kFlatChunkLog2, kFlatChunkMinBlocks * (256 / block));
@@ -408,9 +409,10 @@ inline astra_status_t plan_merge(int64_t T, int64_t NH, int64_t D, int eb, int a
         const int lc = fit_chunk_log2(blocks, kFlatChunkLog2, kFlatChunkMinBlocks * (256 / block));
         *info = launch_info(ASTRA_PATH_VECTOR, block, kMergeUnroll, lc, pad_grid(blocks, lc), 0, 0, kVecBytes,
                             !wide_only && pairs * dvec < kSmallFlatVecs ? 0 : 1);
-    } else if (!wide_only && align != kAlignNone && D >= ne && n < (int64_t(1) << 32)) {
-        // head_dim or pointers off the 16-byte grid, the three dense value tensors in step with each other: one lane per
-        // aligned chunk of the flat tensors, at most one more chunk than whole vectors (merge_attn_states_lse_phased_kernel)
+    } else if (!wide_only && D >= ne && n < (int64_t(1) << 32)) {
+        // head_dim or pointers off the 16-byte grid, dense tensors: one lane per aligned chunk of the flat output, at
+        // most one more chunk than whole vectors (merge_attn_states_lse_phased_kernel: aligned stores, loads at
+        // element alignment)
         const int64_t blocks = ((n + ne - 1) / ne + 1 + 255) / 256;
         const int lc = fit_chunk_log2(blocks, kFlatChunkLog2, kFlatChunkMinBlocks);
         *info = launch_info(ASTRA_PATH_PHASED, 256, 1, lc, pad_grid(blocks, lc), 0, 0);

@@ -164,15 +164,17 @@ __global__ __launch_bounds__(256) void merge_attn_states_lse_ragged_kernel(
     if (jv == 0) lse_out[pair] = w.lse;
 }
 
-// Phased path: head_dim no whole number of vectors (or pointers offset by some elements), with v_a, v_b and v_out dense
-// and congruent modulo 16 bytes, and head_dim >= N.  The three value tensors are then flat arrays at one common phase,
-// and the work is the list of 16-byte aligned chunks of memory they cover: lane c owns flat elements
-// [c*N - phase, c*N - phase + N), moved with aligned 16-byte accesses exactly like the fast path; only the first and
-// the last chunk of the whole tensor can be partial (element by element).  A chunk can straddle the end of a (token,
-// head) pair -- at most one, since head_dim >= N -- so a lane evaluates the weights of the pair of its first and of
-// its last element and takes, per element, those of the pair the element belongs to; the lane that holds a pair's
-// first element stores that pair's S_out.  (An unaligned 16-byte access per lane, as in the ragged kernel above,
-// costs 25-30 % of the streaming rate on MI355X.)
+// Phased path: head_dim no whole number of vectors, or pointers offset by some elements; dense tensors, head_dim >= N.
+// The work is the list of 16-byte aligned chunks of memory the OUTPUT covers: lane c owns flat elements
+// [c*N - phase, c*N - phase + N), `phase` = v_out's offset into the 16-byte grid in elements, and stores them with one
+// aligned 16-byte access; v_a and v_b are loaded with 16-byte accesses at element alignment (aligned ones whenever the
+// inputs are in step with the output, as all 16-byte aligned tensors are).  It is the unaligned store that costs on
+// MI355X: a kernel that also stores at element alignment, like the ragged one above, runs 25-30 % below the fast path,
+// unaligned loads measure the same as aligned ones.  Only the first and the last chunk of the whole tensor can be
+// partial (element by element; nothing outside a tensor is read or written).  A chunk can straddle the end of a
+// (token, head) pair -- at most one, since head_dim >= N -- so a lane evaluates the weights of the pair of its first
+// and of its last element and takes, per element, those of the pair the element belongs to; the lane that holds a
+// pair's first element stores that pair's S_out.
 template <int DT, bool NTL, bool NTS>
 __global__ __launch_bounds__(256) void merge_attn_states_lse_phased_kernel(
     typename Storage<DT>::elem_t* v_out, float* lse_out, const typename Storage<DT>::elem_t* v_a, const float* lse_a,
@@ -188,9 +190,9 @@ __global__ __launch_bounds__(256) void merge_attn_states_lse_phased_kernel(
     const uint32_t last = e0 + N <= (int64_t)n_elems ? (uint32_t)(e0 + N - 1) : n_elems - 1u;
     const uint32_t p0 = by_D.div(first), p1 = by_D.div(last);
     u32x4 av, bv;
-    if (whole) {
-        av = load_vec<NTL>(reinterpret_cast<const u32x4*>(v_a + e0));
-        bv = load_vec<NTL>(reinterpret_cast<const u32x4*>(v_b + e0));
+    if (whole) {  // (aligned whenever the input is in step with the output)
+        av = load_vec_elem_aligned<DT, NTL>(v_a + e0);
+        bv = load_vec_elem_aligned<DT, NTL>(v_b + e0);
     } else {
         av = load_chunk_partial<DT>(v_a, n_elems, e0);
         bv = load_chunk_partial<DT>(v_b, n_elems, e0);

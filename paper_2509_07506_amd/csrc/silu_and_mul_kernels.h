@@ -109,21 +109,22 @@ __global__ __launch_bounds__(256) void silu_and_mul_small_kernel(u32x2* __restri
     out[o] = pack_half_vec<DT>(r);
 }
 
-// Phased path: d a whole number of vectors, dense tensors, `in` and `out` offset from the 16-byte grid by the same
-// `phase` elements (0 < phase < N; a view into a larger allocation, say).  Every row of x, of g and of out then starts at
-// that phase, and the work is the list of 16-byte aligned chunks of memory the OUTPUT covers: lane c owns flat output
-// elements [c*N - phase, c*N - phase + N) and moves them with aligned 16-byte accesses like the fast path.  All but
-// one chunk per row lie inside one row (two aligned loads, one aligned store).  The chunk across the end of row t holds
-// the last k = phase elements of row t and the first N - k of row t + 1; its operands sit in three aligned chunks of
-// the input, because the chunk that ends x's row t starts g's row t, and so on:
+// Phased path: dense tensors, any d >= N and any element-aligned pointers.  The work is the list of 16-byte aligned
+// chunks of memory the OUTPUT covers: lane c owns flat output elements [c*N - phase, c*N - phase + N), `phase` = the
+// output pointer's offset into the 16-byte grid in elements, and stores them with one aligned 16-byte access.  Its
+// operands are loaded with 16-byte accesses at element alignment: on MI355X it is the unaligned STORE that costs (the
+// ragged kernel below, which also stores at element alignment, runs at 0.91-0.95 of the fast path's rate on odd d;
+// this kernel at 0.98-0.99: T=16384, bf16, d=11009 78.2 -> 83.3 % of the HBM peak, d=11012 80.3 -> 84.1 %, d=14337
+// 78.9 -> 84.7 %, d=11008 behind offset pointers 73.1 -> 81.3 %; aligned loads measured the same as unaligned ones).
+// All but one chunk per row lie inside one row (two loads, one store).  The chunk across the end of row t holds the
+// last k elements of row t and the first N - k of row t + 1 (d >= N: never a third row); its operands sit in three
+// 16-byte pieces of the input, because what follows x's row t in memory is g's row t, and so on:
 //     A1 at x[t] + d - k:   x[t, d-k..d) | g[t, 0..N-k)
 //     A2 at g[t] + d - k:   g[t, d-k..d) | x[t+1, 0..N-k)
 //     A3 at x[t+1] + d - k: x[t+1, d-k..d) | g[t+1, 0..N-k)
 // so positions i < k are SiLU(A1[i]) * A2[i] and positions i >= k are SiLU(A2[i]) * A3[i]: one load more, still one
-// aligned store.  Only the first and the last chunk of the whole output are stored element by element (their other
-// positions lie outside the tensor; the aligned loads there stay inside the 16-byte block that holds a valid element).
-// (The ragged kernel below runs the same inputs with 16-byte accesses at element alignment, at about 0.83 of the fast
-// path's rate on MI355X.)
+// aligned store.  The first and the last chunk of the whole output (positions outside the tensor) go element by
+// element, so nothing outside either tensor is read or written.
 template <int DT, bool NTL, bool NTS, int BLOCK>
 __global__ __launch_bounds__(BLOCK) void silu_and_mul_phased_kernel(typename Storage<DT>::elem_t* out,
                                                                     const typename Storage<DT>::elem_t* __restrict__ in,
@@ -145,8 +146,8 @@ __global__ __launch_bounds__(BLOCK) void silu_and_mul_phased_kernel(typename Sto
     float x[N], g[N], o[N];
     if (k >= N) {  // inside row t
         const E* px = in + (t * 2 * (int64_t)d + (d - k));
-        const u32x4 xv = load_vec<NTL>(reinterpret_cast<const u32x4*>(px));
-        const u32x4 gv = load_vec<NTL>(reinterpret_cast<const u32x4*>(px + d));
+        const u32x4 xv = load_vec_elem_aligned<DT, NTL>(px);
+        const u32x4 gv = load_vec_elem_aligned<DT, NTL>(px + d);
         unpack_vec<DT>(xv, x);
         unpack_vec<DT>(gv, g);
 #pragma unroll
@@ -154,24 +155,36 @@ __global__ __launch_bounds__(BLOCK) void silu_and_mul_phased_kernel(typename Sto
         store_vec<NTS>(reinterpret_cast<u32x4*>(out + f0), pack_vec<DT>(o));
         return;
     }
-    // across the end of row t (rows -1 and T do not exist: their positions are neither loaded for nor stored)
-    const bool have_t = t >= 0, have_next = t + 1 < (int64_t)T;
+    if (t < 0 || t + 1 >= (int64_t)T) {
+        // the first or the last chunk of the output: some of its positions lie outside the tensor (rows -1 and T do
+        // not exist), so these two lanes of the grid go element by element
+#pragma unroll
+        for (int e = 0; e < N; ++e) {
+            const int64_t f = f0 + e;
+            if (f >= 0 && f < (int64_t)T * d) {
+                const int64_t row = e < k ? t : t + 1, col = e < k ? (int64_t)d - k + e : e - k;
+                const E* pr = in + row * 2 * (int64_t)d;
+                out[f] = Storage<DT>::narrow(silu_fast(Storage<DT>::widen(pr[col])) * Storage<DT>::widen(pr[d + col]));
+            }
+        }
+        return;
+    }
+    // across the end of row t
     const E* a2 = in + ((t + 1) * 2 * (int64_t)d - k);
-    const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
-    const u32x4 v1 = have_t ? load_vec<NTL>(reinterpret_cast<const u32x4*>(a2 - d)) : zero;
-    const u32x4 v2 = load_vec<NTL>(reinterpret_cast<const u32x4*>(a2));
-    const u32x4 v3 = have_next ? load_vec<NTL>(reinterpret_cast<const u32x4*>(a2 + d)) : zero;
+    const u32x4 v1 = load_vec_elem_aligned<DT, NTL>(a2 - d);
+    const u32x4 v2 = load_vec_elem_aligned<DT, NTL>(a2);
+    const u32x4 v3 = load_vec_elem_aligned<DT, NTL>(a2 + d);
     float m[N];
     unpack_vec<DT>(v1, x);
     unpack_vec<DT>(v2, m);
     unpack_vec<DT>(v3, g);
 #pragma unroll
     for (int e = 0; e < N; ++e) o[e] = e < k ? silu_fast(x[e]) * m[e] : silu_fast(m[e]) * g[e];
-    if (have_t && have_next) store_vec<NTS>(reinterpret_cast<u32x4*>(out + f0), pack_vec<DT>(o));
-    else store_chunk_partial<DT>(out, (int64_t)T * d, f0, o);
+    store_vec<NTS>(reinterpret_cast<u32x4*>(out + f0), pack_vec<DT>(o));
 }
 
-// Ragged path: any d, pointers and row strides only element aligned (dense tensors: out_stride = d, in_stride = 2d).
+// Ragged path (rows shorter than a vector, row-strided views, tensors beyond the phased kernel's 32-bit element index):
+// any d, pointers and row strides only element aligned (dense tensors: out_stride = d, in_stride = 2d).
 // A row is dv = ceil(d/N) vectors, the last one possibly partial; one lane per vector, row and column from a
 // per-lane fast division, 64-bit element offsets.  Full vectors are 16-byte accesses at element alignment; the
 // partial one reads the whole vector that ends at the row end and stores its own elements one by one.

@@ -2,7 +2,7 @@
 // stream come from the HIP runtime directly (hipMalloc / hipStreamCreate), the operators from libastra_hip.so,
 // the expectations from the CPU oracle library (test infrastructure).  Bars as everywhere: residual of
 // fused_add_rmsnorm bit-exact; other 16-bit outputs within rtol 1.6e-2 / atol 1e-2 (bf16), 2e-3 / 1e-3 (fp16);
-// binary32 storage within 1e-4 / 1e-6; lse within 1e-4.
+// binary32 storage within 2e-5 / 1e-6; lse within 1e-4.
 //
 // Build (done by __graft_entry__.build()):
 //   hipcc -O2 -std=c++17 -I include tests/c_abi/check_abi.cpp -o tests/c_abi/check_abi
@@ -84,7 +84,7 @@ uint16_t narrow(float f, int dt) { return dt == ASTRA_BF16 ? oracle_f32_to_bf16(
 struct Tol {
     double rtol, atol;
 };
-Tol tol_of(int dt) { return dt == ASTRA_BF16 ? Tol{1.6e-2, 1e-2} : dt == ASTRA_F16 ? Tol{2e-3, 1e-3} : Tol{1e-4, 1e-6}; }
+Tol tol_of(int dt) { return dt == ASTRA_BF16 ? Tol{1.6e-2, 1e-2} : dt == ASTRA_F16 ? Tol{2e-3, 1e-3} : Tol{2e-5, 1e-6}; }
 
 bool close(double got, double ref, Tol t)
 {
@@ -349,7 +349,8 @@ void check_host_queries()
     expect(astra_plan_fused_add_rmsnorm(32768, 8192, ASTRA_BF16, 1, &li) == ASTRA_OK && li.path == ASTRA_PATH_VECTOR &&
                li.block == 1024 && li.grid == 32768,
            "plan of the headline rmsnorm shape");
-    expect(astra_plan_silu_and_mul(3, 100, ASTRA_F16, 1, &li) == ASTRA_OK && li.path == ASTRA_PATH_RAGGED, "plan of an odd silu shape");
+    expect(astra_plan_silu_and_mul(3, 100, ASTRA_F16, 1, &li) == ASTRA_OK && li.path == ASTRA_PATH_PHASED, "plan of an odd silu shape");
+    expect(astra_plan_silu_and_mul(3, 5, ASTRA_F16, 1, &li) == ASTRA_OK && li.path == ASTRA_PATH_RAGGED, "plan of a silu shape with rows under one vector");
     expect(astra_plan_merge_attn_states_lse(0, 4, 64, ASTRA_F16, 1, &li) == ASTRA_OK && li.path == ASTRA_PATH_NONE, "plan of an empty merge");
     int clk = 0, bits = 0;
     expect(astra_device_memory_info(0, &clk, &bits) == ASTRA_OK && clk > 0 && bits > 0, "device memory info");

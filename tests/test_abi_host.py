@@ -269,12 +269,13 @@ def test_binary32_plans(A):
     assert A.astra_plan_fused_add_rmsnorm(4, 32768, True, dtype=F32)[1].as_dict()["path"] == "generic"  # > 4096 vectors
     s = A.astra_plan_silu_and_mul(4096, 14336, True, dtype=F32)[1].as_dict()
     assert s["path"] == "vector" and s["block"] == 64 and s["grid"] * s["block"] >= 4096 * 14336 // 4
-    assert A.astra_plan_silu_and_mul(3, 1410, True, dtype=F32)[1].as_dict()["path"] == "ragged"
+    assert A.astra_plan_silu_and_mul(3, 1410, True, dtype=F32)[1].as_dict()["path"] == "phased"
+    assert A.astra_plan_silu_and_mul(3, 3, True, dtype=F32)[1].as_dict()["path"] == "ragged"            # rows under one vector
     assert A.astra_plan_silu_and_mul(3, 1412, True, dtype=F32)[1].as_dict()["path"] == "vector"
     m = A.astra_plan_merge_attn_states_lse(4096, 32, 128, True, dtype=F32)[1].as_dict()
     assert m["path"] == "vector" and m["block"] == 64 and m["grid"] * m["block"] == 4096 * 32 * 32
     assert A.astra_plan_merge_attn_states_lse(3, 5, 6, True, dtype=F32)[1].as_dict()["path"] == "phased"
-    assert A.astra_plan_merge_attn_states_lse(3, 5, 6, 0, dtype=F32)[1].as_dict()["path"] == "ragged"
+    assert A.astra_plan_merge_attn_states_lse(3, 5, 6, 0, dtype=F32)[1].as_dict()["path"] == "phased"
     assert A.astra_plan_merge_attn_states_lse(3, 5, 3, True, dtype=F32)[1].as_dict()["path"] == "ragged"     # head_dim under one vector
     assert A.astra_plan_merge_attn_states_lse(3, 5, 4, True, dtype=F32)[1].as_dict()["path"] == "vector"
     assert A.astra_plan_merge_attn_states_lse(3, 5, 4, True, dtype=7)[0] == 3
@@ -288,16 +289,19 @@ def test_silu_and_merge_plans(A):
     assert st == 0 and p["path"] == "vector"
     assert work <= p["grid"] * p["block"] * p["vectors_per_lane"] < work + (8 << p["log2_xcd_chunk"]) * 256
     assert p["grid"] % (8 << p["log2_xcd_chunk"]) == 0
-    assert A.astra_plan_silu_and_mul(3, 100, True)[1].as_dict() == {"path": "ragged", "block": 256, "vectors_per_lane": 1,
-                                                                    "log2_xcd_chunk": 0, "grid": 1, "pace": 0}   # 3 * 13 vectors
-    assert A.astra_plan_silu_and_mul(3, 1408, False)[1].as_dict()["path"] == "ragged"
-    # input and output offset from the 16-byte grid alike, d a whole number of vectors: aligned chunks of the output, one
-    # more than its vectors
+    # every other dense call with rows of at least one vector: the aligned chunks of memory the output covers (aligned
+    # stores, loads at element alignment), at most one more than its vectors; rows under one vector: 16-byte accesses at
+    # element alignment
+    assert A.astra_plan_silu_and_mul(3, 100, True)[1].as_dict() == {"path": "phased", "block": 256, "vectors_per_lane": 1,
+                                                                    "log2_xcd_chunk": 0, "grid": 1, "pace": 0}   # 38 + 1 chunks
+    assert A.astra_plan_silu_and_mul(3, 7, True)[1].as_dict() == {"path": "ragged", "block": 256, "vectors_per_lane": 1,
+                                                                  "log2_xcd_chunk": 0, "grid": 1, "pace": 0}
+    assert A.astra_plan_silu_and_mul(3, 1408, False)[1].as_dict()["path"] == "phased"
     ph = A.astra_plan_silu_and_mul(4096, 14336, 2)[1].as_dict()
     assert ph == {"path": "phased", "block": 64, "vectors_per_lane": 1, "log2_xcd_chunk": 8, "grid": 114688 + 2048, "pace": 0}
     assert A.astra_plan_silu_and_mul(3, 1408, 2)[1].as_dict() == {"path": "phased", "block": 256, "vectors_per_lane": 1,
                                                                   "log2_xcd_chunk": 0, "grid": 3, "pace": 0}
-    assert A.astra_plan_silu_and_mul(3, 1410, 2)[1].as_dict()["path"] == "ragged"          # the two halves of a row out of step
+    assert A.astra_plan_silu_and_mul(3, 1410, 2)[1].as_dict()["path"] == "phased" and A.astra_plan_silu_and_mul(3, 1410, 0)[1].as_dict()["path"] == "phased"
     assert A.astra_plan_silu_and_mul(1 << 17, 1 << 14, 2)[1].as_dict()["path"] == "phased"  # 2^31 output elements: the most
     assert A.astra_plan_silu_and_mul((1 << 17) + 1, 1 << 14, 2)[1].as_dict()["path"] == "ragged"
     assert A.astra_plan_silu_and_mul(1 << 20, (1 << 14) + 1, True)[1].as_dict()["path"] == "generic"
@@ -328,8 +332,8 @@ def test_silu_and_merge_plans(A):
         q = A.astra_plan_merge_attn_states_lse(T, 32, 128, True)[1].as_dict()
         assert q["block"] == block and q.get("non_temporal", 1) == nt and "access_bytes" not in q, (T, q)
     assert A.astra_plan_merge_attn_states_lse(3, 5, 4, True)[1].as_dict()["path"] == "ragged"                 # head_dim under one vector
-    assert A.astra_plan_merge_attn_states_lse(3, 5, 72, False)[1].as_dict()["path"] == "ragged"
-    # head_dim or pointers off the 16-byte grid, value tensors in step with each other: aligned chunks of the flat tensors
+    assert A.astra_plan_merge_attn_states_lse(3, 5, 72, False)[1].as_dict()["path"] == "phased"
+    # head_dim or pointers off the 16-byte grid: aligned chunks of the flat output (loads at element alignment)
     q = A.astra_plan_merge_attn_states_lse(257, 40, 129, True)[1].as_dict()
     assert q["path"] == "phased" and q["block"] == 256 and q["grid"] * 256 >= (257 * 40 * 129 + 7) // 8 + 1
     assert A.astra_plan_merge_attn_states_lse(3, 5, 72, 2)[1].as_dict()["path"] == "phased"

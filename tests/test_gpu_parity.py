@@ -281,7 +281,7 @@ def test_silu_paths_and_canaries(A, T, d, off, dt):
     out_init = np.full((T, d), 0x1234, np.uint16)
     od, ow = padded(out_init, dt, offset_elems=off)
     st, info = A.astra_plan_silu_and_mul(T, d, 1 if off % 8 == 0 else 2)
-    assert info.as_dict()["path"] == ("vector" if d % 8 == 0 and off % 8 == 0 else "phased" if d % 8 == 0 else "ragged")
+    assert info.as_dict()["path"] == ("vector" if d % 8 == 0 and off % 8 == 0 else "phased" if d >= 8 else "ragged")
     A.silu_and_mul(od, ad)
     torch.cuda.synchronize()
     assert_storage_close(to_bits(od), O.silu_and_mul(a, dt), dt, "out")
@@ -292,7 +292,8 @@ def test_silu_paths_and_canaries(A, T, d, off, dt):
 @pytest.mark.parametrize("dt", ["bf16", "f16"])
 @pytest.mark.parametrize("T,d,off_in,off_out", [(5, 1408, 1, 2), (300, 11008, 0, 3), (64, 8, 5, 0), (33, 1416, 7, 7)])
 def test_silu_input_and_output_at_unrelated_offsets(A, T, d, off_in, off_out, dt):
-    """input and output out of step with each other: 16-byte accesses at element alignment (the last case is in step)"""
+    """input and output out of step with each other: the aligned chunks of the output, loads at element alignment (the
+    last case is in step)"""
     _say(f"[parity] silu T={T} d={d} offsets in={off_in} out={off_out} {dt}")
     a = workloads.silu_inputs(T, d, dt, np.random.default_rng([66, T, d, off_in, off_out]))
     ad, aw = padded(a, dt, offset_elems=off_in)
@@ -333,7 +334,8 @@ def test_merge_paths_and_canaries(A, T, NH, D, off, dt):
 @pytest.mark.parametrize("T,NH,D,offs", [(3, 5, 100, (0, 1, 0)), (65, 40, 128, (1, 0, 0)), (257, 40, 129, (2, 5, 7)), (33, 5, 9, (0, 0, 3)),
                                          (100, 7, 132, (4, 4, 0)), (9, 3, 8, (1, 1, 2))])
 def test_merge_tensors_at_unrelated_offsets(A, T, NH, D, offs, dt):
-    """v_a, v_b and v_out each at an offset of its own into the 16-byte grid: the ragged kernel"""
+    """v_a, v_b and v_out each at an offset of its own into the 16-byte grid: the aligned chunks of the output, loads at
+    element alignment (head_dim >= 8; below that the ragged kernel)"""
     _say(f"[parity] merge mixed offsets T={T} NH={NH} D={D} offsets={offs} {dt}")
     va, la, vb, lb = workloads.merge_inputs(T, NH, D, dt, np.random.default_rng([15, T, NH, D]), empty_p=0.15)
     vad, vaw = padded(va, dt, offset_elems=offs[0])
