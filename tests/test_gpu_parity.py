@@ -732,6 +732,42 @@ def test_merge_beyond_2_31_elements(A):
     assert bool((lo[: n * B].view(torch.int32).view(n, B, NH) == lo[:B].view(torch.int32).unsqueeze(0)).all())
 
 
+def test_output_chunk_kernels_at_their_index_limit(A):
+    """silu_and_mul and merge_attn_states_lse on odd row lengths just below the 2^31 (2^32) flat output elements their
+    chunk kernels index with 32 bits: every row starts at another phase, the last chunks sit at the top of the index
+    range"""
+    dt, B = "bf16", 32
+    T, d = 1 << 16, 32767                                 # T*d = 2^31 - 65536 output elements
+    assert A.astra_plan_silu_and_mul(T, d, True)[1].as_dict()["path"] == "phased"
+    assert A.astra_plan_silu_and_mul(T + 3, d, True)[1].as_dict()["path"] == "ragged"
+    print(f"[parity] silu at the chunk kernel's limit T={T} d={d}", flush=True)
+    a = workloads.silu_inputs(B, d, dt, np.random.default_rng(54))
+    ad = _tile_rows(to_dev(a, dt), T // B).contiguous()
+    out = torch.empty((T, d), dtype=TORCH_DT[dt], device="cuda")
+    A.silu_and_mul(out, ad)
+    torch.cuda.synchronize()
+    assert_storage_close(to_bits(out[:B]), O.silu_and_mul(a, dt), dt, "silu out, first tile")
+    assert _all_tiles_equal(out, B)
+    del ad, out
+    torch.cuda.empty_cache()
+    T, NH, D = 1 << 17, 32, 1023                          # 2^22 pairs of 1023 elements: 2^32 - 2^22 elements
+    assert A.astra_plan_merge_attn_states_lse(T, NH, D, True)[1].as_dict()["path"] == "phased"
+    assert A.astra_plan_merge_attn_states_lse(T, NH, D + 2, True)[1].as_dict()["path"] == "ragged"
+    print(f"[parity] merge at the chunk kernel's limit T={T} NH={NH} D={D}", flush=True)
+    va, la, vb, lb = workloads.merge_inputs(B, NH, D, dt, np.random.default_rng(55), empty_p=0.05)
+    reps = T // B
+    vad, vbd = _tile_rows(to_dev(va, dt), reps).contiguous(), _tile_rows(to_dev(vb, dt), reps).contiguous()
+    lad, lbd = _tile_rows(torch.from_numpy(la).cuda(), reps).contiguous(), _tile_rows(torch.from_numpy(lb).cuda(), reps).contiguous()
+    vo, lo = torch.empty_like(vad), torch.empty_like(lad)
+    A.merge_attn_states_lse(vo, lo, vad, lad, vbd, lbd)
+    torch.cuda.synchronize()
+    vo_ref, lo_ref = O.merge_attn_states_lse(va, la, vb, lb, dt)
+    assert_storage_close(to_bits(vo[:B]), vo_ref, dt, "merge v_out, first tile")
+    assert_lse_close(lo[:B].cpu().numpy(), lo_ref, "merge lse_out, first tile")
+    assert _all_tiles_equal(vo, B)
+    assert bool((lo.view(torch.int32).view(reps, B, NH) == lo[:B].view(torch.int32).unsqueeze(0)).all())
+
+
 def test_graph_capture_and_replay(A):
     """The entry points only enqueue kernels on the caller's stream (no allocation, no synchronisation,
     no memset), so a HIP graph can capture them.  Replays are checked against the eager result several
