@@ -24,6 +24,7 @@ taken inside the timed region on the launch stream; `kernels` carries the same f
     python bench.py --ragged         # odd row lengths and offset pointers: chunked kernels vs vector and element-wise kernels
     python bench.py --fit            # t = a + bytes/BW over a T sweep: fixed cost per launch and streaming rate, kernels and probes
     python bench.py --pacing         # fused_add_rmsnorm request pacing A/B over buffer placements (the launch policy's table)
+    python bench.py --stores         # fused_add_rmsnorm store scope and line-grid decisions A/B over buffer placements
 """
 from __future__ import annotations
 
@@ -1008,6 +1009,52 @@ def run_pacing(args):
         print(json.dumps(out), flush=True)
 
 
+def run_stores(args):
+    """A/B of two store decisions of fused_add_rmsnorm, each on the same 12 placements of x and r inside one allocation,
+    one process, 2 warm-up + 10 launches between one event pair per cell (bf16; every cell launches on the same two
+    buffers, so tensors under the 256 MB last-level cache are measured warm, larger ones cold):
+    (1) rows on whole 128-byte lines: the library (plain non-temporal stores) against the same kernel with device-scope
+        stores (ASTRA_VARIANT_STORE_DEVICE_SCOPE_WHOLE_LINES), on tensors far larger than the cache and on cache-sized ones;
+    (2) rows of whole vectors that are no whole lines: the library (chunks counted from the line) against the fast
+        kernel with its waves across line boundaries (forced paces "none" and "gap") and against the fast kernel with
+        device-scope stores (ASTRA_VARIANT_STORE_DEVICE_SCOPE)."""
+    import torch
+
+    import paper_2509_07506_amd as astra
+
+    astra.load_library()
+    torch.cuda.set_device(0)
+    stream = torch.cuda.current_stream()
+    sh = stream.cuda_stream
+    arena = torch.empty(6 << 30, dtype=torch.uint8, device="cuda")
+    arena.view(torch.bfloat16).normal_()
+    MiB = 1 << 20
+    placements = [(i * 96 * MiB, 2560 * MiB + j * 164 * MiB) for i in (0, 1, 2) for j in (0, 1, 2, 3)]
+    on_lines = [(32768, 8192), (65536, 4096), (131072, 2048), (52428, 5120), (18724, 14336),     # 1 GiB of x and r: cold
+                (4096, 8192), (4096, 4096), (512, 8192), (257, 7168)]                             # 134 MB and less: warm
+    off_lines = [(16384, 4104), (16384, 5128), (16384, 8200), (16384, 11016)]
+    for group, shapes, variants in (
+            ("rows on whole lines", on_lines, (("library", 0), ("device_scope_stores", astra.ASTRA_VARIANT_STORE_DEVICE_SCOPE_WHOLE_LINES))),
+            ("rows across lines", off_lines, (("library", 0), ("fast_kernel_none", astra.ASTRA_VARIANT_PACE_NONE),
+                                              ("fast_kernel_gap", astra.ASTRA_VARIANT_PACE_STORE_GAP),
+                                              ("fast_kernel_device_scope_stores", astra.ASTRA_VARIANT_STORE_DEVICE_SCOPE)))):
+        for T, H in shapes:
+            res = {name: [] for name, _ in variants}
+            for off in placements:
+                for name, v in variants:
+                    launch, plan, nbytes, keep = _device_launcher(astra, "rmsnorm", {"T": T, "H": H}, 1, v, arena, off)
+                    res[name].append(batch_us(launch, stream, sh, 10, 2))
+            plan = astra.astra_plan_fused_add_rmsnorm(T, H, True)[1].as_dict()
+            out = {"group": group, "T": T, "H": H, "bytes": nbytes, "cache": "cold" if nbytes > (512 << 20) else "warm",
+                   "placements": len(placements), "library_plan": plan}
+            for name, v in res.items():
+                gains = [t - l for l, t in zip(res["library"], v)]       # positive: the library is faster
+                out[name] = {"mean_us": round(sum(v) / len(v), 2), "frac_of_peak": round(nbytes / (sum(v) / len(v)) / 1e3 / HBM_PEAK_GBS, 4),
+                             "library_faster_by_us": round(sum(gains) / len(gains), 2),
+                             "placements_library_faster": sum(g > 0 for g in gains)}
+            print(json.dumps(out), flush=True)
+
+
 def run_pacing_few_rounds(args):
     """The same A/B on grids of one to a few rounds of resident workgroups (prefill chunks), where the launch policy
     asks for "x before r" once a compute unit requests 48 KiB at once: forced "none", forced "x" and the library's
@@ -1179,6 +1226,7 @@ def main():
                     help="context: the step workloads through this library and through plain PyTorch tensor ops")
     ap.add_argument("--fit", action="store_true", help="fixed cost per launch and streaming rate: T sweeps of kernels and probes")
     ap.add_argument("--pacing", action="store_true", help="fused_add_rmsnorm request pacing A/B over buffer placements")
+    ap.add_argument("--stores", action="store_true", help="fused_add_rmsnorm store scope and line-grid decisions A/B over buffer placements")
     ap.add_argument("--few-rounds", action="store_true", help="with --pacing: grids of one to a few rounds (prefill chunks) instead")
     ap.add_argument("--rows", default=None, help="with --pacing: comma-separated row lengths instead of the full list")
     ap.add_argument("--ablation", action="store_true",
@@ -1190,6 +1238,8 @@ def main():
         sys.exit(2)
     if args.fit:
         run_fit(args)
+    elif args.stores:
+        run_stores(args)
     elif args.pacing and args.few_rounds:
         run_pacing_few_rounds(args)
     elif args.pacing:

@@ -129,7 +129,7 @@ typedef enum {
     ASTRA_PROBE_READ2 = 1,        /* a and b are read, nothing is written */
     ASTRA_PROBE_WRITE1 = 2,       /* c is written */
     ASTRA_PROBE_READ2_WRITE1 = 3, /* c <- a ^ b: the mix of silu_and_mul and merge_attn_states_lse */
-    ASTRA_PROBE_UPDATE2 = 4,      /* a <- a ^ b, b <- a + b, in place: the mix of fused_add_rmsnorm (and its store form) */
+    ASTRA_PROBE_UPDATE2 = 4,      /* a <- a ^ b, b <- a + b, in place: the mix of fused_add_rmsnorm */
     ASTRA_ENUM_SPANS_INT32(ASTRA_PROBE)
 } astra_probe_t;
 

@@ -39,6 +39,13 @@ typedef enum {
     ASTRA_VARIANT_PACE_STORE_GAP = 7,     /* output store held until the residual store has completed */
     ASTRA_VARIANT_PACE_X_BEFORE_R = 8,    /* x arrived before r is requested */
     ASTRA_VARIANT_PACE_WEIGHT_X_R = 9,    /* weight, then x, then r, one after the other */
+    /* fused_add_rmsnorm only, every storage type, the same shapes as variants 6 to 9: the tuned row kernel, paced as the
+       launch policy says, with its two stores at device scope (the line goes on to memory instead of staying dirty in
+       the L2) instead of plain non-temporal stores.  Not an optimisation of the paper: a choice this library measured
+       and decided against (a small gain on some tensors far larger than the last-level cache, a loss of 2-15 % on
+       cache-sized ones); the variants keep the measurement repeatable.  Same results as the tuned kernel. */
+    ASTRA_VARIANT_STORE_DEVICE_SCOPE_WHOLE_LINES = 10, /* for rows that begin and end on 128-byte lines only */
+    ASTRA_VARIANT_STORE_DEVICE_SCOPE = 11,             /* for every row (rows that share lines lose 15-25 % with it) */
     ASTRA_ENUM_SPANS_INT32(ASTRA_VARIANT)
 } astra_variant_t;
 

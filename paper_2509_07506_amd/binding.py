@@ -30,6 +30,8 @@ ASTRA_VARIANT_PACE_NONE = 6
 ASTRA_VARIANT_PACE_STORE_GAP = 7
 ASTRA_VARIANT_PACE_X_BEFORE_R = 8
 ASTRA_VARIANT_PACE_WEIGHT_X_R = 9
+ASTRA_VARIANT_STORE_DEVICE_SCOPE_WHOLE_LINES = 10
+ASTRA_VARIANT_STORE_DEVICE_SCOPE = 11
 ASTRA_ERR_VARIANT = 8
 
 _PKG = os.path.dirname(os.path.abspath(__file__))

@@ -38,7 +38,7 @@ int plan_align(int aligned16) { return aligned16 == 2 ? kAlignPhased : (aligned1
 template <int DT, int VPT, int MAXT, bool LDS_TREE = false, bool STRIDED = false>
 void launch_rmsnorm_row(const astra_launch_info_t& li, void* input, void* residual, const void* weight, int64_t T,
                         int64_t H, float eps, hipStream_t stream, void* y_out = nullptr, void* r_out = nullptr,
-                        RowViews views = RowViews{0, 0, 0, 0})
+                        RowViews views = RowViews{0, 0, 0, 0}, int store_scope = kStoreScopeNone)
 {
     const uint32_t hv = (uint32_t)(H / Storage<DT>::kN);
     u32x4* const in = static_cast<u32x4*>(input);
@@ -51,25 +51,25 @@ void launch_rmsnorm_row(const astra_launch_info_t& li, void* input, void* residu
     const int lc = li.log2_xcd_chunk;
     if (li.grid < T) {  // more rows than the grid limit: workgroups walk several rows
         fused_add_rmsnorm_row_kernel<DT, VPT, MAXT, kNTLoad, kNTStore, LDS_TREE, true, kPaceNone, STRIDED>
-            <<<grid, block, 0, stream>>>(in, res, w, T, hv, inv_h, eps, lc, yo, ro, views);
+            <<<grid, block, 0, stream>>>(in, res, w, T, hv, inv_h, eps, lc, yo, ro, views, store_scope);
         return;
     }
     switch (li.pace) {
         case kPaceStoreGap:
             fused_add_rmsnorm_row_kernel<DT, VPT, MAXT, kNTLoad, kNTStore, LDS_TREE, false, kPaceStoreGap, STRIDED>
-                <<<grid, block, 0, stream>>>(in, res, w, T, hv, inv_h, eps, lc, yo, ro, views);
+                <<<grid, block, 0, stream>>>(in, res, w, T, hv, inv_h, eps, lc, yo, ro, views, store_scope);
             return;
         case kPaceWeightFirst | kPaceXBeforeR:
             fused_add_rmsnorm_row_kernel<DT, VPT, MAXT, kNTLoad, kNTStore, LDS_TREE, false, kPaceWeightFirst | kPaceXBeforeR, STRIDED>
-                <<<grid, block, 0, stream>>>(in, res, w, T, hv, inv_h, eps, lc, yo, ro, views);
+                <<<grid, block, 0, stream>>>(in, res, w, T, hv, inv_h, eps, lc, yo, ro, views, store_scope);
             return;
         case kPaceXBeforeR:
             fused_add_rmsnorm_row_kernel<DT, VPT, MAXT, kNTLoad, kNTStore, LDS_TREE, false, kPaceXBeforeR, STRIDED>
-                <<<grid, block, 0, stream>>>(in, res, w, T, hv, inv_h, eps, lc, yo, ro, views);
+                <<<grid, block, 0, stream>>>(in, res, w, T, hv, inv_h, eps, lc, yo, ro, views, store_scope);
             return;
         default:
             fused_add_rmsnorm_row_kernel<DT, VPT, MAXT, kNTLoad, kNTStore, LDS_TREE, false, kPaceNone, STRIDED>
-                <<<grid, block, 0, stream>>>(in, res, w, T, hv, inv_h, eps, lc, yo, ro, views);
+                <<<grid, block, 0, stream>>>(in, res, w, T, hv, inv_h, eps, lc, yo, ro, views, store_scope);
             return;
     }
 }
@@ -178,10 +178,14 @@ void launch_rmsnorm(const astra_launch_info_t& li, void* input, void* residual, 
         launch_rmsnorm_short<DT, false>(li, input, residual, weight, T, H, eps, stream);
         return;
     }
+    // (ablation: device-scope stores instead of plain non-temporal ones)
+    const int scope = variant == ASTRA_VARIANT_STORE_DEVICE_SCOPE_WHOLE_LINES ? kStoreScopeWholeLineRows
+                      : variant == ASTRA_VARIANT_STORE_DEVICE_SCOPE ? kStoreScopeAlways : kStoreScopeNone;
+    const RowViews none{0, 0, 0, 0};
     switch (li.vectors_per_lane) {
-        case 1: launch_rmsnorm_row<DT, 1, 1024>(li, input, residual, weight, T, H, eps, stream); break;
-        case 2: launch_rmsnorm_row<DT, 2, 1024>(li, input, residual, weight, T, H, eps, stream); break;
-        default: launch_rmsnorm_row<DT, 4, 1024>(li, input, residual, weight, T, H, eps, stream); break;
+        case 1: launch_rmsnorm_row<DT, 1, 1024>(li, input, residual, weight, T, H, eps, stream, nullptr, nullptr, none, scope); break;
+        case 2: launch_rmsnorm_row<DT, 2, 1024>(li, input, residual, weight, T, H, eps, stream, nullptr, nullptr, none, scope); break;
+        default: launch_rmsnorm_row<DT, 4, 1024>(li, input, residual, weight, T, H, eps, stream, nullptr, nullptr, none, scope); break;
     }
 }
 
@@ -449,6 +453,9 @@ static astra_status_t run_fused_add_rmsnorm(void* input, void* residual, const v
         static const int forced[4] = {kPaceNone, kPaceStoreGap, kPaceXBeforeR, kPaceWeightFirst | kPaceXBeforeR};
         li.pace = forced[variant - ASTRA_VARIANT_PACE_NONE];
         variant = ASTRA_VARIANT_TUNED;
+    } else if (variant == ASTRA_VARIANT_STORE_DEVICE_SCOPE_WHOLE_LINES || variant == ASTRA_VARIANT_STORE_DEVICE_SCOPE) {
+        // the tuned row kernel, paced as the plan says, with device-scope stores: same shapes as the forced paces
+        if (T > 0 && (li.path != ASTRA_PATH_VECTOR || li.rows_per_block != 0 || li.grid < T)) return ASTRA_ERR_VARIANT;
     } else if (variant != ASTRA_VARIANT_TUNED) {
         if (dtype == ASTRA_F32) return ASTRA_ERR_VARIANT;
         if (variant != ASTRA_VARIANT_SCALAR_LOADS && variant != ASTRA_VARIANT_LDS_TREE_REDUCTION) return ASTRA_ERR_VARIANT;

@@ -42,35 +42,36 @@ __device__ __forceinline__ void store_vec(u32x4* p, u32x4 v)
     else *p = v;
 }
 
-// Store of an in-place update (the destination line was read by this workgroup a moment ago): vector `v` of the row
-// that starts at `row` and holds `row_vecs` vectors.  NT: non-temporal like every activation store, and in addition at
-// device scope (the `sc1` bit of the CDNA3/CDNA4 memory instructions), which sends the line on to memory instead of
-// leaving it dirty in the L2.  Measured on MI355X in the fused_add_rmsnorm row kernel against the plain non-temporal
-// store, cold: T=32768 H=8192 83.5 -> 84.0 % of the HBM peak, T=65536 H=4096 83.5 -> 84.8 %, T=16384 H=5120
-// 81.1 -> 81.3 %, T=4096 H=8192 78.5 -> 79.0 %, T=4096 H=4096 72.7 -> 74.2 %; with device scope but without the
-// non-temporal hint 1-2 points lower than either.  Stores to lines the kernel has not read (silu_and_mul,
-// merge_attn_states_lse) gain nothing from it (-0.5 to +0.4 points) and keep the plain non-temporal store.  A row that
-// shares its first or last 128-byte line with the neighbouring row loses heavily with it (T=16384: H=4104 77.5 -> 61 %,
-// H=8200 73.9 -> 59 %, H=4096 sixteen bytes off the line 77 -> 61 %; the phased kernel 10-15 %), so the device-scope
-// form is used for rows that begin and end on line boundaries only, and every other row keeps the plain non-temporal
-// store.
+// Store of vector `v` of the row that starts at `row` and holds `row_vecs` vectors, for the fused_add_rmsnorm row
+// kernel.  `scope` (uniform over the wave) 0, what the library uses: the plain non-temporal store.  The other two
+// values exist for the ablation entry point: the same store at device scope (the `sc1` bit of the CDNA3/CDNA4 memory
+// instructions), which sends the line on to memory instead of leaving it dirty in the L2 -- 1: for rows that begin
+// and end on 128-byte lines only, 2: for every row.  Measured on MI355X (`bench.py --stores`, 12 placements): for an
+// in-place update of tensors far larger than the last-level cache device scope is worth between -0.9 and +1.4 %,
+// depending on the row length and the run (T*H = 2^28: H=4096 +1.1 to +1.4 %, H=8192 and 2048 0 to +0.5 %, H=5120 -0.6
+// to -0.9 %, H=14336 -0.7 to +0.4 %); on cache-sized tensors that are reused launch after launch it COSTS 3-14 %
+// (T=4096 H=4096 23.1 against 21.6 us, T=512 H=8192 7.1 against 6.2 us, T=257 H=7168 5.1 against 4.5 us),
+// because the data has to go out to memory; and a row that shares its first or last line with the neighbouring row
+// loses 15-25 % with it (H=4104 77 -> 60 % of the HBM peak, H=8200 73 -> 59 %).  Stores to lines the kernel has not
+// read (silu_and_mul, merge_attn_states_lse) gain nothing either (-0.5 to +0.4 points).  Hence scope 0 everywhere.
 // The scope bits are reachable through the buffer form of the store only: `row` must be uniform over the wave (it
 // becomes the scalar buffer descriptor, bounds = the row), `v` is the per-lane part.
+enum : int { kStoreScopeNone = 0, kStoreScopeWholeLineRows = 1, kStoreScopeAlways = 2 };
+
 template <bool NT>
-__device__ __forceinline__ void store_row_vec_in_place(u32x4* row, uint32_t row_vecs, uint32_t v, u32x4 value)
+__device__ __forceinline__ void store_row_vec(u32x4* row, uint32_t row_vecs, uint32_t v, u32x4 value, int scope = kStoreScopeNone)
 {
-    // rows that begin and end on 128-byte lines only (uniform over the wave)
-    const bool whole_lines = ((reinterpret_cast<uintptr_t>(row) | (uintptr_t)(row_vecs * 16u)) & (kLineBytes - 1)) == 0;
-    if (NT && !whole_lines) {
-        store_vec<true>(row + v, value);
-    } else if constexpr (NT) {
-        constexpr int kNonTemporal = 2, kDeviceScope = 16;  // cache-policy bits of the buffer instructions: nt, sc1
-        constexpr int kRawBuffer = 0x00020000;              // descriptor word 3: untyped 32-bit data, no swizzle
-        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(row, 0, row_vecs * 16u, kRawBuffer);
-        __builtin_amdgcn_raw_buffer_store_b128(value, rsrc, v * 16u, 0, kNonTemporal | kDeviceScope);
-    } else {
-        row[v] = value;
+    if constexpr (NT) {
+        const bool whole_lines = ((reinterpret_cast<uintptr_t>(row) | (uintptr_t)(row_vecs * 16u)) & (kLineBytes - 1)) == 0;
+        if (scope == kStoreScopeAlways || (scope == kStoreScopeWholeLineRows && whole_lines)) {
+            constexpr int kNonTemporal = 2, kDeviceScope = 16;  // cache-policy bits of the buffer instructions: nt, sc1
+            constexpr int kRawBuffer = 0x00020000;              // descriptor word 3: untyped 32-bit data, no swizzle
+            const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(row, 0, row_vecs * 16u, kRawBuffer);
+            __builtin_amdgcn_raw_buffer_store_b128(value, rsrc, v * 16u, 0, kNonTemporal | kDeviceScope);
+            return;
+        }
     }
+    store_vec<NT>(row + v, value);
 }
 
 // Request pacing of the fused_add_rmsnorm row kernel (a template parameter there, chosen by the host's launch plan;

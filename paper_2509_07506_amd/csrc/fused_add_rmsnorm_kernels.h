@@ -25,8 +25,8 @@ namespace astra {
 //   kPaceXBeforeR     the x vectors must have arrived before the r vectors are requested
 //   kPaceStoreGap     the residual store must have completed before the output store is issued
 // With PACE = 0 every request goes out as early as possible: the shortest dependent chain, used for few rows.
-// Both results go out through store_row_vec_in_place (device_common.h): non-temporal, and at device scope when the
-// row begins and ends on 128-byte lines.
+// Both results go out through store_row_vec (device_common.h): the plain non-temporal store; `store_scope` lets the
+// ablation entry point run the same kernel with device-scope stores.
 // The empty asm statements (`arrive`) consume the loaded registers at a chosen point, which fixes where the wait
 // for that load is placed; no instruction is emitted for them.  All loads are consumed before the arithmetic
 // starts, so the compiler has no reason to add a wait of its own later on.
@@ -51,7 +51,8 @@ __global__ __launch_bounds__(MAX_THREADS) void fused_add_rmsnorm_row_kernel(u32x
                                                                             int64_t T, uint32_t hv, float inv_h, float eps,
                                                                             int log2_chunk, u32x4* y_out = nullptr,
                                                                             u32x4* r_out = nullptr,
-                                                                            RowViews views = RowViews{0, 0, 0, 0})
+                                                                            RowViews views = RowViews{0, 0, 0, 0},
+                                                                            int store_scope = kStoreScopeNone)
 {
     constexpr int N = Storage<DT>::kN;
     __shared__ float partials[2][16];
@@ -110,7 +111,7 @@ __global__ __launch_bounds__(MAX_THREADS) void fused_add_rmsnorm_row_kernel(u32x
                     s[k][e] = x[e] + r[e];
                     acc += s[k][e] * s[k][e];
                 }
-                store_row_vec_in_place<NTS>(sumrow, hv, v, pack_vec<DT>(s[k]));
+                store_row_vec<NTS>(sumrow, hv, v, pack_vec<DT>(s[k]), store_scope);
             }
         }
 
@@ -126,7 +127,7 @@ __global__ __launch_bounds__(MAX_THREADS) void fused_add_rmsnorm_row_kernel(u32x
                 unpack_vec<DT>(wv[k], w);
 #pragma unroll
                 for (int e = 0; e < N; ++e) y[e] = (s[k][e] * scale) * w[e];
-                store_row_vec_in_place<NTS>(yrow, hv, v, pack_vec<DT>(y));
+                store_row_vec<NTS>(yrow, hv, v, pack_vec<DT>(y), store_scope);
             }
         }
         row += gridDim.x;

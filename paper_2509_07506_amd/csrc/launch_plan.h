@@ -170,26 +170,22 @@ inline bool rmsnorm_row_plan(int64_t hv, RowPlan* plan)
 // 1-5 % with the placement alone, so a row length gets a pace of its own only if that pace beat the default on at
 // least 23 of the 24 paired placements of the two runs and by at least 1 % on average in each; everything else takes
 // the default.  Rows kept (H in 16-bit elements):
-//   H =  1536   gap  333.1 / 333.6   w,x  +7.6 (12/12), +4.7 (12/12)
-//   H =  2048   gap  326.1 / 326.8   w,x  +7.2 (12/12), +5.4 (11/12)
-//   H =  2560   gap  329.9 / 331.0   x    +7.6 (12/12), +9.6 (12/12)
-//   H =  3072   gap  331.1 / 331.4   x    +5.7 (12/12), +5.8 (12/12)
-//   H =  6144   gap  331.2 / 331.7   none +3.6 (12/12), +4.2 (12/12)
-//   H =  7168   gap  333.9 / 335.0   x    +5.3 (12/12), +5.8 (11/12)
-//   H =  7680   gap  338.9 / 339.9   w,x  +11.2 (12/12), +6.4 (12/12)
-//   H =  8192   gap  326.3 / 328.4   w,x  +4.1 (12/12), +6.0 (12/12)
-//   H = 10240   gap  341.2 / 343.9   w,x  +6.3 (12/12), +7.8 (12/12)     two vectors per lane
-//   H = 11008   gap  340.9 / 340.6   w,x  +8.6 (12/12), +4.7 (12/12)     two vectors per lane
-//   H = 12288   gap  340.1 / 342.3   w,x  +9.3 (12/12), +5.8 (12/12)     two vectors per lane
-//   H = 14336   gap  345.0 / 346.1   w,x  +9.1 (12/12), +9.8 (12/12)     two vectors per lane
-//   H = 20480   none 355.2 / 356.1   w,x  +4.4 (12/12), +4.7 (12/12)     four vectors per lane
-//   H = 28672   none 353.6 / 356.4   x    +8.4 (12/12), +7.9 (12/12)     four vectors per lane
-// Rows measured and left at the default (best alternative, either run): H = 512 x +4.1 (11/12), +3.4 (9/12); 1024 w,x
-// +4.1 (12/12), +4.3 (10/12); 4096 w,x +1.2 (8/12), +0.8 (9/12); 5120 none +1.6 (9/12), +1.3 (7/12); 16384 w,x +2.1
-// (10/12), +0.2 (7/12); 32768 x +3.5 (11/12), +3.3 (10/12).  A forced pace can also lose a lot: "w,x" costs 22 us (7 %)
-// at H = 5120, 15 us at H = 32768 and 6 us at H = 6144 and 28672, "none" 10 us at H = 4096, which is why there is no
-// blanket rule.  (floor at 8 TB/s: 268 us.)
-// Default: "gap" against "none" is 3-10 us better for rows of 1536 to 4096 elements and level elsewhere.  The gap
+//   H =  1024   gap  330.0 / 329.7   w,x  +7.9 (11/12), +6.8 (12/12)
+//   H =  1536   gap  338.2 / 338.0   w,x  +8.8 (12/12), +8.1 (12/12)
+//   H =  2048   gap  330.3 / 331.0   w,x  +6.9 (11/12), +8.4 (12/12)
+//   H =  2560   gap  330.2 / 330.7   x    +8.2 (12/12), +8.3 (12/12)
+//   H =  3072   gap  334.5 / 335.1   x    +7.2 (12/12), +7.4 (12/12)
+//   H =  8192   gap  329.4 / 330.2   w,x  +5.2 (12/12), +5.9 (12/12)
+//   H = 10240   gap  341.9 / 342.4   w,x  +6.0 (12/12), +4.4 (11/12)     two vectors per lane
+//   H = 14336   gap  343.9 / 344.6   w,x  +9.5 (12/12), +8.2 (12/12)     two vectors per lane
+//   H = 16384   gap  343.9 / 344.8   x    +5.0 (12/12), +4.7 (11/12)     two vectors per lane
+// Rows measured and left at the default (best alternative, either run): H = 512 x +4.5 (9/12), +4.6 (10/12); 4096 w,x
+// +2.3 (10/12), +3.8 (12/12); 5120 none -0.9, -0.5; 6144 none +0.6 (9/12), +0.3 (8/12); 7168 x +3.5 (11/12), +3.4
+// (11/12); 7680 x +2.9 (11/12), +3.3 (11/12); 11008 w,x +1.0 (8/12), +0.9 (8/12); 12288 w,x +1.6 (11/12), +0.7 (6/12);
+// 20480 w,x +3.5 (11/12), +2.7 (11/12); 28672 x -0.5, +0.1; 32768 x +5.5 (10/12), +5.2 (11/12).  A forced pace can also
+// lose a lot: "w,x" costs 31 us (10 %) at H = 5120, 26 us at H = 28672 and 10 us at H = 6144, "x" 8 us at H = 5120,
+// "none" 9 us at H = 4096, which is why there is no blanket rule.  (floor at 8 TB/s: 268 us.)
+// Default: "gap" against "none" is 3-9 us better for rows of 1536 to 4096 elements and level elsewhere.  The gap
 // lengthens every workgroup's life by one store round trip, which the end of the grid pays once: about a microsecond
 // whatever the size (H = 1024: 23.5 against 22.5 at T = 16384, 84.0 against 82.6 at T = 65536), so under kGapMinRounds
 // rounds of resident workgroups the default is "none".
@@ -198,10 +194,8 @@ constexpr int kGapMinRounds = 32;
 inline int rmsnorm_stream_pace(int64_t hv, bool long_grid)
 {
     // keys are row lengths in 16-byte vectors: H / 8 for the 16-bit storage types the table was measured with
-    if (hv == 320 || hv == 384 || hv == 896 || hv == 3584) return kPaceXBeforeR;
-    if (hv == 192 || hv == 256 || hv == 960 || hv == 1024 || hv == 1280 || hv == 1376 || hv == 1536 || hv == 1792 || hv == 2560)
-        return kPaceWeightFirst | kPaceXBeforeR;
-    if (hv == 768) return kPaceNone;
+    if (hv == 320 || hv == 384 || hv == 2048) return kPaceXBeforeR;
+    if (hv == 128 || hv == 192 || hv == 256 || hv == 1024 || hv == 1280 || hv == 1792) return kPaceWeightFirst | kPaceXBeforeR;
     return long_grid ? kPaceStoreGap : kPaceNone;
 }
 

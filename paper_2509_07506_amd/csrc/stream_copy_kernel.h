@@ -31,13 +31,11 @@ __global__ __launch_bounds__(256) void stream_copy_kernel(u32x4* __restrict__ ds
 //   1 a and b are read only       two read streams (the loaded registers are consumed by an empty asm statement)
 //   2 c <- a pattern              one write stream
 //   3 c <- a ^ b                  two read streams, one write stream: the mix of silu_and_mul and merge_attn_states_lse
-//   4 a <- a ^ b, b <- a + b      two streams updated in place: the mix of fused_add_rmsnorm, with its store form
-//                                 (device scope on whole lines, store_row_vec_in_place)
+//   4 a <- a ^ b, b <- a + b      two streams updated in place: the mix of fused_add_rmsnorm
 template <int MODE, int BLOCK>
 __global__ __launch_bounds__(BLOCK) void stream_probe_kernel(u32x4* a, u32x4* b, u32x4* c, uint32_t nvec, int log2_chunk)
 {
-    const uint32_t first = xcd_chunked(blockIdx.x, log2_chunk) * uint32_t(BLOCK);  // uniform over the workgroup
-    const uint32_t i = first + threadIdx.x;
+    const uint32_t i = xcd_chunked(blockIdx.x, log2_chunk) * uint32_t(BLOCK) + threadIdx.x;
     if (i >= nvec) return;
     u32x4 x = u32x4{i, i, i, i}, y = x;
     if constexpr (MODE != 2) x = load_vec<true>(a + i);
@@ -45,9 +43,8 @@ __global__ __launch_bounds__(BLOCK) void stream_probe_kernel(u32x4* a, u32x4* b,
     if constexpr (MODE == 1) {
         asm volatile("" : : "v"(x), "v"(y));
     } else if constexpr (MODE == 4) {
-        const uint32_t span = nvec - first < uint32_t(BLOCK) ? nvec - first : uint32_t(BLOCK);
-        store_row_vec_in_place<true>(a + first, span, threadIdx.x, x ^ y);
-        store_row_vec_in_place<true>(b + first, span, threadIdx.x, x + y);
+        store_vec<true>(a + i, x ^ y);
+        store_vec<true>(b + i, x + y);
     } else {
         store_vec<true>(c + i, MODE == 3 ? (x ^ y) : x);
     }

@@ -216,16 +216,14 @@ def test_rmsnorm_plans(A):
     # grids (three rounds or more) "store gap" (4) by default on long grids, and a pace of its own for the row lengths that
     # beat the default on nearly every buffer placement (bench.py --pacing): weight-then-x-then-r (1 | 2), x-then-r (2)
     assert plan(255, 8192)["pace"] == 0 and plan(512, 4096)["pace"] == 0 and big["pace"] == 0
-    for T, H, pace in [(32768, 8192, 3), (32768, 2048, 3), (32768, 1536, 3), (4096, 14336, 3), (32768, 7680, 3), (32768, 10240, 3),
-                       (32768, 11008, 3), (32768, 12288, 3), (16384, 20480, 3),
-                       (32768, 2560, 2), (32768, 3072, 2), (32768, 7168, 2), (16384, 28672, 2),
-                       (32768, 6144, 0), (32768, 1024, 0),
-                       (32768, 4096, 4), (32768, 5120, 4), (32768, 16384, 4), (16384, 32768, 4), (1 << 20, 512, 4), (1 << 20, 1024, 4)]:
+    for T, H, pace in [(32768, 8192, 3), (32768, 2048, 3), (32768, 1024, 3), (32768, 1536, 3), (4096, 14336, 3), (32768, 10240, 3),
+                       (32768, 2560, 2), (32768, 3072, 2), (4096, 16384, 2),
+                       (32768, 4096, 4), (32768, 5120, 4), (32768, 6144, 4), (32768, 7168, 4), (32768, 7680, 4), (32768, 11008, 4),
+                       (32768, 12288, 4), (16384, 32768, 4), (1 << 20, 512, 4)]:
         assert plan(T, H)["pace"] == pace, (T, H, plan(T, H))
-    # ... the gap only where its extra microsecond at the end of the grid is small change (32 rounds or more); the row
-    # lengths with a pace of their own keep it on every streaming grid
-    assert plan(4099, 5120)["pace"] == 0 and plan(4099, 4096)["pace"] == 0 and plan(4096, 16384)["pace"] == 0
-    assert plan(4099, 7168)["pace"] == 2 and plan(2048, 28672)["pace"] == 2
+    # ... the gap only where its extra microsecond at the end of the grid is small change (32 rounds or more)
+    assert plan(4099, 5120)["pace"] == 0 and plan(2048, 28672)["pace"] == 0 and plan(4099, 7168)["pace"] == 0
+    assert plan(13107, 20480)["pace"] == 0 and plan(9362, 28672)["pace"] == 0
     assert plan(2048, 3072)["pace"] == 2 and plan(2048, 32768)["pace"] == 0
     assert plan(2048, 11008)["vectors_per_lane"] == 2 and plan(2048, 28672)["vectors_per_lane"] == 4
     # grids of under three rounds: x-then-r once a compute unit requests 48 KiB at once ...
@@ -248,7 +246,7 @@ def test_rmsnorm_plans(A):
         assert plan(T, H)["vectors_per_lane"] == 2, (T, H)
     assert A.astra_plan_fused_add_rmsnorm(1280, 2048, True, dtype=A.ASTRA_F32)[1].as_dict()["vectors_per_lane"] == 2
     assert A.astra_plan_fused_add_rmsnorm(32768, 4096, True, dtype=A.ASTRA_F32)[1].as_dict()["pace"] == 3   # 16 KiB rows
-    assert A.astra_plan_fused_add_rmsnorm(32768, 8192, True, dtype=A.ASTRA_F32)[1].as_dict()["pace"] == 4   # 32 KiB rows: the default
+    assert A.astra_plan_fused_add_rmsnorm(32768, 8192, True, dtype=A.ASTRA_F32)[1].as_dict()["pace"] == 2   # 32 KiB rows
     assert A.astra_plan_silu_and_mul(4096, 14336, True)[1].as_dict()["pace"] == 0
 
 
@@ -426,7 +424,8 @@ def test_stream_probe_validation(A):
 def test_pace_variants_validate_like_the_operator(A):
     f = A.astra_ablation_fused_add_rmsnorm
     a, b, c = 1 << 40, 2 << 40, 3 << 40          # never dereferenced
-    for v in (A.ASTRA_VARIANT_PACE_NONE, A.ASTRA_VARIANT_PACE_STORE_GAP, A.ASTRA_VARIANT_PACE_X_BEFORE_R, A.ASTRA_VARIANT_PACE_WEIGHT_X_R):
+    for v in (A.ASTRA_VARIANT_PACE_NONE, A.ASTRA_VARIANT_PACE_STORE_GAP, A.ASTRA_VARIANT_PACE_X_BEFORE_R, A.ASTRA_VARIANT_PACE_WEIGHT_X_R,
+              A.ASTRA_VARIANT_STORE_DEVICE_SCOPE_WHOLE_LINES, A.ASTRA_VARIANT_STORE_DEVICE_SCOPE):   # the store-form variants: the same shapes
         assert f(0, b, c, 1, 8, 1, 1e-6, v) == 1 and f(a, b, c, -1, 8, 1, 1e-6, v) == 2 and f(a, b, c, 1, 8, 7, 1e-6, v) == 3
         assert f(a, b, c, 1, 8, 1, -1.0, v) == 4 and f(a + 1, b, c, 1, 8, 1, 1e-6, v) == 5 and f(a, a, c, 1, 8, 1, 1e-6, v) == 6
         assert f(a, b, c, 0, 8, 1, 1e-6, v) == 0                                          # T == 0: nothing to do
@@ -434,4 +433,4 @@ def test_pace_variants_validate_like_the_operator(A):
         assert f(a, b, c, 4, 4100, 1, 1e-6, v) == A.ASTRA_ERR_VARIANT
         assert f(a, b, c, 4, 40000, 1, 1e-6, v) == A.ASTRA_ERR_VARIANT                    # element-wise path
         assert f(a, b, c, 1 << 22, 264, 1, 1e-6, v) == A.ASTRA_ERR_VARIANT                # row loop beyond the grid limit
-    assert f(a, b, c, 4, 4096, 1, 1e-6, 10) == A.ASTRA_ERR_VARIANT and f(a, b, c, 4, 4096, 1, 1e-6, -1) == A.ASTRA_ERR_VARIANT
+    assert f(a, b, c, 4, 4096, 1, 1e-6, 12) == A.ASTRA_ERR_VARIANT and f(a, b, c, 4, 4096, 1, 1e-6, -1) == A.ASTRA_ERR_VARIANT

@@ -145,7 +145,8 @@ def test_variant_validation_on_device(A):
 
 
 @pytest.mark.parametrize("dt", ["bf16", "f16"])
-@pytest.mark.parametrize("T,H", [(3, 4096), (700, 2048), (1100, 5120), (300, 8192), (65, 10240), (20, 20480), (1500, 512)])
+@pytest.mark.parametrize("T,H", [(3, 4096), (700, 2048), (1100, 5120), (300, 8192), (65, 10240), (20, 20480), (1500, 512),
+                                 (40, 4104), (9, 8200)])           # rows that are no whole 128-byte lines
 def test_forced_pacing_gives_the_tuned_kernels_bits(A, T, H, dt):
     """The pace-forcing variants run the tuned row kernel with another order of memory requests: same arithmetic, so
     the same bits as astra_fused_add_rmsnorm, and the oracle's bars."""
@@ -155,7 +156,8 @@ def test_forced_pacing_gives_the_tuned_kernels_bits(A, T, H, dt):
     A.fused_add_rmsnorm(xd, rd, wd, 1e-5)
     torch.cuda.synchronize()
     y0, r0 = to_bits(xd), to_bits(rd)
-    for v in (A.ASTRA_VARIANT_PACE_NONE, A.ASTRA_VARIANT_PACE_STORE_GAP, A.ASTRA_VARIANT_PACE_X_BEFORE_R, A.ASTRA_VARIANT_PACE_WEIGHT_X_R):
+    for v in (A.ASTRA_VARIANT_PACE_NONE, A.ASTRA_VARIANT_PACE_STORE_GAP, A.ASTRA_VARIANT_PACE_X_BEFORE_R, A.ASTRA_VARIANT_PACE_WEIGHT_X_R,
+              A.ASTRA_VARIANT_STORE_DEVICE_SCOPE_WHOLE_LINES, A.ASTRA_VARIANT_STORE_DEVICE_SCOPE):   # ... or another form of its stores
         _rmsnorm(A, x, r, w, 1e-5, dt, v)          # against the oracle
         xd, rd = to_dev(x, dt), to_dev(r, dt)
         st = A.astra_ablation_fused_add_rmsnorm(xd.data_ptr(), rd.data_ptr(), wd.data_ptr(), T, H, _code(A, dt), 1e-5, v,
