@@ -20,10 +20,11 @@
  *     16-byte aligned pointers and a row length that is a multiple of 16 bytes (8 16-bit or 4 binary32
  *     elements); anything else is served by other paths that compute the same thing.  The usual one works on the
  *     16-byte aligned chunks of memory the OUTPUT covers, at nearly the fast path's rate: silu_and_mul and
- *     merge_attn_states_lse for any element-aligned dense tensors with rows (d, head_dim) of at least one vector,
+ *     merge_attn_states_lse for any element-aligned dense tensors with rows of at least eight vectors (d) / one
+ *     vector (head_dim),
  *     fused_add_rmsnorm when its activation tensors are in step with each other (congruent modulo 16 bytes, as all
  *     16-byte aligned dense tensors are).  Otherwise 16-byte accesses at element alignment (fused_add_rmsnorm tensors
- *     out of step, rows under one vector), and plain element-wise kernels for fused_add_rmsnorm rows of more than 4096
+ *     out of step, shorter rows), and plain element-wise kernels for fused_add_rmsnorm rows of more than 4096
  *     vectors or less than one and for inputs beyond 2^31 vectors.  Equal up to the order of binary32 roundings; the
  *     residual of fused_add_rmsnorm is bit-identical on every path.
  *   - Nothing outside a tensor is ever written.  One path READS outside: the chunked path of fused_add_rmsnorm loads

@@ -21,13 +21,13 @@ typedef enum {
                                the 32-bit vector index */
     ASTRA_PATH_RAGGED = 3,  /* 16-byte accesses at element alignment, loads and stores alike, the partial last vector of a row
                                element-wise: fused_add_rmsnorm with its activation tensors at unrelated offsets into the
-                               16-byte grid; silu_and_mul and merge_attn_states_lse with rows (d, head_dim) under one
-                               vector, row-strided views, or more than 2^31 (2^32) elements */
+                               16-byte grid; silu_and_mul with rows (d) under eight vectors and merge_attn_states_lse
+                               with rows (head_dim) under one, row-strided views, or more than 2^31 (2^32) elements */
     ASTRA_PATH_PHASED = 4   /* row lengths that are no whole number of vectors, or pointers that are only element aligned:
                                lanes own the 16-byte aligned chunks of memory the output covers, so every store is an
                                aligned one (the partial chunk at an end element-wise); runs at nearly the vector path's
                                rate.  silu_and_mul and merge_attn_states_lse: any dense tensors with rows of at least
-                               one vector, loads at element alignment.  fused_add_rmsnorm (in place, so loads and stores
+                               eight vectors / one vector, loads at element alignment.  fused_add_rmsnorm (in place, so loads and stores
                                share their chunks): activation tensors in step with each other (congruent modulo 16
                                bytes -- every dense call on 16-byte aligned tensors is); it also takes this path for
                                16-byte aligned rows of whole vectors that are no whole number of 128-byte lines, on

@@ -343,6 +343,8 @@ inline int flat_block(int64_t vecs)
     return 256;
 }
 
+constexpr int64_t kSiluChunkMinRowVecs = 8;  // shortest rows (in vectors) for the output-chunk kernel of silu_and_mul
+
 // `wide_only`: the caller's kernel exists with 256-lane workgroups only (strided views)
 inline astra_status_t plan_silu(int64_t T, int64_t d, int eb, int align, astra_launch_info_t* info, bool wide_only = false)
 {
@@ -366,10 +368,13 @@ inline astra_status_t plan_silu(int64_t T, int64_t d, int eb, int align, astra_l
         const int64_t blocks = (T * dv + span - 1) / span;
         const int lc = fit_chunk_log2(blocks, kFlatChunkLog2, kFlatChunkMinBlocks * (256 / block));
         *info = launch_info(ASTRA_PATH_VECTOR, block, kSiluUnroll, lc, pad_grid(blocks, lc), 0, 0);
-    } else if (!wide_only && d >= ne && T * d <= kMaxVecIndex) {
-        // any other dense call with rows of at least one vector: the aligned chunks of memory the output covers, at
+    } else if (!wide_only && d >= kSiluChunkMinRowVecs * ne && T * d <= kMaxVecIndex) {
+        // any other dense call with rows of at least eight vectors: the aligned chunks of memory the output covers, at
         // most one more than ceil(T * d / N) (silu_and_mul_phased_kernel: aligned stores, loads at element
-        // alignment); flat output elements are indexed with 32 bits
+        // alignment); flat output elements are indexed with 32 bits.  Shorter rows have a chunk across a row end (three
+        // loads and a divergent branch) every few chunks, and the ragged kernel is faster there (HIP-graph replay, bf16,
+        // ragged / chunked: T=1000 d=36 2.4 / 2.8-3.4 us, T=16 d=100 1.9-2.4 / 2.1-2.4, T=1000 d=68 2.5-3.2 / 2.4-3.1,
+        // T=1000 d=132 2.8-3.6 / 2.4-3.2, d=260 3.2-3.8 / 2.5-3.2, T=40000 d=68 5.0-7.1 / 4.9-6.5)
         const int64_t chunks = (T * d + ne - 1) / ne + 1;
         const int block = flat_block(chunks);
         const int64_t blocks = (chunks + block - 1) / block;

@@ -109,7 +109,7 @@ __global__ __launch_bounds__(256) void silu_and_mul_small_kernel(u32x2* __restri
     out[o] = pack_half_vec<DT>(r);
 }
 
-// Phased path: dense tensors, any d >= N and any element-aligned pointers.  The work is the list of 16-byte aligned
+// Phased path: dense tensors, any d >= N (the host sends rows of eight vectors or more) and any element-aligned pointers.  The work is the list of 16-byte aligned
 // chunks of memory the OUTPUT covers: lane c owns flat output elements [c*N - phase, c*N - phase + N), `phase` = the
 // output pointer's offset into the 16-byte grid in elements, and stores them with one aligned 16-byte access.  Its
 // operands are loaded with 16-byte accesses at element alignment: on MI355X it is the unaligned STORE that costs (the
@@ -183,7 +183,7 @@ __global__ __launch_bounds__(BLOCK) void silu_and_mul_phased_kernel(typename Sto
     store_vec<NTS>(reinterpret_cast<u32x4*>(out + f0), pack_vec<DT>(o));
 }
 
-// Ragged path (rows shorter than a vector, row-strided views, tensors beyond the phased kernel's 32-bit element index):
+// Ragged path (rows shorter than eight vectors, row-strided views, tensors beyond the phased kernel's 32-bit element index):
 // any d, pointers and row strides only element aligned (dense tensors: out_stride = d, in_stride = 2d).
 // A row is dv = ceil(d/N) vectors, the last one possibly partial; one lane per vector, row and column from a
 // per-lane fast division, 64-bit element offsets.  Full vectors are 16-byte accesses at element alignment; the

@@ -350,7 +350,7 @@ void check_host_queries()
                li.block == 1024 && li.grid == 32768,
            "plan of the headline rmsnorm shape");
     expect(astra_plan_silu_and_mul(3, 100, ASTRA_F16, 1, &li) == ASTRA_OK && li.path == ASTRA_PATH_PHASED, "plan of an odd silu shape");
-    expect(astra_plan_silu_and_mul(3, 5, ASTRA_F16, 1, &li) == ASTRA_OK && li.path == ASTRA_PATH_RAGGED, "plan of a silu shape with rows under one vector");
+    expect(astra_plan_silu_and_mul(3, 5, ASTRA_F16, 1, &li) == ASTRA_OK && li.path == ASTRA_PATH_RAGGED, "plan of a silu shape with short rows");
     expect(astra_plan_merge_attn_states_lse(0, 4, 64, ASTRA_F16, 1, &li) == ASTRA_OK && li.path == ASTRA_PATH_NONE, "plan of an empty merge");
     int clk = 0, bits = 0;
     expect(astra_device_memory_info(0, &clk, &bits) == ASTRA_OK && clk > 0 && bits > 0, "device memory info");

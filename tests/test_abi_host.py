@@ -288,12 +288,14 @@ def test_silu_and_merge_plans(A):
     assert work <= p["grid"] * p["block"] * p["vectors_per_lane"] < work + (8 << p["log2_xcd_chunk"]) * 256
     assert p["grid"] % (8 << p["log2_xcd_chunk"]) == 0
     # every other dense call with rows of at least one vector: the aligned chunks of memory the output covers (aligned
-    # stores, loads at element alignment), at most one more than its vectors; rows under one vector: 16-byte accesses at
-    # element alignment
+    # stores, loads at element alignment), at most one more than its vectors; rows under eight vectors: 16-byte accesses
+    # at element alignment
     assert A.astra_plan_silu_and_mul(3, 100, True)[1].as_dict() == {"path": "phased", "block": 256, "vectors_per_lane": 1,
                                                                     "log2_xcd_chunk": 0, "grid": 1, "pace": 0}   # 38 + 1 chunks
     assert A.astra_plan_silu_and_mul(3, 7, True)[1].as_dict() == {"path": "ragged", "block": 256, "vectors_per_lane": 1,
                                                                   "log2_xcd_chunk": 0, "grid": 1, "pace": 0}
+    assert A.astra_plan_silu_and_mul(3, 63, True)[1].as_dict()["path"] == "ragged"          # rows under eight vectors
+    assert A.astra_plan_silu_and_mul(3, 65, True)[1].as_dict()["path"] == "phased" and A.astra_plan_silu_and_mul(3, 64, 2)[1].as_dict()["path"] == "phased"
     assert A.astra_plan_silu_and_mul(3, 1408, False)[1].as_dict()["path"] == "phased"
     ph = A.astra_plan_silu_and_mul(4096, 14336, 2)[1].as_dict()
     assert ph == {"path": "phased", "block": 64, "vectors_per_lane": 1, "log2_xcd_chunk": 8, "grid": 114688 + 2048, "pace": 0}

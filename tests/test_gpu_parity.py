@@ -270,8 +270,8 @@ def test_rmsnorm_vector_path_canaries(A, T, H, dt):
 @pytest.mark.parametrize("T,d,off", [(3, 100, 0), (2, 1412, 0), (5, 1, 0), (4, 2049, 0), (3, 1408, 1), (2, 248, 0), (3, 11008, 2),
                                      (4, 1408, 0), (257, 11008, 0),
                                      (300, 11009, 0), (1000, 7, 3), (257, 1410, 5), (64, 8, 1), (129, 13825, 0), (50, 11012, 7),
-                                     # d a whole number of vectors behind offset pointers: aligned chunks of the output, one
-                                     # per row across the row end (every chunk when d = 8)
+                                     # offset pointers: aligned chunks of the output, one per row across the row end
+                                     # (rows of eight vectors or more; shorter rows at element alignment)
                                      (1, 8, 7), (1, 16, 3), (2, 8, 4), (513, 1408, 4), (1030, 64, 5), (257, 11008, 6),
                                      (40, 14336, 9), (3, 24, 15)])
 def test_silu_paths_and_canaries(A, T, d, off, dt):
@@ -281,7 +281,7 @@ def test_silu_paths_and_canaries(A, T, d, off, dt):
     out_init = np.full((T, d), 0x1234, np.uint16)
     od, ow = padded(out_init, dt, offset_elems=off)
     st, info = A.astra_plan_silu_and_mul(T, d, 1 if off % 8 == 0 else 2)
-    assert info.as_dict()["path"] == ("vector" if d % 8 == 0 and off % 8 == 0 else "phased" if d >= 8 else "ragged")
+    assert info.as_dict()["path"] == ("vector" if d % 8 == 0 and off % 8 == 0 else "phased" if d >= 64 else "ragged")
     A.silu_and_mul(od, ad)
     torch.cuda.synchronize()
     assert_storage_close(to_bits(od), O.silu_and_mul(a, dt), dt, "out")
