@@ -1082,7 +1082,9 @@ def run_pacing_few_rounds(args):
 
 def run_ceiling(args):
     """Streaming ceiling of this machine with the operators' access pattern: astra_stream_copy over
-    512 MiB, alternating between two source/destination pairs (2 GiB footprint, so always cold)."""
+    512 MiB, alternating between two source/destination pairs (2 GiB footprint, so always cold); the
+    library's five traffic probes (read only, write only, copy, read-read-write, in-place update of two
+    streams) at 512 MiB per stream; and three reference points from the vendor stack on the same buffers."""
     import torch
 
     import paper_2509_07506_amd as astra
@@ -1129,6 +1131,21 @@ def run_ceiling(args):
         print(json.dumps({"case": name, "cache": "cold", "bytes": nbytes, "batch_avg_us": round(t, 2),
                           "GBs": round(nbytes / t / 1e3, 1), "frac_of_peak": round(nbytes / t / 1e3 / HBM_PEAK_GBS, 4)}), flush=True)
 
+    # the library's probes, 512 MiB per stream: every traffic mix of the operators (and the pure read and the pure
+    # write beside them) with none of the arithmetic, in the flat kernels' launch geometry
+    src2 = [torch.zeros(n, dtype=torch.uint8, device="cuda") for _ in range(2)]
+
+    def probe(mode):
+        def go(k):
+            st = astra.astra_stream_probe(src[k & 1].data_ptr(), src2[k & 1].data_ptr(), dst[k & 1].data_ptr(), n, mode, sh)
+            if st != 0:
+                raise RuntimeError(f"astra_stream_probe: status {st}")
+        return go
+
+    for name, mode, streams in (("read2", astra.ASTRA_PROBE_READ2, 2), ("write1", astra.ASTRA_PROBE_WRITE1, 1),
+                                ("copy", astra.ASTRA_PROBE_COPY, 2), ("read2_write1", astra.ASTRA_PROBE_READ2_WRITE1, 3),
+                                ("update2", astra.ASTRA_PROBE_UPDATE2, 4)):
+        timed(probe(mode), streams * n, f"probe_{name}_512MiB_per_stream")
     timed(lambda k: dst[k & 1].copy_(src[k & 1]), 2 * n, "vendor_copy_512MiB (Tensor.copy_)")
     s16 = [t.view(torch.bfloat16) for t in src]
     d16 = [t.view(torch.bfloat16) for t in dst]

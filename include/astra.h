@@ -128,7 +128,8 @@ astra_status_t astra_stream_copy(void* dst, const void* src, int64_t nbytes, hip
 typedef enum {
     ASTRA_PROBE_COPY = 0,         /* c <- a: one read stream, one write stream */
     ASTRA_PROBE_READ2 = 1,        /* a and b are read, nothing is written */
-    ASTRA_PROBE_WRITE1 = 2,       /* c is written */
+    ASTRA_PROBE_WRITE1 = 2,       /* c is written; 256-lane workgroups at every size (a single-wave workgroup per
+                                     1 KiB store would measure the workgroup launch rate, not memory) */
     ASTRA_PROBE_READ2_WRITE1 = 3, /* c <- a ^ b: the mix of silu_and_mul and merge_attn_states_lse */
     ASTRA_PROBE_UPDATE2 = 4,      /* a <- a ^ b, b <- a + b, in place: the mix of fused_add_rmsnorm */
     ASTRA_ENUM_SPANS_INT32(ASTRA_PROBE)

@@ -792,7 +792,10 @@ astra_status_t astra_stream_probe(void* a, void* b, void* c, int64_t nbytes, ast
         return ASTRA_ERR_ALIAS;
     if (nbytes == 0) return ASTRA_OK;
     const int64_t nvec = nbytes / 16;
-    const int block = flat_block(nvec);
+    // the operators' geometry, except for the write-only mode on streaming grids: one 1 KiB store per single-wave
+    // workgroup runs at the rate the chip starts workgroups (4.7 per ns on MI355X: 58 % of the HBM peak), which says
+    // nothing about memory, so that mode keeps four waves per workgroup (83-84 %)
+    const int block = (m == ASTRA_PROBE_WRITE1 && flat_block(nvec) == 64) ? 256 : flat_block(nvec);
     const int64_t blocks = (nvec + block - 1) / block;
     const int lc = fit_chunk_log2(blocks, kFlatChunkLog2, kFlatChunkMinBlocks * (256 / block));
     const dim3 grid((uint32_t)pad_grid(blocks, lc));
