@@ -297,9 +297,13 @@ void launch_merge(const astra_launch_info_t& li, void* v_out, float* lse_out, co
         constexpr int N = Storage<DT>::kN;
         const int phase = (int)((reinterpret_cast<uintptr_t>(v_out) / sizeof(E)) & (N - 1));
         const int64_t n = pairs * D;
-        merge_attn_states_lse_phased_kernel<DT, kNTLoad, kNTStore><<<dim3((uint32_t)li.grid), dim3(256), 0, stream>>>(
-            static_cast<E*>(v_out), lse_out, static_cast<const E*>(v_a), lse_a, static_cast<const E*>(v_b), lse_b, (uint32_t)n,
-            (uint32_t)D, make_fastdiv((uint32_t)D), (uint32_t)((n + phase + N - 1) / N), phase, li.log2_xcd_chunk);
+        for_flat_block(li.block, [&](auto bc) {
+            constexpr int B = decltype(bc)::value;
+            merge_attn_states_lse_phased_kernel<DT, kNTLoad, kNTStore, B><<<dim3((uint32_t)li.grid), dim3(B), 0, stream>>>(
+                static_cast<E*>(v_out), lse_out, static_cast<const E*>(v_a), lse_a, static_cast<const E*>(v_b), lse_b,
+                (uint32_t)n, (uint32_t)D, make_fastdiv((uint32_t)D), (uint32_t)((n + phase + N - 1) / N), phase,
+                li.log2_xcd_chunk);
+        });
         return;
     }
     const uint32_t dvec = (uint32_t)(D / Storage<DT>::kN);
@@ -580,8 +584,6 @@ astra_status_t astra_merge_attn_states_lse_kway(void* v_out, float* lse_out, con
     const int align = aligned(v_out, 16) && aligned(v_parts, 16) ? kAlign16 : kAlignNone;
     astra_status_t st = plan_merge(T, num_heads, head_dim, eb, align, &li, true);
     if (st != ASTRA_OK) return st;
-    // the fast kernel exists for every workgroup width of the flat grids; the ragged one with 256 lanes only
-    if (li.path == ASTRA_PATH_VECTOR) plan_merge(T, num_heads, head_dim, eb, align, &li, false);
     if (li.path == ASTRA_PATH_GENERIC) return ASTRA_ERR_SHAPE;  // more than 2^31 output vectors
     const int64_t pairs = T * num_heads;
     int64_t part_elems = pairs * head_dim, all_elems;
@@ -677,9 +679,12 @@ astra_status_t astra_silu_and_mul_strided(void* out, int64_t out_stride, const v
                 make_fastdiv(dvr));
         } else {
             const uint32_t dv = (uint32_t)(d / Storage<DT>::kN);
-            silu_and_mul_strided_vec_kernel<DT, kNTLoad, kNTStore><<<dim3((uint32_t)li.grid), dim3(256), 0, stream>>>(
-                static_cast<u32x4*>(out), out_stride / Storage<DT>::kN, static_cast<const u32x4*>(input),
-                in_stride / Storage<DT>::kN, (uint32_t)(T * dv), dv, make_fastdiv(dv), li.log2_xcd_chunk);
+            for_flat_block(li.block, [&](auto bc) {
+                constexpr int B = decltype(bc)::value;
+                silu_and_mul_strided_vec_kernel<DT, kNTLoad, kNTStore, B><<<dim3((uint32_t)li.grid), dim3(B), 0, stream>>>(
+                    static_cast<u32x4*>(out), out_stride / Storage<DT>::kN, static_cast<const u32x4*>(input),
+                    in_stride / Storage<DT>::kN, (uint32_t)(T * dv), dv, make_fastdiv(dv), li.log2_xcd_chunk);
+            });
         }
     });
     return after_launch();
@@ -742,10 +747,13 @@ astra_status_t astra_merge_attn_states_lse_strided(void* v_out, int64_t out_toke
         } else {
             const ValueStrides vs{ts[0] / N, hs[0] / N, ts[1] / N, hs[1] / N, ts[2] / N, hs[2] / N};
             const uint32_t dvec = (uint32_t)(head_dim / N);
-            merge_attn_states_lse_strided_vec_kernel<DT, kNTLoad, kNTStore><<<dim3((uint32_t)li.grid), dim3(256), 0, stream>>>(
-                static_cast<u32x4*>(v_out), lse_out, static_cast<const u32x4*>(v_a), lse_a, static_cast<const u32x4*>(v_b),
-                lse_b, vs, (uint32_t)(pairs * dvec), dvec, make_fastdiv(dvec), make_fastdiv((uint32_t)num_heads),
-                (uint32_t)num_heads, li.log2_xcd_chunk);
+            for_flat_block(li.block, [&](auto bc) {
+                constexpr int B = decltype(bc)::value;
+                merge_attn_states_lse_strided_vec_kernel<DT, kNTLoad, kNTStore, B><<<dim3((uint32_t)li.grid), dim3(B), 0, stream>>>(
+                    static_cast<u32x4*>(v_out), lse_out, static_cast<const u32x4*>(v_a), lse_a,
+                    static_cast<const u32x4*>(v_b), lse_b, vs, (uint32_t)(pairs * dvec), dvec, make_fastdiv(dvec),
+                    make_fastdiv((uint32_t)num_heads), (uint32_t)num_heads, li.log2_xcd_chunk);
+            });
         }
     });
     return after_launch();

@@ -329,6 +329,9 @@ inline astra_status_t plan_rmsnorm(int64_t T, int64_t H, int eb, int align, astr
 //   * fewer workgroups than compute units (33 to 255 of 256 lanes): 128 lanes spread the work over twice as many
 //     compute units (silu T=16 d=12288: 2.06 against 2.14 us; T=32 d=5120: 2.06 against 2.13);
 //   * everything else: 256 lanes (up to 32 workgroups: 1.79 against 1.95 us; 2048 workgroups: 5.9 against 6.1).
+// Single-wave workgroups are bounded by the rate at which the chip starts workgroups, 4.7 per ns whatever their width
+// (an empty kernel over 524288 workgroups of 64 lanes: 111.5 us; of 256 lanes, a quarter as many: 28.8 us), so a
+// kernel that moves less than 1.5 KiB per wave must not use them; the flat kernels move 3 KiB per wave or more.
 // Small flat problems (fewer than this many output vectors, about 1.5 MiB moved) use plain cached accesses, and
 // silu_and_mul 8 bytes per lane: see silu_and_mul_small_kernel.  merge_attn_states_lse, same measurement: T=1 40x256
 // 1.76 us against 2.04 non-temporal, T=16 32x128 1.94 against 2.04, and from T=64 32x128 (2^15 vectors) on 2.25
@@ -345,8 +348,8 @@ inline int flat_block(int64_t vecs)
 
 constexpr int64_t kSiluChunkMinRowVecs = 8;  // shortest rows (in vectors) for the output-chunk kernel of silu_and_mul
 
-// `wide_only`: the caller's kernel exists with 256-lane workgroups only (strided views)
-inline astra_status_t plan_silu(int64_t T, int64_t d, int eb, int align, astra_launch_info_t* info, bool wide_only = false)
+// `views`: the call is on row-strided views, whose kernels have no small-problem and no output-chunk form
+inline astra_status_t plan_silu(int64_t T, int64_t d, int eb, int align, astra_launch_info_t* info, bool views = false)
 {
     const bool aligned16 = (align == kAlign16);
     const int64_t ne = kVecBytes / eb;
@@ -359,16 +362,16 @@ inline astra_status_t plan_silu(int64_t T, int64_t d, int eb, int align, astra_l
     const int64_t dv = d / ne;
     // the input holds 2*T*dv vectors and is indexed with 32 bits
     if (aligned16 && d % ne == 0 && 2 * T * dv <= kMaxVecIndex) {  // rows under kSiluLaneDivBelow vectors: per-lane division
-        if (!wide_only && T * dv < kSmallFlatVecs) {  // half a vector per lane, plain accesses
+        if (!views && T * dv < kSmallFlatVecs) {  // half a vector per lane, plain accesses
             *info = launch_info(ASTRA_PATH_VECTOR, 256, 1, 0, (2 * T * dv + 255) / 256, 0, 0, kVecBytes / 2, 0);
             return ASTRA_OK;
         }
-        const int block = wide_only ? 256 : flat_block(T * dv);
+        const int block = flat_block(T * dv);
         const int64_t span = block * kSiluUnroll;
         const int64_t blocks = (T * dv + span - 1) / span;
         const int lc = fit_chunk_log2(blocks, kFlatChunkLog2, kFlatChunkMinBlocks * (256 / block));
         *info = launch_info(ASTRA_PATH_VECTOR, block, kSiluUnroll, lc, pad_grid(blocks, lc), 0, 0);
-    } else if (!wide_only && d >= kSiluChunkMinRowVecs * ne && T * d <= kMaxVecIndex) {
+    } else if (!views && d >= kSiluChunkMinRowVecs * ne && T * d <= kMaxVecIndex) {
         // any other dense call with rows of at least eight vectors: the aligned chunks of memory the output covers, at
         // most one more than ceil(T * d / N) (silu_and_mul_phased_kernel: aligned stores, loads at element
         // alignment); flat output elements are indexed with 32 bits.  Shorter rows have a chunk across a row end (three
@@ -388,9 +391,9 @@ inline astra_status_t plan_silu(int64_t T, int64_t d, int eb, int align, astra_l
     return ASTRA_OK;
 }
 
-// `wide_only`: the caller's kernel exists with 256-lane workgroups only (strided views, the ragged K-way merge)
+// `views`: the call is on strided views or a K-way merge, whose kernels have no plain-access and no output-chunk form
 inline astra_status_t plan_merge(int64_t T, int64_t NH, int64_t D, int eb, int align, astra_launch_info_t* info,
-                                 bool wide_only = false)
+                                 bool views = false)
 {
     const bool aligned16 = (align == kAlign16);
     const int64_t ne = kVecBytes / eb;
@@ -402,19 +405,22 @@ inline astra_status_t plan_merge(int64_t T, int64_t NH, int64_t D, int eb, int a
     if (T == 0) return ASTRA_OK;
     const int64_t dvec = D / ne;
     if (aligned16 && D % ne == 0 && pairs * dvec <= kMaxVecIndex) {
-        const int block = wide_only ? 256 : flat_block(pairs * dvec);
+        const int block = flat_block(pairs * dvec);
         const int64_t span = block * kMergeUnroll;
         const int64_t blocks = (pairs * dvec + span - 1) / span;
         const int lc = fit_chunk_log2(blocks, kFlatChunkLog2, kFlatChunkMinBlocks * (256 / block));
         *info = launch_info(ASTRA_PATH_VECTOR, block, kMergeUnroll, lc, pad_grid(blocks, lc), 0, 0, kVecBytes,
-                            !wide_only && pairs * dvec < kSmallFlatVecs ? 0 : 1);
-    } else if (!wide_only && D >= ne && n < (int64_t(1) << 32)) {
+                            !views && pairs * dvec < kSmallFlatVecs ? 0 : 1);
+    } else if (!views && D >= ne && n < (int64_t(1) << 32)) {
         // head_dim or pointers off the 16-byte grid, dense tensors: one lane per aligned chunk of the flat output, at
         // most one more chunk than whole vectors (merge_attn_states_lse_phased_kernel: aligned stores, loads at
-        // element alignment)
-        const int64_t blocks = ((n + ne - 1) / ne + 1 + 255) / 256;
-        const int lc = fit_chunk_log2(blocks, kFlatChunkLog2, kFlatChunkMinBlocks);
-        *info = launch_info(ASTRA_PATH_PHASED, 256, 1, lc, pad_grid(blocks, lc), 0, 0);
+        // element alignment); workgroup width as for the fast kernel (T=16384 32x129, 256 -> 64 lanes: 78.4 -> 81.2 %
+        // of the HBM peak, 32x132 80.8 -> 83.1 %, 32x128 one element off the grid 80.6 -> 83.3 %)
+        const int64_t chunks = (n + ne - 1) / ne + 1;
+        const int block = flat_block(chunks);
+        const int64_t blocks = (chunks + block - 1) / block;
+        const int lc = fit_chunk_log2(blocks, kFlatChunkLog2, kFlatChunkMinBlocks * (256 / block));
+        *info = launch_info(ASTRA_PATH_PHASED, block, 1, lc, pad_grid(blocks, lc), 0, 0);
     } else if (pairs * ((D + ne - 1) / ne) <= kMaxVecIndex) {
         *info = launch_info(ASTRA_PATH_RAGGED, 256, 1, 0, (pairs * ((D + ne - 1) / ne) + 255) / 256, 0, 0);
     } else {

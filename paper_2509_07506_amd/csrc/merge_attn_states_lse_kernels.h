@@ -175,14 +175,14 @@ __global__ __launch_bounds__(256) void merge_attn_states_lse_ragged_kernel(
 // (token, head) pair -- at most one, since head_dim >= N -- so a lane evaluates the weights of the pair of its first
 // and of its last element and takes, per element, those of the pair the element belongs to; the lane that holds a
 // pair's first element stores that pair's S_out.
-template <int DT, bool NTL, bool NTS>
-__global__ __launch_bounds__(256) void merge_attn_states_lse_phased_kernel(
+template <int DT, bool NTL, bool NTS, int BLOCK = 256>
+__global__ __launch_bounds__(BLOCK) void merge_attn_states_lse_phased_kernel(
     typename Storage<DT>::elem_t* v_out, float* lse_out, const typename Storage<DT>::elem_t* v_a, const float* lse_a,
     const typename Storage<DT>::elem_t* v_b, const float* lse_b, uint32_t n_elems, uint32_t D, FastDiv by_D,
     uint32_t total_chunks, int phase, int log2_chunk)
 {
     constexpr int N = Storage<DT>::kN;
-    const uint32_t c = xcd_chunked(blockIdx.x, log2_chunk) * 256u + threadIdx.x;
+    const uint32_t c = xcd_chunked(blockIdx.x, log2_chunk) * uint32_t(BLOCK) + threadIdx.x;
     if (c >= total_chunks) return;
     const int64_t e0 = (int64_t)c * N - phase;  // first flat element of the chunk; negative only for chunk 0
     const bool whole = e0 >= 0 && e0 + N <= (int64_t)n_elems;
@@ -235,15 +235,15 @@ __global__ __launch_bounds__(256) void merge_attn_states_lse_generic_kernel(type
 // (strides in vectors for the fast kernel, in elements for the ragged and the element-wise one); the scores stay dense [T, NH].
 // One lane per output vector; pair, token and head from per-lane fast divisions; 64-bit offsets.
 
-template <int DT, bool NTL, bool NTS>
-__global__ __launch_bounds__(256) void merge_attn_states_lse_strided_vec_kernel(u32x4* v_out, float* lse_out, const u32x4* v_a,
+template <int DT, bool NTL, bool NTS, int BLOCK = 256>
+__global__ __launch_bounds__(BLOCK) void merge_attn_states_lse_strided_vec_kernel(u32x4* v_out, float* lse_out, const u32x4* v_a,
                                                                                 const float* lse_a, const u32x4* v_b,
                                                                                 const float* lse_b, ValueStrides vs,
                                                                                 uint32_t total_vecs, uint32_t dvec,
                                                                                 FastDiv by_dvec, FastDiv by_heads,
                                                                                 uint32_t heads, int log2_chunk)
 {
-    const uint32_t i = xcd_chunked(blockIdx.x, log2_chunk) * 256u + threadIdx.x;
+    const uint32_t i = xcd_chunked(blockIdx.x, log2_chunk) * uint32_t(BLOCK) + threadIdx.x;
     if (i >= total_vecs) return;
     const uint32_t pair = by_dvec.div(i), jv = i - pair * dvec;
     const uint32_t t = by_heads.div(pair), h = pair - t * heads;

@@ -233,14 +233,14 @@ __global__ __launch_bounds__(256) void silu_and_mul_generic_kernel(typename Stor
 // t-1, likewise the output (views with odd strides or extents take the ragged kernel above).  One lane per output vector, row and column from a per-lane fast division,
 // 64-bit offsets (a strided view has no 32-bit bound on its extent).
 
-template <int DT, bool NTL, bool NTS>
-__global__ __launch_bounds__(256) void silu_and_mul_strided_vec_kernel(u32x4* __restrict__ out, int64_t out_stride,
+template <int DT, bool NTL, bool NTS, int BLOCK = 256>
+__global__ __launch_bounds__(BLOCK) void silu_and_mul_strided_vec_kernel(u32x4* __restrict__ out, int64_t out_stride,
                                                                        const u32x4* __restrict__ in, int64_t in_stride,
                                                                        uint32_t total_vecs, uint32_t dv, FastDiv by_dv,
                                                                        int log2_chunk)
 {
     constexpr int N = Storage<DT>::kN;
-    const uint32_t o = xcd_chunked(blockIdx.x, log2_chunk) * 256u + threadIdx.x;
+    const uint32_t o = xcd_chunked(blockIdx.x, log2_chunk) * uint32_t(BLOCK) + threadIdx.x;
     if (o >= total_vecs) return;
     const uint32_t t = by_dv.div(o);
     const uint32_t j = o - t * dv;

@@ -336,6 +336,12 @@ def test_silu_and_merge_plans(A):
     # head_dim or pointers off the 16-byte grid: aligned chunks of the flat output (loads at element alignment)
     q = A.astra_plan_merge_attn_states_lse(257, 40, 129, True)[1].as_dict()
     assert q["path"] == "phased" and q["block"] == 256 and q["grid"] * 256 >= (257 * 40 * 129 + 7) // 8 + 1
+    # workgroup width as for the fast kernel: single waves on streaming grids, 128 lanes under one workgroup per compute unit
+    for T, block in [(16384, 64), (4096, 64), (64, 128), (3, 256)]:
+        q = A.astra_plan_merge_attn_states_lse(T, 32, 129, True)[1].as_dict()
+        chunks = (T * 32 * 129 + 7) // 8 + 1
+        assert q["path"] == "phased" and q["block"] == block and q["grid"] * block >= chunks, (T, q)
+        assert q["grid"] % (8 << q["log2_xcd_chunk"]) == 0 or q["log2_xcd_chunk"] == 0
     assert A.astra_plan_merge_attn_states_lse(3, 5, 72, 2)[1].as_dict()["path"] == "phased"
     assert A.astra_plan_merge_attn_states_lse(1 << 16, 512, 129, True)[1].as_dict()["path"] == "ragged"       # 2^32 elements and more
     assert A.astra_plan_merge_attn_states_lse(1 << 24, 64, 129, True)[1].as_dict()["path"] == "generic"   # 2^30 * 17 vectors

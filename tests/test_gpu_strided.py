@@ -124,6 +124,8 @@ from tests.gpu_util import assert_lse_close  # noqa: E402
     (4, 100, 2 * 100 + 1, 100 + 7, 1),              # odd everything
     (270, 1411, 2 * 1411 + 5, 1411 + 3, 3),
     (1, 4096, 2 * 4096, 4096, 0),
+    (4100, 2048, 2 * 2048 + 64, 2048 + 8, 0),       # streaming grid: single-wave workgroups, XCD-aware order
+    (100, 1024, 2 * 1024 + 8, 1024 + 8, 8),         # fewer 256-lane workgroups than compute units: 128 lanes
 ])
 def test_silu_strided(A, T, d, in_stride, out_stride, col0, dt):
     print(f"[strided] silu T={T} d={d} in_stride={in_stride} out_stride={out_stride} col0={col0} {dt}", flush=True)
@@ -171,6 +173,8 @@ def _gaps_intact3(whole, NH, D, head_stride, col0):
     (3, 5, 36, (40, 37, 36), 3, 1),                  # odd everything
     (70, 9, 100, (103, 100, 109), 5, 3),
     (1, 1, 256, (256, 256, 256), 0, 0),
+    (2051, 32, 128, (136, 128, 144), 8, 0),          # streaming grid: single-wave workgroups, XCD-aware order
+    (60, 32, 128, (128, 136, 128), 0, 8),            # fewer 256-lane workgroups than compute units: 128 lanes
 ])
 def test_merge_strided(A, T, NH, D, head_strides, token_pad, col0, dt):
     print(f"[strided] merge T={T} NH={NH} D={D} head_strides={head_strides} pad={token_pad} col0={col0} {dt}", flush=True)
