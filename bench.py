@@ -993,7 +993,7 @@ def run_pacing(args):
             for name, v in variants:
                 launch, plan, nbytes, keep = _device_launcher(astra, "rmsnorm", {"T": T, "H": H}, 1, v, arena, off)
                 res[name].append(batch_us(launch, stream, sh, 10, 2))
-        pace_names = {0: "none", 4: "gap", 2: "x", 3: "w,x"}
+        pace_names = {0: "none", 4: "gap", 2: "x", 3: "w,x", 11: "w,x, one resident"}
         out = {"H": H, "T": T, "bytes": nbytes, "placements": len(placements), "policy_pace": pace_names.get(plan["pace"], plan["pace"]),
                "vectors_per_lane": plan["vectors_per_lane"], "block": plan["block"]}
         # paired with the default pace on the same placement: a special case is worth having only if it wins on

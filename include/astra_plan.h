@@ -54,7 +54,9 @@ enum {
     ASTRA_PACE_NONE = 0,         /* every request as early as possible (few rows: shortest dependent chain) */
     ASTRA_PACE_WEIGHT_FIRST = 1, /* the weight has arrived before the activations are requested */
     ASTRA_PACE_X_BEFORE_R = 2,   /* x has arrived before r is requested */
-    ASTRA_PACE_STORE_GAP = 4     /* the residual store has completed before the output store is issued */
+    ASTRA_PACE_STORE_GAP = 4,    /* the residual store has completed before the output store is issued */
+    ASTRA_PACE_ONE_RESIDENT = 8  /* not a wait: the workgroup reserves 96 KiB of LDS so that a compute unit holds one
+                                    workgroup at a time (long rows: two resident ones keep too many loads in flight) */
 };
 
 /* `dtype` is the storage type of the call.  `aligned16` tells how the tensor pointers of the call sit on the 16-byte

@@ -67,11 +67,19 @@ void launch_rmsnorm_row(const astra_launch_info_t& li, void* input, void* residu
             fused_add_rmsnorm_row_kernel<DT, VPT, MAXT, kNTLoad, kNTStore, LDS_TREE, false, kPaceXBeforeR, STRIDED>
                 <<<grid, block, 0, stream>>>(in, res, w, T, hv, inv_h, eps, lc, yo, ro, views, store_scope);
             return;
-        default:
-            fused_add_rmsnorm_row_kernel<DT, VPT, MAXT, kNTLoad, kNTStore, LDS_TREE, false, kPaceNone, STRIDED>
-                <<<grid, block, 0, stream>>>(in, res, w, T, hv, inv_h, eps, lc, yo, ro, views, store_scope);
-            return;
+        // one workgroup per compute unit at a time: planned for rows of two vectors per lane only
+        case kPaceWeightFirst | kPaceXBeforeR | kPaceOneResident:
+            if constexpr (VPT == 2) {
+                fused_add_rmsnorm_row_kernel<DT, VPT, MAXT, kNTLoad, kNTStore, LDS_TREE, false,
+                                             kPaceWeightFirst | kPaceXBeforeR | kPaceOneResident, STRIDED>
+                    <<<grid, block, 0, stream>>>(in, res, w, T, hv, inv_h, eps, lc, yo, ro, views, store_scope);
+                return;
+            }
+            break;
+        default: break;
     }
+    fused_add_rmsnorm_row_kernel<DT, VPT, MAXT, kNTLoad, kNTStore, LDS_TREE, false, kPaceNone, STRIDED>
+        <<<grid, block, 0, stream>>>(in, res, w, T, hv, inv_h, eps, lc, yo, ro, views, store_scope);
 }
 
 // rows of at most 32 vectors, 256 / G rows per workgroup; `views` (strides in vectors) only when STRIDED

@@ -76,7 +76,10 @@ __device__ __forceinline__ void store_row_vec(u32x4* row, uint32_t row_vecs, uin
 
 // Request pacing of the fused_add_rmsnorm row kernel (a template parameter there, chosen by the host's launch plan;
 // the values are those of ASTRA_PACE_* in include/astra_plan.h)
-enum : int { kPaceNone = 0, kPaceWeightFirst = 1, kPaceXBeforeR = 2, kPaceStoreGap = 4 };
+enum : int { kPaceNone = 0, kPaceWeightFirst = 1, kPaceXBeforeR = 2, kPaceStoreGap = 4, kPaceOneResident = 8 };
+// kPaceOneResident: the workgroup reserves this much LDS, more than half of a compute unit's 160 KiB, so that a compute
+// unit holds one workgroup at a time (the longest rows of two vectors per lane: see the host's launch plan)
+constexpr int kOneResidentLdsBytes = 96 << 10;
 
 // Waits until every global load and store this wave has issued so far has completed (s_waitcnt vmcnt(0);
 // the LDS / scalar and export counters are left alone).  Used to pace a wave's second store behind its first.

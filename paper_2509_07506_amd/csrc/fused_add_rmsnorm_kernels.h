@@ -24,6 +24,12 @@ namespace astra {
 //   kPaceWeightFirst  the weight must have arrived before the activations are requested
 //   kPaceXBeforeR     the x vectors must have arrived before the r vectors are requested
 //   kPaceStoreGap     the residual store must have completed before the output store is issued
+//   kPaceOneResident  not a wait: the workgroup reserves 96 KiB of LDS it never touches, so that a compute unit holds
+//                     one workgroup at a time.  Two resident workgroups of a two-vector row keep 2048 lanes x 2 x 32
+//                     bytes = 128 KiB of loads in flight per compute unit, twice what the one-vector rows do, and
+//                     the streaming rate is best at 56 to 80 KiB (T=8192, bf16, two -> one resident workgroup:
+//                     H=16384 78.0 -> 79.6 % of the HBM peak, H=14336 78.6 -> 79.5 %; H=10240, whose rows are
+//                     20 KiB, 79.1 -> 73.6 %)
 // With PACE = 0 every request goes out as early as possible: the shortest dependent chain, used for few rows.
 // Both results go out through store_row_vec (device_common.h): the plain non-temporal store; `store_scope` lets the
 // ablation entry point run the same kernel with device-scope stores.
@@ -57,6 +63,10 @@ __global__ __launch_bounds__(MAX_THREADS) void fused_add_rmsnorm_row_kernel(u32x
     constexpr int N = Storage<DT>::kN;
     __shared__ float partials[2][16];
     __shared__ float tree[LDS_TREE ? 1024 : 1];  // ablation only
+    if constexpr ((PACE & kPaceOneResident) != 0) {
+        __shared__ char reserved[kOneResidentLdsBytes];  // never accessed; its address is consumed so that it is allocated
+        asm volatile("" : : "v"((uint32_t)(uintptr_t)&reserved[0]));
+    }
     const int nwaves = blockDim.x >> 6;
     const int64_t first_row = xcd_chunked(blockIdx.x, log2_chunk);
     if (first_row >= T) return;  // grid padding; uniform for the whole workgroup

@@ -191,6 +191,21 @@ inline bool rmsnorm_row_plan(int64_t hv, RowPlan* plan)
 // rounds of resident workgroups the default is "none".
 constexpr int kGapMinRounds = 32;
 
+// The longest two-vector rows: one workgroup per compute unit at a time (kPaceOneResident).  What a compute unit has
+// in flight is resident lanes x vectors per lane x 32 bytes: 64 KiB for every one-vector row (2048 lanes), but up to
+// 128 KiB once a row takes two vectors per lane and two workgroups are resident, and the streaming rate is best at 56
+// to 80 KiB.  Measured on MI355X (development harness, T = 8192, bf16, cold, two -> one resident workgroup, best pace
+// of either): H = 13312 78.6 -> 79.0 % of the HBM peak, 14336 78.6 -> 79.5 %, 15360 77.5 -> 78.4 %, 16384 78.0 ->
+// 79.6 %; too little in flight below that (H = 12288 78.7 -> 78.0 %, 10240 79.1 -> 73.6 %).  Through the library
+// (`bench.py --pacing`, T*H = 2^28, 12 placements, two runs; the policy's choice against the best forced pace with two
+// resident workgroups): H = 14336 331.0 / 331.0 us against "w,x" 333.3 / 335.1, H = 16384 334.3 / 334.6 against "x"
+// 338.1 / 338.5, faster on 12 of 12 placements each time.  With one resident workgroup "w,x" is the best pace or level
+// with it.  Rows of four vectors per lane (H = 20480, 24576) gain 3-4 % from the same at T = 4096 but nothing at
+// T = 13107 (352.5 us against 348.6-350.6 for "w,x" with two resident), so they are left alone.  Hence: two-vector rows
+// of 28 KiB or more, from 16 rows per compute unit on (what was measured).
+constexpr int64_t kOneResidentMinRowBytes = 28 << 10;
+constexpr int64_t kOneResidentMinRowsPerCu = 16;
+
 inline int rmsnorm_stream_pace(int64_t hv, bool long_grid)
 {
     // keys are row lengths in 16-byte vectors: H / 8 for the 16-bit storage types the table was measured with
@@ -249,6 +264,8 @@ inline bool rmsnorm_row_policy(int64_t T, int64_t hv, int64_t row_bytes, RowPlan
         *pace = kPaceXBeforeR;
     } else if (n < kStreamingRounds * resident) {
         *pace = kPaceXBeforeR;
+    } else if (plan->vpt == 2 && row_bytes >= kOneResidentMinRowBytes && n >= kOneResidentMinRowsPerCu) {
+        *pace = kPaceWeightFirst | kPaceXBeforeR | kPaceOneResident;
     } else {
         *pace = rmsnorm_stream_pace(hv, n >= kGapMinRounds * resident);
     }

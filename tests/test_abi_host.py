@@ -216,10 +216,15 @@ def test_rmsnorm_plans(A):
     # grids (three rounds or more) "store gap" (4) by default on long grids, and a pace of its own for the row lengths that
     # beat the default on nearly every buffer placement (bench.py --pacing): weight-then-x-then-r (1 | 2), x-then-r (2)
     assert plan(255, 8192)["pace"] == 0 and plan(512, 4096)["pace"] == 0 and big["pace"] == 0
-    for T, H, pace in [(32768, 8192, 3), (32768, 2048, 3), (32768, 1024, 3), (32768, 1536, 3), (4096, 14336, 3), (32768, 10240, 3),
-                       (32768, 2560, 2), (32768, 3072, 2), (4096, 16384, 2),
+    for T, H, pace in [(32768, 8192, 3), (32768, 2048, 3), (32768, 1024, 3), (32768, 1536, 3), (2048, 14336, 3), (32768, 10240, 3),
+                       (32768, 2560, 2), (32768, 3072, 2), (2048, 16384, 2),
                        (32768, 4096, 4), (32768, 5120, 4), (32768, 6144, 4), (32768, 7168, 4), (32768, 7680, 4), (32768, 11008, 4),
                        (32768, 12288, 4), (16384, 32768, 4), (1 << 20, 512, 4)]:
+        assert plan(T, H)["pace"] == pace, (T, H, plan(T, H))
+    # two-vector rows of 28 KiB or more on grids of 16 rows per compute unit or more: one workgroup per compute unit at a
+    # time (8), paced weight-then-x-then-r
+    for T, H, pace in [(4096, 14336, 11), (8192, 16384, 11), (4096, 15360, 11), (4096, 20480, 0), (4096, 24576, 0),
+                       (4095, 16384, 11), (3840, 16384, 2), (4096, 14328, 0), (4096, 16392, 0), (4096, 28672, 0), (4096, 12288, 0)]:
         assert plan(T, H)["pace"] == pace, (T, H, plan(T, H))
     # ... the gap only where its extra microsecond at the end of the grid is small change (32 rounds or more)
     assert plan(4099, 5120)["pace"] == 0 and plan(2048, 28672)["pace"] == 0 and plan(4099, 7168)["pace"] == 0
@@ -246,7 +251,7 @@ def test_rmsnorm_plans(A):
         assert plan(T, H)["vectors_per_lane"] == 2, (T, H)
     assert A.astra_plan_fused_add_rmsnorm(1280, 2048, True, dtype=A.ASTRA_F32)[1].as_dict()["vectors_per_lane"] == 2
     assert A.astra_plan_fused_add_rmsnorm(32768, 4096, True, dtype=A.ASTRA_F32)[1].as_dict()["pace"] == 3   # 16 KiB rows
-    assert A.astra_plan_fused_add_rmsnorm(32768, 8192, True, dtype=A.ASTRA_F32)[1].as_dict()["pace"] == 2   # 32 KiB rows
+    assert A.astra_plan_fused_add_rmsnorm(32768, 8192, True, dtype=A.ASTRA_F32)[1].as_dict()["pace"] == 11  # 32 KiB rows: one resident workgroup
     assert A.astra_plan_silu_and_mul(4096, 14336, True)[1].as_dict()["pace"] == 0
 
 

@@ -90,7 +90,8 @@ def test_paper_table4_shapes_all_variants(A, name):
 
 
 @pytest.mark.parametrize("dt", ["bf16", "f16"])
-@pytest.mark.parametrize("T,H", [(3, 8), (5, 520), (7, 5120), (300, 7168), (2, 8192), (4, 11008), (600, 14336), (3, 16384)])
+@pytest.mark.parametrize("T,H", [(3, 8), (5, 520), (7, 5120), (300, 7168), (2, 8192), (4, 11008), (600, 14336), (3, 16384),
+                                 (4096, 14336)])                   # long rows, streaming: one resident workgroup per compute unit
 def test_rmsnorm_variants_edge_shapes(A, T, H, dt):
     x, r, w = workloads.rmsnorm_inputs(T, H, dt, np.random.default_rng([31, T, H]), r_std=2.0)
     for v in RMS_VARIANTS[1:]:
@@ -146,7 +147,8 @@ def test_variant_validation_on_device(A):
 
 @pytest.mark.parametrize("dt", ["bf16", "f16"])
 @pytest.mark.parametrize("T,H", [(3, 4096), (700, 2048), (1100, 5120), (300, 8192), (65, 10240), (20, 20480), (1500, 512),
-                                 (40, 4104), (9, 8200)])           # rows that are no whole 128-byte lines
+                                 (40, 4104), (9, 8200),            # rows that are no whole 128-byte lines
+                                 (4096, 16384)])                   # the tuned kernel holds one workgroup per compute unit here
 def test_forced_pacing_gives_the_tuned_kernels_bits(A, T, H, dt):
     """The pace-forcing variants run the tuned row kernel with another order of memory requests: same arithmetic, so
     the same bits as astra_fused_add_rmsnorm, and the oracle's bars."""

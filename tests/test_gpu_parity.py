@@ -125,6 +125,17 @@ def test_benchmark_workload(A, name):
 # ---------------------------------------------------------------------------------------------------
 # shapes around the kernels' tiles: every vectors-per-lane variant, ragged last wave, row loop
 
+@pytest.mark.parametrize("T,H,dt,pace", [(4100, 16384, "bf16", 11), (4096, 14336, "f16", 11), (4097, 15360, "bf16", 11)])
+def test_rmsnorm_long_rows_one_workgroup_per_compute_unit(A, T, H, dt, pace):
+    """two-vector rows of 28 KiB or more on streaming grids: the row kernel reserves LDS so that a compute unit holds one workgroup at
+    a time (ASTRA_PACE_ONE_RESIDENT = 8 in the plan's pace); same results as every other instantiation"""
+    st, info = A.astra_plan_fused_add_rmsnorm(T, H, True)
+    _say(f"[parity] rmsnorm one resident workgroup T={T} H={H} {dt} plan={info.as_dict()}")
+    assert st == 0 and info.as_dict()["pace"] == pace and info.as_dict()["path"] == "vector"
+    x, r, w = workloads.rmsnorm_inputs(T, H, dt, np.random.default_rng([12, T, H]), r_std=2.0)
+    check_rmsnorm(A, x, r, w, 1e-5, dt, f"rmsnorm T={T} H={H} {dt}", f64=False)
+
+
 @pytest.mark.parametrize("dt", ["bf16", "f16"])
 @pytest.mark.parametrize("T,H", [(1, 8), (2, 64), (5, 512), (3, 520), (300, 1024), (700, 2048), (513, 4096), (600, 6144),
                                  (530, 11008), (515, 14336), (520, 16384), (4, 16384), (2, 32768), (530, 28672),

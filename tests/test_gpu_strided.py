@@ -56,6 +56,7 @@ def _gaps_intact(whole, col0, H):
     (270, 5124, (5124 + 5, 5124 + 1, 5124, 5124 + 3), 3),
     (3, 33000, (33000 + 1, 33000, 33000 + 7, 33000), 0),           # more than 4096 vectors: element-wise path
     (1, 4096, (4096, 4096, 4096, 4096), 0),
+    (4096, 14336, (14336 + 8, 14336, 14336 + 16, 14336 + 8), 0),   # long rows on a streaming grid: one resident workgroup
 ])
 def test_strided_out_of_place(A, T, H, strides, col0, dt):
     print(f"[strided] T={T} H={H} strides={strides} col0={col0} {dt}", flush=True)
