@@ -82,7 +82,8 @@ void launch_rmsnorm_row(const astra_launch_info_t& li, void* input, void* residu
         <<<grid, block, 0, stream>>>(in, res, w, T, hv, inv_h, eps, lc, yo, ro, views, store_scope);
 }
 
-// rows of at most 32 vectors, 256 / G rows per workgroup; `views` (strides in vectors) only when STRIDED
+// rows of at most 32 vectors, G lanes per row, li.block / G rows per workgroup (li.block is 256, or 64 on streaming
+// grids); `views` (strides in vectors) only when STRIDED
 template <int DT, bool STRIDED>
 void launch_rmsnorm_short(const astra_launch_info_t& li, void* input, void* residual, const void* weight, int64_t T, int64_t H,
                           float eps, hipStream_t stream, void* y_out = nullptr, void* r_out = nullptr,
@@ -94,21 +95,21 @@ void launch_rmsnorm_short(const astra_launch_info_t& li, void* input, void* resi
     const u32x4* const w = static_cast<const u32x4*>(weight);
     u32x4* const yo = static_cast<u32x4*>(y_out);
     u32x4* const ro = static_cast<u32x4*>(r_out);
-    const dim3 grid((uint32_t)li.grid), block(256);
+    const dim3 grid((uint32_t)li.grid);
     const float inv_h = 1.0f / (float)H;
-    switch (256 / li.rows_per_block) {
-        case 8:
-            fused_add_rmsnorm_short_row_kernel<DT, 8, kNTLoad, kNTStore, STRIDED>
-                <<<grid, block, 0, stream>>>(in, res, w, T, hv, inv_h, eps, li.log2_xcd_chunk, yo, ro, views);
-            break;
-        case 16:
-            fused_add_rmsnorm_short_row_kernel<DT, 16, kNTLoad, kNTStore, STRIDED>
-                <<<grid, block, 0, stream>>>(in, res, w, T, hv, inv_h, eps, li.log2_xcd_chunk, yo, ro, views);
-            break;
-        default:
-            fused_add_rmsnorm_short_row_kernel<DT, 32, kNTLoad, kNTStore, STRIDED>
-                <<<grid, block, 0, stream>>>(in, res, w, T, hv, inv_h, eps, li.log2_xcd_chunk, yo, ro, views);
-            break;
+    auto go = [&](auto group, auto width) {
+        constexpr int G = decltype(group)::value, B = decltype(width)::value;
+        fused_add_rmsnorm_short_row_kernel<DT, G, kNTLoad, kNTStore, STRIDED, B>
+            <<<grid, dim3(B), 0, stream>>>(in, res, w, T, hv, inv_h, eps, li.log2_xcd_chunk, yo, ro, views);
+    };
+    auto with_group = [&](auto group) {
+        if (li.block == 64) go(group, std::integral_constant<int, 64>{});
+        else go(group, std::integral_constant<int, 256>{});
+    };
+    switch (li.block / li.rows_per_block) {
+        case 8: with_group(std::integral_constant<int, 8>{}); break;
+        case 16: with_group(std::integral_constant<int, 16>{}); break;
+        default: with_group(std::integral_constant<int, 32>{}); break;
     }
 }
 

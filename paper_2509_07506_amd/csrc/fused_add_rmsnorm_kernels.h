@@ -146,19 +146,19 @@ __global__ __launch_bounds__(MAX_THREADS) void fused_add_rmsnorm_row_kernel(u32x
 }
 
 // Short rows (at most 32 vectors: H <= 256 in 16 bits): one row per workgroup would leave most of a wave idle, so a
-// row takes G = 8, 16 or 32 lanes (the smallest that holds it) and a 256-lane workgroup 256/G rows; the sum of
+// row takes G = 8, 16 or 32 lanes (the smallest that holds it) and a workgroup of BLOCK lanes BLOCK/G rows; the sum of
 // squares stays inside the wave (group_sum: no LDS, no barrier).  Measured on MI355X with T*H = 2^28: H = 64
 // 3040 -> 6507 GB/s, H = 128 4659 -> 6409, H = 256 6365 -> 6415 against one row per 64-lane workgroup.
 // STRIDED as in the row kernel.
-template <int DT, int G, bool NTL, bool NTS, bool STRIDED = false>
-__global__ __launch_bounds__(256) void fused_add_rmsnorm_short_row_kernel(u32x4* input, u32x4* residual,
+template <int DT, int G, bool NTL, bool NTS, bool STRIDED = false, int BLOCK = 256>
+__global__ __launch_bounds__(BLOCK) void fused_add_rmsnorm_short_row_kernel(u32x4* input, u32x4* residual,
                                                                           const u32x4* __restrict__ weight, int64_t T,
                                                                           uint32_t hv, float inv_h, float eps, int log2_chunk,
                                                                           u32x4* y_out = nullptr, u32x4* r_out = nullptr,
                                                                           RowViews views = RowViews{0, 0, 0, 0})
 {
     constexpr int N = Storage<DT>::kN;
-    constexpr uint32_t kRows = 256 / G;  // rows per workgroup
+    constexpr uint32_t kRows = BLOCK / G;  // rows per workgroup
     const int64_t row = (int64_t)xcd_chunked(blockIdx.x, log2_chunk) * kRows + threadIdx.x / G;
     const uint32_t v = threadIdx.x % G;
     const bool live = row < T && v < hv;  // whole waves stay together: group_sum needs every lane

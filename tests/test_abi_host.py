@@ -204,8 +204,14 @@ def test_rmsnorm_plans(A):
     big = plan(1 << 23, 264)                                           # row loop beyond the grid limit
     assert big["grid"] == 1 << 21 and big["grid"] % (8 << big["log2_xcd_chunk"]) == 0
     # rows of at most 32 vectors share a workgroup: 8, 16 or 32 lanes per row, 256-lane workgroups
-    assert plan(1 << 23, 64) == {"path": "vector", "block": 256, "vectors_per_lane": 1, "log2_xcd_chunk": 8, "grid": 1 << 18,
-                                 "pace": 0, "rows_per_block": 32}
+    # ... and single-wave workgroups on streaming grids when the rows fill their lane groups (H = 64, 128, 256)
+    assert plan(1 << 23, 64) == {"path": "vector", "block": 64, "vectors_per_lane": 1, "log2_xcd_chunk": 8, "grid": 1 << 20,
+                                 "pace": 0, "rows_per_block": 8}
+    assert plan(1 << 21, 256)["block"] == 64 and plan(1 << 21, 256)["rows_per_block"] == 2
+    assert plan(1 << 22, 128)["block"] == 64 and plan(1 << 22, 128)["rows_per_block"] == 4
+    assert plan(1 << 23, 72)["block"] == 256 and plan(1 << 22, 192)["block"] == 256      # rows that leave lanes of their group idle
+    assert plan(100000, 64)["block"] == 256                                               # under 4096 workgroups of 256 lanes
+    assert plan(1 << 25, 64)["block"] == 256 and plan(1 << 25, 64)["rows_per_block"] == 32  # 64-lane workgroups: over the grid limit
     assert plan(1000, 128)["rows_per_block"] == 16 and plan(1000, 128)["grid"] == 63 and plan(1000, 136)["rows_per_block"] == 8
     assert plan(5, 256)["rows_per_block"] == 8 and plan(5, 256)["grid"] == 1 and "rows_per_block" not in plan(5, 264)
     assert "rows_per_block" not in plan(5, 260) and plan(5, 260)["path"] == "phased" and plan(5, 260, al=0)["path"] == "ragged"

@@ -159,13 +159,16 @@ def test_rmsnorm_streaming_grids(A, T, H, dt):
 
 @pytest.mark.parametrize("dt", ["bf16", "f16"])
 @pytest.mark.parametrize("T,H,rows", [(1, 8, 32), (7, 16, 32), (33, 24, 32), (1000, 64, 32), (5000, 72, 16), (257, 128, 16),
-                                      (4099, 136, 8), (65, 200, 8), (3, 256, 8), (100000, 128, 16)])
+                                      (4099, 136, 8), (65, 200, 8), (3, 256, 8), (60000, 128, 16),
+                                      # streaming grids of rows that fill their lane groups: single-wave workgroups
+                                      (140001, 64, 8), (70003, 128, 4), (33001, 256, 2)])
 def test_rmsnorm_short_rows_share_a_workgroup(A, T, H, rows, dt):
     """Rows of at most 32 vectors: 8, 16 or 32 lanes per row, several rows per workgroup, the sum inside the wave;
     ragged last workgroups and rows that leave lanes of their group idle included."""
     plan = A.astra_plan_fused_add_rmsnorm(T, H, True)[1].as_dict()
     _say(f"[parity] rmsnorm short rows T={T} H={H} {dt} plan={plan}")
-    assert plan.get("rows_per_block") == rows and plan["block"] == 256
+    lanes_per_row = 8 if H <= 64 else 16 if H <= 128 else 32
+    assert plan.get("rows_per_block") == rows and plan["block"] == rows * lanes_per_row == (64 if T > 30000 and T != 60000 else 256)
     x, r, w = workloads.rmsnorm_inputs(T, H, dt, np.random.default_rng([13, T, H]), r_std=2.0)
     check_rmsnorm(A, x, r, w, 1e-5, dt, f"rmsnorm T={T} H={H} {dt}")
 

@@ -49,6 +49,7 @@ def _gaps_intact(whole, col0, H):
     (1280, 4096, (4096 + 8, 4096 + 16, 4096 + 8, 4096), 0),        # half-sized workgroups, two vectors per lane
     (300, 128, (128 + 8, 128, 128 + 16, 128 + 8), 0),              # short rows: several rows per workgroup
     (77, 64, (64, 64 + 8, 64 + 8, 64 + 24), 8),
+    (140001, 64, (64 + 8, 64, 64 + 16, 64 + 8), 0),                # ... in single-wave workgroups on a streaming grid
     (700, 8192, (8192 + 8, 8192, 8192 + 8, 8192 + 8), 8),          # x requested before r
     (1100, 2048, (2048 + 64, 2048 + 8, 2048, 2048 + 8), 0),        # launch order in chunks
     (5, 4096, (4096 + 3, 4096 + 8, 4096 + 8, 4096 + 8), 0),        # odd stride: ragged path
