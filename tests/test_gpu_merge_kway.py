@@ -45,6 +45,8 @@ def _run(A, v, s, dt):
 @pytest.mark.parametrize("dt", ["bf16", "f16"])
 @pytest.mark.parametrize("K,T,NH,D", [(1, 5, 3, 64), (2, 33, 8, 128), (3, 257, 40, 64), (4, 64, 32, 128), (8, 129, 8, 256), (16, 7, 5, 72),
                                       (5, 3, 2, 8), (3, 4, 3, 100), (7, 2, 2, 4), (2, 1, 1, 1024), (32, 16, 4, 128),
+                                      (3, 2100, 32, 128),      # streaming grid: single-wave workgroups, XCD-aware order
+                                      (2, 20, 32, 128),        # fewer 256-lane workgroups than compute units: 128 lanes
                                       (4, 70, 9, 129), (5, 33, 7, 13), (3, 9, 4, 7), (6, 300, 5, 132)])    # ragged path
 def test_kway_matches_oracle(A, K, T, NH, D, dt):
     print(f"[kway] K={K} T={T} NH={NH} D={D} {dt}", flush=True)
