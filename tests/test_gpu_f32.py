@@ -92,7 +92,8 @@ def test_rmsnorm_unaligned_and_canaries(A):
 
 
 @pytest.mark.parametrize("T,d", [(1, 128), (3, 1412), (257, 1408), (64, 8192), (700, 5120), (5, 130), (4, 7), (9, 96),
-                                 (333, 4), (50, 88)])
+                                 (333, 4), (50, 88),
+                                 (1100, 4096)])            # streaming grid: single-wave workgroups, XCD-aware order
 def test_silu_tiles(A, T, d):
     plan = A.astra_plan_silu_and_mul(T, d, True, dtype=A.ASTRA_F32)[1].as_dict()
     _say(f"[f32] silu T={T} d={d} plan={plan}")
@@ -162,7 +163,8 @@ def run_merge(A, va, la, vb, lb):
     return to_bits(vo), lo.cpu().numpy()
 
 
-@pytest.mark.parametrize("T,NH,D", [(1, 1, 4), (3, 40, 64), (257, 40, 256), (600, 32, 128), (5, 7, 36), (4, 3, 6), (2, 5, 1)])
+@pytest.mark.parametrize("T,NH,D", [(1, 1, 4), (3, 40, 64), (257, 40, 256), (600, 32, 128), (5, 7, 36), (4, 3, 6), (2, 5, 1),
+                                    (1100, 32, 128)])      # streaming grid: single-wave workgroups, XCD-aware order
 def test_merge_tiles(A, T, NH, D):
     plan = A.astra_plan_merge_attn_states_lse(T, NH, D, True, dtype=A.ASTRA_F32)[1].as_dict()
     _say(f"[f32] merge T={T} NH={NH} D={D} plan={plan}")

@@ -194,7 +194,8 @@ def test_rmsnorm_grids_of_few_rounds(A, T, H, dt, vpt, pace):
 @pytest.mark.parametrize("dt", ["bf16", "f16"])
 @pytest.mark.parametrize("T,d", [(1, 256), (3, 264), (2, 512), (7, 1000), (33, 2048), (5, 4096), (19, 5120), (2, 12288),
                                  (1, 14336), (129, 3584),
-                                 (300, 8), (17, 64), (1000, 176), (5, 248), (4099, 24)])   # rows under 32 vectors
+                                 (300, 8), (17, 64), (1000, 176), (5, 248), (4099, 24),    # rows under 32 vectors
+                                 (50000, 176)])            # ... on a streaming grid (single-wave workgroups, per-lane division)
 def test_silu_tile_shapes(A, T, d, dt):
     _say(f"[parity] silu tiles T={T} d={d} {dt} plan={A.astra_plan_silu_and_mul(T, d, True)[1].as_dict()}")
     a = workloads.silu_inputs(T, d, dt, np.random.default_rng([2, T, d]))
@@ -203,7 +204,8 @@ def test_silu_tile_shapes(A, T, d, dt):
 
 @pytest.mark.parametrize("dt", ["bf16", "f16"])
 @pytest.mark.parametrize("T,NH,D", [(1, 1, 8), (3, 5, 16), (7, 3, 72), (9, 8, 80), (5, 32, 96), (512, 32, 256), (512, 40, 128),
-                                    (11, 64, 128), (2, 7, 192), (1, 1, 1024), (3, 2, 576)])
+                                    (11, 64, 128), (2, 7, 192), (1, 1, 1024), (3, 2, 576),
+                                    (4000, 32, 72)])       # streaming grid, head_dim no power of two (single-wave workgroups)
 def test_merge_tile_shapes(A, T, NH, D, dt):
     _say(f"[parity] merge tiles T={T} NH={NH} D={D} {dt} plan={A.astra_plan_merge_attn_states_lse(T, NH, D, True)[1].as_dict()}")
     va, la, vb, lb = workloads.merge_inputs(T, NH, D, dt, np.random.default_rng([3, T, NH, D]), empty_p=0.1)
