@@ -61,6 +61,7 @@ def check_rmsnorm(A, x, r, w, eps, what):
 
 @pytest.mark.parametrize("T,H", [(1, 4), (2, 64), (5, 512), (3, 516), (300, 1024), (700, 4096), (40, 8192), (600, 8192),
                                  (1000, 32), (333, 68), (50, 128),             # short rows: several rows per workgroup
+                                 (140001, 32), (40000, 128),                   # ... in single-wave workgroups on streaming grids
                                  (9, 16384), (520, 11008), (1024, 4096), (1050, 2048), (1030, 6144),  # last three: paced grids
                                  (4100, 8192),                                   # 32 KiB rows, streaming: one resident workgroup
                                  (2, 32768),                                     # beyond 4096 vectors: element-wise path
